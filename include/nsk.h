@@ -1,0 +1,167 @@
+/*
+ * nsk.h -- C ABI of libnsk: the residual-CNN training hot path on one MI355X (gfx950).
+ *
+ * The paper's system hands 2-D convolutions to a vendor library and runs batch-norm, ReLU and
+ * the residual add as separate kernels (abstract; section "Experiments and Discussion";
+ * ReLU fusion is named as future work in the conclusion).  This library is that device layer,
+ * hand-written: implicit-GEMM convolution forward / backward-data / backward-weight on the
+ * MFMA units, and fused batch-norm + ReLU + residual-add forward / backward, plus the 3x3
+ * max pooling the large-image stem needs.
+ *
+ * Calling convention, taken from what the paper says about its runtime:
+ *  - Tensors are raw DEVICE pointers owned by the caller (section "Caching and Pooling": a
+ *    pool hands out raw float pointers and nothing is malloc'd after the first iteration).
+ *    No entry point allocates or frees device memory; scratch space is a caller-provided
+ *    `workspace` whose size comes from a host-only query.
+ *  - Every call is asynchronous on the caller's stream (section "Operation Overlapping");
+ *    `stream` is a hipStream_t passed as void* (NULL = the default stream).  No call
+ *    synchronises the device.
+ *  - Gradients ACCUMULATE when asked to (section "Automatic Differentiation": the gradient
+ *    reaching an operand is added to the one it already holds; section "Caching and
+ *    Pooling": weight gradients are accumulated until the optimizer zeroes them):
+ *    `accumulate` = 0 overwrites the whole output (elements no product reaches become 0),
+ *    `accumulate` = 1 adds to what the buffer holds.
+ *
+ * Layouts and types.  Activations are NSK_NCHW (filters KCRS) or NSK_NHWC (filters KRSC),
+ * dense and C-contiguous; NHWC is the fast path, NCHW is converted inside the call through
+ * the workspace.  Element type NSK_F32 or NSK_BF16 (bfloat16, fp32 accumulation, round to
+ * nearest even on store).  Filter gradients, batch-norm parameters, statistics and their
+ * gradients are always float.  There is no convolution bias (batch-norm follows each one).
+ *
+ * Errors.  Every entry point returns an nsk_status_t and never throws or aborts.  Argument
+ * validation happens on the host BEFORE any HIP call, so it behaves the same without a GPU.
+ * All pointers must be 16-byte aligned.  Outputs must not overlap inputs.
+ */
+#ifndef NSK_H
+#define NSK_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NSK_OK = 0,
+    NSK_ERR_NULL = 1,        /* a required pointer is NULL */
+    NSK_ERR_BAD_DESC = 2,    /* a descriptor field is out of range or the output would be empty */
+    NSK_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for */
+    NSK_ERR_WORKSPACE = 4,   /* workspace is NULL or smaller than the query says */
+    NSK_ERR_ALIGNMENT = 5,   /* a pointer is not 16-byte aligned */
+    NSK_ERR_HIP = 6          /* a HIP runtime call failed; see nsk_last_hip_error() */
+} nsk_status_t;
+
+enum { NSK_F32 = 0, NSK_BF16 = 1 };
+enum { NSK_NCHW = 0, NSK_NHWC = 1 };
+enum { NSK_PASS_FWD = 0, NSK_PASS_DGRAD = 1, NSK_PASS_WGRAD = 2 };
+enum { NSK_BN_FWD = 0, NSK_BN_BWD = 1 };
+
+/* Convolution y[N,K,P,Q] = x[N,C,H,W] (*) w[K,C,R,S]: cross-correlation, zero padding,
+ * P = floor((H + 2*pad_h - dil_h*(R-1) - 1)/stride_h) + 1, Q likewise. */
+typedef struct {
+    int N, C, H, W;
+    int K, R, S;
+    int stride_h, stride_w;
+    int pad_h, pad_w;
+    int dil_h, dil_w;
+    int dtype;  /* NSK_F32 | NSK_BF16: type of x, w, y, dy, dx */
+    int layout; /* NSK_NCHW (w is KCRS) | NSK_NHWC (w is KRSC) */
+} nsk_conv_desc_t;
+
+/* Batch-norm over (n,h,w) per channel of a tensor [N,C,H,W], with optional ReLU. */
+typedef struct {
+    int N, C, H, W;
+    int dtype;      /* of x, residual, out, dout, dx, dresidual */
+    int layout;
+    float eps;      /* added to the biased batch variance */
+    float momentum; /* running = (1-momentum)*running + momentum*batch */
+    int relu;       /* 0 | 1 */
+} nsk_bn_desc_t;
+
+/* Max pooling with window R x S over a tensor [N,C,H,W]; padding counts as -infinity. */
+typedef struct {
+    int N, C, H, W;
+    int R, S;
+    int stride_h, stride_w;
+    int pad_h, pad_w;
+    int dtype;
+    int layout;
+} nsk_pool_desc_t;
+
+/* Library version as major*10000 + minor*100 + patch.  Host only. */
+int nsk_version(void);
+
+/* Static, never-NULL description of a status code.  Host only. */
+const char *nsk_status_string(int status);
+
+/* The hipError_t (as int) of the last HIP call that failed on this thread, 0 if none. */
+int nsk_last_hip_error(void);
+
+/* Output extent of a convolution.  Host only.  NSK_ERR_BAD_DESC if the descriptor is invalid
+ * (then *P and *Q are not written); an extent may legitimately come out as 0. */
+int nsk_conv2d_out_dims(const nsk_conv_desc_t *desc, int *P, int *Q);
+
+/* Bytes of workspace the given pass (NSK_PASS_*) needs for this descriptor; 0 for an invalid
+ * descriptor or pass.  Host only, deterministic, never exceeds what the call will use. */
+size_t nsk_conv2d_workspace_bytes(const nsk_conv_desc_t *desc, int pass);
+
+/* Forward convolution.  x: [N,C,H,W] in desc->layout, w: [K,C,R,S] (KCRS or KRSC),
+ * y: [N,K,P,Q] in desc->layout; all of desc->dtype, device memory.  y is overwritten. */
+int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y,
+                   void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward-data: dx = adjoint of the forward map with respect to x applied to dy.
+ * dy: [N,K,P,Q], w as in forward, dx: [N,C,H,W].  accumulate: see the header comment;
+ * with accumulate = 0 input positions that no filter tap reaches (strided cases) are
+ * written as 0. */
+int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w, void *dx,
+                     int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward-weight: dw[K,C,R,S] (always float, laid out like w for desc->layout) =
+ * sum over (n,p,q) of dy * shifted x.  The reduction is split over (n,p,q) into float
+ * partials in the workspace and combined in a fixed order, so results are bitwise
+ * reproducible from run to run. */
+int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy, float *dw,
+                     int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Workspace bytes for the batch-norm pass (NSK_BN_FWD | NSK_BN_BWD); 0 if invalid. */
+size_t nsk_bn_workspace_bytes(const nsk_bn_desc_t *desc, int pass);
+
+/* out = relu?( gamma*(x-mean)*invstd + beta [+ residual] ), with mean and the biased variance
+ * taken over (n,h,w) of this batch and invstd = 1/sqrt(var + eps).
+ * residual may be NULL.  save_mean / save_invstd ([C] float) receive the batch statistics
+ * for the backward pass.  running_mean / running_var ([C] float, both or neither NULL) are
+ * updated in place with desc->momentum, the variance in its unbiased form. */
+int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *residual,
+                        const float *gamma, const float *beta, void *out, float *save_mean,
+                        float *save_invstd, float *running_mean, float *running_var,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* Backward of nsk_bn_relu_add_fwd.  x, out: the forward input and its stored result;
+ * dout: gradient of out.  With dz = relu ? dout*[out>0] : dout and xhat = (x-mean)*invstd:
+ *   dbeta = sum dz, dgamma = sum dz*xhat  (overwritten, [C] float),
+ *   dx = gamma*invstd*(dz - dbeta/M - xhat*dgamma/M),  dresidual = dz (NULL to skip).
+ * dx and dresidual are overwritten; dresidual may later be the target of an accumulating
+ * nsk_conv2d_dgrad. */
+int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *out,
+                        const void *dout, const float *gamma, const float *save_mean,
+                        const float *save_invstd, void *dx, void *dresidual, float *dgamma,
+                        float *dbeta, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Output extent of a pooling descriptor.  Host only. */
+int nsk_maxpool2d_out_dims(const nsk_pool_desc_t *desc, int *P, int *Q);
+
+/* y[N,C,P,Q] = window maximum; idx (signed char, same shape and layout as y) = r*S+s of the
+ * FIRST maximum in row-major window order, -1 for a window with no input element (y = -inf).
+ * Needs R*S <= 127.  No workspace. */
+int nsk_maxpool2d_fwd(const nsk_pool_desc_t *desc, const void *x, void *y, signed char *idx,
+                      void *stream);
+
+/* dx[N,C,H,W] = sum of dy over the windows whose idx names that element (dx overwritten). */
+int nsk_maxpool2d_bwd(const nsk_pool_desc_t *desc, const void *dy, const signed char *idx,
+                      void *dx, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NSK_H */

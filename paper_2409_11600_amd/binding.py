@@ -1,0 +1,327 @@
+"""ctypes binding of libnsk (argument marshalling only; every computation runs in the HIP kernels).
+
+The raw entry points carry the names of ``include/nsk.h`` (``nsk_conv2d_fwd`` ...).  The
+tensor-level helpers below take torch CUDA tensors that are ALREADY in the physical layout the
+descriptor names (NHWC tensors have shape [N,H,W,C], filters [K,R,S,C]; NCHW tensors [N,C,H,W],
+filters [K,C,R,S]) and only build descriptors, fetch pointers and the current stream, and size
+the caller-owned workspace.  PyTorch is used for device memory and streams, nothing else.
+
+There is no CPU fallback: if libnsk.so has not been built, importing works but the first call
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnsk.so")
+
+NSK_OK = 0
+NSK_ERR_NULL, NSK_ERR_BAD_DESC, NSK_ERR_UNSUPPORTED, NSK_ERR_WORKSPACE, NSK_ERR_ALIGNMENT, NSK_ERR_HIP = 1, 2, 3, 4, 5, 6
+NSK_F32, NSK_BF16 = 0, 1
+NSK_NCHW, NSK_NHWC = 0, 1
+NSK_PASS_FWD, NSK_PASS_DGRAD, NSK_PASS_WGRAD = 0, 1, 2
+NSK_BN_FWD, NSK_BN_BWD = 0, 1
+
+
+class nsk_conv_desc_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("N", "C", "H", "W", "K", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "dil_h", "dil_w",
+                 "dtype", "layout")]
+
+
+class nsk_bn_desc_t(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int), ("C", ctypes.c_int), ("H", ctypes.c_int), ("W", ctypes.c_int),
+                ("dtype", ctypes.c_int), ("layout", ctypes.c_int), ("eps", ctypes.c_float),
+                ("momentum", ctypes.c_float), ("relu", ctypes.c_int)]
+
+
+class nsk_pool_desc_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in
+                ("N", "C", "H", "W", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "dtype", "layout")]
+
+
+class NskError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = lib().nsk_status_string(status).decode()
+        if status == NSK_ERR_HIP:
+            msg += f" (hipError_t {lib().nsk_last_hip_error()})"
+        super().__init__(f"{where}: {msg}")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Loads libnsk.so (built by paper_2409_11600_amd.build).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2409_11600_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, ci = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        cd, bd, pd = ctypes.POINTER(nsk_conv_desc_t), ctypes.POINTER(nsk_bn_desc_t), ctypes.POINTER(nsk_pool_desc_t)
+        ip = ctypes.POINTER(ctypes.c_int)
+        L.nsk_version.restype = ci
+        L.nsk_version.argtypes = []
+        L.nsk_status_string.restype = ctypes.c_char_p
+        L.nsk_status_string.argtypes = [ci]
+        L.nsk_last_hip_error.restype = ci
+        L.nsk_last_hip_error.argtypes = []
+        L.nsk_conv2d_out_dims.restype = ci
+        L.nsk_conv2d_out_dims.argtypes = [cd, ip, ip]
+        L.nsk_conv2d_workspace_bytes.restype = sz
+        L.nsk_conv2d_workspace_bytes.argtypes = [cd, ci]
+        L.nsk_conv2d_fwd.restype = ci
+        L.nsk_conv2d_fwd.argtypes = [cd, vp, vp, vp, vp, sz, vp]
+        L.nsk_conv2d_dgrad.restype = ci
+        L.nsk_conv2d_dgrad.argtypes = [cd, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_conv2d_wgrad.restype = ci
+        L.nsk_conv2d_wgrad.argtypes = [cd, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_bn_workspace_bytes.restype = sz
+        L.nsk_bn_workspace_bytes.argtypes = [bd, ci]
+        L.nsk_bn_relu_add_fwd.restype = ci
+        L.nsk_bn_relu_add_fwd.argtypes = [bd] + [vp] * 10 + [sz, vp]
+        L.nsk_bn_relu_add_bwd.restype = ci
+        L.nsk_bn_relu_add_bwd.argtypes = [bd] + [vp] * 11 + [sz, vp]
+        L.nsk_maxpool2d_out_dims.restype = ci
+        L.nsk_maxpool2d_out_dims.argtypes = [pd, ip, ip]
+        L.nsk_maxpool2d_fwd.restype = ci
+        L.nsk_maxpool2d_fwd.argtypes = [pd, vp, vp, vp, vp]
+        L.nsk_maxpool2d_bwd.restype = ci
+        L.nsk_maxpool2d_bwd.argtypes = [pd, vp, vp, vp, vp]
+        _lib = L
+    return _lib
+
+
+EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d_out_dims",
+           "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
+           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_maxpool2d_out_dims",
+           "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd")
+
+
+def __getattr__(name):  # raw entry points under their C names: binding.nsk_conv2d_fwd(...)
+    if name in EXPORTS:
+        return getattr(lib(), name)
+    raise AttributeError(name)
+
+
+# ------------------------------------------------------------------------------------ helpers
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return NSK_F32
+    if t.dtype == torch.bfloat16:
+        return NSK_BF16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors handed to libnsk must be contiguous CUDA tensors")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _pair(v) -> Tuple[int, int]:
+    return (int(v[0]), int(v[1])) if isinstance(v, (tuple, list)) else (int(v), int(v))
+
+
+class Workspace:
+    """Caller-owned scratch buffer, grown on demand and then reused (the paper's pooling idea:
+    nothing is allocated in steady state)."""
+
+    def __init__(self, device="cuda:0"):
+        self.device = torch.device(device)
+        self.buf: Optional[torch.Tensor] = None
+
+    def get(self, nbytes: int):
+        if nbytes == 0:
+            return None, 0
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = torch.empty(int(nbytes), dtype=torch.uint8, device=self.device)
+        return ctypes.c_void_p(self.buf.data_ptr()), self.buf.numel()
+
+
+def conv_desc(act_dims, filt_dims, stride, pad, dilation, dtype_code, layout) -> nsk_conv_desc_t:
+    """act_dims = (N,C,H,W), filt_dims = (K,R,S): logical sizes, whatever the physical layout."""
+    N, C, H, W = act_dims
+    K, R, S = filt_dims
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    dh, dw = _pair(dilation)
+    return nsk_conv_desc_t(N, C, H, W, K, R, S, sh, sw, ph, pw, dh, dw, dtype_code, layout)
+
+
+def _logical(t: torch.Tensor, layout: int):
+    """(N, C, H, W) of an activation tensor stored in `layout`."""
+    if layout == NSK_NHWC:
+        N, H, W, C = t.shape
+    else:
+        N, C, H, W = t.shape
+    return int(N), int(C), int(H), int(W)
+
+
+def _filter_logical(w: torch.Tensor, layout: int):
+    if layout == NSK_NHWC:
+        K, R, S, C = w.shape
+    else:
+        K, C, R, S = w.shape
+    return int(K), int(C), int(R), int(S)
+
+
+def _act_shape(N, C, H, W, layout):
+    return (N, H, W, C) if layout == NSK_NHWC else (N, C, H, W)
+
+
+def _check(status: int, where: str):
+    if status != NSK_OK:
+        raise NskError(status, where)
+
+
+def conv2d_out_dims(desc: nsk_conv_desc_t) -> Tuple[int, int]:
+    P, Q = ctypes.c_int(), ctypes.c_int()
+    _check(lib().nsk_conv2d_out_dims(ctypes.byref(desc), ctypes.byref(P), ctypes.byref(Q)), "nsk_conv2d_out_dims")
+    return P.value, Q.value
+
+
+def conv2d_fwd(x, w, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None, ws: Optional[Workspace] = None):
+    N, C, H, W = _logical(x, layout)
+    K, Cw, R, S = _filter_logical(w, layout)
+    assert Cw == C and w.dtype == x.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), layout)
+    P, Q = conv2d_out_dims(d)
+    if out is None:
+        out = torch.empty(_act_shape(N, K, P, Q, layout), dtype=x.dtype, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_workspace_bytes(ctypes.byref(d), NSK_PASS_FWD))
+    _check(lib().nsk_conv2d_fwd(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(out), wp, wb, _stream()), "nsk_conv2d_fwd")
+    return out
+
+
+def conv2d_dgrad(dy, w, x_logical, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None, accumulate=False,
+                 ws: Optional[Workspace] = None):
+    """x_logical = (N,C,H,W) of the forward input."""
+    N, C, H, W = x_logical
+    K, Cw, R, S = _filter_logical(w, layout)
+    assert Cw == C and w.dtype == dy.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(dy), layout)
+    if out is None:
+        assert not accumulate
+        out = torch.empty(_act_shape(N, C, H, W, layout), dtype=dy.dtype, device=dy.device)
+    ws = ws or Workspace(dy.device)
+    wp, wb = ws.get(lib().nsk_conv2d_workspace_bytes(ctypes.byref(d), NSK_PASS_DGRAD))
+    _check(lib().nsk_conv2d_dgrad(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(out), int(bool(accumulate)), wp, wb,
+                                  _stream()), "nsk_conv2d_dgrad")
+    return out
+
+
+def conv2d_wgrad(x, dy, filt_logical, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None, accumulate=False,
+                 ws: Optional[Workspace] = None):
+    """filt_logical = (K,C,R,S).  Returns float32 dw shaped like the filter in `layout`."""
+    N, C, H, W = _logical(x, layout)
+    K, Cw, R, S = filt_logical
+    assert Cw == C and x.dtype == dy.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), layout)
+    if out is None:
+        assert not accumulate
+        shape = (K, R, S, C) if layout == NSK_NHWC else (K, C, R, S)
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    assert out.dtype == torch.float32
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_workspace_bytes(ctypes.byref(d), NSK_PASS_WGRAD))
+    _check(lib().nsk_conv2d_wgrad(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(out), int(bool(accumulate)), wp, wb,
+                                  _stream()), "nsk_conv2d_wgrad")
+    return out
+
+
+def bn_desc(x: torch.Tensor, layout, eps, momentum, relu) -> nsk_bn_desc_t:
+    N, C, H, W = _logical(x, layout)
+    return nsk_bn_desc_t(N, C, H, W, _dtype_code(x), layout, float(eps), float(momentum), int(bool(relu)))
+
+
+def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=NSK_NHWC, momentum=0.1,
+                    running_mean=None, running_var=None, out=None, save_mean=None, save_invstd=None,
+                    ws: Optional[Workspace] = None):
+    """Returns (out, save_mean, save_invstd)."""
+    d = bn_desc(x, layout, eps, momentum, relu)
+    C = d.C
+    if out is None:
+        out = torch.empty_like(x)
+    if save_mean is None:
+        save_mean = torch.empty(C, dtype=torch.float32, device=x.device)
+    if save_invstd is None:
+        save_invstd = torch.empty(C, dtype=torch.float32, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_FWD))
+    _check(lib().nsk_bn_relu_add_fwd(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
+                                     _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean), _ptr(running_var),
+                                     wp, wb, _stream()), "nsk_bn_relu_add_fwd")
+    return out, save_mean, save_invstd
+
+
+def bn_relu_add_bwd(x, out, dout, gamma, save_mean, save_invstd, relu=True, layout=NSK_NHWC, eps=1e-5,
+                    dx=None, dresidual=None, want_dresidual=False, dgamma=None, dbeta=None,
+                    ws: Optional[Workspace] = None):
+    """Returns (dx, dresidual or None, dgamma, dbeta)."""
+    d = bn_desc(x, layout, eps, 0.1, relu)
+    C = d.C
+    if dx is None:
+        dx = torch.empty_like(x)
+    if dresidual is None and want_dresidual:
+        dresidual = torch.empty_like(x)
+    if dgamma is None:
+        dgamma = torch.empty(C, dtype=torch.float32, device=x.device)
+    if dbeta is None:
+        dbeta = torch.empty(C, dtype=torch.float32, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_BWD))
+    _check(lib().nsk_bn_relu_add_bwd(ctypes.byref(d), _ptr(x), _ptr(out), _ptr(dout), _ptr(gamma), _ptr(save_mean),
+                                     _ptr(save_invstd), _ptr(dx), _ptr(dresidual), _ptr(dgamma), _ptr(dbeta),
+                                     wp, wb, _stream()), "nsk_bn_relu_add_bwd")
+    return dx, dresidual, dgamma, dbeta
+
+
+def pool_desc(x: torch.Tensor, window, stride, pad, layout) -> nsk_pool_desc_t:
+    N, C, H, W = _logical(x, layout)
+    R, S = _pair(window)
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    return nsk_pool_desc_t(N, C, H, W, R, S, sh, sw, ph, pw, _dtype_code(x), layout)
+
+
+def maxpool2d_fwd(x, window=3, stride=2, pad=1, layout=NSK_NHWC, out=None, idx=None):
+    """Returns (y, idx int8)."""
+    d = pool_desc(x, window, stride, pad, layout)
+    P, Q = ctypes.c_int(), ctypes.c_int()
+    _check(lib().nsk_maxpool2d_out_dims(ctypes.byref(d), ctypes.byref(P), ctypes.byref(Q)), "nsk_maxpool2d_out_dims")
+    shape = _act_shape(d.N, d.C, P.value, Q.value, layout)
+    if out is None:
+        out = torch.empty(shape, dtype=x.dtype, device=x.device)
+    if idx is None:
+        idx = torch.empty(shape, dtype=torch.int8, device=x.device)
+    _check(lib().nsk_maxpool2d_fwd(ctypes.byref(d), _ptr(x), _ptr(out), _ptr(idx), _stream()), "nsk_maxpool2d_fwd")
+    return out, idx
+
+
+def maxpool2d_bwd(dy, idx, x_logical, window=3, stride=2, pad=1, layout=NSK_NHWC, out=None):
+    N, C, H, W = x_logical
+    R, S = _pair(window)
+    sh, sw = _pair(stride)
+    ph, pw = _pair(pad)
+    d = nsk_pool_desc_t(N, C, H, W, R, S, sh, sw, ph, pw, _dtype_code(dy), layout)
+    if out is None:
+        out = torch.empty(_act_shape(N, C, H, W, layout), dtype=dy.dtype, device=dy.device)
+    _check(lib().nsk_maxpool2d_bwd(ctypes.byref(d), _ptr(dy), _ptr(idx), _ptr(out), _stream()), "nsk_maxpool2d_bwd")
+    return out

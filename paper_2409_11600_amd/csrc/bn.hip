@@ -1,0 +1,471 @@
+// Batch-norm (batch statistics) + residual add + ReLU, forward and backward, as HBM-streaming
+// kernels.  The paper runs these element-wise steps unfused and names ReLU fusion as future work
+// (conclusion); here each direction is one statistics pass and one fused apply pass:
+//
+//   forward : stats   x -> per-block partial sums          (read x)
+//             finalize -> mean, invstd, scale, bias         (tiny)
+//             apply   out = relu?(x*scale + bias [+ res])   (read x [,res], write out)
+//   backward: reduce  dbeta, dgamma partials                (read x, out, dout)
+//             finalize -> dbeta, dgamma, coefficients       (tiny)
+//             apply   dx, dres                              (read x, out, dout; write dx [,dres])
+//
+// Statistics are accumulated in fp32 around a per-channel shift (the channel's first element), so
+// E[(x-s)^2] - E[x-s]^2 does not cancel badly, and the per-block partials are combined in fp64 in
+// a fixed order (reproducible, no atomics).
+//
+// Two code paths: a vectorised NHWC path (16-byte accesses, a thread keeps the same channels for
+// all its rows) and a generic strided path that serves NCHW and channel counts the fast path
+// cannot tile.
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+template <typename T> struct BT;
+template <> struct BT<float> {
+    static constexpr int VEC = 4;
+    typedef f32x4 Vec;
+};
+template <> struct BT<bf16_t> {
+    static constexpr int VEC = 8;
+    typedef bf16x8 Vec;
+};
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+bool nhwc_fast(const nsk_bn_desc_t &d)
+{
+    if (d.layout != NSK_NHWC) return false;
+    const int VEC = d.dtype == NSK_BF16 ? 8 : 4;
+    if (d.C % VEC) return false;
+    const int cv = d.C / VEC;
+    return cv <= 256 && 256 % cv == 0;
+}
+
+// ----------------------------------------------------------------------------- NHWC fast path
+
+// Accumulates, per channel, sum(f0) and sum(f1) over the rows of this block, where (f0,f1) is
+//   MODE 0 (forward stats):  (x - shift, (x - shift)^2)
+//   MODE 1 (backward)     :  (dz, dz * xhat)
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, const T *__restrict__ out,
+                                                      const T *__restrict__ dout, const float *__restrict__ mean,
+                                                      const float *__restrict__ invstd, int relu, long M, int C,
+                                                      long rows_per_block, float *__restrict__ p0,
+                                                      float *__restrict__ p1)
+{
+    typedef typename BT<T>::Vec Vec;
+    constexpr int VEC = BT<T>::VEC;
+    const int CV = C / VEC, RP = 256 / CV;
+    const int cv = threadIdx.x % CV, rr = threadIdx.x / CV;
+    float s0[VEC], s1[VEC], sh[VEC], sc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        s0[e] = 0.f;
+        s1[e] = 0.f;
+        if (MODE == 0) {
+            sh[e] = (float)x[cv * VEC + e];
+            sc[e] = 1.f;
+        } else {
+            sh[e] = mean[cv * VEC + e];
+            sc[e] = invstd[cv * VEC + e];
+        }
+    }
+    const long r_begin = (long)blockIdx.x * rows_per_block;
+    const long r_end = min(M, r_begin + rows_per_block);
+    for (long r = r_begin + rr; r < r_end; r += RP) {
+        const long off = r * C + cv * VEC;
+        const Vec xv = *(const Vec *)(x + off);
+        if (MODE == 0) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float dlt = (float)xv[e] - sh[e];
+                s0[e] += dlt;
+                s1[e] += dlt * dlt;
+            }
+        } else {
+            const Vec gv = *(const Vec *)(dout + off);
+            Vec ov;
+            if (relu) ov = *(const Vec *)(out + off);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                float dz = (float)gv[e];
+                if (relu && !((float)ov[e] > 0.f)) dz = 0.f;
+                s0[e] += dz;
+                s1[e] += dz * (((float)xv[e] - sh[e]) * sc[e]);
+            }
+        }
+    }
+    __shared__ float red0[256 * VEC], red1[256 * VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        red0[threadIdx.x * VEC + e] = s0[e];
+        red1[threadIdx.x * VEC + e] = s1[e];
+    }
+    __syncthreads();
+    // thread t < C sums column t over the RP row groups (row group rr holds channels at rr*C..)
+    for (int c = threadIdx.x; c < C; c += 256) {
+        float a0 = 0.f, a1 = 0.f;
+        for (int g = 0; g < RP; ++g) {
+            a0 += red0[g * C + c];
+            a1 += red1[g * C + c];
+        }
+        p0[(long)blockIdx.x * C + c] = a0;
+        p1[(long)blockIdx.x * C + c] = a1;
+    }
+}
+
+template <typename T, bool HAS_RES, bool RELU>
+__global__ __launch_bounds__(256) void bn_apply_nhwc(const T *__restrict__ x, const T *__restrict__ res,
+                                                     T *__restrict__ out, const float *__restrict__ scale,
+                                                     const float *__restrict__ bias, long nvec, int C)
+{
+    typedef typename BT<T>::Vec Vec;
+    constexpr int VEC = BT<T>::VEC;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (long)gridDim.x * 256) {
+        const int c0 = (int)((i * VEC) % C);
+        const Vec xv = *(const Vec *)(x + i * VEC);
+        Vec rv;
+        if (HAS_RES) rv = *(const Vec *)(res + i * VEC);
+        Vec ov;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            float z = (float)xv[e] * scale[c0 + e] + bias[c0 + e];
+            if (HAS_RES) z += (float)rv[e];
+            if (RELU) z = z > 0.f ? z : 0.f;
+            ov[e] = (T)z;
+        }
+        *(Vec *)(out + i * VEC) = ov;
+    }
+}
+
+// dx = a*(dz - b - xhat*cc) with a = gamma*invstd, b = dbeta/M, cc = dgamma/M ; dres = dz
+template <typename T, bool HAS_RES, bool RELU>
+__global__ __launch_bounds__(256) void bn_bwd_apply_nhwc(const T *__restrict__ x, const T *__restrict__ out,
+                                                         const T *__restrict__ dout, T *__restrict__ dx,
+                                                         T *__restrict__ dres, const float *__restrict__ mean,
+                                                         const float *__restrict__ invstd,
+                                                         const float *__restrict__ coef, long nvec, int C)
+{
+    typedef typename BT<T>::Vec Vec;
+    constexpr int VEC = BT<T>::VEC;
+    const float *ca = coef, *cb = coef + C, *cc = coef + 2 * C;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (long)gridDim.x * 256) {
+        const int c0 = (int)((i * VEC) % C);
+        const Vec xv = *(const Vec *)(x + i * VEC);
+        const Vec gv = *(const Vec *)(dout + i * VEC);
+        Vec ov;
+        if (RELU) ov = *(const Vec *)(out + i * VEC);
+        Vec dxv, drv;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const int c = c0 + e;
+            float dz = (float)gv[e];
+            if (RELU && !((float)ov[e] > 0.f)) dz = 0.f;
+            const float xhat = ((float)xv[e] - mean[c]) * invstd[c];
+            dxv[e] = (T)(ca[c] * (dz - cb[c] - xhat * cc[c]));
+            drv[e] = (T)dz;
+        }
+        *(Vec *)(dx + i * VEC) = dxv;
+        if (HAS_RES) *(Vec *)(dres + i * VEC) = drv;
+    }
+}
+
+// ----------------------------------------------------------------------------- generic strided path
+// element (n, c, s) lives at n*sn + c*sc + s*ss ; block (c, g) covers images [g*npg, (g+1)*npg)
+template <typename T, int MODE>
+__global__ __launch_bounds__(256) void bn_reduce_generic(const T *__restrict__ x, const T *__restrict__ out,
+                                                         const T *__restrict__ dout, const float *__restrict__ mean,
+                                                         const float *__restrict__ invstd, int relu, int N, long HW,
+                                                         long sn, long scs, long ss, int npg, int C,
+                                                         float *__restrict__ p0, float *__restrict__ p1)
+{
+    const int c = blockIdx.x, g = blockIdx.y;
+    const float sh = MODE == 0 ? (float)x[c * scs] : mean[c];
+    const float scl = MODE == 0 ? 1.f : invstd[c];
+    float s0 = 0.f, s1 = 0.f;
+    const int n_end = min(N, (g + 1) * npg);
+    for (int n = g * npg; n < n_end; ++n)
+        for (long s = threadIdx.x; s < HW; s += 256) {
+            const long off = n * sn + c * scs + s * ss;
+            if (MODE == 0) {
+                const float dlt = (float)x[off] - sh;
+                s0 += dlt;
+                s1 += dlt * dlt;
+            } else {
+                float dz = (float)dout[off];
+                if (relu && !((float)out[off] > 0.f)) dz = 0.f;
+                s0 += dz;
+                s1 += dz * (((float)x[off] - sh) * scl);
+            }
+        }
+    s0 = wave_sum(s0);
+    s1 = wave_sum(s1);
+    __shared__ float w0[4], w1[4];
+    if ((threadIdx.x & 63) == 0) {
+        w0[threadIdx.x >> 6] = s0;
+        w1[threadIdx.x >> 6] = s1;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        p0[(long)g * C + c] = (w0[0] + w0[1]) + (w0[2] + w0[3]);
+        p1[(long)g * C + c] = (w1[0] + w1[1]) + (w1[2] + w1[3]);
+    }
+}
+
+template <typename T, bool NCHW>
+__global__ __launch_bounds__(256) void bn_apply_generic(const T *__restrict__ x, const T *__restrict__ res,
+                                                        T *__restrict__ out, const float *__restrict__ scale,
+                                                        const float *__restrict__ bias, long total, int C, long HW,
+                                                        int relu)
+{
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int c = NCHW ? (int)((i / HW) % C) : (int)(i % C);
+        float z = (float)x[i] * scale[c] + bias[c];
+        if (res) z += (float)res[i];
+        if (relu) z = z > 0.f ? z : 0.f;
+        out[i] = (T)z;
+    }
+}
+
+template <typename T, bool NCHW>
+__global__ __launch_bounds__(256) void bn_bwd_apply_generic(const T *__restrict__ x, const T *__restrict__ out,
+                                                            const T *__restrict__ dout, T *__restrict__ dx,
+                                                            T *__restrict__ dres, const float *__restrict__ mean,
+                                                            const float *__restrict__ invstd,
+                                                            const float *__restrict__ coef, long total, int C,
+                                                            long HW, int relu)
+{
+    const float *ca = coef, *cb = coef + C, *cc = coef + 2 * C;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int c = NCHW ? (int)((i / HW) % C) : (int)(i % C);
+        float dz = (float)dout[i];
+        if (relu && !((float)out[i] > 0.f)) dz = 0.f;
+        const float xhat = ((float)x[i] - mean[c]) * invstd[c];
+        dx[i] = (T)(ca[c] * (dz - cb[c] - xhat * cc[c]));
+        if (dres) dres[i] = (T)dz;
+    }
+}
+
+// ----------------------------------------------------------------------------- finalize (tiny)
+template <typename T>
+__global__ void bn_fwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
+                                const T *__restrict__ x, long shift_stride, const float *__restrict__ gamma,
+                                const float *__restrict__ beta, float eps, float momentum,
+                                float *__restrict__ save_mean, float *__restrict__ save_invstd,
+                                float *__restrict__ running_mean, float *__restrict__ running_var,
+                                float *__restrict__ scale, float *__restrict__ bias)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double S = 0.0, Q = 0.0;
+    for (int g = 0; g < G; ++g) {
+        S += (double)p0[(long)g * C + c];
+        Q += (double)p1[(long)g * C + c];
+    }
+    const double ms = S / M;
+    double var = Q / M - ms * ms;
+    if (var < 0.0) var = 0.0;
+    const double mean = (double)(float)x[c * shift_stride] + ms;
+    const double invstd = 1.0 / sqrt(var + (double)eps);
+    save_mean[c] = (float)mean;
+    save_invstd[c] = (float)invstd;
+    const double sc = (double)gamma[c] * invstd;
+    scale[c] = (float)sc;
+    bias[c] = (float)((double)beta[c] - mean * sc);
+    if (running_mean) {
+        const double unbiased = M > 1.0 ? var * M / (M - 1.0) : var;
+        running_mean[c] = (float)((1.0 - (double)momentum) * (double)running_mean[c] + (double)momentum * mean);
+        running_var[c] = (float)((1.0 - (double)momentum) * (double)running_var[c] + (double)momentum * unbiased);
+    }
+}
+
+__global__ void bn_bwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
+                                const float *__restrict__ gamma, const float *__restrict__ invstd,
+                                float *__restrict__ dgamma, float *__restrict__ dbeta, float *__restrict__ coef)
+{
+    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    if (c >= C) return;
+    double S = 0.0, Q = 0.0;
+    for (int g = 0; g < G; ++g) {
+        S += (double)p0[(long)g * C + c];
+        Q += (double)p1[(long)g * C + c];
+    }
+    dbeta[c] = (float)S;
+    dgamma[c] = (float)Q;
+    coef[c] = gamma[c] * invstd[c];
+    coef[C + c] = (float)(S / M);
+    coef[2 * C + c] = (float)(Q / M);
+}
+
+struct Geom {
+    long M, HW, total;
+    int G;
+    bool fast;
+    long rows_per_block;  // fast path
+    int npg;              // generic path: images per partial block
+    long sn, sc, ss;
+};
+
+Geom geometry(const nsk_bn_desc_t &d)
+{
+    Geom g;
+    g.HW = (long)d.H * d.W;
+    g.M = (long)d.N * g.HW;
+    g.total = g.M * d.C;
+    g.fast = nhwc_fast(d);
+    if (g.fast) {
+        const int VEC = d.dtype == NSK_BF16 ? 8 : 4;
+        const int RP = 256 / (d.C / VEC);
+        long G = (g.M + (long)RP * 8 - 1) / ((long)RP * 8);
+        if (G > 1024) G = 1024;
+        if (G < 1) G = 1;
+        g.rows_per_block = (g.M + G - 1) / G;
+        g.G = (int)((g.M + g.rows_per_block - 1) / g.rows_per_block);
+        g.npg = 0;
+    } else {
+        int G = 1024 / d.C;
+        if (G < 1) G = 1;
+        if (G > d.N) G = d.N;
+        g.npg = ceil_div(d.N, G);
+        g.G = ceil_div(d.N, g.npg);
+        g.rows_per_block = 0;
+    }
+    if (d.layout == NSK_NCHW) {
+        g.sn = (long)d.C * g.HW;
+        g.sc = g.HW;
+        g.ss = 1;
+    } else {
+        g.sn = g.HW * d.C;
+        g.sc = 1;
+        g.ss = d.C;
+    }
+    return g;
+}
+
+int stream_blocks(long work_items)
+{
+    long b = (work_items + 255) / 256;
+    const long cap = 256 * 16;  // 16 blocks per CU keep every CU streaming
+    if (b > cap) b = cap;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+template <typename T>
+int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *gamma, const float *beta, T *out,
+                 float *save_mean, float *save_invstd, float *running_mean, float *running_var, float *ws,
+                 hipStream_t stream)
+{
+    const Geom g = geometry(d);
+    float *p0 = ws, *p1 = ws + (long)g.G * d.C, *scale = p1 + (long)g.G * d.C, *bias = scale + d.C;
+    constexpr int VEC = BT<T>::VEC;
+    if (g.fast) {
+        hipLaunchKernelGGL((bn_reduce_nhwc<T, 0>), dim3(g.G), dim3(256), 0, stream, x, (const T *)nullptr,
+                           (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, g.M, d.C,
+                           g.rows_per_block, p0, p1);
+    } else {
+        hipLaunchKernelGGL((bn_reduce_generic<T, 0>), dim3(d.C, g.G), dim3(256), 0, stream, x, (const T *)nullptr,
+                           (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, d.N, g.HW, g.sn,
+                           g.sc, g.ss, g.npg, d.C, p0, p1);
+    }
+    hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 256)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+                       (double)g.M, x, g.sc, gamma, beta, d.eps, d.momentum, save_mean, save_invstd, running_mean,
+                       running_var, scale, bias);
+    if (g.fast) {
+        const long nvec = g.total / VEC;
+        const dim3 grid(stream_blocks(nvec));
+#define NSK_APPLY(R, L) \
+    hipLaunchKernelGGL((bn_apply_nhwc<T, R, L>), grid, dim3(256), 0, stream, x, res, out, scale, bias, nvec, d.C)
+        if (res) {
+            if (d.relu) NSK_APPLY(true, true); else NSK_APPLY(true, false);
+        } else {
+            if (d.relu) NSK_APPLY(false, true); else NSK_APPLY(false, false);
+        }
+#undef NSK_APPLY
+    } else {
+        const dim3 grid(stream_blocks(g.total));
+        if (d.layout == NSK_NCHW)
+            hipLaunchKernelGGL((bn_apply_generic<T, true>), grid, dim3(256), 0, stream, x, res, out, scale, bias,
+                               g.total, d.C, g.HW, d.relu);
+        else
+            hipLaunchKernelGGL((bn_apply_generic<T, false>), grid, dim3(256), 0, stream, x, res, out, scale, bias,
+                               g.total, d.C, g.HW, d.relu);
+    }
+    return check_launch();
+}
+
+template <typename T>
+int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout, const float *gamma,
+                 const float *mean, const float *invstd, T *dx, T *dres, float *dgamma, float *dbeta, float *ws,
+                 hipStream_t stream)
+{
+    const Geom g = geometry(d);
+    float *p0 = ws, *p1 = ws + (long)g.G * d.C, *coef = p1 + (long)g.G * d.C;
+    constexpr int VEC = BT<T>::VEC;
+    if (g.fast) {
+        hipLaunchKernelGGL((bn_reduce_nhwc<T, 1>), dim3(g.G), dim3(256), 0, stream, x, out, dout, mean, invstd,
+                           d.relu, g.M, d.C, g.rows_per_block, p0, p1);
+    } else {
+        hipLaunchKernelGGL((bn_reduce_generic<T, 1>), dim3(d.C, g.G), dim3(256), 0, stream, x, out, dout, mean,
+                           invstd, d.relu, d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1);
+    }
+    hipLaunchKernelGGL(bn_bwd_finalize, dim3(ceil_div(d.C, 256)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+                       (double)g.M, gamma, invstd, dgamma, dbeta, coef);
+    if (g.fast) {
+        const long nvec = g.total / VEC;
+        const dim3 grid(stream_blocks(nvec));
+#define NSK_BAPPLY(R, L)                                                                                       \
+    hipLaunchKernelGGL((bn_bwd_apply_nhwc<T, R, L>), grid, dim3(256), 0, stream, x, out, dout, dx, dres, mean, \
+                       invstd, coef, nvec, d.C)
+        if (dres) {
+            if (d.relu) NSK_BAPPLY(true, true); else NSK_BAPPLY(true, false);
+        } else {
+            if (d.relu) NSK_BAPPLY(false, true); else NSK_BAPPLY(false, false);
+        }
+#undef NSK_BAPPLY
+    } else {
+        const dim3 grid(stream_blocks(g.total));
+        if (d.layout == NSK_NCHW)
+            hipLaunchKernelGGL((bn_bwd_apply_generic<T, true>), grid, dim3(256), 0, stream, x, out, dout, dx, dres,
+                               mean, invstd, coef, g.total, d.C, g.HW, d.relu);
+        else
+            hipLaunchKernelGGL((bn_bwd_apply_generic<T, false>), grid, dim3(256), 0, stream, x, out, dout, dx, dres,
+                               mean, invstd, coef, g.total, d.C, g.HW, d.relu);
+    }
+    return check_launch();
+}
+
+}  // namespace
+
+int bn_partial_blocks(const nsk_bn_desc_t &d) { return geometry(d).G; }
+
+int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
+                  const float *beta, void *out, float *save_mean, float *save_invstd, float *running_mean,
+                  float *running_var, void *ws, hipStream_t stream)
+{
+    if (d.dtype == NSK_BF16)
+        return bn_fwd_typed<bf16_t>(d, (const bf16_t *)x, (const bf16_t *)residual, gamma, beta, (bf16_t *)out,
+                                    save_mean, save_invstd, running_mean, running_var, (float *)ws, stream);
+    return bn_fwd_typed<float>(d, (const float *)x, (const float *)residual, gamma, beta, (float *)out, save_mean,
+                               save_invstd, running_mean, running_var, (float *)ws, stream);
+}
+
+int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout, const float *gamma,
+                  const float *save_mean, const float *save_invstd, void *dx, void *dres, float *dgamma,
+                  float *dbeta, void *ws, hipStream_t stream)
+{
+    if (d.dtype == NSK_BF16)
+        return bn_bwd_typed<bf16_t>(d, (const bf16_t *)x, (const bf16_t *)out, (const bf16_t *)dout, gamma,
+                                    save_mean, save_invstd, (bf16_t *)dx, (bf16_t *)dres, dgamma, dbeta,
+                                    (float *)ws, stream);
+    return bn_bwd_typed<float>(d, (const float *)x, (const float *)out, (const float *)dout, gamma, save_mean,
+                               save_invstd, (float *)dx, (float *)dres, dgamma, dbeta, (float *)ws, stream);
+}
+
+}  // namespace nsk

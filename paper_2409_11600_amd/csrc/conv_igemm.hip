@@ -1,0 +1,268 @@
+// Implicit-GEMM convolution on the MFMA units of gfx950: the kernel behind conv forward and
+// backward-data (both are "gather a shifted activation tile, multiply by a packed filter").
+//
+// GEMM view (the forward pass of a convolution layer of the ResNet recipe the paper trains,
+// section "Experiments and Discussion"): rows m = output pixels, columns n = output channels,
+// reduction k = (filter tap, input channel).  In NHWC each tap is a contiguous run of channels,
+// so a k-tile is fetched with 16-byte loads and no im2col buffer ever exists in memory.
+//
+// Work decomposition: 256 threads = 4 wavefronts per block, block tile BM x BN, k-tile of 64
+// bytes per row.  Tiles are staged through LDS (rows padded to 80 bytes so the 16-byte fragment
+// reads of 8 consecutive lanes cover all 32 banks once) with register prefetch of the next
+// k-tile and two LDS buffers, so one barrier per k-tile suffices.  Each wavefront owns a
+// WM x WN sub-tile made of 32x32 MFMA accumulators.
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+template <typename T> struct Traits;
+template <> struct Traits<float> {
+    static constexpr int VEC = 4, BK = 16, LDK = 20;
+    typedef f32x4 Vec;
+};
+template <> struct Traits<bf16_t> {
+    static constexpr int VEC = 8, BK = 32, LDK = 40;
+    typedef bf16x8 Vec;
+};
+
+template <typename Vec> __device__ inline Vec zero_vec()
+{
+    Vec v;
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(Vec) / sizeof(v[0])); ++i) v[i] = 0;
+    return v;
+}
+
+__device__ inline float to_float(float v) { return v; }
+__device__ inline float to_float(bf16_t v) { return (float)v; }
+
+template <typename T, int BM, int BN, int WM, int WN, bool VECLOAD>
+__global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
+{
+    typedef Traits<T> TR;
+    typedef typename TR::Vec Vec;
+    constexpr int VEC = TR::VEC, BK = TR::BK, LDK = TR::LDK;
+    constexpr int WAVES_N = BN / WN;
+    static_assert((BM / WM) * WAVES_N == 4, "four wavefronts per block");
+    constexpr int FM = WM / 32, FN = WN / 32;
+    constexpr int A_PASSES = BM / 64;
+    constexpr int B_PASSES = (BN + 63) / 64;
+
+    __shared__ __attribute__((aligned(16))) T As[2][BM * LDK];
+    __shared__ __attribute__((aligned(16))) T Bs[2][BN * LDK];
+    __shared__ long out_off[BM];
+    __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const int m0 = blockIdx.x * BM;
+    const int n0 = blockIdx.y * BN;
+
+    if (tid < kMaxTaps) {
+        s_offh[tid] = a.off_h[tid];
+        s_offw[tid] = a.off_w[tid];
+    }
+
+    const T *__restrict__ src = (const T *)a.src;
+    const T *__restrict__ wpk = (const T *)a.wpk;
+
+    // Each thread gathers the same rows in every k-tile: decode them once.
+    const int kv = tid & 3;   // which 16-byte vector of the k-tile row
+    const int r0 = tid >> 2;  // row within a pass of 64 rows
+    int a_img[A_PASSES], a_bh[A_PASSES], a_bw[A_PASSES];
+    bool a_ok[A_PASSES];
+#pragma unroll
+    for (int u = 0; u < A_PASSES; ++u) {
+        const int row = r0 + 64 * u;
+        const int m = m0 + row;
+        a_ok[u] = m < a.M;
+        const int mm = a_ok[u] ? m : 0;
+        const int per_img = a.Mi * a.Mj;
+        const int img = mm / per_img;
+        const int rem = mm - img * per_img;
+        const int i = rem / a.Mj;
+        const int j = rem - i * a.Mj;
+        a_img[u] = img * a.Hs;
+        a_bh[u] = i * a.mult_h + a.add_h;
+        a_bw[u] = j * a.mult_w + a.add_w;
+        if (kv == 0)
+            out_off[row] = a_ok[u] ? (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co
+                                   : -1L;
+    }
+    __syncthreads();
+
+    Vec ra[A_PASSES], rb[B_PASSES];
+    int cur_tap = 0, cur_c = kv * VEC;  // position of this thread's vector inside (tap, channel)
+    if (VECLOAD) {
+        while (cur_c >= a.Cs && cur_tap < a.ntaps) {
+            cur_c -= a.Cs;
+            ++cur_tap;
+        }
+    }
+
+    auto load_tile = [&](int kt) {
+        const int kk = kt * BK + kv * VEC;
+        if (VECLOAD) {
+            const bool kok = kk < a.Ktot;
+            const int oh = kok ? s_offh[cur_tap] : 0, ow = kok ? s_offw[cur_tap] : 0;
+#pragma unroll
+            for (int u = 0; u < A_PASSES; ++u) {
+                const int h = a_bh[u] + oh, w = a_bw[u] + ow;
+                const bool ok = kok && a_ok[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
+                ra[u] = ok ? *(const Vec *)(src + ((long)(a_img[u] + h) * a.Ws + w) * a.Cs + cur_c) : zero_vec<Vec>();
+            }
+#pragma unroll
+            for (int u = 0; u < B_PASSES; ++u) {
+                const int row = r0 + 64 * u;
+                const int n = n0 + row;
+                const bool ok = kok && row < BN && n < a.Ngemm;
+                rb[u] = ok ? *(const Vec *)(wpk + (long)n * a.Ktot + kk) : zero_vec<Vec>();
+            }
+            // advance to the next k-tile
+            cur_c += BK;
+            while (cur_c >= a.Cs && cur_tap < a.ntaps) {
+                cur_c -= a.Cs;
+                ++cur_tap;
+            }
+        } else {
+            // Element-wise gather for channel counts that are not a multiple of the vector width
+            // (the 3-channel image stem).
+#pragma unroll
+            for (int u = 0; u < A_PASSES; ++u) ra[u] = zero_vec<Vec>();
+#pragma unroll
+            for (int u = 0; u < B_PASSES; ++u) rb[u] = zero_vec<Vec>();
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const int k = kk + e;
+                if (k < a.Ktot) {
+                    const int tap = k / a.Cs;
+                    const int c = k - tap * a.Cs;
+                    const int oh = s_offh[tap], ow = s_offw[tap];
+#pragma unroll
+                    for (int u = 0; u < A_PASSES; ++u) {
+                        const int h = a_bh[u] + oh, w = a_bw[u] + ow;
+                        const bool ok = a_ok[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
+                        if (ok) ra[u][e] = src[((long)(a_img[u] + h) * a.Ws + w) * a.Cs + c];
+                    }
+#pragma unroll
+                    for (int u = 0; u < B_PASSES; ++u) {
+                        const int row = r0 + 64 * u;
+                        const int n = n0 + row;
+                        if (row < BN && n < a.Ngemm) rb[u][e] = wpk[(long)n * a.Ktot + k];
+                    }
+                }
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < A_PASSES; ++u) *(Vec *)&As[buf][(r0 + 64 * u) * LDK + kv * VEC] = ra[u];
+#pragma unroll
+        for (int u = 0; u < B_PASSES; ++u) {
+            const int row = r0 + 64 * u;
+            if (row < BN) *(Vec *)&Bs[buf][row * LDK + kv * VEC] = rb[u];
+        }
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+    const int nk = (a.Ktot + BK - 1) / BK;
+    const int frow = lane & 31, fk = lane >> 5;
+    if (nk > 0) {
+        load_tile(0);
+        store_tile(0);
+    }
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nk) load_tile(kt + 1);
+        const T *pa = &As[buf][(wm * WM + frow) * LDK + fk * VEC];
+        const T *pb = &Bs[buf][(wn * WN + frow) * LDK + fk * VEC];
+#pragma unroll
+        for (int ks = 0; ks < BK; ks += 2 * VEC) {
+            Vec af[FM], bfv[FN];
+#pragma unroll
+            for (int mi = 0; mi < FM; ++mi) af[mi] = *(const Vec *)(pa + mi * 32 * LDK + ks);
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni) bfv[ni] = *(const Vec *)(pb + ni * 32 * LDK + ks);
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+                    for (int ni = 0; ni < FN; ++ni)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfv[ni], acc[mi][ni], 0, 0, 0);
+            } else {
+                // Lane (row, half) holds k = 4*half + t of this group of 8; the same map is used
+                // for both operands, so the four steps together cover the 8 k exactly once.
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < FN; ++ni)
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bfv[ni][t], acc[mi][ni], 0, 0, 0);
+            }
+        }
+        if (kt + 1 < nk) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // Accumulator element v of a 32x32 tile sits at row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+    T *__restrict__ out = (T *)a.out;
+#pragma unroll
+    for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = wm * WM + mi * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+            const long off = out_off[row];
+            if (off < 0) continue;
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni) {
+                const int col = n0 + wn * WN + ni * 32 + frow;
+                if (col < a.Ngemm) {
+                    float r = acc[mi][ni][v];
+                    if (a.accumulate) r += to_float(out[off + col]);
+                    out[off + col] = (T)r;
+                }
+            }
+        }
+}
+
+template <typename T, int BM, int BN, int WM, int WN>
+int launch_tile(const IgemmArgs &a, bool vec, hipStream_t stream)
+{
+    dim3 grid(ceil_div(a.M, BM), ceil_div(a.Ngemm, BN));
+    if (vec)
+        hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, true>), grid, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, false>), grid, dim3(256), 0, stream, a);
+    return check_launch();
+}
+
+template <typename T> int launch_typed(const IgemmArgs &a, hipStream_t stream)
+{
+    constexpr int VEC = Traits<T>::VEC;
+    const bool vec = a.Cs % VEC == 0 && a.Ktot % VEC == 0 && ((uintptr_t)a.src % 16 == 0) && ((uintptr_t)a.wpk % 16 == 0);
+    if (a.Ngemm <= 32) return launch_tile<T, 256, 32, 64, 32>(a, vec, stream);
+    if (a.Ngemm <= 64) return launch_tile<T, 256, 64, 64, 64>(a, vec, stream);
+    return launch_tile<T, 128, 128, 64, 64>(a, vec, stream);
+}
+
+}  // namespace
+
+int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
+{
+    if (a.M <= 0 || a.Ngemm <= 0) return NSK_OK;
+    return dtype == NSK_BF16 ? launch_typed<bf16_t>(a, stream) : launch_typed<float>(a, stream);
+}
+
+}  // namespace nsk

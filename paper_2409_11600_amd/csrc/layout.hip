@@ -1,0 +1,105 @@
+// Layout helpers at the library boundary: the kernels compute in NHWC / "filter row = all taps of
+// one output channel"; callers that hold NCHW / KCRS tensors are served by these copies through
+// the workspace.  Pure data movement, bounded by HBM bandwidth.
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+// Per image: src [rows][cols] -> dst [cols][rows], 32x32 tiles through LDS (padded by one
+// column so the transposed reads are conflict-free).  accumulate adds into dst.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_kernel(const T *__restrict__ src, T *__restrict__ dst, int rows,
+                                                        int cols, int accumulate)
+{
+    __shared__ float tile[32][33];
+    const long img = blockIdx.z;
+    src += img * rows * cols;
+    dst += img * rows * cols;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int r = r0 + ty + i, c = c0 + tx;
+        if (r < rows && c < cols) tile[ty + i][tx] = (float)src[(long)r * cols + c];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 32; i += 8) {
+        const int c = c0 + ty + i, r = r0 + tx;
+        if (r < rows && c < cols) {
+            float v = tile[tx][ty + i];
+            T *o = dst + (long)c * rows + r;
+            if (accumulate) v += (float)*o;
+            *o = (T)v;
+        }
+    }
+}
+
+struct PackArgs {
+    const void *w;
+    void *out;
+    int Nn, ntaps, Cs;
+    long sn, sc;
+    int tap_off[kMaxTaps];
+};
+
+template <typename T> __global__ __launch_bounds__(256) void pack_filter_kernel(const PackArgs a)
+{
+    const long total = (long)a.Nn * a.ntaps * a.Cs;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % a.Cs);
+    const long r = i / a.Cs;
+    const int t = (int)(r % a.ntaps);
+    const long n = r / a.ntaps;
+    ((T *)a.out)[i] = ((const T *)a.w)[n * a.sn + a.tap_off[t] + c * a.sc];
+}
+
+template <typename T>
+int transpose_typed(const void *src, void *dst, int batch, int rows, int cols, int accumulate, hipStream_t stream)
+{
+    dim3 grid(ceil_div(cols, 32), ceil_div(rows, 32), batch);
+    hipLaunchKernelGGL((transpose_kernel<T>), grid, dim3(256), 0, stream, (const T *)src, (T *)dst, rows, cols,
+                       accumulate);
+    return check_launch();
+}
+
+}  // namespace
+
+int launch_nchw_to_nhwc(int dtype, const void *src, void *dst, int N, int C, int H, int W, hipStream_t stream)
+{
+    if (dtype == NSK_BF16) return transpose_typed<bf16_t>(src, dst, N, C, H * W, 0, stream);
+    return transpose_typed<float>(src, dst, N, C, H * W, 0, stream);
+}
+
+int launch_nhwc_to_nchw(int dtype, const void *src, void *dst, int N, int C, int H, int W, int accumulate,
+                        hipStream_t stream)
+{
+    if (dtype == NSK_BF16) return transpose_typed<bf16_t>(src, dst, N, H * W, C, accumulate, stream);
+    return transpose_typed<float>(src, dst, N, H * W, C, accumulate, stream);
+}
+
+int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, int Cs, long sn, long sc,
+                       const int *tap_off_host, hipStream_t stream)
+{
+    PackArgs a;
+    a.w = w;
+    a.out = out;
+    a.Nn = Nn;
+    a.ntaps = ntaps;
+    a.Cs = Cs;
+    a.sn = sn;
+    a.sc = sc;
+    for (int t = 0; t < kMaxTaps; ++t) a.tap_off[t] = t < ntaps ? tap_off_host[t] : 0;
+    const long total = (long)Nn * ntaps * Cs;
+    if (total == 0) return NSK_OK;
+    dim3 grid((unsigned)((total + 255) / 256));
+    if (dtype == NSK_BF16)
+        hipLaunchKernelGGL((pack_filter_kernel<bf16_t>), grid, dim3(256), 0, stream, a);
+    else
+        hipLaunchKernelGGL((pack_filter_kernel<float>), grid, dim3(256), 0, stream, a);
+    return check_launch();
+}
+
+}  // namespace nsk

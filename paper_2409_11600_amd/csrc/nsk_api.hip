@@ -1,0 +1,414 @@
+// The C ABI of libnsk: host-side validation, workspace planning and dispatch to the kernels.
+// Every check that can be made without touching the device is made before the first HIP call, so
+// the error paths behave identically on a machine without a GPU.
+#include <limits.h>
+
+#include "nsk_internal.h"
+
+namespace nsk {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+
+namespace {
+
+struct ConvGeo {
+    int N, C, H, W, K, R, S, sh, sw, ph, pw, dh, dw, P, Q;
+    int dtype, layout;
+    size_t es;
+    size_t x_elems, y_elems, w_elems;
+};
+
+int out_extent(int in, int pad, int dil, int filt, int stride)
+{
+    const long span = (long)in + 2L * pad - (long)dil * (filt - 1) - 1;
+    return span < 0 ? 0 : (int)(span / stride + 1);
+}
+
+// NSK_OK, NSK_ERR_NULL, NSK_ERR_BAD_DESC or NSK_ERR_UNSUPPORTED.  `need_output`: an empty output
+// (P or Q = 0) is a bad descriptor for the compute calls, but legal for the extent query.
+int conv_geometry(const nsk_conv_desc_t *d, ConvGeo *g, bool need_output)
+{
+    if (!d) return NSK_ERR_NULL;
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->K < 1 || d->R < 1 || d->S < 1) return NSK_ERR_BAD_DESC;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->dil_h < 1 || d->dil_w < 1) return NSK_ERR_BAD_DESC;
+    if (d->pad_h < 0 || d->pad_w < 0) return NSK_ERR_BAD_DESC;
+    if (d->dtype != NSK_F32 && d->dtype != NSK_BF16) return NSK_ERR_BAD_DESC;
+    if (d->layout != NSK_NCHW && d->layout != NSK_NHWC) return NSK_ERR_BAD_DESC;
+    g->N = d->N; g->C = d->C; g->H = d->H; g->W = d->W; g->K = d->K; g->R = d->R; g->S = d->S;
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w; g->dh = d->dil_h; g->dw = d->dil_w;
+    g->dtype = d->dtype; g->layout = d->layout; g->es = elem_size(d->dtype);
+    g->P = out_extent(d->H, d->pad_h, d->dil_h, d->R, d->stride_h);
+    g->Q = out_extent(d->W, d->pad_w, d->dil_w, d->S, d->stride_w);
+    if (!need_output) return NSK_OK;
+    if (g->P < 1 || g->Q < 1) return NSK_ERR_BAD_DESC;
+    // Limits of this build: pixel counts index with 32-bit ints, tap tables hold 64 entries with
+    // 16-bit offsets, NCHW conversion puts the batch on gridDim.z.
+    const long long pix_in = (long long)d->N * d->H * d->W, pix_out = (long long)d->N * g->P * g->Q;
+    if (pix_in >= INT_MAX || pix_out >= INT_MAX) return NSK_ERR_UNSUPPORTED;
+    if ((long long)d->R * d->S > kMaxTaps) return NSK_ERR_UNSUPPORTED;
+    if ((long long)(d->R - 1) * d->dil_h > 30000 || (long long)(d->S - 1) * d->dil_w > 30000) return NSK_ERR_UNSUPPORTED;
+    if ((long long)d->K * d->R * d->S * d->C >= INT_MAX) return NSK_ERR_UNSUPPORTED;
+    if (d->layout == NSK_NCHW && d->N > 65535) return NSK_ERR_UNSUPPORTED;
+    g->x_elems = (size_t)pix_in * d->C;
+    g->y_elems = (size_t)pix_out * d->K;
+    g->w_elems = (size_t)d->K * d->R * d->S * d->C;
+    return NSK_OK;
+}
+
+// Workspace segments (byte offsets, each 256-aligned).
+struct ConvPlan {
+    size_t act_in = 0;   // NHWC copy of the NCHW input activation (x or dy)
+    size_t act_in2 = 0;  // wgrad only: NHWC copy of dy
+    size_t filt = 0;     // packed filter
+    size_t act_out = 0;  // NHWC result before conversion to NCHW
+    size_t part = 0;     // wgrad partial sums
+    size_t total = 0;
+    int splits = 1, rows_per_split = 0;
+};
+
+ConvPlan plan_conv(const ConvGeo &g, int pass)
+{
+    ConvPlan p;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += align_up(bytes);
+        return at;
+    };
+    const bool nchw = g.layout == NSK_NCHW;
+    if (pass == NSK_PASS_FWD) {
+        if (nchw) {
+            p.act_in = take(g.x_elems * g.es);
+            p.filt = take(g.w_elems * g.es);
+            p.act_out = take(g.y_elems * g.es);
+        }
+    } else if (pass == NSK_PASS_DGRAD) {
+        if (nchw) p.act_in = take(g.y_elems * g.es);
+        // one packed filter per stride parity class; together they hold every tap once
+        p.filt = take(g.w_elems * g.es + 256 * (size_t)g.sh * g.sw);
+        if (nchw) p.act_out = take(g.x_elems * g.es);
+    } else {
+        if (nchw) {
+            p.act_in = take(g.x_elems * g.es);
+            p.act_in2 = take(g.y_elems * g.es);
+        }
+        p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, &p.splits);
+        p.part = take((size_t)p.splits * g.w_elems * sizeof(float));
+    }
+    p.total = off;
+    return p;
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15) != 0; }
+
+int check_ws(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return NSK_OK;
+    if (!ws || have < need) return NSK_ERR_WORKSPACE;
+    if (misaligned(ws)) return NSK_ERR_ALIGNMENT;
+    return NSK_OK;
+}
+
+#define NSK_TRY(expr)                 \
+    do {                              \
+        const int st__ = (expr);      \
+        if (st__ != NSK_OK) return st__; \
+    } while (0)
+
+int bn_geometry(const nsk_bn_desc_t *d)
+{
+    if (!d) return NSK_ERR_NULL;
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1) return NSK_ERR_BAD_DESC;
+    if (d->dtype != NSK_F32 && d->dtype != NSK_BF16) return NSK_ERR_BAD_DESC;
+    if (d->layout != NSK_NCHW && d->layout != NSK_NHWC) return NSK_ERR_BAD_DESC;
+    if (!(d->eps >= 0.f) || !(d->momentum >= 0.f && d->momentum <= 1.f)) return NSK_ERR_BAD_DESC;
+    if (d->relu != 0 && d->relu != 1) return NSK_ERR_BAD_DESC;
+    if (d->C > 65535) return NSK_ERR_UNSUPPORTED;
+    return NSK_OK;
+}
+
+int pool_geometry(const nsk_pool_desc_t *d, int *P, int *Q)
+{
+    if (!d) return NSK_ERR_NULL;
+    if (d->N < 1 || d->C < 1 || d->H < 1 || d->W < 1 || d->R < 1 || d->S < 1) return NSK_ERR_BAD_DESC;
+    if (d->stride_h < 1 || d->stride_w < 1 || d->pad_h < 0 || d->pad_w < 0) return NSK_ERR_BAD_DESC;
+    if (d->dtype != NSK_F32 && d->dtype != NSK_BF16) return NSK_ERR_BAD_DESC;
+    if (d->layout != NSK_NCHW && d->layout != NSK_NHWC) return NSK_ERR_BAD_DESC;
+    if ((long)d->R * d->S > 127) return NSK_ERR_UNSUPPORTED;
+    *P = out_extent(d->H, d->pad_h, 1, d->R, d->stride_h);
+    *Q = out_extent(d->W, d->pad_w, 1, d->S, d->stride_w);
+    return NSK_OK;
+}
+
+}  // namespace
+}  // namespace nsk
+
+using namespace nsk;
+
+extern "C" {
+
+int nsk_version(void) { return 100; }
+
+const char *nsk_status_string(int status)
+{
+    switch (status) {
+    case NSK_OK: return "ok";
+    case NSK_ERR_NULL: return "a required pointer is NULL";
+    case NSK_ERR_BAD_DESC: return "descriptor field out of range or empty output";
+    case NSK_ERR_UNSUPPORTED: return "valid request not supported by this build";
+    case NSK_ERR_WORKSPACE: return "workspace missing or too small";
+    case NSK_ERR_ALIGNMENT: return "pointer not 16-byte aligned";
+    case NSK_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int nsk_last_hip_error(void) { return g_last_hip_error; }
+
+int nsk_conv2d_out_dims(const nsk_conv_desc_t *desc, int *P, int *Q)
+{
+    if (!desc || !P || !Q) return NSK_ERR_NULL;
+    ConvGeo g;
+    NSK_TRY(conv_geometry(desc, &g, false));
+    *P = g.P;
+    *Q = g.Q;
+    return NSK_OK;
+}
+
+size_t nsk_conv2d_workspace_bytes(const nsk_conv_desc_t *desc, int pass)
+{
+    ConvGeo g;
+    if (pass < NSK_PASS_FWD || pass > NSK_PASS_WGRAD) return 0;
+    if (conv_geometry(desc, &g, true) != NSK_OK) return 0;
+    return plan_conv(g, pass).total;
+}
+
+int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, void *workspace,
+                   size_t workspace_bytes, void *stream)
+{
+    ConvGeo g;
+    NSK_TRY(conv_geometry(desc, &g, true));
+    if (!x || !w || !y) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(w) || misaligned(y)) return NSK_ERR_ALIGNMENT;
+    const ConvPlan p = plan_conv(g, NSK_PASS_FWD);
+    NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+
+    const void *src = x, *filt = w;
+    void *dst = y;
+    if (g.layout == NSK_NCHW) {
+        NSK_TRY(launch_nchw_to_nhwc(g.dtype, x, ws + p.act_in, g.N, g.C, g.H, g.W, st));
+        int tap_off[kMaxTaps];
+        for (int t = 0; t < g.R * g.S; ++t) tap_off[t] = t;
+        NSK_TRY(launch_pack_filter(g.dtype, w, ws + p.filt, g.K, g.R * g.S, g.C, (long)g.C * g.R * g.S,
+                                   (long)g.R * g.S, tap_off, st));
+        src = ws + p.act_in;
+        filt = ws + p.filt;
+        dst = ws + p.act_out;
+    }
+    IgemmArgs a{};
+    a.src = src; a.wpk = filt; a.out = dst;
+    a.Nimg = g.N; a.Hs = g.H; a.Ws = g.W; a.Cs = g.C;
+    a.Mi = g.P; a.Mj = g.Q; a.M = g.N * g.P * g.Q;
+    a.mult_h = g.sh; a.add_h = -g.ph; a.mult_w = g.sw; a.add_w = -g.pw;
+    a.ntaps = g.R * g.S; a.Ktot = a.ntaps * g.C;
+    a.Ngemm = g.K;
+    a.Ho = g.P; a.Wo = g.Q; a.Co = g.K; a.osh = 1; a.oa = 0; a.osw = 1; a.ob = 0;
+    a.accumulate = 0;
+    for (int r = 0; r < g.R; ++r)
+        for (int s = 0; s < g.S; ++s) {
+            a.off_h[r * g.S + s] = (short)(r * g.dh);
+            a.off_w[r * g.S + s] = (short)(s * g.dw);
+        }
+    NSK_TRY(launch_igemm(g.dtype, a, st));
+    if (g.layout == NSK_NCHW) NSK_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));
+    return NSK_OK;
+}
+
+int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w, void *dx, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    ConvGeo g;
+    NSK_TRY(conv_geometry(desc, &g, true));
+    if (!dy || !w || !dx) return NSK_ERR_NULL;
+    if (accumulate != 0 && accumulate != 1) return NSK_ERR_BAD_DESC;
+    if (misaligned(dy) || misaligned(w) || misaligned(dx)) return NSK_ERR_ALIGNMENT;
+    const ConvPlan p = plan_conv(g, NSK_PASS_DGRAD);
+    NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const bool nchw = g.layout == NSK_NCHW;
+
+    const void *src = dy;
+    void *dst = dx;
+    int acc_kernel = accumulate;
+    if (nchw) {
+        NSK_TRY(launch_nchw_to_nhwc(g.dtype, dy, ws + p.act_in, g.N, g.K, g.P, g.Q, st));
+        src = ws + p.act_in;
+        dst = ws + p.act_out;
+        acc_kernel = 0;  // the conversion back to NCHW does the add
+    }
+    // dx[h] with h = a + sh*i receives dy[p] * w[r] exactly for the taps r with
+    // (a + ph - r*dh) divisible by sh, at p = i + (a + ph - r*dh)/sh: one dense sub-problem per
+    // residue class (a, b) of (h mod sh, w mod sw), so no multiply is spent on inserted zeros.
+    size_t filt_off = p.filt;
+    for (int ca = 0; ca < g.sh; ++ca)
+        for (int cb = 0; cb < g.sw; ++cb) {
+            const int Mi = ca < g.H ? (g.H - ca + g.sh - 1) / g.sh : 0;
+            const int Mj = cb < g.W ? (g.W - cb + g.sw - 1) / g.sw : 0;
+            if (Mi == 0 || Mj == 0) continue;
+            IgemmArgs a{};
+            int tap_off[kMaxTaps];
+            int nt = 0;
+            for (int r = 0; r < g.R; ++r) {
+                const int th = ca + g.ph - r * g.dh;
+                if (((th % g.sh) + g.sh) % g.sh != 0) continue;
+                for (int s = 0; s < g.S; ++s) {
+                    const int tw = cb + g.pw - s * g.dw;
+                    if (((tw % g.sw) + g.sw) % g.sw != 0) continue;
+                    a.off_h[nt] = (short)(th / g.sh);  // exact division, may be negative
+                    a.off_w[nt] = (short)(tw / g.sw);
+                    tap_off[nt] = nchw ? r * g.S + s : (r * g.S + s) * g.C;
+                    ++nt;
+                }
+            }
+            if (nt == 0 && accumulate && !nchw) continue;  // nothing to add
+            // packed filter of this class: [c][tap][k]
+            if (nt > 0) {
+                if (nchw)
+                    NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, (long)g.R * g.S,
+                                               (long)g.C * g.R * g.S, tap_off, st));
+                else
+                    NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, 1L, (long)g.R * g.S * g.C,
+                                               tap_off, st));
+            }
+            a.src = src; a.wpk = ws + filt_off; a.out = dst;
+            a.Nimg = g.N; a.Hs = g.P; a.Ws = g.Q; a.Cs = g.K;
+            a.Mi = Mi; a.Mj = Mj; a.M = g.N * Mi * Mj;
+            a.mult_h = 1; a.add_h = 0; a.mult_w = 1; a.add_w = 0;
+            a.ntaps = nt; a.Ktot = nt * g.K;
+            a.Ngemm = g.C;
+            a.Ho = g.H; a.Wo = g.W; a.Co = g.C; a.osh = g.sh; a.oa = ca; a.osw = g.sw; a.ob = cb;
+            a.accumulate = acc_kernel;
+            NSK_TRY(launch_igemm(g.dtype, a, st));
+            filt_off += align_up((size_t)g.C * nt * g.K * g.es);
+        }
+    if (nchw) NSK_TRY(launch_nhwc_to_nchw(g.dtype, dst, dx, g.N, g.C, g.H, g.W, accumulate, st));
+    return NSK_OK;
+}
+
+int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy, float *dw, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    ConvGeo g;
+    NSK_TRY(conv_geometry(desc, &g, true));
+    if (!x || !dy || !dw) return NSK_ERR_NULL;
+    if (accumulate != 0 && accumulate != 1) return NSK_ERR_BAD_DESC;
+    if (misaligned(x) || misaligned(dy) || misaligned(dw)) return NSK_ERR_ALIGNMENT;
+    const ConvPlan p = plan_conv(g, NSK_PASS_WGRAD);
+    NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    const bool nchw = g.layout == NSK_NCHW;
+    const void *xs = x, *dys = dy;
+    if (nchw) {
+        NSK_TRY(launch_nchw_to_nhwc(g.dtype, x, ws + p.act_in, g.N, g.C, g.H, g.W, st));
+        NSK_TRY(launch_nchw_to_nhwc(g.dtype, dy, ws + p.act_in2, g.N, g.K, g.P, g.Q, st));
+        xs = ws + p.act_in;
+        dys = ws + p.act_in2;
+    }
+    WgradArgs a{};
+    a.x = xs; a.dy = dys; a.part = (float *)(ws + p.part);
+    a.Nimg = g.N; a.H = g.H; a.W = g.W; a.C = g.C; a.P = g.P; a.Q = g.Q; a.K = g.K;
+    a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
+    a.ntaps = g.R * g.S;
+    a.L = g.N * g.P * g.Q;
+    a.rows_per_split = p.rows_per_split;
+    a.splits = p.splits;
+    for (int r = 0; r < g.R; ++r)
+        for (int s = 0; s < g.S; ++s) {
+            a.off_h[r * g.S + s] = (short)(r * g.dh);
+            a.off_w[r * g.S + s] = (short)(s * g.dw);
+        }
+    NSK_TRY(launch_wgrad(g.dtype, a, st));
+    const long RS = (long)g.R * g.S;
+    if (nchw)
+        NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, g.C, (long)g.C * RS, 1L, RS, accumulate, st));
+    else
+        NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, g.C, RS * g.C, (long)g.C, 1L, accumulate, st));
+    return NSK_OK;
+}
+
+size_t nsk_bn_workspace_bytes(const nsk_bn_desc_t *desc, int pass)
+{
+    if (pass != NSK_BN_FWD && pass != NSK_BN_BWD) return 0;
+    if (bn_geometry(desc) != NSK_OK) return 0;
+    const size_t G = (size_t)bn_partial_blocks(*desc);
+    return align_up((2 * G * desc->C + 4 * (size_t)desc->C) * sizeof(float));
+}
+
+int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *residual, const float *gamma,
+                        const float *beta, void *out, float *save_mean, float *save_invstd, float *running_mean,
+                        float *running_var, void *workspace, size_t workspace_bytes, void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (!x || !gamma || !beta || !out || !save_mean || !save_invstd) return NSK_ERR_NULL;
+    if ((running_mean == nullptr) != (running_var == nullptr)) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(residual) || misaligned(out) || misaligned(gamma) || misaligned(beta) ||
+        misaligned(save_mean) || misaligned(save_invstd) || misaligned(running_mean) || misaligned(running_var))
+        return NSK_ERR_ALIGNMENT;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
+    return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
+                         workspace, (hipStream_t)stream);
+}
+
+int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *out, const void *dout,
+                        const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
+                        void *dresidual, float *dgamma, float *dbeta, void *workspace, size_t workspace_bytes,
+                        void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (!x || !dout || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta) return NSK_ERR_NULL;
+    if (desc->relu && !out) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(out) || misaligned(dout) || misaligned(dx) || misaligned(dresidual) ||
+        misaligned(gamma) || misaligned(save_mean) || misaligned(save_invstd) || misaligned(dgamma) ||
+        misaligned(dbeta))
+        return NSK_ERR_ALIGNMENT;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_BWD)));
+    return launch_bn_bwd(*desc, x, out, dout, gamma, save_mean, save_invstd, dx, dresidual, dgamma, dbeta, workspace,
+                         (hipStream_t)stream);
+}
+
+int nsk_maxpool2d_out_dims(const nsk_pool_desc_t *desc, int *P, int *Q)
+{
+    if (!desc || !P || !Q) return NSK_ERR_NULL;
+    int p, q;
+    NSK_TRY(pool_geometry(desc, &p, &q));
+    *P = p;
+    *Q = q;
+    return NSK_OK;
+}
+
+int nsk_maxpool2d_fwd(const nsk_pool_desc_t *desc, const void *x, void *y, signed char *idx, void *stream)
+{
+    int P, Q;
+    NSK_TRY(pool_geometry(desc, &P, &Q));
+    if (P < 1 || Q < 1) return NSK_ERR_BAD_DESC;
+    if (!x || !y || !idx) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(y) || misaligned(idx)) return NSK_ERR_ALIGNMENT;
+    return launch_maxpool_fwd(*desc, P, Q, x, y, idx, (hipStream_t)stream);
+}
+
+int nsk_maxpool2d_bwd(const nsk_pool_desc_t *desc, const void *dy, const signed char *idx, void *dx, void *stream)
+{
+    int P, Q;
+    NSK_TRY(pool_geometry(desc, &P, &Q));
+    if (P < 1 || Q < 1) return NSK_ERR_BAD_DESC;
+    if (!dy || !idx || !dx) return NSK_ERR_NULL;
+    if (misaligned(dy) || misaligned(idx) || misaligned(dx)) return NSK_ERR_ALIGNMENT;
+    return launch_maxpool_bwd(*desc, P, Q, dy, idx, dx, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,107 @@
+// Internal declarations shared by the translation units of libnsk (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "nsk.h"
+
+namespace nsk {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kMaxTaps = 64;    // R*S of one launch (a 7x7 filter has 49)
+constexpr int kMaxBnChannels = 4096;
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t elem_size(int dtype) { return dtype == NSK_BF16 ? 2 : 4; }
+
+void set_last_hip_error(hipError_t e);
+// Returns NSK_OK or records the error and returns NSK_ERR_HIP.
+inline int check_launch()
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        set_last_hip_error(e);
+        return NSK_ERR_HIP;
+    }
+    return NSK_OK;
+}
+
+// ------------------------------------------------------------------ implicit GEMM (fwd, dgrad)
+// One launch computes, for every GEMM row m = (img, i, j) with i < Mi, j < Mj and every
+// column n < Ngemm:
+//   acc[m][n] = sum over taps t and channels c of
+//               src[img][i*mult_h + add_h + off_h[t]][j*mult_w + add_w + off_w[t]][c] * wpk[n][t][c]
+// (source positions outside [0,Hs) x [0,Ws) count as zero) and stores it, converted to the
+// element type, at out[img][i*osh + oa][j*osw + ob][n], adding the old value if `accumulate`.
+struct IgemmArgs {
+    const void *src;  // NHWC [Nimg][Hs][Ws][Cs]
+    const void *wpk;  // [Ngemm][ntaps][Cs]
+    void *out;        // NHWC [Nimg][Ho][Wo][Co]
+    int Nimg, Hs, Ws, Cs;
+    int Mi, Mj, M;
+    int mult_h, add_h, mult_w, add_w;
+    int ntaps, Ktot;
+    int Ngemm;
+    int Ho, Wo, Co;
+    int osh, oa, osw, ob;
+    int accumulate;
+    short off_h[kMaxTaps];
+    short off_w[kMaxTaps];
+};
+int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream);
+
+// ------------------------------------------------------------------ wgrad
+// part[split][k][t][c] = sum over the split's share of rows l = (img, p, q) of
+//   dy[img][p][q][k] * x[img][p*sh - ph + off_h[t]][q*sw - pw + off_w[t]][c]
+struct WgradArgs {
+    const void *x;   // NHWC [Nimg][H][W][C]
+    const void *dy;  // NHWC [Nimg][P][Q][K]
+    float *part;     // [splits][K][ntaps*C]
+    int Nimg, H, W, C, P, Q, K;
+    int sh, sw, ph, pw;
+    int ntaps;
+    int L;           // Nimg*P*Q
+    int rows_per_split;  // multiple of the kernel's BK
+    int splits;
+    short off_h[kMaxTaps];
+    short off_w[kMaxTaps];
+};
+int wgrad_rows_per_split(int dtype, int L, int K, int ntapsC, int *splits);
+int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);
+// dw[k*sk + t*st + c*sc] (=|+=) sum_s part[s][k][t][c], fixed order.
+int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int ntaps, int C,
+                        long sk, long st, long sc, int accumulate, hipStream_t stream);
+
+// ------------------------------------------------------------------ layout helpers
+// dst NHWC <- src NCHW (plain copy).
+int launch_nchw_to_nhwc(int dtype, const void *src, void *dst, int N, int C, int H, int W,
+                        hipStream_t stream);
+// dst NCHW (=|+=) src NHWC.
+int launch_nhwc_to_nchw(int dtype, const void *src, void *dst, int N, int C, int H, int W,
+                        int accumulate, hipStream_t stream);
+// out[n][t][c] = w[n*sn + tap_off[t] + c*sc] for n < Nn, t < ntaps, c < Cs.
+int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, int Cs, long sn,
+                       long sc, const int *tap_off_host, hipStream_t stream);
+
+// ------------------------------------------------------------------ batch-norm, pooling
+int bn_partial_blocks(const nsk_bn_desc_t &d);
+int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
+                  const float *beta, void *out, float *save_mean, float *save_invstd,
+                  float *running_mean, float *running_var, void *ws, hipStream_t stream);
+int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout,
+                  const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
+                  void *dres, float *dgamma, float *dbeta, void *ws, hipStream_t stream);
+int launch_maxpool_fwd(const nsk_pool_desc_t &d, int P, int Q, const void *x, void *y,
+                       signed char *idx, hipStream_t stream);
+int launch_maxpool_bwd(const nsk_pool_desc_t &d, int P, int Q, const void *dy,
+                       const signed char *idx, void *dx, hipStream_t stream);
+
+}  // namespace nsk

@@ -1,0 +1,182 @@
+// Max pooling forward / backward (the 3x3 stride-2 pool after the large-image stem of the ResNet
+// recipe the paper follows, section "Experiments and Discussion").  Pure streaming: compares only.
+// Forward records, per output, the window position r*S+s of the FIRST maximum in row-major order;
+// backward is a gather over the (at most ceil(R/sh)*ceil(S/sw)) windows that contain an input
+// element, so no atomics are needed and the result is reproducible.
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+struct PoolGeom {
+    int N, C, H, W, R, S, sh, sw, ph, pw, P, Q;
+    long xs_n, xs_c, xs_h, xs_w;  // element strides of the input-shaped tensors
+    long ys_n, ys_c, ys_h, ys_w;  // element strides of the output-shaped tensors
+};
+
+PoolGeom make_geom(const nsk_pool_desc_t &d, int P, int Q)
+{
+    PoolGeom g{d.N, d.C, d.H, d.W, d.R, d.S, d.stride_h, d.stride_w, d.pad_h, d.pad_w, P, Q, 0, 0, 0, 0, 0, 0, 0, 0};
+    if (d.layout == NSK_NCHW) {
+        g.xs_n = (long)d.C * d.H * d.W; g.xs_c = (long)d.H * d.W; g.xs_h = d.W; g.xs_w = 1;
+        g.ys_n = (long)d.C * P * Q; g.ys_c = (long)P * Q; g.ys_h = Q; g.ys_w = 1;
+    } else {
+        g.xs_n = (long)d.H * d.W * d.C; g.xs_c = 1; g.xs_h = (long)d.W * d.C; g.xs_w = d.C;
+        g.ys_n = (long)P * Q * d.C; g.ys_c = 1; g.ys_h = (long)Q * d.C; g.ys_w = d.C;
+    }
+    return g;
+}
+
+// One thread per (n, p, q, group of VEC channels).  VEC > 1 needs channel-contiguous (NHWC) data;
+// with VEC = 1 the strides make it work for either layout (then consecutive threads walk the
+// fastest-varying axis of the layout: c for NHWC, q for NCHW).
+template <typename T, int VEC, bool NCHW>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y,
+                                                          signed char *__restrict__ idx, const PoolGeom g)
+{
+    const int CV = g.C / VEC;
+    const long total = (long)g.N * g.P * g.Q * CV;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    int n, p, q, c;
+    if (NCHW) {
+        q = (int)(i % g.Q); long r = i / g.Q;
+        p = (int)(r % g.P); r /= g.P;
+        c = (int)(r % CV) * VEC; n = (int)(r / CV);
+    } else {
+        c = (int)(i % CV) * VEC; long r = i / CV;
+        q = (int)(r % g.Q); r /= g.Q;
+        p = (int)(r % g.P); n = (int)(r / g.P);
+    }
+    float best[VEC];
+    int where[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        best[e] = -INFINITY;
+        where[e] = -1;
+    }
+    for (int r = 0; r < g.R; ++r) {
+        const int h = p * g.sh - g.ph + r;
+        if ((unsigned)h >= (unsigned)g.H) continue;
+        for (int s = 0; s < g.S; ++s) {
+            const int w = q * g.sw - g.pw + s;
+            if ((unsigned)w >= (unsigned)g.W) continue;
+            const T *px = x + n * g.xs_n + c * g.xs_c + h * g.xs_h + w * g.xs_w;
+            float v[VEC];
+            if constexpr (VEC == 8) {
+                const bf16x8 t = *(const bf16x8 *)px;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[e] = (float)t[e];
+            } else if constexpr (VEC == 4) {
+                const f32x4 t = *(const f32x4 *)px;
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[e] = t[e];
+            } else {
+                v[0] = (float)px[0];
+            }
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+                const float f = v[e];
+                if (where[e] < 0 || f > best[e]) {
+                    best[e] = f;
+                    where[e] = r * g.S + s;
+                }
+            }
+        }
+    }
+    const long o = n * g.ys_n + c * g.ys_c + p * g.ys_h + q * g.ys_w;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        y[o + e] = (T)best[e];
+        idx[o + e] = (signed char)where[e];
+    }
+}
+
+template <typename T, int VEC, bool NCHW>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T *__restrict__ dy, const signed char *__restrict__ idx,
+                                                          T *__restrict__ dx, const PoolGeom g)
+{
+    const int CV = g.C / VEC;
+    const long total = (long)g.N * g.H * g.W * CV;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    int n, h, w, c;
+    if (NCHW) {
+        w = (int)(i % g.W); long r = i / g.W;
+        h = (int)(r % g.H); r /= g.H;
+        c = (int)(r % CV) * VEC; n = (int)(r / CV);
+    } else {
+        c = (int)(i % CV) * VEC; long r = i / CV;
+        w = (int)(r % g.W); r /= g.W;
+        h = (int)(r % g.H); n = (int)(r / g.H);
+    }
+    float acc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+    // windows p with p*sh - ph <= h <= p*sh - ph + R - 1
+    int p_lo = h + g.ph - g.R + 1;
+    p_lo = p_lo <= 0 ? 0 : (p_lo + g.sh - 1) / g.sh;
+    int p_hi = (h + g.ph) / g.sh;
+    if (p_hi > g.P - 1) p_hi = g.P - 1;
+    int q_lo = w + g.pw - g.S + 1;
+    q_lo = q_lo <= 0 ? 0 : (q_lo + g.sw - 1) / g.sw;
+    int q_hi = (w + g.pw) / g.sw;
+    if (q_hi > g.Q - 1) q_hi = g.Q - 1;
+    for (int p = p_lo; p <= p_hi; ++p)
+        for (int q = q_lo; q <= q_hi; ++q) {
+            const int pos = (h + g.ph - p * g.sh) * g.S + (w + g.pw - q * g.sw);
+            const long o = n * g.ys_n + c * g.ys_c + p * g.ys_h + q * g.ys_w;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                if (idx[o + e] == pos) acc[e] += (float)dy[o + e];
+        }
+    const long o = n * g.xs_n + c * g.xs_c + h * g.xs_h + w * g.xs_w;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) dx[o + e] = (T)acc[e];
+}
+
+template <typename T, int VEC>
+int pool_typed(bool fwd, const nsk_pool_desc_t &d, int P, int Q, const void *a, void *b, const signed char *idx_in,
+               signed char *idx_out, hipStream_t stream)
+{
+    const PoolGeom g = make_geom(d, P, Q);
+    const bool vec = d.layout == NSK_NHWC && d.C % VEC == 0;
+    const long pix = fwd ? (long)d.N * P * Q : (long)d.N * d.H * d.W;
+    const long total = pix * (vec ? d.C / VEC : d.C);
+    if (total == 0) return NSK_OK;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (fwd) {
+        if (vec)
+            hipLaunchKernelGGL((maxpool_fwd_kernel<T, VEC, false>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g);
+        else if (d.layout == NSK_NCHW)
+            hipLaunchKernelGGL((maxpool_fwd_kernel<T, 1, true>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g);
+        else
+            hipLaunchKernelGGL((maxpool_fwd_kernel<T, 1, false>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g);
+    } else {
+        if (vec)
+            hipLaunchKernelGGL((maxpool_bwd_kernel<T, VEC, false>), grid, block, 0, stream, (const T *)a, idx_in, (T *)b, g);
+        else if (d.layout == NSK_NCHW)
+            hipLaunchKernelGGL((maxpool_bwd_kernel<T, 1, true>), grid, block, 0, stream, (const T *)a, idx_in, (T *)b, g);
+        else
+            hipLaunchKernelGGL((maxpool_bwd_kernel<T, 1, false>), grid, block, 0, stream, (const T *)a, idx_in, (T *)b, g);
+    }
+    return check_launch();
+}
+
+}  // namespace
+
+int launch_maxpool_fwd(const nsk_pool_desc_t &d, int P, int Q, const void *x, void *y, signed char *idx,
+                       hipStream_t stream)
+{
+    if (d.dtype == NSK_BF16) return pool_typed<bf16_t, 8>(true, d, P, Q, x, y, nullptr, idx, stream);
+    return pool_typed<float, 4>(true, d, P, Q, x, y, nullptr, idx, stream);
+}
+
+int launch_maxpool_bwd(const nsk_pool_desc_t &d, int P, int Q, const void *dy, const signed char *idx, void *dx,
+                       hipStream_t stream)
+{
+    if (d.dtype == NSK_BF16) return pool_typed<bf16_t, 8>(false, d, P, Q, dy, dx, idx, nullptr, stream);
+    return pool_typed<float, 4>(false, d, P, Q, dy, dx, idx, nullptr, stream);
+}
+
+}  // namespace nsk

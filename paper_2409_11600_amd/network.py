@@ -1,0 +1,166 @@
+"""Issues the libnsk call sequence of a whole workload (forward, then backward) on one GPU.
+
+Sequencing and buffer management only: every arithmetic step is a libnsk entry point.  A workload
+is the flat unit list of ``nsk_inputs.workload``; forward walks it in order, backward in reverse,
+and a tensor that feeds several units gets its gradient contributions ACCUMULATED -- the first
+writer overwrites, later ones pass accumulate=1 (the paper's rule for the right operand of
+``y = x@w + x``, section "Automatic Differentiation").  All buffers, descriptors and the
+workspace are created once in the constructor, so running a step allocates nothing (section
+"Caching and Pooling") and the step can be captured into a HIP graph.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Dict, List
+
+import numpy as np
+import torch
+
+import nsk_inputs
+from . import binding as B
+
+
+def _to_device(a: np.ndarray, dtype, layout, device, is_filter=False):
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32))
+    if layout == B.NSK_NHWC:
+        t = t.permute(0, 2, 3, 1)          # NCHW -> NHWC, KCRS -> KRSC
+    return t.contiguous().to(device=device, dtype=dtype)
+
+
+class GpuNetwork:
+    def __init__(self, wl: dict, tensors: dict, layout: int = B.NSK_NHWC, device: str = "cuda:0", eps: float = 1e-5):
+        self.wl, self.layout, self.device = wl, layout, torch.device(device)
+        self.dtype = torch.bfloat16 if wl["dtype"] == "bf16" else torch.float32
+        self.code = B.NSK_BF16 if wl["dtype"] == "bf16" else B.NSK_F32
+        self.shapes = nsk_inputs.tensor_shapes(wl)
+        L = B.lib()
+        dev, dt = self.device, self.dtype
+
+        def act_buf(name):
+            N, C, H, W = self.shapes[name]
+            return torch.empty(B._act_shape(N, C, H, W, layout), dtype=dt, device=dev)
+
+        self.act: Dict[str, torch.Tensor] = {n: act_buf(n) for n in self.shapes}
+        self.grad: Dict[str, torch.Tensor] = {n: act_buf(n) for n in self.shapes}
+        self.act["x"].copy_(_to_device(tensors["x"], dt, layout, dev))
+        self.grad[wl["output"]].copy_(_to_device(tensors["dout"], dt, layout, dev))
+        self.w, self.gamma, self.beta = {}, {}, {}
+        self.dw, self.dgamma, self.dbeta = {}, {}, {}
+        self.y, self.dy, self.mean, self.invstd, self.idx = {}, {}, {}, {}, {}
+        ws_bytes = 0
+        self.fwd_calls: List[tuple] = []
+        self.bwd_calls: List[tuple] = []
+        self._keep = []          # descriptors must outlive the call lists
+        ptr = lambda t: ctypes.c_void_p(t.data_ptr()) if t is not None else None
+
+        fwd_plan, bwd_plan = [], []
+        written = {wl["output"]}
+        for u in wl["units"]:
+            name = u["name"]
+            N, C, H, W = self.shapes[u["src"]]
+            if u["kind"] == "pool":
+                d = B.nsk_pool_desc_t(N, C, H, W, 3, 3, 2, 2, 1, 1, self.code, layout)
+                self._keep.append(d)
+                self.idx[name] = torch.empty(self.act[u["dst"]].shape, dtype=torch.int8, device=dev)
+                fwd_plan.append((L.nsk_maxpool2d_fwd, (ctypes.byref(d), ptr(self.act[u["src"]]), ptr(self.act[u["dst"]]),
+                                                       ptr(self.idx[name])), None))
+                continue
+            p = tensors["params"][name]
+            K, R, S = u["K"], u["R"], u["S"]
+            self.w[name] = _to_device(p["w"], dt, layout, dev, True)
+            self.dw[name] = torch.zeros_like(self.w[name], dtype=torch.float32)
+            cd = B.conv_desc((N, C, H, W), (K, R, S), u["stride"], u["pad"], 1, self.code, layout)
+            self._keep.append(cd)
+            for ps in (B.NSK_PASS_FWD, B.NSK_PASS_DGRAD, B.NSK_PASS_WGRAD):
+                ws_bytes = max(ws_bytes, L.nsk_conv2d_workspace_bytes(ctypes.byref(cd), ps))
+            if u["kind"] == "conv":
+                fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
+                                                    ptr(self.act[u["dst"]])), "ws"))
+                continue
+            self.gamma[name] = torch.from_numpy(np.asarray(p["gamma"], np.float32)).to(dev)
+            self.beta[name] = torch.from_numpy(np.asarray(p["beta"], np.float32)).to(dev)
+            self.dgamma[name] = torch.zeros(K, dtype=torch.float32, device=dev)
+            self.dbeta[name] = torch.zeros(K, dtype=torch.float32, device=dev)
+            self.mean[name] = torch.zeros(K, dtype=torch.float32, device=dev)
+            self.invstd[name] = torch.zeros(K, dtype=torch.float32, device=dev)
+            self.y[name] = torch.empty_like(self.act[u["dst"]])
+            self.dy[name] = torch.empty_like(self.act[u["dst"]])
+            Nn, Kk, P, Q = self.shapes[u["dst"]]
+            bd = B.nsk_bn_desc_t(Nn, Kk, P, Q, self.code, layout, eps, 0.1, int(u["relu"]))
+            self._keep.append(bd)
+            ws_bytes = max(ws_bytes, L.nsk_bn_workspace_bytes(ctypes.byref(bd), B.NSK_BN_FWD),
+                           L.nsk_bn_workspace_bytes(ctypes.byref(bd), B.NSK_BN_BWD))
+            fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
+                                                ptr(self.y[name])), "ws"))
+            res = self.act[u["res"]] if u["res"] else None
+            fwd_plan.append((L.nsk_bn_relu_add_fwd, (ctypes.byref(bd), ptr(self.y[name]), ptr(res), ptr(self.gamma[name]),
+                                                     ptr(self.beta[name]), ptr(self.act[u["dst"]]), ptr(self.mean[name]),
+                                                     ptr(self.invstd[name]), None, None), "ws"))
+
+        # backward: reverse walk; first contribution to a gradient overwrites, later ones accumulate
+        for u in reversed(wl["units"]):
+            name = u["name"]
+            N, C, H, W = self.shapes[u["src"]]
+            g_dst = self.grad[u["dst"]]
+            if u["kind"] == "pool":
+                assert u["src"] not in written
+                d = B.nsk_pool_desc_t(N, C, H, W, 3, 3, 2, 2, 1, 1, self.code, layout)
+                self._keep.append(d)
+                bwd_plan.append((L.nsk_maxpool2d_bwd, (ctypes.byref(d), ptr(g_dst), ptr(self.idx[name]),
+                                                       ptr(self.grad[u["src"]])), None))
+                written.add(u["src"])
+                continue
+            K, R, S = u["K"], u["R"], u["S"]
+            cd = B.conv_desc((N, C, H, W), (K, R, S), u["stride"], u["pad"], 1, self.code, layout)
+            self._keep.append(cd)
+            if u["kind"] == "conv_bn":
+                Nn, Kk, P, Q = self.shapes[u["dst"]]
+                bd = B.nsk_bn_desc_t(Nn, Kk, P, Q, self.code, layout, eps, 0.1, int(u["relu"]))
+                self._keep.append(bd)
+                dres = None
+                if u["res"]:
+                    assert u["res"] not in written, "residual gradient must be the first contribution"
+                    dres = self.grad[u["res"]]
+                    written.add(u["res"])
+                bwd_plan.append((L.nsk_bn_relu_add_bwd, (ctypes.byref(bd), ptr(self.y[name]), ptr(self.act[u["dst"]]),
+                                                         ptr(g_dst), ptr(self.gamma[name]), ptr(self.mean[name]),
+                                                         ptr(self.invstd[name]), ptr(self.dy[name]), ptr(dres),
+                                                         ptr(self.dgamma[name]), ptr(self.dbeta[name])), "ws"))
+                dy = self.dy[name]
+            else:
+                dy = g_dst
+            bwd_plan.append((L.nsk_conv2d_wgrad, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(dy), ptr(self.dw[name]), 0),
+                             "ws"))
+            acc = 1 if u["src"] in written else 0
+            bwd_plan.append((L.nsk_conv2d_dgrad, (ctypes.byref(cd), ptr(dy), ptr(self.w[name]), ptr(self.grad[u["src"]]),
+                                                  acc), "ws"))
+            written.add(u["src"])
+
+        self.ws = torch.empty(max(int(ws_bytes), 256), dtype=torch.uint8, device=dev)
+        wsp, wsb = ctypes.c_void_p(self.ws.data_ptr()), ctypes.c_size_t(self.ws.numel())
+        fin = lambda plan: [(f, a + ((wsp, wsb) if w else ())) for f, a, w in plan]
+        self.fwd_calls, self.bwd_calls = fin(fwd_plan), fin(bwd_plan)
+
+    def _run(self, calls):
+        st = ctypes.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)
+        for f, args in calls:
+            rc = f(*args, st)
+            if rc != B.NSK_OK:
+                raise B.NskError(rc, f.__name__)
+
+    def forward(self):
+        self._run(self.fwd_calls)
+
+    def backward(self):
+        self._run(self.bwd_calls)
+
+    def step(self):
+        self._run(self.fwd_calls)
+        self._run(self.bwd_calls)
+
+    # ---- results back on the host in the oracle's index order (NCHW / KCRS, float64)
+    def host(self, t: torch.Tensor) -> np.ndarray:
+        a = t.detach().to(torch.float32).cpu()
+        if self.layout == B.NSK_NHWC and a.dim() == 4:
+            a = a.permute(0, 3, 1, 2)
+        return a.contiguous().numpy().astype(np.float64)
