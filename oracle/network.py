@@ -57,22 +57,25 @@ def forward(wl: dict, x: np.ndarray, params: Dict[str, dict], eps: float = 1e-5)
 def backward(wl: dict, fwd: dict, params: Dict[str, dict], dout: np.ndarray) -> dict:
     """Walks the units in reverse from the gradient of the workload's output.
 
-    Returns dict(grad=<activation gradients by tensor name>, dw=, dgamma=, dbeta= by unit name).
+    Returns dict(grad=<activation gradients by tensor name>, dw=, dgamma=, dbeta= by unit name,
+    trace=<per unit: the tensors each backward step consumed and produced, for per-step parity>).
     """
     grid = storage_grid(wl["dtype"])
     act, saved = fwd["act"], fwd["saved"]
     grad: Dict[str, np.ndarray] = {wl["output"]: np.asarray(dout, dtype=np.float64)}
-    dw, dgamma, dbeta = {}, {}, {}
+    dw, dgamma, dbeta, trace = {}, {}, {}, {}
 
     def send(name, g_unrounded):
         # the storage rounding happens after the add, as one store of the accumulated value
         grad[name] = grid(grad[name] + g_unrounded) if name in grad else grid(g_unrounded)
+        return grad[name]
 
     for u in reversed(wl["units"]):
         g = grad[u["dst"]]
         src = act[u["src"]]
+        tr = trace[u["name"]] = dict(g_in=g, src_grad_before=grad.get(u["src"]))
         if u["kind"] == "pool":
-            send(u["src"], oracle.maxpool2d_bwd(g, saved[u["name"]]["idx"], src.shape, 3, 2, 1))
+            tr["src_grad_after"] = send(u["src"], oracle.maxpool2d_bwd(g, saved[u["name"]]["idx"], src.shape, 3, 2, 1))
             continue
         p = params[u["name"]]
         if u["kind"] == "conv_bn":
@@ -83,9 +86,12 @@ def backward(wl: dict, fwd: dict, params: Dict[str, dict], dout: np.ndarray) -> 
             dgamma[u["name"]], dbeta[u["name"]] = dg, db
             dy = grid(dy)
             if u["res"]:
-                send(u["res"], dres)
+                tr["dres"] = send(u["res"], dres)
+                if u["res"] == u["src"]:
+                    tr["src_grad_before"] = tr["dres"]
         else:
             dy = g
+        tr["dy"] = dy
         dw[u["name"]] = oracle.conv2d_wgrad(src, dy, p["w"].shape, u["stride"], u["pad"], 1)
-        send(u["src"], oracle.conv2d_dgrad(dy, p["w"], src.shape, u["stride"], u["pad"], 1))
-    return dict(grad=grad, dw=dw, dgamma=dgamma, dbeta=dbeta)
+        tr["src_grad_after"] = send(u["src"], oracle.conv2d_dgrad(dy, p["w"], src.shape, u["stride"], u["pad"], 1))
+    return dict(grad=grad, dw=dw, dgamma=dgamma, dbeta=dbeta, trace=trace)

@@ -38,6 +38,14 @@ __device__ inline float wave_sum(float v)
     return v;
 }
 
+// Butterfly sum: every lane ends with the same value, combined in a fixed order.
+__device__ inline double wave_sum_f64(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
 bool nhwc_fast(const nsk_bn_desc_t &d)
 {
     if (d.layout != NSK_NHWC) return false;
@@ -78,6 +86,7 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
     }
     const long r_begin = (long)blockIdx.x * rows_per_block;
     const long r_end = min(M, r_begin + rows_per_block);
+#pragma unroll 4
     for (long r = r_begin + rr; r < r_end; r += RP) {
         const long off = r * C + cv * VEC;
         const Vec xv = *(const Vec *)(x + off);
@@ -127,15 +136,23 @@ __global__ __launch_bounds__(256) void bn_apply_nhwc(const T *__restrict__ x, co
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
+    // C/VEC divides 256 and the grid stride is a multiple of 256 vectors, so a thread always sees
+    // the same VEC channels: their coefficients live in registers.
+    const int c0 = (threadIdx.x % (C / VEC)) * VEC;
+    float sc[VEC], bi[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        sc[e] = scale[c0 + e];
+        bi[e] = bias[c0 + e];
+    }
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (long)gridDim.x * 256) {
-        const int c0 = (int)((i * VEC) % C);
         const Vec xv = *(const Vec *)(x + i * VEC);
         Vec rv;
         if (HAS_RES) rv = *(const Vec *)(res + i * VEC);
         Vec ov;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            float z = (float)xv[e] * scale[c0 + e] + bias[c0 + e];
+            float z = (float)xv[e] * sc[e] + bi[e];
             if (HAS_RES) z += (float)rv[e];
             if (RELU) z = z > 0.f ? z : 0.f;
             ov[e] = (T)z;
@@ -154,9 +171,17 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_nhwc(const T *__restrict__ x
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
-    const float *ca = coef, *cb = coef + C, *cc = coef + 2 * C;
+    const int c0 = (threadIdx.x % (C / VEC)) * VEC;   // fixed per thread, see bn_apply_nhwc
+    float mu[VEC], is[VEC], ka[VEC], kb[VEC], kc[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        mu[e] = mean[c0 + e];
+        is[e] = invstd[c0 + e];
+        ka[e] = coef[c0 + e];
+        kb[e] = coef[C + c0 + e];
+        kc[e] = coef[2 * C + c0 + e];
+    }
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (long)gridDim.x * 256) {
-        const int c0 = (int)((i * VEC) % C);
         const Vec xv = *(const Vec *)(x + i * VEC);
         const Vec gv = *(const Vec *)(dout + i * VEC);
         Vec ov;
@@ -164,11 +189,10 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_nhwc(const T *__restrict__ x
         Vec dxv, drv;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-            const int c = c0 + e;
             float dz = (float)gv[e];
             if (RELU && !((float)ov[e] > 0.f)) dz = 0.f;
-            const float xhat = ((float)xv[e] - mean[c]) * invstd[c];
-            dxv[e] = (T)(ca[c] * (dz - cb[c] - xhat * cc[c]));
+            const float xhat = ((float)xv[e] - mu[e]) * is[e];
+            dxv[e] = (T)(ka[e] * (dz - kb[e] - xhat * kc[e]));
             drv[e] = (T)dz;
         }
         *(Vec *)(dx + i * VEC) = dxv;
@@ -261,13 +285,16 @@ __global__ void bn_fwd_finalize(const float *__restrict__ p0, const float *__res
                                 float *__restrict__ running_mean, float *__restrict__ running_var,
                                 float *__restrict__ scale, float *__restrict__ bias)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (c >= C) return;
     double S = 0.0, Q = 0.0;
-    for (int g = 0; g < G; ++g) {
+    for (int g = threadIdx.x & 63; g < G; g += 64) {
         S += (double)p0[(long)g * C + c];
         Q += (double)p1[(long)g * C + c];
     }
+    S = wave_sum_f64(S);
+    Q = wave_sum_f64(Q);
+    if ((threadIdx.x & 63) != 0) return;
     const double ms = S / M;
     double var = Q / M - ms * ms;
     if (var < 0.0) var = 0.0;
@@ -289,13 +316,16 @@ __global__ void bn_bwd_finalize(const float *__restrict__ p0, const float *__res
                                 const float *__restrict__ gamma, const float *__restrict__ invstd,
                                 float *__restrict__ dgamma, float *__restrict__ dbeta, float *__restrict__ coef)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (c >= C) return;
     double S = 0.0, Q = 0.0;
-    for (int g = 0; g < G; ++g) {
+    for (int g = threadIdx.x & 63; g < G; g += 64) {
         S += (double)p0[(long)g * C + c];
         Q += (double)p1[(long)g * C + c];
     }
+    S = wave_sum_f64(S);
+    Q = wave_sum_f64(Q);
+    if ((threadIdx.x & 63) != 0) return;
     dbeta[c] = (float)S;
     dgamma[c] = (float)Q;
     coef[c] = gamma[c] * invstd[c];
@@ -323,7 +353,7 @@ Geom geometry(const nsk_bn_desc_t &d)
         const int VEC = d.dtype == NSK_BF16 ? 8 : 4;
         const int RP = 256 / (d.C / VEC);
         long G = (g.M + (long)RP * 8 - 1) / ((long)RP * 8);
-        if (G > 1024) G = 1024;
+        if (G > 512) G = 512;   // two blocks per CU; each thread then streams a long run of rows
         if (G < 1) G = 1;
         g.rows_per_block = (g.M + G - 1) / G;
         g.G = (int)((g.M + g.rows_per_block - 1) / g.rows_per_block);
@@ -374,7 +404,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, d.N, g.HW, g.sn,
                            g.sc, g.ss, g.npg, d.C, p0, p1);
     }
-    hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 256)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+    hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, p0, p1, g.G, d.C,
                        (double)g.M, x, g.sc, gamma, beta, d.eps, d.momentum, save_mean, save_invstd, running_mean,
                        running_var, scale, bias);
     if (g.fast) {
@@ -415,7 +445,7 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
         hipLaunchKernelGGL((bn_reduce_generic<T, 1>), dim3(d.C, g.G), dim3(256), 0, stream, x, out, dout, mean,
                            invstd, d.relu, d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1);
     }
-    hipLaunchKernelGGL(bn_bwd_finalize, dim3(ceil_div(d.C, 256)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+    hipLaunchKernelGGL(bn_bwd_finalize, dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, p0, p1, g.G, d.C,
                        (double)g.M, gamma, invstd, dgamma, dbeta, coef);
     if (g.fast) {
         const long nvec = g.total / VEC;
