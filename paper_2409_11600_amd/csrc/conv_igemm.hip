@@ -11,18 +11,22 @@
 // reads of 8 consecutive lanes cover all 32 banks once) with register prefetch of the next
 // k-tile and two LDS buffers, so one barrier per k-tile suffices.  Each wavefront owns a
 // WM x WN sub-tile made of 32x32 MFMA accumulators.
+#include <stdlib.h>
+
 #include "nsk_internal.h"
 
 namespace nsk {
 namespace {
 
+// BKB = bytes of reduction index per k-tile row (64 or 128); LDS rows are padded by 16 bytes so
+// that the 16-byte fragment reads of 8 consecutive rows fall into 8 different bank groups.
 template <typename T> struct Traits;
 template <> struct Traits<float> {
-    static constexpr int VEC = 4, BK = 16, LDK = 20;
+    static constexpr int VEC = 4;
     typedef f32x4 Vec;
 };
 template <> struct Traits<bf16_t> {
-    static constexpr int VEC = 8, BK = 32, LDK = 40;
+    static constexpr int VEC = 8;
     typedef bf16x8 Vec;
 };
 
@@ -37,17 +41,19 @@ template <typename Vec> __device__ inline Vec zero_vec()
 __device__ inline float to_float(float v) { return v; }
 __device__ inline float to_float(bf16_t v) { return (float)v; }
 
-template <typename T, int BM, int BN, int WM, int WN, bool VECLOAD>
+template <typename T, int BM, int BN, int WM, int WN, int BKB, bool VECLOAD>
 __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
 {
     typedef Traits<T> TR;
     typedef typename TR::Vec Vec;
-    constexpr int VEC = TR::VEC, BK = TR::BK, LDK = TR::LDK;
+    constexpr int VEC = TR::VEC, BK = BKB / (int)sizeof(T), LDK = BK + VEC;
     constexpr int WAVES_N = BN / WN;
     static_assert((BM / WM) * WAVES_N == 4, "four wavefronts per block");
     constexpr int FM = WM / 32, FN = WN / 32;
-    constexpr int A_PASSES = BM / 64;
-    constexpr int B_PASSES = (BN + 63) / 64;
+    constexpr int VPR = BK / VEC;        // 16-byte vectors per tile row
+    constexpr int RPP = 256 / VPR;       // tile rows loaded per pass of the 256 threads
+    constexpr int A_PASSES = BM / RPP;
+    constexpr int B_PASSES = (BN + RPP - 1) / RPP;
 
     __shared__ __attribute__((aligned(16))) T As[2][BM * LDK];
     __shared__ __attribute__((aligned(16))) T Bs[2][BN * LDK];
@@ -69,14 +75,19 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
     const T *__restrict__ src = (const T *)a.src;
     const T *__restrict__ wpk = (const T *)a.wpk;
 
-    // Each thread gathers the same rows in every k-tile: decode them once.
-    const int kv = tid & 3;   // which 16-byte vector of the k-tile row
-    const int r0 = tid >> 2;  // row within a pass of 64 rows
+    // Each thread gathers the same rows in every k-tile: decode them once.  For the vector path the
+    // per-row state is a 32-bit byte offset of the row's base pixel and a bit mask of the taps that
+    // fall inside the image; a k-tile then costs one shift, one add and one select per load.  Loads go
+    // through buffer descriptors: an offset of ~0 is out of range and returns zeros without a branch.
+    const int kv = tid % VPR;  // which 16-byte vector of the k-tile row
+    const int r0 = tid / VPR;  // row within a pass of RPP rows
     int a_img[A_PASSES], a_bh[A_PASSES], a_bw[A_PASSES];
     bool a_ok[A_PASSES];
+    unsigned a_base[A_PASSES];
+    unsigned long long a_mask[A_PASSES];
 #pragma unroll
     for (int u = 0; u < A_PASSES; ++u) {
-        const int row = r0 + 64 * u;
+        const int row = r0 + RPP * u;
         const int m = m0 + row;
         a_ok[u] = m < a.M;
         const int mm = a_ok[u] ? m : 0;
@@ -88,11 +99,26 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         a_img[u] = img * a.Hs;
         a_bh[u] = i * a.mult_h + a.add_h;
         a_bw[u] = j * a.mult_w + a.add_w;
+        a_base[u] = (unsigned)((((long)a_img[u] + a_bh[u]) * a.Ws + a_bw[u]) * a.Cs * (long)sizeof(T));
         if (kv == 0)
             out_off[row] = a_ok[u] ? (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co
                                    : -1L;
     }
     __syncthreads();
+    if (VECLOAD) {
+#pragma unroll
+        for (int u = 0; u < A_PASSES; ++u) {
+            unsigned long long mask = 0;
+            if (a_ok[u])
+                for (int t = 0; t < a.ntaps; ++t) {
+                    const int h = a_bh[u] + s_offh[t], w = a_bw[u] + s_offw[t];
+                    if ((unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws) mask |= 1ull << t;
+                }
+            a_mask[u] = mask;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wpk_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.wpk, 0, a.wpk_bytes, 0x00020000);
 
     Vec ra[A_PASSES], rb[B_PASSES];
     int cur_tap = 0, cur_c = kv * VEC;  // position of this thread's vector inside (tap, channel)
@@ -102,24 +128,30 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
             ++cur_tap;
         }
     }
+    unsigned b_row_off[B_PASSES];
+#pragma unroll
+    for (int u = 0; u < B_PASSES; ++u) {
+        const int row = r0 + RPP * u;
+        const int n = n0 + row;
+        b_row_off[u] = (row < BN && n < a.Ngemm) ? (unsigned)((long)n * a.Ktot * (long)sizeof(T)) : ~0u;
+    }
 
     auto load_tile = [&](int kt) {
         const int kk = kt * BK + kv * VEC;
         if (VECLOAD) {
             const bool kok = kk < a.Ktot;
-            const int oh = kok ? s_offh[cur_tap] : 0, ow = kok ? s_offw[cur_tap] : 0;
+            const int tap = kok ? cur_tap : 0;
+            const unsigned delta = (unsigned)((((int)s_offh[tap] * a.Ws + (int)s_offw[tap]) * a.Cs + cur_c) * (int)sizeof(T));
 #pragma unroll
             for (int u = 0; u < A_PASSES; ++u) {
-                const int h = a_bh[u] + oh, w = a_bw[u] + ow;
-                const bool ok = kok && a_ok[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
-                ra[u] = ok ? *(const Vec *)(src + ((long)(a_img[u] + h) * a.Ws + w) * a.Cs + cur_c) : zero_vec<Vec>();
+                const bool ok = kok && ((a_mask[u] >> tap) & 1ull);
+                const unsigned off = ok ? a_base[u] + delta : ~0u;
+                ra[u] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, off, 0, 0));
             }
 #pragma unroll
             for (int u = 0; u < B_PASSES; ++u) {
-                const int row = r0 + 64 * u;
-                const int n = n0 + row;
-                const bool ok = kok && row < BN && n < a.Ngemm;
-                rb[u] = ok ? *(const Vec *)(wpk + (long)n * a.Ktot + kk) : zero_vec<Vec>();
+                const unsigned off = (kok && b_row_off[u] != ~0u) ? b_row_off[u] + (unsigned)(kk * (int)sizeof(T)) : ~0u;
+                rb[u] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(wpk_rsrc, off, 0, 0));
             }
             // advance to the next k-tile
             cur_c += BK;
@@ -149,7 +181,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
                     }
 #pragma unroll
                     for (int u = 0; u < B_PASSES; ++u) {
-                        const int row = r0 + 64 * u;
+                        const int row = r0 + RPP * u;
                         const int n = n0 + row;
                         if (row < BN && n < a.Ngemm) rb[u][e] = wpk[(long)n * a.Ktot + k];
                     }
@@ -159,10 +191,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
     };
     auto store_tile = [&](int buf) {
 #pragma unroll
-        for (int u = 0; u < A_PASSES; ++u) *(Vec *)&As[buf][(r0 + 64 * u) * LDK + kv * VEC] = ra[u];
+        for (int u = 0; u < A_PASSES; ++u) *(Vec *)&As[buf][(r0 + RPP * u) * LDK + kv * VEC] = ra[u];
 #pragma unroll
         for (int u = 0; u < B_PASSES; ++u) {
-            const int row = r0 + 64 * u;
+            const int row = r0 + RPP * u;
             if (row < BN) *(Vec *)&Bs[buf][row * LDK + kv * VEC] = rb[u];
         }
     };
@@ -237,24 +269,44 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         }
 }
 
-template <typename T, int BM, int BN, int WM, int WN>
+template <typename T, int BM, int BN, int WM, int WN, int BKB>
 int launch_tile(const IgemmArgs &a, bool vec, hipStream_t stream)
 {
     dim3 grid(ceil_div(a.M, BM), ceil_div(a.Ngemm, BN));
     if (vec)
-        hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, true>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, BKB, true>), grid, dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, false>), grid, dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, 64, false>), grid, dim3(256), 0, stream, a);
     return check_launch();
+}
+
+// NSK_IGEMM_TILE=<n> forces a tile variant (A/B experiments); unset or 0 = automatic choice.
+int forced_tile()
+{
+    const char *e = getenv("NSK_IGEMM_TILE");
+    return e ? atoi(e) : 0;
 }
 
 template <typename T> int launch_typed(const IgemmArgs &a, hipStream_t stream)
 {
     constexpr int VEC = Traits<T>::VEC;
     const bool vec = a.Cs % VEC == 0 && a.Ktot % VEC == 0 && ((uintptr_t)a.src % 16 == 0) && ((uintptr_t)a.wpk % 16 == 0);
-    if (a.Ngemm <= 32) return launch_tile<T, 256, 32, 64, 32>(a, vec, stream);
-    if (a.Ngemm <= 64) return launch_tile<T, 256, 64, 64, 64>(a, vec, stream);
-    return launch_tile<T, 128, 128, 64, 64>(a, vec, stream);
+    switch (forced_tile()) {
+    case 1: return launch_tile<T, 256, 64, 64, 64, 64>(a, vec, stream);
+    case 2: return launch_tile<T, 256, 64, 64, 64, 128>(a, vec, stream);
+    case 3: return launch_tile<T, 128, 64, 32, 64, 64>(a, vec, stream);
+    case 4: return launch_tile<T, 128, 64, 32, 64, 128>(a, vec, stream);
+    case 5: return launch_tile<T, 128, 128, 64, 64, 64>(a, vec, stream);
+    case 6: return launch_tile<T, 128, 128, 64, 64, 128>(a, vec, stream);
+    default: break;
+    }
+    // Measured on MI355X: with 64 or fewer columns the 128-row tile wins (more blocks in flight hide
+    // the per-block prologue and epilogue); wide problems with a long reduction take 128x128 tiles
+    // with 128-byte k-tiles (half as many barriers).
+    if (a.Ngemm <= 32) return launch_tile<T, 256, 32, 64, 32, 64>(a, vec, stream);
+    if (a.Ngemm <= 64) return launch_tile<T, 128, 64, 32, 64, 64>(a, vec, stream);
+    if ((long)a.Ktot * (long)sizeof(T) >= 1024) return launch_tile<T, 128, 128, 64, 64, 128>(a, vec, stream);
+    return launch_tile<T, 128, 64, 32, 64, 64>(a, vec, stream);
 }
 
 }  // namespace

@@ -47,6 +47,8 @@ int conv_geometry(const nsk_conv_desc_t *d, ConvGeo *g, bool need_output)
     const long long pix_in = (long long)d->N * d->H * d->W, pix_out = (long long)d->N * g->P * g->Q;
     if (pix_in >= INT_MAX || pix_out >= INT_MAX) return NSK_ERR_UNSUPPORTED;
     if ((long long)d->R * d->S > kMaxTaps) return NSK_ERR_UNSUPPORTED;
+    // activations are addressed with 32-bit byte offsets through buffer descriptors
+    if (pix_in * d->C * 4 >= 0xFFFFFFFFLL || pix_out * d->K * 4 >= 0xFFFFFFFFLL) return NSK_ERR_UNSUPPORTED;
     if ((long long)(d->R - 1) * d->dil_h > 30000 || (long long)(d->S - 1) * d->dil_w > 30000) return NSK_ERR_UNSUPPORTED;
     if ((long long)d->K * d->R * d->S * d->C >= INT_MAX) return NSK_ERR_UNSUPPORTED;
     if (d->layout == NSK_NCHW && d->N > 65535) return NSK_ERR_UNSUPPORTED;
@@ -217,6 +219,8 @@ int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, vo
     a.Ngemm = g.K;
     a.Ho = g.P; a.Wo = g.Q; a.Co = g.K; a.osh = 1; a.oa = 0; a.osw = 1; a.ob = 0;
     a.accumulate = 0;
+    a.src_bytes = (unsigned)(g.x_elems * g.es);
+    a.wpk_bytes = (unsigned)(g.w_elems * g.es);
     for (int r = 0; r < g.R; ++r)
         for (int s = 0; s < g.S; ++s) {
             a.off_h[r * g.S + s] = (short)(r * g.dh);
@@ -292,6 +296,8 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
             a.Ngemm = g.C;
             a.Ho = g.H; a.Wo = g.W; a.Co = g.C; a.osh = g.sh; a.oa = ca; a.osw = g.sw; a.ob = cb;
             a.accumulate = acc_kernel;
+            a.src_bytes = (unsigned)(g.y_elems * g.es);
+            a.wpk_bytes = (unsigned)((size_t)g.C * nt * g.K * g.es);
             NSK_TRY(launch_igemm(g.dtype, a, st));
             filt_off += align_up((size_t)g.C * nt * g.K * g.es);
         }
