@@ -1,0 +1,300 @@
+// 3x3, stride 1, 64 -> 64 channel bf16 convolution (forward, and backward-data through the packed
+// transposed filter): the layer shape that carries most of the 3x3 FLOPs of the residual networks the
+// paper trains (section "Experiments and Discussion").
+//
+// Why a second kernel.  On gfx950 a bf16 32x32x16 MFMA lasts 32 clocks, so an instruction stream may
+// spend only a handful of other vector instructions per MFMA, and a k-tile that is re-staged from
+// L2 for each of the nine taps saturates the L1 fill bandwidth of a CU.  This kernel therefore
+//   * keeps the whole packed filter (64 x 9 x 64 bf16 = 72 KB) resident in LDS for the life of the
+//     block (the 160 KB LDS of a CU makes that possible),
+//   * stages each input tile ONCE, with its halo, and reads the nine taps as shifted LDS rows,
+//   * is persistent: a block walks over many tiles, prefetching the next tile into registers while
+//     the MFMAs of the current one run, so no per-block prologue is paid per tile.
+//
+// Flat padded coordinates.  Every image is viewed as a zero-padded (H+2) x (W+2) grid and all images
+// are laid end to end; position q = img*(H+2)*(W+2) + hp*(W+2) + wp.  A tap (dh, dw) is then the same
+// constant shift dh*(W+2) + dw for every position, image borders need no special case (padding
+// positions load zeros through an out-of-range buffer offset), and a tile is simply 256 consecutive
+// positions.  Outputs computed at padding positions are discarded; that wastes
+// ((H+2)(W+2) - HW)/HW of the MFMA work (7% at 56 x 56).
+//
+// Block = 256 threads = 4 wavefronts, each owning 64 positions x 64 output channels as 2 x 2
+// accumulators of 32x32.  LDS rows are padded (144 B per position, 1168 B per filter row) so that the
+// 16-byte fragment reads of 8 consecutive rows cover all banks once.
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+constexpr int HT = 256;            // positions per tile
+constexpr int H_MAX_IN = 400;      // staged positions incl. halo: HT + 2*(W+3) <= 400  ->  W <= 69
+constexpr int H_IN_STRIDE = 144;   // bytes per staged position (64 ch bf16 + 16 pad)
+constexpr int H_W_STRIDE = 1168;   // bytes per filter row (9*64 bf16 + 16 pad)
+constexpr int H_PASSES = (H_MAX_IN + 31) / 32;
+constexpr unsigned H_OOB = 0xF0000000u;
+
+struct HaloArgs {
+    const void *src, *wpk;
+    void *out;
+    int N, H, W;
+    int PW, PI;               // padded width, padded image size
+    int total_pos, tiles, halo;
+    unsigned long long magic_pi, magic_pw;  // ceil(2^40 / d)
+    unsigned src_bytes, out_bytes;
+    int accumulate;
+    int tapoff[9];            // shift of each tap in flat padded positions
+};
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <bool ACCUM>
+__global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *in_lds = smem;                                    // H_MAX_IN * 144
+    unsigned char *w_lds = smem + H_MAX_IN * H_IN_STRIDE;            // 64 * 1168
+    unsigned *out_tab = (unsigned *)(w_lds + 64 * H_W_STRIDE);       // 256 byte offsets
+    unsigned *in_tab = out_tab + 256;                                // H_MAX_IN byte offsets
+    unsigned char *st_lds = (unsigned char *)(in_tab + H_MAX_IN);    // 4 wavefronts x 32 positions x 144 B
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fk = lane >> 5;
+    const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, a.out_bytes, 0x00020000);
+
+    // filter -> LDS, once per block: 64 rows x 72 vectors
+    {
+        const u32x4 *w = (const u32x4 *)a.wpk;
+        u32x4 tmp[18];   // 64 * 72 / 256 vectors per thread, all loads in flight before the first write
+#pragma unroll
+        for (int u = 0; u < 18; ++u) tmp[u] = w[tid + 256 * u];
+#pragma unroll
+        for (int u = 0; u < 18; ++u) {
+            const int i = tid + 256 * u, row = i / 72, v = i - row * 72;
+            *(u32x4 *)(w_lds + row * H_W_STRIDE + v * 16) = tmp[u];
+        }
+    }
+
+    const int n_in = HT + 2 * a.halo;        // staged positions of a tile
+    const int chunk = tid & 7, prow = tid >> 3;
+
+    // byte offset of padded position q (channel chunk `chunk`) in the NHWC tensor, or out of range
+    auto src_offset = [&](int q) -> unsigned {
+        // branch-free: an invalid position is clamped for the arithmetic and replaced at the end
+        const bool inside = (unsigned)q < (unsigned)a.total_pos;
+        const unsigned qq = inside ? (unsigned)q : 0u;
+        const unsigned img = (unsigned)(((unsigned long long)qq * a.magic_pi) >> 40);
+        const unsigned rem = qq - img * (unsigned)a.PI;
+        const unsigned hp = (unsigned)(((unsigned long long)rem * a.magic_pw) >> 40);
+        const unsigned wp = rem - hp * (unsigned)a.PW;
+        const bool ok = inside & (hp - 1u < (unsigned)a.H) & (wp - 1u < (unsigned)a.W);
+        const unsigned off = (((img * a.H + (hp - 1u)) * a.W + (wp - 1u)) * 64u) * 2u;
+        return ok ? off : H_OOB;
+    };
+
+    u32x4 stage[H_PASSES];
+    // one of the H_PASSES 16-byte loads of a tile's staged input (8 lanes per position)
+    // in_tab[p] = byte offset of staged position p of the tile being prefetched (or out of range):
+    // computed by two positions per thread, so the eight lanes that share a position do not repeat
+    // the index arithmetic and a prefetch step is one table read, one add and one load.
+    auto fill_in_tab = [&](int tile) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int p = tid + 256 * u;
+            if (p < H_MAX_IN) in_tab[p] = p < n_in ? src_offset(tile * HT - a.halo + p) : H_OOB;
+        }
+    };
+    // The table is read in one batch (LDS returns in order, so a table read in the middle of the MFMA
+    // loop would force a wait on the fragment reads issued before it); a prefetch step is then one load.
+    unsigned poff[H_PASSES];
+    auto read_in_tab = [&]() {
+#pragma unroll
+        for (int u = 0; u < H_PASSES; ++u) {
+            const unsigned off = in_tab[u * 32 + prow];
+            poff[u] = off == H_OOB ? H_OOB : off + chunk * 16;
+        }
+    };
+    auto prefetch_piece = [&](int u) { stage[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, poff[u], 0, 0); };
+
+    int tile = blockIdx.x;
+    if (tile < a.tiles) {
+        fill_in_tab(tile);
+        __syncthreads();
+        read_in_tab();
+#pragma unroll
+        for (int u = 0; u < H_PASSES; ++u) prefetch_piece(u);
+    }
+
+    const unsigned a_base0 = (unsigned)((wave * 64 + frow + a.halo) * H_IN_STRIDE + fk * 16);
+    const unsigned b_base0 = (unsigned)(frow * H_W_STRIDE + fk * 16);
+    unsigned char *my_st = st_lds + wave * (32 * H_IN_STRIDE);
+
+    for (; tile < a.tiles; tile += gridDim.x) {
+        // staged registers -> LDS (the barrier at the end of the previous tile freed the buffer)
+#pragma unroll
+        for (int u = 0; u < H_PASSES; ++u) {
+            const int p = u * 32 + prow;
+            if (p < n_in) *(u32x4 *)(in_lds + p * H_IN_STRIDE + chunk * 16) = stage[u];
+        }
+        out_tab[tid] = src_offset(tile * HT + tid);   // the output tensor has the same geometry
+        const int next = tile + (int)gridDim.x;
+        const bool have_next = next < a.tiles;
+        if (have_next) fill_in_tab(next);   // the previous tile's reads of in_tab are complete
+        __syncthreads();
+        if (have_next) {
+            read_in_tab();
+        } else {
+#pragma unroll
+            for (int u = 0; u < H_PASSES; ++u) poff[u] = H_OOB;
+        }
+
+        // The filter rows are the MFMA "A" operand and the positions the "B" operand, so a lane ends up
+        // with 4 CONSECUTIVE CHANNELS of one position per accumulator quad: acc[ni][mi][4g+j] is channel
+        // 32*ni + 8*g + 4*(lane/32) + j of position 32*mi + lane%32.
+        f32x16 acc[2][2];
+        if (ACCUM) {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const unsigned off = out_tab[wave * 64 + mi * 32 + frow];
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        const unsigned o = off == H_OOB ? H_OOB : off + (unsigned)((ni * 32 + g * 8 + fk * 4) * 2);
+                        const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(out_rsrc, o, 0, 0);
+                        const bf16x4 ob = __builtin_bit_cast(bf16x4, old);
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) acc[ni][mi][g * 4 + jj] = (float)ob[jj];
+                    }
+            }
+        } else {
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
+        }
+
+        // 36 reduction steps (9 taps x 4 groups of 16 channels).  One wavefront per SIMD means nobody
+        // else hides LDS latency, so fragments are fetched two steps ahead into a rotating set of
+        // registers; the scheduling barriers keep the compiler from sinking the reads back to their use.
+        // The loads of the NEXT tile are issued one per step, in the shadow of the MFMAs.
+        unsigned ta[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) ta[t] = a_base0 + (unsigned)(a.tapoff[t] * H_IN_STRIDE);
+        bf16x8 af[3][2], bfr[3][2];
+        auto fetch = [&](int step, int set) {
+            const int t = step >> 2, kc = step & 3;
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+                af[set][mi] = *(const bf16x8 *)(in_lds + ta[t] + mi * 32 * H_IN_STRIDE + kc * 32);
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+                bfr[set][ni] = *(const bf16x8 *)(w_lds + b_base0 + ni * 32 * H_W_STRIDE + (t * 64 + kc * 16) * 2);
+        };
+        fetch(0, 0);
+        fetch(1, 1);
+#pragma unroll
+        for (int step = 0; step < 36; ++step) {
+            if (step + 2 < 36) fetch(step + 2, (step + 2) % 3);
+            if (step < H_PASSES) prefetch_piece(step);   // unconditional: without a next tile the offsets are out of range
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < 2; ++ni)
+                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[step % 3][ni], af[step % 3][mi], acc[ni][mi], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        // Epilogue: round to bf16, transpose through this wavefront's private LDS strip so that every
+        // lane stores 16 contiguous bytes (8 lanes cover the 128 bytes of one position).
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi) {
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 pk;
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) pk[jj] = (bf16_t)acc[ni][mi][g * 4 + jj];
+                    *(bf16x4 *)(my_st + frow * H_IN_STRIDE + (ni * 32 + g * 8 + fk * 4) * 2) = pk;
+                }
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const int idx = lane + 64 * jj, pos = idx >> 3, ck = idx & 7;
+                const u32x4 v = *(const u32x4 *)(my_st + pos * H_IN_STRIDE + ck * 16);
+                const unsigned off = out_tab[wave * 64 + mi * 32 + pos];
+                const unsigned o = off == H_OOB ? H_OOB : off + (unsigned)(ck * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, o, 0, 0);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+}  // namespace
+
+// True if the launch described by `a` is the shape this kernel covers.
+bool halo64_applicable(int dtype, const IgemmArgs &a)
+{
+    if (dtype != NSK_BF16 || a.Cs != 64 || a.Ngemm != 64 || a.ntaps != 9 || a.Co != 64) return false;
+    if (a.mult_h != 1 || a.mult_w != 1 || a.osh != 1 || a.osw != 1 || a.oa != 0 || a.ob != 0) return false;
+    if (a.Hs != a.Ho || a.Ws != a.Wo || a.Mi != a.Ho || a.Mj != a.Wo) return false;
+    if (HT + 2 * (a.Ws + 3) > H_MAX_IN) return false;
+    for (int t = 0; t < 9; ++t) {
+        const int eh = a.add_h + a.off_h[t], ew = a.add_w + a.off_w[t];
+        if (eh < -1 || eh > 1 || ew < -1 || ew > 1) return false;
+    }
+    const long long pi = (long long)(a.Hs + 2) * (a.Ws + 2), total = pi * a.Nimg;
+    if (total >= (1LL << 30) || total * pi >= (1LL << 40)) return false;   // exactness of the reciprocal division
+    if ((unsigned long long)a.src_bytes >= H_OOB) return false;
+    if (((uintptr_t)a.src | (uintptr_t)a.wpk | (uintptr_t)a.out) & 15) return false;
+    return true;
+}
+
+int launch_halo64(const IgemmArgs &g, hipStream_t stream)
+{
+    HaloArgs a{};
+    a.src = g.src; a.wpk = g.wpk; a.out = g.out;
+    a.N = g.Nimg; a.H = g.Hs; a.W = g.Ws;
+    a.PW = g.Ws + 2; a.PI = (g.Hs + 2) * a.PW;
+    a.total_pos = a.PI * g.Nimg;
+    a.tiles = ceil_div(a.total_pos, HT);
+    a.halo = a.PW + 1;
+    a.magic_pi = ((1ULL << 40) + a.PI - 1) / a.PI;
+    a.magic_pw = ((1ULL << 40) + a.PW - 1) / a.PW;
+    a.src_bytes = g.src_bytes;
+    a.out_bytes = g.src_bytes;   // same geometry: N*H*W*64 bf16
+    a.accumulate = g.accumulate;
+    for (int t = 0; t < 9; ++t) a.tapoff[t] = (g.add_h + g.off_h[t]) * a.PW + (g.add_w + g.off_w[t]);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NSK_ERR_HIP;
+        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
+    const int smem = H_MAX_IN * H_IN_STRIDE + 64 * H_W_STRIDE + 256 * 4 + H_MAX_IN * 4 + 4 * 32 * H_IN_STRIDE;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)conv_halo64_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv_halo64_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e != hipSuccess) {
+            set_last_hip_error(e);
+            return NSK_ERR_HIP;
+        }
+        attr_set = true;
+    }
+    const int grid = a.tiles < cus ? a.tiles : cus;
+    if (a.accumulate)
+        hipLaunchKernelGGL(conv_halo64_kernel<true>, dim3(grid), dim3(256), smem, stream, a);
+    else
+        hipLaunchKernelGGL(conv_halo64_kernel<false>, dim3(grid), dim3(256), smem, stream, a);
+    return check_launch();
+}
+
+}  // namespace nsk

@@ -7,6 +7,11 @@
 // across blocks (blockIdx.z) into float partials that a second kernel adds in a fixed order:
 // results are bitwise reproducible, no floating-point atomics.
 //
+// Block tile: 64 rows x (64*FN) columns, four wavefronts as 2 x 2, each owning a 32 x (32*FN) strip
+// of 32x32 MFMA accumulators.  FN = 3 makes a column tile exactly one filter row of a 3x3 filter with
+// 64 channels, so x is re-read three times (not nine) across column tiles and every barrier is
+// followed by three times as many MFMAs.
+//
 // Both operands are stored channel-contiguous, i.e. with the REDUCTION index as the slow one.
 //  - fp32 (mfma 32x32x2, one k per lane): the tile is kept in LDS as [pixel][channel], exactly
 //    as loaded, and a fragment is one conflict-free 4-byte read per lane.
@@ -17,7 +22,7 @@
 namespace nsk {
 namespace {
 
-constexpr int WBM = 64, WBN = 64;
+constexpr int WBM = 64;
 
 template <typename T> struct WTraits;
 template <> struct WTraits<float> {
@@ -29,19 +34,24 @@ template <> struct WTraits<bf16_t> {
     typedef bf16x8 Vec;
 };
 
-template <typename T, bool VECLOAD>
+template <typename T, int FN, bool VECLOAD>
 __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
 {
     typedef WTraits<T> TR;
     typedef typename TR::Vec Vec;
     constexpr int VEC = TR::VEC, BK = TR::BK;
     constexpr bool F32 = sizeof(T) == 4;
-    // fp32: [BK][64+4] (pixel-major) ; bf16: [64][BK+8] (channel-major, pixel contiguous)
-    constexpr int LD = F32 ? (64 + 4) : (BK + 8);
-    constexpr int TILE = F32 ? BK * LD : 64 * LD;
-    constexpr int VPR = 64 / VEC;          // vectors per pixel row of the tile
-    __shared__ __attribute__((aligned(16))) T As[2][TILE];
-    __shared__ __attribute__((aligned(16))) T Bs[2][TILE];
+    constexpr int WBN = 64 * FN;
+    // fp32: [BK][cols+4] (pixel-major) ; bf16: [cols][BK+8] (channel-major, pixel contiguous)
+    constexpr int LDA = F32 ? (WBM + 4) : (BK + 8);
+    constexpr int LDB = F32 ? (WBN + 4) : (BK + 8);
+    constexpr int TILE_A = F32 ? BK * LDA : WBM * LDA;
+    constexpr int TILE_B = F32 ? BK * LDB : WBN * LDB;
+    constexpr int VPR_A = WBM / VEC;       // vectors per pixel row of the dy tile (BK * VPR_A = 256)
+    constexpr int VPR_B = WBN / VEC;
+    constexpr int B_LOADS = FN;            // vectors of the x tile per thread
+    __shared__ __attribute__((aligned(16))) T As[2][TILE_A];
+    __shared__ __attribute__((aligned(16))) T Bs[2][TILE_B];
     __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -58,83 +68,114 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
     const T *__restrict__ x = (const T *)a.x;
     const T *__restrict__ dy = (const T *)a.dy;
 
-    // thread -> (pixel row of the tile, vector of 64 channels); bf16 keeps lanes along the pixel
-    // index so the transposing 2-byte LDS writes of a wavefront fall into consecutive addresses.
-    const int l_loc = F32 ? tid / VPR : tid % BK;
-    const int vv = F32 ? tid % VPR : tid / BK;
+    // thread -> (pixel row of the tile, vector of channels); bf16 keeps lanes along the pixel index so
+    // the transposing 2-byte LDS writes of a wavefront fall into consecutive addresses.
+    const int la = F32 ? tid / VPR_A : tid % BK;
+    const int va = F32 ? tid % VPR_A : tid / BK;
+    int lb[B_LOADS], vb[B_LOADS];
+#pragma unroll
+    for (int u = 0; u < B_LOADS; ++u) {
+        const int idx = tid + 256 * u;
+        lb[u] = F32 ? idx / VPR_B : idx % BK;
+        vb[u] = F32 ? idx % VPR_B : idx / BK;
+    }
 
     const int l_begin = split * a.rows_per_split;
     const int l_end = min(a.L, l_begin + a.rows_per_split);
     const int nk = (l_end - l_begin + BK - 1) / BK;
 
-    // column (tap, channel) of this thread's B vector: fixed for the whole loop
-    const int nB = n0 + vv * VEC;
-    int b_tap = 0, b_c = 0, b_oh = 0, b_ow = 0;
-    bool b_col_ok = false;
-    if (VECLOAD) {
-        b_col_ok = nB < NT;
-        if (b_col_ok) {
-            b_tap = nB / a.C;
-            b_c = nB - b_tap * a.C;
-            b_oh = s_offh[b_tap];
-            b_ow = s_offw[b_tap];
+    // column (tap, channel) of this thread's x vectors: fixed for the whole loop
+    int b_c[B_LOADS], b_oh[B_LOADS], b_ow[B_LOADS];
+    bool b_ok[B_LOADS];
+#pragma unroll
+    for (int u = 0; u < B_LOADS; ++u) {
+        const int n = n0 + vb[u] * VEC;
+        b_ok[u] = VECLOAD && n < NT;
+        b_c[u] = b_oh[u] = b_ow[u] = 0;
+        if (b_ok[u]) {
+            const int tap = n / a.C;
+            b_c[u] = n - tap * a.C;
+            b_oh[u] = s_offh[tap];
+            b_ow[u] = s_offw[tap];
         }
     }
-    const int kA = k0 + vv * VEC;
+    const int kA = k0 + va * VEC;
 
-    Vec ra, rb;
+    Vec ra, rb[B_LOADS];
     auto zero = [](Vec &v) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) v[e] = 0;
     };
-    auto load_tile = [&](int kt) {
-        const int l = l_begin + kt * BK + l_loc;
-        zero(ra);
-        zero(rb);
-        if (l >= l_end) return;
+    auto decode = [&](int l, int &img, int &p, int &q) {
         const int pq = a.P * a.Q;
-        const int img = l / pq;
+        img = l / pq;
         const int rem = l - img * pq;
-        const int p = rem / a.Q;
-        const int q = rem - p * a.Q;
-        if (VECLOAD) {
-            if (kA < a.K) ra = *(const Vec *)(dy + (long)l * a.K + kA);
-            if (b_col_ok) {
-                const int h = p * a.sh - a.ph + b_oh, w = q * a.sw - a.pw + b_ow;
-                if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
-                    rb = *(const Vec *)(x + (((long)img * a.H + h) * a.W + w) * a.C + b_c);
-            }
-        } else {
+        p = rem / a.Q;
+        q = rem - p * a.Q;
+    };
+    auto load_tile = [&](int kt) {
+        const int base = l_begin + kt * BK;
+        zero(ra);
+        {
+            const int l = base + la;
+            if (l < l_end) {
+                if (VECLOAD) {
+                    if (kA < a.K) ra = *(const Vec *)(dy + (long)l * a.K + kA);
+                } else {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                if (kA + e < a.K) ra[e] = dy[(long)l * a.K + kA + e];
-                const int n = nB + e;
-                if (n < NT) {
-                    const int tap = n / a.C;
-                    const int c = n - tap * a.C;
-                    const int h = p * a.sh - a.ph + s_offh[tap], w = q * a.sw - a.pw + s_offw[tap];
+                    for (int e = 0; e < VEC; ++e)
+                        if (kA + e < a.K) ra[e] = dy[(long)l * a.K + kA + e];
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < B_LOADS; ++u) {
+            zero(rb[u]);
+            const int l = base + lb[u];
+            if (l >= l_end) continue;
+            int img, p, q;
+            decode(l, img, p, q);
+            if (VECLOAD) {
+                if (b_ok[u]) {
+                    const int h = p * a.sh - a.ph + b_oh[u], w = q * a.sw - a.pw + b_ow[u];
                     if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
-                        rb[e] = x[(((long)img * a.H + h) * a.W + w) * a.C + c];
+                        rb[u] = *(const Vec *)(x + (((long)img * a.H + h) * a.W + w) * a.C + b_c[u]);
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    const int n = n0 + vb[u] * VEC + e;
+                    if (n < NT) {
+                        const int tap = n / a.C;
+                        const int c = n - tap * a.C;
+                        const int h = p * a.sh - a.ph + s_offh[tap], w = q * a.sw - a.pw + s_offw[tap];
+                        if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
+                            rb[u][e] = x[(((long)img * a.H + h) * a.W + w) * a.C + c];
+                    }
                 }
             }
         }
     };
     auto store_tile = [&](int buf) {
         if constexpr (F32) {
-            *(Vec *)&As[buf][l_loc * LD + vv * VEC] = ra;
-            *(Vec *)&Bs[buf][l_loc * LD + vv * VEC] = rb;
+            *(Vec *)&As[buf][la * LDA + va * VEC] = ra;
+#pragma unroll
+            for (int u = 0; u < B_LOADS; ++u) *(Vec *)&Bs[buf][lb[u] * LDB + vb[u] * VEC] = rb[u];
         } else {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                As[buf][(vv * VEC + e) * LD + l_loc] = ra[e];
-                Bs[buf][(vv * VEC + e) * LD + l_loc] = rb[e];
-            }
+            for (int e = 0; e < VEC; ++e) As[buf][(va * VEC + e) * LDA + la] = ra[e];
+#pragma unroll
+            for (int u = 0; u < B_LOADS; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) Bs[buf][(vb[u] * VEC + e) * LDB + lb[u]] = rb[u][e];
         }
     };
 
-    f32x16 acc;
+    f32x16 acc[FN];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[ni][v] = 0.f;
 
     if (nk > 0) {
         load_tile(0);
@@ -147,16 +188,22 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
         if constexpr (F32) {
 #pragma unroll
             for (int t = 0; t < BK / 2; ++t) {
-                const float av = As[buf][(2 * t + fk) * LD + wm * 32 + frow];
-                const float bv = Bs[buf][(2 * t + fk) * LD + wn * 32 + frow];
-                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc, 0, 0, 0);
+                const float av = As[buf][(2 * t + fk) * LDA + wm * 32 + frow];
+#pragma unroll
+                for (int ni = 0; ni < FN; ++ni) {
+                    const float bv = Bs[buf][(2 * t + fk) * LDB + (wn * FN + ni) * 32 + frow];
+                    acc[ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv, acc[ni], 0, 0, 0);
+                }
             }
         } else {
 #pragma unroll
             for (int ks = 0; ks < BK; ks += 16) {
-                const Vec av = *(const Vec *)&As[buf][(wm * 32 + frow) * LD + ks + 8 * fk];
-                const Vec bv = *(const Vec *)&Bs[buf][(wn * 32 + frow) * LD + ks + 8 * fk];
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+                const Vec av = *(const Vec *)&As[buf][(wm * 32 + frow) * LDA + ks + 8 * fk];
+#pragma unroll
+                for (int ni = 0; ni < FN; ++ni) {
+                    const Vec bv = *(const Vec *)&Bs[buf][((wn * FN + ni) * 32 + frow) * LDB + ks + 8 * fk];
+                    acc[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc[ni], 0, 0, 0);
+                }
             }
         }
         if (kt + 1 < nk) store_tile(buf ^ 1);
@@ -164,23 +211,34 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
     }
 
     float *__restrict__ part = a.part + (long)split * a.K * NT;
-    const int col = n0 + wn * 32 + frow;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int k = k0 + wm * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
-        if (k < a.K && col < NT) part[(long)k * NT + col] = acc[v];
+    for (int ni = 0; ni < FN; ++ni) {
+        const int col = n0 + (wn * FN + ni) * 32 + frow;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = k0 + wm * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+            if (k < a.K && col < NT) part[(long)k * NT + col] = acc[ni][v];
+        }
     }
 }
 
+// dw[...] (=|+=) sum over splits of part[split][i], splits taken in four interleaved groups that
+// are combined in a fixed order (reproducible).  One block covers 64 consecutive outputs.
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restrict__ part, float *__restrict__ dw,
                                                             int splits, int K, int ntaps, int C, long sk, long st,
                                                             long sc, int accumulate)
 {
+    __shared__ float red[4][64];
     const long total = (long)K * ntaps * C;
-    const long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
+    const int g = threadIdx.x >> 6;
+    const long i = (long)blockIdx.x * 64 + (threadIdx.x & 63);
     float s = 0.f;
-    for (int sp = 0; sp < splits; ++sp) s += part[(long)sp * total + i];
+    if (i < total)
+        for (int sp = g; sp < splits; sp += 4) s += part[(long)sp * total + i];
+    red[g][threadIdx.x & 63] = s;
+    __syncthreads();
+    if (g != 0 || i >= total) return;
+    s = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
     const int c = (int)(i % C);
     const long r = i / C;
     const int t = (int)(r % ntaps);
@@ -189,13 +247,15 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     *o = accumulate ? *o + s : s;
 }
 
+int column_frags(int ntapsC) { return ntapsC % 192 == 0 ? 3 : 1; }
+
 }  // namespace
 
 int wgrad_rows_per_split(int dtype, int L, int K, int ntapsC, int *splits)
 {
     const int BK = dtype == NSK_BF16 ? WTraits<bf16_t>::BK : WTraits<float>::BK;
-    const long tiles = (long)ceil_div(K, WBM) * ceil_div(ntapsC, WBN);
-    long want = (1024 + tiles - 1) / tiles;
+    const long tiles = (long)ceil_div(K, WBM) * ceil_div(ntapsC, 64 * column_frags(ntapsC));
+    long want = (768 + tiles - 1) / tiles;  // about three blocks per CU
     const long most = (L + 4 * BK - 1) / (4 * BK);
     if (want > most) want = most;
     if (want < 1) want = 1;
@@ -205,31 +265,38 @@ int wgrad_rows_per_split(int dtype, int L, int K, int ntapsC, int *splits)
     return rows;
 }
 
-int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream)
+template <typename T> int launch_wgrad_typed(const WgradArgs &a, bool vec, hipStream_t stream)
 {
     const int NT = a.ntaps * a.C;
-    dim3 grid(ceil_div(NT, WBN), ceil_div(a.K, WBM), a.splits);
-    const int VEC = dtype == NSK_BF16 ? 8 : 4;
-    const bool vec = a.C % VEC == 0 && a.K % VEC == 0 && (uintptr_t)a.x % 16 == 0 && (uintptr_t)a.dy % 16 == 0;
-    if (dtype == NSK_BF16) {
+    const int fn = column_frags(NT);
+    dim3 grid(ceil_div(NT, 64 * fn), ceil_div(a.K, WBM), a.splits);
+    if (fn == 3) {
         if (vec)
-            hipLaunchKernelGGL((wgrad_kernel<bf16_t, true>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((wgrad_kernel<T, 3, true>), grid, dim3(256), 0, stream, a);
         else
-            hipLaunchKernelGGL((wgrad_kernel<bf16_t, false>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((wgrad_kernel<T, 3, false>), grid, dim3(256), 0, stream, a);
     } else {
         if (vec)
-            hipLaunchKernelGGL((wgrad_kernel<float, true>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((wgrad_kernel<T, 1, true>), grid, dim3(256), 0, stream, a);
         else
-            hipLaunchKernelGGL((wgrad_kernel<float, false>), grid, dim3(256), 0, stream, a);
+            hipLaunchKernelGGL((wgrad_kernel<T, 1, false>), grid, dim3(256), 0, stream, a);
     }
     return check_launch();
+}
+
+int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream)
+{
+    const int VEC = dtype == NSK_BF16 ? 8 : 4;
+    const bool vec = a.C % VEC == 0 && a.K % VEC == 0 && (uintptr_t)a.x % 16 == 0 && (uintptr_t)a.dy % 16 == 0;
+    if (dtype == NSK_BF16) return launch_wgrad_typed<bf16_t>(a, vec, stream);
+    return launch_wgrad_typed<float>(a, vec, stream);
 }
 
 int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int ntaps, int C, long sk,
                         long st, long sc, int accumulate, hipStream_t stream)
 {
     const long total = (long)K * ntaps * C;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, part, dw,
+    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream, part, dw,
                        splits, K, ntaps, C, sk, st, sc, accumulate);
     return check_launch();
 }

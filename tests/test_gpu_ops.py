@@ -73,7 +73,7 @@ def test_conv_fwd_dgrad_wgrad(i, dtype, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [2, 3, 8])
+@pytest.mark.parametrize("i", [1, 2, 3, 8])
 def test_conv_gradients_accumulate(i, dtype, layout):
     x, w, dy, st, pd, dl = _conv_case(i, dtype)
     ws = B.Workspace()
