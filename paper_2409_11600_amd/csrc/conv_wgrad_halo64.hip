@@ -1,0 +1,291 @@
+// Backward-weight for the 3x3, stride 1, 64 -> 64 channel layers (fp32 and bf16): the weight gradient
+// the paper accumulates into its gradient cache (section "Caching and Pooling"), for the layer shape
+// that carries most of the 3x3 FLOPs of the residual networks it trains.
+//
+// dw[k][tap][c] = sum over positions q of dy[q][k] * x[q + shift(tap)][c].  As in the forward halo
+// kernel, x and dy are addressed in flat zero-padded coordinates (every image a (H+2) x (W+2) grid,
+// all images end to end), so a tap is one constant shift, padding positions load zeros through
+// out-of-range buffer offsets, and the reduction simply runs over consecutive positions.
+//
+// A block walks over chunks of P consecutive positions.  Per chunk it stages dy[P][64] and
+// x[P + 2*halo][64] ONCE in LDS (natural position-major layout) and all nine taps read the x tile at
+// shifted rows; the 64 x 576 result lives in registers for the life of the block (2 x 18 accumulator
+// tiles of 32x32 over 4 wavefronts: each wavefront both row halves and 5 (or 4) of the 18 column
+// tiles) and is written once, as a float partial that wgrad_reduce_kernel combines in fixed order.
+//
+// The reduction index (position) is the slow index of both operands.  fp32 (mfma 32x32x2, one k per
+// lane) reads that layout directly.  bf16 (mfma 32x32x16, 8 consecutive k per lane) uses the gfx950
+// transposing LDS read (ds_read_b64_tr_b16): lanes 4j..4j+3 of a 16-lane group address row j (16
+// consecutive channels) and lane i receives channel i of the four rows, i.e. four consecutive
+// positions of one channel; rows are padded to 160 bytes so the four rows of a group cover all banks.
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned WH_OOB = 0xF0000000u;
+constexpr int WH_MAX_HALO = 64;
+
+struct WHArgs {
+    const void *x, *dy;
+    float *part;  // [blocks][64][9][64]
+    int PW, PI, H, W;
+    int total_pos, chunks, chunks_per_block, halo;
+    unsigned long long magic_pi, magic_pw;
+    unsigned bytes;  // size of x (= size of dy)
+    int tapoff[9];
+};
+
+template <typename T> struct WH;
+template <> struct WH<float> {
+    static constexpr int P = 64, ROW = 256, VPP = 16, FRAG_COL = 128;
+};
+template <> struct WH<bf16_t> {
+    static constexpr int P = 128, ROW = 160, VPP = 8, FRAG_COL = 64;
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
+{
+    typedef WH<T> C;
+    constexpr bool F32 = sizeof(T) == 4;
+    constexpr int P = C::P, ROW = C::ROW, VPP = C::VPP;
+    constexpr int XMAX = P + 2 * WH_MAX_HALO;
+    constexpr int XL = XMAX * VPP / 256, DL = P * VPP / 256;
+    constexpr int BUF = (XMAX + P) * ROW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned *in_tab = (unsigned *)(smem + 2 * BUF);  // [2][XMAX]
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fk = lane >> 5;
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t dy_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.bytes, 0x00020000);
+    const int xn = P + 2 * a.halo;
+
+    auto src_offset = [&](int q) -> unsigned {
+        const bool inside = (unsigned)q < (unsigned)a.total_pos;
+        const unsigned qq = inside ? (unsigned)q : 0u;
+        const unsigned img = (unsigned)(((unsigned long long)qq * a.magic_pi) >> 40);
+        const unsigned rem = qq - img * (unsigned)a.PI;
+        const unsigned hp = (unsigned)(((unsigned long long)rem * a.magic_pw) >> 40);
+        const unsigned wp = rem - hp * (unsigned)a.PW;
+        const bool ok = inside & (hp - 1u < (unsigned)a.H) & (wp - 1u < (unsigned)a.W);
+        const unsigned off = (((img * a.H + (hp - 1u)) * a.W + (wp - 1u)) * 64u) * (unsigned)sizeof(T);
+        return ok ? off : WH_OOB;
+    };
+    auto fill_tab = [&](int chunk, int which) {
+        if (tid < XMAX) in_tab[which * XMAX + tid] = tid < xn ? src_offset(chunk * P - a.halo + tid) : WH_OOB;
+    };
+
+    u32x4 stage[XL + DL];
+    auto issue_loads = [&](int which) {
+        const unsigned *tab = in_tab + which * XMAX;
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int idx = tid + 256 * u, pos = idx / VPP, v = idx % VPP;
+            const unsigned off = tab[pos];
+            stage[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off == WH_OOB ? WH_OOB : off + v * 16, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < DL; ++u) {
+            const int idx = tid + 256 * u, pos = idx / VPP, v = idx % VPP;
+            const unsigned off = tab[a.halo + pos];
+            stage[XL + u] = __builtin_amdgcn_raw_buffer_load_b128(dy_rsrc, off == WH_OOB ? WH_OOB : off + v * 16, 0, 0);
+        }
+    };
+    auto write_stage = [&](unsigned char *buf) {
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int idx = tid + 256 * u, pos = idx / VPP, v = idx % VPP;
+            *(u32x4 *)(buf + pos * ROW + v * 16) = stage[u];
+        }
+#pragma unroll
+        for (int u = 0; u < DL; ++u) {
+            const int idx = tid + 256 * u, pos = idx / VPP, v = idx % VPP;
+            *(u32x4 *)(buf + (XMAX + pos) * ROW + v * 16) = stage[XL + u];
+        }
+    };
+
+    // column tiles of this wavefront: nf = wave + 4*ni (tap = nf/2, channel half = nf%2); the fifth
+    // one of wavefronts 2 and 3 does not exist: it computes on tap 0 and is never stored.
+    int n_tap[5], n_half[5];
+    unsigned n_base[5];
+#pragma unroll
+    for (int ni = 0; ni < 5; ++ni) {
+        const int nf = wave + 4 * ni;
+        n_tap[ni] = nf < 18 ? nf >> 1 : 0;
+        n_half[ni] = nf < 18 ? nf & 1 : 0;
+        n_base[ni] = (unsigned)((a.halo + a.tapoff[n_tap[ni]]) * ROW + n_half[ni] * C::FRAG_COL);
+    }
+    // per-lane offset of a fragment element inside a tile (see the header comment)
+    unsigned lane_off;
+    if (F32) {
+        lane_off = (unsigned)(fk * ROW + frow * 4);
+    } else {
+        const int g = lane >> 4, i16 = lane & 15;
+        lane_off = (unsigned)((8 * (g >> 1) + (i16 >> 2)) * ROW + (16 * (g & 1) + 4 * (i16 & 3)) * 2);
+    }
+
+    f32x16 acc[2][5];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < 5; ++ni)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+
+    const int c_begin = blockIdx.x * a.chunks_per_block;
+    const int c_end = min(a.chunks, c_begin + a.chunks_per_block);
+    if (c_begin < c_end) {
+        fill_tab(c_begin, 0);
+        __syncthreads();
+        issue_loads(0);
+    }
+    for (int c = c_begin; c < c_end; ++c) {
+        const int cur = (c - c_begin) & 1;
+        unsigned char *buf = smem + cur * BUF;
+        write_stage(buf);
+        if (c + 1 < c_end) fill_tab(c + 1, cur ^ 1);
+        __syncthreads();
+        if (c + 1 < c_end) issue_loads(cur ^ 1);   // lands in registers while this chunk is computed
+
+        const unsigned char *xb = buf + lane_off;
+        const unsigned char *db = buf + XMAX * ROW + lane_off;
+        if constexpr (F32) {
+#pragma unroll 4
+            for (int s = 0; s < P / 2; ++s) {
+                float av[2], bv[5];
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) av[mi] = *(const float *)(db + 2 * s * ROW + mi * 128);
+#pragma unroll
+                for (int ni = 0; ni < 5; ++ni) bv[ni] = *(const float *)(xb + n_base[ni] + 2 * s * ROW);
+#pragma unroll
+                for (int ni = 0; ni < 5; ++ni)
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[mi], bv[ni], acc[mi][ni], 0, 0, 0);
+            }
+        } else {
+            typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+            auto tr8 = [&](const unsigned char *p) -> bf16x8 {
+                // 8 consecutive positions of this lane's channel: two transposing reads of 4 rows each
+                const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
+                const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p + 4 * ROW));
+                bf16x8 r;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    r[e] = lo[e];
+                    r[4 + e] = hi[e];
+                }
+                return r;
+            };
+            bf16x8 af[2][2], bq[2][5];
+            auto fetch = [&](int s, int set) {
+#pragma unroll
+                for (int mi = 0; mi < 2; ++mi) af[set][mi] = tr8(db + 16 * s * ROW + mi * 64);
+#pragma unroll
+                for (int ni = 0; ni < 5; ++ni) bq[set][ni] = tr8(xb + n_base[ni] + 16 * s * ROW);
+            };
+            fetch(0, 0);
+#pragma unroll
+            for (int s = 0; s < P / 16; ++s) {
+                if (s + 1 < P / 16) fetch(s + 1, (s + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int ni = 0; ni < 5; ++ni)
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi)
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[s & 1][mi], bq[s & 1][ni], acc[mi][ni], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    }
+
+    // acc[mi][ni][v]: row k = 32*mi + 8*(v/4) + 4*(lane/32) + v%4, column c = 32*half + lane%32
+    float *__restrict__ part = a.part + (long)blockIdx.x * 64 * 9 * 64;
+#pragma unroll
+    for (int ni = 0; ni < 5; ++ni) {
+        if (wave + 4 * ni >= 18) continue;
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = 32 * mi + 8 * (v >> 2) + 4 * fk + (v & 3);
+                part[(k * 9 + n_tap[ni]) * 64 + n_half[ni] * 32 + frow] = acc[mi][ni][v];
+            }
+    }
+}
+
+template <typename T> int smem_bytes()
+{
+    constexpr int XMAX = WH<T>::P + 2 * WH_MAX_HALO;
+    return 2 * (XMAX + WH<T>::P) * WH<T>::ROW + 2 * XMAX * 4;
+}
+
+}  // namespace
+
+// Geometry test shared by the workspace planner and the launcher (host only, no HIP calls).
+bool wgrad_halo64_applicable(int dtype, const WgradArgs &a)
+{
+    if (a.C != 64 || a.K != 64 || a.ntaps != 9) return false;
+    if (a.sh != 1 || a.sw != 1 || a.ph != 1 || a.pw != 1 || a.P != a.H || a.Q != a.W) return false;
+    for (int t = 0; t < 9; ++t)
+        if (a.off_h[t] != t / 3 || a.off_w[t] != t % 3) return false;
+    if (a.W + 3 > WH_MAX_HALO) return false;
+    const long long pi = (long long)(a.H + 2) * (a.W + 2), total = pi * a.Nimg;
+    if (total >= (1LL << 30) || total * pi >= (1LL << 40)) return false;
+    const unsigned long long bytes = (unsigned long long)a.Nimg * a.H * a.W * 64 * (dtype == NSK_BF16 ? 2 : 4);
+    if (bytes >= WH_OOB) return false;
+    return true;
+}
+
+// Number of float partials ([64][9][64] each) the launcher will write: at most one per CU.
+int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block)
+{
+    const int P = dtype == NSK_BF16 ? WH<bf16_t>::P : WH<float>::P;
+    const long long total = (long long)(a.H + 2) * (a.W + 2) * a.Nimg;
+    const int chunks = (int)((total + P - 1) / P);
+    const int grid = chunks < 256 ? chunks : 256;
+    const int cpb = (chunks + grid - 1) / grid;
+    if (chunks_per_block) *chunks_per_block = cpb;
+    return (chunks + cpb - 1) / cpb;
+}
+
+int launch_wgrad_halo64(int dtype, const WgradArgs &g, hipStream_t stream)
+{
+    if (((uintptr_t)g.x | (uintptr_t)g.dy) & 15) return NSK_ERR_ALIGNMENT;
+    WHArgs a{};
+    a.x = g.x; a.dy = g.dy; a.part = g.part;
+    a.H = g.H; a.W = g.W;
+    a.PW = g.W + 2; a.PI = (g.H + 2) * a.PW;
+    a.total_pos = a.PI * g.Nimg;
+    const int P = dtype == NSK_BF16 ? WH<bf16_t>::P : WH<float>::P;
+    a.chunks = ceil_div(a.total_pos, P);
+    const int blocks = wgrad_halo64_partials(dtype, g, &a.chunks_per_block);
+    a.halo = a.PW + 1;
+    a.magic_pi = ((1ULL << 40) + a.PI - 1) / a.PI;
+    a.magic_pw = ((1ULL << 40) + a.PW - 1) / a.PW;
+    a.bytes = (unsigned)((size_t)g.Nimg * g.H * g.W * 64 * (dtype == NSK_BF16 ? 2 : 4));
+    for (int t = 0; t < 9; ++t) a.tapoff[t] = (t / 3 - 1) * a.PW + (t % 3 - 1);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           smem_bytes<float>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    smem_bytes<bf16_t>());
+        if (e != hipSuccess) {
+            set_last_hip_error(e);
+            return NSK_ERR_HIP;
+        }
+        attr_set = true;
+    }
+    if (dtype == NSK_BF16)
+        hipLaunchKernelGGL(wgrad_halo64_kernel<bf16_t>, dim3(blocks), dim3(256), smem_bytes<bf16_t>(), stream, a);
+    else
+        hipLaunchKernelGGL(wgrad_halo64_kernel<float>, dim3(blocks), dim3(256), smem_bytes<float>(), stream, a);
+    return check_launch();
+}
+
+}  // namespace nsk

@@ -2,6 +2,7 @@
 // Every check that can be made without touching the device is made before the first HIP call, so
 // the error paths behave identically on a machine without a GPU.
 #include <limits.h>
+#include <stdlib.h>
 
 #include "nsk_internal.h"
 
@@ -58,6 +59,25 @@ int conv_geometry(const nsk_conv_desc_t *d, ConvGeo *g, bool need_output)
     return NSK_OK;
 }
 
+// Geometry part of the backward-weight arguments (pointers and split sizes are set by the caller).
+void wgrad_geometry(const ConvGeo &g, WgradArgs *a)
+{
+    a->Nimg = g.N; a->H = g.H; a->W = g.W; a->C = g.C; a->P = g.P; a->Q = g.Q; a->K = g.K;
+    a->sh = g.sh; a->sw = g.sw; a->ph = g.ph; a->pw = g.pw;
+    a->ntaps = g.R * g.S;
+    a->L = g.N * g.P * g.Q;
+    for (int r = 0; r < g.R; ++r)
+        for (int s = 0; s < g.S; ++s) {
+            a->off_h[r * g.S + s] = (short)(r * g.dh);
+            a->off_w[r * g.S + s] = (short)(s * g.dw);
+        }
+}
+
+bool use_wgrad_halo(const ConvGeo &g, const WgradArgs &a)
+{
+    return wgrad_halo64_applicable(g.dtype, a) && getenv("NSK_NO_HALO") == nullptr;
+}
+
 // Workspace segments (byte offsets, each 256-aligned).
 struct ConvPlan {
     size_t act_in = 0;   // NHWC copy of the NCHW input activation (x or dy)
@@ -67,6 +87,7 @@ struct ConvPlan {
     size_t part = 0;     // wgrad partial sums
     size_t total = 0;
     int splits = 1, rows_per_split = 0;
+    bool halo = false;   // wgrad: the 3x3 64->64 kernel writes one partial per block
 };
 
 ConvPlan plan_conv(const ConvGeo &g, int pass)
@@ -95,7 +116,13 @@ ConvPlan plan_conv(const ConvGeo &g, int pass)
             p.act_in = take(g.x_elems * g.es);
             p.act_in2 = take(g.y_elems * g.es);
         }
-        p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, &p.splits);
+        WgradArgs wa{};
+        wgrad_geometry(g, &wa);
+        p.halo = use_wgrad_halo(g, wa);
+        if (p.halo)
+            p.splits = wgrad_halo64_partials(g.dtype, wa, nullptr);
+        else
+            p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, &p.splits);
         p.part = take((size_t)p.splits * g.w_elems * sizeof(float));
     }
     p.total = off;
@@ -327,18 +354,13 @@ int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy,
     }
     WgradArgs a{};
     a.x = xs; a.dy = dys; a.part = (float *)(ws + p.part);
-    a.Nimg = g.N; a.H = g.H; a.W = g.W; a.C = g.C; a.P = g.P; a.Q = g.Q; a.K = g.K;
-    a.sh = g.sh; a.sw = g.sw; a.ph = g.ph; a.pw = g.pw;
-    a.ntaps = g.R * g.S;
-    a.L = g.N * g.P * g.Q;
+    wgrad_geometry(g, &a);
     a.rows_per_split = p.rows_per_split;
     a.splits = p.splits;
-    for (int r = 0; r < g.R; ++r)
-        for (int s = 0; s < g.S; ++s) {
-            a.off_h[r * g.S + s] = (short)(r * g.dh);
-            a.off_w[r * g.S + s] = (short)(s * g.dw);
-        }
-    NSK_TRY(launch_wgrad(g.dtype, a, st));
+    if (p.halo)
+        NSK_TRY(launch_wgrad_halo64(g.dtype, a, st));
+    else
+        NSK_TRY(launch_wgrad(g.dtype, a, st));
     const long RS = (long)g.R * g.S;
     if (nchw)
         NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, g.C, (long)g.C * RS, 1L, RS, accumulate, st));

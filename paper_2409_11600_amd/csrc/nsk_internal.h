@@ -80,6 +80,10 @@ struct WgradArgs {
 };
 int wgrad_rows_per_split(int dtype, int L, int K, int ntapsC, int *splits);
 int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);
+// 3x3 stride-1 64->64 special case: one [K][taps][C] partial per block, `partials` of them
+bool wgrad_halo64_applicable(int dtype, const WgradArgs &a);
+int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block);
+int launch_wgrad_halo64(int dtype, const WgradArgs &a, hipStream_t stream);
 // dw[k*sk + t*st + c*sc] (=|+=) sum_s part[s][k][t][c], fixed order.
 int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int ntaps, int C,
                         long sk, long st, long sc, int accumulate, hipStream_t stream);
