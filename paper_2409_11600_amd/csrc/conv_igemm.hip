@@ -315,6 +315,7 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
 {
     if (a.M <= 0 || a.Ngemm <= 0) return NSK_OK;
     if (forced_tile() == 0 && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
+    if (forced_tile() == 0 && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
     return dtype == NSK_BF16 ? launch_typed<bf16_t>(a, stream) : launch_typed<float>(a, stream);
 }
 

@@ -234,6 +234,7 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     const long i = (long)blockIdx.x * 64 + (threadIdx.x & 63);
     float s = 0.f;
     if (i < total)
+#pragma unroll 8
         for (int sp = g; sp < splits; sp += 4) s += part[(long)sp * total + i];
     red[g][threadIdx.x & 63] = s;
     __syncthreads();

@@ -217,6 +217,107 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// fp32, images 32 pixels wide: ROW-ALIGNED chunks.  A chunk is two rows of one image (64 real output
+// pixels, contiguous in memory for dy); x is staged as the four rows around them, each with its two
+// padding columns (4 x 34 positions).  No matrix work goes to padding positions, N*H/2 chunks divide
+// evenly over the blocks for the configured batches, and every LDS offset is a compile-time constant.
+// Each wavefront owns one half of the output channels k and one half of the input channels c for all
+// nine taps: 9 accumulator tiles, perfectly balanced.
+constexpr int R32_W = 32, R32_PW = 34;
+constexpr int R32_XPOS = 4 * R32_PW;   // 136 staged x positions
+constexpr int R32_ROW = 256;           // bytes per position (64 floats)
+constexpr int R32_BUF = (R32_XPOS + 64) * R32_ROW;
+constexpr int R32_XL = (R32_XPOS * 16 + 255) / 256;   // 9 x vectors per thread (the last pass is partial)
+
+struct WR32Args {
+    const void *x, *dy;
+    float *part;
+    int H, PI, chunks_per_img, chunks, chunks_per_block, total_pos;
+    unsigned long long magic_pi;
+    unsigned bytes;
+};
+
+__global__ __launch_bounds__(256) void wgrad_rows32_f32_kernel(const WR32Args a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int frow = lane & 31, fk = lane >> 5;
+    const int mi = wave & 1, ch = wave >> 1;
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t dy_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.bytes, 0x00020000);
+
+    // staged x position p of chunk (img, h0): padded row h0 + p/34 (real row h0 - 1 + p/34), padded column p%34
+    u32x4 stage[R32_XL + 4];
+    auto issue_loads = [&](int chunk) {
+        const int img = chunk / a.chunks_per_img, h0 = (chunk % a.chunks_per_img) * 2;
+#pragma unroll
+        for (int u = 0; u < R32_XL; ++u) {
+            const int idx = tid + 256 * u, p = idx >> 4, v = idx & 15;
+            const int pr = p / R32_PW, pc = p - pr * R32_PW;
+            const int h = h0 - 1 + pr, w = pc - 1;
+            const bool ok = p < R32_XPOS && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)R32_W;
+            const unsigned off = (unsigned)((((img * a.H + h) * R32_W + w) * 64 + v * 4) * 4);
+            stage[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, ok ? off : WH_OOB, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int idx = tid + 256 * u;   // 64 pixels x 16 vectors, contiguous in memory
+            stage[R32_XL + u] = __builtin_amdgcn_raw_buffer_load_b128(
+                dy_rsrc, (unsigned)(((img * a.H + h0) * R32_W * 64 + idx * 4) * 4), 0, 0);
+        }
+    };
+    auto write_stage = [&](unsigned char *buf) {
+#pragma unroll
+        for (int u = 0; u < R32_XL; ++u) {
+            const int idx = tid + 256 * u;
+            if (idx < R32_XPOS * 16) *(u32x4 *)(buf + idx * 16) = stage[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) *(u32x4 *)(buf + R32_XPOS * R32_ROW + (tid + 256 * u) * 16) = stage[R32_XL + u];
+    };
+
+    f32x16 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+    const int c_begin = blockIdx.x * a.chunks_per_block;
+    const int c_end = min(a.chunks, c_begin + a.chunks_per_block);
+    if (c_begin < c_end) issue_loads(c_begin);
+    const unsigned a_lane = (unsigned)(R32_XPOS * R32_ROW + fk * R32_ROW + (32 * mi + frow) * 4);
+    const unsigned b_lane = (unsigned)(fk * R32_ROW + (32 * ch + frow) * 4);
+    for (int c = c_begin; c < c_end; ++c) {
+        unsigned char *buf = smem + ((c - c_begin) & 1) * R32_BUF;
+        write_stage(buf);
+        __syncthreads();
+        if (c + 1 < c_end) issue_loads(c + 1);
+#pragma unroll
+        for (int s = 0; s < 32; ++s) {
+            // output pixels 2s, 2s+1 of the chunk: row r = s/16, columns (2s)%32 + {0,1}
+            const int r = s >> 4, col = (2 * s) & 31;
+            const float av = *(const float *)(buf + a_lane + 2 * s * R32_ROW);
+            float bv[9];
+#pragma unroll
+            for (int t = 0; t < 9; ++t)
+                bv[t] = *(const float *)(buf + b_lane + ((r + t / 3) * R32_PW + col + t % 3) * R32_ROW);
+#pragma unroll
+            for (int t = 0; t < 9; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(av, bv[t], acc[t], 0, 0, 0);
+        }
+    }
+    float *__restrict__ part = a.part + (long)blockIdx.x * 64 * 9 * 64;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = 32 * mi + 8 * (v >> 2) + 4 * fk + (v & 3);
+            part[(k * 9 + t) * 64 + ch * 32 + frow] = acc[t][v];
+        }
+}
+
+bool rows32_f32(int dtype, const WgradArgs &a) { return dtype == NSK_F32 && a.W == R32_W && a.H % 2 == 0; }
+
 template <typename T> int smem_bytes()
 {
     constexpr int XMAX = WH<T>::P + 2 * WH_MAX_HALO;
@@ -245,7 +346,8 @@ int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block)
 {
     const int P = dtype == NSK_BF16 ? WH<bf16_t>::P : WH<float>::P;
     const long long total = (long long)(a.H + 2) * (a.W + 2) * a.Nimg;
-    const int chunks = (int)((total + P - 1) / P);
+    int chunks = (int)((total + P - 1) / P);
+    if (rows32_f32(dtype, a)) chunks = a.Nimg * (a.H / 2);   // row-aligned chunks of two image rows
     const int grid = chunks < 256 ? chunks : 256;
     const int cpb = (chunks + grid - 1) / grid;
     if (chunks_per_block) *chunks_per_block = cpb;
@@ -255,6 +357,26 @@ int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block)
 int launch_wgrad_halo64(int dtype, const WgradArgs &g, hipStream_t stream)
 {
     if (((uintptr_t)g.x | (uintptr_t)g.dy) & 15) return NSK_ERR_ALIGNMENT;
+    if (rows32_f32(dtype, g)) {
+        WR32Args r{};
+        r.x = g.x; r.dy = g.dy; r.part = g.part;
+        r.H = g.H;
+        r.chunks_per_img = g.H / 2;
+        r.chunks = g.Nimg * r.chunks_per_img;
+        const int blocks = wgrad_halo64_partials(dtype, g, &r.chunks_per_block);
+        r.bytes = (unsigned)((size_t)g.Nimg * g.H * g.W * 64 * 4);
+        static bool r_attr = false;
+        if (!r_attr) {
+            hipError_t e = hipFuncSetAttribute((const void *)wgrad_rows32_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R32_BUF);
+            if (e != hipSuccess) {
+                set_last_hip_error(e);
+                return NSK_ERR_HIP;
+            }
+            r_attr = true;
+        }
+        hipLaunchKernelGGL(wgrad_rows32_f32_kernel, dim3(blocks), dim3(256), 2 * R32_BUF, stream, r);
+        return check_launch();
+    }
     WHArgs a{};
     a.x = g.x; a.dy = g.dy; a.part = g.part;
     a.H = g.H; a.W = g.W;

@@ -61,6 +61,9 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream);
 // bf16 3x3 stride-1 64->64 special case (filter resident in LDS, input tile staged once with halo)
 bool halo64_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64(const IgemmArgs &a, hipStream_t stream);
+// fp32 sibling (filter streamed one tap at a time through LDS)
+bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
+int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);
 
 // ------------------------------------------------------------------ wgrad
 // part[split][k][t][c] = sum over the split's share of rows l = (img, p, q) of
