@@ -56,6 +56,26 @@ template <typename T> __global__ __launch_bounds__(256) void pack_filter_kernel(
     ((T *)a.out)[i] = ((const T *)a.w)[n * a.sn + a.tap_off[t] + c * a.sc];
 }
 
+// Zero the pixels (i*osh + oa, j*osw + ob), i < Mi, j < Mj, of every image of an NHWC tensor: the cells
+// of a strided backward-data result that no filter tap reaches.  `unit` = bytes written per thread.
+__global__ __launch_bounds__(256) void zero_class_kernel(unsigned char *__restrict__ out, long total, int Mi, int Mj, int Ho,
+                                                         int Wo, int osh, int oa, int osw, int ob, int pix_bytes,
+                                                         int unit)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int upp = pix_bytes / unit;            // units per pixel
+    const int u = (int)(i % upp);
+    long r = i / upp;
+    const int j = (int)(r % Mj); r /= Mj;
+    const int ii = (int)(r % Mi);
+    const long img = r / Mi;
+    unsigned char *p = out + ((img * Ho + (ii * osh + oa)) * Wo + (j * osw + ob)) * (long)pix_bytes + (long)u * unit;
+    if (unit == 16) *(f32x4 *)p = f32x4{0.f, 0.f, 0.f, 0.f};
+    else if (unit == 4) *(float *)p = 0.f;
+    else *(unsigned short *)p = 0;
+}
+
 template <typename T>
 int transpose_typed(const void *src, void *dst, int batch, int rows, int cols, int accumulate, hipStream_t stream)
 {
@@ -78,6 +98,18 @@ int launch_nhwc_to_nchw(int dtype, const void *src, void *dst, int N, int C, int
 {
     if (dtype == NSK_BF16) return transpose_typed<bf16_t>(src, dst, N, H * W, C, accumulate, stream);
     return transpose_typed<float>(src, dst, N, H * W, C, accumulate, stream);
+}
+
+int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, int Mi, int Mj, int osh, int oa, int osw,
+                      int ob, hipStream_t stream)
+{
+    const int pix_bytes = Co * (int)elem_size(dtype);
+    const int unit = pix_bytes % 16 == 0 ? 16 : (pix_bytes % 4 == 0 ? 4 : 2);
+    const long total = (long)Nimg * Mi * Mj * (pix_bytes / unit);
+    if (total == 0) return NSK_OK;
+    hipLaunchKernelGGL(zero_class_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, (unsigned char *)out,
+                       total, Mi, Mj, Ho, Wo, osh, oa, osw, ob, pix_bytes, unit);
+    return check_launch();
 }
 
 int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, int Cs, long sn, long sc,

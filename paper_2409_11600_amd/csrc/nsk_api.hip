@@ -306,6 +306,10 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
                 }
             }
             if (nt == 0 && accumulate && !nchw) continue;  // nothing to add
+            if (nt == 0) {   // no tap reaches this class: plain zero fill
+                NSK_TRY(launch_zero_class(g.dtype, dst, g.N, g.H, g.W, g.C, Mi, Mj, g.sh, ca, g.sw, cb, st));
+                continue;
+            }
             // packed filter of this class: [c][tap][k]
             if (nt > 0) {
                 if (nchw)

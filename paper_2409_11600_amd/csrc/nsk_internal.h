@@ -102,6 +102,10 @@ int launch_nhwc_to_nchw(int dtype, const void *src, void *dst, int N, int C, int
 int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, int Cs, long sn,
                        long sc, const int *tap_off_host, hipStream_t stream);
 
+// out[img][i*osh + oa][j*osw + ob][0..Co) = 0 for i < Mi, j < Mj (NHWC).
+int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, int Mi, int Mj, int osh, int oa, int osw,
+                      int ob, hipStream_t stream);
+
 // ------------------------------------------------------------------ batch-norm, pooling
 int bn_partial_blocks(const nsk_bn_desc_t &d);
 int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,

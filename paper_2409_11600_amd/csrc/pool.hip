@@ -85,10 +85,29 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T *__restrict__ 
         }
     }
     const long o = n * g.ys_n + c * g.ys_c + p * g.ys_h + q * g.ys_w;
+    if constexpr (VEC == 8) {
+        bf16x8 yv;
+        unsigned long long iv = 0;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) {
-        y[o + e] = (T)best[e];
-        idx[o + e] = (signed char)where[e];
+        for (int e = 0; e < VEC; ++e) {
+            yv[e] = (bf16_t)best[e];
+            iv |= (unsigned long long)(unsigned char)(signed char)where[e] << (8 * e);
+        }
+        *(bf16x8 *)(y + o) = yv;
+        *(unsigned long long *)(idx + o) = iv;
+    } else if constexpr (VEC == 4) {
+        f32x4 yv;
+        unsigned iv = 0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            yv[e] = best[e];
+            iv |= (unsigned)(unsigned char)(signed char)where[e] << (8 * e);
+        }
+        *(f32x4 *)(y + o) = yv;
+        *(unsigned *)(idx + o) = iv;
+    } else {
+        y[o] = (T)best[0];
+        idx[o] = (signed char)where[0];
     }
 }
 
@@ -126,13 +145,36 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T *__restrict__ 
         for (int q = q_lo; q <= q_hi; ++q) {
             const int pos = (h + g.ph - p * g.sh) * g.S + (w + g.pw - q * g.sw);
             const long o = n * g.ys_n + c * g.ys_c + p * g.ys_h + q * g.ys_w;
+            if constexpr (VEC == 8) {   // one 8-byte index load and one 16-byte gradient load per window
+                const unsigned long long iv = *(const unsigned long long *)(idx + o);
+                const bf16x8 gv = *(const bf16x8 *)(dy + o);
 #pragma unroll
-            for (int e = 0; e < VEC; ++e)
-                if (idx[o + e] == pos) acc[e] += (float)dy[o + e];
+                for (int e = 0; e < VEC; ++e)
+                    if ((int)(signed char)(iv >> (8 * e)) == pos) acc[e] += (float)gv[e];
+            } else if constexpr (VEC == 4) {
+                const unsigned iv = *(const unsigned *)(idx + o);
+                const f32x4 gv = *(const f32x4 *)(dy + o);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+                    if ((int)(signed char)(iv >> (8 * e)) == pos) acc[e] += gv[e];
+            } else {
+                if (idx[o] == pos) acc[0] += (float)dy[o];
+            }
         }
     const long o = n * g.xs_n + c * g.xs_c + h * g.xs_h + w * g.xs_w;
+    if constexpr (VEC == 8) {
+        bf16x8 v;
 #pragma unroll
-    for (int e = 0; e < VEC; ++e) dx[o + e] = (T)acc[e];
+        for (int e = 0; e < VEC; ++e) v[e] = (bf16_t)acc[e];
+        *(bf16x8 *)(dx + o) = v;
+    } else if constexpr (VEC == 4) {
+        f32x4 v;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = acc[e];
+        *(f32x4 *)(dx + o) = v;
+    } else {
+        dx[o] = (T)acc[0];
+    }
 }
 
 template <typename T, int VEC>
