@@ -93,7 +93,10 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
         return ok ? off : H_OOB;
     };
 
-    u32x4 stage[H_PASSES];
+    // Two register sets: while tile t is multiplied, tile t+G is already in (or on its way into) one
+    // set and the loads of tile t+2G are issued into the set that tile t has just vacated.  HBM latency
+    // under load (several microseconds) is longer than the matrix work of one tile.
+    u32x4 stageA[H_PASSES], stageB[H_PASSES];
     // one of the H_PASSES 16-byte loads of a tile's staged input (8 lanes per position)
     // in_tab[p] = byte offset of staged position p of the tile being prefetched (or out of range):
     // computed by two positions per thread, so the eight lanes that share a position do not repeat
@@ -115,22 +118,35 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
             poff[u] = off == H_OOB ? H_OOB : off + chunk * 16;
         }
     };
-    auto prefetch_piece = [&](int u) { stage[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, poff[u], 0, 0); };
+    auto prefetch_piece = [&](u32x4 (&S)[H_PASSES], int u) { S[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, poff[u], 0, 0); };
 
-    int tile = blockIdx.x;
-    if (tile < a.tiles) {
+    // each block owns a contiguous run of tiles: the halo a tile shares with its successor was fetched by
+    // this same CU moments ago and is still in its L2 (a strided assignment re-fetched every halo from HBM)
+    constexpr int G = 1;
+    const int tiles_per_block = (a.tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int t_end = min(a.tiles, ((int)blockIdx.x + 1) * tiles_per_block);
+    int tile = blockIdx.x * tiles_per_block;
+    if (tile < t_end) {
         fill_in_tab(tile);
         __syncthreads();
         read_in_tab();
 #pragma unroll
-        for (int u = 0; u < H_PASSES; ++u) prefetch_piece(u);
+        for (int u = 0; u < H_PASSES; ++u) prefetch_piece(stageA, u);
+        __syncthreads();
+        if (tile + G < t_end) {
+            fill_in_tab(tile + G);
+            __syncthreads();
+            read_in_tab();
+#pragma unroll
+            for (int u = 0; u < H_PASSES; ++u) prefetch_piece(stageB, u);
+        }
     }
 
     const unsigned a_base0 = (unsigned)((wave * 64 + frow + a.halo) * H_IN_STRIDE + fk * 16);
     const unsigned b_base0 = (unsigned)(frow * H_W_STRIDE + fk * 16);
     unsigned char *my_st = st_lds + wave * (32 * H_IN_STRIDE);
 
-    for (; tile < a.tiles; tile += gridDim.x) {
+    auto do_tile = [&](int tile, u32x4 (&stage)[H_PASSES]) {
         // staged registers -> LDS (the barrier at the end of the previous tile freed the buffer)
 #pragma unroll
         for (int u = 0; u < H_PASSES; ++u) {
@@ -138,8 +154,8 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
             if (p < n_in) *(u32x4 *)(in_lds + p * H_IN_STRIDE + chunk * 16) = stage[u];
         }
         out_tab[tid] = src_offset(tile * HT + tid);   // the output tensor has the same geometry
-        const int next = tile + (int)gridDim.x;
-        const bool have_next = next < a.tiles;
+        const int next = tile + 2 * G;                // the tile whose loads go into the set just emptied
+        const bool have_next = next < t_end;
         if (have_next) fill_in_tab(next);   // the previous tile's reads of in_tab are complete
         __syncthreads();
         if (have_next) {
@@ -199,7 +215,7 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
 #pragma unroll
         for (int step = 0; step < 36; ++step) {
             if (step + 2 < 36) fetch(step + 2, (step + 2) % 3);
-            if (step < H_PASSES) prefetch_piece(step);   // unconditional: without a next tile the offsets are out of range
+            if (step < H_PASSES) prefetch_piece(stage, step);   // unconditional: without a next tile the offsets are out of range
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mi = 0; mi < 2; ++mi)
@@ -232,6 +248,10 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
             }
         }
         __syncthreads();
+    };
+    for (; tile < t_end; tile += 2 * G) {
+        do_tile(tile, stageA);
+        if (tile + G < t_end) do_tile(tile + G, stageB);
     }
 }
 

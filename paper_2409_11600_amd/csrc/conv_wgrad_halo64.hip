@@ -17,7 +17,8 @@
 // lane) reads that layout directly.  bf16 (mfma 32x32x16, 8 consecutive k per lane) uses the gfx950
 // transposing LDS read (ds_read_b64_tr_b16): lanes 4j..4j+3 of a 16-lane group address row j (16
 // consecutive channels) and lane i receives channel i of the four rows, i.e. four consecutive
-// positions of one channel; rows are padded to 160 bytes so the four rows of a group cover all banks.
+// positions of one channel; rows are padded to 192 bytes so that the four rows read by each of two
+// neighbouring 16-lane groups fall into eight different 32-byte bank groups of the 64-bank LDS.
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -42,7 +43,7 @@ template <> struct WH<float> {
     static constexpr int P = 64, ROW = 256, VPP = 16, FRAG_COL = 128;
 };
 template <> struct WH<bf16_t> {
-    static constexpr int P = 128, ROW = 160, VPP = 8, FRAG_COL = 64;
+    static constexpr int P = 128, ROW = 192, VPP = 8, FRAG_COL = 64;
 };
 
 template <typename T>
