@@ -55,8 +55,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
     constexpr int A_PASSES = BM / RPP;
     constexpr int B_PASSES = (BN + RPP - 1) / RPP;
 
-    __shared__ __attribute__((aligned(16))) T As[2][BM * LDK];
-    __shared__ __attribute__((aligned(16))) T Bs[2][BN * LDK];
+    __shared__ __attribute__((aligned(16))) T smem_ab[2 * (BM + BN) * LDK];
+    T(*As)[BM * LDK] = (T(*)[BM * LDK])smem_ab;
+    T(*Bs)[BN * LDK] = (T(*)[BN * LDK])(smem_ab + 2 * BM * LDK);
     __shared__ long out_off[BM];
     __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
 
@@ -199,6 +200,12 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         }
     };
 
+    // The filter rows are the MFMA "A" operand and the pixels the "B" operand, so a lane ends up with 4
+    // CONSECUTIVE CHANNELS of one pixel per accumulator quad: acc[mi][ni][4g+j] is channel
+    // 32*ni + 8*g + 4*(lane/32) + j of pixel 32*mi + lane%32 of the wavefront's sub-tile.
+    const int frow = lane & 31, fk = lane >> 5;
+    T *__restrict__ out = (T *)a.out;
+    const int wcol0 = n0 + wn * WN;   // first output channel of this wavefront
     f32x16 acc[FM][FN];
 #pragma unroll
     for (int mi = 0; mi < FM; ++mi)
@@ -206,9 +213,25 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         for (int ni = 0; ni < FN; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    if (a.accumulate && a.vec_out) {
+        // start from the old values: the sum is then rounded to the storage type exactly once
+#pragma unroll
+        for (int mi = 0; mi < FM; ++mi) {
+            const long off = out_off[wm * WM + mi * 32 + frow];
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = wcol0 + ni * 32 + g * 8 + fk * 4;
+                    if (off >= 0 && col < a.Ngemm) {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) acc[mi][ni][g * 4 + j] = to_float(out[off + col + j]);
+                    }
+                }
+        }
+    }
 
     const int nk = (a.Ktot + BK - 1) / BK;
-    const int frow = lane & 31, fk = lane >> 5;
     if (nk > 0) {
         load_tile(0);
         store_tile(0);
@@ -231,7 +254,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
                 for (int mi = 0; mi < FM; ++mi)
 #pragma unroll
                     for (int ni = 0; ni < FN; ++ni)
-                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfv[ni], acc[mi][ni], 0, 0, 0);
+                        acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfv[ni], af[mi], acc[mi][ni], 0, 0, 0);
             } else {
                 // Lane (row, half) holds k = 4*half + t of this group of 8; the same map is used
                 // for both operands, so the four steps together cover the 8 k exactly once.
@@ -241,32 +264,60 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
                     for (int mi = 0; mi < FM; ++mi)
 #pragma unroll
                         for (int ni = 0; ni < FN; ++ni)
-                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[mi][t], bfv[ni][t], acc[mi][ni], 0, 0, 0);
+                            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x2f32(bfv[ni][t], af[mi][t], acc[mi][ni], 0, 0, 0);
             }
         }
         if (kt + 1 < nk) store_tile(buf ^ 1);
         __syncthreads();
     }
 
-    // Accumulator element v of a 32x32 tile sits at row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
-    T *__restrict__ out = (T *)a.out;
+    if (a.vec_out) {
+        // Round to the storage type, transpose one 32 x 32 accumulator tile at a time through this
+        // wavefront's strip of the (now idle) operand buffers, and store 16 contiguous bytes per lane.
+        typedef T T4 __attribute__((ext_vector_type(4)));
+        constexpr int SROW = 32 * (int)sizeof(T) + 16;      // staged bytes per pixel (padded)
+        constexpr int CPP = 32 * (int)sizeof(T) / 16;       // 16-byte chunks per pixel
+        static_assert(4 * 32 * SROW <= (int)sizeof(smem_ab), "epilogue staging fits in the operand buffers");
+        unsigned char *my_st = (unsigned char *)smem_ab + wave * (32 * SROW);
 #pragma unroll
-    for (int mi = 0; mi < FM; ++mi)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int row = wm * WM + mi * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
-            const long off = out_off[row];
-            if (off < 0) continue;
+        for (int mi = 0; mi < FM; ++mi)
 #pragma unroll
             for (int ni = 0; ni < FN; ++ni) {
-                const int col = n0 + wn * WN + ni * 32 + frow;
-                if (col < a.Ngemm) {
-                    float r = acc[mi][ni][v];
-                    if (a.accumulate) r += to_float(out[off + col]);
-                    out[off + col] = (T)r;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    T4 pk;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) pk[j] = (T)acc[mi][ni][g * 4 + j];
+                    *(T4 *)(my_st + frow * SROW + (g * 8 + fk * 4) * (int)sizeof(T)) = pk;
+                }
+#pragma unroll
+                for (int jj = 0; jj < 32 * CPP / 64; ++jj) {
+                    const int idx = lane + 64 * jj, pos = idx / CPP, ck = idx % CPP;
+                    const Vec v = *(const Vec *)(my_st + pos * SROW + ck * 16);
+                    const long off = out_off[wm * WM + mi * 32 + pos];
+                    const int col = wcol0 + ni * 32 + ck * VEC;
+                    if (off >= 0 && col < a.Ngemm) *(Vec *)(out + off + col) = v;
                 }
             }
+    } else {
+        // element-wise stores (output rows that are not 16-byte granular)
+#pragma unroll
+        for (int mi = 0; mi < FM; ++mi) {
+            const long off = out_off[wm * WM + mi * 32 + frow];
+            if (off < 0) continue;
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int col = wcol0 + ni * 32 + 8 * (v >> 2) + 4 * fk + (v & 3);
+                    if (col < a.Ngemm) {
+                        float r = acc[mi][ni][v];
+                        if (a.accumulate) r += to_float(out[off + col]);
+                        out[off + col] = (T)r;
+                    }
+                }
         }
+    }
 }
 
 template <typename T, int BM, int BN, int WM, int WN, int BKB>
@@ -316,7 +367,10 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (a.M <= 0 || a.Ngemm <= 0) return NSK_OK;
     if (forced_tile() == 0 && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
     if (forced_tile() == 0 && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
-    return dtype == NSK_BF16 ? launch_typed<bf16_t>(a, stream) : launch_typed<float>(a, stream);
+    IgemmArgs b = a;
+    const int vec = dtype == NSK_BF16 ? 8 : 4;
+    b.vec_out = (b.Ngemm % vec == 0 && b.Co % vec == 0 && (uintptr_t)b.out % 16 == 0) ? 1 : 0;
+    return dtype == NSK_BF16 ? launch_typed<bf16_t>(b, stream) : launch_typed<float>(b, stream);
 }
 
 }  // namespace nsk

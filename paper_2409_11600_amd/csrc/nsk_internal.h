@@ -53,6 +53,7 @@ struct IgemmArgs {
     int Ho, Wo, Co;
     int osh, oa, osw, ob;
     int accumulate;
+    int vec_out;  // set by launch_igemm: output rows are 16-byte granular, vector epilogue
     unsigned src_bytes, wpk_bytes;  // sizes of src and wpk (both below 4 GiB: buffer addressing)
     short off_h[kMaxTaps];
     short off_w[kMaxTaps];
