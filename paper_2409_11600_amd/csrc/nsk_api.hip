@@ -13,13 +13,6 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 
 namespace {
 
-struct ConvGeo {
-    int N, C, H, W, K, R, S, sh, sw, ph, pw, dh, dw, P, Q;
-    int dtype, layout;
-    size_t es;
-    size_t x_elems, y_elems, w_elems;
-};
-
 int out_extent(int in, int pad, int dil, int filt, int stride)
 {
     const long span = (long)in + 2L * pad - (long)dil * (filt - 1) - 1;
@@ -88,11 +81,17 @@ struct ConvPlan {
     size_t total = 0;
     int splits = 1, rows_per_split = 0;
     bool halo = false;   // wgrad: the 3x3 64->64 kernel writes one partial per block
+    bool stem = false;   // the space-to-depth path plans its own workspace
 };
 
 ConvPlan plan_conv(const ConvGeo &g, int pass)
 {
     ConvPlan p;
+    p.stem = stem_applicable(g);
+    if (p.stem) {
+        p.total = stem_workspace_bytes(g, pass);
+        return p;
+    }
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
@@ -224,6 +223,7 @@ int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, vo
     NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
+    if (p.stem) return stem_fwd(g, x, w, y, ws, st);
 
     const void *src = x, *filt = w;
     void *dst = y;
@@ -271,6 +271,7 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const bool nchw = g.layout == NSK_NCHW;
+    if (p.stem) return stem_dgrad(g, dy, w, dx, accumulate, ws, st);
 
     const void *src = dy;
     void *dst = dx;
@@ -349,6 +350,7 @@ int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy,
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
     const bool nchw = g.layout == NSK_NCHW;
+    if (p.stem) return stem_wgrad(g, x, dy, dw, accumulate, ws, st);
     const void *xs = x, *dys = dy;
     if (nchw) {
         NSK_TRY(launch_nchw_to_nhwc(g.dtype, x, ws + p.act_in, g.N, g.C, g.H, g.W, st));

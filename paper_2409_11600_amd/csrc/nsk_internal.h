@@ -34,6 +34,14 @@ inline int check_launch()
     return NSK_OK;
 }
 
+// Validated geometry of one convolution descriptor.
+struct ConvGeo {
+    int N, C, H, W, K, R, S, sh, sw, ph, pw, dh, dw, P, Q;
+    int dtype, layout;
+    size_t es;
+    size_t x_elems, y_elems, w_elems;
+};
+
 // ------------------------------------------------------------------ implicit GEMM (fwd, dgrad)
 // One launch computes, for every GEMM row m = (img, i, j) with i < Mi, j < Mj and every
 // column n < Ngemm:
@@ -91,6 +99,16 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &a, hipStream_t stream);
 // dw[k*sk + t*st + c*sc] (=|+=) sum_s part[s][k][t][c], fixed order.
 int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int ntaps, int C,
                         long sk, long st, long sc, int accumulate, hipStream_t stream);
+
+// ------------------------------------------------------------------ image stem
+// Stride-2 odd square filter with "same" padding on at most 4 input channels and even H, W: all three
+// passes run on a space-to-depth copy of the image (16 channels, stride 1).  `ws` must hold
+// stem_workspace_bytes(g, pass) bytes.
+bool stem_applicable(const ConvGeo &g);
+size_t stem_workspace_bytes(const ConvGeo &g, int pass);
+int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, hipStream_t stream);
+int stem_dgrad(const ConvGeo &g, const void *dy, const void *w, void *dx, int accumulate, char *ws, hipStream_t stream);
+int stem_wgrad(const ConvGeo &g, const void *x, const void *dy, float *dw, int accumulate, char *ws, hipStream_t stream);
 
 // ------------------------------------------------------------------ layout helpers
 // dst NHWC <- src NCHW (plain copy).

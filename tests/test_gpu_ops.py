@@ -27,6 +27,9 @@ CONV_SHAPES = [
     (2, 24, 14, 12, 20, 3, 2, (2, 1), (1, 0), (1, 2)),   # anisotropic stride, pad, dilation
     (1, 8, 12, 12, 8, 3, 3, 1, 2, 2),          # dilation 2
     (1, 5, 9, 9, 7, 3, 3, 3, 1, 1),            # stride 3, odd channel counts (scalar paths)
+    (2, 3, 38, 42, 64, 7, 7, 2, 3, 1),         # 7x7 stride-2 stem, even extents (space-to-depth path)
+    (1, 4, 20, 16, 24, 5, 5, 2, 2, 1),         # 5x5 stride-2, 4 channels (space-to-depth, 3x3 coarse taps)
+    (2, 1, 12, 18, 16, 3, 3, 2, 1, 1),         # 3x3 stride-2, single channel (space-to-depth, 2x2 coarse taps)
 ]
 
 
@@ -73,7 +76,7 @@ def test_conv_fwd_dgrad_wgrad(i, dtype, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [1, 2, 3, 8])
+@pytest.mark.parametrize("i", [1, 2, 3, 8, 12, 13])
 def test_conv_gradients_accumulate(i, dtype, layout):
     x, w, dy, st, pd, dl = _conv_case(i, dtype)
     ws = B.Workspace()
