@@ -21,6 +21,8 @@
 // Block = 256 threads = 4 wavefronts, each owning 64 positions x 64 output channels as 2 x 2
 // accumulators of 32x32.  LDS rows are padded (144 B per position, 1168 B per filter row) so that the
 // 16-byte fragment reads of 8 consecutive rows cover all banks once.
+#include <stdlib.h>
+
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -255,6 +257,236 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// Two-group ("ping-pong") variant.  In the kernel above the four wavefronts stage, multiply and store
+// one after the other, so the matrix units idle during staging and the epilogue (about 45% of a tile's
+// time).  Here a block has EIGHT wavefronts in two groups of four that share the resident filter.  In
+// phase p one group multiplies tile p while the other stores tile p-1 and stages the input rows tile p+1
+// will need; one block-wide barrier per phase, and the groups swap roles.  Two wavefronts share each SIMD,
+// so the vector, LDS and memory instructions of one run in the shadow of the other's MFMAs.
+//
+// Input ring.  Consecutive tiles of a block overlap by their halos, so the staged positions live in a
+// ring of RING = 512 + 2*halo slots of 128 bytes: tile p reads ring rows [256p, 256p + 256 + 2*halo), and
+// the 256 rows staged in phase p (for tile p+1) land exactly on the rows tile p-1 has just finished with.
+// Those same dead rows, split into four private 64-slot strips, first serve as the transposing buffer of
+// the storing group's epilogue, so no wavefront ever needs another's LDS data inside a phase.
+// Slots are not padded; the 16-byte chunk index is XOR-ed with bits 1..3 of the slot number, which makes
+// the fragment reads of 16 consecutive slots hit all 64 banks once.
+constexpr int P_RING_MAX = 640;    // 512 + 2*halo <= 640  ->  W <= 61
+constexpr int P_SLOT = 128;
+
+template <bool ACCUM>
+__global__ __launch_bounds__(512) void conv_halo64_pp_kernel(const HaloArgs a)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *ring = smem;                                  // P_RING_MAX * 128
+    unsigned char *w_lds = smem + P_RING_MAX * P_SLOT;           // 64 * 1168
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int grp = wave >> 2, x = wave & 3;
+    const int frow = lane & 31, fk = lane >> 5;
+    const int prow = lane >> 3, chunk = lane & 7;
+    const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, a.out_bytes, 0x00020000);
+
+    const int tiles_per_block = (a.tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int T0 = blockIdx.x * tiles_per_block;
+    const int n = min(a.tiles, T0 + tiles_per_block) - T0;      // tiles of this block
+    if (n <= 0) return;                                          // uniform for the block: no barrier is skipped
+    const unsigned RING = 512u + 2u * (unsigned)a.halo;
+    const int Q0 = T0 * HT - a.halo;                             // padded position held by ring row 0
+
+    auto src_offset = [&](int q) -> unsigned {
+        const bool inside = (unsigned)q < (unsigned)a.total_pos;
+        const unsigned qq = inside ? (unsigned)q : 0u;
+        const unsigned img = (unsigned)(((unsigned long long)qq * a.magic_pi) >> 40);
+        const unsigned rem = qq - img * (unsigned)a.PI;
+        const unsigned hp = (unsigned)(((unsigned long long)rem * a.magic_pw) >> 40);
+        const unsigned wp = rem - hp * (unsigned)a.PW;
+        const bool ok = inside & (hp - 1u < (unsigned)a.H) & (wp - 1u < (unsigned)a.W);
+        const unsigned off = (((img * a.H + (hp - 1u)) * a.W + (wp - 1u)) * 64u) * 2u;
+        return ok ? off : H_OOB;
+    };
+    // s < 2*RING  ->  s mod RING  (s - RING wraps to a huge value when s < RING)
+    auto wrap = [&](unsigned s) -> unsigned { return min(s, s - RING); };
+    auto slot_addr = [&](unsigned slot, unsigned c) -> unsigned { return slot * P_SLOT + ((c ^ ((slot >> 1) & 7u)) << 4); };
+    // Byte offsets of 64 consecutive padded positions starting at q_first, as this lane needs them for
+    // its eight 16-byte pieces (piece u = position prow + 8u, channel chunk `chunk`): lane L does the index
+    // arithmetic for position L and the results are exchanged across lanes.  An out-of-range marker stays
+    // out of range after the chunk offset is added.
+    auto row_offsets = [&](int q_first, bool valid, unsigned (&off)[8]) {
+        const unsigned mine = valid ? src_offset(q_first + lane) : H_OOB;
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            off[u] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * u) * 4, (int)mine) + (unsigned)(chunk * 16);
+    };
+
+    // prologue: the filter (64 rows x 72 vectors) and ring rows [0, 384), which cover everything tile 0
+    // needs (256 + 2*halo <= 384 rows); all loads are in flight before the first LDS write
+    {
+        unsigned off[8];
+        row_offsets(Q0 + 64 * wave, wave < 6, off);
+        u32x4 v[8], tmp[9];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, off[u], 0, 0);
+        const u32x4 *w = (const u32x4 *)a.wpk;
+#pragma unroll
+        for (int u = 0; u < 9; ++u) tmp[u] = w[tid + 512 * u];
+        if (wave < 6) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                *(u32x4 *)(ring + slot_addr((unsigned)(64 * wave + prow + 8 * u), (unsigned)chunk)) = v[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 9; ++u) {
+            const int i = tid + 512 * u, row = i / 72, vv = i - row * 72;
+            *(u32x4 *)(w_lds + row * H_W_STRIDE + vv * 16) = tmp[u];
+        }
+    }
+
+    // Staging unit u = ring rows [2*halo + 256(u-1), 2*halo + 256u): the rows tile u-1 needs beyond those
+    // of tile u-2.  A wavefront stages 64 of them; units past the block's last tile load nothing.
+    u32x4 st[8];
+    auto issue = [&](int unit) {
+        unsigned off[8];
+        row_offsets(Q0 + 2 * a.halo + 256 * (unit - 1) + 64 * x, unit <= n, off);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) st[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, off[u], 0, 0);
+    };
+    unsigned ss = grp ? (unsigned)(2 * a.halo + 256 + 64 * x) : (unsigned)(64 * x);   // first slot of this wavefront's strip
+    unsigned cs = (unsigned)(256 * grp);                                              // ring slot of row 0 of the next tile to multiply
+    issue(grp ? 2 : 3);
+
+    const unsigned b_base0 = (unsigned)(frow * H_W_STRIDE + fk * 16);
+    f32x16 acc[2][2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // LDS address of this lane's input fragment for tap t, position tile mi, channel group 0 of the next
+    // tile this group multiplies; prepared outside the multiply phase, which then only XORs in the group
+    unsigned ta[9][2];
+    auto prepare_ta = [&]() {
+#pragma unroll
+        for (int t = 0; t < 9; ++t)
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi) {
+                const unsigned r = wrap(cs + (unsigned)(x * 64 + mi * 32 + frow + a.halo + a.tapoff[t]));
+                ta[t][mi] = r * P_SLOT + (((unsigned)fk ^ ((r >> 1) & 7u)) << 4);
+            }
+    };
+    prepare_ta();
+    __syncthreads();
+
+    for (int p = 0; p <= n; ++p) {
+        if ((p & 1) == grp) {
+            if (p < n) {
+                // ---- multiply tile p: 36 reduction steps (9 taps x 4 groups of 16 channels), fragments
+                // fetched two steps ahead into a rotating register set
+                bf16x8 af[3][2], bfr[3][2];
+                auto fetch = [&](int step, int set) {
+                    const int t = step >> 2, kc = step & 3;
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi) af[set][mi] = *(const bf16x8 *)(ring + (ta[t][mi] ^ (unsigned)(kc << 5)));
+#pragma unroll
+                    for (int ni = 0; ni < 2; ++ni)
+                        bfr[set][ni] = *(const bf16x8 *)(w_lds + b_base0 + ni * 32 * H_W_STRIDE + (t * 64 + kc * 16) * 2);
+                };
+                // the multiplying wavefront goes first whenever both wavefronts of a SIMD are ready
+                __builtin_amdgcn_s_setprio(3);
+                fetch(0, 0);
+                fetch(1, 1);
+#pragma unroll
+                for (int step = 0; step < 36; ++step) {
+                    if (step + 2 < 36) fetch(step + 2, (step + 2) % 3);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni)
+                            acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[step % 3][ni], af[step % 3][mi],
+                                                                                  step == 0 ? zero16 : acc[ni][mi], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                __builtin_amdgcn_s_setprio(0);
+                cs = wrap(cs + 512u);
+            }
+        } else {
+            if (p >= 1) {
+                // ---- store tile p-1.  acc[ni][mi][4g+j] is channel 32ni + 8g + 4fk + j of position 32mi + frow;
+                // transposed through the private strip so that a lane stores 16 contiguous bytes.
+                unsigned ooff[8];
+                row_offsets((T0 + p - 1) * HT + 64 * x, true, ooff);
+                if (ACCUM) {
+                    // fp32 through the strip (two slots per position), 32 positions at a time, so the sum
+                    // with the old value is rounded once
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi) {
+                        u32x4 old[4];
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) old[jj] = __builtin_amdgcn_raw_buffer_load_b128(out_rsrc, ooff[mi * 4 + jj], 0, 0);
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni) {
+                            const unsigned sl = wrap(ss + (unsigned)(2 * frow + ni));
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                f32x4 v;
+#pragma unroll
+                                for (int jj = 0; jj < 4; ++jj) v[jj] = acc[ni][mi][g * 4 + jj];
+                                *(f32x4 *)(ring + slot_addr(sl, (unsigned)(2 * g + fk))) = v;
+                            }
+                        }
+#pragma unroll
+                        for (int jj = 0; jj < 4; ++jj) {
+                            const int pos = prow + 8 * jj;     // position within this half; channels 8*chunk..+7
+                            const unsigned sl = wrap(ss + (unsigned)(2 * pos + (chunk >> 2)));
+                            const f32x4 lo = *(const f32x4 *)(ring + slot_addr(sl, (unsigned)(2 * (chunk & 3))));
+                            const f32x4 hi = *(const f32x4 *)(ring + slot_addr(sl, (unsigned)(2 * (chunk & 3) + 1)));
+                            const bf16x8 ob = __builtin_bit_cast(bf16x8, old[jj]);
+                            bf16x8 r;
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                r[e] = (bf16_t)(lo[e] + (float)ob[e]);
+                                r[4 + e] = (bf16_t)(hi[e] + (float)ob[4 + e]);
+                            }
+                            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, r), out_rsrc, ooff[mi * 4 + jj], 0, 0);
+                        }
+                    }
+                } else {
+#pragma unroll
+                    for (int mi = 0; mi < 2; ++mi) {
+                        const unsigned sl = wrap(ss + (unsigned)(mi * 32 + frow));
+#pragma unroll
+                        for (int ni = 0; ni < 2; ++ni)
+#pragma unroll
+                            for (int g = 0; g < 4; ++g) {
+                                bf16x4 pk;
+#pragma unroll
+                                for (int jj = 0; jj < 4; ++jj) pk[jj] = (bf16_t)acc[ni][mi][g * 4 + jj];
+                                *(bf16x4 *)(ring + slot_addr(sl, (unsigned)(ni * 4 + g)) + fk * 8) = pk;
+                            }
+                    }
+#pragma unroll
+                    for (int jj = 0; jj < 8; ++jj) {
+                        const unsigned sl = wrap(ss + (unsigned)(prow + 8 * jj));
+                        const u32x4 v = *(const u32x4 *)(ring + slot_addr(sl, (unsigned)chunk));
+                        __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, ooff[jj], 0, 0);
+                    }
+                }
+            }
+            if (p + 1 < n) {
+                // ---- commit the rows loaded two phases ago (tile p+1 reads them in the next phase)
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    *(u32x4 *)(ring + slot_addr(wrap(ss + (unsigned)(prow + 8 * u)), (unsigned)chunk)) = st[u];
+            }
+            ss = wrap(ss + 512u);
+            issue(p + 4);
+            prepare_ta();
+        }
+        __syncthreads();
+    }
+}
+
 }  // namespace
 
 // True if the launch described by `a` is the shape this kernel covers.
@@ -297,20 +529,32 @@ int launch_halo64(const IgemmArgs &g, hipStream_t stream)
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NSK_ERR_HIP;
         cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     }
-    const int smem = H_MAX_IN * H_IN_STRIDE + 64 * H_W_STRIDE + 256 * 4 + H_MAX_IN * 4 + 4 * 32 * H_IN_STRIDE;
+    const int grid = a.tiles < cus ? a.tiles : cus;
     static bool attr_set = false;
+    const int smem = H_MAX_IN * H_IN_STRIDE + 64 * H_W_STRIDE + 256 * 4 + H_MAX_IN * 4 + 4 * 32 * H_IN_STRIDE;
+    const int smem_pp = P_RING_MAX * P_SLOT + 64 * H_W_STRIDE;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)conv_halo64_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)conv_halo64_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv_halo64_pp_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_pp);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv_halo64_pp_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_pp);
         if (e != hipSuccess) {
             set_last_hip_error(e);
             return NSK_ERR_HIP;
         }
         attr_set = true;
     }
-    const int grid = a.tiles < cus ? a.tiles : cus;
-    if (a.accumulate)
+    // the two-group kernel needs its ring (512 + 2*halo slots) to fit; wider images take the single-group kernel
+    const bool pp = 512 + 2 * a.halo <= P_RING_MAX && getenv("NSK_HALO_SINGLE") == nullptr;
+    if (pp) {
+        if (a.accumulate)
+            hipLaunchKernelGGL(conv_halo64_pp_kernel<true>, dim3(grid), dim3(512), smem_pp, stream, a);
+        else
+            hipLaunchKernelGGL(conv_halo64_pp_kernel<false>, dim3(grid), dim3(512), smem_pp, stream, a);
+    } else if (a.accumulate)
         hipLaunchKernelGGL(conv_halo64_kernel<true>, dim3(grid), dim3(256), smem, stream, a);
     else
         hipLaunchKernelGGL(conv_halo64_kernel<false>, dim3(grid), dim3(256), smem, stream, a);
