@@ -14,6 +14,12 @@ residual block (N=128, C=K=64, 32x32), NHWC.  Prints ONE JSON line:
 
 Other workloads: --config {1,2,3,4,5} [--stage A|B] [--batch N].  --breakdown prints a per-call
 table to stderr.  Runs on one GPU only.
+
+--layers prints, instead, one line per distinct convolution layer of configurations 2-5 at its full
+size: microseconds and TFLOP/s of forward, backward-data and backward-weight, the fraction of the
+MFMA peak and the fraction of the layer's own roofline cap min(MFMA peak, intensity x 8 TB/s), and
+the FLOP-weighted total over the bf16 3x3 layers of configurations 4 and 5.  Every call of a layer
+runs on its own buffer set, rotated so that the sets together exceed the 256 MB last-level cache.
 """
 from __future__ import annotations
 
@@ -42,7 +48,78 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="issue every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--layers", action="store_true", help="per-layer convolution table instead of the step benchmark")
     return ap.parse_args()
+
+
+def layer_table(repeats=20):
+    """Per-layer convolution timings at full size (see the module docstring)."""
+    import torch
+    import nsk_inputs as gen
+    from paper_2409_11600_amd import binding as B
+
+    seen, layers = set(), []
+    for config, stage in ((2, "A"), (3, "A"), (4, "A"), (5, "A"), (5, "B")):
+        wl = gen.workload(config, stage=stage)
+        shapes = gen.tensor_shapes(wl)
+        for u in wl["units"]:
+            if u["kind"] == "pool":
+                continue
+            key = (wl["dtype"],) + tuple(shapes[u["src"]]) + (u["K"], u["R"], u["stride"], u["pad"])
+            if key not in seen:
+                seen.add(key)
+                layers.append((f"C{config}{stage if config == 5 else ''}", key))
+    ws = B.Workspace()
+    gen_t = torch.Generator(device="cuda").manual_seed(7)
+    head_flops = head_ms = 0.0
+    print(f"{'cfg':<5}{'layer':<34}{'pass':<7}{'us':>9}{'TFLOP/s':>9}{'%peak':>7}{'cap TF':>8}{'%cap':>6}")
+    rows = []
+    for cfg, (dtype, N, C, H, W, K, R, stride, pad) in layers:
+        dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        es = 2 if dtype == "bf16" else 4
+        peak = PEAK["mfma_bf16" if dtype == "bf16" else "mfma_f32"]
+        P = (H + 2 * pad - R) // stride + 1
+        flops = 2.0 * N * P * P * K * C * R * R
+        xb, yb, wb = N * H * W * C * es, N * P * P * K * es, K * R * R * C
+        nset = max(2, int(300e6 // (xb + yb)) + 1)          # buffer sets that together exceed the last-level cache
+        sets = []
+        for _ in range(nset):
+            x = torch.randn(N, H, W, C, device="cuda", generator=gen_t).to(dt)
+            dy = torch.randn(N, P, P, K, device="cuda", generator=gen_t).to(dt)
+            sets.append((x, dy, torch.empty_like(dy), torch.empty_like(x)))
+        w = (torch.randn(K, R, R, C, device="cuda", generator=gen_t) * (2.0 / (C * R * R)) ** 0.5).to(dt)
+        dw = torch.empty(K, R, R, C, device="cuda")
+        passes = {
+            "fwd": (lambda s: B.conv2d_fwd(s[0], w, stride, pad, 1, out=s[2], ws=ws), (xb + yb + wb * es)),
+            "dgrad": (lambda s: B.conv2d_dgrad(s[1], w, (N, C, H, W), stride, pad, 1, out=s[3], ws=ws), (xb + yb + wb * es)),
+            "wgrad": (lambda s: B.conv2d_wgrad(s[0], s[1], (K, C, R, R), stride, pad, 1, out=dw, ws=ws), (xb + yb + wb * 4)),
+        }
+        name = f"{R}x{R} s{stride} {C}->{K} @{H}x{W} N={N} {dtype}"
+        for pname, (fn, byts) in passes.items():
+            for i in range(3):
+                fn(sets[i % nset])
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(repeats):
+                fn(sets[i % nset])
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / repeats
+            cap = min(peak, flops / byts * PEAK["hbm"])
+            tf = flops / ms / 1e9
+            print(f"{cfg:<5}{name:<34}{pname:<7}{ms * 1e3:9.1f}{tf:9.1f}{100 * tf * 1e12 / peak:7.1f}{cap / 1e12:8.0f}{100 * tf * 1e12 / cap:6.1f}",
+                  flush=True)
+            rows.append({"config": cfg, "layer": name, "pass": pname, "us": ms * 1e3, "tflops": tf,
+                         "frac_of_mfma_peak": tf * 1e12 / peak, "roofline_cap_tflops": cap / 1e12, "frac_of_cap": tf * 1e12 / cap})
+            if dtype == "bf16" and R == 3 and cfg in ("C4", "C5A", "C5B"):
+                head_flops += flops
+                head_ms += ms
+        del sets
+    head = head_flops / head_ms / 1e9
+    print(f"bf16 3x3 layers of configurations 4 and 5, all passes: {head:.1f} TFLOP/s = {100 * head * 1e12 / PEAK['mfma_bf16']:.1f}% of the bf16 MFMA peak")
+    print(json.dumps({"metric": "bf16 3x3 conv TFLOP/s over configs 4 and 5 (fwd+dgrad+wgrad, FLOP-weighted)", "value": head,
+                      "unit": "TFLOP/s", "frac_of_mfma_peak": head * 1e12 / PEAK["mfma_bf16"], "layers": rows}))
 
 
 def call_cost(net, f, args):
@@ -108,6 +185,9 @@ def main():
         sys.exit(1)
     B.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    if a.layers:
+        layer_table()
+        return
     wl = gen.workload(a.config, batch=a.batch, stage=a.stage)
     tensors = gen.workload_tensors(wl)
     layout = B.NSK_NHWC if a.layout == "nhwc" else B.NSK_NCHW
