@@ -130,14 +130,14 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
     int tile = blockIdx.x * tiles_per_block;
     if (tile < t_end) {
         fill_in_tab(tile);
-        __syncthreads();
+        lds_barrier();
         read_in_tab();
 #pragma unroll
         for (int u = 0; u < H_PASSES; ++u) prefetch_piece(stageA, u);
-        __syncthreads();
+        lds_barrier();
         if (tile + G < t_end) {
             fill_in_tab(tile + G);
-            __syncthreads();
+            lds_barrier();
             read_in_tab();
 #pragma unroll
             for (int u = 0; u < H_PASSES; ++u) prefetch_piece(stageB, u);
@@ -159,7 +159,7 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
         const int next = tile + 2 * G;                // the tile whose loads go into the set just emptied
         const bool have_next = next < t_end;
         if (have_next) fill_in_tab(next);   // the previous tile's reads of in_tab are complete
-        __syncthreads();
+        lds_barrier();
         if (have_next) {
             read_in_tab();
         } else {
@@ -249,7 +249,7 @@ __global__ __launch_bounds__(256) void conv_halo64_kernel(const HaloArgs a)
                 __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, o, 0, 0);
             }
         }
-        __syncthreads();
+        lds_barrier();
     };
     for (; tile < t_end; tile += 2 * G) {
         do_tile(tile, stageA);
@@ -375,7 +375,7 @@ __global__ __launch_bounds__(512) void conv_halo64_pp_kernel(const HaloArgs a)
             }
     };
     prepare_ta();
-    __syncthreads();
+    lds_barrier();
 
     for (int p = 0; p <= n; ++p) {
         if ((p & 1) == grp) {
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(512) void conv_halo64_pp_kernel(const HaloArgs a)
             issue(p + 4);
             prepare_ta();
         }
-        __syncthreads();
+        lds_barrier();
     }
 }
 

@@ -367,6 +367,7 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (a.M <= 0 || a.Ngemm <= 0) return NSK_OK;
     if (forced_tile() == 0 && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
     if (forced_tile() == 0 && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
+    if (forced_tile() == 0 && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
     IgemmArgs b = a;
     const int vec = dtype == NSK_BF16 ? 8 : 4;
     b.vec_out = (b.Ngemm % vec == 0 && b.Co % vec == 0 && (uintptr_t)b.out % 16 == 0) ? 1 : 0;

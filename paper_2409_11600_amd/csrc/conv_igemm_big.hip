@@ -1,0 +1,310 @@
+// Large-tile bf16 implicit GEMM for the wide layers of the bottleneck stages (1x1 and 3x3 convolutions
+// with 64..1024 channels; section "Experiments and Discussion" of the paper names the ResNet recipe
+// these shapes come from).  Same GEMM view and the same argument block as the generic kernel
+// (rows = output pixels, columns = output channels, k = (tap, channel)), built for the case where the
+// matrix units, not memory, should be the limit:
+//
+//   * block tile 256 pixels x 128 channels (or 256 x 64), four wavefronts of 128 x 64 (64 x 64): a
+//     wavefront reads 6 operand fragments from LDS per 8 MFMAs, which keeps LDS traffic (fragment reads
+//     plus the staging writes) near 60% of what the CU's LDS delivers at the full MFMA rate;
+//   * the reduction index advances 64 channels per k-tile and a tap never straddles a k-tile (C % 64 == 0),
+//     so tap and channel offset of a k-tile are wavefront-uniform: a gather address is one add plus the
+//     select on the row's tap-validity bit; padding is read as zeros through out-of-range buffer offsets;
+//   * hand-scheduled pipeline, one barrier per k-tile: the k-tile two ahead is in flight from memory into
+//     one of two register sets, the k-tile one ahead is written to the other LDS buffer during the first
+//     two MFMA steps, fragments are fetched one step (8 MFMAs) ahead, and the barrier sits between the
+//     third and fourth step so that the fourth step already reads the next buffer;
+//   * block ids are swizzled so that the column blocks of one row block run on the same XCD (they share
+//     the activation rows through that XCD's L2).
+#include <stdlib.h>
+
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+constexpr int GB_BM = 256;
+constexpr int GB_BK = 64;            // bf16 elements per k-tile row (128 bytes)
+constexpr int GB_ROW = 144;          // LDS bytes per row: 128 + 16 pad (conflict-free 16-byte reads of consecutive rows)
+constexpr unsigned GB_OOB = 0xF0000000u;
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int BN>
+__global__ __launch_bounds__(256) void igemm_big_kernel(const IgemmArgs a, const int tiles_m, const int tiles_n,
+                                                        const unsigned out_bytes)
+{
+    constexpr int FM = BN == 128 ? 4 : 2, FN = 2;                 // 32x32 accumulators per wavefront
+    constexpr int WM = FM * 32;
+    constexpr int A_LD = GB_BM * 8 / 256, B_LD = BN * 8 / 256;    // 16-byte loads per thread and k-tile
+    constexpr int BUF = (GB_BM + BN) * GB_ROW;                    // bytes of one LDS buffer (A rows, then B rows)
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned *out_tab = (unsigned *)(smem + 2 * BUF);             // 256 byte offsets of the output rows
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = BN == 128 ? wave >> 1 : wave, wn = BN == 128 ? wave & 1 : 0;
+    const int frow = lane & 31, fk = lane >> 5;
+    const int chunk = tid & 7, lrow = tid >> 3;                   // loader role: 16-byte chunk, row within a pass of 32
+
+    // block id -> (row block, column block): consecutive ids go to different XCDs, so the column blocks of a
+    // row block are given ids that differ by a multiple of 8
+    int mt, nt;
+    {
+        const int b = blockIdx.x, grp = b / (8 * tiles_n), r = b - grp * 8 * tiles_n;
+        const int full = tiles_m / 8;   // groups of 8 row blocks; the tail group is laid out plainly
+        if (grp < full) {
+            mt = grp * 8 + (r & 7);
+            nt = r >> 3;
+        } else {
+            const int rr = b - full * 8 * tiles_n;
+            mt = full * 8 + rr / tiles_n;
+            nt = rr % tiles_n;
+        }
+    }
+    const int m0 = mt * GB_BM, n0 = nt * BN;
+
+    const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wpk_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.wpk, 0, a.wpk_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, out_bytes, 0x00020000);
+
+    // lane t keeps the byte shift of tap t; a k-tile fetches its tap's shift with one cross-lane read
+    const int my_tap_shift = lane < a.ntaps ? ((int)a.off_h[lane] * a.Ws + (int)a.off_w[lane]) * a.Cs * 2 : 0;
+
+    // the rows this thread gathers (the same in every k-tile): byte offset of the row's base pixel and the
+    // bit mask of the taps that fall inside the image
+    unsigned a_base[A_LD];
+    unsigned long long a_mask[A_LD];
+    const int per_img = a.Mi * a.Mj;
+#pragma unroll
+    for (int u = 0; u < A_LD; ++u) {
+        const int m = m0 + lrow + 32 * u;
+        const bool ok = m < a.M;
+        const int mm = ok ? m : 0;
+        const int img = mm / per_img, rem = mm - img * per_img;
+        const int i = rem / a.Mj, j = rem - i * a.Mj;
+        const int bh = i * a.mult_h + a.add_h, bw = j * a.mult_w + a.add_w;
+        a_base[u] = (unsigned)((img * a.Hs + bh) * a.Ws + bw) * (unsigned)(a.Cs * 2) + (unsigned)(chunk * 16);   // wraps for bh, bw < 0; the tap shift wraps it back
+        unsigned long long mask = 0;
+        if (ok)
+            for (int t = 0; t < a.ntaps; ++t) {
+                const int h = bh + a.off_h[t], w = bw + a.off_w[t];
+                if ((unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws) mask |= 1ull << t;
+            }
+        a_mask[u] = mask;
+    }
+    {   // output row offsets (one row per thread)
+        const int m = m0 + tid;
+        unsigned off = GB_OOB;
+        if (m < a.M) {
+            const int img = m / per_img, rem = m - img * per_img;
+            const int i = rem / a.Mj, j = rem - i * a.Mj;
+            off = (unsigned)((img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * (unsigned)(a.Co * 2);
+        }
+        out_tab[tid] = off;
+    }
+    unsigned b_base[B_LD];
+#pragma unroll
+    for (int u = 0; u < B_LD; ++u) {
+        const int n = n0 + lrow + 32 * u;
+        b_base[u] = n < a.Ngemm ? (unsigned)n * (unsigned)(a.Ktot * 2) + (unsigned)(chunk * 16) : GB_OOB;
+    }
+
+    const int nk = a.Ktot / GB_BK;
+    const int cpt = a.Cs / GB_BK;       // k-tiles per tap
+    // two register sets for the k-tiles in flight
+    u32x4 ra[2][A_LD], rb[2][B_LD];
+    int ld_tap = 0, ld_cc = 0, ld_kt = 0;   // (tap, chunk within tap) of the next k-tile to load
+    auto issue_loads = [&](u32x4 (&A)[A_LD], u32x4 (&B)[B_LD]) {
+        const bool live = ld_kt < nk;
+        const int tap = live ? ld_tap : 0;
+        const int shift = __builtin_amdgcn_readlane(my_tap_shift, tap) + ld_cc * (GB_BK * 2);
+#pragma unroll
+        for (int u = 0; u < A_LD; ++u) {
+            const bool ok = live && ((a_mask[u] >> tap) & 1ull);
+            A[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, ok ? a_base[u] + (unsigned)shift : GB_OOB, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < B_LD; ++u)
+            B[u] = __builtin_amdgcn_raw_buffer_load_b128(wpk_rsrc, live ? b_base[u] + (unsigned)(ld_kt * GB_BK * 2) : GB_OOB, 0, 0);
+        ++ld_kt;
+        if (++ld_cc == cpt) {
+            ld_cc = 0;
+            ++ld_tap;
+        }
+    };
+    auto store_tile = [&](int buf, const u32x4 (&A)[A_LD], const u32x4 (&B)[B_LD], int part) {
+        // part 0 / 1: first / second half of the rows (spread over two MFMA steps)
+        unsigned char *base = smem + buf * BUF;
+#pragma unroll
+        for (int u = part * (A_LD / 2); u < (part + 1) * (A_LD / 2); ++u)
+            *(u32x4 *)(base + (lrow + 32 * u) * GB_ROW + chunk * 16) = A[u];
+#pragma unroll
+        for (int u = part * (B_LD / 2); u < (part + 1) * (B_LD / 2); ++u)
+            *(u32x4 *)(base + (GB_BM + lrow + 32 * u) * GB_ROW + chunk * 16) = B[u];
+    };
+
+    // accumulators: acc[mi][ni][4g+j] is channel 32ni + 8g + 4fk + j of pixel 32mi + frow of the wavefront's
+    // sub-tile (filter rows are the MFMA "A" operand)
+    f32x16 acc[FM][FN];
+    const int wcol0 = n0 + wn * 64;
+    __syncthreads();   // out_tab
+    if (a.accumulate) {
+        // start from the old values: the sum is rounded to bf16 exactly once
+#pragma unroll
+        for (int mi = 0; mi < FM; ++mi) {
+            const unsigned off = out_tab[wm * WM + mi * 32 + frow];
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int col = wcol0 + ni * 32 + g * 8 + fk * 4;
+                    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+                    const u32x2 old =
+                        __builtin_amdgcn_raw_buffer_load_b64(out_rsrc, col < a.Ngemm ? off + (unsigned)(col * 2) : GB_OOB, 0, 0);
+                    const bf16x4 ob = __builtin_bit_cast(bf16x4, old);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) acc[mi][ni][g * 4 + j] = (float)ob[j];
+                }
+        }
+    } else {
+#pragma unroll
+        for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
+    }
+
+    // prologue: k-tile 0 -> LDS buffer 0, k-tiles 1 and 2 in flight
+    issue_loads(ra[0], rb[0]);
+    issue_loads(ra[1], rb[1]);
+    store_tile(0, ra[0], rb[0], 0);
+    store_tile(0, ra[0], rb[0], 1);
+    issue_loads(ra[0], rb[0]);
+    lds_barrier();
+
+    const unsigned fa0 = (unsigned)((wm * WM + frow) * GB_ROW + fk * 16);
+    const unsigned fb0 = (unsigned)((GB_BM + wn * 64 + frow) * GB_ROW + fk * 16);
+    bf16x8 af[2][FM], bfr[2][FN];
+    auto fetch = [&](int buf, int ks, int set) {
+        const unsigned char *base = smem + buf * BUF + ks * 32;
+#pragma unroll
+        for (int mi = 0; mi < FM; ++mi) af[set][mi] = *(const bf16x8 *)(base + fa0 + mi * 32 * GB_ROW);
+#pragma unroll
+        for (int ni = 0; ni < FN; ++ni) bfr[set][ni] = *(const bf16x8 *)(base + fb0 + ni * 32 * GB_ROW);
+    };
+    auto mfmas = [&](int set) {
+#pragma unroll
+        for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni)
+                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0);
+    };
+
+    fetch(0, 0, 0);
+    // k-tile kt: registers ra[(kt+1)&1] hold k-tile kt+1, ra[kt&1] holds k-tile kt+2 (in flight)
+    auto k_tile = [&](int kt, u32x4 (&A)[A_LD], u32x4 (&B)[B_LD]) {
+        const int buf = kt & 1;
+        // step 0
+        fetch(buf, 1, 1);
+        store_tile(buf ^ 1, A, B, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(0);
+        __builtin_amdgcn_sched_barrier(0);
+        // step 1
+        fetch(buf, 2, 0);
+        store_tile(buf ^ 1, A, B, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(1);
+        __builtin_amdgcn_sched_barrier(0);
+        // step 2: the set just written to LDS is free again: k-tile kt+3
+        fetch(buf, 3, 1);
+        issue_loads(A, B);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(0);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_barrier();   // buffer buf^1 complete, buffer buf no longer needed after this step's fragments (loads stay in flight)
+        // step 3 already reads the next buffer
+        fetch(buf ^ 1, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        mfmas(1);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    for (int kt = 0; kt < nk; kt += 2) {
+        k_tile(kt, ra[1], rb[1]);
+        if (kt + 1 < nk) k_tile(kt + 1, ra[0], rb[0]);
+    }
+    __syncthreads();   // every wavefront is done with the operand buffers: they become the epilogue staging area
+
+    // Epilogue: round to bf16, transpose one 32x32 accumulator tile at a time through this wavefront's strip
+    // and store 16 contiguous bytes per lane.
+    constexpr int SROW = 80;   // 32 channels bf16 + 16 pad
+    unsigned char *my_st = smem + wave * (32 * SROW);
+#pragma unroll
+    for (int mi = 0; mi < FM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < FN; ++ni) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 pk;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) pk[j] = (bf16_t)acc[mi][ni][g * 4 + j];
+                *(bf16x4 *)(my_st + frow * SROW + (g * 8 + fk * 4) * 2) = pk;
+            }
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int idx = lane + 64 * jj, pos = idx >> 2, ck = idx & 3;
+                const u32x4 v = *(const u32x4 *)(my_st + pos * SROW + ck * 16);
+                const unsigned off = out_tab[wm * WM + mi * 32 + pos];
+                const int col = wcol0 + ni * 32 + ck * 8;
+                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, col < a.Ngemm ? off + (unsigned)(col * 2) : GB_OOB, 0, 0);
+            }
+        }
+}
+
+template <int BN> int smem_bytes() { return 2 * (GB_BM + BN) * GB_ROW + 256 * 4; }
+
+}  // namespace
+
+bool igemm_big_applicable(int dtype, const IgemmArgs &a)
+{
+    if (dtype != NSK_BF16 || getenv("NSK_NO_BIG") != nullptr) return false;
+    if (a.Cs % GB_BK != 0 || a.Ngemm % 64 != 0 || a.Co % 8 != 0 || a.ntaps > 64 || a.ntaps < 1) return false;
+    if (((uintptr_t)a.src | (uintptr_t)a.wpk | (uintptr_t)a.out) & 15) return false;
+    const long long out_bytes = (long long)a.Nimg * a.Ho * a.Wo * a.Co * 2;
+    if ((unsigned long long)a.src_bytes >= GB_OOB || (unsigned long long)a.wpk_bytes >= GB_OOB || out_bytes >= (long long)GB_OOB)
+        return false;
+    // worth it only when the 256-row tiles still fill the chip (NSK_BIG_MIN_TILES overrides the threshold: tests use
+    // it to run small shapes through this kernel)
+    const long long tiles = (long long)ceil_div(a.M, GB_BM) * ceil_div(a.Ngemm, a.Ngemm >= 128 ? 128 : 64);
+    const char *e = getenv("NSK_BIG_MIN_TILES");
+    return tiles >= (e ? atoll(e) : 160);
+}
+
+int launch_igemm_big(const IgemmArgs &a, hipStream_t stream)
+{
+    const int bn = a.Ngemm >= 128 ? 128 : 64;
+    const int tiles_m = ceil_div(a.M, GB_BM), tiles_n = ceil_div(a.Ngemm, bn);
+    const unsigned out_bytes = (unsigned)((long long)a.Nimg * a.Ho * a.Wo * a.Co * 2);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)igemm_big_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           smem_bytes<128>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)igemm_big_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes<64>());
+        if (e != hipSuccess) {
+            set_last_hip_error(e);
+            return NSK_ERR_HIP;
+        }
+        attr_set = true;
+    }
+    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    if (bn == 128)
+        hipLaunchKernelGGL(igemm_big_kernel<128>, grid, dim3(256), smem_bytes<128>(), stream, a, tiles_m, tiles_n, out_bytes);
+    else
+        hipLaunchKernelGGL(igemm_big_kernel<64>, grid, dim3(256), smem_bytes<64>(), stream, a, tiles_m, tiles_n, out_bytes);
+    return check_launch();
+}
+
+}  // namespace nsk

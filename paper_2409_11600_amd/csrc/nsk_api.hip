@@ -81,6 +81,7 @@ struct ConvPlan {
     size_t total = 0;
     int splits = 1, rows_per_split = 0;
     bool halo = false;   // wgrad: the 3x3 64->64 kernel writes one partial per block
+    bool wide = false;   // wgrad: the large-tile kernel for wide bf16 layers
     bool stem = false;   // the space-to-depth path plans its own workspace
 };
 
@@ -118,8 +119,11 @@ ConvPlan plan_conv(const ConvGeo &g, int pass)
         WgradArgs wa{};
         wgrad_geometry(g, &wa);
         p.halo = use_wgrad_halo(g, wa);
+        p.wide = !p.halo && wgrad_wide_applicable(g.dtype, wa);
         if (p.halo)
             p.splits = wgrad_halo64_partials(g.dtype, wa, nullptr);
+        else if (p.wide)
+            p.rows_per_split = wgrad_wide_rows_per_split(wa, &p.splits);
         else
             p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, &p.splits);
         p.part = take((size_t)p.splits * g.w_elems * sizeof(float));
@@ -365,6 +369,8 @@ int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy,
     a.splits = p.splits;
     if (p.halo)
         NSK_TRY(launch_wgrad_halo64(g.dtype, a, st));
+    else if (p.wide)
+        NSK_TRY(launch_wgrad_wide(a, st));
     else
         NSK_TRY(launch_wgrad(g.dtype, a, st));
     const long RS = (long)g.R * g.S;

@@ -22,6 +22,16 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t elem_size(int dtype) { return dtype == NSK_BF16 ? 2 : 4; }
 
+// Block-wide barrier that orders LDS traffic only.  __syncthreads() also drains the wavefront's global loads
+// (its fence covers global memory), which would end every register prefetch at each barrier; kernels whose
+// wavefronts exchange data through LDS alone use this one and keep their loads in flight across it.
+__device__ inline void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 void set_last_hip_error(hipError_t e);
 // Returns NSK_OK or records the error and returns NSK_ERR_HIP.
 inline int check_launch()
@@ -67,6 +77,9 @@ struct IgemmArgs {
     short off_w[kMaxTaps];
 };
 int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream);
+// bf16 large-tile kernel for wide layers (channel counts that are multiples of 64, enough tiles to fill the chip)
+bool igemm_big_applicable(int dtype, const IgemmArgs &a);
+int launch_igemm_big(const IgemmArgs &a, hipStream_t stream);
 // bf16 3x3 stride-1 64->64 special case (filter resident in LDS, input tile staged once with halo)
 bool halo64_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64(const IgemmArgs &a, hipStream_t stream);
@@ -96,6 +109,10 @@ int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);
 bool wgrad_halo64_applicable(int dtype, const WgradArgs &a);
 int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block);
 int launch_wgrad_halo64(int dtype, const WgradArgs &a, hipStream_t stream);
+// wide bf16 layers (C, K multiples of 64, long reduction): large tiles, about one block per CU
+bool wgrad_wide_applicable(int dtype, const WgradArgs &a);
+int wgrad_wide_rows_per_split(const WgradArgs &a, int *splits);
+int launch_wgrad_wide(const WgradArgs &a, hipStream_t stream);
 // dw[k*sk + t*st + c*sc] (=|+=) sum_s part[s][k][t][c], fixed order.
 int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int ntaps, int C,
                         long sk, long st, long sc, int accumulate, hipStream_t stream);

@@ -74,6 +74,63 @@ def test_conv_fwd_dgrad_wgrad(i, dtype, layout):
     assert max_rel_err(to_host(dw_view, layout), oracle.conv2d_wgrad(x, dy, w.shape, st, pd, dl)) <= tol
 
 
+# Shapes with channel counts that are multiples of 64: routed through the large-tile bf16 kernel by lowering
+# its tile-count threshold (at their full sizes these layers take it on their own).
+WIDE_SHAPES = [
+    (2, 128, 9, 9, 256, 1, 1, 1, 0, 1),        # 1x1, two column blocks, ragged row block
+    (3, 256, 10, 9, 64, 1, 1, 1, 0, 1),        # 1x1, 64-column variant, four k-tiles
+    (2, 64, 18, 14, 128, 3, 3, 2, 1, 1),       # 3x3 stride 2 (four parity classes in backward-data)
+    (2, 128, 11, 13, 128, 3, 3, 1, 1, 1),      # 3x3 stride 1, 18 k-tiles, padding on every side
+    (4, 64, 16, 16, 192, 1, 1, 2, 0, 1),       # 1x1 stride 2, 192 columns (half-empty second column block)
+    (1, 64, 33, 17, 64, 3, 3, 1, 2, 2),        # dilation 2
+]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("i", range(len(WIDE_SHAPES)))
+def test_conv_wide_layers_large_tile_kernel(i, layout, monkeypatch):
+    monkeypatch.setenv("NSK_BIG_MIN_TILES", "1")
+    monkeypatch.setenv("NSK_WIDE_MIN_ROWS", "1")
+    N, C, H, W, K, R, S, st, pd, dl = WIDE_SHAPES[i]
+    print(f"wide conv case {i} {WIDE_SHAPES[i]} layout={layout}", flush=True)
+    dtype = "bf16"
+    x = on_grid(gen.normal(700 + i, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(700 + i, 1, (K, C, R, S)), dtype)
+    P, Q = oracle.conv2d_out_dims(x.shape, w.shape, st, pd, dl)
+    dy = on_grid(gen.normal(700 + i, 2, (N, K, P, Q)), dtype)
+    base = on_grid(gen.normal(700 + i, 3, x.shape), dtype)
+    tol = TOL[dtype]
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    y_view, y_check = guarded(gdy.shape, torch_dtype(dtype))
+    B.conv2d_fwd(gx, gw, st, pd, dl, layout, out=y_view, ws=ws)
+    dx_view, dx_check = guarded(gx.shape, torch_dtype(dtype))
+    B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, out=dx_view, ws=ws)
+    gacc = to_gpu(base, dtype, layout)
+    B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, out=gacc, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    y_check()
+    dx_check()
+    assert max_rel_err(to_host(y_view, layout), oracle.conv2d_fwd(x, w, st, pd, dl)) <= tol
+    want_dx = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl)
+    got_dx = to_host(dx_view, layout)
+    assert max_rel_err(got_dx, want_dx) <= tol
+    assert np.all(got_dx[want_dx == 0.0] == 0.0)
+    want_acc = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl, into=base.astype(np.float64))
+    assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
+    # backward-weight through the large-tile kernel, overwrite and accumulate
+    dw_view, dw_check = guarded(gw.shape, torch.float32)
+    B.conv2d_wgrad(gx, gdy, w.shape, st, pd, dl, layout, out=dw_view, ws=ws)
+    base_w = gen.normal(700 + i, 4, w.shape).astype(np.float32)
+    gdw = to_gpu(base_w, "f32", layout)
+    B.conv2d_wgrad(gx, gdy, w.shape, st, pd, dl, layout, out=gdw, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    dw_check()
+    want_dw = oracle.conv2d_wgrad(x, dy, w.shape, st, pd, dl)
+    assert max_rel_err(to_host(dw_view, layout), want_dw) <= TOL["f32"] * 10   # fp32 sums of exact bf16 products
+    assert max_rel_err(to_host(gdw, layout), want_dw + base_w.astype(np.float64)) <= TOL["f32"] * 10
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", [1, 2, 3, 8, 12, 13])
