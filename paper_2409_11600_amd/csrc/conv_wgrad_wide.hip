@@ -16,8 +16,9 @@
 //   * both operands are copied to LDS exactly as they lie in memory ([pixel][channel], 16-byte pieces) and
 //     come out through the transposing LDS read, which delivers 8 consecutive pixels of one channel per lane
 //     (the MFMA operand layout) without any 2-byte shuffling;
-//   * two k-tiles (64 pixels each) are in flight in registers while a third is multiplied; one LDS-only
-//     barrier per k-tile;
+//   * eight wavefronts with split roles: four only multiply (fragment reads + MFMAs), four only move data
+//     (two k-tiles of 64 pixels in flight in registers, a third being written to the other LDS buffer); one
+//     LDS-only barrier per k-tile;
 //   * the tiles of one split get block ids that land on the same XCD, so its dy and x rows are shared
 //     through that XCD's L2.
 #include <stdlib.h>
@@ -42,7 +43,7 @@ struct WWArgs {
 };
 
 template <int FM>   // 32-row accumulator tiles per wavefront in k: block rows = 64 * FM
-__global__ __launch_bounds__(256) void wgrad_wide_kernel(const WWArgs w)
+__global__ __launch_bounds__(512) void wgrad_wide_kernel(const WWArgs w)
 {
     const WgradArgs &a = w.g;
     constexpr int BM = 64 * FM;
@@ -54,9 +55,14 @@ __global__ __launch_bounds__(256) void wgrad_wide_kernel(const WWArgs w)
     constexpr int BUF = WW_KT * (DROW + WW_XROW);
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    // Eight wavefronts, two per SIMD: 0..3 multiply (fragment reads and MFMAs only), 4..7 move data (global loads
+    // and LDS writes only).  A wavefront issues in order, so a load that waits for room in the CU's memory pipeline
+    // would hold back every MFMA behind it; with the roles split, only the movers ever wait there.
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const bool mover = wave >= 4;
+    const int tid = threadIdx.x & 255;   // index within the role's 256 threads
+    const int wm = (wave & 3) >> 1, wn = wave & 1;
     const int frow = lane & 31, fk = lane >> 5;
 
     // block id -> (split, tile): within a group of 8 splits the split index is the fastest, so the tiles of a
@@ -89,7 +95,6 @@ __global__ __launch_bounds__(256) void wgrad_wide_kernel(const WWArgs w)
     const int d_chunk = tid % D_CPR, d_row = tid / D_CPR;
     const int x_chunk = tid & 15, x_row = tid >> 4;
     const int d_k = k0 + d_chunk * 8;
-    const unsigned d_col = d_k < a.K ? (unsigned)(d_k * 2) : WW_OOB;
     // this thread's x column: a fixed (tap, channel)
     const int x_n = n0 + x_chunk * 8;
     const bool x_live = x_n < NT;
@@ -99,39 +104,108 @@ __global__ __launch_bounds__(256) void wgrad_wide_kernel(const WWArgs w)
 
     u32x4 rd[2][D_LD], rx[2][X_LD];
     int ld_l = l_begin;   // first pixel of the next k-tile to load
+    // Running addresses, advanced by one k-tile (64 pixels) at a time with adds and selects only (no
+    // multiplication, division or branch inside the loop).
+    //   dy: byte offset of each row of this thread.
+    //   x:  per row the pixel's (p*sh, q*sw) and the byte offset of its tap-shifted source element; 64 pixels
+    //       further is adv_q columns and adv_p rows on, with a carry from q into p and up to two from p into
+    //       the image index (the applicability test guarantees adv_p + 1 <= 2P).
+    unsigned d_off[D_LD];
+#pragma unroll
+    for (int u = 0; u < D_LD; ++u) d_off[u] = (unsigned)(l_begin + d_row + D_RPP * u) * (unsigned)(a.K * 2) + (unsigned)(d_k * 2);
+    const bool d_live = d_k < a.K;
+    const unsigned d_step = (unsigned)(WW_KT * a.K * 2);
+    int x_hh[X_LD], x_wq[X_LD];
+    unsigned x_off[X_LD];
+    const unsigned C2 = (unsigned)(a.C * 2);
+#pragma unroll
+    for (int u = 0; u < X_LD; ++u) {
+        const unsigned ll = (unsigned)min(l_begin + x_row + 16 * u, a.L - 1);
+        const unsigned img = (unsigned)(((unsigned long long)ll * w.magic_pq) >> 40);
+        const unsigned rem = ll - img * (unsigned)(a.P * a.Q);
+        const unsigned p = (unsigned)(((unsigned long long)rem * w.magic_q) >> 40);
+        const unsigned q = rem - p * (unsigned)a.Q;
+        x_hh[u] = (int)p * a.sh;
+        x_wq[u] = (int)q * a.sw;
+        x_off[u] = ((img * (unsigned)a.H + (unsigned)(x_hh[u] + x_oh)) * (unsigned)a.W + (unsigned)(x_wq[u] + x_ow)) * C2 + (unsigned)(x_c * 2);
+    }
+    const int adv_p = WW_KT / a.Q, adv_q = WW_KT % a.Q;
+    const int Qs = a.Q * a.sw, Ps = a.P * a.sh, aqs = adv_q * a.sw, aps = adv_p * a.sh;
+    const unsigned s_q = (unsigned)(aqs + aps * a.W) * C2;             // adv_q columns and adv_p rows on
+    const unsigned s_qwrap = (unsigned)(a.sh * a.W - Qs) * C2;         // q wrapped: back Q columns, one row on
+    const unsigned s_pwrap = (unsigned)(a.H * a.W - Ps * a.W) * C2;    // p wrapped: back P rows, one image on
+    auto load_d = [&](u32x4 (&D)[D_LD], int u) {
+        const bool ok = d_live && ld_l + d_row + D_RPP * u < l_end;
+        D[u] = __builtin_amdgcn_raw_buffer_load_b128(dy_rsrc, ok ? d_off[u] : WW_OOB, 0, 0);
+        d_off[u] += d_step;
+    };
+    auto load_x = [&](u32x4 (&X)[X_LD], int u) {
+        const int h = x_hh[u] + x_oh, ww = x_wq[u] + x_ow;
+        const bool ok = x_live & (ld_l + x_row + 16 * u < l_end) & ((unsigned)h < (unsigned)a.H) & ((unsigned)ww < (unsigned)a.W);
+        X[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, ok ? x_off[u] : WW_OOB, 0, 0);
+        // advance this row to the next k-tile
+        int wq = x_wq[u] + aqs, hh = x_hh[u] + aps;
+        unsigned off = x_off[u] + s_q;
+        const bool c1 = wq >= Qs;
+        wq -= c1 ? Qs : 0;
+        hh += c1 ? a.sh : 0;
+        off += c1 ? s_qwrap : 0u;
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            const bool c2 = hh >= Ps;
+            hh -= c2 ? Ps : 0;
+            off += c2 ? s_pwrap : 0u;
+        }
+        x_wq[u] = wq;
+        x_hh[u] = hh;
+        x_off[u] = off;
+    };
+    // work item i of a k-tile's loads (dy first, then x); ld_l moves on once all items of the k-tile are issued
+    auto load_item = [&](u32x4 (&D)[D_LD], u32x4 (&X)[X_LD], int i) {
+        if (i < D_LD)
+            load_d(D, i);
+        else
+            load_x(X, i - D_LD);
+    };
     auto issue_loads = [&](u32x4 (&D)[D_LD], u32x4 (&X)[X_LD]) {
 #pragma unroll
-        for (int u = 0; u < D_LD; ++u) {
-            const int l = ld_l + d_row + D_RPP * u;
-            const unsigned off = l < l_end ? (unsigned)l * (unsigned)(a.K * 2) + d_col : WW_OOB;
-            D[u] = __builtin_amdgcn_raw_buffer_load_b128(dy_rsrc, off, 0, 0);
-        }
-#pragma unroll
-        for (int u = 0; u < X_LD; ++u) {
-            const int l = ld_l + x_row + 16 * u;
-            const bool in = x_live && l < l_end;
-            const unsigned ll = in ? (unsigned)l : 0u;
-            const unsigned img = (unsigned)(((unsigned long long)ll * w.magic_pq) >> 40);
-            const unsigned rem = ll - img * (unsigned)(a.P * a.Q);
-            const unsigned p = (unsigned)(((unsigned long long)rem * w.magic_q) >> 40);
-            const unsigned q = rem - p * (unsigned)a.Q;
-            const int h = (int)p * a.sh + x_oh, ww = (int)q * a.sw + x_ow;
-            const bool ok = in && (unsigned)h < (unsigned)a.H && (unsigned)ww < (unsigned)a.W;
-            const unsigned off = ((img * (unsigned)a.H + (unsigned)h) * (unsigned)a.W + (unsigned)ww) * (unsigned)(a.C * 2) + (unsigned)(x_c * 2);
-            X[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, ok ? off : WW_OOB, 0, 0);
-        }
+        for (int i = 0; i < D_LD + X_LD; ++i) load_item(D, X, i);
         ld_l += WW_KT;
     };
-    auto store_tile = [&](int buf, const u32x4 (&D)[D_LD], const u32x4 (&X)[X_LD], int part) {
+    auto store_item = [&](int buf, const u32x4 (&D)[D_LD], const u32x4 (&X)[X_LD], int i) {
         unsigned char *base = smem + buf * BUF;
-        constexpr int DH = D_LD / 2, XH = X_LD / 2;
-#pragma unroll
-        for (int u = part * DH; u < (part + 1) * DH; ++u)
-            *(u32x4 *)(base + (d_row + D_RPP * u) * DROW + d_chunk * 16) = D[u];
-#pragma unroll
-        for (int u = part * XH; u < (part + 1) * XH; ++u)
-            *(u32x4 *)(base + WW_KT * DROW + (x_row + 16 * u) * WW_XROW + x_chunk * 16) = X[u];
+        if (i < D_LD)
+            *(u32x4 *)(base + (d_row + D_RPP * i) * DROW + d_chunk * 16) = D[i];
+        else
+            *(u32x4 *)(base + WW_KT * DROW + (x_row + 16 * (i - D_LD)) * WW_XROW + x_chunk * 16) = X[i - D_LD];
     };
+
+    constexpr int NL = D_LD + X_LD;
+    if (mover) {
+        // k-tile 0 -> LDS buffer 0, k-tiles 1 and 2 in flight; then per k-tile kt: write k-tile kt+1 into the other
+        // buffer and refill each register with k-tile kt+3 as soon as it has been written out (measured faster than
+        // all writes followed by all loads, and than a third register set with the loads issued first)
+        issue_loads(rd[0], rx[0]);
+        issue_loads(rd[1], rx[1]);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) store_item(0, rd[0], rx[0], i);
+        issue_loads(rd[0], rx[0]);
+        lds_barrier();
+        auto move = [&](int kt, u32x4 (&D)[D_LD], u32x4 (&X)[X_LD]) {
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                store_item((kt & 1) ^ 1, D, X, i);
+                load_item(D, X, i);
+            }
+            ld_l += WW_KT;
+            lds_barrier();
+        };
+        for (int kt = 0; kt < nk; kt += 2) {
+            move(kt, rd[1], rx[1]);
+            if (kt + 1 < nk) move(kt + 1, rd[0], rx[0]);
+        }
+        return;
+    }
 
     f32x16 acc[FM][2];
 #pragma unroll
@@ -140,13 +214,7 @@ __global__ __launch_bounds__(256) void wgrad_wide_kernel(const WWArgs w)
         for (int ni = 0; ni < 2; ++ni)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
-
-    issue_loads(rd[0], rx[0]);
-    issue_loads(rd[1], rx[1]);
-    store_tile(0, rd[0], rx[0], 0);
-    store_tile(0, rd[0], rx[0], 1);
-    issue_loads(rd[0], rx[0]);
-    lds_barrier();
+    lds_barrier();   // buffer 0 is ready
 
     // Transposing read: within 16 lanes, lanes 4j..4j+3 address row j (four 8-byte pieces = 16 channels) and lane
     // i receives channel i of rows 0..3.  Lane (channel = lane%32, half = lane/32) of an MFMA operand needs pixels
@@ -168,49 +236,36 @@ __global__ __launch_bounds__(256) void wgrad_wide_kernel(const WWArgs w)
         return r;
     };
     bf16x8 af[2][FM], bfr[2][2];
-    auto fetch = [&](int buf, int ks, int set) {
+    // fragment i of a step: the FM dy fragments, then the 2 x fragments
+    auto fetch_item = [&](int buf, int ks, int set, int i) {
         const unsigned char *base = smem + buf * BUF;
-#pragma unroll
-        for (int mi = 0; mi < FM; ++mi) af[set][mi] = tr8(base + fd0 + ks * 16 * DROW + mi * 64, DROW);
-#pragma unroll
-        for (int ni = 0; ni < 2; ++ni) bfr[set][ni] = tr8(base + fx0 + ks * 16 * WW_XROW + ni * 64, WW_XROW);
+        if (i < FM)
+            af[set][i] = tr8(base + fd0 + ks * 16 * DROW + i * 64, DROW);
+        else
+            bfr[set][i - FM] = tr8(base + fx0 + ks * 16 * WW_XROW + (i - FM) * 64, WW_XROW);
     };
-    auto mfmas = [&](int set) {
 #pragma unroll
-        for (int mi = 0; mi < FM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < 2; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][mi], bfr[set][ni], acc[mi][ni], 0, 0, 0);
-    };
+    for (int i = 0; i < FM + 2; ++i) fetch_item(0, 0, 0, i);
 
-    fetch(0, 0, 0);
-    // k-tile kt multiplies LDS buffer kt&1; registers D, X hold k-tile kt+1 (the other set holds kt+2, in flight)
-    auto k_tile = [&](int kt, u32x4 (&D)[D_LD], u32x4 (&X)[X_LD]) {
+    // One k-tile = 4 steps of NS = 2*FM MFMAs; the fragments of step s+1 are fetched one by one behind the MFMAs
+    // of step s.  The barrier (the movers have completed the other buffer) sits before step 3, whose fetches
+    // already read that buffer.
+    constexpr int NS = 2 * FM, NF = FM + 2;
+    for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-        fetch(buf, 1, 1);
-        store_tile(buf ^ 1, D, X, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(0);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(buf, 2, 0);
-        store_tile(buf ^ 1, D, X, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(1);
-        __builtin_amdgcn_sched_barrier(0);
-        fetch(buf, 3, 1);
-        issue_loads(D, X);   // k-tile kt+3 into the set just written out
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(0);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_barrier();       // the other buffer is complete; this one is free after this step's fragments
-        fetch(buf ^ 1, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(1);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    for (int kt = 0; kt < nk; kt += 2) {
-        k_tile(kt, rd[1], rx[1]);
-        if (kt + 1 < nk) k_tile(kt + 1, rd[0], rx[0]);
+#pragma unroll
+        for (int step = 0; step < 4; ++step) {
+            const int set = step & 1;
+            if (step == 3) lds_barrier();
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                acc[j >> 1][j & 1] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][j >> 1], bfr[set][j & 1], acc[j >> 1][j & 1], 0, 0, 0);
+#pragma unroll
+                for (int i = j; i < NF; i += NS) fetch_item(step == 3 ? buf ^ 1 : buf, (step + 1) & 3, set ^ 1, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     }
 
     // acc[mi][ni][v]: row k = 32*mi + 8*(v/4) + 4*(lane/32) + v%4, column = 32*ni + lane%32 of the wavefront's sub-tile
@@ -243,6 +298,7 @@ bool wgrad_wide_applicable(int dtype, const WgradArgs &a)
     if ((long long)a.L >= (1LL << 30) || (long long)a.L * pq >= (1LL << 40)) return false;   // exactness of the reciprocal division
     const long long xb = (long long)a.Nimg * a.H * a.W * a.C * 2, db = (long long)a.L * a.K * 2;
     if (xb >= (long long)WW_OOB || db >= (long long)WW_OOB) return false;
+    if (WW_KT / a.Q + 1 > 2 * a.P) return false;   // the running pixel decode handles at most two image wraps per k-tile
     // a long reduction per block is what pays for the large tile (NSK_WIDE_MIN_ROWS: test hook)
     const char *e = getenv("NSK_WIDE_MIN_ROWS");
     return a.L >= (e ? atoi(e) : 16384);
@@ -287,9 +343,9 @@ int launch_wgrad_wide(const WgradArgs &a, hipStream_t stream)
     }
     const dim3 grid((unsigned)(w.tiles_n * w.tiles_k * a.splits));
     if (bm == 256)
-        hipLaunchKernelGGL(wgrad_wide_kernel<4>, grid, dim3(256), smem_bytes<4>(), stream, w);
+        hipLaunchKernelGGL(wgrad_wide_kernel<4>, grid, dim3(512), smem_bytes<4>(), stream, w);
     else
-        hipLaunchKernelGGL(wgrad_wide_kernel<1>, grid, dim3(256), smem_bytes<1>(), stream, w);
+        hipLaunchKernelGGL(wgrad_wide_kernel<1>, grid, dim3(512), smem_bytes<1>(), stream, w);
     return check_launch();
 }
 
