@@ -10,10 +10,10 @@
 //   * the reduction index advances 64 channels per k-tile and a tap never straddles a k-tile (C % 64 == 0),
 //     so tap and channel offset of a k-tile are wavefront-uniform: a gather address is one add plus the
 //     select on the row's tap-validity bit; padding is read as zeros through out-of-range buffer offsets;
-//   * hand-scheduled pipeline, one barrier per k-tile: the k-tile two ahead is in flight from memory into
-//     one of two register sets, the k-tile one ahead is written to the other LDS buffer during the first
-//     two MFMA steps, fragments are fetched one step (8 MFMAs) ahead, and the barrier sits between the
-//     third and fourth step so that the fourth step already reads the next buffer;
+//   * eight wavefronts with split roles: four only multiply (fragments fetched one step of 8 MFMAs ahead, one by
+//     one behind the MFMAs), four only move data (two k-tiles in flight in registers, a third being written to
+//     the other LDS buffer); one LDS-only barrier per k-tile, placed before the fourth step so that this step
+//     already reads the next buffer;
 //   * block ids are swizzled so that the column blocks of one row block run on the same XCD (they share
 //     the activation rows through that XCD's L2).
 #include <stdlib.h>
@@ -31,7 +31,7 @@ constexpr unsigned GB_OOB = 0xF0000000u;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 template <int BN>
-__global__ __launch_bounds__(256) void igemm_big_kernel(const IgemmArgs a, const int tiles_m, const int tiles_n,
+__global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const int tiles_m, const int tiles_n,
                                                         const unsigned out_bytes)
 {
     constexpr int FM = BN == 128 ? 4 : 2, FN = 2;                 // 32x32 accumulators per wavefront
@@ -41,9 +41,15 @@ __global__ __launch_bounds__(256) void igemm_big_kernel(const IgemmArgs a, const
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned *out_tab = (unsigned *)(smem + 2 * BUF);             // 256 byte offsets of the output rows
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = BN == 128 ? wave >> 1 : wave, wn = BN == 128 ? wave & 1 : 0;
+    // Eight wavefronts, two per SIMD: 0..3 multiply (fragment reads, MFMAs, epilogue), 4..7 move data (global loads
+    // and LDS writes).  A wavefront issues in order, so a load that waits for room in the CU's memory pipeline would
+    // hold back every MFMA behind it; with the roles split only the movers wait there.
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const bool mover = wave >= 4;
+    const int tid = threadIdx.x & 255;   // index within the role's 256 threads
+    const int cw = wave & 3;
+    const int wm = BN == 128 ? cw >> 1 : cw, wn = BN == 128 ? cw & 1 : 0;
     const int frow = lane & 31, fk = lane >> 5;
     const int chunk = tid & 7, lrow = tid >> 3;                   // loader role: 16-byte chunk, row within a pass of 32
 
@@ -93,7 +99,7 @@ __global__ __launch_bounds__(256) void igemm_big_kernel(const IgemmArgs a, const
             }
         a_mask[u] = mask;
     }
-    {   // output row offsets (one row per thread)
+    if (!mover) {   // output row offsets (one row per multiplying thread)
         const int m = m0 + tid;
         unsigned off = GB_OOB;
         if (m < a.M) {
@@ -133,16 +139,52 @@ __global__ __launch_bounds__(256) void igemm_big_kernel(const IgemmArgs a, const
             ++ld_tap;
         }
     };
-    auto store_tile = [&](int buf, const u32x4 (&A)[A_LD], const u32x4 (&B)[B_LD], int part) {
-        // part 0 / 1: first / second half of the rows (spread over two MFMA steps)
+    auto store_item = [&](int buf, const u32x4 (&A)[A_LD], const u32x4 (&B)[B_LD], int i) {
         unsigned char *base = smem + buf * BUF;
-#pragma unroll
-        for (int u = part * (A_LD / 2); u < (part + 1) * (A_LD / 2); ++u)
-            *(u32x4 *)(base + (lrow + 32 * u) * GB_ROW + chunk * 16) = A[u];
-#pragma unroll
-        for (int u = part * (B_LD / 2); u < (part + 1) * (B_LD / 2); ++u)
-            *(u32x4 *)(base + (GB_BM + lrow + 32 * u) * GB_ROW + chunk * 16) = B[u];
+        if (i < A_LD)
+            *(u32x4 *)(base + (lrow + 32 * i) * GB_ROW + chunk * 16) = A[i];
+        else
+            *(u32x4 *)(base + (GB_BM + lrow + 32 * (i - A_LD)) * GB_ROW + chunk * 16) = B[i - A_LD];
     };
+    constexpr int NL = A_LD + B_LD;
+    if (mover) {
+        // k-tile 0 -> LDS buffer 0, k-tiles 1 and 2 in flight; then per k-tile kt: write k-tile kt+1 into the other
+        // buffer, refilling each register with k-tile kt+3 as soon as it has been written out
+        issue_loads(ra[0], rb[0]);
+        issue_loads(ra[1], rb[1]);
+#pragma unroll
+        for (int i = 0; i < NL; ++i) store_item(0, ra[0], rb[0], i);
+        issue_loads(ra[0], rb[0]);
+        __syncthreads();   // out_tab (written by the multiplying wavefronts) and buffer 0
+        auto move = [&](int kt, u32x4 (&A)[A_LD], u32x4 (&B)[B_LD]) {
+            const bool live = ld_kt < nk;
+            const int tap = live ? ld_tap : 0;
+            const int shift = __builtin_amdgcn_readlane(my_tap_shift, tap) + ld_cc * (GB_BK * 2);
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                store_item((kt & 1) ^ 1, A, B, i);
+                if (i < A_LD) {
+                    const bool ok = live && ((a_mask[i] >> tap) & 1ull);
+                    A[i] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, ok ? a_base[i] + (unsigned)shift : GB_OOB, 0, 0);
+                } else {
+                    const int u = i - A_LD;
+                    B[u] = __builtin_amdgcn_raw_buffer_load_b128(wpk_rsrc, live ? b_base[u] + (unsigned)(ld_kt * GB_BK * 2) : GB_OOB, 0, 0);
+                }
+            }
+            ++ld_kt;
+            if (++ld_cc == cpt) {
+                ld_cc = 0;
+                ++ld_tap;
+            }
+            lds_barrier();
+        };
+        for (int kt = 0; kt < nk; kt += 2) {
+            move(kt, ra[1], rb[1]);
+            if (kt + 1 < nk) move(kt + 1, ra[0], rb[0]);
+        }
+        __syncthreads();   // matches the barrier before the epilogue
+        return;
+    }
 
     // accumulators: acc[mi][ni][4g+j] is channel 32ni + 8g + 4fk + j of pixel 32mi + frow of the wavefront's
     // sub-tile (filter rows are the MFMA "A" operand)
@@ -176,71 +218,45 @@ __global__ __launch_bounds__(256) void igemm_big_kernel(const IgemmArgs a, const
                 for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
     }
 
-    // prologue: k-tile 0 -> LDS buffer 0, k-tiles 1 and 2 in flight
-    issue_loads(ra[0], rb[0]);
-    issue_loads(ra[1], rb[1]);
-    store_tile(0, ra[0], rb[0], 0);
-    store_tile(0, ra[0], rb[0], 1);
-    issue_loads(ra[0], rb[0]);
-    lds_barrier();
-
     const unsigned fa0 = (unsigned)((wm * WM + frow) * GB_ROW + fk * 16);
     const unsigned fb0 = (unsigned)((GB_BM + wn * 64 + frow) * GB_ROW + fk * 16);
     bf16x8 af[2][FM], bfr[2][FN];
-    auto fetch = [&](int buf, int ks, int set) {
+    // fragment i of a step: the FM pixel fragments, then the FN filter fragments
+    auto fetch_item = [&](int buf, int ks, int set, int i) {
         const unsigned char *base = smem + buf * BUF + ks * 32;
-#pragma unroll
-        for (int mi = 0; mi < FM; ++mi) af[set][mi] = *(const bf16x8 *)(base + fa0 + mi * 32 * GB_ROW);
-#pragma unroll
-        for (int ni = 0; ni < FN; ++ni) bfr[set][ni] = *(const bf16x8 *)(base + fb0 + ni * 32 * GB_ROW);
+        if (i < FM)
+            af[set][i] = *(const bf16x8 *)(base + fa0 + i * 32 * GB_ROW);
+        else
+            bfr[set][i - FM] = *(const bf16x8 *)(base + fb0 + (i - FM) * 32 * GB_ROW);
     };
-    auto mfmas = [&](int set) {
 #pragma unroll
-        for (int mi = 0; mi < FM; ++mi)
-#pragma unroll
-            for (int ni = 0; ni < FN; ++ni)
-                acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][ni], af[set][mi], acc[mi][ni], 0, 0, 0);
-    };
+    for (int i = 0; i < FM + FN; ++i) fetch_item(0, 0, 0, i);
 
-    fetch(0, 0, 0);
-    // k-tile kt: registers ra[(kt+1)&1] hold k-tile kt+1, ra[kt&1] holds k-tile kt+2 (in flight)
-    auto k_tile = [&](int kt, u32x4 (&A)[A_LD], u32x4 (&B)[B_LD]) {
+    // One k-tile = 4 steps of NS = FM*FN MFMAs; the fragments of step s+1 are fetched one by one behind the MFMAs of
+    // step s.  The barrier (the movers have completed the other buffer) sits before step 3, whose fetches already
+    // read that buffer.
+    constexpr int NS = FM * FN, NF = FM + FN;
+    for (int kt = 0; kt < nk; ++kt) {
         const int buf = kt & 1;
-        // step 0
-        fetch(buf, 1, 1);
-        store_tile(buf ^ 1, A, B, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(0);
-        __builtin_amdgcn_sched_barrier(0);
-        // step 1
-        fetch(buf, 2, 0);
-        store_tile(buf ^ 1, A, B, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(1);
-        __builtin_amdgcn_sched_barrier(0);
-        // step 2: the set just written to LDS is free again: k-tile kt+3
-        fetch(buf, 3, 1);
-        issue_loads(A, B);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(0);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_barrier();   // buffer buf^1 complete, buffer buf no longer needed after this step's fragments (loads stay in flight)
-        // step 3 already reads the next buffer
-        fetch(buf ^ 1, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        mfmas(1);
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    for (int kt = 0; kt < nk; kt += 2) {
-        k_tile(kt, ra[1], rb[1]);
-        if (kt + 1 < nk) k_tile(kt + 1, ra[0], rb[0]);
+#pragma unroll
+        for (int step = 0; step < 4; ++step) {
+            const int set = step & 1;
+            if (step == 3) lds_barrier();
+#pragma unroll
+            for (int j = 0; j < NS; ++j) {
+                acc[j / FN][j % FN] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j % FN], af[set][j / FN], acc[j / FN][j % FN], 0, 0, 0);
+#pragma unroll
+                for (int i = j; i < NF; i += NS) fetch_item(step == 3 ? buf ^ 1 : buf, (step + 1) & 3, set ^ 1, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
     }
     __syncthreads();   // every wavefront is done with the operand buffers: they become the epilogue staging area
 
     // Epilogue: round to bf16, transpose one 32x32 accumulator tile at a time through this wavefront's strip
     // and store 16 contiguous bytes per lane.
     constexpr int SROW = 80;   // 32 channels bf16 + 16 pad
-    unsigned char *my_st = smem + wave * (32 * SROW);
+    unsigned char *my_st = smem + cw * (32 * SROW);
 #pragma unroll
     for (int mi = 0; mi < FM; ++mi)
 #pragma unroll
@@ -275,11 +291,15 @@ bool igemm_big_applicable(int dtype, const IgemmArgs &a)
     const long long out_bytes = (long long)a.Nimg * a.Ho * a.Wo * a.Co * 2;
     if ((unsigned long long)a.src_bytes >= GB_OOB || (unsigned long long)a.wpk_bytes >= GB_OOB || out_bytes >= (long long)GB_OOB)
         return false;
-    // worth it only when the 256-row tiles still fill the chip (NSK_BIG_MIN_TILES overrides the threshold: tests use
-    // it to run small shapes through this kernel)
+    // Measured against the generic kernel on the bottleneck-stage layers: this one wins when the reduction is long
+    // (at least 8 k-tiles) and there are at least 128 output channels; short reductions and 64-channel outputs are
+    // bound by memory and do better with the generic kernel's several small blocks per CU.  The 256-row tiles must
+    // also still fill the chip.  NSK_BIG_MIN_TILES overrides all three tests (tests use it to run small shapes
+    // through this kernel).
     const long long tiles = (long long)ceil_div(a.M, GB_BM) * ceil_div(a.Ngemm, a.Ngemm >= 128 ? 128 : 64);
     const char *e = getenv("NSK_BIG_MIN_TILES");
-    return tiles >= (e ? atoll(e) : 160);
+    if (e) return tiles >= atoll(e);
+    return tiles >= 160 && a.Ngemm >= 128 && a.Ktot >= 8 * GB_BK;
 }
 
 int launch_igemm_big(const IgemmArgs &a, hipStream_t stream)
@@ -301,9 +321,9 @@ int launch_igemm_big(const IgemmArgs &a, hipStream_t stream)
     }
     const dim3 grid((unsigned)(tiles_m * tiles_n));
     if (bn == 128)
-        hipLaunchKernelGGL(igemm_big_kernel<128>, grid, dim3(256), smem_bytes<128>(), stream, a, tiles_m, tiles_n, out_bytes);
+        hipLaunchKernelGGL(igemm_big_kernel<128>, grid, dim3(512), smem_bytes<128>(), stream, a, tiles_m, tiles_n, out_bytes);
     else
-        hipLaunchKernelGGL(igemm_big_kernel<64>, grid, dim3(256), smem_bytes<64>(), stream, a, tiles_m, tiles_n, out_bytes);
+        hipLaunchKernelGGL(igemm_big_kernel<64>, grid, dim3(512), smem_bytes<64>(), stream, a, tiles_m, tiles_n, out_bytes);
     return check_launch();
 }
 
