@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="issue every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--overlap", action="store_true",
+                    help="issue the backward-weight calls on a second stream (measured: no gain on MI355X, the "
+                         "convolution kernels already hold every CU)")
     ap.add_argument("--layers", action="store_true", help="per-layer convolution table instead of the step benchmark")
     return ap.parse_args()
 
@@ -196,6 +199,7 @@ def main():
     calls = net.fwd_calls + net.bwd_calls
     costs = [call_cost(net, f, args) for f, args in calls]
     stream = torch.cuda.Stream()
+    side = torch.cuda.Stream() if a.overlap else None
     st = ctypes.c_void_p(stream.cuda_stream)
 
     def issue(record=None):
@@ -230,11 +234,7 @@ def main():
         if not a.no_graph:
             graph = torch.cuda.CUDAGraph()
             with torch.cuda.graph(graph, stream=stream):
-                gst = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
-                for f, args in calls:
-                    rc = f(*args, gst)
-                    if rc != B.NSK_OK:
-                        raise B.NskError(rc, f.__name__)
+                net.step(side_stream=side)     # backward-weight calls fork to the side stream and join at the end
             graph.replay()
             stream.synchronize()
 
@@ -246,7 +246,7 @@ def main():
             if graph is not None:
                 graph.replay()
             else:
-                issue()
+                net.step(side_stream=side)
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
@@ -291,7 +291,8 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl["dtype"] == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{wl['name']}: {len(wl['units'])} units, input {list(wl['input'])}, "
-                               f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None},
+                               f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None,
+                   "streams": 1 if side is None else 2},
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12,
         "conv_frac_of_mfma_peak": conv_flops / (conv_ms * 1e-3) / PEAK["mfma_bf16" if wl["dtype"] == "bf16" else "mfma_f32"],
         "roofline": roof,

@@ -179,3 +179,43 @@ def test_workload_end_to_end(config, stage, batch, layout):
     print("relative L2 / fraction within tol:", ", ".join(f"{k}={v[1]:.1e}/{v[0]:.3f}" for k, v in stats.items()), flush=True)
     bad = {k: v for k, v in stats.items() if not v[1] <= (ACT_L2_BAR if k.startswith("act:") else GRAD_L2_BAR)}
     assert not bad, bad
+
+
+@pytest.mark.parametrize("config,stage,batch", [(2, "A", 4), (4, "A", 2), (5, "B", 2)])
+def test_backward_weight_on_a_side_stream_is_bitwise_identical(config, stage, batch):
+    """Operation overlapping: with a second stream the backward-weight calls run beside the main stream's work
+    (own workspace, event after their inputs, join at the end of the step).  Every kernel is deterministic, so
+    all results must equal the single-stream run bit for bit, also when the step is repeated (buffers reused)
+    and when it is replayed from a captured graph."""
+    wl, t, _, _ = _setup(config, stage, batch)
+    print(f"workload {wl['name']} input {wl['input']} (side stream)", flush=True)
+    ref = GpuNetwork(wl, t)
+    ref.step()
+    torch.cuda.synchronize()
+    net = GpuNetwork(wl, t)
+    main, side = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def check(what):
+        for name in net.shapes:
+            assert torch.equal(net.act[name], ref.act[name]), (what, "act", name)
+            assert torch.equal(net.grad[name], ref.grad[name]), (what, "grad", name)
+        for name in net.dw:
+            assert torch.equal(net.dw[name], ref.dw[name]), (what, "dw", name)
+        for name in net.dgamma:
+            assert torch.equal(net.dgamma[name], ref.dgamma[name]) and torch.equal(net.dbeta[name], ref.dbeta[name]), (what, name)
+
+    with torch.cuda.stream(main):
+        for rep in range(2):
+            net.step(side_stream=side)
+            main.synchronize()
+            check(f"eager step {rep}")
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=main):
+            net.step(side_stream=side)
+        for rep in range(3):
+            for name in net.dw:
+                net.dw[name].fill_(float("nan"))       # eager work between the replays
+            main.synchronize()
+            graph.replay()
+            main.synchronize()
+            check(f"graph replay {rep}")
