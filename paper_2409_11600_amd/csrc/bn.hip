@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
                                                       const T *__restrict__ dout, const float *__restrict__ mean,
                                                       const float *__restrict__ invstd, int relu, long M, int C,
                                                       long rows_per_block, float *__restrict__ p0,
-                                                      float *__restrict__ p1)
+                                                      float *__restrict__ p1, unsigned char *__restrict__ mask)
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
@@ -101,13 +101,18 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
             const Vec gv = *(const Vec *)(dout + off);
             Vec ov;
             if (relu) ov = *(const Vec *)(out + off);
+            unsigned bits = 0;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 float dz = (float)gv[e];
-                if (relu && !((float)ov[e] > 0.f)) dz = 0.f;
+                const bool on = !relu || (float)ov[e] > 0.f;
+                if (!on) dz = 0.f;
+                bits |= (on ? 1u : 0u) << e;
                 s0[e] += dz;
                 s1[e] += dz * (((float)xv[e] - sh[e]) * sc[e]);
             }
+            // one byte per vector: the apply pass reads this instead of `out` (an eighth or a sixteenth of its bytes)
+            if (relu) mask[off / VEC] = (unsigned char)bits;
         }
     }
     __shared__ float red0[256 * VEC], red1[256 * VEC];
@@ -167,7 +172,8 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_nhwc(const T *__restrict__ x
                                                          const T *__restrict__ dout, T *__restrict__ dx,
                                                          T *__restrict__ dres, const float *__restrict__ mean,
                                                          const float *__restrict__ invstd,
-                                                         const float *__restrict__ coef, long nvec, int C)
+                                                         const float *__restrict__ coef, long nvec, int C,
+                                                         const unsigned char *__restrict__ mask)
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
@@ -184,13 +190,14 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_nhwc(const T *__restrict__ x
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < nvec; i += (long)gridDim.x * 256) {
         const Vec xv = __builtin_nontemporal_load((const Vec *)(x + i * VEC));
         const Vec gv = __builtin_nontemporal_load((const Vec *)(dout + i * VEC));
-        Vec ov;
-        if (RELU) ov = __builtin_nontemporal_load((const Vec *)(out + i * VEC));
+        // ReLU mask of these VEC elements, written by the reduction pass (bit e set: out > 0)
+        unsigned bits = ~0u;
+        if (RELU) bits = __builtin_nontemporal_load(mask + i);
         Vec dxv, drv;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             float dz = (float)gv[e];
-            if (RELU && !((float)ov[e] > 0.f)) dz = 0.f;
+            if (RELU && !((bits >> e) & 1u)) dz = 0.f;
             const float xhat = ((float)xv[e] - mu[e]) * is[e];
             dxv[e] = (T)(ka[e] * (dz - kb[e] - xhat * kc[e]));
             drv[e] = (T)dz;
@@ -401,7 +408,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
     if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 0>), dim3(g.G), dim3(256), 0, stream, x, (const T *)nullptr,
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, g.M, d.C,
-                           g.rows_per_block, p0, p1);
+                           g.rows_per_block, p0, p1, (unsigned char *)nullptr);
     } else {
         hipLaunchKernelGGL((bn_reduce_generic<T, 0>), dim3(d.C, g.G), dim3(256), 0, stream, x, (const T *)nullptr,
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, d.N, g.HW, g.sn,
@@ -440,10 +447,12 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
 {
     const Geom g = geometry(d, true);
     float *p0 = ws, *p1 = ws + (long)g.G * d.C, *coef = p1 + (long)g.G * d.C;
+    // the ReLU mask bytes follow the float part of the workspace (see bn_mask_bytes)
+    unsigned char *mask = (unsigned char *)ws + align_up((2 * (size_t)bn_partial_blocks(d) * d.C + 4 * (size_t)d.C) * sizeof(float));
     constexpr int VEC = BT<T>::VEC;
     if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 1>), dim3(g.G), dim3(256), 0, stream, x, out, dout, mean, invstd,
-                           d.relu, g.M, d.C, g.rows_per_block, p0, p1);
+                           d.relu, g.M, d.C, g.rows_per_block, p0, p1, mask);
     } else {
         hipLaunchKernelGGL((bn_reduce_generic<T, 1>), dim3(d.C, g.G), dim3(256), 0, stream, x, out, dout, mean,
                            invstd, d.relu, d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1);
@@ -455,7 +464,7 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
         const dim3 grid(stream_blocks(nvec));
 #define NSK_BAPPLY(R, L)                                                                                       \
     hipLaunchKernelGGL((bn_bwd_apply_nhwc<T, R, L>), grid, dim3(256), 0, stream, x, out, dout, dx, dres, mean, \
-                       invstd, coef, nvec, d.C)
+                       invstd, coef, nvec, d.C, mask)
         if (dres) {
             if (d.relu) NSK_BAPPLY(true, true); else NSK_BAPPLY(true, false);
         } else {
@@ -475,6 +484,14 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
 }
 
 }  // namespace
+
+// Bytes of ReLU mask the backward pass keeps between its two kernels (one byte per 16-byte vector), 0 if unused.
+size_t bn_mask_bytes(const nsk_bn_desc_t &d)
+{
+    if (!d.relu || !nhwc_fast(d)) return 0;
+    const size_t vec = d.dtype == NSK_BF16 ? 8 : 4;
+    return (size_t)d.N * d.H * d.W * d.C / vec;
+}
 
 int bn_partial_blocks(const nsk_bn_desc_t &d)
 {

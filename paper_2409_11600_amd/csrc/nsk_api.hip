@@ -386,7 +386,8 @@ size_t nsk_bn_workspace_bytes(const nsk_bn_desc_t *desc, int pass)
     if (pass != NSK_BN_FWD && pass != NSK_BN_BWD) return 0;
     if (bn_geometry(desc) != NSK_OK) return 0;
     const size_t G = (size_t)bn_partial_blocks(*desc);
-    return align_up((2 * G * desc->C + 4 * (size_t)desc->C) * sizeof(float));
+    const size_t floats = align_up((2 * G * desc->C + 4 * (size_t)desc->C) * sizeof(float));
+    return floats + (pass == NSK_BN_BWD ? align_up(bn_mask_bytes(*desc)) : 0);
 }
 
 int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *residual, const float *gamma,

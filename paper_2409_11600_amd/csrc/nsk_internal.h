@@ -144,6 +144,7 @@ int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, in
 
 // ------------------------------------------------------------------ batch-norm, pooling
 int bn_partial_blocks(const nsk_bn_desc_t &d);
+size_t bn_mask_bytes(const nsk_bn_desc_t &d);
 int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
                   const float *beta, void *out, float *save_mean, float *save_invstd,
                   float *running_mean, float *running_var, void *ws, hipStream_t stream);
