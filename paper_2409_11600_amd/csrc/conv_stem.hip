@@ -153,7 +153,21 @@ __global__ __launch_bounds__(256) void stem_unpack_dw_kernel(const float *__rest
 struct StemPlan {
     size_t x2 = 0, w2 = 0, dx2 = 0, act = 0, part = 0, dw2 = 0, total = 0;
     int splits = 1, rows_per_split = 0;
+    bool wide = false;   // backward-weight through the large-tile kernel
 };
+
+// backward-weight on the space-to-depth image: 16 channels, stride 1, U x U taps
+void stem_wgrad_geometry(const ConvGeo &g, const StemGeo &s, WgradArgs *a)
+{
+    a->Nimg = s.N; a->H = s.H2; a->W = s.W2; a->C = SC; a->P = g.P; a->Q = g.Q; a->K = s.K;
+    a->sh = 1; a->sw = 1; a->ph = -s.umin; a->pw = -s.umin;
+    a->ntaps = s.U * s.U;
+    a->L = s.N * g.P * g.Q;
+    for (int t = 0; t < a->ntaps; ++t) {
+        a->off_h[t] = (short)(t / s.U);
+        a->off_w[t] = (short)(t % s.U);
+    }
+}
 
 StemPlan stem_plan(const ConvGeo &g, const StemGeo &s, int pass)
 {
@@ -178,7 +192,11 @@ StemPlan stem_plan(const ConvGeo &g, const StemGeo &s, int pass)
     } else {
         p.x2 = take(img2);
         if (nchw) p.act = take(g.y_elems * g.es);   // NHWC copy of dy
-        p.rows_per_split = wgrad_rows_per_split(s.dtype, s.N * s.H2 * s.W2, s.K, s.U * s.U * SC, &p.splits);
+        WgradArgs wa{};
+        stem_wgrad_geometry(g, s, &wa);
+        p.wide = wgrad_wide_applicable(s.dtype, wa);
+        p.rows_per_split = p.wide ? wgrad_wide_rows_per_split(wa, &p.splits)
+                                  : wgrad_rows_per_split(s.dtype, wa.L, s.K, s.U * s.U * SC, &p.splits);
         p.part = take((size_t)p.splits * w2 * sizeof(float));
         p.dw2 = take(w2 * sizeof(float));
     }
@@ -344,18 +362,14 @@ int stem_wgrad(const ConvGeo &g, const void *x, const void *dy, float *dw, int a
         dys = ws + p.act;
     }
     WgradArgs a{};
+    stem_wgrad_geometry(g, s, &a);
     a.x = ws + p.x2; a.dy = dys; a.part = (float *)(ws + p.part);
-    a.Nimg = s.N; a.H = s.H2; a.W = s.W2; a.C = SC; a.P = g.P; a.Q = g.Q; a.K = s.K;
-    a.sh = 1; a.sw = 1; a.ph = -s.umin; a.pw = -s.umin;
-    a.ntaps = s.U * s.U;
-    a.L = s.N * g.P * g.Q;
     a.rows_per_split = p.rows_per_split;
     a.splits = p.splits;
-    for (int t = 0; t < a.ntaps; ++t) {
-        a.off_h[t] = (short)(t / s.U);
-        a.off_w[t] = (short)(t % s.U);
-    }
-    STEM_TRY(launch_wgrad(s.dtype, a, st));
+    if (p.wide)
+        STEM_TRY(launch_wgrad_wide(a, st));
+    else
+        STEM_TRY(launch_wgrad(s.dtype, a, st));
     float *dw2 = (float *)(ws + p.dw2);
     STEM_TRY(launch_wgrad_reduce(a.part, dw2, p.splits, s.K, a.ntaps, SC, (long)a.ntaps * SC, (long)SC, 1L, 0, st));
     long sk, sc, sr, ss;

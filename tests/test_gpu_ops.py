@@ -83,6 +83,8 @@ WIDE_SHAPES = [
     (2, 128, 11, 13, 128, 3, 3, 1, 1, 1),      # 3x3 stride 1, 18 k-tiles, padding on every side
     (4, 64, 16, 16, 192, 1, 1, 2, 0, 1),       # 1x1 stride 2, 192 columns (half-empty second column block)
     (1, 64, 33, 17, 64, 3, 3, 1, 2, 2),        # dilation 2
+    (2, 3, 20, 24, 64, 7, 7, 2, 3, 1),         # image stem: space-to-depth, then the large-tile backward-weight kernel on 16 channels
+    (2, 32, 12, 10, 64, 3, 3, 2, 1, 1),        # 32 input channels (four taps per 128-column tile)
 ]
 
 
