@@ -362,7 +362,10 @@ Geom geometry(const nsk_bn_desc_t &d, bool backward)
         long G = (g.M + (long)RP * 8 - 1) / ((long)RP * 8);
         // Measured: the forward statistics pass over a large tensor (one input stream) is fastest with eight blocks
         // per CU, the backward pass (three input streams) and small tensors with two.
-        const long cap = (!backward && g.total >= (16L << 20)) ? 2048 : 512;
+        // More blocks also mean more partial sums for the finalize kernel to read (G x C floats, twice): the larger
+        // count is only used while that stays within 2 MB per array.
+        long cap = (!backward && g.total >= (16L << 20)) ? 2048 : 512;
+        if (cap * d.C > (512L << 10)) cap = 512;
         if (G > cap) G = cap;
         if (G < 1) G = 1;
         g.rows_per_block = (g.M + G - 1) / G;
