@@ -13,6 +13,7 @@
 //   forward        implicit GEMM on x2 (16 taps x 16 channels),
 //   backward-weight the split-K kernel on x2, then dw2 is folded back into dw's layout,
 //   backward-data  implicit GEMM producing dx2 (16 "channels" = the 2x2 phases x C), then depth-to-space.
+// The bf16 7x7 stem with 64 output channels takes the halo kernels of conv_stem_halo.hip for the two GEMMs.
 // The copies (x -> x2, dx2 -> dx) are plain streaming passes over the small 3-channel image.
 #include "nsk_internal.h"
 
@@ -300,6 +301,11 @@ int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, 
     STEM_TRY(space_to_depth(g, s, x, ws + p.x2, st));
     STEM_TRY(pack_filter<0>(g, s, w, ws + p.w2, st));
     void *dst = nchw ? (void *)(ws + p.act) : y;
+    if (stem_halo_applicable(s.dtype, s.U, s.K, s.N, s.H2, s.W2)) {
+        STEM_TRY(launch_stem_halo(0, ws + p.x2, ws + p.w2, dst, s.N, s.H2, s.W2, st));
+        if (nchw) STEM_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));
+        return NSK_OK;
+    }
     IgemmArgs a{};
     a.src = ws + p.x2; a.wpk = ws + p.w2; a.out = dst;
     a.Nimg = s.N; a.Hs = s.H2; a.Ws = s.W2; a.Cs = SC;
@@ -331,6 +337,11 @@ int stem_dgrad(const ConvGeo &g, const void *dy, const void *w, void *dx, int ac
     }
     STEM_TRY(pack_filter<1>(g, s, w, ws + p.w2, st));
     // dx2[n,i,j,e] = sum_{u,v,k} dy[n, i-u, j-v, k] * w2[k][u,v][e]
+    if (stem_halo_applicable(s.dtype, s.U, s.K, s.N, s.H2, s.W2)) {
+        STEM_TRY(launch_stem_halo(1, src, ws + p.w2, ws + p.dx2, s.N, s.H2, s.W2, st));
+        return s.dtype == NSK_BF16 ? d2s_typed<bf16_t>(g, s, ws + p.dx2, dx, accumulate, st)
+                                   : d2s_typed<float>(g, s, ws + p.dx2, dx, accumulate, st);
+    }
     IgemmArgs a{};
     a.src = src; a.wpk = ws + p.w2; a.out = ws + p.dx2;
     a.Nimg = s.N; a.Hs = g.P; a.Ws = g.Q; a.Cs = s.K;

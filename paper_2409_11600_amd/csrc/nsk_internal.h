@@ -127,6 +127,10 @@ int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, 
 int stem_dgrad(const ConvGeo &g, const void *dy, const void *w, void *dx, int accumulate, char *ws, hipStream_t stream);
 int stem_wgrad(const ConvGeo &g, const void *x, const void *dy, float *dw, int accumulate, char *ws, hipStream_t stream);
 
+// 7x7 stem (4x4 coarse taps), bf16, 64 output channels: forward / backward-data on the space-to-depth grid
+bool stem_halo_applicable(int dtype, int U, int K, int Nimg, int H, int W);
+int launch_stem_halo(int backward, const void *src, const void *wpk, void *out, int Nimg, int H, int W, hipStream_t stream);
+
 // ------------------------------------------------------------------ layout helpers
 // dst NHWC <- src NCHW (plain copy).
 int launch_nchw_to_nhwc(int dtype, const void *src, void *dst, int N, int C, int H, int W,
