@@ -144,12 +144,13 @@ def call_cost(net, f, args):
         return kind, flops, byts
     if name.startswith("nsk_bn"):
         e = d.N * d.C * d.H * d.W
-        res = (args[2] if name.endswith("fwd") else args[8]) is not None
-        if name.endswith("fwd"):
+        fwd = "_fwd" in name                         # nsk_bn_relu_add_fwd[_mask] / nsk_bn_relu_add_bwd[_mask]
+        res = (args[2] if fwd else args[8]) is not None
+        if fwd:
             byts = (2 + res + 1) * e * es          # stats read + apply read (+ residual) + write
         else:
             byts = (6 if d.relu else 4) * e * es + (1 + res) * e * es   # two passes over x,(out),dout + writes
-        return name[len("nsk_"):], 0.0, byts
+        return name[len("nsk_"):].replace("_mask", ""), 0.0, byts
     if name.startswith("nsk_maxpool"):
         e_in = d.N * d.C * d.H * d.W
         e_out = e_in // 4

@@ -148,6 +148,23 @@ int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *ou
                         const float *save_invstd, void *dx, void *dresidual, float *dgamma,
                         float *dbeta, void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same two calls with the ReLU mask handed from forward to backward, so that the backward pass does not
+ * read `out` (one tensor read less in each of its two kernels).  Only for NSK_NHWC descriptors with relu = 1
+ * whose channel count lets the kernels use 16-byte vectors (C a multiple of 8 for bf16, 4 for f32, and a
+ * divisor of 256 vectors: nsk_bn_mask_bytes returns 0 otherwise and the plain calls must be used).
+ * relu_mask: nsk_bn_mask_bytes(desc) bytes of device memory, one byte per 16-byte vector of `out` in storage
+ * order, bit e set iff element e of that vector is > 0 as stored.  The forward call writes it, the backward
+ * call reads it; the backward call takes no `out`. */
+size_t nsk_bn_mask_bytes(const nsk_bn_desc_t *desc);
+int nsk_bn_relu_add_fwd_mask(const nsk_bn_desc_t *desc, const void *x, const void *residual,
+                             const float *gamma, const float *beta, void *out, unsigned char *relu_mask,
+                             float *save_mean, float *save_invstd, float *running_mean,
+                             float *running_var, void *workspace, size_t workspace_bytes, void *stream);
+int nsk_bn_relu_add_bwd_mask(const nsk_bn_desc_t *desc, const void *x, const unsigned char *relu_mask,
+                             const void *dout, const float *gamma, const float *save_mean,
+                             const float *save_invstd, void *dx, void *dresidual, float *dgamma,
+                             float *dbeta, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Output extent of a pooling descriptor.  Host only. */
 int nsk_maxpool2d_out_dims(const nsk_pool_desc_t *desc, int *P, int *Q);
 

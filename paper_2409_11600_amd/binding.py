@@ -90,6 +90,12 @@ def lib() -> ctypes.CDLL:
         L.nsk_bn_relu_add_fwd.argtypes = [bd] + [vp] * 10 + [sz, vp]
         L.nsk_bn_relu_add_bwd.restype = ci
         L.nsk_bn_relu_add_bwd.argtypes = [bd] + [vp] * 11 + [sz, vp]
+        L.nsk_bn_mask_bytes.restype = sz
+        L.nsk_bn_mask_bytes.argtypes = [bd]
+        L.nsk_bn_relu_add_fwd_mask.restype = ci
+        L.nsk_bn_relu_add_fwd_mask.argtypes = [bd] + [vp] * 11 + [sz, vp]
+        L.nsk_bn_relu_add_bwd_mask.restype = ci
+        L.nsk_bn_relu_add_bwd_mask.argtypes = [bd] + [vp] * 11 + [sz, vp]
         L.nsk_maxpool2d_out_dims.restype = ci
         L.nsk_maxpool2d_out_dims.argtypes = [pd, ip, ip]
         L.nsk_maxpool2d_fwd.restype = ci
@@ -102,7 +108,8 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d_out_dims",
            "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
-           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_maxpool2d_out_dims",
+           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
+           "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_maxpool2d_out_dims",
            "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd")
 
 
@@ -251,10 +258,17 @@ def bn_desc(x: torch.Tensor, layout, eps, momentum, relu) -> nsk_bn_desc_t:
     return nsk_bn_desc_t(N, C, H, W, _dtype_code(x), layout, float(eps), float(momentum), int(bool(relu)))
 
 
+def bn_mask_bytes(x, layout=NSK_NHWC, relu=True) -> int:
+    """Bytes of the ReLU mask the *_mask calls exchange for a tensor like x; 0 if they do not apply."""
+    d = bn_desc(x, layout, 1e-5, 0.1, relu)
+    return int(lib().nsk_bn_mask_bytes(ctypes.byref(d)))
+
+
 def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=NSK_NHWC, momentum=0.1,
                     running_mean=None, running_var=None, out=None, save_mean=None, save_invstd=None,
-                    ws: Optional[Workspace] = None):
-    """Returns (out, save_mean, save_invstd)."""
+                    ws: Optional[Workspace] = None, relu_mask=None):
+    """Returns (out, save_mean, save_invstd).  With relu_mask (uint8 tensor of bn_mask_bytes(x) bytes) the ReLU
+    mask is written there for bn_relu_add_bwd(..., relu_mask=...)."""
     d = bn_desc(x, layout, eps, momentum, relu)
     C = d.C
     if out is None:
@@ -265,6 +279,11 @@ def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=N
         save_invstd = torch.empty(C, dtype=torch.float32, device=x.device)
     ws = ws or Workspace(x.device)
     wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_FWD))
+    if relu_mask is not None:
+        _check(lib().nsk_bn_relu_add_fwd_mask(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
+                                              _ptr(relu_mask), _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean),
+                                              _ptr(running_var), wp, wb, _stream()), "nsk_bn_relu_add_fwd_mask")
+        return out, save_mean, save_invstd
     _check(lib().nsk_bn_relu_add_fwd(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
                                      _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean), _ptr(running_var),
                                      wp, wb, _stream()), "nsk_bn_relu_add_fwd")
@@ -273,8 +292,9 @@ def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=N
 
 def bn_relu_add_bwd(x, out, dout, gamma, save_mean, save_invstd, relu=True, layout=NSK_NHWC, eps=1e-5,
                     dx=None, dresidual=None, want_dresidual=False, dgamma=None, dbeta=None,
-                    ws: Optional[Workspace] = None):
-    """Returns (dx, dresidual or None, dgamma, dbeta)."""
+                    ws: Optional[Workspace] = None, relu_mask=None):
+    """Returns (dx, dresidual or None, dgamma, dbeta).  With relu_mask (as written by bn_relu_add_fwd) `out` is
+    not read and may be None."""
     d = bn_desc(x, layout, eps, 0.1, relu)
     C = d.C
     if dx is None:
@@ -287,6 +307,11 @@ def bn_relu_add_bwd(x, out, dout, gamma, save_mean, save_invstd, relu=True, layo
         dbeta = torch.empty(C, dtype=torch.float32, device=x.device)
     ws = ws or Workspace(x.device)
     wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_BWD))
+    if relu_mask is not None:
+        _check(lib().nsk_bn_relu_add_bwd_mask(ctypes.byref(d), _ptr(x), _ptr(relu_mask), _ptr(dout), _ptr(gamma),
+                                              _ptr(save_mean), _ptr(save_invstd), _ptr(dx), _ptr(dresidual), _ptr(dgamma),
+                                              _ptr(dbeta), wp, wb, _stream()), "nsk_bn_relu_add_bwd_mask")
+        return dx, dresidual, dgamma, dbeta
     _check(lib().nsk_bn_relu_add_bwd(ctypes.byref(d), _ptr(x), _ptr(out), _ptr(dout), _ptr(gamma), _ptr(save_mean),
                                      _ptr(save_invstd), _ptr(dx), _ptr(dresidual), _ptr(dgamma), _ptr(dbeta),
                                      wp, wb, _stream()), "nsk_bn_relu_add_bwd")

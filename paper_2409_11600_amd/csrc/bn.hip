@@ -65,7 +65,8 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
                                                       const T *__restrict__ dout, const float *__restrict__ mean,
                                                       const float *__restrict__ invstd, int relu, long M, int C,
                                                       long rows_per_block, float *__restrict__ p0,
-                                                      float *__restrict__ p1, unsigned char *__restrict__ mask)
+                                                      float *__restrict__ p1, unsigned char *__restrict__ mask,
+                                                      const unsigned char *__restrict__ mask_in)
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
@@ -99,20 +100,23 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
             }
         } else {
             const Vec gv = *(const Vec *)(dout + off);
-            Vec ov;
-            if (relu) ov = *(const Vec *)(out + off);
             unsigned bits = 0;
+            if (mask_in) {
+                bits = mask_in[off / VEC];        // handed over by the forward pass: `out` is not read at all
+            } else if (relu) {
+                const Vec ov = *(const Vec *)(out + off);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) bits |= ((float)ov[e] > 0.f ? 1u : 0u) << e;
+                // one byte per vector: the apply pass reads this instead of `out` (an eighth or a sixteenth of its bytes)
+                mask[off / VEC] = (unsigned char)bits;
+            }
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 float dz = (float)gv[e];
-                const bool on = !relu || (float)ov[e] > 0.f;
-                if (!on) dz = 0.f;
-                bits |= (on ? 1u : 0u) << e;
+                if (relu && !((bits >> e) & 1u)) dz = 0.f;
                 s0[e] += dz;
                 s1[e] += dz * (((float)xv[e] - sh[e]) * sc[e]);
             }
-            // one byte per vector: the apply pass reads this instead of `out` (an eighth or a sixteenth of its bytes)
-            if (relu) mask[off / VEC] = (unsigned char)bits;
         }
     }
     __shared__ float red0[256 * VEC], red1[256 * VEC];
@@ -137,7 +141,8 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
 template <typename T, bool HAS_RES, bool RELU>
 __global__ __launch_bounds__(256) void bn_apply_nhwc(const T *__restrict__ x, const T *__restrict__ res,
                                                      T *__restrict__ out, const float *__restrict__ scale,
-                                                     const float *__restrict__ bias, long nvec, int C)
+                                                     const float *__restrict__ bias, long nvec, int C,
+                                                     unsigned char *__restrict__ mask)
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
@@ -155,14 +160,17 @@ __global__ __launch_bounds__(256) void bn_apply_nhwc(const T *__restrict__ x, co
         Vec rv;
         if (HAS_RES) rv = __builtin_nontemporal_load((const Vec *)(res + i * VEC));
         Vec ov;
+        unsigned bits = 0;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
             float z = (float)xv[e] * sc[e] + bi[e];
             if (HAS_RES) z += (float)rv[e];
             if (RELU) z = z > 0.f ? z : 0.f;
             ov[e] = (T)z;
+            bits |= ((float)ov[e] > 0.f ? 1u : 0u) << e;   // of the value as stored
         }
         __builtin_nontemporal_store(ov, (Vec *)(out + i * VEC));
+        if (RELU && mask) mask[i] = (unsigned char)bits;
     }
 }
 
@@ -403,7 +411,7 @@ int stream_blocks(long work_items)
 template <typename T>
 int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *gamma, const float *beta, T *out,
                  float *save_mean, float *save_invstd, float *running_mean, float *running_var, float *ws,
-                 hipStream_t stream)
+                 unsigned char *relu_mask, hipStream_t stream)
 {
     const Geom g = geometry(d, false);
     float *p0 = ws, *p1 = ws + (long)g.G * d.C, *scale = p1 + (long)g.G * d.C, *bias = scale + d.C;
@@ -411,7 +419,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
     if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 0>), dim3(g.G), dim3(256), 0, stream, x, (const T *)nullptr,
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, g.M, d.C,
-                           g.rows_per_block, p0, p1, (unsigned char *)nullptr);
+                           g.rows_per_block, p0, p1, (unsigned char *)nullptr, (const unsigned char *)nullptr);
     } else {
         hipLaunchKernelGGL((bn_reduce_generic<T, 0>), dim3(d.C, g.G), dim3(256), 0, stream, x, (const T *)nullptr,
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, d.N, g.HW, g.sn,
@@ -424,7 +432,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
         const long nvec = g.total / VEC;
         const dim3 grid(stream_blocks(nvec));
 #define NSK_APPLY(R, L) \
-    hipLaunchKernelGGL((bn_apply_nhwc<T, R, L>), grid, dim3(256), 0, stream, x, res, out, scale, bias, nvec, d.C)
+    hipLaunchKernelGGL((bn_apply_nhwc<T, R, L>), grid, dim3(256), 0, stream, x, res, out, scale, bias, nvec, d.C, relu_mask)
         if (res) {
             if (d.relu) NSK_APPLY(true, true); else NSK_APPLY(true, false);
         } else {
@@ -446,7 +454,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
 template <typename T>
 int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout, const float *gamma,
                  const float *mean, const float *invstd, T *dx, T *dres, float *dgamma, float *dbeta, float *ws,
-                 hipStream_t stream)
+                 const unsigned char *mask_in, hipStream_t stream)
 {
     const Geom g = geometry(d, true);
     float *p0 = ws, *p1 = ws + (long)g.G * d.C, *coef = p1 + (long)g.G * d.C;
@@ -455,7 +463,7 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
     constexpr int VEC = BT<T>::VEC;
     if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 1>), dim3(g.G), dim3(256), 0, stream, x, out, dout, mean, invstd,
-                           d.relu, g.M, d.C, g.rows_per_block, p0, p1, mask);
+                           d.relu, g.M, d.C, g.rows_per_block, p0, p1, mask, mask_in);
     } else {
         hipLaunchKernelGGL((bn_reduce_generic<T, 1>), dim3(d.C, g.G), dim3(256), 0, stream, x, out, dout, mean,
                            invstd, d.relu, d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1);
@@ -467,7 +475,7 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
         const dim3 grid(stream_blocks(nvec));
 #define NSK_BAPPLY(R, L)                                                                                       \
     hipLaunchKernelGGL((bn_bwd_apply_nhwc<T, R, L>), grid, dim3(256), 0, stream, x, out, dout, dx, dres, mean, \
-                       invstd, coef, nvec, d.C, mask)
+                       invstd, coef, nvec, d.C, mask_in ? mask_in : mask)
         if (dres) {
             if (d.relu) NSK_BAPPLY(true, true); else NSK_BAPPLY(true, false);
         } else {
@@ -504,25 +512,25 @@ int bn_partial_blocks(const nsk_bn_desc_t &d)
 
 int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
                   const float *beta, void *out, float *save_mean, float *save_invstd, float *running_mean,
-                  float *running_var, void *ws, hipStream_t stream)
+                  float *running_var, void *ws, unsigned char *relu_mask, hipStream_t stream)
 {
     if (d.dtype == NSK_BF16)
         return bn_fwd_typed<bf16_t>(d, (const bf16_t *)x, (const bf16_t *)residual, gamma, beta, (bf16_t *)out,
-                                    save_mean, save_invstd, running_mean, running_var, (float *)ws, stream);
+                                    save_mean, save_invstd, running_mean, running_var, (float *)ws, relu_mask, stream);
     return bn_fwd_typed<float>(d, (const float *)x, (const float *)residual, gamma, beta, (float *)out, save_mean,
-                               save_invstd, running_mean, running_var, (float *)ws, stream);
+                               save_invstd, running_mean, running_var, (float *)ws, relu_mask, stream);
 }
 
 int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout, const float *gamma,
                   const float *save_mean, const float *save_invstd, void *dx, void *dres, float *dgamma,
-                  float *dbeta, void *ws, hipStream_t stream)
+                  float *dbeta, void *ws, const unsigned char *relu_mask, hipStream_t stream)
 {
     if (d.dtype == NSK_BF16)
         return bn_bwd_typed<bf16_t>(d, (const bf16_t *)x, (const bf16_t *)out, (const bf16_t *)dout, gamma,
                                     save_mean, save_invstd, (bf16_t *)dx, (bf16_t *)dres, dgamma, dbeta,
-                                    (float *)ws, stream);
+                                    (float *)ws, relu_mask, stream);
     return bn_bwd_typed<float>(d, (const float *)x, (const float *)out, (const float *)dout, gamma, save_mean,
-                               save_invstd, (float *)dx, (float *)dres, dgamma, dbeta, (float *)ws, stream);
+                               save_invstd, (float *)dx, (float *)dres, dgamma, dbeta, (float *)ws, relu_mask, stream);
 }
 
 }  // namespace nsk

@@ -402,7 +402,7 @@ int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *re
         return NSK_ERR_ALIGNMENT;
     NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
     return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
-                         workspace, (hipStream_t)stream);
+                         workspace, nullptr, (hipStream_t)stream);
 }
 
 int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *out, const void *dout,
@@ -419,7 +419,47 @@ int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *ou
         return NSK_ERR_ALIGNMENT;
     NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_BWD)));
     return launch_bn_bwd(*desc, x, out, dout, gamma, save_mean, save_invstd, dx, dresidual, dgamma, dbeta, workspace,
-                         (hipStream_t)stream);
+                         nullptr, (hipStream_t)stream);
+}
+
+size_t nsk_bn_mask_bytes(const nsk_bn_desc_t *desc)
+{
+    if (bn_geometry(desc) != NSK_OK) return 0;
+    return bn_mask_bytes(*desc);
+}
+
+int nsk_bn_relu_add_fwd_mask(const nsk_bn_desc_t *desc, const void *x, const void *residual, const float *gamma,
+                             const float *beta, void *out, unsigned char *relu_mask, float *save_mean,
+                             float *save_invstd, float *running_mean, float *running_var, void *workspace,
+                             size_t workspace_bytes, void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (bn_mask_bytes(*desc) == 0) return NSK_ERR_UNSUPPORTED;
+    if (!x || !gamma || !beta || !out || !relu_mask || !save_mean || !save_invstd) return NSK_ERR_NULL;
+    if ((running_mean == nullptr) != (running_var == nullptr)) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(residual) || misaligned(out) || misaligned(relu_mask) || misaligned(gamma) ||
+        misaligned(beta) || misaligned(save_mean) || misaligned(save_invstd) || misaligned(running_mean) ||
+        misaligned(running_var))
+        return NSK_ERR_ALIGNMENT;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
+    return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
+                         workspace, relu_mask, (hipStream_t)stream);
+}
+
+int nsk_bn_relu_add_bwd_mask(const nsk_bn_desc_t *desc, const void *x, const unsigned char *relu_mask, const void *dout,
+                             const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
+                             void *dresidual, float *dgamma, float *dbeta, void *workspace, size_t workspace_bytes,
+                             void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (bn_mask_bytes(*desc) == 0) return NSK_ERR_UNSUPPORTED;
+    if (!x || !relu_mask || !dout || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(relu_mask) || misaligned(dout) || misaligned(dx) || misaligned(dresidual) ||
+        misaligned(gamma) || misaligned(save_mean) || misaligned(save_invstd) || misaligned(dgamma) || misaligned(dbeta))
+        return NSK_ERR_ALIGNMENT;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_BWD)));
+    return launch_bn_bwd(*desc, x, nullptr, dout, gamma, save_mean, save_invstd, dx, dresidual, dgamma, dbeta, workspace,
+                         relu_mask, (hipStream_t)stream);
 }
 
 int nsk_maxpool2d_out_dims(const nsk_pool_desc_t *desc, int *P, int *Q)

@@ -151,10 +151,11 @@ int bn_partial_blocks(const nsk_bn_desc_t &d);
 size_t bn_mask_bytes(const nsk_bn_desc_t &d);
 int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
                   const float *beta, void *out, float *save_mean, float *save_invstd,
-                  float *running_mean, float *running_var, void *ws, hipStream_t stream);
+                  float *running_mean, float *running_var, void *ws, unsigned char *relu_mask, hipStream_t stream);
 int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout,
                   const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
-                  void *dres, float *dgamma, float *dbeta, void *ws, hipStream_t stream);
+                  void *dres, float *dgamma, float *dbeta, void *ws, const unsigned char *relu_mask,
+                  hipStream_t stream);
 int launch_maxpool_fwd(const nsk_pool_desc_t &d, int P, int Q, const void *x, void *y,
                        signed char *idx, hipStream_t stream);
 int launch_maxpool_bwd(const nsk_pool_desc_t &d, int P, int Q, const void *dy,

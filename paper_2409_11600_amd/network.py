@@ -36,7 +36,8 @@ def _to_device(a: np.ndarray, dtype, layout, device, is_filter=False):
 
 
 class GpuNetwork:
-    def __init__(self, wl: dict, tensors: dict, layout: int = B.NSK_NHWC, device: str = "cuda:0", eps: float = 1e-5):
+    def __init__(self, wl: dict, tensors: dict, layout: int = B.NSK_NHWC, device: str = "cuda:0", eps: float = 1e-5,
+                 use_relu_mask: bool = True):
         self.wl, self.layout, self.device = wl, layout, torch.device(device)
         self.dtype = torch.bfloat16 if wl["dtype"] == "bf16" else torch.float32
         self.code = B.NSK_BF16 if wl["dtype"] == "bf16" else B.NSK_F32
@@ -54,7 +55,7 @@ class GpuNetwork:
         self.grad[wl["output"]].copy_(_to_device(tensors["dout"], dt, layout, dev))
         self.w, self.gamma, self.beta = {}, {}, {}
         self.dw, self.dgamma, self.dbeta = {}, {}, {}
-        self.y, self.dy, self.mean, self.invstd, self.idx = {}, {}, {}, {}, {}
+        self.y, self.dy, self.mean, self.invstd, self.idx, self.mask = {}, {}, {}, {}, {}, {}
         ws_bytes = 0
         self.fwd_calls: List[tuple] = []
         self.bwd_calls: List[tuple] = []
@@ -101,9 +102,19 @@ class GpuNetwork:
             fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
                                                 ptr(self.y[name])), "ws"))
             res = self.act[u["res"]] if u["res"] else None
-            fwd_plan.append((L.nsk_bn_relu_add_fwd, (ctypes.byref(bd), ptr(self.y[name]), ptr(res), ptr(self.gamma[name]),
-                                                     ptr(self.beta[name]), ptr(self.act[u["dst"]]), ptr(self.mean[name]),
-                                                     ptr(self.invstd[name]), None, None), "ws"))
+            # where the library offers it, the ReLU mask goes from forward to backward as one byte per vector and
+            # the backward pass never reads the normalised activation
+            mb = int(L.nsk_bn_mask_bytes(ctypes.byref(bd))) if use_relu_mask else 0
+            if mb:
+                self.mask[name] = torch.empty(mb, dtype=torch.uint8, device=dev)
+                fwd_plan.append((L.nsk_bn_relu_add_fwd_mask, (ctypes.byref(bd), ptr(self.y[name]), ptr(res),
+                                                              ptr(self.gamma[name]), ptr(self.beta[name]),
+                                                              ptr(self.act[u["dst"]]), ptr(self.mask[name]),
+                                                              ptr(self.mean[name]), ptr(self.invstd[name]), None, None), "ws"))
+            else:
+                fwd_plan.append((L.nsk_bn_relu_add_fwd, (ctypes.byref(bd), ptr(self.y[name]), ptr(res), ptr(self.gamma[name]),
+                                                         ptr(self.beta[name]), ptr(self.act[u["dst"]]), ptr(self.mean[name]),
+                                                         ptr(self.invstd[name]), None, None), "ws"))
 
         # backward: reverse walk; first contribution to a gradient overwrites, later ones accumulate
         for u in reversed(wl["units"]):
@@ -130,10 +141,16 @@ class GpuNetwork:
                     assert u["res"] not in written, "residual gradient must be the first contribution"
                     dres = self.grad[u["res"]]
                     written.add(u["res"])
-                bwd_plan.append((L.nsk_bn_relu_add_bwd, (ctypes.byref(bd), ptr(self.y[name]), ptr(self.act[u["dst"]]),
-                                                         ptr(g_dst), ptr(self.gamma[name]), ptr(self.mean[name]),
-                                                         ptr(self.invstd[name]), ptr(self.dy[name]), ptr(dres),
-                                                         ptr(self.dgamma[name]), ptr(self.dbeta[name])), "ws"))
+                if name in self.mask:
+                    bwd_plan.append((L.nsk_bn_relu_add_bwd_mask, (ctypes.byref(bd), ptr(self.y[name]), ptr(self.mask[name]),
+                                                                  ptr(g_dst), ptr(self.gamma[name]), ptr(self.mean[name]),
+                                                                  ptr(self.invstd[name]), ptr(self.dy[name]), ptr(dres),
+                                                                  ptr(self.dgamma[name]), ptr(self.dbeta[name])), "ws"))
+                else:
+                    bwd_plan.append((L.nsk_bn_relu_add_bwd, (ctypes.byref(bd), ptr(self.y[name]), ptr(self.act[u["dst"]]),
+                                                             ptr(g_dst), ptr(self.gamma[name]), ptr(self.mean[name]),
+                                                             ptr(self.invstd[name]), ptr(self.dy[name]), ptr(dres),
+                                                             ptr(self.dgamma[name]), ptr(self.dbeta[name])), "ws"))
                 dy = self.dy[name]
             else:
                 dy = g_dst

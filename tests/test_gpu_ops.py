@@ -235,6 +235,47 @@ def test_bn_relu_add_fwd_bwd(i, relu, with_res, dtype, layout):
 POOL_SHAPES = [(2, 64, 20, 20), (1, 16, 13, 17), (2, 5, 9, 9), (1, 8, 6, 6)]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("with_res", [True, False])
+@pytest.mark.parametrize("i", [0, 1, 2, 3])
+def test_bn_relu_mask_calls_match_the_plain_calls(i, with_res, dtype):
+    """The *_mask entry points hand the ReLU mask from forward to backward (one byte per 16-byte vector): the mask must
+    equal out > 0 element for element and every result must equal the plain calls bit for bit (same kernels, same
+    order of operations)."""
+    x, r, dout, g, b = _bn_case(i, dtype)
+    layout = B.NSK_NHWC
+    print(f"bn mask case {BN_SHAPES[i]} res={with_res} {dtype}", flush=True)
+    ws = B.Workspace()
+    gx, gr, gd = to_gpu(x, dtype, layout), to_gpu(r, dtype, layout), to_gpu(dout, dtype, layout)
+    gg, gb = torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda()
+    res = gr if with_res else None
+    nbytes = B.bn_mask_bytes(gx, layout, True)
+    vec = 8 if dtype == "bf16" else 4
+    assert nbytes == gx.numel() // vec
+    assert B.bn_mask_bytes(gx, layout, False) == 0 and B.bn_mask_bytes(gx, B.NSK_NCHW, True) == 0
+    raw_mask = torch.full((nbytes + 1024,), 0xAA, dtype=torch.uint8, device="cuda:0")   # canaries on both sides
+    mask_view = raw_mask[512:512 + nbytes]
+
+    def mask_check():
+        assert bool((raw_mask[:512] == 0xAA).all()) and bool((raw_mask[512 + nbytes:] == 0xAA).all())
+
+    out0, mean0, inv0 = B.bn_relu_add_fwd(gx, gg, gb, res, 1e-5, True, layout, ws=ws)
+    out1, mean1, inv1 = B.bn_relu_add_fwd(gx, gg, gb, res, 1e-5, True, layout, ws=ws, relu_mask=mask_view)
+    torch.cuda.synchronize()
+    mask_check()
+    assert torch.equal(out0, out1) and torch.equal(mean0, mean1) and torch.equal(inv0, inv1)
+    bits = (out1.reshape(-1, vec).float() > 0).to(torch.int32)
+    want_mask = (bits << torch.arange(vec, device="cuda:0", dtype=torch.int32)).sum(dim=1).to(torch.uint8)
+    assert torch.equal(mask_view, want_mask)
+    dx0, dr0, dg0, db0 = B.bn_relu_add_bwd(gx, out0, gd, gg, mean0, inv0, True, layout, want_dresidual=with_res, ws=ws)
+    dx1, dr1, dg1, db1 = B.bn_relu_add_bwd(gx, None, gd, gg, mean0, inv0, True, layout, want_dresidual=with_res, ws=ws,
+                                           relu_mask=mask_view)
+    torch.cuda.synchronize()
+    assert torch.equal(dx0, dx1) and torch.equal(dg0, dg1) and torch.equal(db0, db1)
+    if with_res:
+        assert torch.equal(dr0, dr1)
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", range(len(POOL_SHAPES)))
