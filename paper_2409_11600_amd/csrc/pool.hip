@@ -177,12 +177,88 @@ __global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T *__restrict__ 
     }
 }
 
+// Backward of the 3x3 stride-2 pad-1 pool on even H, W (the stem's pool), channel-contiguous data: one thread per
+// 2x2 block of input pixels and VEC channels.  The block (rows 2m, 2m+1, columns 2n, 2n+1) lies in the windows
+// p in {m, m+1}, q in {n, n+1} only, so four window loads serve four pixels (the per-pixel kernel needs nine).
+// Window (p, q) covers rows 2p-1..2p+1: row 2m is its row r = 1 for p = m; row 2m+1 is r = 2 for p = m and r = 0
+// for p = m+1; columns likewise.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void maxpool3s2_bwd_kernel(const T *__restrict__ dy, const signed char *__restrict__ idx,
+                                                             T *__restrict__ dx, int N, int C, int H, int W)
+{
+    typedef T Vec __attribute__((ext_vector_type(VEC)));
+    const int CV = C / VEC, P = H / 2, Q = W / 2;
+    const long total = (long)N * P * Q * CV;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % CV) * VEC;
+    long r = i / CV;
+    const int n_ = (int)(r % Q);
+    r /= Q;
+    const int m = (int)(r % P), img = (int)(r / P);
+    float acc[2][2][VEC];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[a][b][e] = 0.f;
+#pragma unroll
+    for (int dp = 0; dp < 2; ++dp)
+#pragma unroll
+        for (int dq = 0; dq < 2; ++dq) {
+            const int p = m + dp, q = n_ + dq;
+            if (p >= P || q >= Q) continue;
+            const long o = (((long)img * P + p) * Q + q) * C + c;
+            Vec gv;
+            unsigned long long iv;
+            if constexpr (VEC == 8) {
+                iv = __builtin_nontemporal_load((const unsigned long long *)(idx + o));
+            } else {
+                iv = __builtin_nontemporal_load((const unsigned *)(idx + o));
+            }
+            gv = __builtin_nontemporal_load((const Vec *)(dy + o));
+            // pixel (a, b) of the block is window position (ra, sb) of window (p, q), if it is inside it
+#pragma unroll
+            for (int a = 0; a < 2; ++a) {
+                const int ra = dp == 0 ? a + 1 : (a == 1 ? 0 : -1);
+                if (ra < 0) continue;
+#pragma unroll
+                for (int b = 0; b < 2; ++b) {
+                    const int sb = dq == 0 ? b + 1 : (b == 1 ? 0 : -1);
+                    if (sb < 0) continue;
+                    const int pos = ra * 3 + sb;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+                        if ((int)(signed char)(iv >> (8 * e)) == pos) acc[a][b][e] += (float)gv[e];
+                }
+            }
+        }
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            Vec v;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) v[e] = (T)acc[a][b][e];
+            __builtin_nontemporal_store(v, (Vec *)(dx + ((((long)img * H + 2 * m + a) * W + 2 * n_ + b) * C + c)));
+        }
+}
+
 template <typename T, int VEC>
 int pool_typed(bool fwd, const nsk_pool_desc_t &d, int P, int Q, const void *a, void *b, const signed char *idx_in,
                signed char *idx_out, hipStream_t stream)
 {
     const PoolGeom g = make_geom(d, P, Q);
     const bool vec = d.layout == NSK_NHWC && d.C % VEC == 0;
+    if (!fwd && vec && d.R == 3 && d.S == 3 && d.stride_h == 2 && d.stride_w == 2 && d.pad_h == 1 && d.pad_w == 1 &&
+        d.H % 2 == 0 && d.W % 2 == 0) {
+        const long blocks2 = (long)d.N * (d.H / 2) * (d.W / 2) * (d.C / VEC);
+        if (blocks2 == 0) return NSK_OK;
+        hipLaunchKernelGGL((maxpool3s2_bwd_kernel<T, VEC>), dim3((unsigned)((blocks2 + 255) / 256)), dim3(256), 0, stream,
+                           (const T *)a, idx_in, (T *)b, d.N, d.C, d.H, d.W);
+        return check_launch();
+    }
     const long pix = fwd ? (long)d.N * P * Q : (long)d.N * d.H * d.W;
     const long total = pix * (vec ? d.C / VEC : d.C);
     if (total == 0) return NSK_OK;
