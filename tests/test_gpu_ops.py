@@ -30,6 +30,8 @@ CONV_SHAPES = [
     (2, 3, 38, 42, 64, 7, 7, 2, 3, 1),         # 7x7 stride-2 stem, even extents (space-to-depth path)
     (1, 4, 20, 16, 24, 5, 5, 2, 2, 1),         # 5x5 stride-2, 4 channels (space-to-depth, 3x3 coarse taps)
     (2, 1, 12, 18, 16, 3, 3, 2, 1, 1),         # 3x3 stride-2, single channel (space-to-depth, 2x2 coarse taps)
+    (1, 64, 6, 66, 64, 3, 3, 1, 1, 1),         # 64->64 on a 66-wide image: too wide for the input ring, single-group halo kernel
+    (2, 64, 16, 32, 64, 3, 3, 1, 1, 1),        # 64->64 on 32-wide images with H % 8 == 0: the row-aligned fp32 kernels
 ]
 
 
@@ -135,7 +137,7 @@ def test_conv_wide_layers_large_tile_kernel(i, layout, monkeypatch):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [1, 2, 3, 8, 12, 13])
+@pytest.mark.parametrize("i", [1, 2, 3, 8, 12, 13, 15, 16])
 def test_conv_gradients_accumulate(i, dtype, layout):
     x, w, dy, st, pd, dl = _conv_case(i, dtype)
     ws = B.Workspace()
