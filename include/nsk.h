@@ -110,6 +110,16 @@ size_t nsk_conv2d_workspace_bytes(const nsk_conv_desc_t *desc, int pass);
 int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/* Forward convolution that also leaves per-channel partial sums of its output for a batch-norm that follows
+ * (the statistics pass of that batch-norm then need not read y again).  stats: device memory for
+ * 2 * rows * K floats with rows = nsk_conv2d_stats_rows(desc) (host only, 0 for an invalid descriptor):
+ * stats[r*K + k] and stats[(rows + r)*K + k] receive the sum and the sum of squares of y[.., k], as stored, over
+ * the r-th of `rows` disjoint shares of the output pixels; every entry is written.  Where the kernel that
+ * computes y has no such epilogue the sums come from a separate pass over y; the result is the same. */
+int nsk_conv2d_stats_rows(const nsk_conv_desc_t *desc);
+int nsk_conv2d_fwd_stats(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, float *stats,
+                         void *workspace, size_t workspace_bytes, void *stream);
+
 /* Backward-data: dx = adjoint of the forward map with respect to x applied to dy.
  * dy: [N,K,P,Q], w as in forward, dx: [N,C,H,W].  accumulate: see the header comment;
  * with accumulate = 0 input positions that no filter tap reaches (strided cases) are
@@ -160,6 +170,14 @@ int nsk_bn_relu_add_fwd_mask(const nsk_bn_desc_t *desc, const void *x, const voi
                              const float *gamma, const float *beta, void *out, unsigned char *relu_mask,
                              float *save_mean, float *save_invstd, float *running_mean,
                              float *running_var, void *workspace, size_t workspace_bytes, void *stream);
+/* nsk_bn_relu_add_fwd with the batch statistics taken from partial sums of x and x*x (layout as written by
+ * nsk_conv2d_fwd_stats: [2][stats_rows][C] floats) instead of a reduction pass over x.  relu_mask: NULL, or as in
+ * nsk_bn_relu_add_fwd_mask.  The variance is formed as E[x*x] - E[x]^2 in double precision. */
+int nsk_bn_relu_add_fwd_stats(const nsk_bn_desc_t *desc, const void *x, const void *residual,
+                              const float *gamma, const float *beta, void *out, unsigned char *relu_mask,
+                              float *save_mean, float *save_invstd, float *running_mean,
+                              float *running_var, const float *stats, int stats_rows, void *workspace,
+                              size_t workspace_bytes, void *stream);
 int nsk_bn_relu_add_bwd_mask(const nsk_bn_desc_t *desc, const void *x, const unsigned char *relu_mask,
                              const void *dout, const float *gamma, const float *save_mean,
                              const float *save_invstd, void *dx, void *dresidual, float *dgamma,

@@ -90,6 +90,12 @@ def lib() -> ctypes.CDLL:
         L.nsk_bn_relu_add_fwd.argtypes = [bd] + [vp] * 10 + [sz, vp]
         L.nsk_bn_relu_add_bwd.restype = ci
         L.nsk_bn_relu_add_bwd.argtypes = [bd] + [vp] * 11 + [sz, vp]
+        L.nsk_conv2d_stats_rows.restype = ci
+        L.nsk_conv2d_stats_rows.argtypes = [cd]
+        L.nsk_conv2d_fwd_stats.restype = ci
+        L.nsk_conv2d_fwd_stats.argtypes = [cd, vp, vp, vp, vp, vp, sz, vp]
+        L.nsk_bn_relu_add_fwd_stats.restype = ci
+        L.nsk_bn_relu_add_fwd_stats.argtypes = [bd] + [vp] * 11 + [ci, vp, sz, vp]
         L.nsk_bn_mask_bytes.restype = sz
         L.nsk_bn_mask_bytes.argtypes = [bd]
         L.nsk_bn_relu_add_fwd_mask.restype = ci
@@ -109,7 +115,8 @@ def lib() -> ctypes.CDLL:
 EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d_out_dims",
            "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
            "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
-           "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_maxpool2d_out_dims",
+           "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_conv2d_stats_rows", "nsk_conv2d_fwd_stats",
+           "nsk_bn_relu_add_fwd_stats", "nsk_maxpool2d_out_dims",
            "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd")
 
 
@@ -217,6 +224,29 @@ def conv2d_fwd(x, w, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None, ws:
     return out
 
 
+def conv2d_fwd_stats(x, w, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None, stats=None,
+                     ws: Optional[Workspace] = None):
+    """Forward convolution that also returns the per-channel partial sums of its output: (y, stats) with stats a
+    float32 tensor [2, rows, K] (sums, sums of squares) for bn_relu_add_fwd(..., stats=stats)."""
+    N, C, H, W = _logical(x, layout)
+    K, Cw, R, S = _filter_logical(w, layout)
+    assert Cw == C and w.dtype == x.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), layout)
+    P, Q = conv2d_out_dims(d)
+    if out is None:
+        out = torch.empty(_act_shape(N, K, P, Q, layout), dtype=x.dtype, device=x.device)
+    rows = int(lib().nsk_conv2d_stats_rows(ctypes.byref(d)))
+    assert rows > 0
+    if stats is None:
+        stats = torch.empty((2, rows, K), dtype=torch.float32, device=x.device)
+    assert stats.numel() == 2 * rows * K and stats.dtype == torch.float32
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_workspace_bytes(ctypes.byref(d), NSK_PASS_FWD))
+    _check(lib().nsk_conv2d_fwd_stats(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(out), _ptr(stats), wp, wb, _stream()),
+           "nsk_conv2d_fwd_stats")
+    return out, stats
+
+
 def conv2d_dgrad(dy, w, x_logical, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None, accumulate=False,
                  ws: Optional[Workspace] = None):
     """x_logical = (N,C,H,W) of the forward input."""
@@ -266,9 +296,10 @@ def bn_mask_bytes(x, layout=NSK_NHWC, relu=True) -> int:
 
 def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=NSK_NHWC, momentum=0.1,
                     running_mean=None, running_var=None, out=None, save_mean=None, save_invstd=None,
-                    ws: Optional[Workspace] = None, relu_mask=None):
+                    ws: Optional[Workspace] = None, relu_mask=None, stats=None):
     """Returns (out, save_mean, save_invstd).  With relu_mask (uint8 tensor of bn_mask_bytes(x) bytes) the ReLU
-    mask is written there for bn_relu_add_bwd(..., relu_mask=...)."""
+    mask is written there for bn_relu_add_bwd(..., relu_mask=...).  With stats ([2, rows, C] float32 partial sums of
+    x and x*x, as returned by conv2d_fwd_stats) the statistics pass over x is skipped."""
     d = bn_desc(x, layout, eps, momentum, relu)
     C = d.C
     if out is None:
@@ -279,6 +310,12 @@ def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=N
         save_invstd = torch.empty(C, dtype=torch.float32, device=x.device)
     ws = ws or Workspace(x.device)
     wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_FWD))
+    if stats is not None:
+        _check(lib().nsk_bn_relu_add_fwd_stats(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
+                                               _ptr(relu_mask), _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean),
+                                               _ptr(running_var), _ptr(stats), int(stats.shape[1]), wp, wb, _stream()),
+               "nsk_bn_relu_add_fwd_stats")
+        return out, save_mean, save_invstd
     if relu_mask is not None:
         _check(lib().nsk_bn_relu_add_fwd_mask(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
                                               _ptr(relu_mask), _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean),

@@ -66,7 +66,7 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
                                                       const float *__restrict__ invstd, int relu, long M, int C,
                                                       long rows_per_block, float *__restrict__ p0,
                                                       float *__restrict__ p1, unsigned char *__restrict__ mask,
-                                                      const unsigned char *__restrict__ mask_in)
+                                                      const unsigned char *__restrict__ mask_in, int noshift = 0)
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
         s0[e] = 0.f;
         s1[e] = 0.f;
         if (MODE == 0) {
-            sh[e] = (float)x[cv * VEC + e];
+            sh[e] = noshift ? 0.f : (float)x[cv * VEC + e];
             sc[e] = 1.f;
         } else {
             sh[e] = mean[cv * VEC + e];
@@ -222,10 +222,10 @@ __global__ __launch_bounds__(256) void bn_reduce_generic(const T *__restrict__ x
                                                          const T *__restrict__ dout, const float *__restrict__ mean,
                                                          const float *__restrict__ invstd, int relu, int N, long HW,
                                                          long sn, long scs, long ss, int npg, int C,
-                                                         float *__restrict__ p0, float *__restrict__ p1)
+                                                         float *__restrict__ p0, float *__restrict__ p1, int noshift = 0)
 {
     const int c = blockIdx.x, g = blockIdx.y;
-    const float sh = MODE == 0 ? (float)x[c * scs] : mean[c];
+    const float sh = MODE == 0 ? (noshift ? 0.f : (float)x[c * scs]) : mean[c];
     const float scl = MODE == 0 ? 1.f : invstd[c];
     float s0 = 0.f, s1 = 0.f;
     const int n_end = min(N, (g + 1) * npg);
@@ -313,7 +313,7 @@ __global__ void bn_fwd_finalize(const float *__restrict__ p0, const float *__res
     const double ms = S / M;
     double var = Q / M - ms * ms;
     if (var < 0.0) var = 0.0;
-    const double mean = (double)(float)x[c * shift_stride] + ms;
+    const double mean = (x ? (double)(float)x[c * shift_stride] : 0.0) + ms;   // x == nullptr: the sums are not shifted
     const double invstd = 1.0 / sqrt(var + (double)eps);
     save_mean[c] = (float)mean;
     save_invstd[c] = (float)invstd;
@@ -411,12 +411,17 @@ int stream_blocks(long work_items)
 template <typename T>
 int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *gamma, const float *beta, T *out,
                  float *save_mean, float *save_invstd, float *running_mean, float *running_var, float *ws,
-                 unsigned char *relu_mask, hipStream_t stream)
+                 unsigned char *relu_mask, const float *stats, int stats_rows, hipStream_t stream)
 {
     const Geom g = geometry(d, false);
     float *p0 = ws, *p1 = ws + (long)g.G * d.C, *scale = p1 + (long)g.G * d.C, *bias = scale + d.C;
     constexpr int VEC = BT<T>::VEC;
-    if (g.fast) {
+    if (stats) {
+        // partial sums of x and x^2 left by the producer of x ([2][stats_rows][C], not shifted): no reduction pass
+        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, stats,
+                           stats + (long)stats_rows * d.C, stats_rows, d.C, (double)g.M, (const T *)nullptr, 0L, gamma, beta,
+                           d.eps, d.momentum, save_mean, save_invstd, running_mean, running_var, scale, bias);
+    } else if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 0>), dim3(g.G), dim3(256), 0, stream, x, (const T *)nullptr,
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, g.M, d.C,
                            g.rows_per_block, p0, p1, (unsigned char *)nullptr, (const unsigned char *)nullptr);
@@ -425,9 +430,10 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, d.N, g.HW, g.sn,
                            g.sc, g.ss, g.npg, d.C, p0, p1);
     }
-    hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, p0, p1, g.G, d.C,
-                       (double)g.M, x, g.sc, gamma, beta, d.eps, d.momentum, save_mean, save_invstd, running_mean,
-                       running_var, scale, bias);
+    if (!stats)
+        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+                           (double)g.M, x, g.sc, gamma, beta, d.eps, d.momentum, save_mean, save_invstd, running_mean,
+                           running_var, scale, bias);
     if (g.fast) {
         const long nvec = g.total / VEC;
         const dim3 grid(stream_blocks(nvec));
@@ -512,13 +518,41 @@ int bn_partial_blocks(const nsk_bn_desc_t &d)
 
 int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
                   const float *beta, void *out, float *save_mean, float *save_invstd, float *running_mean,
-                  float *running_var, void *ws, unsigned char *relu_mask, hipStream_t stream)
+                  float *running_var, void *ws, unsigned char *relu_mask, const float *stats, int stats_rows,
+                  hipStream_t stream)
 {
     if (d.dtype == NSK_BF16)
         return bn_fwd_typed<bf16_t>(d, (const bf16_t *)x, (const bf16_t *)residual, gamma, beta, (bf16_t *)out,
-                                    save_mean, save_invstd, running_mean, running_var, (float *)ws, relu_mask, stream);
+                                    save_mean, save_invstd, running_mean, running_var, (float *)ws, relu_mask, stats,
+                                    stats_rows, stream);
     return bn_fwd_typed<float>(d, (const float *)x, (const float *)residual, gamma, beta, (float *)out, save_mean,
-                               save_invstd, running_mean, running_var, (float *)ws, relu_mask, stream);
+                               save_invstd, running_mean, running_var, (float *)ws, relu_mask, stats, stats_rows, stream);
+}
+
+// Partial sums of x and x^2 per channel, [2][bn_stats_rows(d)][C] floats, not shifted: what the convolution kernels
+// with a fused statistics epilogue write, produced here by a reduction pass for the shapes they do not cover.
+int bn_stats_rows(const nsk_bn_desc_t &d) { return geometry(d, false).G; }
+
+int launch_bn_stats(const nsk_bn_desc_t &d, const void *x, float *stats, hipStream_t stream)
+{
+    const Geom g = geometry(d, false);
+    float *p0 = stats, *p1 = stats + (long)g.G * d.C;
+#define NSK_STATS(T)                                                                                                   \
+    if (g.fast)                                                                                                        \
+        hipLaunchKernelGGL((bn_reduce_nhwc<T, 0>), dim3(g.G), dim3(256), 0, stream, (const T *)x, (const T *)nullptr,  \
+                           (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, g.M, d.C,            \
+                           g.rows_per_block, p0, p1, (unsigned char *)nullptr, (const unsigned char *)nullptr, 1);     \
+    else                                                                                                               \
+        hipLaunchKernelGGL((bn_reduce_generic<T, 0>), dim3(d.C, g.G), dim3(256), 0, stream, (const T *)x,              \
+                           (const T *)nullptr, (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0,  \
+                           d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1, 1)
+    if (d.dtype == NSK_BF16) {
+        NSK_STATS(bf16_t);
+    } else {
+        NSK_STATS(float);
+    }
+#undef NSK_STATS
+    return check_launch();
 }
 
 int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout, const float *gamma,

@@ -45,6 +45,8 @@ struct HaloArgs {
     unsigned src_bytes, out_bytes;
     int accumulate;
     int tapoff[9];            // shift of each tap in flat padded positions
+    float *stats;             // two-group kernel only: per-channel partial sums of the stored output, or nullptr
+    int stats_rows;           // 8 rows per block (one per wavefront)
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -294,7 +296,34 @@ __global__ __launch_bounds__(512) void conv_halo64_pp_kernel(const HaloArgs a)
     const int tiles_per_block = (a.tiles + (int)gridDim.x - 1) / (int)gridDim.x;
     const int T0 = blockIdx.x * tiles_per_block;
     const int n = min(a.tiles, T0 + tiles_per_block) - T0;      // tiles of this block
-    if (n <= 0) return;                                          // uniform for the block: no barrier is skipped
+    // Statistics epilogue (forward only): every lane adds up the 8 channels of its 16-byte pieces over all the
+    // positions it stores during the life of the block; one cross-lane reduction and one row per wavefront at the end.
+    float ssum[8], ssq[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ssum[e] = ssq[e] = 0.f;
+    auto write_stats = [&]() {
+        if (!a.stats) return;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int o = 8; o < 64; o <<= 1) {
+                ssum[e] += __shfl_xor(ssum[e], o, 64);
+                ssq[e] += __shfl_xor(ssq[e], o, 64);
+            }
+        if (lane < 8) {
+            float *r0 = a.stats + (size_t)(blockIdx.x * 8 + wave) * 64 + lane * 8;
+            float *r1 = r0 + (size_t)a.stats_rows * 64;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                r0[e] = ssum[e];
+                r1[e] = ssq[e];
+            }
+        }
+    };
+    if (n <= 0) {                                                // uniform for the block: no barrier is skipped
+        write_stats();                                           // zeros: every row of the buffer is written
+        return;
+    }
     const unsigned RING = 512u + 2u * (unsigned)a.halo;
     const int Q0 = T0 * HT - a.halo;                             // padded position held by ring row 0
 
@@ -470,6 +499,16 @@ __global__ __launch_bounds__(512) void conv_halo64_pp_kernel(const HaloArgs a)
                         const unsigned sl = wrap(ss + (unsigned)(prow + 8 * jj));
                         const u32x4 v = *(const u32x4 *)(ring + slot_addr(sl, (unsigned)chunk));
                         __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, ooff[jj], 0, 0);
+                        if (a.stats) {
+                            const float live = ooff[jj] < H_OOB ? 1.f : 0.f;   // padding positions are not stored
+                            const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const float f = live * (float)vb[e];
+                                ssum[e] += f;
+                                ssq[e] += f * f;
+                            }
+                        }
                     }
                 }
             }
@@ -485,6 +524,7 @@ __global__ __launch_bounds__(512) void conv_halo64_pp_kernel(const HaloArgs a)
         }
         lds_barrier();
     }
+    write_stats();
 }
 
 }  // namespace
@@ -507,6 +547,21 @@ bool halo64_applicable(int dtype, const IgemmArgs &a)
     return true;
 }
 
+namespace {
+bool two_group(const IgemmArgs &g) { return 512 + 2 * (g.Ws + 3) <= P_RING_MAX && getenv("NSK_HALO_SINGLE") == nullptr; }
+constexpr int kStatsGrid = 256;   // block count when statistics are requested: the row count must not depend on the device
+}  // namespace
+
+// Rows of partial sums the forward launch writes (8 per block), 0 if this shape takes the kernel without a
+// statistics epilogue.
+int halo64_stats_rows(const IgemmArgs &g)
+{
+    if (!two_group(g) || g.accumulate) return 0;
+    const int total = (g.Hs + 2) * (g.Ws + 2) * g.Nimg;
+    const int tiles = ceil_div(total, HT);
+    return (tiles < kStatsGrid ? tiles : kStatsGrid) * 8;
+}
+
 int launch_halo64(const IgemmArgs &g, hipStream_t stream)
 {
     HaloArgs a{};
@@ -521,6 +576,8 @@ int launch_halo64(const IgemmArgs &g, hipStream_t stream)
     a.src_bytes = g.src_bytes;
     a.out_bytes = g.src_bytes;   // same geometry: N*H*W*64 bf16
     a.accumulate = g.accumulate;
+    a.stats = g.stats;
+    a.stats_rows = g.stats_rows;
     for (int t = 0; t < 9; ++t) a.tapoff[t] = (g.add_h + g.off_h[t]) * a.PW + (g.add_w + g.off_w[t]);
     static int cus = 0;
     if (cus == 0) {
@@ -529,7 +586,9 @@ int launch_halo64(const IgemmArgs &g, hipStream_t stream)
         if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NSK_ERR_HIP;
         cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
     }
-    const int grid = a.tiles < cus ? a.tiles : cus;
+    const int want = g.stats ? kStatsGrid : cus;
+    const int grid = a.tiles < want ? a.tiles : want;
+    if (g.stats && g.stats_rows != grid * 8) return NSK_ERR_BAD_DESC;   // the planner and the launch disagree
     static bool attr_set = false;
     const int smem = H_MAX_IN * H_IN_STRIDE + 64 * H_W_STRIDE + 256 * 4 + H_MAX_IN * 4 + 4 * 32 * H_IN_STRIDE;
     const int smem_pp = P_RING_MAX * P_SLOT + 64 * H_W_STRIDE;
@@ -548,7 +607,7 @@ int launch_halo64(const IgemmArgs &g, hipStream_t stream)
         attr_set = true;
     }
     // the two-group kernel needs its ring (512 + 2*halo slots) to fit; wider images take the single-group kernel
-    const bool pp = 512 + 2 * a.halo <= P_RING_MAX && getenv("NSK_HALO_SINGLE") == nullptr;
+    const bool pp = two_group(g);
     if (pp) {
         if (a.accumulate)
             hipLaunchKernelGGL(conv_halo64_pp_kernel<true>, dim3(grid), dim3(512), smem_pp, stream, a);

@@ -279,6 +279,14 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         constexpr int CPP = 32 * (int)sizeof(T) / 16;       // 16-byte chunks per pixel
         static_assert(4 * 32 * SROW <= (int)sizeof(smem_ab), "epilogue staging fits in the operand buffers");
         unsigned char *my_st = (unsigned char *)smem_ab + wave * (32 * SROW);
+        // Statistics epilogue (forward with a batch-norm behind it): a lane always reads back the same 16-byte piece
+        // (VEC channels) of each staged row, so it adds those channels up over all the rows it stores; one cross-lane
+        // reduction per block and one row of partial sums per wavefront.
+        float ssum[FN][VEC], ssq[FN][VEC];
+#pragma unroll
+        for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) ssum[ni][e] = ssq[ni][e] = 0.f;
 #pragma unroll
         for (int mi = 0; mi < FM; ++mi)
 #pragma unroll
@@ -296,9 +304,42 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
                     const Vec v = *(const Vec *)(my_st + pos * SROW + ck * 16);
                     const long off = out_off[wm * WM + mi * 32 + pos];
                     const int col = wcol0 + ni * 32 + ck * VEC;
-                    if (off >= 0 && col < a.Ngemm) *(Vec *)(out + off + col) = v;
+                    if (off >= 0 && col < a.Ngemm) {
+                        *(Vec *)(out + off + col) = v;
+                        if (a.stats) {
+#pragma unroll
+                            for (int e = 0; e < VEC; ++e) {
+                                const float f = to_float(v[e]);
+                                ssum[ni][e] += f;
+                                ssq[ni][e] += f * f;
+                            }
+                        }
+                    }
                 }
             }
+        if (a.stats) {
+            const int row = blockIdx.x * (BM / WM) + wm, ck = lane % CPP;
+#pragma unroll
+            for (int ni = 0; ni < FN; ++ni) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                    for (int o = CPP; o < 64; o <<= 1) {
+                        ssum[ni][e] += __shfl_xor(ssum[ni][e], o, 64);
+                        ssq[ni][e] += __shfl_xor(ssq[ni][e], o, 64);
+                    }
+                const int col = wcol0 + ni * 32 + ck * VEC;
+                if (lane < CPP && col < a.Ngemm) {
+                    float *r0 = a.stats + (size_t)row * a.Ngemm + col;
+                    float *r1 = r0 + (size_t)a.stats_rows * a.Ngemm;
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) {
+                        r0[e] = ssum[ni][e];
+                        r1[e] = ssq[ni][e];
+                    }
+                }
+            }
+        }
     } else {
         // element-wise stores (output rows that are not 16-byte granular)
 #pragma unroll
@@ -338,6 +379,15 @@ int forced_tile()
     return e ? atoi(e) : 0;
 }
 
+// Automatic tile choice: 0 = 256x32 (64-row wavefront tiles), 1 = 128x64 (32-row), 2 = 128x128 (64-row).
+int auto_tile(const IgemmArgs &a, int es)
+{
+    if (a.Ngemm <= 32) return 0;
+    if (a.Ngemm <= 64) return 1;
+    if ((long)a.Ktot * es >= 1024) return 2;
+    return 1;
+}
+
 template <typename T> int launch_typed(const IgemmArgs &a, hipStream_t stream)
 {
     constexpr int VEC = Traits<T>::VEC;
@@ -354,13 +404,30 @@ template <typename T> int launch_typed(const IgemmArgs &a, hipStream_t stream)
     // Measured on MI355X: with 64 or fewer columns the 128-row tile wins (more blocks in flight hide
     // the per-block prologue and epilogue); wide problems with a long reduction take 128x128 tiles
     // with 128-byte k-tiles (half as many barriers).
-    if (a.Ngemm <= 32) return launch_tile<T, 256, 32, 64, 32, 64>(a, vec, stream);
-    if (a.Ngemm <= 64) return launch_tile<T, 128, 64, 32, 64, 64>(a, vec, stream);
-    if ((long)a.Ktot * (long)sizeof(T) >= 1024) return launch_tile<T, 128, 128, 64, 64, 128>(a, vec, stream);
-    return launch_tile<T, 128, 64, 32, 64, 64>(a, vec, stream);
+    switch (auto_tile(a, (int)sizeof(T))) {
+    case 0: return launch_tile<T, 256, 32, 64, 32, 64>(a, vec, stream);
+    case 1: return launch_tile<T, 128, 64, 32, 64, 64>(a, vec, stream);
+    default: return launch_tile<T, 128, 128, 64, 64, 128>(a, vec, stream);
+    }
 }
 
 }  // namespace
+
+int igemm_stats_rows(int dtype, const IgemmArgs &a)
+{
+    // the same order of tests as launch_igemm
+    if (a.M <= 0 || a.Ngemm <= 0 || a.accumulate) return 0;
+    if (forced_tile() != 0) return 0;
+    if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
+    if (halo64_f32_applicable(dtype, a)) return 0;
+    if (igemm_big_applicable(dtype, a)) return 0;
+    // generic kernel: needs the vector epilogue; one row per wavefront row of every row block
+    const int vec = dtype == NSK_BF16 ? 8 : 4;
+    if (!(a.Ngemm % vec == 0 && a.Co % vec == 0 && (uintptr_t)a.out % 16 == 0)) return 0;
+    static const int bm[3] = {256, 128, 128}, wm[3] = {64, 32, 64};
+    const int t = auto_tile(a, dtype == NSK_BF16 ? 2 : 4);
+    return ceil_div(a.M, bm[t]) * (bm[t] / wm[t]);
+}
 
 int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
 {

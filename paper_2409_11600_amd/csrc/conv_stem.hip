@@ -293,14 +293,24 @@ bool stem_applicable(const ConvGeo &g)
 
 size_t stem_workspace_bytes(const ConvGeo &g, int pass) { return stem_plan(g, stem_geo(g), pass).total; }
 
-int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, hipStream_t st)
+int stem_stats_rows(const ConvGeo &g)
 {
+    (void)g;
+    return 0;
+}
+
+int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, float *stats, int stats_rows, void **y_nhwc,
+             hipStream_t st)
+{
+    (void)stats;
+    (void)stats_rows;
     const StemGeo s = stem_geo(g);
     const StemPlan p = stem_plan(g, s, NSK_PASS_FWD);
     const bool nchw = g.layout == NSK_NCHW;
     STEM_TRY(space_to_depth(g, s, x, ws + p.x2, st));
     STEM_TRY(pack_filter<0>(g, s, w, ws + p.w2, st));
     void *dst = nchw ? (void *)(ws + p.act) : y;
+    if (y_nhwc) *y_nhwc = dst;
     if (stem_halo_applicable(s.dtype, s.U, s.K, s.N, s.H2, s.W2)) {
         STEM_TRY(launch_stem_halo(0, ws + p.x2, ws + p.w2, dst, s.N, s.H2, s.W2, st));
         if (nchw) STEM_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));

@@ -173,6 +173,96 @@ int pool_geometry(const nsk_pool_desc_t *d, int *P, int *Q)
     return NSK_OK;
 }
 
+// Geometry part of the forward implicit-GEMM arguments (pointers, byte sizes and statistics are set by the caller).
+void fwd_geometry(const ConvGeo &g, IgemmArgs *a)
+{
+    a->Nimg = g.N; a->Hs = g.H; a->Ws = g.W; a->Cs = g.C;
+    a->Mi = g.P; a->Mj = g.Q; a->M = g.N * g.P * g.Q;
+    a->mult_h = g.sh; a->add_h = -g.ph; a->mult_w = g.sw; a->add_w = -g.pw;
+    a->ntaps = g.R * g.S; a->Ktot = a->ntaps * g.C;
+    a->Ngemm = g.K;
+    a->Ho = g.P; a->Wo = g.Q; a->Co = g.K; a->osh = 1; a->oa = 0; a->osw = 1; a->ob = 0;
+    a->accumulate = 0;
+    a->src_bytes = (unsigned)(g.x_elems * g.es);
+    a->wpk_bytes = (unsigned)(g.w_elems * g.es);
+    for (int r = 0; r < g.R; ++r)
+        for (int s = 0; s < g.S; ++s) {
+            a->off_h[r * g.S + s] = (short)(r * g.dh);
+            a->off_w[r * g.S + s] = (short)(s * g.dw);
+        }
+}
+
+// The output tensor of a convolution as a batch-norm descriptor of its NHWC form (what the kernels write).
+nsk_bn_desc_t output_as_bn(const ConvGeo &g)
+{
+    nsk_bn_desc_t d{};
+    d.N = g.N; d.C = g.K; d.H = g.P; d.W = g.Q;
+    d.dtype = g.dtype; d.layout = NSK_NHWC;
+    d.eps = 0.f; d.momentum = 0.f; d.relu = 0;
+    return d;
+}
+
+// Rows of partial sums nsk_conv2d_fwd_stats writes: those of the kernel's own epilogue where it has one (*fused),
+// else those of the separate reduction pass over the stored output.
+int conv_stats_rows(const ConvGeo &g, bool *fused = nullptr)
+{
+    int rows = 0;
+    if (stem_applicable(g)) {
+        rows = stem_stats_rows(g);
+    } else {
+        IgemmArgs a{};
+        fwd_geometry(g, &a);
+        rows = igemm_stats_rows(g.dtype, a);
+    }
+    if (fused) *fused = rows > 0;
+    return rows > 0 ? rows : bn_stats_rows(output_as_bn(g));
+}
+
+int conv_fwd_impl(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, float *stats, void *workspace,
+                  size_t workspace_bytes, void *stream)
+{
+    ConvGeo g;
+    NSK_TRY(conv_geometry(desc, &g, true));
+    if (!x || !w || !y) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(w) || misaligned(y)) return NSK_ERR_ALIGNMENT;
+    const ConvPlan p = plan_conv(g, NSK_PASS_FWD);
+    NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
+    hipStream_t st = (hipStream_t)stream;
+    char *ws = (char *)workspace;
+    bool fused = false;
+    const int rows = stats ? conv_stats_rows(g, &fused) : 0;
+    if (p.stem) {
+        void *y_nhwc = nullptr;
+        NSK_TRY(stem_fwd(g, x, w, y, ws, fused ? stats : nullptr, rows, &y_nhwc, st));
+        if (stats && !fused) NSK_TRY(launch_bn_stats(output_as_bn(g), y_nhwc, stats, st));
+        return NSK_OK;
+    }
+
+    const void *src = x, *filt = w;
+    void *dst = y;
+    if (g.layout == NSK_NCHW) {
+        NSK_TRY(launch_nchw_to_nhwc(g.dtype, x, ws + p.act_in, g.N, g.C, g.H, g.W, st));
+        int tap_off[kMaxTaps];
+        for (int t = 0; t < g.R * g.S; ++t) tap_off[t] = t;
+        NSK_TRY(launch_pack_filter(g.dtype, w, ws + p.filt, g.K, g.R * g.S, g.C, (long)g.C * g.R * g.S,
+                                   (long)g.R * g.S, tap_off, st));
+        src = ws + p.act_in;
+        filt = ws + p.filt;
+        dst = ws + p.act_out;
+    }
+    IgemmArgs a{};
+    fwd_geometry(g, &a);
+    a.src = src; a.wpk = filt; a.out = dst;
+    if (fused) {
+        a.stats = stats;
+        a.stats_rows = rows;
+    }
+    NSK_TRY(launch_igemm(g.dtype, a, st));
+    if (stats && !fused) NSK_TRY(launch_bn_stats(output_as_bn(g), dst, stats, st));
+    if (g.layout == NSK_NCHW) NSK_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));
+    return NSK_OK;
+}
+
 }  // namespace
 }  // namespace nsk
 
@@ -219,47 +309,22 @@ size_t nsk_conv2d_workspace_bytes(const nsk_conv_desc_t *desc, int pass)
 int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, void *workspace,
                    size_t workspace_bytes, void *stream)
 {
-    ConvGeo g;
-    NSK_TRY(conv_geometry(desc, &g, true));
-    if (!x || !w || !y) return NSK_ERR_NULL;
-    if (misaligned(x) || misaligned(w) || misaligned(y)) return NSK_ERR_ALIGNMENT;
-    const ConvPlan p = plan_conv(g, NSK_PASS_FWD);
-    NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
-    hipStream_t st = (hipStream_t)stream;
-    char *ws = (char *)workspace;
-    if (p.stem) return stem_fwd(g, x, w, y, ws, st);
+    return conv_fwd_impl(desc, x, w, y, nullptr, workspace, workspace_bytes, stream);
+}
 
-    const void *src = x, *filt = w;
-    void *dst = y;
-    if (g.layout == NSK_NCHW) {
-        NSK_TRY(launch_nchw_to_nhwc(g.dtype, x, ws + p.act_in, g.N, g.C, g.H, g.W, st));
-        int tap_off[kMaxTaps];
-        for (int t = 0; t < g.R * g.S; ++t) tap_off[t] = t;
-        NSK_TRY(launch_pack_filter(g.dtype, w, ws + p.filt, g.K, g.R * g.S, g.C, (long)g.C * g.R * g.S,
-                                   (long)g.R * g.S, tap_off, st));
-        src = ws + p.act_in;
-        filt = ws + p.filt;
-        dst = ws + p.act_out;
-    }
-    IgemmArgs a{};
-    a.src = src; a.wpk = filt; a.out = dst;
-    a.Nimg = g.N; a.Hs = g.H; a.Ws = g.W; a.Cs = g.C;
-    a.Mi = g.P; a.Mj = g.Q; a.M = g.N * g.P * g.Q;
-    a.mult_h = g.sh; a.add_h = -g.ph; a.mult_w = g.sw; a.add_w = -g.pw;
-    a.ntaps = g.R * g.S; a.Ktot = a.ntaps * g.C;
-    a.Ngemm = g.K;
-    a.Ho = g.P; a.Wo = g.Q; a.Co = g.K; a.osh = 1; a.oa = 0; a.osw = 1; a.ob = 0;
-    a.accumulate = 0;
-    a.src_bytes = (unsigned)(g.x_elems * g.es);
-    a.wpk_bytes = (unsigned)(g.w_elems * g.es);
-    for (int r = 0; r < g.R; ++r)
-        for (int s = 0; s < g.S; ++s) {
-            a.off_h[r * g.S + s] = (short)(r * g.dh);
-            a.off_w[r * g.S + s] = (short)(s * g.dw);
-        }
-    NSK_TRY(launch_igemm(g.dtype, a, st));
-    if (g.layout == NSK_NCHW) NSK_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));
-    return NSK_OK;
+int nsk_conv2d_stats_rows(const nsk_conv_desc_t *desc)
+{
+    ConvGeo g;
+    if (conv_geometry(desc, &g, true) != NSK_OK) return 0;
+    return conv_stats_rows(g);
+}
+
+int nsk_conv2d_fwd_stats(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, float *stats,
+                         void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!stats) return NSK_ERR_NULL;
+    if (misaligned(stats)) return NSK_ERR_ALIGNMENT;
+    return conv_fwd_impl(desc, x, w, y, stats, workspace, workspace_bytes, stream);
 }
 
 int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w, void *dx, int accumulate,
@@ -402,7 +467,7 @@ int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *re
         return NSK_ERR_ALIGNMENT;
     NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
     return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
-                         workspace, nullptr, (hipStream_t)stream);
+                         workspace, nullptr, nullptr, 0, (hipStream_t)stream);
 }
 
 int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *out, const void *dout,
@@ -443,7 +508,26 @@ int nsk_bn_relu_add_fwd_mask(const nsk_bn_desc_t *desc, const void *x, const voi
         return NSK_ERR_ALIGNMENT;
     NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
     return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
-                         workspace, relu_mask, (hipStream_t)stream);
+                         workspace, relu_mask, nullptr, 0, (hipStream_t)stream);
+}
+
+int nsk_bn_relu_add_fwd_stats(const nsk_bn_desc_t *desc, const void *x, const void *residual, const float *gamma,
+                              const float *beta, void *out, unsigned char *relu_mask, float *save_mean,
+                              float *save_invstd, float *running_mean, float *running_var, const float *stats,
+                              int stats_rows, void *workspace, size_t workspace_bytes, void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (!x || !gamma || !beta || !out || !save_mean || !save_invstd || !stats) return NSK_ERR_NULL;
+    if (stats_rows < 1) return NSK_ERR_BAD_DESC;
+    if (relu_mask && bn_mask_bytes(*desc) == 0) return NSK_ERR_UNSUPPORTED;
+    if ((running_mean == nullptr) != (running_var == nullptr)) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(residual) || misaligned(out) || misaligned(relu_mask) || misaligned(gamma) ||
+        misaligned(beta) || misaligned(save_mean) || misaligned(save_invstd) || misaligned(running_mean) ||
+        misaligned(running_var) || misaligned(stats))
+        return NSK_ERR_ALIGNMENT;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
+    return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
+                         workspace, relu_mask, stats, stats_rows, (hipStream_t)stream);
 }
 
 int nsk_bn_relu_add_bwd_mask(const nsk_bn_desc_t *desc, const void *x, const unsigned char *relu_mask, const void *dout,

@@ -73,16 +73,25 @@ struct IgemmArgs {
     int accumulate;
     int vec_out;  // set by launch_igemm: output rows are 16-byte granular, vector epilogue
     unsigned src_bytes, wpk_bytes;  // sizes of src and wpk (both below 4 GiB: buffer addressing)
+    // Optional per-channel partial sums of the STORED output for a following batch-norm: stats[0][r][n] = sum and
+    // stats[1][r][n] = sum of squares over the r-th disjoint share of the rows, r < stats_rows.  Only set when
+    // igemm_stats_rows() named the row count for exactly this launch.
+    float *stats;
+    int stats_rows;
     short off_h[kMaxTaps];
     short off_w[kMaxTaps];
 };
 int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream);
+// Rows of partial sums the kernel launch_igemm would pick writes from its epilogue; 0 if that kernel has no
+// statistics epilogue (the caller then runs a separate reduction pass).  Host only, depends on the shape alone.
+int igemm_stats_rows(int dtype, const IgemmArgs &a);
 // bf16 large-tile kernel for wide layers (channel counts that are multiples of 64, enough tiles to fill the chip)
 bool igemm_big_applicable(int dtype, const IgemmArgs &a);
 int launch_igemm_big(const IgemmArgs &a, hipStream_t stream);
 // bf16 3x3 stride-1 64->64 special case (filter resident in LDS, input tile staged once with halo)
 bool halo64_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64(const IgemmArgs &a, hipStream_t stream);
+int halo64_stats_rows(const IgemmArgs &a);
 // fp32 sibling (filter streamed one tap at a time through LDS)
 bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);
@@ -123,7 +132,11 @@ int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int nta
 // stem_workspace_bytes(g, pass) bytes.
 bool stem_applicable(const ConvGeo &g);
 size_t stem_workspace_bytes(const ConvGeo &g, int pass);
-int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, hipStream_t stream);
+// stats / stats_rows: as in IgemmArgs (nullptr: none); *y_nhwc receives the NHWC result (y itself, or its workspace
+// copy for NCHW descriptors)
+int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, float *stats, int stats_rows,
+             void **y_nhwc, hipStream_t stream);
+int stem_stats_rows(const ConvGeo &g);
 int stem_dgrad(const ConvGeo &g, const void *dy, const void *w, void *dx, int accumulate, char *ws, hipStream_t stream);
 int stem_wgrad(const ConvGeo &g, const void *x, const void *dy, float *dw, int accumulate, char *ws, hipStream_t stream);
 
@@ -151,7 +164,10 @@ int bn_partial_blocks(const nsk_bn_desc_t &d);
 size_t bn_mask_bytes(const nsk_bn_desc_t &d);
 int launch_bn_fwd(const nsk_bn_desc_t &d, const void *x, const void *residual, const float *gamma,
                   const float *beta, void *out, float *save_mean, float *save_invstd,
-                  float *running_mean, float *running_var, void *ws, unsigned char *relu_mask, hipStream_t stream);
+                  float *running_mean, float *running_var, void *ws, unsigned char *relu_mask, const float *stats,
+                  int stats_rows, hipStream_t stream);
+int bn_stats_rows(const nsk_bn_desc_t &d);
+int launch_bn_stats(const nsk_bn_desc_t &d, const void *x, float *stats, hipStream_t stream);
 int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout,
                   const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
                   void *dres, float *dgamma, float *dbeta, void *ws, const unsigned char *relu_mask,

@@ -171,6 +171,62 @@ def test_conv_is_bitwise_reproducible(dtype):
 
 
 # N, C, H, W
+# Shapes for the convolution + batch-norm statistics hand-over: one per kernel family with a statistics epilogue,
+# plus shapes that take the separate reduction pass.
+STATS_SHAPES = [
+    ("bf16", (3, 64, 20, 24, 64, 3, 3, 1, 1, 1)),      # bf16 3x3 64->64 (two-group halo kernel), several tiles per block
+    ("f32", (2, 64, 16, 32, 64, 3, 3, 1, 1, 1)),       # fp32 row-aligned halo kernel
+    ("bf16", (2, 128, 9, 9, 256, 1, 1, 1, 0, 1)),      # generic kernel, 128x128 tiles
+    ("bf16", (2, 32, 16, 16, 64, 3, 3, 2, 1, 1)),      # generic kernel, 128x64 tiles, stride 2
+    ("f32", (2, 16, 15, 15, 32, 1, 1, 2, 0, 1)),       # generic kernel, fp32, 256x32 tiles, ragged
+    ("bf16", (2, 3, 20, 24, 64, 7, 7, 2, 3, 1)),       # image stem (space-to-depth + halo kernel)
+    ("bf16", (1, 5, 9, 9, 7, 3, 3, 3, 1, 1)),          # scalar epilogue: separate reduction pass
+    ("f32", (2, 3, 30, 30, 16, 3, 3, 1, 1, 1)),        # 3-channel stem on the generic path
+]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("big", [False, True])
+@pytest.mark.parametrize("i", range(len(STATS_SHAPES)))
+def test_conv_statistics_feed_the_batch_norm(i, big, layout, monkeypatch):
+    """nsk_conv2d_fwd_stats leaves per-channel partial sums of its stored output; nsk_bn_relu_add_fwd_stats takes its
+    batch statistics from them.  y must equal the plain forward bit for bit, the partial sums must add up to the
+    sums of the stored y, and the batch-norm results must agree with the plain call (which reads y once more) and
+    with the oracle."""
+    dtype, (N, C, H, W, K, R, S, st, pd, dl) = STATS_SHAPES[i]
+    if big:
+        if dtype != "bf16" or C % 64 or K % 64:
+            pytest.skip("the large-tile kernel takes bf16 layers with channel counts that are multiples of 64")
+        monkeypatch.setenv("NSK_BIG_MIN_TILES", "1")
+    print(f"stats case {STATS_SHAPES[i]} big={big} layout={layout}", flush=True)
+    x = on_grid(gen.normal(900 + i, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(900 + i, 1, (K, C, R, S)), dtype)
+    g = (1.0 + 0.3 * gen.normal(900 + i, 3, (K,))).astype(np.float32)
+    b = (0.2 * gen.normal(900 + i, 4, (K,))).astype(np.float32)
+    ws = B.Workspace()
+    gx, gw = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout)
+    gg, gb = torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda()
+    y0 = B.conv2d_fwd(gx, gw, st, pd, dl, layout, ws=ws)
+    y1, stats = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    yh = to_host(y1, layout)                                   # NCHW float64 of the stored values
+    sums = stats.double().sum(dim=1).cpu().numpy()             # [2, K]
+    want0, want1 = yh.sum(axis=(0, 2, 3)), (yh * yh).sum(axis=(0, 2, 3))
+    scale0 = np.sqrt(want1 * yh[:, 0].size) + 1e-30            # sum of n terms of rms r: compare on the scale n*r... sqrt(n*sum sq)
+    assert np.max(np.abs(sums[0] - want0) / scale0) <= 1e-6
+    assert np.max(np.abs(sums[1] - want1) / (want1 + 1e-30)) <= 1e-5
+    out0, mean0, inv0 = B.bn_relu_add_fwd(y1, gg, gb, None, 1e-5, True, layout, ws=ws)
+    out1, mean1, inv1 = B.bn_relu_add_fwd(y1, gg, gb, None, 1e-5, True, layout, ws=ws, stats=stats)
+    torch.cuda.synchronize()
+    assert max_rel_err(mean1.cpu().numpy(), mean0.cpu().numpy()) <= 1e-5
+    assert max_rel_err(inv1.cpu().numpy(), inv0.cpu().numpy()) <= 1e-5
+    want_out, want_mean, want_inv = oracle.bn_relu_add_fwd(yh, g, b, None, 1e-5, True)
+    assert max_rel_err(mean1.cpu().numpy(), want_mean) <= 1e-5
+    assert max_rel_err(inv1.cpu().numpy(), want_inv) <= 1e-5
+    assert max_rel_err(to_host(out1, layout), want_out) <= TOL[dtype]
+
+
 BN_SHAPES = [(4, 64, 9, 11), (3, 16, 16, 16), (2, 256, 7, 7), (2, 1024, 5, 5), (5, 24, 6, 7), (2, 3, 10, 10),
              (3, 40, 33, 17)]
 
