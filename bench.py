@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="issue every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--no-fusion", action="store_true",
+                    help="plain entry points only: no statistics hand-over from convolution to batch-norm, no ReLU mask")
     ap.add_argument("--overlap", action="store_true",
                     help="issue the backward-weight calls on a second stream (measured: no gain on MI355X, the "
                          "convolution kernels already hold every CU)")
@@ -150,7 +152,7 @@ def call_cost(net, f, args):
             byts = (2 + res + 1) * e * es          # stats read + apply read (+ residual) + write
         else:
             byts = (6 if d.relu else 4) * e * es + (1 + res) * e * es   # two passes over x,(out),dout + writes
-        return name[len("nsk_"):].replace("_mask", ""), 0.0, byts
+        return name[len("nsk_"):].replace("_mask", "").replace("_stats", ""), 0.0, byts
     if name.startswith("nsk_maxpool"):
         e_in = d.N * d.C * d.H * d.W
         e_out = e_in // 4
@@ -195,7 +197,7 @@ def main():
     wl = gen.workload(a.config, batch=a.batch, stage=a.stage)
     tensors = gen.workload_tensors(wl)
     layout = B.NSK_NHWC if a.layout == "nhwc" else B.NSK_NCHW
-    net = GpuNetwork(wl, tensors, layout=layout)
+    net = GpuNetwork(wl, tensors, layout=layout, use_relu_mask=not a.no_fusion, use_fused_stats=not a.no_fusion)
     batch = wl["input"][0]
     calls = net.fwd_calls + net.bwd_calls
     costs = [call_cost(net, f, args) for f, args in calls]
@@ -254,7 +256,7 @@ def main():
         # ---- timed region B: same steps issued call by call with events around the dominant kernel.
         # A forward call launches exactly that kernel; a backward-data call also packs the filter
         # first, so when both are in the group only the forward launches are bracketed.
-        fwd_only = [i for i in dom_idx if calls[i][0].__name__ == "nsk_conv2d_fwd"]
+        fwd_only = [i for i in dom_idx if calls[i][0].__name__.startswith("nsk_conv2d_fwd")]
         timed_idx = fwd_only or dom_idx
         rec = {i: [] for i in timed_idx}
         for _ in range(a.steps):
@@ -292,7 +294,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl["dtype"] == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{wl['name']}: {len(wl['units'])} units, input {list(wl['input'])}, "
-                               f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None,
+                               f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None, "fused_bn_statistics": not a.no_fusion,
                    "streams": 1 if side is None else 2},
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12,
         "conv_frac_of_mfma_peak": conv_flops / (conv_ms * 1e-3) / PEAK["mfma_bf16" if wl["dtype"] == "bf16" else "mfma_f32"],

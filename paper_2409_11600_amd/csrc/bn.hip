@@ -291,6 +291,29 @@ __global__ __launch_bounds__(256) void bn_bwd_apply_generic(const T *__restrict_
     }
 }
 
+// Folds many rows of partial sums into few: out[j][c] = sum of in[r][c] over the j-th run of `run` rows, for the
+// two arrays (sums, sums of squares) that follow each other in both buffers.  Fixed order: reproducible.
+__global__ __launch_bounds__(256) void bn_stats_fold(const float *__restrict__ in, int R, int C, int run,
+                                                     float *__restrict__ out, int R2)
+{
+    const int j = blockIdx.x;
+    const int r0 = j * run, r1 = min(R, r0 + run);
+    for (int c = threadIdx.x; c < 2 * C; c += 256) {
+        const int arr = c / C, cc = c - arr * C;
+        const float *p = in + (size_t)arr * R * C + cc;
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int r = r0;
+        for (; r + 3 < r1; r += 4) {
+            s0 += p[(size_t)r * C];
+            s1 += p[(size_t)(r + 1) * C];
+            s2 += p[(size_t)(r + 2) * C];
+            s3 += p[(size_t)(r + 3) * C];
+        }
+        for (; r < r1; ++r) s0 += p[(size_t)r * C];
+        out[(size_t)arr * R2 * C + (size_t)j * C + cc] = (s0 + s1) + (s2 + s3);
+    }
+}
+
 // ----------------------------------------------------------------------------- finalize (tiny)
 template <typename T>
 __global__ void bn_fwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
@@ -417,10 +440,21 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
     float *p0 = ws, *p1 = ws + (long)g.G * d.C, *scale = p1 + (long)g.G * d.C, *bias = scale + d.C;
     constexpr int VEC = BT<T>::VEC;
     if (stats) {
-        // partial sums of x and x^2 left by the producer of x ([2][stats_rows][C], not shifted): no reduction pass
-        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, stats,
-                           stats + (long)stats_rows * d.C, stats_rows, d.C, (double)g.M, (const T *)nullptr, 0L, gamma, beta,
-                           d.eps, d.momentum, save_mean, save_invstd, running_mean, running_var, scale, bias);
+        // partial sums of x and x^2 left by the producer of x ([2][stats_rows][C], not shifted): no reduction pass.
+        // A producer with small tiles leaves tens of thousands of rows: those are first folded into at most G rows
+        // (the finalize kernel has one wavefront per channel).
+        const float *q0 = stats, *q1 = stats + (long)stats_rows * d.C;
+        int rows = stats_rows;
+        if (stats_rows > 1024 && stats_rows > g.G) {
+            const int run = ceil_div(stats_rows, g.G), r2 = ceil_div(stats_rows, run);
+            hipLaunchKernelGGL(bn_stats_fold, dim3(r2), dim3(256), 0, stream, stats, stats_rows, d.C, run, p0, r2);
+            q0 = p0;
+            q1 = p0 + (long)r2 * d.C;
+            rows = r2;
+        }
+        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, q0, q1, rows, d.C,
+                           (double)g.M, (const T *)nullptr, 0L, gamma, beta, d.eps, d.momentum, save_mean, save_invstd,
+                           running_mean, running_var, scale, bias);
     } else if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 0>), dim3(g.G), dim3(256), 0, stream, x, (const T *)nullptr,
                            (const T *)nullptr, (const float *)nullptr, (const float *)nullptr, 0, g.M, d.C,

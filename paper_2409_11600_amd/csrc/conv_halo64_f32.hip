@@ -26,7 +26,6 @@
 namespace nsk {
 namespace {
 
-constexpr int FT = 256;            // positions per tile
 constexpr int F_W = 32;            // image width this kernel takes
 constexpr int F_MAX_IN = 352;      // 10 rows of W+2 = 340 staged positions, rounded up to a multiple of 16
 constexpr int F_ROW = 272;         // bytes per staged position / filter row (64 floats + 16 pad)
@@ -42,6 +41,8 @@ struct HaloF32Args {
     unsigned long long magic_pi, magic_pw;
     unsigned src_bytes, wpk_bytes;
     int tapoff[9];
+    float *stats;      // forward only: per-channel partial sums of the stored output, or nullptr
+    int stats_rows;    // 4 rows per block (one per wavefront)
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -109,6 +110,9 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
         }
     };
 
+    // statistics epilogue (forward): a lane reads back the same 4 channels of every staged row and adds them up over
+    // all the positions it stores during the life of the block; each wavefront leaves one row of partial sums
+    float ssum[4] = {0.f, 0.f, 0.f, 0.f}, ssq[4] = {0.f, 0.f, 0.f, 0.f};
     int tile = blockIdx.x;
     int wb = 0;   // LDS buffer holding the tap about to be multiplied
     if (tile < a.tiles) {
@@ -217,9 +221,35 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
                 const u32x4 v = *(const u32x4 *)(my_st + pos * F_ROW + ck * 16);
                 const unsigned off = out_tab[wave * 64 + mi * 32 + pos];
                 __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, off == F_OOB ? F_OOB : off + (unsigned)(ck * 16), 0, 0);
+                if (!ACCUM && a.stats && off != F_OOB) {
+                    const f32x4 vf = __builtin_bit_cast(f32x4, v);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        ssum[e] += vf[e];
+                        ssq[e] += vf[e] * vf[e];
+                    }
+                }
             }
         }
         __syncthreads();
+    }
+    if (!ACCUM && a.stats) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int o = 16; o < 64; o <<= 1) {
+                ssum[e] += __shfl_xor(ssum[e], o, 64);
+                ssq[e] += __shfl_xor(ssq[e], o, 64);
+            }
+        if (lane < 16) {
+            float *r0 = a.stats + (size_t)(blockIdx.x * 4 + wave) * 64 + lane * 4;
+            float *r1 = r0 + (size_t)a.stats_rows * 64;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                r0[e] = ssum[e];
+                r1[e] = ssq[e];
+            }
+        }
     }
 }
 
@@ -242,6 +272,18 @@ bool halo64_f32_applicable(int dtype, const IgemmArgs &a)
     if ((unsigned long long)a.src_bytes >= F_OOB) return false;
     if (((uintptr_t)a.src | (uintptr_t)a.wpk | (uintptr_t)a.out) & 15) return false;
     return true;
+}
+
+namespace {
+constexpr int kStatsGridF32 = 256;   // block count when statistics are requested (independent of the device)
+}
+
+// Rows of partial sums the forward launch writes (4 per block).
+int halo64_f32_stats_rows(const IgemmArgs &g)
+{
+    if (g.accumulate) return 0;
+    const int tiles = g.Nimg * (g.Hs / 8);
+    return (tiles < kStatsGridF32 ? tiles : kStatsGridF32) * 4;
 }
 
 int launch_halo64_f32(const IgemmArgs &g, hipStream_t stream)
@@ -276,7 +318,11 @@ int launch_halo64_f32(const IgemmArgs &g, hipStream_t stream)
         }
         attr_set = true;
     }
-    const int grid = a.tiles < cus ? a.tiles : cus;
+    const int want = g.stats ? kStatsGridF32 : cus;
+    const int grid = a.tiles < want ? a.tiles : want;
+    if (g.stats && g.stats_rows != grid * 4) return NSK_ERR_BAD_DESC;   // the planner and the launch disagree
+    a.stats = g.stats;
+    a.stats_rows = g.stats_rows;
     if (g.accumulate)
         hipLaunchKernelGGL(conv_halo64_f32_kernel<true>, dim3(grid), dim3(256), kSmemF32, stream, a);
     else

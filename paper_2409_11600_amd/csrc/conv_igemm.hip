@@ -419,11 +419,14 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     if (a.M <= 0 || a.Ngemm <= 0 || a.accumulate) return 0;
     if (forced_tile() != 0) return 0;
     if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
-    if (halo64_f32_applicable(dtype, a)) return 0;
-    if (igemm_big_applicable(dtype, a)) return 0;
-    // generic kernel: needs the vector epilogue; one row per wavefront row of every row block
+    if (halo64_f32_applicable(dtype, a)) return halo64_f32_stats_rows(a);
+    if (igemm_big_applicable(dtype, a)) return igemm_big_stats_rows(a);
+    // generic kernel: needs the vector epilogue; one row per wavefront row of every row block.  Measured: with a
+    // short reduction the per-block cross-lane sums and the many rows of partial sums cost more than the separate
+    // statistics pass they replace (config 5 stage A: +45 us on a 140 us layer), so only long reductions use it.
     const int vec = dtype == NSK_BF16 ? 8 : 4;
     if (!(a.Ngemm % vec == 0 && a.Co % vec == 0 && (uintptr_t)a.out % 16 == 0)) return 0;
+    if (a.Ktot < 1024 && getenv("NSK_STATS_ALWAYS") == nullptr) return 0;   // the variable is a test hook
     static const int bm[3] = {256, 128, 128}, wm[3] = {64, 32, 64};
     const int t = auto_tile(a, dtype == NSK_BF16 ? 2 : 4);
     return ceil_div(a.M, bm[t]) * (bm[t] / wm[t]);

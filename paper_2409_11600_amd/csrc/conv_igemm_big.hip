@@ -257,6 +257,13 @@ __global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const
     // and store 16 contiguous bytes per lane.
     constexpr int SROW = 80;   // 32 channels bf16 + 16 pad
     unsigned char *my_st = smem + cw * (32 * SROW);
+    // statistics epilogue (forward with a batch-norm behind it): a lane reads back the same 8 channels of every staged
+    // row, adds them up over the rows it stores, and the wavefront leaves one row of partial sums
+    float ssum[FN][8], ssq[FN][8];
+#pragma unroll
+    for (int ni = 0; ni < FN; ++ni)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ssum[ni][e] = ssq[ni][e] = 0.f;
 #pragma unroll
     for (int mi = 0; mi < FM; ++mi)
 #pragma unroll
@@ -274,9 +281,42 @@ __global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const
                 const u32x4 v = *(const u32x4 *)(my_st + pos * SROW + ck * 16);
                 const unsigned off = out_tab[wm * WM + mi * 32 + pos];
                 const int col = wcol0 + ni * 32 + ck * 8;
-                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, col < a.Ngemm ? off + (unsigned)(col * 2) : GB_OOB, 0, 0);
+                const bool live = col < a.Ngemm && off != GB_OOB;
+                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, live ? off + (unsigned)(col * 2) : GB_OOB, 0, 0);
+                if (a.stats && live) {
+                    const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const float f = (float)vb[e];
+                        ssum[ni][e] += f;
+                        ssq[ni][e] += f * f;
+                    }
+                }
             }
         }
+    if (a.stats) {
+        const int row = mt * (GB_BM / WM) + wm, ck = lane & 3;
+#pragma unroll
+        for (int ni = 0; ni < FN; ++ni) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int o = 4; o < 64; o <<= 1) {
+                    ssum[ni][e] += __shfl_xor(ssum[ni][e], o, 64);
+                    ssq[ni][e] += __shfl_xor(ssq[ni][e], o, 64);
+                }
+            const int col = wcol0 + ni * 32 + ck * 8;
+            if (lane < 4 && col < a.Ngemm) {
+                float *r0 = a.stats + (size_t)row * a.Ngemm + col;
+                float *r1 = r0 + (size_t)a.stats_rows * a.Ngemm;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    r0[e] = ssum[ni][e];
+                    r1[e] = ssq[ni][e];
+                }
+            }
+        }
+    }
 }
 
 template <int BN> int smem_bytes() { return 2 * (GB_BM + BN) * GB_ROW + 256 * 4; }
@@ -300,6 +340,13 @@ bool igemm_big_applicable(int dtype, const IgemmArgs &a)
     const char *e = getenv("NSK_BIG_MIN_TILES");
     if (e) return tiles >= atoll(e);
     return tiles >= 160 && a.Ngemm >= 128 && a.Ktot >= 8 * GB_BK;
+}
+
+// Rows of partial sums the forward launch writes: one per multiplying wavefront row of every row block.
+int igemm_big_stats_rows(const IgemmArgs &a)
+{
+    const int wm = a.Ngemm >= 128 ? 128 : 64;
+    return ceil_div(a.M, GB_BM) * (GB_BM / wm);
 }
 
 int launch_igemm_big(const IgemmArgs &a, hipStream_t stream)

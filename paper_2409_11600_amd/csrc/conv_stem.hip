@@ -295,15 +295,14 @@ size_t stem_workspace_bytes(const ConvGeo &g, int pass) { return stem_plan(g, st
 
 int stem_stats_rows(const ConvGeo &g)
 {
-    (void)g;
-    return 0;
+    const StemGeo s = stem_geo(g);
+    return stem_halo_applicable(s.dtype, s.U, s.K, s.N, s.H2, s.W2) ? stem_halo_stats_rows(s.N, s.H2, s.W2) : 0;
 }
 
 int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, float *stats, int stats_rows, void **y_nhwc,
              hipStream_t st)
 {
-    (void)stats;
-    (void)stats_rows;
+
     const StemGeo s = stem_geo(g);
     const StemPlan p = stem_plan(g, s, NSK_PASS_FWD);
     const bool nchw = g.layout == NSK_NCHW;
@@ -312,7 +311,7 @@ int stem_fwd(const ConvGeo &g, const void *x, const void *w, void *y, char *ws, 
     void *dst = nchw ? (void *)(ws + p.act) : y;
     if (y_nhwc) *y_nhwc = dst;
     if (stem_halo_applicable(s.dtype, s.U, s.K, s.N, s.H2, s.W2)) {
-        STEM_TRY(launch_stem_halo(0, ws + p.x2, ws + p.w2, dst, s.N, s.H2, s.W2, st));
+        STEM_TRY(launch_stem_halo(0, ws + p.x2, ws + p.w2, dst, s.N, s.H2, s.W2, stats, stats_rows, st));
         if (nchw) STEM_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));
         return NSK_OK;
     }
@@ -348,7 +347,7 @@ int stem_dgrad(const ConvGeo &g, const void *dy, const void *w, void *dx, int ac
     STEM_TRY(pack_filter<1>(g, s, w, ws + p.w2, st));
     // dx2[n,i,j,e] = sum_{u,v,k} dy[n, i-u, j-v, k] * w2[k][u,v][e]
     if (stem_halo_applicable(s.dtype, s.U, s.K, s.N, s.H2, s.W2)) {
-        STEM_TRY(launch_stem_halo(1, src, ws + p.w2, ws + p.dx2, s.N, s.H2, s.W2, st));
+        STEM_TRY(launch_stem_halo(1, src, ws + p.w2, ws + p.dx2, s.N, s.H2, s.W2, nullptr, 0, st));
         return s.dtype == NSK_BF16 ? d2s_typed<bf16_t>(g, s, ws + p.dx2, dx, accumulate, st)
                                    : d2s_typed<float>(g, s, ws + p.dx2, dx, accumulate, st);
     }

@@ -35,6 +35,8 @@ struct StemHaloArgs {
     unsigned long long magic_pi, magic_pw;   // ceil(2^40 / d)
     unsigned src_bytes, out_bytes;
     int tapoff[16];                    // shift of each tap in flat padded positions
+    float *stats;                      // forward only: per-channel partial sums of the stored output, or nullptr
+    int stats_rows;                    // 4 rows per block (one per wavefront)
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -118,10 +120,37 @@ __global__ __launch_bounds__(256) void stem_halo_kernel(const StemHaloArgs a)
         for (int u = 0; u < PASSES; ++u) stage[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, off[u], 0, 0);
     };
 
+    // Statistics epilogue (forward): a lane reads back the same 8 channels of every staged row; it adds them up over
+    // all the positions it stores during the life of the block, and each wavefront leaves one row of partial sums.
+    float ssum[8], ssq[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ssum[e] = ssq[e] = 0.f;
+    auto write_stats = [&]() {
+        if (OC != 64 || !a.stats) return;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int o = 8; o < 64; o <<= 1) {
+                ssum[e] += __shfl_xor(ssum[e], o, 64);
+                ssq[e] += __shfl_xor(ssq[e], o, 64);
+            }
+        if (lane < 8) {
+            float *r0 = a.stats + (size_t)(blockIdx.x * 4 + wave) * 64 + lane * 8;
+            float *r1 = r0 + (size_t)a.stats_rows * 64;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                r0[e] = ssum[e];
+                r1[e] = ssq[e];
+            }
+        }
+    };
     const int tiles_per_block = (a.tiles + (int)gridDim.x - 1) / (int)gridDim.x;
     const int t_begin = blockIdx.x * tiles_per_block;
     const int t_end = min(a.tiles, t_begin + tiles_per_block);
-    if (t_begin >= t_end) return;   // uniform for the block
+    if (t_begin >= t_end) {   // uniform for the block
+        write_stats();        // zeros: every row of the buffer is written
+        return;
+    }
     fill_in_tab(t_begin, true);
     __syncthreads();                // in_tab and the filter
     issue_tile();
@@ -201,11 +230,21 @@ __global__ __launch_bounds__(256) void stem_halo_kernel(const StemHaloArgs a)
                     const unsigned px = out_tab[wave * 64 + mi * 32 + pos];
                     const unsigned o = px == SH_OOB ? SH_OOB : px * (unsigned)OUT_B + (unsigned)(ck * 16);
                     __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, o, 0, 0);
+                    if (OC == 64 && a.stats && px != SH_OOB) {
+                        const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const float f = (float)vb[e];
+                            ssum[e] += f;
+                            ssq[e] += f * f;
+                        }
+                    }
                 }
             }
         }
         lds_barrier();   // strips and out_tab are free again
     }
+    write_stats();
 }
 
 template <int CPP, int NT, int OC> constexpr int stem_halo_smem()
@@ -230,7 +269,19 @@ bool stem_halo_applicable(int dtype, int U, int K, int Nimg, int H, int W)
 // backward = 0: src = x2 [Nimg][H][W][16], wpk = w2 [64][16 taps][16], out = y [Nimg][H][W][64]
 // backward = 1: src = dy [Nimg][H][W][64], wpk = w2 [16][16 taps][64], out = dx2 [Nimg][H][W][16]
 // umin = -2: the taps are u, v in [-2, 1]; the backward pass reads dy at pos - (u, v).
-int launch_stem_halo(int backward, const void *src, const void *wpk, void *out, int Nimg, int H, int W, hipStream_t stream)
+namespace {
+constexpr int kStemStatsGrid = 512;   // block count when statistics are requested (independent of the device)
+}
+
+// Rows of partial sums the forward launch writes (4 per block).
+int stem_halo_stats_rows(int Nimg, int H, int W)
+{
+    const int tiles = ceil_div((H + 3) * (W + 3) * Nimg, SH_T);
+    return (tiles < kStemStatsGrid ? tiles : kStemStatsGrid) * 4;
+}
+
+int launch_stem_halo(int backward, const void *src, const void *wpk, void *out, int Nimg, int H, int W, float *stats,
+                     int stats_rows, hipStream_t stream)
 {
     StemHaloArgs a{};
     a.src = src; a.wpk = wpk; a.out = out;
@@ -271,8 +322,11 @@ int launch_stem_halo(int backward, const void *src, const void *wpk, void *out, 
         attr_set = true;
     }
     // two blocks per CU in the forward pass (65 KB of LDS each): one block's epilogue overlaps the other's MFMAs
-    const int want = backward ? cus : 2 * cus;
+    const int want = backward ? cus : (stats ? kStemStatsGrid : 2 * cus);
     const int grid = a.tiles < want ? a.tiles : want;
+    if (stats && (backward || stats_rows != grid * 4)) return NSK_ERR_BAD_DESC;   // the planner and the launch disagree
+    a.stats = stats;
+    a.stats_rows = stats_rows;
     const int smem_b = stem_halo_smem<8, 1, 16>(), smem_f = stem_halo_smem<2, 2, 64>();
     if (backward)
         hipLaunchKernelGGL((stem_halo_kernel<8, 1, 16>), dim3(grid), dim3(256), smem_b, stream, a);

@@ -88,6 +88,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a);
 // bf16 large-tile kernel for wide layers (channel counts that are multiples of 64, enough tiles to fill the chip)
 bool igemm_big_applicable(int dtype, const IgemmArgs &a);
 int launch_igemm_big(const IgemmArgs &a, hipStream_t stream);
+int igemm_big_stats_rows(const IgemmArgs &a);
 // bf16 3x3 stride-1 64->64 special case (filter resident in LDS, input tile staged once with halo)
 bool halo64_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64(const IgemmArgs &a, hipStream_t stream);
@@ -95,6 +96,7 @@ int halo64_stats_rows(const IgemmArgs &a);
 // fp32 sibling (filter streamed one tap at a time through LDS)
 bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);
+int halo64_f32_stats_rows(const IgemmArgs &a);
 
 // ------------------------------------------------------------------ wgrad
 // part[split][k][t][c] = sum over the split's share of rows l = (img, p, q) of
@@ -142,7 +144,9 @@ int stem_wgrad(const ConvGeo &g, const void *x, const void *dy, float *dw, int a
 
 // 7x7 stem (4x4 coarse taps), bf16, 64 output channels: forward / backward-data on the space-to-depth grid
 bool stem_halo_applicable(int dtype, int U, int K, int Nimg, int H, int W);
-int launch_stem_halo(int backward, const void *src, const void *wpk, void *out, int Nimg, int H, int W, hipStream_t stream);
+int launch_stem_halo(int backward, const void *src, const void *wpk, void *out, int Nimg, int H, int W, float *stats,
+                     int stats_rows, hipStream_t stream);
+int stem_halo_stats_rows(int Nimg, int H, int W);
 
 // ------------------------------------------------------------------ layout helpers
 // dst NHWC <- src NCHW (plain copy).

@@ -37,7 +37,7 @@ def _to_device(a: np.ndarray, dtype, layout, device, is_filter=False):
 
 class GpuNetwork:
     def __init__(self, wl: dict, tensors: dict, layout: int = B.NSK_NHWC, device: str = "cuda:0", eps: float = 1e-5,
-                 use_relu_mask: bool = True):
+                 use_relu_mask: bool = True, use_fused_stats: bool = True):
         self.wl, self.layout, self.device = wl, layout, torch.device(device)
         self.dtype = torch.bfloat16 if wl["dtype"] == "bf16" else torch.float32
         self.code = B.NSK_BF16 if wl["dtype"] == "bf16" else B.NSK_F32
@@ -55,7 +55,7 @@ class GpuNetwork:
         self.grad[wl["output"]].copy_(_to_device(tensors["dout"], dt, layout, dev))
         self.w, self.gamma, self.beta = {}, {}, {}
         self.dw, self.dgamma, self.dbeta = {}, {}, {}
-        self.y, self.dy, self.mean, self.invstd, self.idx, self.mask = {}, {}, {}, {}, {}, {}
+        self.y, self.dy, self.mean, self.invstd, self.idx, self.mask, self.stats = {}, {}, {}, {}, {}, {}, {}
         ws_bytes = 0
         self.fwd_calls: List[tuple] = []
         self.bwd_calls: List[tuple] = []
@@ -99,14 +99,28 @@ class GpuNetwork:
             self._keep.append(bd)
             ws_bytes = max(ws_bytes, L.nsk_bn_workspace_bytes(ctypes.byref(bd), B.NSK_BN_FWD),
                            L.nsk_bn_workspace_bytes(ctypes.byref(bd), B.NSK_BN_BWD))
-            fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
-                                                ptr(self.y[name])), "ws"))
             res = self.act[u["res"]] if u["res"] else None
             # where the library offers it, the ReLU mask goes from forward to backward as one byte per vector and
             # the backward pass never reads the normalised activation
             mb = int(L.nsk_bn_mask_bytes(ctypes.byref(bd))) if use_relu_mask else 0
             if mb:
                 self.mask[name] = torch.empty(mb, dtype=torch.uint8, device=dev)
+            if use_fused_stats:
+                # the convolution leaves per-channel partial sums of its output; the batch-norm takes its statistics
+                # from them instead of reading the activation once more
+                rows = int(L.nsk_conv2d_stats_rows(ctypes.byref(cd)))
+                self.stats[name] = torch.empty((2, rows, K), dtype=torch.float32, device=dev)
+                fwd_plan.append((L.nsk_conv2d_fwd_stats, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
+                                                          ptr(self.y[name]), ptr(self.stats[name])), "ws"))
+                fwd_plan.append((L.nsk_bn_relu_add_fwd_stats, (ctypes.byref(bd), ptr(self.y[name]), ptr(res),
+                                                               ptr(self.gamma[name]), ptr(self.beta[name]),
+                                                               ptr(self.act[u["dst"]]), ptr(self.mask.get(name)),
+                                                               ptr(self.mean[name]), ptr(self.invstd[name]), None, None,
+                                                               ptr(self.stats[name]), rows), "ws"))
+                continue
+            fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
+                                                ptr(self.y[name])), "ws"))
+            if mb:
                 fwd_plan.append((L.nsk_bn_relu_add_fwd_mask, (ctypes.byref(bd), ptr(self.y[name]), ptr(res),
                                                               ptr(self.gamma[name]), ptr(self.beta[name]),
                                                               ptr(self.act[u["dst"]]), ptr(self.mask[name]),

@@ -141,8 +141,9 @@ def _within(got, want, tol):
     return float(np.mean(rel <= tol)), l2
 
 
+@pytest.mark.parametrize("fused", [True, False], ids=["fused", "plain"])
 @pytest.mark.parametrize("config,stage,batch,layout", CASES)
-def test_workload_end_to_end(config, stage, batch, layout):
+def test_workload_end_to_end(config, stage, batch, layout, fused):
     """The real call sequence (GPU tensors flow from call to call, gradients accumulate in place).
     fp32 workloads meet the max-relative-error bar on every tensor.  In bf16 the two executions round
     intermediate tensors independently, one-ulp differences move a few pre-activations across zero and
@@ -152,8 +153,9 @@ def test_workload_end_to_end(config, stage, batch, layout):
     <= 2e-2 for every forward activation and <= 0.25 for every gradient (measured: up to 1.1e-2 and
     0.16); every single step is held to the strict element-wise bar by the per-step test above."""
     wl, t, fwd, bwd = _setup(config, stage, batch)
-    print(f"workload {wl['name']} input {wl['input']} layout={layout} (end to end)", flush=True)
-    net = GpuNetwork(wl, t, layout=layout)
+    print(f"workload {wl['name']} input {wl['input']} layout={layout} fused={fused} (end to end)", flush=True)
+    # fused: statistics handed from the convolution to the batch-norm, ReLU mask handed from forward to backward
+    net = GpuNetwork(wl, t, layout=layout, use_relu_mask=fused, use_fused_stats=fused)
     net.forward()
     net.backward()
     torch.cuda.synchronize()
