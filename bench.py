@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="issue every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--no-stats", action="store_true",
+                    help="keep the ReLU-mask hand-over but let every batch-norm compute its own statistics")
     ap.add_argument("--no-fusion", action="store_true",
                     help="plain entry points only: no statistics hand-over from convolution to batch-norm, no ReLU mask")
     ap.add_argument("--overlap", action="store_true",
@@ -197,7 +199,7 @@ def main():
     wl = gen.workload(a.config, batch=a.batch, stage=a.stage)
     tensors = gen.workload_tensors(wl)
     layout = B.NSK_NHWC if a.layout == "nhwc" else B.NSK_NCHW
-    net = GpuNetwork(wl, tensors, layout=layout, use_relu_mask=not a.no_fusion, use_fused_stats=not a.no_fusion)
+    net = GpuNetwork(wl, tensors, layout=layout, use_relu_mask=not a.no_fusion, use_fused_stats=not (a.no_fusion or a.no_stats))
     batch = wl["input"][0]
     calls = net.fwd_calls + net.bwd_calls
     costs = [call_cost(net, f, args) for f, args in calls]
@@ -294,7 +296,7 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if wl["dtype"] == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{wl['name']}: {len(wl['units'])} units, input {list(wl['input'])}, "
-                               f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None, "fused_bn_statistics": not a.no_fusion,
+                               f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None, "fused_bn_statistics": not (a.no_fusion or a.no_stats), "relu_mask": not a.no_fusion,
                    "streams": 1 if side is None else 2},
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12,
         "conv_frac_of_mfma_peak": conv_flops / (conv_ms * 1e-3) / PEAK["mfma_bf16" if wl["dtype"] == "bf16" else "mfma_f32"],

@@ -330,12 +330,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
                     }
                 const int col = wcol0 + ni * 32 + ck * VEC;
                 if (lane < CPP && col < a.Ngemm) {
+                    // 16-byte stores: a handful of lanes writing single floats would cost one memory instruction each
                     float *r0 = a.stats + (size_t)row * a.Ngemm + col;
                     float *r1 = r0 + (size_t)a.stats_rows * a.Ngemm;
 #pragma unroll
-                    for (int e = 0; e < VEC; ++e) {
-                        r0[e] = ssum[ni][e];
-                        r1[e] = ssq[ni][e];
+                    for (int e = 0; e < VEC; e += 4) {
+                        *(f32x4 *)(r0 + e) = f32x4{ssum[ni][e], ssum[ni][e + 1], ssum[ni][e + 2], ssum[ni][e + 3]};
+                        *(f32x4 *)(r1 + e) = f32x4{ssq[ni][e], ssq[ni][e + 1], ssq[ni][e + 2], ssq[ni][e + 3]};
                     }
                 }
             }
@@ -427,6 +428,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     const int vec = dtype == NSK_BF16 ? 8 : 4;
     if (!(a.Ngemm % vec == 0 && a.Co % vec == 0 && (uintptr_t)a.out % 16 == 0)) return 0;
     if (a.Ktot < 1024 && getenv("NSK_STATS_ALWAYS") == nullptr) return 0;   // the variable is a test hook
+    if (a.Ngemm % 4 != 0) return 0;   // 16-byte stores of the partial sums
     static const int bm[3] = {256, 128, 128}, wm[3] = {64, 32, 64};
     const int t = auto_tile(a, dtype == NSK_BF16 ? 2 : 4);
     return ceil_div(a.M, bm[t]) * (bm[t] / wm[t]);
