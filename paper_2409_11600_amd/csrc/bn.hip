@@ -315,24 +315,51 @@ __global__ __launch_bounds__(256) void bn_stats_fold(const float *__restrict__ i
 }
 
 // ----------------------------------------------------------------------------- finalize (tiny)
+// Column sums of the two arrays of partial sums for channel c, by one block of 256 threads: every thread adds the
+// rows g = t, t + 256, ... (four independent loads at a time), then lanes and wavefronts are combined in a fixed
+// order.  The result is valid in thread 0.
+__device__ inline void block_column_sums(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, int c,
+                                         double *S_out, double *Q_out)
+{
+    __shared__ double part[2][4];
+    const int t = threadIdx.x;
+    double S = 0.0, Q = 0.0;
+    int g = t;
+    for (; g + 768 < G; g += 1024) {
+        const float a0 = p0[(long)g * C + c], a1 = p0[(long)(g + 256) * C + c], a2 = p0[(long)(g + 512) * C + c],
+                    a3 = p0[(long)(g + 768) * C + c];
+        const float b0 = p1[(long)g * C + c], b1 = p1[(long)(g + 256) * C + c], b2 = p1[(long)(g + 512) * C + c],
+                    b3 = p1[(long)(g + 768) * C + c];
+        S += ((double)a0 + (double)a1) + ((double)a2 + (double)a3);
+        Q += ((double)b0 + (double)b1) + ((double)b2 + (double)b3);
+    }
+    for (; g < G; g += 256) {
+        S += (double)p0[(long)g * C + c];
+        Q += (double)p1[(long)g * C + c];
+    }
+    S = wave_sum_f64(S);
+    Q = wave_sum_f64(Q);
+    if ((t & 63) == 0) {
+        part[0][t >> 6] = S;
+        part[1][t >> 6] = Q;
+    }
+    __syncthreads();
+    *S_out = (part[0][0] + part[0][1]) + (part[0][2] + part[0][3]);
+    *Q_out = (part[1][0] + part[1][1]) + (part[1][2] + part[1][3]);
+}
+
 template <typename T>
-__global__ void bn_fwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
+__global__ __launch_bounds__(256) void bn_fwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
                                 const T *__restrict__ x, long shift_stride, const float *__restrict__ gamma,
                                 const float *__restrict__ beta, float eps, float momentum,
                                 float *__restrict__ save_mean, float *__restrict__ save_invstd,
                                 float *__restrict__ running_mean, float *__restrict__ running_var,
                                 float *__restrict__ scale, float *__restrict__ bias)
 {
-    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (c >= C) return;
-    double S = 0.0, Q = 0.0;
-    for (int g = threadIdx.x & 63; g < G; g += 64) {
-        S += (double)p0[(long)g * C + c];
-        Q += (double)p1[(long)g * C + c];
-    }
-    S = wave_sum_f64(S);
-    Q = wave_sum_f64(Q);
-    if ((threadIdx.x & 63) != 0) return;
+    const int c = blockIdx.x;
+    double S, Q;
+    block_column_sums(p0, p1, G, C, c, &S, &Q);
+    if (threadIdx.x != 0) return;
     const double ms = S / M;
     double var = Q / M - ms * ms;
     if (var < 0.0) var = 0.0;
@@ -350,20 +377,14 @@ __global__ void bn_fwd_finalize(const float *__restrict__ p0, const float *__res
     }
 }
 
-__global__ void bn_bwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
+__global__ __launch_bounds__(256) void bn_bwd_finalize(const float *__restrict__ p0, const float *__restrict__ p1, int G, int C, double M,
                                 const float *__restrict__ gamma, const float *__restrict__ invstd,
                                 float *__restrict__ dgamma, float *__restrict__ dbeta, float *__restrict__ coef)
 {
-    const int c = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (c >= C) return;
-    double S = 0.0, Q = 0.0;
-    for (int g = threadIdx.x & 63; g < G; g += 64) {
-        S += (double)p0[(long)g * C + c];
-        Q += (double)p1[(long)g * C + c];
-    }
-    S = wave_sum_f64(S);
-    Q = wave_sum_f64(Q);
-    if ((threadIdx.x & 63) != 0) return;
+    const int c = blockIdx.x;
+    double S, Q;
+    block_column_sums(p0, p1, G, C, c, &S, &Q);
+    if (threadIdx.x != 0) return;
     dbeta[c] = (float)S;
     dgamma[c] = (float)Q;
     coef[c] = gamma[c] * invstd[c];
@@ -452,7 +473,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
             q1 = p0 + (long)r2 * d.C;
             rows = r2;
         }
-        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, q0, q1, rows, d.C,
+        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(d.C), dim3(256), 0, stream, q0, q1, rows, d.C,
                            (double)g.M, (const T *)nullptr, 0L, gamma, beta, d.eps, d.momentum, save_mean, save_invstd,
                            running_mean, running_var, scale, bias);
     } else if (g.fast) {
@@ -465,7 +486,7 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
                            g.sc, g.ss, g.npg, d.C, p0, p1);
     }
     if (!stats)
-        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+        hipLaunchKernelGGL((bn_fwd_finalize<T>), dim3(d.C), dim3(256), 0, stream, p0, p1, g.G, d.C,
                            (double)g.M, x, g.sc, gamma, beta, d.eps, d.momentum, save_mean, save_invstd, running_mean,
                            running_var, scale, bias);
     if (g.fast) {
@@ -508,7 +529,7 @@ int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout
         hipLaunchKernelGGL((bn_reduce_generic<T, 1>), dim3(d.C, g.G), dim3(256), 0, stream, x, out, dout, mean,
                            invstd, d.relu, d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1);
     }
-    hipLaunchKernelGGL(bn_bwd_finalize, dim3(ceil_div(d.C, 4)), dim3(256), 0, stream, p0, p1, g.G, d.C,
+    hipLaunchKernelGGL(bn_bwd_finalize, dim3(d.C), dim3(256), 0, stream, p0, p1, g.G, d.C,
                        (double)g.M, gamma, invstd, dgamma, dbeta, coef);
     if (g.fast) {
         const long nvec = g.total / VEC;

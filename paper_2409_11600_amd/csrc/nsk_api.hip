@@ -354,51 +354,69 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
     // dx[h] with h = a + sh*i receives dy[p] * w[r] exactly for the taps r with
     // (a + ph - r*dh) divisible by sh, at p = i + (a + ph - r*dh)/sh: one dense sub-problem per
     // residue class (a, b) of (h mod sh, w mod sw), so no multiply is spent on inserted zeros.
+    // Geometry of one class (everything but the pointers); returns its number of taps.
+    auto class_args = [&](int ca, int cb, IgemmArgs *a, int *tap_off) {
+        int nt = 0;
+        for (int r = 0; r < g.R; ++r) {
+            const int th = ca + g.ph - r * g.dh;
+            if (((th % g.sh) + g.sh) % g.sh != 0) continue;
+            for (int s = 0; s < g.S; ++s) {
+                const int tw = cb + g.pw - s * g.dw;
+                if (((tw % g.sw) + g.sw) % g.sw != 0) continue;
+                a->off_h[nt] = (short)(th / g.sh);  // exact division, may be negative
+                a->off_w[nt] = (short)(tw / g.sw);
+                tap_off[nt] = nchw ? r * g.S + s : (r * g.S + s) * g.C;
+                ++nt;
+            }
+        }
+        a->Nimg = g.N; a->Hs = g.P; a->Ws = g.Q; a->Cs = g.K;
+        a->Mi = ca < g.H ? (g.H - ca + g.sh - 1) / g.sh : 0;
+        a->Mj = cb < g.W ? (g.W - cb + g.sw - 1) / g.sw : 0;
+        a->M = g.N * a->Mi * a->Mj;
+        a->mult_h = 1; a->add_h = 0; a->mult_w = 1; a->add_w = 0;
+        a->ntaps = nt; a->Ktot = nt * g.K;
+        a->Ngemm = g.C;
+        a->Ho = g.H; a->Wo = g.W; a->Co = g.C; a->osh = g.sh; a->oa = ca; a->osw = g.sw; a->ob = cb;
+        a->accumulate = acc_kernel;
+        a->src_bytes = (unsigned)(g.y_elems * g.es);
+        a->wpk_bytes = (unsigned)((size_t)g.C * nt * g.K * g.es);
+        return nt;
+    };
+    // Stride 2 with every tap in class (0, 0) (a 1x1 layer): the other three classes are plain zeros, which the
+    // short-reduction kernel writes along with class (0, 0) when it takes that class.
+    bool zero_cell = false;
+    if (g.sh == 2 && g.sw == 2 && !acc_kernel) {
+        IgemmArgs a{};
+        int tap_off[kMaxTaps];
+        bool others_empty = true;
+        for (int c = 1; c < 4; ++c) others_empty = others_empty && class_args(c >> 1, c & 1, &a, tap_off) == 0;
+        if (others_empty && class_args(0, 0, &a, tap_off) > 0) {
+            a.src = src; a.wpk = ws + p.filt; a.out = dst;
+            zero_cell = conv_pw_applicable(g.dtype, a);
+        }
+    }
     size_t filt_off = p.filt;
     for (int ca = 0; ca < g.sh; ++ca)
         for (int cb = 0; cb < g.sw; ++cb) {
-            const int Mi = ca < g.H ? (g.H - ca + g.sh - 1) / g.sh : 0;
-            const int Mj = cb < g.W ? (g.W - cb + g.sw - 1) / g.sw : 0;
-            if (Mi == 0 || Mj == 0) continue;
             IgemmArgs a{};
             int tap_off[kMaxTaps];
-            int nt = 0;
-            for (int r = 0; r < g.R; ++r) {
-                const int th = ca + g.ph - r * g.dh;
-                if (((th % g.sh) + g.sh) % g.sh != 0) continue;
-                for (int s = 0; s < g.S; ++s) {
-                    const int tw = cb + g.pw - s * g.dw;
-                    if (((tw % g.sw) + g.sw) % g.sw != 0) continue;
-                    a.off_h[nt] = (short)(th / g.sh);  // exact division, may be negative
-                    a.off_w[nt] = (short)(tw / g.sw);
-                    tap_off[nt] = nchw ? r * g.S + s : (r * g.S + s) * g.C;
-                    ++nt;
-                }
-            }
+            const int nt = class_args(ca, cb, &a, tap_off);
+            if (a.Mi == 0 || a.Mj == 0) continue;
             if (nt == 0 && accumulate && !nchw) continue;  // nothing to add
             if (nt == 0) {   // no tap reaches this class: plain zero fill
-                NSK_TRY(launch_zero_class(g.dtype, dst, g.N, g.H, g.W, g.C, Mi, Mj, g.sh, ca, g.sw, cb, st));
+                if (!zero_cell)
+                    NSK_TRY(launch_zero_class(g.dtype, dst, g.N, g.H, g.W, g.C, a.Mi, a.Mj, g.sh, ca, g.sw, cb, st));
                 continue;
             }
             // packed filter of this class: [c][tap][k]
-            if (nt > 0) {
-                if (nchw)
-                    NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, (long)g.R * g.S,
-                                               (long)g.C * g.R * g.S, tap_off, st));
-                else
-                    NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, 1L, (long)g.R * g.S * g.C,
-                                               tap_off, st));
-            }
+            if (nchw)
+                NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, (long)g.R * g.S,
+                                           (long)g.C * g.R * g.S, tap_off, st));
+            else
+                NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, 1L, (long)g.R * g.S * g.C,
+                                           tap_off, st));
             a.src = src; a.wpk = ws + filt_off; a.out = dst;
-            a.Nimg = g.N; a.Hs = g.P; a.Ws = g.Q; a.Cs = g.K;
-            a.Mi = Mi; a.Mj = Mj; a.M = g.N * Mi * Mj;
-            a.mult_h = 1; a.add_h = 0; a.mult_w = 1; a.add_w = 0;
-            a.ntaps = nt; a.Ktot = nt * g.K;
-            a.Ngemm = g.C;
-            a.Ho = g.H; a.Wo = g.W; a.Co = g.C; a.osh = g.sh; a.oa = ca; a.osw = g.sw; a.ob = cb;
-            a.accumulate = acc_kernel;
-            a.src_bytes = (unsigned)(g.y_elems * g.es);
-            a.wpk_bytes = (unsigned)((size_t)g.C * nt * g.K * g.es);
+            a.zero_cell = zero_cell ? 1 : 0;
             NSK_TRY(launch_igemm(g.dtype, a, st));
             filt_off += align_up((size_t)g.C * nt * g.K * g.es);
         }

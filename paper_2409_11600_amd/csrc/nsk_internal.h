@@ -78,6 +78,10 @@ struct IgemmArgs {
     // igemm_stats_rows() named the row count for exactly this launch.
     float *stats;
     int stats_rows;
+    // Backward-data of a stride-2 layer whose taps all fall into residue class (0, 0): the launch for that class also
+    // writes zeros to the other (up to three) pixels of each row's 2x2 output cell.  Only the short-reduction kernel
+    // honours it: set it only after conv_pw_applicable() said yes for these arguments.
+    int zero_cell;
     short off_h[kMaxTaps];
     short off_w[kMaxTaps];
 };
@@ -89,6 +93,11 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a);
 bool igemm_big_applicable(int dtype, const IgemmArgs &a);
 int launch_igemm_big(const IgemmArgs &a, hipStream_t stream);
 int igemm_big_stats_rows(const IgemmArgs &a);
+// bf16 layers with one, two or four taps and at most 256 reduction indices (memory-bound: filter resident in LDS,
+// pixels loaded straight into MFMA operand registers)
+bool conv_pw_applicable(int dtype, const IgemmArgs &a);
+int launch_conv_pw(const IgemmArgs &a, hipStream_t stream);
+int conv_pw_stats_rows(const IgemmArgs &a);
 // bf16 3x3 stride-1 64->64 special case (filter resident in LDS, input tile staged once with halo)
 bool halo64_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64(const IgemmArgs &a, hipStream_t stream);

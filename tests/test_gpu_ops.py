@@ -135,6 +135,68 @@ def test_conv_wide_layers_large_tile_kernel(i, layout, monkeypatch):
     assert max_rel_err(to_host(gdw, layout), want_dw + base_w.astype(np.float64)) <= TOL["f32"] * 10
 
 
+# Short-reduction bf16 layers (1, 2 or 4 taps, at most 256 reduction indices) for the kernel that keeps the filter
+# in LDS and loads pixels straight into MFMA operands.
+PW_SHAPES = [
+    (2, 128, 9, 9, 256, 1, 1, 1, 0, 1),        # four column chunks forward, 256 input channels (32-pixel tiles) backward
+    (3, 256, 10, 9, 64, 1, 1, 1, 0, 1),        # 256 -> 64 and back
+    (4, 64, 16, 16, 192, 1, 1, 2, 0, 1),       # stride 2, three column chunks (backward takes the generic kernel)
+    (2, 64, 15, 13, 64, 1, 1, 2, 0, 1),        # stride 2 on odd extents: ragged residue classes in backward-data
+    (5, 128, 7, 7, 128, 1, 1, 1, 0, 1),        # ragged last tile
+    (1, 64, 6, 6, 64, 1, 1, 1, 1, 1),          # padded 1x1: source positions outside the image read as zero
+    (4, 64, 250, 260, 64, 1, 1, 1, 0, 1),      # several tiles per wavefront (both register sets, prefetch across tiles)
+    (2, 64, 18, 14, 64, 3, 3, 2, 1, 1),        # backward-data classes with 1, 2, 2 and 4 taps on 64 channels
+    (2, 64, 17, 15, 64, 3, 3, 2, 1, 1),        # the same on odd extents
+    (2, 64, 12, 12, 128, 3, 3, 2, 1, 1),       # 128 channels: classes with 1 and 2 taps (the 4-tap class is generic)
+    (2, 64, 12, 14, 64, 2, 2, 2, 0, 1),        # 2x2 stride-2 filter: four taps forward, one tap per class backward
+    (1, 128, 9, 9, 64, 1, 2, 1, 0, 1),         # two taps of 128 channels forward
+]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("i", range(len(PW_SHAPES)))
+def test_conv_pointwise_kernel(i, layout, monkeypatch):
+    monkeypatch.setenv("NSK_PW_MIN_ROWS", "1")
+    N, C, H, W, K, R, S, st, pd, dl = PW_SHAPES[i]
+    if layout == "nchw" and N * H * W > 100000:
+        pytest.skip("large case once (NHWC)")
+    print(f"pointwise conv case {i} {PW_SHAPES[i]} layout={layout}", flush=True)
+    dtype = "bf16"
+    x = on_grid(gen.normal(1100 + i, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(1100 + i, 1, (K, C, R, S)), dtype)
+    P, Q = oracle.conv2d_out_dims(x.shape, w.shape, st, pd, dl)
+    dy = on_grid(gen.normal(1100 + i, 2, (N, K, P, Q)), dtype)
+    tol = TOL[dtype]
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    y_view, y_check = guarded(gdy.shape, torch_dtype(dtype))
+    B.conv2d_fwd(gx, gw, st, pd, dl, layout, out=y_view, ws=ws)
+    y1, stats = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    dx_view, dx_check = guarded(gx.shape, torch_dtype(dtype))
+    B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, out=dx_view, ws=ws)
+    torch.cuda.synchronize()
+    y_check()
+    dx_check()
+    assert torch.equal(y_view, y1)
+    yh = to_host(y_view, layout)
+    assert max_rel_err(yh, oracle.conv2d_fwd(x, w, st, pd, dl)) <= tol
+    sums = stats.double().sum(dim=1).cpu().numpy()             # [2, K]
+    want0, want1 = yh.sum(axis=(0, 2, 3)), (yh * yh).sum(axis=(0, 2, 3))
+    assert np.max(np.abs(sums[0] - want0) / (np.sqrt(want1 * yh[:, 0].size) + 1e-30)) <= 1e-6
+    assert np.max(np.abs(sums[1] - want1) / (want1 + 1e-30)) <= 1e-5
+    want_dx = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl)
+    got_dx = to_host(dx_view, layout)
+    assert max_rel_err(got_dx, want_dx) <= tol
+    assert np.all(got_dx[want_dx == 0.0] == 0.0)
+    # accumulating backward-data (old values fetched one chunk ahead, one rounding of old + sum)
+    base = on_grid(gen.normal(1100 + i, 3, x.shape), dtype)
+    gacc = to_gpu(base, dtype, layout)
+    B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, out=gacc, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    want_acc = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl, into=base.astype(np.float64))
+    assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
+
+
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", [1, 2, 3, 8, 12, 13, 15, 16])
