@@ -55,6 +55,9 @@ def parse():
     ap.add_argument("--overlap", action="store_true",
                     help="issue the backward-weight calls on a second stream (measured: no gain on MI355X, the "
                          "convolution kernels already hold every CU)")
+    ap.add_argument("--train-step", action="store_true",
+                    help="also time the whole training step: the workload followed by average pool, fully connected "
+                         "layer, loss, their backward passes and the SGD update of every parameter")
     ap.add_argument("--layers", action="store_true", help="per-layer convolution table instead of the step benchmark")
     return ap.parse_args()
 
@@ -302,6 +305,35 @@ def main():
         "conv_frac_of_mfma_peak": conv_flops / (conv_ms * 1e-3) / PEAK["mfma_bf16" if wl["dtype"] == "bf16" else "mfma_f32"],
         "roofline": roof,
     }
+
+    if a.train_step:
+        from paper_2409_11600_amd.trainer import GpuTrainer
+        classes = 10 if a.config <= 3 else 1000
+        Cout = gen.tensor_shapes(wl)[wl["output"]][1]
+        fc_w = (gen.normal(wl["seed"], 2000, (classes, Cout)) / np.sqrt(Cout)).astype(np.float32)
+        fc_b = np.zeros((classes,), np.float32)
+        labels = (gen.uniform(wl["seed"], 2002, (batch,)) * classes).astype(np.int32) % classes
+        with torch.cuda.stream(stream):
+            tr = GpuTrainer(net, fc_w, fc_b, labels, lr=0.1, momentum=0.9, weight_decay=1e-4)
+            for _ in range(2):
+                tr.step()
+            stream.synchronize()
+            tgraph = None
+            if not a.no_graph:
+                tgraph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(tgraph, stream=stream):
+                    tr.step()
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for _ in range(a.steps):
+                tgraph.replay() if tgraph is not None else tr.step()
+            stream.synchronize()
+            torch.cuda.synchronize()
+            c1 = time.perf_counter()
+        n_params = sum(p[0].numel() for g in tr.groups.values() for p in g)
+        out["train_step"] = {"ms_per_step": (c1 - c0) * 1e3 / a.steps, "images_per_s": batch * a.steps / (c1 - c0),
+                             "tail": f"avgpool + fc({Cout}->{classes}) + softmax-xent + backward + SGD-momentum over "
+                                     f"{n_params} parameters", "loss": float(tr.loss.item())}
 
     if not a.no_cpu_baseline:
         import oracle

@@ -6,7 +6,8 @@
  * ReLU fusion is named as future work in the conclusion).  This library is that device layer,
  * hand-written: implicit-GEMM convolution forward / backward-data / backward-weight on the
  * MFMA units, and fused batch-norm + ReLU + residual-add forward / backward, plus the 3x3
- * max pooling the large-image stem needs.
+ * max pooling the large-image stem needs, and (last section) the small operations that close
+ * a training step: network head, loss and optimizer updates.
  *
  * Calling convention, taken from what the paper says about its runtime:
  *  - Tensors are raw DEVICE pointers owned by the caller (section "Caching and Pooling": a
@@ -195,6 +196,88 @@ int nsk_maxpool2d_fwd(const nsk_pool_desc_t *desc, const void *x, void *y, signe
 /* dx[N,C,H,W] = sum of dy over the windows whose idx names that element (dx overwritten). */
 int nsk_maxpool2d_bwd(const nsk_pool_desc_t *desc, const void *dy, const signed char *idx,
                       void *dx, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------------------
+ * The tail that closes a training step behind the residual blocks: the head of the ResNet recipe the paper
+ * trains (global average pool, fully connected layer), the loss node that must end every step, and the optimizer
+ * updates (sections "Automatic Differentiation", "Caching and Pooling", "Experiments and Discussion").  The
+ * paper gives no formulas for them; the textbook definitions below are used.
+ * --------------------------------------------------------------------------------------------------------------- */
+
+/* Global average pool: y[n][c] = mean over (h, w) of x[n][c][h][w].  x: [N,C,H,W] in `layout`, y: [N,C], both of
+ * `dtype`; sums in float.  No workspace.  NSK_ERR_BAD_DESC for non-positive extents. */
+int nsk_global_avgpool_fwd(int dtype, int layout, int N, int C, int H, int W, const void *x, void *y,
+                           void *stream);
+/* Its adjoint: dx[n][c][h][w] (+)= dy[n][c] / (H*W); accumulate as in the header comment. */
+int nsk_global_avgpool_bwd(int dtype, int layout, int N, int C, int H, int W, const void *dy, void *dx,
+                           int accumulate, void *stream);
+
+/* Fully connected layer, the `@` operator of section "Automatic Differentiation": y = x @ w multiplies by the
+ * TRANSPOSED weight, y[n][k] = sum_c x[n][c] * w[k][c] (+ bias[k]).  x: [N,C], w: [K,C], y: [N,K] of `dtype`,
+ * row-major; bias, dw, db are float.  The three calls run on the convolution kernels (a 1x1 filter on a 1x1
+ * image); `workspace` must hold nsk_linear_workspace_bytes(desc, NSK_PASS_*) bytes. */
+typedef struct {
+    int N, C, K;
+    int dtype;
+} nsk_linear_desc_t;
+size_t nsk_linear_workspace_bytes(const nsk_linear_desc_t *desc, int pass);
+/* bias may be NULL. */
+int nsk_linear_fwd(const nsk_linear_desc_t *desc, const void *x, const void *w, const float *bias, void *y,
+                   void *workspace, size_t workspace_bytes, void *stream);
+/* dx[n][c] (+)= sum_k dy[n][k] * w[k][c]. */
+int nsk_linear_dgrad(const nsk_linear_desc_t *desc, const void *dy, const void *w, void *dx, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream);
+/* dw[k][c] (+)= sum_n dy[n][k] * x[n][c];  db[k] (+)= sum_n dy[n][k] (db may be NULL).  Fixed summation order. */
+int nsk_linear_wgrad(const nsk_linear_desc_t *desc, const void *x, const void *dy, float *dw, float *db,
+                     int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Softmax cross-entropy, the loss node: per_sample[n] = log sum_k exp(z[n][k]) - z[n][label_n] (computed with
+ * the row maximum subtracted), loss[0] = mean over n, summed in a fixed order.  logits: [N,K] of `dtype`;
+ * labels: [N] int, each in [0,K) (a label outside that range gives NaN for its sample and for the loss);
+ * per_sample: [N] float, loss: [1] float, all device memory. */
+int nsk_softmax_xent_fwd(int dtype, int N, int K, const void *logits, const int *labels, float *per_sample,
+                         float *loss, void *stream);
+/* dlogits[n][k] = dloss/N * (softmax(z[n])[k] - [k == label_n]), of `dtype`, overwritten. */
+int nsk_softmax_xent_bwd(int dtype, int N, int K, const void *logits, const int *labels, float dloss,
+                         void *dlogits, void *stream);
+
+/* Optimizer updates over one parameter tensor of n floats (master weights, gradient and state are float).  Each
+ * call is asynchronous on its stream, so parameter groups can be updated on streams of their own (section
+ * "Operation Overlapping").  The gradient buffer is overwritten with zeros (section "Caching and Pooling").
+ * w_lp: NULL, or n bf16 elements that receive the updated weights rounded to bf16 (the copy the bf16 kernels
+ * read).  grad_scale: NULL, or a device float (4-byte aligned, like the other single-float arguments below) that
+ * multiplies every gradient first (see nsk_clip_scale).
+ *
+ * SGD with momentum (the ResNet recipe):  g' = scale*g + weight_decay*w;  v <- momentum*v + g';  w <- w - lr*v. */
+int nsk_sgd_momentum_step(size_t n, float *w, float *grad, float *velocity, void *w_lp, float lr,
+                          float momentum, float weight_decay, const float *grad_scale, void *stream);
+/* AdamW (the recurrent experiment of section "Experiments and Discussion"), step counted from 1:
+ * w <- w*(1 - lr*weight_decay);  m <- beta1*m + (1-beta1)*g;  v <- beta2*v + (1-beta2)*g*g;
+ * w <- w - lr * (m/(1-beta1^step)) / (sqrt(v/(1-beta2^step)) + eps). */
+int nsk_adamw_step(size_t n, float *w, float *grad, float *m, float *v, void *w_lp, int step, float lr,
+                   float beta1, float beta2, float eps, float weight_decay, const float *grad_scale,
+                   void *stream);
+/* The same updates for `count` parameter tensors in one launch per 32 tensors (a network has many small ones, and a
+ * launch per tensor costs more than the update).  params: HOST array of `count` records; state1 is the velocity
+ * (SGD) or m (AdamW), state2 is v (AdamW; ignored by SGD); w_lp NULL or the bf16 copy; each tensor has its own
+ * weight decay.  All records are validated before anything is launched. */
+typedef struct {
+    float *w, *grad, *state1, *state2;
+    void *w_lp;
+    size_t n;
+    float weight_decay;
+} nsk_param_t;
+int nsk_sgd_momentum_step_multi(int count, const nsk_param_t *params, float lr, float momentum,
+                                const float *grad_scale, void *stream);
+int nsk_adamw_step_multi(int count, const nsk_param_t *params, int step, float lr, float beta1, float beta2,
+                         float eps, const float *grad_scale, void *stream);
+/* Gradient clip by global norm (the "gradient clip of 5" of the same experiment), in two steps that never
+ * synchronise: nsk_sumsq_accumulate adds the sum of squares of g[0..n) to the device float *sumsq (zero it before
+ * the first tensor; `partials`: NSK_SUMSQ_PARTIALS floats of device scratch; fixed summation order), then
+ * nsk_clip_scale writes *scale = min(1, max_norm / (sqrt(*sumsq) + 1e-6)) for the optimizer calls to read. */
+#define NSK_SUMSQ_PARTIALS 256
+int nsk_sumsq_accumulate(size_t n, const float *g, float *partials, float *sumsq, void *stream);
+int nsk_clip_scale(const float *sumsq, float max_norm, float *scale, void *stream);
 
 #ifdef __cplusplus
 }

@@ -45,6 +45,15 @@ class nsk_pool_desc_t(ctypes.Structure):
                 ("N", "C", "H", "W", "R", "S", "stride_h", "stride_w", "pad_h", "pad_w", "dtype", "layout")]
 
 
+class nsk_linear_desc_t(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int) for n in ("N", "C", "K", "dtype")]
+
+
+class nsk_param_t(ctypes.Structure):
+    _fields_ = [("w", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("state1", ctypes.c_void_p), ("state2", ctypes.c_void_p),
+                ("w_lp", ctypes.c_void_p), ("n", ctypes.c_size_t), ("weight_decay", ctypes.c_float)]
+
+
 class NskError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -108,6 +117,36 @@ def lib() -> ctypes.CDLL:
         L.nsk_maxpool2d_fwd.argtypes = [pd, vp, vp, vp, vp]
         L.nsk_maxpool2d_bwd.restype = ci
         L.nsk_maxpool2d_bwd.argtypes = [pd, vp, vp, vp, vp]
+        ld, cf = ctypes.POINTER(nsk_linear_desc_t), ctypes.c_float
+        L.nsk_global_avgpool_fwd.restype = ci
+        L.nsk_global_avgpool_fwd.argtypes = [ci] * 6 + [vp, vp, vp]
+        L.nsk_global_avgpool_bwd.restype = ci
+        L.nsk_global_avgpool_bwd.argtypes = [ci] * 6 + [vp, vp, ci, vp]
+        L.nsk_linear_workspace_bytes.restype = sz
+        L.nsk_linear_workspace_bytes.argtypes = [ld, ci]
+        L.nsk_linear_fwd.restype = ci
+        L.nsk_linear_fwd.argtypes = [ld, vp, vp, vp, vp, vp, sz, vp]
+        L.nsk_linear_dgrad.restype = ci
+        L.nsk_linear_dgrad.argtypes = [ld, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_linear_wgrad.restype = ci
+        L.nsk_linear_wgrad.argtypes = [ld, vp, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_softmax_xent_fwd.restype = ci
+        L.nsk_softmax_xent_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp]
+        L.nsk_softmax_xent_bwd.restype = ci
+        L.nsk_softmax_xent_bwd.argtypes = [ci, ci, ci, vp, vp, cf, vp, vp]
+        L.nsk_sgd_momentum_step.restype = ci
+        L.nsk_sgd_momentum_step.argtypes = [sz, vp, vp, vp, vp, cf, cf, cf, vp, vp]
+        L.nsk_adamw_step.restype = ci
+        L.nsk_adamw_step.argtypes = [sz, vp, vp, vp, vp, vp, ci, cf, cf, cf, cf, cf, vp, vp]
+        pp = ctypes.POINTER(nsk_param_t)
+        L.nsk_sgd_momentum_step_multi.restype = ci
+        L.nsk_sgd_momentum_step_multi.argtypes = [ci, pp, cf, cf, vp, vp]
+        L.nsk_adamw_step_multi.restype = ci
+        L.nsk_adamw_step_multi.argtypes = [ci, pp, ci, cf, cf, cf, cf, vp, vp]
+        L.nsk_sumsq_accumulate.restype = ci
+        L.nsk_sumsq_accumulate.argtypes = [sz, vp, vp, vp, vp]
+        L.nsk_clip_scale.restype = ci
+        L.nsk_clip_scale.argtypes = [vp, cf, vp, vp]
         _lib = L
     return _lib
 
@@ -117,7 +156,11 @@ EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d
            "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
            "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_conv2d_stats_rows", "nsk_conv2d_fwd_stats",
            "nsk_bn_relu_add_fwd_stats", "nsk_maxpool2d_out_dims",
-           "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd")
+           "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd",
+           "nsk_global_avgpool_fwd", "nsk_global_avgpool_bwd", "nsk_linear_workspace_bytes", "nsk_linear_fwd",
+           "nsk_linear_dgrad", "nsk_linear_wgrad", "nsk_softmax_xent_fwd", "nsk_softmax_xent_bwd",
+           "nsk_sgd_momentum_step", "nsk_adamw_step", "nsk_sgd_momentum_step_multi", "nsk_adamw_step_multi", "nsk_sumsq_accumulate", "nsk_clip_scale")
+NSK_SUMSQ_PARTIALS = 256
 
 
 def __getattr__(name):  # raw entry points under their C names: binding.nsk_conv2d_fwd(...)
@@ -387,3 +430,158 @@ def maxpool2d_bwd(dy, idx, x_logical, window=3, stride=2, pad=1, layout=NSK_NHWC
         out = torch.empty(_act_shape(N, C, H, W, layout), dtype=dy.dtype, device=dy.device)
     _check(lib().nsk_maxpool2d_bwd(ctypes.byref(d), _ptr(dy), _ptr(idx), _ptr(out), _stream()), "nsk_maxpool2d_bwd")
     return out
+
+
+# ------------------------------------------------------------------------------------ training-step tail
+
+def global_avgpool_fwd(x, layout=NSK_NHWC, out=None):
+    N, C, H, W = _logical(x, layout)
+    if out is None:
+        out = torch.empty((N, C), dtype=x.dtype, device=x.device)
+    _check(lib().nsk_global_avgpool_fwd(_dtype_code(x), layout, N, C, H, W, _ptr(x), _ptr(out), _stream()),
+           "nsk_global_avgpool_fwd")
+    return out
+
+
+def global_avgpool_bwd(dy, x_logical, layout=NSK_NHWC, out=None, accumulate=False):
+    N, C, H, W = x_logical
+    if out is None:
+        assert not accumulate
+        out = torch.empty(_act_shape(N, C, H, W, layout), dtype=dy.dtype, device=dy.device)
+    _check(lib().nsk_global_avgpool_bwd(_dtype_code(dy), layout, N, C, H, W, _ptr(dy), _ptr(out), int(accumulate),
+                                        _stream()), "nsk_global_avgpool_bwd")
+    return out
+
+
+def _linear_desc(N, C, K, t):
+    return nsk_linear_desc_t(int(N), int(C), int(K), _dtype_code(t))
+
+
+def linear_fwd(x, w, bias=None, out=None, ws: Optional[Workspace] = None):
+    """y = x @ w^T (+ bias): x [N,C], w [K,C], bias float [K]."""
+    (N, C), (K, Cw) = x.shape, w.shape
+    assert C == Cw and w.dtype == x.dtype
+    d = _linear_desc(N, C, K, x)
+    if out is None:
+        out = torch.empty((N, K), dtype=x.dtype, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_linear_workspace_bytes(ctypes.byref(d), NSK_PASS_FWD))
+    _check(lib().nsk_linear_fwd(ctypes.byref(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(out), wp, wb, _stream()),
+           "nsk_linear_fwd")
+    return out
+
+
+def linear_dgrad(dy, w, out=None, accumulate=False, ws: Optional[Workspace] = None):
+    (N, K), (Kw, C) = dy.shape, w.shape
+    assert K == Kw and w.dtype == dy.dtype
+    d = _linear_desc(N, C, K, dy)
+    if out is None:
+        assert not accumulate
+        out = torch.empty((N, C), dtype=dy.dtype, device=dy.device)
+    ws = ws or Workspace(dy.device)
+    wp, wb = ws.get(lib().nsk_linear_workspace_bytes(ctypes.byref(d), NSK_PASS_DGRAD))
+    _check(lib().nsk_linear_dgrad(ctypes.byref(d), _ptr(dy), _ptr(w), _ptr(out), int(accumulate), wp, wb, _stream()),
+           "nsk_linear_dgrad")
+    return out
+
+
+def linear_wgrad(x, dy, dw=None, db=None, accumulate=False, want_db=True, ws: Optional[Workspace] = None):
+    (N, C), (Nd, K) = x.shape, dy.shape
+    assert N == Nd and x.dtype == dy.dtype
+    d = _linear_desc(N, C, K, x)
+    if dw is None:
+        assert not accumulate
+        dw = torch.empty((K, C), dtype=torch.float32, device=x.device)
+    if db is None and want_db:
+        assert not accumulate
+        db = torch.empty((K,), dtype=torch.float32, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_linear_workspace_bytes(ctypes.byref(d), NSK_PASS_WGRAD))
+    _check(lib().nsk_linear_wgrad(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(dw), _ptr(db), int(accumulate), wp, wb,
+                                  _stream()), "nsk_linear_wgrad")
+    return dw, db
+
+
+def softmax_xent_fwd(logits, labels, per_sample=None, loss=None):
+    """labels: int32 [N].  Returns (loss [1] float32, per_sample [N] float32), both on the device."""
+    N, K = logits.shape
+    assert labels.dtype == torch.int32 and labels.numel() == N
+    if per_sample is None:
+        per_sample = torch.empty((N,), dtype=torch.float32, device=logits.device)
+    if loss is None:
+        loss = torch.empty((1,), dtype=torch.float32, device=logits.device)
+    _check(lib().nsk_softmax_xent_fwd(_dtype_code(logits), int(N), int(K), _ptr(logits), _ptr(labels), _ptr(per_sample),
+                                      _ptr(loss), _stream()), "nsk_softmax_xent_fwd")
+    return loss, per_sample
+
+
+def softmax_xent_bwd(logits, labels, dloss=1.0, out=None):
+    N, K = logits.shape
+    assert labels.dtype == torch.int32 and labels.numel() == N
+    if out is None:
+        out = torch.empty_like(logits)
+    _check(lib().nsk_softmax_xent_bwd(_dtype_code(logits), int(N), int(K), _ptr(logits), _ptr(labels), float(dloss),
+                                      _ptr(out), _stream()), "nsk_softmax_xent_bwd")
+    return out
+
+
+def sgd_momentum_step(w, grad, velocity, lr, momentum=0.9, weight_decay=0.0, w_lp=None, grad_scale=None):
+    """In place on the float32 tensors w, grad (zeroed), velocity; w_lp: optional bfloat16 copy of w."""
+    n = w.numel()
+    assert grad.numel() == n and velocity.numel() == n and all(t.dtype == torch.float32 for t in (w, grad, velocity))
+    assert w_lp is None or (w_lp.dtype == torch.bfloat16 and w_lp.numel() == n)
+    _check(lib().nsk_sgd_momentum_step(n, _ptr(w), _ptr(grad), _ptr(velocity), _ptr(w_lp), float(lr), float(momentum),
+                                       float(weight_decay), _ptr(grad_scale), _stream()), "nsk_sgd_momentum_step")
+
+
+def adamw_step(w, grad, m, v, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0, w_lp=None,
+               grad_scale=None):
+    n = w.numel()
+    assert all(t.numel() == n and t.dtype == torch.float32 for t in (w, grad, m, v))
+    assert w_lp is None or (w_lp.dtype == torch.bfloat16 and w_lp.numel() == n)
+    _check(lib().nsk_adamw_step(n, _ptr(w), _ptr(grad), _ptr(m), _ptr(v), _ptr(w_lp), int(step), float(lr), float(beta1),
+                                float(beta2), float(eps), float(weight_decay), _ptr(grad_scale), _stream()),
+           "nsk_adamw_step")
+
+
+def param_table(records):
+    """records: iterable of (w, grad, state1, state2 or None, w_lp or None, weight_decay) tensors -> ctypes array of
+    nsk_param_t (keep the tensors alive while it is in use)."""
+    records = list(records)
+    tab = (nsk_param_t * len(records))()
+    for i, (w, g, s1, s2, lp, wd) in enumerate(records):
+        n = w.numel()
+        assert all(t.dtype == torch.float32 and t.numel() == n and t.is_contiguous() for t in (w, g, s1))
+        assert s2 is None or (s2.dtype == torch.float32 and s2.numel() == n)
+        assert lp is None or (lp.dtype == torch.bfloat16 and lp.numel() == n)
+        tab[i] = nsk_param_t(w.data_ptr(), g.data_ptr(), s1.data_ptr(), s2.data_ptr() if s2 is not None else None,
+                             lp.data_ptr() if lp is not None else None, n, float(wd))
+    return tab
+
+
+def sgd_momentum_step_multi(tab, lr, momentum=0.9, grad_scale=None):
+    _check(lib().nsk_sgd_momentum_step_multi(len(tab), tab, float(lr), float(momentum), _ptr(grad_scale), _stream()),
+           "nsk_sgd_momentum_step_multi")
+
+
+def adamw_step_multi(tab, step, lr, beta1=0.9, beta2=0.999, eps=1e-8, grad_scale=None):
+    _check(lib().nsk_adamw_step_multi(len(tab), tab, int(step), float(lr), float(beta1), float(beta2), float(eps),
+                                      _ptr(grad_scale), _stream()), "nsk_adamw_step_multi")
+
+
+def clip_scale(grads, max_norm, partials=None, sumsq=None, scale=None):
+    """Device float [1] = min(1, max_norm / (global L2 norm of `grads` + 1e-6)); no host synchronisation."""
+    dev = grads[0].device
+    if partials is None:
+        partials = torch.empty((NSK_SUMSQ_PARTIALS,), dtype=torch.float32, device=dev)
+    if sumsq is None:
+        sumsq = torch.empty((1,), dtype=torch.float32, device=dev)
+    if scale is None:
+        scale = torch.empty((1,), dtype=torch.float32, device=dev)
+    sumsq.zero_()
+    for g in grads:
+        assert g.dtype == torch.float32
+        _check(lib().nsk_sumsq_accumulate(g.numel(), _ptr(g), _ptr(partials), _ptr(sumsq), _stream()),
+               "nsk_sumsq_accumulate")
+    _check(lib().nsk_clip_scale(_ptr(sumsq), float(max_norm), _ptr(scale), _stream()), "nsk_clip_scale")
+    return scale
