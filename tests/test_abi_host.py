@@ -106,6 +106,44 @@ def test_compute_calls_reject_bad_arguments_without_a_gpu():
     assert L.nsk_maxpool2d_fwd(ctypes.byref(pd), FAKE, FAKE, FAKE, None) == B.NSK_ERR_UNSUPPORTED
 
 
+def test_tail_entry_points_reject_bad_arguments_without_a_gpu():
+    L = B.lib()
+    # global average pool
+    assert L.nsk_global_avgpool_fwd(B.NSK_F32, B.NSK_NHWC, 0, 4, 2, 2, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_global_avgpool_fwd(B.NSK_F32, 5, 1, 4, 2, 2, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_global_avgpool_fwd(B.NSK_F32, B.NSK_NHWC, 1, 4, 2, 2, None, FAKE, None) == B.NSK_ERR_NULL
+    assert L.nsk_global_avgpool_bwd(B.NSK_BF16, B.NSK_NCHW, 1, 4, 2, 2, FAKE, ODD, 0, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_global_avgpool_bwd(B.NSK_BF16, B.NSK_NCHW, 1, 4, 2, 2, FAKE, FAKE, 3, None) == B.NSK_ERR_BAD_DESC
+    # fully connected layer: same workspace rules as the convolution it runs on
+    ld = B.nsk_linear_desc_t(128, 512, 10, B.NSK_BF16)
+    assert L.nsk_linear_workspace_bytes(ctypes.byref(ld), B.NSK_PASS_WGRAD) > 0
+    assert L.nsk_linear_workspace_bytes(ctypes.byref(B.nsk_linear_desc_t(0, 512, 10, B.NSK_BF16)), B.NSK_PASS_FWD) == 0
+    assert L.nsk_linear_fwd(None, FAKE, FAKE, None, FAKE, None, 0, None) == B.NSK_ERR_NULL
+    assert L.nsk_linear_fwd(ctypes.byref(B.nsk_linear_desc_t(4, 4, 4, 9)), FAKE, FAKE, None, FAKE, None, 0, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_linear_fwd(ctypes.byref(ld), FAKE, FAKE, ODD, FAKE, None, 0, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_linear_wgrad(ctypes.byref(ld), FAKE, FAKE, FAKE, FAKE, 0, None, 0, None) == B.NSK_ERR_WORKSPACE
+    assert L.nsk_linear_dgrad(ctypes.byref(ld), FAKE, FAKE, None, 0, FAKE, 1 << 30, None) == B.NSK_ERR_NULL
+    # loss
+    assert L.nsk_softmax_xent_fwd(B.NSK_F32, 0, 10, FAKE, FAKE, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_softmax_xent_fwd(B.NSK_F32, 4, 10, FAKE, None, FAKE, FAKE, None) == B.NSK_ERR_NULL
+    assert L.nsk_softmax_xent_bwd(B.NSK_F32, 4, 10, FAKE, FAKE, 1.0, ODD, None) == B.NSK_ERR_ALIGNMENT
+    # optimizers
+    assert L.nsk_sgd_momentum_step(0, FAKE, FAKE, FAKE, None, 0.1, 0.9, 0.0, None, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_sgd_momentum_step(4, FAKE, None, FAKE, None, 0.1, 0.9, 0.0, None, None) == B.NSK_ERR_NULL
+    assert L.nsk_sgd_momentum_step(4, FAKE, FAKE, ODD, None, 0.1, 0.9, 0.0, None, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_adamw_step(4, FAKE, FAKE, FAKE, FAKE, None, 0, 0.1, 0.9, 0.999, 1e-8, 0.0, None, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_adamw_step(4, FAKE, FAKE, FAKE, FAKE, None, 1, 0.1, 1.0, 0.999, 1e-8, 0.0, None, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_adamw_step(4, FAKE, FAKE, FAKE, None, None, 1, 0.1, 0.9, 0.999, 1e-8, 0.0, None, None) == B.NSK_ERR_NULL
+    tab = (B.nsk_param_t * 2)(B.nsk_param_t(0x10000, 0x10000, 0x10000, None, None, 8, 0.0),
+                              B.nsk_param_t(0x10000, 0x10004, 0x10000, None, None, 8, 0.0))
+    assert L.nsk_sgd_momentum_step_multi(2, tab, 0.1, 0.9, None, None) == B.NSK_ERR_ALIGNMENT   # nothing launched
+    assert L.nsk_sgd_momentum_step_multi(0, tab, 0.1, 0.9, None, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_adamw_step_multi(1, tab, 1, 0.1, 0.9, 0.999, 1e-8, None, None) == B.NSK_ERR_NULL     # AdamW needs state2
+    assert L.nsk_sumsq_accumulate(0, FAKE, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_clip_scale(FAKE, 0.0, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_clip_scale(None, 5.0, FAKE, None) == B.NSK_ERR_NULL
+
+
 def test_binding_raises_loudly_when_library_is_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libnsk.so"))
