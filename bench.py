@@ -82,7 +82,7 @@ def layer_table(repeats=20):
     ws = B.Workspace()
     gen_t = torch.Generator(device="cuda").manual_seed(7)
     head_flops = head_ms = 0.0
-    print(f"{'cfg':<5}{'layer':<34}{'pass':<7}{'us':>9}{'TFLOP/s':>9}{'%peak':>7}{'cap TF':>8}{'%cap':>6}")
+    print(f"{'cfg':<5}{'layer':<38}{'pass':<7}{'us':>9}{'TFLOP/s':>9}{'%peak':>7}{'cap TF':>8}{'%cap':>6}")
     rows = []
     for cfg, (dtype, N, C, H, W, K, R, stride, pad) in layers:
         dt = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -118,7 +118,7 @@ def layer_table(repeats=20):
             ms = e0.elapsed_time(e1) / repeats
             cap = min(peak, flops / byts * PEAK["hbm"])
             tf = flops / ms / 1e9
-            print(f"{cfg:<5}{name:<34}{pname:<7}{ms * 1e3:9.1f}{tf:9.1f}{100 * tf * 1e12 / peak:7.1f}{cap / 1e12:8.0f}{100 * tf * 1e12 / cap:6.1f}",
+            print(f"{cfg:<5}{name:<38}{pname:<7}{ms * 1e3:9.1f}{tf:9.1f}{100 * tf * 1e12 / peak:7.1f}{cap / 1e12:8.0f}{100 * tf * 1e12 / cap:6.1f}",
                   flush=True)
             rows.append({"config": cfg, "layer": name, "pass": pname, "us": ms * 1e3, "tflops": tf,
                          "frac_of_mfma_peak": tf * 1e12 / peak, "roofline_cap_tflops": cap / 1e12, "frac_of_cap": tf * 1e12 / cap})
