@@ -1,5 +1,5 @@
 // Short-reduction convolution for narrow bf16 layers: one, two or four taps and at most 256 reduction indices in
-// all.  These are the 1x1 layers of a bottleneck block (forward with any stride, and their backward-data pass) and
+// all (plus the nine taps of a strided 3x3 layer on 64 -> 64 channels).  These are the 1x1 layers of a bottleneck block (forward with any stride, and their backward-data pass) and
 // the residue classes of the backward-data pass of a stride-2 3x3 layer on 64 channels, on the large early feature
 // maps of the ResNet recipe the paper trains (section "Experiments and Discussion").
 //
@@ -282,7 +282,7 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
     }
 }
 
-int tile_rows(const IgemmArgs &a) { return a.Ktot == 256 ? 32 : 64; }
+int tile_rows(const IgemmArgs &a) { return a.Ktot >= 256 ? 32 : 64; }
 
 size_t pw_smem(const IgemmArgs &a, int tm)
 {
@@ -320,9 +320,14 @@ bool conv_pw_applicable(int dtype, const IgemmArgs &a)
 {
     if (getenv("NSK_NO_PW")) return false;
     if (dtype != NSK_BF16 || (a.accumulate && (a.stats || a.zero_cell))) return false;
-    if (!(a.ntaps == 1 || a.ntaps == 2 || a.ntaps == 4)) return false;
-    if (!(a.Cs == 64 || a.Cs == 128 || a.Cs == 256) || a.Ktot != a.ntaps * a.Cs || a.Ktot > 256) return false;
-    if (a.Ngemm % 64 != 0 || a.Ngemm > 64 * PW_MAX_NCH || (long)a.Ngemm * a.Ktot > 32768) return false;
+    if (a.Ktot != a.ntaps * a.Cs || a.Ngemm % 64 != 0 || a.Ngemm > 64 * PW_MAX_NCH) return false;
+    if (a.ntaps == 9) {
+        // a whole 3x3 filter on 64 -> 64 channels (the stride-2 layer: stride 1 has a kernel that reuses the halo)
+        if (a.Cs != 64 || a.Ngemm != 64 || (a.mult_h == 1 && a.mult_w == 1)) return false;
+    } else {
+        if (!(a.ntaps == 1 || a.ntaps == 2 || a.ntaps == 4)) return false;
+        if (!(a.Cs == 64 || a.Cs == 128 || a.Cs == 256) || a.Ktot > 256 || (long)a.Ngemm * a.Ktot > 32768) return false;
+    }
     if (a.Co % 8 != 0 || (uintptr_t)a.out % 16 != 0 || (uintptr_t)a.src % 16 != 0 || (uintptr_t)a.wpk % 16 != 0) return false;
     // 32-bit byte offsets below the out-of-range marker
     if ((long)a.Nimg * a.Ho * a.Wo * a.Co * 2 >= (long)PW_OOB || (long)a.src_bytes >= (long)PW_OOB) return false;
@@ -355,6 +360,7 @@ int launch_conv_pw(const IgemmArgs &a, hipStream_t stream)
     case 16 * 8 + 1: return launch_pw<16, 1, 1>(pa, stream);
     case 16 * 8 + 2: return launch_pw<16, 1, 2>(pa, stream);
     case 16 * 8 + 4: return launch_pw<16, 1, 4>(pa, stream);
+    case 36 * 8 + 9: return launch_pw<36, 1, 9>(pa, stream);
     default: return NSK_ERR_UNSUPPORTED;
     }
 }
