@@ -279,6 +279,33 @@ int nsk_adamw_step_multi(int count, const nsk_param_t *params, int step, float l
 int nsk_sumsq_accumulate(size_t n, const float *g, float *partials, float *sumsq, void *stream);
 int nsk_clip_scale(const float *sumsq, float max_norm, float *scale, void *stream);
 
+/* ---------------------------------------------------------------------------------------------------------------
+ * Device memory pool and cache (section "Caching and Pooling"): what hands out the raw pointers every entry point
+ * above takes, for callers that have no allocator of their own.  Host code; no entry point above uses it.
+ *
+ * Pool: a dictionary from a byte size (rounded up to 256) to a list of free pointers of exactly that size.
+ * nsk_pool_get pops one, or allocates when the list is empty; nsk_pool_put appends the pointer to its size's list
+ * instead of freeing it.  A step that requests the same sizes every iteration allocates nothing from the second
+ * iteration on.  Cache: nsk_pool_cached maps a name to a buffer that lives until the pool is destroyed (the
+ * paper keeps parameter gradients this way); *created (may be NULL) says whether this call allocated it, so the
+ * caller can zero it once.  kind: NSK_POOL_DEVICE (hipMalloc on the current device) or NSK_POOL_HOST (plain host
+ * memory, 256-byte aligned).  Not thread-safe.  nsk_pool_put returns NSK_ERR_BAD_DESC for a pointer that is not
+ * out on loan from this pool (foreign, or returned twice); nsk_pool_cached for a known name with another size.
+ * nsk_pool_destroy frees everything the pool ever allocated, on loan or not.  Contents of a buffer are whatever its
+ * last user left.
+ * --------------------------------------------------------------------------------------------------------------- */
+enum { NSK_POOL_DEVICE = 0, NSK_POOL_HOST = 1 };
+typedef struct nsk_pool nsk_pool_t;
+int nsk_pool_create(int kind, nsk_pool_t **pool);
+int nsk_pool_get(nsk_pool_t *pool, size_t bytes, void **ptr);
+int nsk_pool_put(nsk_pool_t *pool, void *ptr);
+int nsk_pool_cached(nsk_pool_t *pool, const char *name, size_t bytes, void **ptr, int *created);
+/* Any output pointer may be NULL.  allocations = calls that reached the backing allocator; hits = requests served
+ * from a free list. */
+int nsk_pool_stats(const nsk_pool_t *pool, size_t *bytes_allocated, size_t *allocations, size_t *requests,
+                   size_t *hits);
+int nsk_pool_destroy(nsk_pool_t *pool);
+
 #ifdef __cplusplus
 }
 #endif

@@ -147,6 +147,19 @@ def lib() -> ctypes.CDLL:
         L.nsk_sumsq_accumulate.argtypes = [sz, vp, vp, vp, vp]
         L.nsk_clip_scale.restype = ci
         L.nsk_clip_scale.argtypes = [vp, cf, vp, vp]
+        vpp, szp = ctypes.POINTER(vp), ctypes.POINTER(sz)
+        L.nsk_pool_create.restype = ci
+        L.nsk_pool_create.argtypes = [ci, vpp]
+        L.nsk_pool_get.restype = ci
+        L.nsk_pool_get.argtypes = [vp, sz, vpp]
+        L.nsk_pool_put.restype = ci
+        L.nsk_pool_put.argtypes = [vp, vp]
+        L.nsk_pool_cached.restype = ci
+        L.nsk_pool_cached.argtypes = [vp, ctypes.c_char_p, sz, vpp, ip]
+        L.nsk_pool_stats.restype = ci
+        L.nsk_pool_stats.argtypes = [vp, szp, szp, szp, szp]
+        L.nsk_pool_destroy.restype = ci
+        L.nsk_pool_destroy.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -159,7 +172,9 @@ EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d
            "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd",
            "nsk_global_avgpool_fwd", "nsk_global_avgpool_bwd", "nsk_linear_workspace_bytes", "nsk_linear_fwd",
            "nsk_linear_dgrad", "nsk_linear_wgrad", "nsk_softmax_xent_fwd", "nsk_softmax_xent_bwd",
-           "nsk_sgd_momentum_step", "nsk_adamw_step", "nsk_sgd_momentum_step_multi", "nsk_adamw_step_multi", "nsk_sumsq_accumulate", "nsk_clip_scale")
+           "nsk_sgd_momentum_step", "nsk_adamw_step", "nsk_sgd_momentum_step_multi", "nsk_adamw_step_multi", "nsk_sumsq_accumulate", "nsk_clip_scale",
+           "nsk_pool_create", "nsk_pool_get", "nsk_pool_put", "nsk_pool_cached", "nsk_pool_stats", "nsk_pool_destroy")
+NSK_POOL_DEVICE, NSK_POOL_HOST = 0, 1
 NSK_SUMSQ_PARTIALS = 256
 
 
@@ -585,3 +600,37 @@ def clip_scale(grads, max_norm, partials=None, sumsq=None, scale=None):
                "nsk_sumsq_accumulate")
     _check(lib().nsk_clip_scale(_ptr(sumsq), float(max_norm), _ptr(scale), _stream()), "nsk_clip_scale")
     return scale
+
+
+# ------------------------------------------------------------------------------------ memory pool
+
+class Pool:
+    """Size-keyed pool of raw buffers plus a name-keyed cache (nsk_pool_*).  Pointers are plain integers."""
+
+    def __init__(self, kind=NSK_POOL_DEVICE):
+        self._h = ctypes.c_void_p()
+        _check(lib().nsk_pool_create(kind, ctypes.byref(self._h)), "nsk_pool_create")
+
+    def get(self, nbytes: int) -> int:
+        p = ctypes.c_void_p()
+        _check(lib().nsk_pool_get(self._h, int(nbytes), ctypes.byref(p)), "nsk_pool_get")
+        return p.value
+
+    def put(self, ptr: int):
+        _check(lib().nsk_pool_put(self._h, ctypes.c_void_p(ptr)), "nsk_pool_put")
+
+    def cached(self, name: str, nbytes: int):
+        """(pointer, created)"""
+        p, c = ctypes.c_void_p(), ctypes.c_int()
+        _check(lib().nsk_pool_cached(self._h, name.encode(), int(nbytes), ctypes.byref(p), ctypes.byref(c)), "nsk_pool_cached")
+        return p.value, bool(c.value)
+
+    def stats(self) -> dict:
+        v = [ctypes.c_size_t() for _ in range(4)]
+        _check(lib().nsk_pool_stats(self._h, *[ctypes.byref(x) for x in v]), "nsk_pool_stats")
+        return dict(zip(("bytes_allocated", "allocations", "requests", "hits"), (x.value for x in v)))
+
+    def destroy(self):
+        if self._h:
+            _check(lib().nsk_pool_destroy(self._h), "nsk_pool_destroy")
+            self._h = ctypes.c_void_p()
