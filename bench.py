@@ -13,7 +13,9 @@ residual block (N=128, C=K=64, 32x32), NHWC.  Prints ONE JSON line:
                workload, bounded to about 10-30 s of CPU work
 
 Other workloads: --config {1,2,3,4,5} [--stage A|B] [--batch N].  --breakdown prints a per-call
-table to stderr.  Runs on one GPU only.
+table to stderr.  --train-step adds a "train_step" object: the same workload followed by the head of the network,
+the loss, their backward passes and the SGD update of every parameter, timed as one HIP graph.  --no-fusion /
+--no-stats switch the fused batch-norm statistics and the ReLU-mask hand-over off (A/B runs).  Runs on one GPU only.
 
 --layers prints, instead, one line per distinct convolution layer of configurations 2-5 at its full
 size: microseconds and TFLOP/s of forward, backward-data and backward-weight, the fraction of the

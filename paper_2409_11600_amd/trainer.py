@@ -11,6 +11,7 @@ All buffers are created in the constructor; a step allocates nothing.
 """
 from __future__ import annotations
 
+import contextlib
 from typing import Dict, List, Optional
 
 import numpy as np
@@ -97,7 +98,7 @@ class GpuTrainer:
             st = self.streams[gname] if self.streams else None
             if st is not None:
                 st.wait_stream(main)
-            with torch.cuda.stream(st) if st is not None else _null():
+            with torch.cuda.stream(st) if st is not None else contextlib.nullcontext():
                 if self.optimizer == "adamw":
                     B.adamw_step_multi(self.tables[gname], self.t, self.lr, grad_scale=scale)
                 else:
@@ -110,10 +111,3 @@ class GpuTrainer:
         self.backward()
         self.update()
 
-
-class _null:
-    def __enter__(self):
-        return None
-
-    def __exit__(self, *a):
-        return False

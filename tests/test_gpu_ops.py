@@ -158,7 +158,7 @@ PW_SHAPES = [
 def test_conv_pointwise_kernel(i, layout, monkeypatch):
     monkeypatch.setenv("NSK_PW_MIN_ROWS", "1")
     N, C, H, W, K, R, S, st, pd, dl = PW_SHAPES[i]
-    if layout == "nchw" and N * H * W > 100000:
+    if layout == B.NSK_NCHW and N * H * W > 100000:
         pytest.skip("large case once (NHWC)")
     print(f"pointwise conv case {i} {PW_SHAPES[i]} layout={layout}", flush=True)
     dtype = "bf16"

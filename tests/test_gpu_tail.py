@@ -120,7 +120,7 @@ def test_softmax_cross_entropy(i, dtype):
     torch.cuda.synchronize()
     dz_check()
     want_loss, want_per = T.softmax_xent_fwd(z, labels)
-    assert max_rel_err(host(per), want_per) <= 1e-5 + (0 if K > 1 else 1)
+    assert max_rel_err(host(per), want_per) <= 1e-5
     assert abs(float(loss.item()) - want_loss) <= 1e-5 * max(1.0, abs(want_loss))
     assert max_rel_err(host(dz_view), T.softmax_xent_bwd(z, labels, 1.5)) <= TOL[dtype]
 
