@@ -150,6 +150,17 @@ PW_SHAPES = [
     (2, 64, 12, 12, 128, 3, 3, 2, 1, 1),       # 128 channels: classes with 1 and 2 taps (the 4-tap class is generic)
     (2, 64, 12, 14, 64, 2, 2, 2, 0, 1),        # 2x2 stride-2 filter: four taps forward, one tap per class backward
     (1, 128, 9, 9, 64, 1, 2, 1, 0, 1),         # two taps of 128 channels forward
+    # narrow outputs (16 and 32 channels): the layers of the CIFAR-sized network
+    (4, 16, 12, 12, 16, 3, 3, 1, 1, 1),        # 16 -> 16 3x3: half of each MFMA tile is padding
+    (4, 16, 12, 12, 32, 3, 3, 2, 1, 1),        # 16 -> 32 stride 2; backward-data classes of 1, 2, 4 taps on 32 channels
+    (4, 16, 10, 10, 32, 1, 1, 2, 0, 1),        # its projection shortcut (zero fill of the 2x2 cells in backward-data)
+    (3, 32, 9, 9, 32, 3, 3, 1, 1, 1),          # 32 -> 32 3x3
+    (3, 32, 10, 10, 64, 3, 3, 2, 1, 1),        # 32 -> 64 stride 2: 64-channel chunk forward, 32-channel outputs backward
+    (3, 32, 11, 9, 64, 1, 1, 2, 0, 1),         # and its projection, odd extents
+    (2, 64, 9, 9, 16, 1, 1, 1, 0, 1),          # 64 -> 16: four k-steps, 16-channel output
+    (2, 16, 8, 8, 16, 2, 2, 2, 0, 1),          # 2x2 stride 2 on 16 channels: four taps forward
+    (2, 32, 6, 7, 32, 1, 2, 1, 0, 1),          # two taps of 32 channels
+    (300, 16, 32, 32, 16, 3, 3, 1, 1, 1),      # the CIFAR layer itself at more than full batch: several tiles per wavefront
 ]
 
 
@@ -178,6 +189,8 @@ def test_conv_pointwise_kernel(i, layout, monkeypatch):
     y_check()
     dx_check()
     assert torch.equal(y_view, y1)
+    # one row of partial sums per wavefront of this kernel's fixed grid: the forward pass really took it
+    assert stats.shape[1] == 1024 or (C, K, R) == (64, 128, 3)     # (nine taps into 128 channels: generic kernel)
     yh = to_host(y_view, layout)
     assert max_rel_err(yh, oracle.conv2d_fwd(x, w, st, pd, dl)) <= tol
     sums = stats.double().sum(dim=1).cpu().numpy()             # [2, K]
