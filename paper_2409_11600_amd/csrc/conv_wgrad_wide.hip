@@ -293,7 +293,8 @@ bool wgrad_wide_applicable(int dtype, const WgradArgs &a)
 {
     if (dtype != NSK_BF16 || getenv("NSK_NO_WIDE") != nullptr) return false;
     // a thread's 8 x-columns must share one tap (C % 8), a dy row is loaded in 16-byte pieces up to the tile height
-    if (a.C % 8 != 0 || a.K % 64 != 0 || (a.K % 256 != 0 && a.K != 64)) return false;
+    // (a tile of 64 rows also serves fewer output channels: the missing rows are neither loaded nor stored)
+    if (a.C % 8 != 0 || a.K % 8 != 0 || (a.K % 256 != 0 && a.K > 64)) return false;
     if (((uintptr_t)a.x | (uintptr_t)a.dy) & 15) return false;
     const long long pq = (long long)a.P * a.Q;
     if ((long long)a.L >= (1LL << 30) || (long long)a.L * pq >= (1LL << 40)) return false;   // exactness of the reciprocal division

@@ -87,6 +87,11 @@ WIDE_SHAPES = [
     (1, 64, 33, 17, 64, 3, 3, 1, 2, 2),        # dilation 2
     (2, 3, 20, 24, 64, 7, 7, 2, 3, 1),         # image stem: space-to-depth, then the large-tile backward-weight kernel on 16 channels
     (2, 32, 12, 10, 64, 3, 3, 2, 1, 1),        # 32 input channels (four taps per 128-column tile)
+    (4, 16, 12, 12, 16, 3, 3, 1, 1, 1),        # 16 -> 16: a quarter of the 64-row backward-weight tile is live
+    (4, 16, 12, 12, 32, 3, 3, 2, 1, 1),        # 16 -> 32 stride 2
+    (3, 32, 9, 9, 32, 3, 3, 1, 1, 1),          # 32 -> 32
+    (4, 16, 10, 10, 32, 1, 1, 2, 0, 1),        # 1x1 projection, 16 columns
+    (2, 24, 9, 9, 40, 3, 3, 1, 1, 1),          # 40 output channels, 24 input channels
 ]
 
 
