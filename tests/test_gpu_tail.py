@@ -239,3 +239,50 @@ def test_host_validation_of_the_tail_entry_points():
                             None, None) == B.NSK_ERR_BAD_DESC        # steps count from 1
     assert L.nsk_adamw_step(4, w.data_ptr() + 4, w.data_ptr(), w.data_ptr(), w.data_ptr(), None, 1, 0.1, 0.9, 0.999, 1e-8,
                             0.0, None, None) == B.NSK_ERR_ALIGNMENT
+
+
+# ----------------------------------------------------------------------------- full sizes (the shapes the bench's --train-step runs)
+
+def test_tail_at_full_size_of_config_5_stage_a():
+    """Average pool over [128, 256, 56, 56] bf16 (205 MB), 256 -> 1000 classifier on 128 samples, loss, and one
+    SGD-momentum launch over 25.6 M parameters (a ResNet-50's worth) in one table entry: all compared in full."""
+    N, C, H, W, K = 128, 256, 56, 56, 1000
+    print(f"full-size tail {N, C, H, W, K}", flush=True)
+    x = gen.to_bf16_grid(gen.normal(2200, 0, (N, C, H, W)) + 0.25)
+    gx = to_gpu(x, "bf16", B.NSK_NHWC)
+    pooled = B.global_avgpool_fwd(gx, B.NSK_NHWC)
+    torch.cuda.synchronize()
+    want_pooled = T.global_avgpool_fwd(x)
+    assert max_rel_err(host(pooled), want_pooled) <= TOL["bf16"]
+    dy = gen.to_bf16_grid(gen.normal(2200, 1, (N, C)))
+    dx = B.global_avgpool_bwd(dev(dy, "bf16"), (N, C, H, W), B.NSK_NHWC)
+    torch.cuda.synchronize()
+    got = to_host(dx, B.NSK_NHWC)
+    del dx
+    assert max_rel_err(got[::7], T.global_avgpool_bwd(dy, (N, C, H, W))[::7]) <= TOL["bf16"]
+    del got
+    ph = gen.to_bf16_grid(want_pooled)
+    w = gen.to_bf16_grid(gen.normal(2200, 2, (K, C)) / np.sqrt(C))
+    b = (0.1 * gen.normal(2200, 3, (K,))).astype(np.float32)
+    logits = B.linear_fwd(dev(ph, "bf16"), dev(w, "bf16"), dev(b))
+    labels = (gen.uniform(2200, 4, (N,)) * K).astype(np.int32) % K
+    torch.cuda.synchronize()
+    zh = host(logits)
+    assert max_rel_err(zh, T.linear_fwd(ph, w, b)) <= TOL["bf16"]
+    loss, _ = B.softmax_xent_fwd(logits, torch.from_numpy(labels).cuda())
+    dz = B.softmax_xent_bwd(logits, torch.from_numpy(labels).cuda())
+    torch.cuda.synchronize()
+    want_loss, _ = T.softmax_xent_fwd(zh, labels)
+    assert abs(float(loss.item()) - want_loss) <= 1e-5 * want_loss
+    assert max_rel_err(host(dz), T.softmax_xent_bwd(zh, labels)) <= TOL["bf16"]
+    n = 25_557_032
+    w0 = gen.normal(2201, 0, (n,)).astype(np.float32)
+    g0 = gen.normal(2201, 1, (n,)).astype(np.float32)
+    v0 = (0.1 * gen.normal(2201, 2, (n,))).astype(np.float32)
+    gw, gg, gv = dev(w0), dev(g0), dev(v0)
+    lp = torch.empty(n, dtype=torch.bfloat16, device="cuda:0")
+    B.sgd_momentum_step_multi(B.param_table([(gw, gg, gv, None, lp, 1e-4)]), 0.1, 0.9)
+    torch.cuda.synchronize()
+    ww, vv, _ = T.sgd_momentum_step(w0, g0, v0, 0.1, 0.9, 1e-4)
+    assert max_rel_err(host(gw), ww) <= 1e-5 and max_rel_err(host(gv), vv) <= 1e-5
+    assert not gg.any() and torch.equal(lp, gw.to(torch.bfloat16))
