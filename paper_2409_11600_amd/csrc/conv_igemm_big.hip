@@ -29,10 +29,12 @@ constexpr int GB_ROW = 144;          // LDS bytes per row: 128 + 16 pad (conflic
 constexpr unsigned GB_OOB = 0xF0000000u;
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kBigMultiMax = 4;
 
+// One block's work: tile `b` of the launch described by `a` (b runs over tiles_m * tiles_n).
 template <int BN>
-__global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const int tiles_m, const int tiles_n,
-                                                        const unsigned out_bytes)
+__device__ __forceinline__ void igemm_big_block(const IgemmArgs &a, const int b, const int tiles_m, const int tiles_n,
+                                                const unsigned out_bytes)
 {
     constexpr int FM = BN == 128 ? 4 : 2, FN = 2;                 // 32x32 accumulators per wavefront
     constexpr int WM = FM * 32;
@@ -57,7 +59,7 @@ __global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const
     // row block are given ids that differ by a multiple of 8
     int mt, nt;
     {
-        const int b = blockIdx.x, grp = b / (8 * tiles_n), r = b - grp * 8 * tiles_n;
+        const int grp = b / (8 * tiles_n), r = b - grp * 8 * tiles_n;
         const int full = tiles_m / 8;   // groups of 8 row blocks; the tail group is laid out plainly
         if (grp < full) {
             mt = grp * 8 + (r & 7);
@@ -319,6 +321,32 @@ __global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const
     }
 }
 
+template <int BN>
+__global__ __launch_bounds__(512) void igemm_big_kernel(const IgemmArgs a, const int tiles_m, const int tiles_n,
+                                                        const unsigned out_bytes)
+{
+    igemm_big_block<BN>(a, blockIdx.x, tiles_m, tiles_n, out_bytes);
+}
+
+// Several launches in one: the residue classes of a strided backward-data pass (same source, same output tensor, same
+// column count; each class with its own taps, filter and row count).  Each class alone leaves part of the chip idle
+// and pays its own start-up; together their tiles fill it.  Block ids are assigned class by class, longest reduction
+// first.
+struct BigMulti {
+    IgemmArgs a[kBigMultiMax];
+    int first[kBigMultiMax + 1];   // first block id of each class
+    int tiles_m[kBigMultiMax];
+    int count;
+};
+
+template <int BN>
+__global__ __launch_bounds__(512) void igemm_big_multi_kernel(const BigMulti m, const int tiles_n, const unsigned out_bytes)
+{
+    int cls = 0;
+    while (cls + 1 < m.count && (int)blockIdx.x >= m.first[cls + 1]) ++cls;
+    igemm_big_block<BN>(m.a[cls], (int)blockIdx.x - m.first[cls], m.tiles_m[cls], tiles_n, out_bytes);
+}
+
 template <int BN> int smem_bytes() { return 2 * (GB_BM + BN) * GB_ROW + 256 * 4; }
 
 }  // namespace
@@ -371,6 +399,77 @@ int launch_igemm_big(const IgemmArgs &a, hipStream_t stream)
         hipLaunchKernelGGL(igemm_big_kernel<128>, grid, dim3(512), smem_bytes<128>(), stream, a, tiles_m, tiles_n, out_bytes);
     else
         hipLaunchKernelGGL(igemm_big_kernel<64>, grid, dim3(512), smem_bytes<64>(), stream, a, tiles_m, tiles_n, out_bytes);
+    return check_launch();
+}
+
+
+// The shape tests of igemm_big_applicable without its size thresholds.
+static bool big_shape_ok(const IgemmArgs &a)
+{
+    if (a.Cs % GB_BK != 0 || a.Ngemm % 64 != 0 || a.Co % 8 != 0 || a.ntaps > 64 || a.ntaps < 1) return false;
+    if (((uintptr_t)a.src | (uintptr_t)a.wpk | (uintptr_t)a.out) & 15) return false;
+    const long long out_bytes = (long long)a.Nimg * a.Ho * a.Wo * a.Co * 2;
+    return (unsigned long long)a.src_bytes < GB_OOB && (unsigned long long)a.wpk_bytes < GB_OOB && out_bytes < (long long)GB_OOB;
+}
+
+bool igemm_big_multi_applicable(int dtype, const IgemmArgs *a, int count)
+{
+    if (dtype != NSK_BF16 || getenv("NSK_NO_BIG") != nullptr || getenv("NSK_NO_BIG_MULTI") != nullptr) return false;
+    if (count < 2 || count > kBigMultiMax) return false;
+    long long tiles = 0;
+    int longest = 0;
+    for (int i = 0; i < count; ++i) {
+        if (!big_shape_ok(a[i]) || a[i].stats || a[i].zero_cell) return false;
+        if (a[i].Ngemm != a[0].Ngemm || a[i].out != a[0].out || a[i].Co != a[0].Co || a[i].Nimg != a[0].Nimg ||
+            a[i].Ho != a[0].Ho || a[i].Wo != a[0].Wo)
+            return false;
+        tiles += (long long)ceil_div(a[i].M, GB_BM) * ceil_div(a[i].Ngemm, a[i].Ngemm >= 128 ? 128 : 64);
+        if (a[i].Ktot > longest) longest = a[i].Ktot;
+    }
+    const char *e = getenv("NSK_BIG_MIN_TILES");   // test hook, as in igemm_big_applicable
+    if (e) return tiles >= atoll(e);
+    return tiles >= 160 && a[0].Ngemm >= 128 && longest >= 8 * GB_BK;
+}
+
+int launch_igemm_big_multi(const IgemmArgs *a, int count, hipStream_t stream)
+{
+    const int bn = a[0].Ngemm >= 128 ? 128 : 64;
+    const int tiles_n = ceil_div(a[0].Ngemm, bn);
+    // longest reduction first
+    int order[kBigMultiMax];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && a[order[j]].Ktot > a[order[j - 1]].Ktot; --j) {
+            const int t = order[j];
+            order[j] = order[j - 1];
+            order[j - 1] = t;
+        }
+    BigMulti m{};
+    m.count = count;
+    int blocks = 0;
+    for (int i = 0; i < count; ++i) {
+        m.a[i] = a[order[i]];
+        m.tiles_m[i] = ceil_div(m.a[i].M, GB_BM);
+        m.first[i] = blocks;
+        blocks += m.tiles_m[i] * tiles_n;
+    }
+    m.first[count] = blocks;
+    const unsigned out_bytes = (unsigned)((long long)a[0].Nimg * a[0].Ho * a[0].Wo * a[0].Co * 2);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)igemm_big_multi_kernel<128>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes<128>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)igemm_big_multi_kernel<64>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_bytes<64>());
+        if (e != hipSuccess) {
+            set_last_hip_error(e);
+            return NSK_ERR_HIP;
+        }
+        attr_set = true;
+    }
+    if (bn == 128)
+        hipLaunchKernelGGL(igemm_big_multi_kernel<128>, dim3(blocks), dim3(512), smem_bytes<128>(), stream, m, tiles_n, out_bytes);
+    else
+        hipLaunchKernelGGL(igemm_big_multi_kernel<64>, dim3(blocks), dim3(512), smem_bytes<64>(), stream, m, tiles_n, out_bytes);
     return check_launch();
 }
 

@@ -44,8 +44,16 @@ struct PackArgs {
     int tap_off[kMaxTaps];
 };
 
-template <typename T> __global__ __launch_bounds__(256) void pack_filter_kernel(const PackArgs a)
+// Up to four packings in one launch (blockIdx.y names the packing): the residue classes of a strided backward-data
+// pass each need their own packed filter, and a launch per class costs more than the copy.
+constexpr int kPackMulti = 4;
+struct PackMulti {
+    PackArgs e[kPackMulti];
+};
+
+template <typename T> __global__ __launch_bounds__(256) void pack_filter_kernel(const PackMulti m)
 {
+    const PackArgs &a = m.e[blockIdx.y];
     const long total = (long)a.Nn * a.ntaps * a.Cs;
     const long i = (long)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
@@ -112,26 +120,41 @@ int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, in
     return check_launch();
 }
 
+int launch_pack_filters(int dtype, int count, const void *w, void *const *out, int Nn, const int *ntaps, int Cs, long sn,
+                        long sc, const int (*tap_off_host)[kMaxTaps], hipStream_t stream)
+{
+    if (count < 1 || count > kPackMulti) return NSK_ERR_BAD_DESC;
+    PackMulti m{};
+    long most = 0;
+    for (int k = 0; k < count; ++k) {
+        PackArgs &a = m.e[k];
+        a.w = w;
+        a.out = out[k];
+        a.Nn = Nn;
+        a.ntaps = ntaps[k];
+        a.Cs = Cs;
+        a.sn = sn;
+        a.sc = sc;
+        for (int t = 0; t < kMaxTaps; ++t) a.tap_off[t] = t < ntaps[k] ? tap_off_host[k][t] : 0;
+        const long total = (long)Nn * ntaps[k] * Cs;
+        if (total > most) most = total;
+    }
+    if (most == 0) return NSK_OK;
+    dim3 grid((unsigned)((most + 255) / 256), (unsigned)count);
+    if (dtype == NSK_BF16)
+        hipLaunchKernelGGL((pack_filter_kernel<bf16_t>), grid, dim3(256), 0, stream, m);
+    else
+        hipLaunchKernelGGL((pack_filter_kernel<float>), grid, dim3(256), 0, stream, m);
+    return check_launch();
+}
+
 int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, int Cs, long sn, long sc,
                        const int *tap_off_host, hipStream_t stream)
 {
-    PackArgs a;
-    a.w = w;
-    a.out = out;
-    a.Nn = Nn;
-    a.ntaps = ntaps;
-    a.Cs = Cs;
-    a.sn = sn;
-    a.sc = sc;
-    for (int t = 0; t < kMaxTaps; ++t) a.tap_off[t] = t < ntaps ? tap_off_host[t] : 0;
-    const long total = (long)Nn * ntaps * Cs;
-    if (total == 0) return NSK_OK;
-    dim3 grid((unsigned)((total + 255) / 256));
-    if (dtype == NSK_BF16)
-        hipLaunchKernelGGL((pack_filter_kernel<bf16_t>), grid, dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL((pack_filter_kernel<float>), grid, dim3(256), 0, stream, a);
-    return check_launch();
+    int taps[1][kMaxTaps];
+    for (int t = 0; t < kMaxTaps; ++t) taps[0][t] = t < ntaps ? tap_off_host[t] : 0;
+    void *outs[1] = {out};
+    return launch_pack_filters(dtype, 1, w, outs, Nn, &ntaps, Cs, sn, sc, taps, stream);
 }
 
 }  // namespace nsk

@@ -395,7 +395,15 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
             zero_cell = conv_pw_applicable(g.dtype, a);
         }
     }
+    const long w_sn = nchw ? (long)g.R * g.S : 1L, w_sc = nchw ? (long)g.C * g.R * g.S : (long)g.R * g.S * g.C;
     size_t filt_off = p.filt;
+    // classes with taps: filters are packed first, then the launches follow (one for all classes where the large-tile
+    // kernel takes them together)
+    IgemmArgs pending[4];
+    int n_pending = 0;
+    const bool may_merge = g.sh * g.sw <= 4;
+    int pk_taps[4][kMaxTaps], pk_nt[4];
+    void *pk_out[4];
     for (int ca = 0; ca < g.sh; ++ca)
         for (int cb = 0; cb < g.sw; ++cb) {
             IgemmArgs a{};
@@ -408,18 +416,27 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
                     NSK_TRY(launch_zero_class(g.dtype, dst, g.N, g.H, g.W, g.C, a.Mi, a.Mj, g.sh, ca, g.sw, cb, st));
                 continue;
             }
-            // packed filter of this class: [c][tap][k]
-            if (nchw)
-                NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, (long)g.R * g.S,
-                                           (long)g.C * g.R * g.S, tap_off, st));
-            else
-                NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, 1L, (long)g.R * g.S * g.C,
-                                           tap_off, st));
+            // packed filter of this class: [c][tap][k] with element (c, t, k) = w[c*sn + tap_off[t] + k*sc]
             a.src = src; a.wpk = ws + filt_off; a.out = dst;
             a.zero_cell = zero_cell ? 1 : 0;
-            NSK_TRY(launch_igemm(g.dtype, a, st));
+            if (may_merge) {
+                for (int t = 0; t < kMaxTaps; ++t) pk_taps[n_pending][t] = t < nt ? tap_off[t] : 0;
+                pk_nt[n_pending] = nt;
+                pk_out[n_pending] = ws + filt_off;
+                pending[n_pending++] = a;
+            } else {
+                NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, w_sn, w_sc, tap_off, st));
+                NSK_TRY(launch_igemm(g.dtype, a, st));
+            }
             filt_off += align_up((size_t)g.C * nt * g.K * g.es);
         }
+    // one packing launch for all classes, then their multiplies
+    if (n_pending > 0) NSK_TRY(launch_pack_filters(g.dtype, n_pending, w, pk_out, g.C, pk_nt, g.K, w_sn, w_sc, pk_taps, st));
+    if (n_pending > 1 && igemm_big_multi_applicable(g.dtype, pending, n_pending)) {
+        NSK_TRY(launch_igemm_big_multi(pending, n_pending, st));
+    } else {
+        for (int i = 0; i < n_pending; ++i) NSK_TRY(launch_igemm(g.dtype, pending[i], st));
+    }
     if (nchw) NSK_TRY(launch_nhwc_to_nchw(g.dtype, dst, dx, g.N, g.C, g.H, g.W, accumulate, st));
     return NSK_OK;
 }

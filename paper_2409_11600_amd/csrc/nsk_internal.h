@@ -93,6 +93,9 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a);
 bool igemm_big_applicable(int dtype, const IgemmArgs &a);
 int launch_igemm_big(const IgemmArgs &a, hipStream_t stream);
 int igemm_big_stats_rows(const IgemmArgs &a);
+// the residue classes of one strided backward-data pass (2..4 argument sets on the same tensors) in one launch
+bool igemm_big_multi_applicable(int dtype, const IgemmArgs *a, int count);
+int launch_igemm_big_multi(const IgemmArgs *a, int count, hipStream_t stream);
 // bf16 layers with one, two or four taps and at most 256 reduction indices (memory-bound: filter resident in LDS,
 // pixels loaded straight into MFMA operand registers)
 bool conv_pw_applicable(int dtype, const IgemmArgs &a);
@@ -167,6 +170,9 @@ int launch_nhwc_to_nchw(int dtype, const void *src, void *dst, int N, int C, int
 // out[n][t][c] = w[n*sn + tap_off[t] + c*sc] for n < Nn, t < ntaps, c < Cs.
 int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, int Cs, long sn,
                        long sc, const int *tap_off_host, hipStream_t stream);
+// The same for up to four tap subsets of one filter in one launch: out[k][n][t][c] with ntaps[k] taps tap_off_host[k][.].
+int launch_pack_filters(int dtype, int count, const void *w, void *const *out, int Nn, const int *ntaps, int Cs, long sn,
+                        long sc, const int (*tap_off_host)[kMaxTaps], hipStream_t stream);
 
 // out[img][i*osh + oa][j*osw + ob][0..Co) = 0 for i < Mi, j < Mj (NHWC).
 int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, int Mi, int Mj, int osh, int oa, int osw,

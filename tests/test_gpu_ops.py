@@ -92,6 +92,9 @@ WIDE_SHAPES = [
     (3, 32, 9, 9, 32, 3, 3, 1, 1, 1),          # 32 -> 32
     (4, 16, 10, 10, 32, 1, 1, 2, 0, 1),        # 1x1 projection, 16 columns
     (2, 24, 9, 9, 40, 3, 3, 1, 1, 1),          # 40 output channels, 24 input channels
+    (2, 128, 10, 10, 128, 3, 3, 2, 1, 1),      # stride 2, 128 columns: the four backward-data classes in one launch
+    (3, 64, 9, 11, 64, 3, 3, 2, 1, 1),         # the same with 64 columns on odd extents (classes of different sizes)
+    (2, 64, 8, 8, 128, 2, 2, 2, 0, 1),         # 2x2 stride 2: four one-tap classes
 ]
 
 
