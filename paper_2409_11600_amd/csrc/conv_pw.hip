@@ -1,20 +1,25 @@
-// Short-reduction convolution for narrow bf16 layers: one, two or four taps and at most 256 reduction indices in
-// all (plus the nine taps of a strided 3x3 layer on 64 -> 64 channels).  These are the 1x1 layers of a bottleneck block (forward with any stride, and their backward-data pass) and
-// the residue classes of the backward-data pass of a stride-2 3x3 layer on 64 channels, on the large early feature
-// maps of the ResNet recipe the paper trains (section "Experiments and Discussion").
+// Short-reduction convolution for bf16 layers whose whole reduction fits in a lane's registers: one, two, four or
+// nine taps of 16 to 256 channels, at most 256 reduction indices (288 / 576 for a 3x3 filter on 32 / 64 channels).
+// These are the 1x1 layers of a bottleneck block in both directions, the residue classes of the backward-data pass
+// of a stride-2 layer, the strided 3x3 64 -> 64 layer, and every 16- and 32-channel layer of the CIFAR-sized network
+// of the ResNet recipe the paper trains (section "Experiments and Discussion").
 //
-// Such layers move about ten times more bytes per multiply than the matrix units need, so the kernel is built
-// around the memory stream and not around the multiply:
-//   * the whole filter ([Ngemm][Cs], at most 64 KB) is copied to LDS once per block and stays there;
+// Such layers move about ten times more bytes per multiply than the matrix units need (or are so small that every
+// kernel is latency-bound), so the kernel is built around the memory stream and not around the multiply:
+//   * the whole filter ([Ngemm][taps][Cs], at most 74 KB) is copied to LDS once per block and stays there;
 //   * a wavefront owns a tile of 32*FM pixels and loads their channels straight into registers in the MFMA
 //     operand layout (lane = pixel, 16 bytes = 8 consecutive channels): the activations never pass through LDS;
 //   * the loads of the next tile are issued before the current tile is multiplied, so every wavefront keeps a
 //     whole tile of loads in flight while it multiplies, converts and stores;
 //   * wavefronts never wait for each other after the filter copy (no barrier in the tile loop);
-//   * output rows are staged through a per-wavefront LDS strip so that 8 lanes store 128 contiguous bytes;
-//   * an accumulating launch fetches the old output values the same way, one 64-channel chunk ahead, and adds them
-//     to the fp32 sums before the single rounding.
-// One block of 4 wavefronts per CU (the register file then allows two tiles of up to 256 channels per lane).
+//   * output channels are handled in chunks of NW (64, or a whole 32- or 16-channel output), staged through a
+//     per-wavefront LDS strip so that a pixel's chunk leaves as 16-byte pieces of contiguous lanes;
+//   * an accumulating launch fetches the old output values the same way, one chunk ahead, and adds them to the
+//     fp32 sums before the single rounding;
+//   * a forward launch can leave per-channel partial sums for the batch-norm behind it, and the launch for the one
+//     live class of a 1x1 stride-2 backward-data pass also writes the zeros of the other three pixels of each cell.
+// One block of 4 wavefronts per CU (the register file then allows two tiles of up to 256 channels per lane);
+// 256 persistent blocks.  This file holds the 64-channel-chunk instances, conv_pw_narrow16/32.hip the narrow ones.
 #include "conv_pw_kernel.h"
 
 namespace nsk {

@@ -1,6 +1,6 @@
-// Kernel template of the short-reduction convolution (see conv_pw.hip for the description); included by the two
-// translation units that instantiate it (64-channel output chunks there, 16- and 32-channel outputs in
-// conv_pw_narrow.hip), so that they compile side by side.
+// Kernel template of the short-reduction convolution (see conv_pw.hip for the description); included by the
+// translation units that instantiate it (64-channel output chunks in conv_pw.hip, 16- and 32-channel outputs in
+// conv_pw_narrow16.hip and conv_pw_narrow32.hip), so that they compile side by side.
 #pragma once
 #include <stdlib.h>
 
@@ -29,13 +29,11 @@ inline bool conv_pw_narrow_instance(int ks, int taps)
 
 namespace {
 
-
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kPwGrid = 256;            // blocks; fixed so that the number of statistics rows is a shape property
 constexpr unsigned PW_OOB = 0xF0000000u;  // beyond every buffer: loads return zero, stores are dropped
 constexpr int PW_MAX_NCH = 4;           // column chunks of 64 (Ngemm <= 256)
-
 
 template <int KS, int FM, int TAPS, bool ACC, int NW>
 __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
