@@ -421,8 +421,8 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     if (forced_tile() != 0) return 0;
     if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
     if (halo64_f32_applicable(dtype, a)) return halo64_f32_stats_rows(a);
-    if (igemm_big_applicable(dtype, a)) return igemm_big_stats_rows(a);
     if (conv_pw_applicable(dtype, a)) return conv_pw_stats_rows(a);
+    if (igemm_big_applicable(dtype, a)) return igemm_big_stats_rows(a);
     // generic kernel: needs the vector epilogue; one row per wavefront row of every row block.  Measured: with a
     // short reduction the per-block cross-lane sums and the many rows of partial sums cost more than the separate
     // statistics pass they replace (config 5 stage A: +45 us on a 140 us layer), so only long reductions use it.
@@ -441,8 +441,8 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (a.zero_cell) return launch_conv_pw(a, stream);   // the caller has checked that this kernel applies
     if (forced_tile() == 0 && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
     if (forced_tile() == 0 && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
-    if (forced_tile() == 0 && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
     if (forced_tile() == 0 && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
+    if (forced_tile() == 0 && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
     IgemmArgs b = a;
     const int vec = dtype == NSK_BF16 ? 8 : 4;
     b.vec_out = (b.Ngemm % vec == 0 && b.Co % vec == 0 && (uintptr_t)b.out % 16 == 0) ? 1 : 0;

@@ -28,7 +28,7 @@ bool conv_pw_applicable(int dtype, const IgemmArgs &a)
 {
     if (getenv("NSK_NO_PW")) return false;
     if (dtype != NSK_BF16 || (a.accumulate && (a.stats || a.zero_cell))) return false;
-    if (a.Cs % 16 != 0 || a.Ktot != a.ntaps * a.Cs || a.Ngemm > 64 * PW_MAX_NCH) return false;
+    if (a.Cs % 16 != 0 || a.Ktot != a.ntaps * a.Cs) return false;
     const int ks = a.Ktot / 16;
     long min_rows;
     if (a.Ngemm == 16 || a.Ngemm == 32) {
@@ -41,12 +41,15 @@ bool conv_pw_applicable(int dtype, const IgemmArgs &a)
             if (!(a.Cs == 64 || a.Cs == 32) || a.Ngemm != 64 || (a.Cs == 64 && a.mult_h == 1 && a.mult_w == 1)) return false;
         } else {
             if (!(a.ntaps == 1 || a.ntaps == 2 || a.ntaps == 4)) return false;
-            if (!(a.Cs == 64 || a.Cs == 128 || a.Cs == 256 || (a.Cs == 32 && a.ntaps == 1)) || a.Ktot > 256 ||
-                (long)a.Ngemm * a.Ktot > 32768)
+            // (512 channels in one tap: 128 registers per lane and tile, two tiles in flight)
+            if (!(a.Cs == 64 || a.Cs == 128 || a.Cs == 256 || ((a.Cs == 32 || a.Cs == 512) && a.ntaps == 1)) || (a.Ktot > 256 && a.Cs != 512))
                 return false;
         }
-        // enough tiles to give every wavefront of the grid a few (below that the generic kernel's many small blocks win)
-        min_rows = a.Cs == 32 ? 8192 : 4L * kPwGrid * 4 * 64;
+        const int cols = pw_cols(a);
+        if (cols == 0) return false;
+        // enough tiles to give every wavefront of the grid a few (below that the generic kernel's many small blocks
+        // win); with the columns split into groups every group walks over all rows, so fewer rows are enough
+        min_rows = a.Cs == 32 ? 8192 : (4L * kPwGrid * 4 * 64) / ((a.Ngemm / cols) * (a.Ngemm / cols));
     } else {
         return false;
     }
@@ -60,7 +63,12 @@ bool conv_pw_applicable(int dtype, const IgemmArgs &a)
     return a.M >= min_rows;
 }
 
-int conv_pw_stats_rows(const IgemmArgs &) { return kPwGrid * 4; }
+// one row per wavefront of every row share (the column groups of a split output write different columns of a row)
+int conv_pw_stats_rows(const IgemmArgs &a)
+{
+    const int cols = pw_cols(a);
+    return cols > 0 ? kPwGrid * 4 / (a.Ngemm / cols) : kPwGrid * 4;
+}
 
 int launch_conv_pw(const IgemmArgs &a, hipStream_t stream)
 {
@@ -83,6 +91,7 @@ int launch_conv_pw(const IgemmArgs &a, hipStream_t stream)
     case 16 * 16 + 2: return launch_pw<16, 1, 2, 64>(pa, stream);
     case 16 * 16 + 4: return launch_pw<16, 1, 4, 64>(pa, stream);
     case 36 * 16 + 9: return launch_pw<36, 1, 9, 64>(pa, stream);
+    case 32 * 16 + 1: return launch_pw<32, 1, 1, 64>(pa, stream);    // 512 channels, one tap
     case 2 * 16 + 1: return launch_pw<2, 2, 1, 64>(pa, stream);      // 32 -> 64 channels, one tap
     case 18 * 16 + 9: return launch_pw<18, 2, 9, 64>(pa, stream);    // 32 -> 64 channels, 3x3
     default: return NSK_ERR_UNSUPPORTED;

@@ -12,6 +12,9 @@ struct PwArgs {
     IgemmArgs g;
     int tiles;
     int zero_cell;   // also write zeros to the other pixels of each row's 2x2 output cell (see IgemmArgs::zero_cell)
+    // Wide outputs whose filter does not fit in LDS are split into col_groups column groups of `cols` channels: a block
+    // keeps one group's filter and walks over the tiles of its share of the rows (col_groups divides 32; 1 = no split).
+    int cols, col_groups;
     unsigned out_bytes;
     unsigned long long magic_img, magic_row;   // ceil(2^40 / (Mi*Mj)), ceil(2^40 / Mj)
 };
@@ -55,7 +58,8 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int frow = lane & 31, fk = lane >> 5;
     unsigned char *w_lds = smem;
-    unsigned char *my_st = smem + (size_t)(a.Ngemm < 32 ? 32 : a.Ngemm) * WROW + wave * (STRIP + (2 * TAPS + 2) * TM * 4);
+    const int w_rows = pa.cols < 32 ? 32 : pa.cols;   // filter rows in LDS (a 16-channel output still multiplies 32: the rest are zero)
+    unsigned char *my_st = smem + (size_t)w_rows * WROW + wave * (STRIP + (2 * TAPS + 2) * TM * 4);
     unsigned *soff_lds = (unsigned *)(my_st + STRIP);   // [2][TAPS][TM] byte offsets of the tile's source pixels
     unsigned *ooff_lds = soff_lds + 2 * TAPS * TM;             // [2][TM] byte offsets of its output pixels (+ flags)
 
@@ -64,10 +68,15 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
     const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, pa.out_bytes, 0x00020000);
 
     // filter -> LDS
-    // (a 16-channel output still multiplies 32 filter rows: the missing ones are zero)
-    for (int idx = tid; idx < (a.Ngemm < 32 ? 32 : a.Ngemm) * (2 * KS); idx += 256) {
+    // block id -> (column group, row share).  Consecutive ids go to different XCDs, so the column groups of one row
+    // share get ids that differ by a multiple of 8: they read the same pixels through one XCD's L2.
+    const int cg = ((int)blockIdx.x >> 3) % pa.col_groups;
+    const int rb = ((int)blockIdx.x & 7) + 8 * (((int)blockIdx.x >> 3) / pa.col_groups);
+    const int n_rb = (int)gridDim.x / pa.col_groups;      // row shares
+    const int col0 = cg * pa.cols;                        // first output channel of this block
+    for (int idx = tid; idx < w_rows * (2 * KS); idx += 256) {
         const int n = idx / (2 * KS), ch = idx % (2 * KS);
-        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(wpk_rsrc, n < a.Ngemm ? (unsigned)((n * KS * 16 + ch * 8) * 2) : PW_OOB, 0, 0);
+        const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(wpk_rsrc, n < pa.cols ? (unsigned)(((col0 + n) * KS * 16 + ch * 8) * 2) : PW_OOB, 0, 0);
         *(u32x4 *)(w_lds + n * WROW + ch * 16) = v;
     }
     __syncthreads();
@@ -129,7 +138,7 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
             for (int jj = 0; jj < JJ; ++jj) {
                 const int idx = lane + 64 * jj, pos = idx / CPP, ck = idx % CPP;
                 const unsigned oo = ooff_lds[par * TM + 32 * mi + pos] & ~15u;
-                Ob[mi][jj] = __builtin_amdgcn_raw_buffer_load_b128(out_rsrc, oo + (unsigned)((nc * NW + ck * 8) * 2), 0, 0);
+                Ob[mi][jj] = __builtin_amdgcn_raw_buffer_load_b128(out_rsrc, oo + (unsigned)((col0 + nc * NW + ck * 8) * 2), 0, 0);
             }
     };
 
@@ -138,7 +147,7 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
     for (int nc = 0; nc < PW_MAX_NCH; ++nc)
 #pragma unroll
         for (int e = 0; e < 8; ++e) ssum[nc][e] = ssq[nc][e] = 0.f;
-    const int nch = a.Ngemm / NW;
+    const int nch = pa.cols / NW;
     const bool want_stats = a.stats != nullptr;
 
     auto compute = [&](const u32x4 (&A)[FM][KS], int par, bool has_next) {
@@ -208,7 +217,7 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
                         v = *(const u32x4 *)(my_st + pos * SROW + ck * 16);
                     }
                     const unsigned oraw = ooff_lds[par * TM + 32 * mi + pos];
-                    const unsigned oo = oraw & ~15u, cb = (unsigned)((nc * NW + ck * 8) * 2);
+                    const unsigned oo = oraw & ~15u, cb = (unsigned)((col0 + nc * NW + ck * 8) * 2);
                     __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, oo + cb, 0, 0);
                     if (!ACC && pa.zero_cell) {
                         const u32x4 z = {0u, 0u, 0u, 0u};
@@ -235,9 +244,9 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
     };
 
     u32x4 A0[FM][KS], A1[FM][KS];
-    const int stride = gridDim.x * 4;
+    const int stride = n_rb * 4;
     // few tiles: spread them over the CUs first (one wavefront per CU) instead of filling the first blocks
-    int t = pa.tiles >= stride ? blockIdx.x * 4 + wave : wave * (int)gridDim.x + blockIdx.x;
+    int t = pa.tiles >= stride ? rb * 4 + wave : wave * n_rb + rb;
     if (t < pa.tiles) {
         decode(t, 0);
         if constexpr (ACC) issue_old(O[0], 0, 0);
@@ -267,7 +276,7 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
 
     if (!ACC && want_stats) {
         // lanes with equal (lane % CPP) hold the same channels: add them up, one row of partial sums per wavefront
-        const int row = blockIdx.x * 4 + wave, ck = lane % CPP;
+        const int row = rb * 4 + wave, ck = lane % CPP;
 #pragma unroll
         for (int nc = 0; nc < PW_MAX_NCH; ++nc) {
             if (nc >= nch) break;
@@ -279,7 +288,7 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
                     ssq[nc][e] += __shfl_xor(ssq[nc][e], o, 64);
                 }
             if (lane < CPP) {
-                float *r0 = a.stats + (size_t)row * a.Ngemm + nc * NW + ck * 8;
+                float *r0 = a.stats + (size_t)row * a.Ngemm + col0 + nc * NW + ck * 8;
                 float *r1 = r0 + (size_t)a.stats_rows * a.Ngemm;
                 *(f32x4 *)r0 = f32x4{ssum[nc][0], ssum[nc][1], ssum[nc][2], ssum[nc][3]};
                 *(f32x4 *)(r0 + 4) = f32x4{ssum[nc][4], ssum[nc][5], ssum[nc][6], ssum[nc][7]};
@@ -292,16 +301,33 @@ __global__ __launch_bounds__(256, 1) void conv_pw_kernel(const PwArgs pa)
 
 inline int pw_chunk(const IgemmArgs &a) { return a.Ngemm % 64 == 0 ? 64 : a.Ngemm; }   // NW: 64, 32 or 16
 
+// Output channels per block: all of them if their filter fits in LDS, else the largest multiple of 64 that does and
+// splits the columns into 2, 4, ... 32 groups; 0 if there is none.
+inline int pw_cols(const IgemmArgs &a)
+{
+    const long limit = a.ntaps == 9 ? 36864 : 32768;       // filter elements a block keeps in LDS
+    if (a.Ngemm <= 64 * PW_MAX_NCH && (long)a.Ngemm * a.Ktot <= limit) return a.Ngemm;
+    if (a.Ngemm % 64 != 0) return 0;
+    for (int cols = 64 * PW_MAX_NCH; cols >= 64; cols -= 64) {
+        if ((long)cols * a.Ktot > limit || a.Ngemm % cols != 0) continue;
+        const int groups = a.Ngemm / cols;
+        if (groups <= 32 && 32 % groups == 0) return cols;
+    }
+    return 0;
+}
+
 inline size_t pw_smem(const IgemmArgs &a, int tm)
 {
-    const int nw = pw_chunk(a);
-    return (size_t)(a.Ngemm < 32 ? 32 : a.Ngemm) * (a.Ktot * 2 + 16) +
+    const int nw = pw_chunk(a), cols = pw_cols(a);
+    return (size_t)(cols < 32 ? 32 : cols) * (a.Ktot * 2 + 16) +
            4 * (size_t)(32 * (a.accumulate ? nw * 4 + 16 : nw * 2 + 16) + (2 * a.ntaps + 2) * tm * 4);
 }
 
 template <int KS, int FM, int TAPS, bool ACC, int NW> int launch_pw_acc(PwArgs pa, hipStream_t stream)
 {
     pa.tiles = ceil_div(pa.g.M, 32 * FM);
+    pa.cols = pw_cols(pa.g);
+    pa.col_groups = pa.g.Ngemm / pa.cols;
     // at least half of a CU's LDS, so that the 256 blocks land on 256 different CUs
     size_t smem = pw_smem(pa.g, 32 * FM);
     if (smem < 84 * 1024) smem = 84 * 1024;
