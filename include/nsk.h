@@ -173,7 +173,9 @@ int nsk_bn_relu_add_fwd_mask(const nsk_bn_desc_t *desc, const void *x, const voi
                              float *running_var, void *workspace, size_t workspace_bytes, void *stream);
 /* nsk_bn_relu_add_fwd with the batch statistics taken from partial sums of x and x*x (layout as written by
  * nsk_conv2d_fwd_stats: [2][stats_rows][C] floats) instead of a reduction pass over x.  relu_mask: NULL, or as in
- * nsk_bn_relu_add_fwd_mask.  The variance is formed as E[x*x] - E[x]^2 in double precision. */
+ * nsk_bn_relu_add_fwd_mask.  The variance is formed as E[x*x] - E[x]^2 in double precision from float partial sums
+ * that are not shifted: it loses accuracy when |mean| is hundreds of standard deviations (1e-4 of invstd at about
+ * 250); nsk_bn_relu_add_fwd, which subtracts a per-channel shift first, has no such limit. */
 int nsk_bn_relu_add_fwd_stats(const nsk_bn_desc_t *desc, const void *x, const void *residual,
                               const float *gamma, const float *beta, void *out, unsigned char *relu_mask,
                               float *save_mean, float *save_invstd, float *running_mean,
