@@ -148,3 +148,36 @@ def test_random_batch_norm_problems_match_the_oracle():
         assert max_rel_err(db.cpu().numpy(), wdb) <= 1e-4, shape
         if with_res:
             assert np.array_equal(to_host(dres, layout), wdres), shape
+
+
+def test_random_max_pool_problems_match_the_oracle():
+    """Random windows (1..4 per axis), strides and paddings, inputs with many tied zeros: values, first-maximum indices
+    (bit exact) and the backward scatter."""
+    rng = np.random.default_rng(4400)
+    for case in range(60):
+        R, S = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        sh, sw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        ph, pw = int(rng.integers(0, R // 2 + 1)), int(rng.integers(0, S // 2 + 1))
+        if rng.random() < 0.4:
+            R, S, sh, sw, ph, pw = 3, 3, 2, 2, 1, 1                      # the recipe's pool
+        N, C = int(rng.integers(1, 4)), int(rng.choice([3, 8, 16, 24, 64]))
+        H, W = int(rng.integers(R, 23)), int(rng.integers(S, 23))
+        if rng.random() < 0.3:
+            H, W = H + H % 2, W + W % 2                                  # even extents: the 2x2-block backward kernel
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        layout = B.NSK_NHWC if rng.random() < 0.75 else B.NSK_NCHW
+        shape = (N, C, H, W)
+        print(f"pool fuzz case {case}: {shape} window {(R, S)} stride {(sh, sw)} pad {(ph, pw)} {dtype} layout={layout}", flush=True)
+        x = on_grid(np.maximum(gen.normal(7000 + case, 0, shape), 0.0), dtype)
+        y, idx = B.maxpool2d_fwd(to_gpu(x, dtype, layout), (R, S), (sh, sw), (ph, pw), layout)
+        wy, widx = oracle.maxpool2d_fwd(x, (R, S), (sh, sw), (ph, pw))
+        torch.cuda.synchronize()
+        assert np.array_equal(to_host(y, layout), wy), shape
+        got_idx = idx.cpu()
+        if layout == B.NSK_NHWC:
+            got_idx = got_idx.permute(0, 3, 1, 2)
+        assert np.array_equal(got_idx.numpy(), widx), shape
+        dy = on_grid(gen.normal(7000 + case, 1, wy.shape), dtype)
+        dx = B.maxpool2d_bwd(to_gpu(dy, dtype, layout), idx, shape, (R, S), (sh, sw), (ph, pw), layout)
+        torch.cuda.synchronize()
+        assert max_rel_err(to_host(dx, layout), oracle.maxpool2d_bwd(dy, widx, shape, (R, S), (sh, sw), (ph, pw))) <= TOL[dtype], shape
