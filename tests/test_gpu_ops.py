@@ -224,6 +224,11 @@ def test_conv_pointwise_kernel(i, layout, monkeypatch):
     torch.cuda.synchronize()
     want_acc = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl, into=base.astype(np.float64))
     assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
+    # a second run gives the same bits (fixed summation order, no atomics), partial sums included
+    y2, stats2 = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    dx2 = B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y2, y1) and torch.equal(stats2, stats) and torch.equal(dx2, dx_view)
 
 
 @pytest.mark.parametrize("layout", LAYOUTS)
