@@ -141,3 +141,39 @@ def test_adamw_with_gradient_clip_runs_the_recurrent_experiments_recipe():
                                      beta1=float(np.float32(0.9)), beta2=float(np.float32(0.999)), weight_decay=1e-4,
                                      grad_scale=s)
         assert max_rel_err(net.host(tr.master[n]) - before[n], want - before[n]) <= 1e-3
+
+
+def test_a_captured_training_step_replays_to_the_same_bits_as_eager_steps():
+    """The whole step (blocks, head, loss, backward, multi-tensor SGD) captured into a HIP graph: every replay leaves
+    exactly the state the same number of eager steps leaves.  Replays are separated by host synchronisations and an
+    eager read of the loss, as a training loop would do."""
+    def make():
+        wl, t, fc_w, fc_b, labels = _setup(3, 8)
+        net = GpuNetwork(wl, t, B.NSK_NHWC)
+        return GpuTrainer(net, fc_w, fc_b, labels, lr=LR, momentum=MU, weight_decay=WD)
+
+    eager, graphed = make(), make()
+    eager_losses, graph_losses = [], []
+    for _ in range(5):
+        eager.step()
+        torch.cuda.synchronize()
+        eager_losses.append(float(eager.loss.item()))
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        graphed.step()                       # first step eagerly (sizes the workspaces)
+        stream.synchronize()
+        graph_losses.append(float(graphed.loss.item()))
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            graphed.step()
+        for _ in range(4):
+            g.replay()
+            stream.synchronize()
+            graph_losses.append(float(graphed.loss.item()))
+    torch.cuda.synchronize()
+    assert graph_losses == eager_losses
+    for n in eager.net.w:
+        assert torch.equal(eager.master[n], graphed.master[n]) and torch.equal(eager.net.w[n], graphed.net.w[n])
+    assert torch.equal(eager.fc_w_master, graphed.fc_w_master) and torch.equal(eager.fc_b, graphed.fc_b)
+    for n in eager.net.gamma:
+        assert torch.equal(eager.net.gamma[n], graphed.net.gamma[n]) and torch.equal(eager.net.beta[n], graphed.net.beta[n])
