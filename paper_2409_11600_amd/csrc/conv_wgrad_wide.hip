@@ -311,7 +311,10 @@ int wgrad_wide_rows_per_split(const WgradArgs &a, int *splits)
 {
     const int NT = a.ntaps * a.C;
     const int T = ceil_div(NT, WW_BN) * ceil_div(a.K, tile_rows(a));
-    int want = 256 / T;
+    // The 64-row kernel needs 65 KB of LDS, so two of its blocks can share a CU.  Measured: that pays for long
+    // reductions over several taps (image stem 83 -> 71 us, strided 3x3 64->64 82 -> 71 us), whose blocks wait on
+    // gathered loads; single-tap layers are bound by HBM and lose (110 -> 117 us), and so do short reductions.
+    int want = (tile_rows(a) == 64 && a.ntaps > 1 && a.L >= 400000 ? 512 : 256) / T;
     if (want < 1) want = 1;
     const int most = ceil_div(a.L, 2 * WW_KT);   // at least two k-tiles per split
     if (want > most) want = most;
