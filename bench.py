@@ -60,6 +60,9 @@ def parse():
     ap.add_argument("--train-step", action="store_true",
                     help="also time the whole training step: the workload followed by average pool, fully connected "
                          "layer, loss, their backward passes and the SGD update of every parameter")
+    ap.add_argument("--gru", action="store_true",
+                    help="time the recurrent workload instead: embedding + GRU(256) + output layer, batch 50, sequence "
+                         "length 200, vocabulary 32768, 2 classes, forward + backward through time + clipped AdamW")
     ap.add_argument("--layers", action="store_true", help="per-layer convolution table instead of the step benchmark")
     return ap.parse_args()
 
@@ -181,6 +184,55 @@ def stored_traffic(workload, kind):
     return None
 
 
+def gru_bench(a):
+    """The recurrent workload of the paper's section "Experiments and Discussion" at its stated sizes (the embedding
+    width is not stated: 256, the hidden size).  A step is forward, backward through time, gradient clip and AdamW
+    over one batch of seeded random tokens; fp32 as in the paper.  Prints one JSON line."""
+    import numpy as np
+    import torch
+    import nsk_inputs as gen
+    from paper_2409_11600_amd.recurrent import GpuGruClassifier
+
+    T, N, E, H, V, K = 200, 50, 256, 256, 32768, 2
+    tokens = ((gen.uniform(77, 0, (T, N)) * V).astype(np.int32)) % V
+    labels = ((gen.uniform(77, 1, (N,)) * K).astype(np.int32)) % K
+    p = dict(table=gen.normal(77, 2, (V, E)), w_ih=gen.normal(77, 3, (3 * H, E)) / np.sqrt(E),
+             w_hh=gen.normal(77, 4, (3 * H, H)) / np.sqrt(H), b_ih=np.zeros(3 * H), b_hh=np.zeros(3 * H),
+             w_out=gen.normal(77, 7, (K, H)) / np.sqrt(H), b_out=np.zeros(K))
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        m = GpuGruClassifier(tokens, labels, **p, dtype="f32", lr=1e-3, weight_decay=1e-4, clip=5.0)
+        for _ in range(max(a.warmup, 2)):
+            m.step()
+        stream.synchronize()
+        graph = None
+        if not a.no_graph:
+            # forward and backward through time as one HIP graph (about 1000 launches); the optimizer call carries the
+            # step number as a host argument and is issued after each replay
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                m.forward()
+                m.backward()
+        steps = min(a.steps, 20)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            if graph is not None:
+                graph.replay()
+                m.update()
+            else:
+                m.step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms = (t1 - t0) * 1e3 / steps
+    print(json.dumps({"metric": "GRU sentiment classifier training step (embedding + GRU 256 + output layer, clipped AdamW)",
+                      "value": N * steps / (t1 - t0), "unit": "sequences/s", "n_gpus": 1, "steps": steps, "warmup": a.warmup,
+                      "ms_per_step": ms, "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": f"tokens [{T}, {N}], vocabulary {V}, embedding {E}, hidden {H}, {K} classes",
+                                 "hip_graph": graph is not None}, "loss": float(m.loss.item())}))
+
+
 def main():
     a = parse()
     if a.gpus != 1:
@@ -200,6 +252,9 @@ def main():
     torch.cuda.set_device(0)
     if a.layers:
         layer_table()
+        return
+    if a.gru:
+        gru_bench(a)
         return
     wl = gen.workload(a.config, batch=a.batch, stage=a.stage)
     tensors = gen.workload_tensors(wl)

@@ -233,6 +233,11 @@ int nsk_linear_dgrad(const nsk_linear_desc_t *desc, const void *dy, const void *
 int nsk_linear_wgrad(const nsk_linear_desc_t *desc, const void *x, const void *dy, float *dw, float *db,
                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
+/* dst[c][r] = src[r][c] for a row-major [rows][cols] matrix of `dtype` (dst must not overlap src).  A caller that
+ * multiplies few rows by the same weight many times (a recurrent layer) keeps a transposed copy: the product with
+ * W^T read row by row is then nsk_linear_dgrad on the copy, whose memory accesses are contiguous. */
+int nsk_transpose2d(int dtype, int rows, int cols, const void *src, void *dst, void *stream);
+
 /* Softmax cross-entropy, the loss node: per_sample[n] = log sum_k exp(z[n][k]) - z[n][label_n] (computed with
  * the row maximum subtracted), loss[0] = mean over n, summed in a fixed order.  logits: [N,K] of `dtype`;
  * labels: [N] int, each in [0,K) (a label outside that range gives NaN for its sample and for the loss);
@@ -280,6 +285,37 @@ int nsk_adamw_step_multi(int count, const nsk_param_t *params, int step, float l
 #define NSK_SUMSQ_PARTIALS 256
 int nsk_sumsq_accumulate(size_t n, const float *g, float *partials, float *sumsq, void *stream);
 int nsk_clip_scale(const float *sumsq, float max_norm, float *scale, void *stream);
+
+/* ---------------------------------------------------------------------------------------------------------------
+ * The recurrent workload (section "Experiments and Discussion": an embedding over the vocabulary, one GRU layer, an
+ * output layer, cross entropy, AdamW with a gradient clip).  Its matrix products are the `@` operator
+ * (nsk_linear_*): gi = x @ W_ih for all time steps in one call, gh = h @ W_hh once per step, and their gradients.
+ * What is declared here is the rest: the embedding lookup with its gradient, and the elementwise part of one GRU step
+ * in one kernel per direction (the paper ran it as separate unfused operations and names that as the cause of its
+ * slowdown on this experiment).  Gate order (r, z, n); weights W_ih [3H][E], W_hh [3H][H]; biases float [3H]:
+ *   r = sigmoid(gi_r + b_ir + gh_r + b_hr),  z = sigmoid(gi_z + b_iz + gh_z + b_hz),
+ *   q = gh_n + b_hn,  n = tanh(gi_n + b_in + r*q),  h_new = (1 - z)*n + z*h_prev.
+ * --------------------------------------------------------------------------------------------------------------- */
+
+/* out[i][0..E) = table[tokens[i]][0..E) for i < n.  tokens: int [n], each in [0,V) (a token outside that range gives
+ * a row of NaN); table [V,E] and out [n,E] of `dtype`. */
+int nsk_embedding_fwd(int dtype, int n, int E, int V, const int *tokens, const void *table, void *out,
+                      void *stream);
+/* dtable[v][e] (+)= sum over the positions i with tokens[i] == v of dout[i][e]; dtable is float [V,E] and with
+ * accumulate = 0 it is overwritten as a whole.  No atomics: every element is summed in position order (bitwise
+ * reproducible).  Tokens outside [0,V) are ignored. */
+int nsk_embedding_bwd(int dtype, int n, int E, int V, const int *tokens, const void *dout, float *dtable,
+                      int accumulate, void *stream);
+/* Elementwise part of a GRU step.  gi, gh: [N,3H]; h_prev, h_new: [N,H]; saved: [N,4H] receives (r, z, n, q) for
+ * the backward call; all of `dtype`, math in float. */
+int nsk_gru_gates_fwd(int dtype, int N, int H, const void *gi, const void *gh, const float *b_ih,
+                      const float *b_hh, const void *h_prev, void *h_new, void *saved, void *stream);
+/* Its gradient.  dh = dh_a + dh_b + dh_c is the gradient of h_new (dh_b, dh_c may be NULL: the contributions of the
+ * following step arrive in separate buffers).  Writes dgi, dgh [N,3H] (the gradients of the two products; their
+ * column sums are the bias gradients) and dh_direct [N,H] = dh * z, the part of the gradient of h_prev that does not
+ * pass through gh; the rest is nsk_linear_dgrad(dgh, W_hh). */
+int nsk_gru_gates_bwd(int dtype, int N, int H, const void *saved, const void *h_prev, const void *dh_a,
+                      const void *dh_b, const void *dh_c, void *dgi, void *dgh, void *dh_direct, void *stream);
 
 /* ---------------------------------------------------------------------------------------------------------------
  * Device memory pool and cache (section "Caching and Pooling"): what hands out the raw pointers every entry point

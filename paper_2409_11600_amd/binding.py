@@ -130,6 +130,8 @@ def lib() -> ctypes.CDLL:
         L.nsk_linear_dgrad.argtypes = [ld, vp, vp, vp, ci, vp, sz, vp]
         L.nsk_linear_wgrad.restype = ci
         L.nsk_linear_wgrad.argtypes = [ld, vp, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_transpose2d.restype = ci
+        L.nsk_transpose2d.argtypes = [ci, ci, ci, vp, vp, vp]
         L.nsk_softmax_xent_fwd.restype = ci
         L.nsk_softmax_xent_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp]
         L.nsk_softmax_xent_bwd.restype = ci
@@ -147,6 +149,14 @@ def lib() -> ctypes.CDLL:
         L.nsk_sumsq_accumulate.argtypes = [sz, vp, vp, vp, vp]
         L.nsk_clip_scale.restype = ci
         L.nsk_clip_scale.argtypes = [vp, cf, vp, vp]
+        L.nsk_embedding_fwd.restype = ci
+        L.nsk_embedding_fwd.argtypes = [ci, ci, ci, ci, vp, vp, vp, vp]
+        L.nsk_embedding_bwd.restype = ci
+        L.nsk_embedding_bwd.argtypes = [ci, ci, ci, ci, vp, vp, vp, ci, vp]
+        L.nsk_gru_gates_fwd.restype = ci
+        L.nsk_gru_gates_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.nsk_gru_gates_bwd.restype = ci
+        L.nsk_gru_gates_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         vpp, szp = ctypes.POINTER(vp), ctypes.POINTER(sz)
         L.nsk_pool_create.restype = ci
         L.nsk_pool_create.argtypes = [ci, vpp]
@@ -171,8 +181,9 @@ EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d
            "nsk_bn_relu_add_fwd_stats", "nsk_maxpool2d_out_dims",
            "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd",
            "nsk_global_avgpool_fwd", "nsk_global_avgpool_bwd", "nsk_linear_workspace_bytes", "nsk_linear_fwd",
-           "nsk_linear_dgrad", "nsk_linear_wgrad", "nsk_softmax_xent_fwd", "nsk_softmax_xent_bwd",
+           "nsk_linear_dgrad", "nsk_linear_wgrad", "nsk_transpose2d", "nsk_softmax_xent_fwd", "nsk_softmax_xent_bwd",
            "nsk_sgd_momentum_step", "nsk_adamw_step", "nsk_sgd_momentum_step_multi", "nsk_adamw_step_multi", "nsk_sumsq_accumulate", "nsk_clip_scale",
+           "nsk_embedding_fwd", "nsk_embedding_bwd", "nsk_gru_gates_fwd", "nsk_gru_gates_bwd",
            "nsk_pool_create", "nsk_pool_get", "nsk_pool_put", "nsk_pool_cached", "nsk_pool_stats", "nsk_pool_destroy")
 NSK_POOL_DEVICE, NSK_POOL_HOST = 0, 1
 NSK_SUMSQ_PARTIALS = 256
@@ -517,6 +528,15 @@ def linear_wgrad(x, dy, dw=None, db=None, accumulate=False, want_db=True, ws: Op
     return dw, db
 
 
+def transpose2d(src, out=None):
+    """out[c][r] = src[r][c]."""
+    rows, cols = src.shape
+    if out is None:
+        out = torch.empty((cols, rows), dtype=src.dtype, device=src.device)
+    _check(lib().nsk_transpose2d(_dtype_code(src), int(rows), int(cols), _ptr(src), _ptr(out), _stream()), "nsk_transpose2d")
+    return out
+
+
 def softmax_xent_fwd(logits, labels, per_sample=None, loss=None):
     """labels: int32 [N].  Returns (loss [1] float32, per_sample [N] float32), both on the device."""
     N, K = logits.shape
@@ -600,6 +620,52 @@ def clip_scale(grads, max_norm, partials=None, sumsq=None, scale=None):
                "nsk_sumsq_accumulate")
     _check(lib().nsk_clip_scale(_ptr(sumsq), float(max_norm), _ptr(scale), _stream()), "nsk_clip_scale")
     return scale
+
+
+# ------------------------------------------------------------------------------------ recurrent workload
+
+def embedding_fwd(tokens, table, out=None):
+    """tokens: int32 [n]; table [V, E] -> out [n, E]."""
+    n, (V, E) = tokens.numel(), table.shape
+    assert tokens.dtype == torch.int32
+    if out is None:
+        out = torch.empty((n, E), dtype=table.dtype, device=table.device)
+    _check(lib().nsk_embedding_fwd(_dtype_code(table), n, int(E), int(V), _ptr(tokens), _ptr(table), _ptr(out), _stream()),
+           "nsk_embedding_fwd")
+    return out
+
+
+def embedding_bwd(tokens, dout, V, dtable=None, accumulate=False):
+    n, E = tokens.numel(), dout.shape[-1]
+    assert tokens.dtype == torch.int32 and dout.numel() == n * E
+    if dtable is None:
+        assert not accumulate
+        dtable = torch.empty((V, E), dtype=torch.float32, device=dout.device)
+    _check(lib().nsk_embedding_bwd(_dtype_code(dout), n, int(E), int(V), _ptr(tokens), _ptr(dout), _ptr(dtable),
+                                   int(accumulate), _stream()), "nsk_embedding_bwd")
+    return dtable
+
+
+def gru_gates_fwd(gi, gh, b_ih, b_hh, h_prev, h_new=None, saved=None):
+    N, H = h_prev.shape
+    if h_new is None:
+        h_new = torch.empty_like(h_prev)
+    if saved is None:
+        saved = torch.empty((N, 4 * H), dtype=h_prev.dtype, device=h_prev.device)
+    _check(lib().nsk_gru_gates_fwd(_dtype_code(h_prev), int(N), int(H), _ptr(gi), _ptr(gh), _ptr(b_ih), _ptr(b_hh),
+                                   _ptr(h_prev), _ptr(h_new), _ptr(saved), _stream()), "nsk_gru_gates_fwd")
+    return h_new, saved
+
+
+def gru_gates_bwd(saved, h_prev, dh_a, dh_b=None, dh_c=None, dgi=None, dgh=None, dh_direct=None):
+    N, H = h_prev.shape
+    mk = lambda w: torch.empty((N, w), dtype=h_prev.dtype, device=h_prev.device)
+    dgi = mk(3 * H) if dgi is None else dgi
+    dgh = mk(3 * H) if dgh is None else dgh
+    dh_direct = mk(H) if dh_direct is None else dh_direct
+    _check(lib().nsk_gru_gates_bwd(_dtype_code(h_prev), int(N), int(H), _ptr(saved), _ptr(h_prev), _ptr(dh_a), _ptr(dh_b),
+                                   _ptr(dh_c), _ptr(dgi), _ptr(dgh), _ptr(dh_direct), _stream()), "nsk_gru_gates_bwd")
+    return dgi, dgh, dh_direct
 
 
 # ------------------------------------------------------------------------------------ memory pool

@@ -133,6 +133,73 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const T *__restrict__ dy
     if ((threadIdx.x & 63) == 0) db[k] = accumulate ? db[k] + s : s;
 }
 
+// Matrix products with very few rows (a recurrent step: 50 samples): a tile kernel would run on a handful of blocks,
+// so here every output element has its own thread and the product runs on the vector units.
+//   forward:  y[n][k] = sum_c x[n][c] * w[k][c] (+ bias[k]); lane = k (the 64 rows of w a wavefront walks stay in L1
+//             for the iterations that share a cache line)
+//   backward: dx[n][c] (+)= sum_k dy[n][k] * w[k][c]; lane = c, w read row by row with consecutive lanes on
+//             consecutive c, so no packed transposed copy of the filter is needed
+// forward: one thread per output element (splitting its reduction over wavefronts, as the backward kernel below does,
+// is slower here: four times as many wavefronts then walk the rows of w with a stride)
+template <typename T>
+__global__ __launch_bounds__(256) void linear_small_fwd_kernel(const T *__restrict__ x, const T *__restrict__ w,
+                                                               const float *__restrict__ bias, T *__restrict__ y, int N,
+                                                               int C, int K)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (long)N * K) return;
+    const int n = (int)(i / K), k = (int)(i - (long)n * K);
+    const T *xr = x + (long)n * C, *wr = w + (long)k * C;
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int c = 0;
+    for (; c + 3 < C; c += 4) {
+        s0 += ld(xr, c) * ld(wr, c);
+        s1 += ld(xr, c + 1) * ld(wr, c + 1);
+        s2 += ld(xr, c + 2) * ld(wr, c + 2);
+        s3 += ld(xr, c + 3) * ld(wr, c + 3);
+    }
+    for (; c < C; ++c) s0 += ld(xr, c) * ld(wr, c);
+    float r = (s0 + s1) + (s2 + s3);
+    if (bias) r = (float)(T)r + bias[k];      // as the large path: product rounded to the storage type, then the bias
+    y[i] = (T)r;
+}
+
+// backward: a block computes 64 consecutive outputs of one row; its four wavefronts each take a quarter of the
+// reduction and the quarters are added in a fixed order through LDS.  (Giving a block several rows, so that a weight
+// element is loaded once for all of them, was measured slower: 16 us against 9 us at 50 rows x 768 -> 256, because the
+// launch then has too few blocks to hide the latency of its loads.)
+template <typename T>
+__global__ __launch_bounds__(256) void linear_small_dgrad_kernel(const T *__restrict__ dy, const T *__restrict__ w,
+                                                                 T *__restrict__ dx, int N, int C, int K, int accumulate)
+{
+    __shared__ float part[4][64];
+    const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int n = blockIdx.y, c = blockIdx.x * 64 + lane;
+    const int k0 = (int)((long)K * q / 4), k1 = (int)((long)K * (q + 1) / 4);
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    if (c < C) {
+        const T *dr = dy + (long)n * K, *wc = w + c;
+        int k = k0;
+        for (; k + 3 < k1; k += 4) {
+            s0 += ld(dr, k) * ld(wc, (long)k * C);
+            s1 += ld(dr, k + 1) * ld(wc, (long)(k + 1) * C);
+            s2 += ld(dr, k + 2) * ld(wc, (long)(k + 2) * C);
+            s3 += ld(dr, k + 3) * ld(wc, (long)(k + 3) * C);
+        }
+        for (; k < k1; ++k) s0 += ld(dr, k) * ld(wc, (long)k * C);
+    }
+    part[q][lane] = (s0 + s1) + (s2 + s3);
+    __syncthreads();
+    if (q == 0 && c < C) {
+        float r = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
+        const long i = (long)n * C + c;
+        if (accumulate) r += ld(dx, i);
+        dx[i] = (T)r;
+    }
+}
+
+constexpr int kSmallRows = 64;     // up to this many rows the per-element kernels are used
+
 // ----------------------------------------------------------------------------- softmax cross-entropy
 // One wavefront per sample.  mode 0: per-sample loss; mode 1: gradient of the logits.
 template <typename T, int MODE>
@@ -350,6 +417,19 @@ int nsk_linear_fwd(const nsk_linear_desc_t *desc, const void *x, const void *w, 
 {
     TAIL_TRY(linear_check(desc));
     if (bias && unaligned(bias)) return NSK_ERR_ALIGNMENT;
+    if (desc->N <= kSmallRows) {
+        if (!x || !w || !y) return NSK_ERR_NULL;
+        if (unaligned(x) || unaligned(w) || unaligned(y)) return NSK_ERR_ALIGNMENT;
+        const long total = (long)desc->N * desc->K;
+        const dim3 grid((unsigned)((total + 255) / 256));
+        if (desc->dtype == NSK_BF16)
+            hipLaunchKernelGGL(linear_small_fwd_kernel<bf16_t>, grid, dim3(256), 0, (hipStream_t)stream, (const bf16_t *)x,
+                               (const bf16_t *)w, bias, (bf16_t *)y, desc->N, desc->C, desc->K);
+        else
+            hipLaunchKernelGGL(linear_small_fwd_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)x,
+                               (const float *)w, bias, (float *)y, desc->N, desc->C, desc->K);
+        return check_launch();
+    }
     const nsk_conv_desc_t c = linear_as_conv(desc);
     TAIL_TRY(nsk_conv2d_fwd(&c, x, w, y, workspace, workspace_bytes, stream));
     if (bias) {
@@ -368,6 +448,19 @@ int nsk_linear_dgrad(const nsk_linear_desc_t *desc, const void *dy, const void *
                      void *workspace, size_t workspace_bytes, void *stream)
 {
     TAIL_TRY(linear_check(desc));
+    if (desc->N <= kSmallRows) {
+        if (accumulate != 0 && accumulate != 1) return NSK_ERR_BAD_DESC;
+        if (!dy || !w || !dx) return NSK_ERR_NULL;
+        if (unaligned(dy) || unaligned(w) || unaligned(dx)) return NSK_ERR_ALIGNMENT;
+        const dim3 grid((unsigned)((desc->C + 63) / 64), (unsigned)desc->N);
+        if (desc->dtype == NSK_BF16)
+            hipLaunchKernelGGL(linear_small_dgrad_kernel<bf16_t>, grid, dim3(256), 0, (hipStream_t)stream, (const bf16_t *)dy,
+                               (const bf16_t *)w, (bf16_t *)dx, desc->N, desc->C, desc->K, accumulate);
+        else
+            hipLaunchKernelGGL(linear_small_dgrad_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)dy,
+                               (const float *)w, (float *)dx, desc->N, desc->C, desc->K, accumulate);
+        return check_launch();
+    }
     const nsk_conv_desc_t c = linear_as_conv(desc);
     return nsk_conv2d_dgrad(&c, dy, w, dx, accumulate, workspace, workspace_bytes, stream);
 }
@@ -390,6 +483,15 @@ int nsk_linear_wgrad(const nsk_linear_desc_t *desc, const void *x, const void *d
         return check_launch();
     }
     return NSK_OK;
+}
+
+int nsk_transpose2d(int dtype, int rows, int cols, const void *src, void *dst, void *stream)
+{
+    if (rows <= 0 || cols <= 0 || !dtype_ok(dtype)) return NSK_ERR_BAD_DESC;
+    if (!src || !dst) return NSK_ERR_NULL;
+    if (unaligned(src) || unaligned(dst)) return NSK_ERR_ALIGNMENT;
+    // [rows][cols] -> [cols][rows] is the NHWC -> NCHW copy of one image with rows pixels and cols channels
+    return launch_nhwc_to_nchw(dtype, src, dst, 1, cols, rows, 1, 0, (hipStream_t)stream);
 }
 
 int nsk_softmax_xent_fwd(int dtype, int N, int K, const void *logits, const int *labels, float *per_sample, float *loss,

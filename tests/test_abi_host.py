@@ -144,6 +144,27 @@ def test_tail_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.nsk_clip_scale(None, 5.0, FAKE, None) == B.NSK_ERR_NULL
 
 
+def test_recurrent_entry_points_reject_bad_arguments_without_a_gpu():
+    L = B.lib()
+    assert L.nsk_embedding_fwd(B.NSK_F32, 0, 8, 16, FAKE, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_embedding_fwd(B.NSK_F32, 4, 8, 16, None, FAKE, FAKE, None) == B.NSK_ERR_NULL
+    assert L.nsk_embedding_fwd(B.NSK_BF16, 4, 8, 16, FAKE, ODD, FAKE, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_embedding_bwd(B.NSK_F32, 4, 8, 16, FAKE, FAKE, FAKE, 2, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_embedding_bwd(B.NSK_F32, 4, 8, 16, FAKE, FAKE, None, 0, None) == B.NSK_ERR_NULL
+    assert L.nsk_gru_gates_fwd(B.NSK_F32, 4, 0, *([FAKE] * 7), None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_gru_gates_fwd(B.NSK_F32, 4, 8, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE, None) == B.NSK_ERR_NULL
+    assert L.nsk_gru_gates_bwd(9, 4, 8, *([FAKE] * 8), None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_gru_gates_bwd(B.NSK_F32, 4, 8, FAKE, FAKE, None, None, None, FAKE, FAKE, FAKE, None) == B.NSK_ERR_NULL     # dh_a is required
+    assert L.nsk_gru_gates_bwd(B.NSK_F32, 4, 8, FAKE, FAKE, FAKE, ODD, None, FAKE, FAKE, FAKE, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_transpose2d(B.NSK_F32, 0, 4, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_transpose2d(B.NSK_F32, 4, 4, FAKE, None, None) == B.NSK_ERR_NULL
+    # few rows: the per-element product kernels validate like the rest
+    small = B.nsk_linear_desc_t(50, 256, 768, B.NSK_F32)
+    assert L.nsk_linear_fwd(ctypes.byref(small), FAKE, None, None, FAKE, None, 0, None) == B.NSK_ERR_NULL
+    assert L.nsk_linear_dgrad(ctypes.byref(small), FAKE, FAKE, ODD, 0, None, 0, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_linear_dgrad(ctypes.byref(small), FAKE, FAKE, FAKE, 5, None, 0, None) == B.NSK_ERR_BAD_DESC
+
+
 def test_binding_raises_loudly_when_library_is_missing(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "libnsk.so"))

@@ -286,3 +286,14 @@ def test_tail_at_full_size_of_config_5_stage_a():
     ww, vv, _ = T.sgd_momentum_step(w0, g0, v0, 0.1, 0.9, 1e-4)
     assert max_rel_err(host(gw), ww) <= 1e-5 and max_rel_err(host(gv), vv) <= 1e-5
     assert not gg.any() and torch.equal(lp, gw.to(torch.bfloat16))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("rows,cols", [(768, 256), (5, 3), (33, 70), (1, 16), (1000, 2048)])
+def test_transpose2d_is_an_exact_copy(rows, cols, dtype):
+    a = on_grid(gen.normal(2300 + rows, 0, (rows, cols)), dtype)
+    view, check = guarded((cols, rows), torch_dtype(dtype))
+    B.transpose2d(dev(a, dtype), out=view)
+    torch.cuda.synchronize()
+    check()
+    assert np.array_equal(host(view), a.T.astype(np.float64))
