@@ -422,6 +422,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
     if (halo64_f32_applicable(dtype, a)) return halo64_f32_stats_rows(a);
     if (conv_pw_applicable(dtype, a)) return conv_pw_stats_rows(a);
+    if (halo_wide_applicable(dtype, a)) return halo_wide_stats_rows(a);
     if (igemm_big_applicable(dtype, a)) return igemm_big_stats_rows(a);
     // generic kernel: needs the vector epilogue; one row per wavefront row of every row block.  Measured: with a
     // short reduction the per-block cross-lane sums and the many rows of partial sums cost more than the separate
@@ -442,6 +443,7 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (forced_tile() == 0 && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
     if (forced_tile() == 0 && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
     if (forced_tile() == 0 && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
+    if (forced_tile() == 0 && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
     if (forced_tile() == 0 && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
     IgemmArgs b = a;
     const int vec = dtype == NSK_BF16 ? 8 : 4;

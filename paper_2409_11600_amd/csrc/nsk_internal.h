@@ -105,6 +105,11 @@ int conv_pw_stats_rows(const IgemmArgs &a);
 bool halo64_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64(const IgemmArgs &a, hipStream_t stream);
 int halo64_stats_rows(const IgemmArgs &a);
+// bf16 3x3 stride-1 layers with 128..512 input channels (input rows with halo staged once, filter streamed from L2
+// into MFMA operand registers)
+bool halo_wide_applicable(int dtype, const IgemmArgs &a);
+int launch_halo_wide(const IgemmArgs &a, hipStream_t stream);
+int halo_wide_stats_rows(const IgemmArgs &a);
 // fp32 sibling (filter streamed one tap at a time through LDS)
 bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);

@@ -143,6 +143,63 @@ def test_conv_wide_layers_large_tile_kernel(i, layout, monkeypatch):
     assert max_rel_err(to_host(gdw, layout), want_dw + base_w.astype(np.float64)) <= TOL["f32"] * 10
 
 
+# 3x3 stride-1 bf16 layers with 128..512 input channels for the kernel that stages whole image rows (all channels, with
+# halo) once and streams the filter from L2 into MFMA operand registers.  NSK_HALO_WIDE_ALWAYS lifts its size
+# thresholds so that these small shapes take it.
+HALO_WIDE_SHAPES = [
+    (3, 128, 14, 14, 128),       # one image per tile (14 rows of 16 padded positions), one column block
+    (2, 256, 14, 14, 256),       # the bottleneck-stage layer itself: two column blocks
+    (2, 128, 9, 11, 256),        # the tile ends inside its last position tile
+    (1, 256, 20, 13, 128),       # two tiles per image, the second with fewer rows
+    (2, 128, 30, 30, 128),       # 32 padded positions per row: 7 rows per tile, 5 tiles per image (ragged last one)
+    (1, 512, 7, 7, 128),         # 512 input channels, 72 reduction groups
+    (1, 128, 5, 100, 128),       # wide rows: two rows per tile, halo of 103 positions on each side
+    (1, 128, 3, 220, 128),       # one row per tile
+]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("i", range(len(HALO_WIDE_SHAPES)))
+def test_conv_wide_halo_kernel(i, layout, monkeypatch):
+    monkeypatch.setenv("NSK_HALO_WIDE_ALWAYS", "1")
+    N, C, H, W, K = HALO_WIDE_SHAPES[i]
+    print(f"wide halo conv case {i} {HALO_WIDE_SHAPES[i]} layout={layout}", flush=True)
+    dtype, st, pd, dl = "bf16", 1, 1, 1
+    x = on_grid(gen.normal(1300 + i, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(1300 + i, 1, (K, C, 3, 3)), dtype)
+    dy = on_grid(gen.normal(1300 + i, 2, (N, K, H, W)), dtype)
+    base = on_grid(gen.normal(1300 + i, 3, x.shape), dtype)
+    tol = TOL[dtype]
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    y_view, y_check = guarded(gdy.shape, torch_dtype(dtype))
+    B.conv2d_fwd(gx, gw, st, pd, dl, layout, out=y_view, ws=ws)
+    y1, stats = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    y2, _ = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    if C == K:       # backward-data of a C -> K layer is a K -> C layer: the kernel needs 128..512 channels there too
+        dx_view, dx_check = guarded(gx.shape, torch_dtype(dtype))
+        B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, out=dx_view, ws=ws)
+        gacc = to_gpu(base, dtype, layout)
+        B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, out=gacc, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    y_check()
+    want_y = oracle.conv2d_fwd(x, w, st, pd, dl)
+    assert max_rel_err(to_host(y_view, layout), want_y) <= tol
+    assert torch.equal(y1, y2) and torch.equal(y1.flatten(), y_view.reshape(y1.shape).flatten())   # reproducible; same as plain
+    yh = to_host(y1, layout)
+    sums = stats.double().sum(dim=1).cpu().numpy()
+    want0, want1 = yh.sum(axis=(0, 2, 3)), (yh * yh).sum(axis=(0, 2, 3))
+    assert np.max(np.abs(sums[0] - want0) / (np.sqrt(want1 * yh[:, 0].size) + 1e-30)) <= 1e-6
+    assert np.max(np.abs(sums[1] - want1) / (want1 + 1e-30)) <= 1e-5
+    if C == K:
+        dx_check()
+        want_dx = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl)
+        assert max_rel_err(to_host(dx_view, layout), want_dx) <= tol
+        want_acc = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl, into=base.astype(np.float64))
+        assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
+
+
+
 # Short-reduction bf16 layers (1, 2 or 4 taps, at most 256 reduction indices) for the kernel that keeps the filter
 # in LDS and loads pixels straight into MFMA operands.
 PW_SHAPES = [
