@@ -1,7 +1,8 @@
-// 3x3, stride 1, bf16 convolution with many channels (128, 256 or 512 in, a multiple of 128 out): forward, and
-// backward-data through the packed transposed filter.  These are the 3x3 layers of the later bottleneck stages of
-// the residual networks the paper trains (section "Experiments and Discussion"); with 2304 or more reduction indices
-// they are the layers where the matrix units, not memory, should be the limit.
+// 3x3 bf16 convolution with many channels (128 or 256 in, a multiple of 128 out): forward and backward-data of
+// stride-1 layers, and backward-data of strided layers (whose residue classes are stride-1 convolutions over dy).
+// These are the 3x3 layers of the later bottleneck stages of the residual networks the paper trains (section
+// "Experiments and Discussion"); with 2304 or more reduction indices they are the layers where the matrix units, not
+// memory, should be the limit.
 //
 // The large-tile kernel re-stages every activation row nine times (once per tap) and every filter row once per row
 // block, all through LDS: 144 KB of LDS traffic and 48 KB of L2 traffic per 1024 MFMA clocks, which holds it below
@@ -27,7 +28,7 @@ namespace {
 
 constexpr unsigned W_OOB = 0xF0000000u;
 constexpr int W_BN = 128;                           // output channels per block
-constexpr int W_LDS_MAX = 152 * 1024;               // staged input + output row table
+constexpr int W_LDS_MAX = 160 * 1024;               // epilogue strips + staged input + tables
 constexpr int W_MAXLD = 36;                         // 16-byte loads the moving wavefront keeps in flight
 constexpr int W_THREADS = 320;                      // four multiplying wavefronts and one that moves data
 constexpr int W_STAGE_MAX = 576;                    // staged positions of a tile, at most (two rounds of the moving wavefront)
@@ -36,30 +37,61 @@ constexpr int W_LD0 = (W_STAGE_MAX * 8 + W_THREADS - 1) / W_THREADS;   // loads 
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) const bf16x8 lds_bf16x8;
 
+// 16-byte LDS read at a 32-bit LDS address (no generic-pointer arithmetic: the address register goes straight into
+// the instruction, constants into its offset field)
+__device__ __forceinline__ bf16x8 lds_read16(unsigned addr)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return *(lds_bf16x8 *)addr;
+#else
+    return bf16x8{};   // the host pass only parses this (its pointers are 64 bits wide)
+#endif
+}
+
+constexpr int W_CLS = 4;     // output classes of one launch
+
+// One launch = up to four "classes" that read the same source tensor through the same tiles and write disjoint
+// position sets of the same output tensor: the forward pass and the backward-data pass of a stride-1 layer have one
+// class with nine taps; the backward-data pass of a stride-2 3x3 layer has four (the residue classes of the output
+// position modulo 2, with 4, 2, 2 and 1 taps), each a stride-1 convolution over the same dy tile.
 struct WideArgs {
-    const void *src, *wpk;
+    const void *src;
     void *out;
-    int N, H, W, C, K, Co;
+    const void *wpk[W_CLS];       // packed filter of each class: [K][ntaps][C]
+    unsigned wpk_bytes[W_CLS];
+    int ntaps[W_CLS];
+    int Mi[W_CLS], Mj[W_CLS];     // output extent of each class in tile coordinates
+    int oa[W_CLS], ob[W_CLS];     // output position of (i, j): (i*osh + oa, j*osw + ob)
+    unsigned long long tapcode[W_CLS];   // 4 bits per tap: (dh + 1) * 4 + (dw + 1)
+    int ncls;
+    int N, H, W, C, K;            // source extent, channels in, channels out
+    int Ho, Wo, Co, osh, osw;
     int PW;                       // padded width W + 2
     int rows_per_tile, tiles_per_img, tiles;
     int n_stage;                  // staged positions: NT*32 + 2*(PW + 1)
     int row_bytes;                // LDS bytes per staged position: 2*C + 16
     unsigned long long magic_pw;  // ceil(2^40 / PW)
-    unsigned src_bytes, wpk_bytes, out_bytes;
-    int accumulate;
-    int tapbyte[9];               // LDS byte shift of each tap: (PW + 1 + dh*PW + dw) * row_bytes
-    float *stats;                 // per-channel partial sums of the stored output (one row per tile), or nullptr
+    unsigned src_bytes, out_bytes;
+    float *stats;                 // single class only: per-channel partial sums of the stored output (one row per tile)
     int stats_rows;
 };
+
+template <typename T> __device__ __forceinline__ T sel4(const T (&v)[W_CLS], int c)
+{
+    return c == 0 ? v[0] : c == 1 ? v[1] : c == 2 ? v[2] : v[3];
+}
 
 template <int NT, bool ACCUM>
 __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArgs a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *in_lds = smem;
-    unsigned *out_tab = (unsigned *)(smem + a.n_stage * a.row_bytes);   // NT*32 byte offsets of the output rows
-    unsigned *in_tab = out_tab + NT * 32;                               // W_TAB byte offsets of the staged positions
+    constexpr int SROW = 80;                                            // epilogue strip row: 32 channels bf16 + 16 pad
+    unsigned char *strips = smem;                                       // 4 wavefronts x 32 rows
+    unsigned char *in_lds = smem + 4 * 32 * SROW;
+    unsigned *out_tab = (unsigned *)(in_lds + a.n_stage * a.row_bytes); // per class NT*32 byte offsets of the output rows
+    unsigned *in_tab = out_tab + W_CLS * NT * 32;                       // W_TAB byte offsets of the staged positions
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -73,27 +105,38 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
     const int n0 = nt * W_BN;
 
     const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
-    const __amdgpu_buffer_rsrc_t wpk_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.wpk, 0, a.wpk_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, a.out_bytes, 0x00020000);
 
     const int cpt = a.C >> 6;    // 64-channel groups
     const unsigned tile_step = (unsigned)(32 * a.row_bytes);
 
-    // ---- filter stream (wavefronts 0..3): lane (row r = lane % 32, half h = lane / 32) reads bytes [64h, 64h + 64) of
-    // the 128 bytes that one (tap, 64-channel group) occupies in filter row n0 + 32*wave + r.  Groups are the outer
-    // loop, taps the inner.  The first three pieces are requested before anything else.
-    const unsigned wrow = (unsigned)(n0 + (wave & 3) * 32 + frow) * (unsigned)(9 * a.C * 2) + (unsigned)(fk * 64);
+    // ---- filter stream (wavefronts 0..3).  The reduction runs over "pieces": one (class, 64-channel group, tap),
+    // classes outermost, taps innermost.  Lane (row r = lane % 32, half h = lane / 32) reads bytes [64h, 64h + 64) of
+    // the 128 bytes a piece occupies in filter row n0 + 32*wave + r of its class.  Three pieces are in flight; the
+    // first three of a class are requested before the epilogue of the class before it.
+    const unsigned wrow_idx = (unsigned)(n0 + (wave & 3) * 32 + frow);
     u32x4 wf[3][4];
-    int ld_t = 0, ld_g = 0;      // (tap, group) of the next filter piece to load
-    auto load_w = [&](u32x4 (&Wf)[4]) {
-        const unsigned off = ld_g < cpt ? wrow + (unsigned)(ld_t * a.C * 2 + ld_g * 128) : W_OOB;
+    // per class: filter descriptor, taps, byte offset of the lane's row; (tap, group) of the next piece to load
+    __amdgpu_buffer_rsrc_t w_rs;
+    int w_ntaps = 1, ld_t = 0, ld_g = 0;
+    unsigned w_row = 0;
+    auto filter_class = [&](int c) {
+        w_ntaps = sel4(a.ntaps, c);
+        w_rs = __builtin_amdgcn_make_buffer_rsrc((void *)sel4(a.wpk, c), 0, sel4(a.wpk_bytes, c), 0x00020000);
+        w_row = wrow_idx * (unsigned)(w_ntaps * a.C * 2) + (unsigned)(fk * 64);
+        ld_t = 0;
+        ld_g = 0;
+    };
+    auto load_w = [&](u32x4 (&Wf)[4]) {   // past the last piece of the class: nothing (zeros)
+        const unsigned off = ld_g < cpt ? w_row + (unsigned)(ld_t * a.C * 2 + ld_g * 128) : W_OOB;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) Wf[s] = __builtin_amdgcn_raw_buffer_load_b128(wpk_rsrc, off + (unsigned)(s * 16), 0, 0);
-        if (++ld_t == 9) {
+        for (int s = 0; s < 4; ++s) Wf[s] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, off + (unsigned)(s * 16), 0, 0);
+        if (++ld_t >= w_ntaps) {
             ld_t = 0;
             ++ld_g;
         }
     };
+    filter_class(0);
     if (wave < 4) {
         load_w(wf[0]);
         load_w(wf[1]);
@@ -103,9 +146,9 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
     // ---- staging.  Staged position s is position r0*PW - 1 + s of the zero-padded image (row-major from the top-left
     // corner of the padding); in_tab[s] is its byte offset in src, or out of range for padding.  The tile is staged
     // one 64-channel group at a time: group 0 by all five wavefronts, group g+1 by the fifth wavefront alone while the
-    // other four multiply group g (they meet at one barrier per group).  After the first group no input load is
-    // exposed, and the multiplying wavefronts have nothing but their filter stream in their (in-order) load queue.
-    // One-time code is kept short on purpose: a block runs once per launch, so all of it is fetched cold.
+    // other four multiply group g of the first class (they meet at one barrier per group).  After the first group no
+    // input load is exposed, and the multiplying wavefronts have nothing but their filter stream in their (in-order)
+    // load queue.  One-time code is kept short on purpose: a block runs once per launch, so all of it is fetched cold.
     for (int s = tid; s < W_TAB; s += W_THREADS) {
         // u counts from one row above the padded image (so that it is never negative): u / PW is the image row + 2,
         // u % PW the image column + 1
@@ -115,12 +158,12 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
         const bool ok = s < a.n_stage && (hp1 - 2u < (unsigned)a.H) && (wp - 1u < (unsigned)a.W);
         in_tab[s] = ok ? (((unsigned)(img * a.H) + (hp1 - 2u)) * (unsigned)a.W + (wp - 1u)) * (unsigned)(a.C * 2) : W_OOB;
     }
-    if (tid < NT * 32) {   // output row of position p of the tile
-        const int p = tid;
+    for (int e = tid; e < a.ncls * NT * 32; e += W_THREADS) {   // output row of position p of the tile, per class
+        const int c = e / (NT * 32), p = e - c * (NT * 32);
         const unsigned pr = (unsigned)(((unsigned long long)(unsigned)p * a.magic_pw) >> 40), pc = (unsigned)p - pr * (unsigned)a.PW;
         const int row = r0 + (int)pr, col = (int)pc - 1;
-        const bool ok = (int)pr < a.rows_per_tile && row < a.H && (unsigned)col < (unsigned)a.W;
-        out_tab[p] = ok ? (unsigned)((img * a.H + row) * a.W + col) * (unsigned)(a.Co * 2) : W_OOB;
+        const bool ok = (int)pr < a.rows_per_tile && row < sel4(a.Mi, c) && (unsigned)col < (unsigned)sel4(a.Mj, c);
+        out_tab[e] = ok ? (unsigned)((img * a.Ho + row * a.osh + sel4(a.oa, c)) * a.Wo + col * a.osw + sel4(a.ob, c)) * (unsigned)(a.Co * 2) : W_OOB;
     }
     lds_barrier();   // the tables
     {
@@ -156,123 +199,190 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
             }
             lds_barrier();   // group g is staged
         }
-        __syncthreads();     // matches the barrier before the epilogue
         return;
     }
 
     // ---- accumulators: acc[p][4g+j] is channel 8g + 4*fk + j (of the wavefront's 32) at position 32p + frow
     f32x16 acc[NT];
     const int wcol0 = n0 + wave * 32;
-    if (ACCUM) {
-#pragma unroll
-        for (int p = 0; p < NT; ++p) {
-            const unsigned off = out_tab[p * 32 + frow];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = wcol0 + g * 8 + fk * 4;
-                const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(out_rsrc, off != W_OOB ? off + (unsigned)(col * 2) : W_OOB, 0, 0);
-                const bf16x4 ob = __builtin_bit_cast(bf16x4, old);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[p][g * 4 + j] = (float)ob[j];
-            }
-        }
-    } else {
-#pragma unroll
-        for (int p = 0; p < NT; ++p)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
-    }
-
-    // ---- main loop over (64-channel group, tap).  The pixel fragments of k-step s+1 are read one by one behind the
-    // MFMAs of k-step s; the last k-step of a tap already reads the next tap's first fragments.
-    const unsigned lane_base = (unsigned)(frow * a.row_bytes + fk * 64);
-    unsigned bp[NT];
-    bf16x8 pf[2][NT];
-    for (int g = 0; g < cpt; ++g) {
-        if (g > 0) lds_barrier();   // group g is staged
-        {
-            const unsigned b0 = lane_base + (unsigned)(a.tapbyte[0] + g * 128);
+    auto init_acc = [&](int cls) {
+        if (ACCUM) {   // start from the old values: the sum is rounded to bf16 exactly once
 #pragma unroll
             for (int p = 0; p < NT; ++p) {
-                bp[p] = b0 + (unsigned)p * tile_step;
-                pf[0][p] = *(const bf16x8 *)(in_lds + bp[p]);
-            }
-        }
+                const unsigned off = out_tab[cls * (NT * 32) + p * 32 + frow];
 #pragma unroll
-        for (int t = 0; t < 9; ++t) {
-            const unsigned to_next = t < 8 ? (unsigned)(a.tapbyte[t < 8 ? t + 1 : 0] - a.tapbyte[t]) : 0u;   // wraps for negative steps
+                for (int g = 0; g < 4; ++g) {
+                    const int col = wcol0 + g * 8 + fk * 4;
+                    const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(out_rsrc, off != W_OOB ? off + (unsigned)(col * 2) : W_OOB, 0, 0);
+                    const bf16x4 ob = __builtin_bit_cast(bf16x4, old);
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const bf16x8 wfrag = __builtin_bit_cast(bf16x8, wf[t % 3][s]);
-#pragma unroll
-                for (int p = 0; p < NT; ++p) {
-                    acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag, pf[s & 1][p], acc[p], 0, 0, 0);
-                    if (s < 3) {
-                        pf[(s + 1) & 1][p] = *(const bf16x8 *)(in_lds + bp[p] + (s + 1) * 16);
-                    } else if (t < 8) {
-                        bp[p] += to_next;
-                        pf[0][p] = *(const bf16x8 *)(in_lds + bp[p]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int j = 0; j < 4; ++j) acc[p][g * 4 + j] = (float)ob[j];
                 }
             }
-            load_w(wf[t % 3]);
+        } else {
+#pragma unroll
+            for (int p = 0; p < NT; ++p)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[p][v] = 0.f;
         }
-    }
-    __syncthreads();   // every wavefront is done with the staged input: it becomes the epilogue staging area
+    };
 
-    // ---- epilogue: round to bf16, transpose one 32x32 accumulator at a time through this wavefront's strip, store
-    // 16 contiguous bytes per lane (64 bytes per position and wavefront)
-    constexpr int SROW = 80;   // 32 channels bf16 + 16 pad
-    unsigned char *my_st = smem + wave * (32 * SROW);
-    float ssum[8], ssq[8];
+    // ---- epilogue of one class: round to bf16, transpose one 32x32 accumulator at a time through this wavefront's
+    // strip, store 16 contiguous bytes per lane (64 bytes per position and wavefront)
+    unsigned char *my_st = strips + wave * (32 * SROW);
+    auto epilogue = [&](int cls) {
+        float ssum[8], ssq[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) ssum[e] = ssq[e] = 0.f;
-    // out_tab lies behind the staged input, the strips at its start: no overlap as long as n_stage*row_bytes >= 4*32*80
+        for (int e = 0; e < 8; ++e) ssum[e] = ssq[e] = 0.f;
 #pragma unroll
-    for (int p = 0; p < NT; ++p) {
+        for (int p = 0; p < NT; ++p) {
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            bf16x4 pk;
+            for (int g = 0; g < 4; ++g) {
+                bf16x4 pk;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) pk[j] = (bf16_t)acc[p][g * 4 + j];
-            *(bf16x4 *)(my_st + frow * SROW + (g * 8 + fk * 4) * 2) = pk;
-        }
+                for (int j = 0; j < 4; ++j) pk[j] = (bf16_t)acc[p][g * 4 + j];
+                *(bf16x4 *)(my_st + frow * SROW + (g * 8 + fk * 4) * 2) = pk;
+            }
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int idx = lane + 64 * jj, pos = idx >> 2, ck = idx & 3;
-            const u32x4 v = *(const u32x4 *)(my_st + pos * SROW + ck * 16);
-            const unsigned off = out_tab[p * 32 + pos];
-            const bool live = off != W_OOB;
-            __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, live ? off + (unsigned)((wcol0 + ck * 8) * 2) : W_OOB, 0, 0);
-            if (a.stats && live) {
-                const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
+            for (int jj = 0; jj < 2; ++jj) {
+                const int idx = lane + 64 * jj, pos = idx >> 2, ck = idx & 3;
+                const u32x4 v = *(const u32x4 *)(my_st + pos * SROW + ck * 16);
+                const unsigned off = out_tab[cls * (NT * 32) + p * 32 + pos];
+                const bool live = off != W_OOB;
+                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, live ? off + (unsigned)((wcol0 + ck * 8) * 2) : W_OOB, 0, 0);
+                if (a.stats && live) {
+                    const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float f = (float)vb[e];
-                    ssum[e] += f;
-                    ssq[e] += f * f;
+                    for (int e = 0; e < 8; ++e) {
+                        const float f = (float)vb[e];
+                        ssum[e] += f;
+                        ssq[e] += f * f;
+                    }
                 }
             }
         }
-    }
-    if (a.stats) {
-        // lanes with the same lane % 4 hold the same 8 channels
+        if (a.stats) {
+            // lanes with the same lane % 4 hold the same 8 channels
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+            for (int e = 0; e < 8; ++e)
 #pragma unroll
-            for (int o = 4; o < 64; o <<= 1) {
-                ssum[e] += __shfl_xor(ssum[e], o, 64);
-                ssq[e] += __shfl_xor(ssq[e], o, 64);
+                for (int o = 4; o < 64; o <<= 1) {
+                    ssum[e] += __shfl_xor(ssum[e], o, 64);
+                    ssq[e] += __shfl_xor(ssq[e], o, 64);
+                }
+            if (lane < 4) {
+                float *r0p = a.stats + (size_t)tile * a.K + wcol0 + lane * 8;
+                float *r1p = r0p + (size_t)a.stats_rows * a.K;
+                *(f32x4 *)r0p = f32x4{ssum[0], ssum[1], ssum[2], ssum[3]};
+                *(f32x4 *)(r0p + 4) = f32x4{ssum[4], ssum[5], ssum[6], ssum[7]};
+                *(f32x4 *)r1p = f32x4{ssq[0], ssq[1], ssq[2], ssq[3]};
+                *(f32x4 *)(r1p + 4) = f32x4{ssq[4], ssq[5], ssq[6], ssq[7]};
             }
-        if (lane < 4) {
-            float *r0p = a.stats + (size_t)tile * a.K + wcol0 + lane * 8;
-            float *r1p = r0p + (size_t)a.stats_rows * a.K;
-            *(f32x4 *)r0p = f32x4{ssum[0], ssum[1], ssum[2], ssum[3]};
-            *(f32x4 *)(r0p + 4) = f32x4{ssum[4], ssum[5], ssum[6], ssum[7]};
-            *(f32x4 *)r1p = f32x4{ssq[0], ssq[1], ssq[2], ssq[3]};
-            *(f32x4 *)(r1p + 4) = f32x4{ssq[4], ssq[5], ssq[6], ssq[7]};
         }
+    };
+
+    // ---- main loop over the pieces.  The pixel fragments of k-step s+1 are read one by one behind the MFMAs of k-step
+    // s; the last k-step of a piece already reads the next piece's first fragments, unless that piece opens a group
+    // that is still being staged (first class only: then they are read after the barrier) or a new class.
+    // lane 16*c + t keeps the LDS shift of tap t = (dh, dw) of class c: (PW + 1 + dh*PW + dw) * row_bytes
+    const int my_code = (int)(sel4(a.tapcode, lane >> 4) >> (4 * (lane & 15))) & 15;
+    const int my_tap = (a.PW + 1 + ((my_code >> 2) - 1) * a.PW + ((my_code & 3) - 1)) * a.row_bytes;
+    const unsigned lane_base = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)in_lds + (unsigned)(frow * a.row_bytes + fk * 64);
+    unsigned bp[NT];
+    bf16x8 pf[2][NT];
+    int cls = 0, tap = 0, grp = 0;      // the piece being multiplied
+    int ntaps_c = a.ntaps[0];
+    auto first_fragments = [&]() {
+        const unsigned b0 = lane_base + (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tap) + grp * 128);
+#pragma unroll
+        for (int p = 0; p < NT; ++p) {
+            bp[p] = b0 + (unsigned)p * tile_step;
+            asm volatile("" : "+v"(bp[p]));
+            pf[0][p] = lds_read16(bp[p]);
+        }
+    };
+    init_acc(0);
+    first_fragments();
+    // The bookkeeping of a piece (which piece follows, where its fragments and the next filter piece lie) is spread
+    // over the gaps between its first MFMAs: a wavefront issues in order, and fifty scalar instructions between two
+    // pieces would cost several MFMA slots.
+    auto piece = [&](u32x4 (&Wf)[4]) {
+        int tn = 0, gn = 0;
+        bool wait_group = false;
+        unsigned to_next = 0u, w_off = W_OOB;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bf16x8 wfrag = __builtin_bit_cast(bf16x8, Wf[s]);
+#pragma unroll
+            for (int p = 0; p < NT; ++p) {
+                acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag, pf[s & 1][p], acc[p], 0, 0, 0);
+                if (s < 3) {
+                    pf[(s + 1) & 1][p] = lds_read16(bp[p] + (s + 1) * 16);
+                } else {
+                    bp[p] += to_next;
+                    asm volatile("" : "+v"(bp[p]));   // keep the running address in its register (else: base + scalar sum, one add per read)
+                    pf[0][p] = lds_read16(bp[p]);
+                }
+                if (s == 0 && p == 0) {   // the piece after this one
+                    tn = tap + 1;
+                    gn = grp;
+                    if (tn == ntaps_c) {
+                        tn = 0;
+                        ++gn;
+                    }
+                }
+                if (s == 0 && p == 1) {
+                    const bool class_ends = gn == cpt;
+                    wait_group = !class_ends && tn == 0 && cls == 0;   // group gn of the first class: staged behind a barrier
+                    // without a piece to read ahead the fragments are re-read where they are: in range, unused
+                    if (!class_ends && !wait_group)
+                        to_next = (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tn) + gn * 128) -
+                                  (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tap) + grp * 128);   // wraps for negative steps
+                }
+                if (s == 0 && p == 2) {   // the filter piece to request into this set: three pieces ahead
+                    if (ld_g < cpt) w_off = w_row + (unsigned)(ld_t * a.C * 2 + ld_g * 128);
+                    if (++ld_t >= w_ntaps) {
+                        ld_t = 0;
+                        ++ld_g;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // this k-step's filter fragment is spent
+            Wf[s] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, w_off + (unsigned)(s * 16), 0, 0);
+        }
+        tap = tn;
+        grp = gn;
+        if (wait_group) {
+            lds_barrier();   // group gn is staged
+            first_fragments();
+        }
+    };
+    for (;;) {
+        const int np = ntaps_c * cpt;
+        int i = 0;
+        for (; i + 3 <= np; i += 3) {
+            piece(wf[0]);
+            piece(wf[1]);
+            piece(wf[2]);
+        }
+        if (i < np) piece(wf[0]);
+        if (i + 1 < np) piece(wf[1]);
+        const bool more = cls + 1 < a.ncls;
+        if (more) {   // the next class's filter is on its way while this one is stored
+            filter_class(cls + 1);
+            load_w(wf[0]);
+            load_w(wf[1]);
+            load_w(wf[2]);
+        }
+        epilogue(cls);
+        if (!more) break;
+        ++cls;
+        tap = 0;
+        grp = 0;
+        ntaps_c = w_ntaps;
+        init_acc(cls);
+        first_fragments();
     }
 }
 
@@ -291,64 +401,91 @@ bool make_plan(const IgemmArgs &g, Plan *p)
     p->tiles_per_img = ceil_div(g.Hs, p->rows_per_tile);
     p->n_stage = kNT * 32 + 2 * (PW + 1);
     p->row_bytes = g.Cs * 2 + 16;
-    p->smem = p->n_stage * p->row_bytes + (kNT * 32 + W_TAB) * 4;
+    p->smem = 4 * 32 * 80 + p->n_stage * p->row_bytes + (W_CLS * kNT * 32 + W_TAB) * 4;
     return p->smem <= W_LDS_MAX && p->n_stage <= W_STAGE_MAX;
 }
 
-}  // namespace
-
-bool halo_wide_applicable(int dtype, const IgemmArgs &a)
+// Shape tests of one class; `first` is the class the shared fields are compared with.
+bool class_ok(const IgemmArgs &a, const IgemmArgs &first)
 {
-    if (dtype != NSK_BF16 || getenv("NSK_NO_HALO_WIDE") != nullptr) return false;
-    if (a.ntaps != 9 || (a.Cs != 128 && a.Cs != 256 && a.Cs != 512) || a.Ngemm % W_BN != 0 || a.Co % 8 != 0) return false;
-    if (a.Ktot != 9 * a.Cs) return false;
-    if (a.mult_h != 1 || a.mult_w != 1 || a.osh != 1 || a.osw != 1 || a.oa != 0 || a.ob != 0) return false;
-    if (a.Hs != a.Ho || a.Ws != a.Wo || a.Mi != a.Ho || a.Mj != a.Wo) return false;
-    for (int t = 0; t < 9; ++t) {
+    if (a.ntaps < 1 || a.ntaps > 9 || (a.Cs != 128 && a.Cs != 256) || a.Ngemm % W_BN != 0 || a.Co % 8 != 0) return false;
+    if (a.Ktot != a.ntaps * a.Cs || a.stats_rows < 0) return false;
+    if (a.mult_h != 1 || a.mult_w != 1 || a.Mi > a.Hs || a.Mj > a.Ws || a.Mi < 1 || a.Mj < 1) return false;
+    if (a.osh < 1 || a.osw < 1 || a.oa < 0 || a.ob < 0) return false;
+    if ((a.Mi - 1) * a.osh + a.oa >= a.Ho || (a.Mj - 1) * a.osw + a.ob >= a.Wo) return false;
+    for (int t = 0; t < a.ntaps; ++t) {
         const int eh = a.add_h + a.off_h[t], ew = a.add_w + a.off_w[t];
         if (eh < -1 || eh > 1 || ew < -1 || ew > 1) return false;
     }
+    if (a.src != first.src || a.out != first.out || a.Cs != first.Cs || a.Ngemm != first.Ngemm || a.Nimg != first.Nimg ||
+        a.Hs != first.Hs || a.Ws != first.Ws || a.Ho != first.Ho || a.Wo != first.Wo || a.Co != first.Co || a.osh != first.osh ||
+        a.osw != first.osw || a.accumulate != first.accumulate || a.src_bytes != first.src_bytes)
+        return false;
+    if ((unsigned long long)a.wpk_bytes >= W_OOB || ((uintptr_t)a.wpk & 15)) return false;
+    return true;
+}
+
+bool classes_ok(const IgemmArgs *a, int count)
+{
+    if (count < 1 || count > W_CLS) return false;
+    for (int i = 0; i < count; ++i)
+        if (!class_ok(a[i], a[0])) return false;
     Plan p;
-    if (!make_plan(a, &p)) return false;
-    const long long out_bytes = (long long)a.Nimg * a.Ho * a.Wo * a.Co * 2;
-    if ((unsigned long long)a.src_bytes >= W_OOB || (unsigned long long)a.wpk_bytes >= W_OOB || out_bytes >= (long long)W_OOB) return false;
-    if (((uintptr_t)a.src | (uintptr_t)a.wpk | (uintptr_t)a.out) & 15) return false;
+    if (!make_plan(a[0], &p)) return false;
+    const long long out_bytes = (long long)a[0].Nimg * a[0].Ho * a[0].Wo * a[0].Co * 2;
+    if ((unsigned long long)a[0].src_bytes >= W_OOB || out_bytes >= (long long)W_OOB) return false;
+    if (((uintptr_t)a[0].src | (uintptr_t)a[0].out) & 15) return false;
     // the positions a tile computes beyond the image rows it owns are wasted MFMA work: take the layer only if at
     // least two thirds of it is useful, and only if the tiles fill a good part of the chip (NSK_HALO_WIDE_ALWAYS:
     // test hook, small shapes)
     if (getenv("NSK_HALO_WIDE_ALWAYS") != nullptr) return true;
-    const long long useful = (long long)a.Hs * a.Ws, computed = (long long)p.tiles_per_img * kNT * 32;
+    const long long useful = (long long)a[0].Hs * a[0].Ws, computed = (long long)p.tiles_per_img * kNT * 32;
     if (useful * 3 < computed * 2) return false;
-    return (long long)a.Nimg * p.tiles_per_img * (a.Ngemm / W_BN) >= 128;
+    return (long long)a[0].Nimg * p.tiles_per_img * (a[0].Ngemm / W_BN) >= 128;
 }
 
-int halo_wide_stats_rows(const IgemmArgs &a)
+int launch_classes(const IgemmArgs *g, int count, hipStream_t stream)
 {
     Plan p;
-    if (a.accumulate || !make_plan(a, &p)) return 0;
-    return a.Nimg * p.tiles_per_img;
-}
-
-int launch_halo_wide(const IgemmArgs &g, hipStream_t stream)
-{
-    Plan p;
-    if (!make_plan(g, &p)) return NSK_ERR_BAD_DESC;
+    if (!make_plan(g[0], &p)) return NSK_ERR_BAD_DESC;
+    // longest reduction first: the staging of the later channel groups hides behind the first class
+    int order[W_CLS];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && g[order[j]].ntaps > g[order[j - 1]].ntaps; --j) {
+            const int t = order[j];
+            order[j] = order[j - 1];
+            order[j - 1] = t;
+        }
     WideArgs a{};
-    a.src = g.src; a.wpk = g.wpk; a.out = g.out;
-    a.N = g.Nimg; a.H = g.Hs; a.W = g.Ws; a.C = g.Cs; a.K = g.Ngemm; a.Co = g.Co;
-    a.PW = g.Ws + 2;
+    const IgemmArgs &f = g[0];
+    a.src = f.src; a.out = f.out;
+    a.ncls = count;
+    for (int i = 0; i < count; ++i) {
+        const IgemmArgs &c = g[order[i]];
+        a.wpk[i] = c.wpk; a.wpk_bytes[i] = c.wpk_bytes; a.ntaps[i] = c.ntaps;
+        a.Mi[i] = c.Mi; a.Mj[i] = c.Mj; a.oa[i] = c.oa; a.ob[i] = c.ob;
+        unsigned long long code = 0;
+        for (int t = 0; t < c.ntaps; ++t)
+            code |= (unsigned long long)((c.add_h + c.off_h[t] + 1) * 4 + (c.add_w + c.off_w[t] + 1)) << (4 * t);
+        a.tapcode[i] = code;
+    }
+    for (int i = count; i < W_CLS; ++i) {
+        a.wpk[i] = f.wpk; a.wpk_bytes[i] = 0; a.ntaps[i] = 1;
+    }
+    a.N = f.Nimg; a.H = f.Hs; a.W = f.Ws; a.C = f.Cs; a.K = f.Ngemm;
+    a.Ho = f.Ho; a.Wo = f.Wo; a.Co = f.Co; a.osh = f.osh; a.osw = f.osw;
+    a.PW = f.Ws + 2;
     a.rows_per_tile = p.rows_per_tile;
     a.tiles_per_img = p.tiles_per_img;
-    a.tiles = g.Nimg * p.tiles_per_img;
+    a.tiles = f.Nimg * p.tiles_per_img;
     a.n_stage = p.n_stage;
     a.row_bytes = p.row_bytes;
     a.magic_pw = ((1ULL << 40) + a.PW - 1) / a.PW;
-    a.src_bytes = g.src_bytes; a.wpk_bytes = g.wpk_bytes;
-    a.out_bytes = (unsigned)((long long)g.Nimg * g.Ho * g.Wo * g.Co * 2);
-    a.accumulate = g.accumulate;
-    for (int t = 0; t < 9; ++t)
-        a.tapbyte[t] = (a.PW + 1 + (g.add_h + g.off_h[t]) * a.PW + (g.add_w + g.off_w[t])) * a.row_bytes;
-    a.stats = g.stats; a.stats_rows = g.stats_rows;
+    a.src_bytes = f.src_bytes;
+    a.out_bytes = (unsigned)((long long)f.Nimg * f.Ho * f.Wo * f.Co * 2);
+    a.stats = count == 1 ? f.stats : nullptr;
+    a.stats_rows = f.stats_rows;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)conv_halo_wide_kernel<kNT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS_MAX);
@@ -361,11 +498,43 @@ int launch_halo_wide(const IgemmArgs &g, hipStream_t stream)
         attr_set = true;
     }
     const dim3 grid((unsigned)(a.tiles * (a.K / W_BN)));
-    if (g.accumulate)
+    if (f.accumulate)
         hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, true>), grid, dim3(W_THREADS), p.smem, stream, a);
     else
         hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, false>), grid, dim3(W_THREADS), p.smem, stream, a);
     return check_launch();
 }
+
+}  // namespace
+
+// One class with all nine taps on its own grid: the forward pass, or the backward-data pass of a stride-1 layer.
+bool halo_wide_applicable(int dtype, const IgemmArgs &a)
+{
+    if (dtype != NSK_BF16 || getenv("NSK_NO_HALO_WIDE") != nullptr) return false;
+    if (a.ntaps != 9 || a.osh != 1 || a.osw != 1 || a.oa != 0 || a.ob != 0) return false;
+    if (a.Hs != a.Ho || a.Ws != a.Wo || a.Mi != a.Ho || a.Mj != a.Wo) return false;
+    return classes_ok(&a, 1);
+}
+
+int halo_wide_stats_rows(const IgemmArgs &a)
+{
+    Plan p;
+    if (a.accumulate || !make_plan(a, &p)) return 0;
+    return a.Nimg * p.tiles_per_img;
+}
+
+int launch_halo_wide(const IgemmArgs &g, hipStream_t stream) { return launch_classes(&g, 1, stream); }
+
+// The residue classes of a strided backward-data pass (2..4 argument sets on the same tensors), each a stride-1
+// convolution over the same source grid with at most nine taps.
+bool halo_wide_multi_applicable(int dtype, const IgemmArgs *a, int count)
+{
+    if (dtype != NSK_BF16 || getenv("NSK_NO_HALO_WIDE") != nullptr || count < 2) return false;
+    for (int i = 0; i < count; ++i)
+        if (a[i].stats || a[i].zero_cell) return false;
+    return classes_ok(a, count);
+}
+
+int launch_halo_wide_multi(const IgemmArgs *a, int count, hipStream_t stream) { return launch_classes(a, count, stream); }
 
 }  // namespace nsk

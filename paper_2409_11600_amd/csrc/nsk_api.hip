@@ -432,7 +432,9 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
         }
     // one packing launch for all classes, then their multiplies
     if (n_pending > 0) NSK_TRY(launch_pack_filters(g.dtype, n_pending, w, pk_out, g.C, pk_nt, g.K, w_sn, w_sc, pk_taps, st));
-    if (n_pending > 1 && igemm_big_multi_applicable(g.dtype, pending, n_pending)) {
+    if (n_pending > 1 && halo_wide_multi_applicable(g.dtype, pending, n_pending)) {
+        NSK_TRY(launch_halo_wide_multi(pending, n_pending, st));
+    } else if (n_pending > 1 && igemm_big_multi_applicable(g.dtype, pending, n_pending)) {
         NSK_TRY(launch_igemm_big_multi(pending, n_pending, st));
     } else {
         for (int i = 0; i < n_pending; ++i) NSK_TRY(launch_igemm(g.dtype, pending[i], st));

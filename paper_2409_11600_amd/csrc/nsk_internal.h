@@ -110,6 +110,9 @@ int halo64_stats_rows(const IgemmArgs &a);
 bool halo_wide_applicable(int dtype, const IgemmArgs &a);
 int launch_halo_wide(const IgemmArgs &a, hipStream_t stream);
 int halo_wide_stats_rows(const IgemmArgs &a);
+// the residue classes of one strided backward-data pass of such a layer in one launch, sharing the staged tiles
+bool halo_wide_multi_applicable(int dtype, const IgemmArgs *a, int count);
+int launch_halo_wide_multi(const IgemmArgs *a, int count, hipStream_t stream);
 // fp32 sibling (filter streamed one tap at a time through LDS)
 bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);

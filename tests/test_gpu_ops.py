@@ -143,7 +143,7 @@ def test_conv_wide_layers_large_tile_kernel(i, layout, monkeypatch):
     assert max_rel_err(to_host(gdw, layout), want_dw + base_w.astype(np.float64)) <= TOL["f32"] * 10
 
 
-# 3x3 stride-1 bf16 layers with 128..512 input channels for the kernel that stages whole image rows (all channels, with
+# 3x3 stride-1 bf16 layers with 128 or 256 input channels for the kernel that stages whole image rows (all channels, with
 # halo) once and streams the filter from L2 into MFMA operand registers.  NSK_HALO_WIDE_ALWAYS lifts its size
 # thresholds so that these small shapes take it.
 HALO_WIDE_SHAPES = [
@@ -152,7 +152,7 @@ HALO_WIDE_SHAPES = [
     (2, 128, 9, 11, 256),        # the tile ends inside its last position tile
     (1, 256, 20, 13, 128),       # two tiles per image, the second with fewer rows
     (2, 128, 30, 30, 128),       # 32 padded positions per row: 7 rows per tile, 5 tiles per image (ragged last one)
-    (1, 512, 7, 7, 128),         # 512 input channels, 72 reduction groups
+    (3, 256, 7, 7, 128),         # a tile of 7 rows of 9 padded positions: two of the seven position tiles are live
     (1, 128, 5, 100, 128),       # wide rows: two rows per tile, halo of 103 positions on each side
     (1, 128, 3, 220, 128),       # one row per tile
 ]
@@ -197,6 +197,51 @@ def test_conv_wide_halo_kernel(i, layout, monkeypatch):
         assert max_rel_err(to_host(dx_view, layout), want_dx) <= tol
         want_acc = oracle.conv2d_dgrad(dy, w, x.shape, st, pd, dl, into=base.astype(np.float64))
         assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
+
+
+
+# Backward-data of strided layers through the same kernel: the residue classes of the output position (four for
+# stride 2) are stride-1 convolutions over the same dy tiles and share one launch.  N, C, H, W, K, R, stride, pad
+HALO_WIDE_STRIDED = [
+    (2, 128, 28, 28, 128, 3, 2, 1),      # 3x3 stride 2: classes with 4, 2, 2 and 1 taps
+    (2, 256, 14, 14, 256, 3, 2, 1),      # 7x7 dy grid, two column blocks
+    (1, 256, 27, 25, 128, 3, 2, 1),      # odd extents: classes of different sizes
+    (2, 128, 12, 20, 128, 2, 2, 0),      # 2x2 stride 2: four one-tap classes
+    (1, 128, 16, 16, 128, 4, 2, 1),      # 4x4 stride 2: four taps in every class
+    (1, 128, 20, 18, 128, 3, (2, 1), 1), # stride 2 along rows only: two classes with 6 and 3 taps
+]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("i", range(len(HALO_WIDE_STRIDED)))
+def test_conv_wide_halo_kernel_strided_backward_data(i, layout, monkeypatch):
+    monkeypatch.setenv("NSK_HALO_WIDE_ALWAYS", "1")
+    N, C, H, W, K, R, st, pd = HALO_WIDE_STRIDED[i]
+    print(f"wide halo strided dgrad case {i} {HALO_WIDE_STRIDED[i]} layout={layout}", flush=True)
+    dtype, dl = "bf16", 1
+    x_shape = (N, C, H, W)
+    w = on_grid(gen.he_normal(1400 + i, 1, (K, C, R, R)), dtype)
+    P, Q = oracle.conv2d_out_dims(x_shape, w.shape, st, pd, dl)
+    dy = on_grid(gen.normal(1400 + i, 2, (N, K, P, Q)), dtype)
+    base = on_grid(gen.normal(1400 + i, 3, x_shape), dtype)
+    tol = TOL[dtype]
+    ws = B.Workspace()
+    gw, gdy = to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    dx_view, dx_check = guarded(x_shape if layout == B.NSK_NCHW else (N, H, W, C), torch_dtype(dtype))
+    B.conv2d_dgrad(gdy, gw, x_shape, st, pd, dl, layout, out=dx_view, ws=ws)
+    again = torch.empty_like(dx_view)
+    B.conv2d_dgrad(gdy, gw, x_shape, st, pd, dl, layout, out=again, ws=ws)
+    gacc = to_gpu(base, dtype, layout)
+    B.conv2d_dgrad(gdy, gw, x_shape, st, pd, dl, layout, out=gacc, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    dx_check()
+    want_dx = oracle.conv2d_dgrad(dy, w, x_shape, st, pd, dl)
+    got_dx = to_host(dx_view, layout)
+    assert max_rel_err(got_dx, want_dx) <= tol
+    assert np.all(got_dx[want_dx == 0.0] == 0.0)
+    assert torch.equal(again, dx_view)
+    want_acc = oracle.conv2d_dgrad(dy, w, x_shape, st, pd, dl, into=base.astype(np.float64))
+    assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
 
 
 
