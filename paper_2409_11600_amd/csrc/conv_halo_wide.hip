@@ -1,4 +1,4 @@
-// 3x3 bf16 convolution with many channels (128 or 256 in, a multiple of 128 out): forward and backward-data of
+// 3x3 bf16 convolution with 64, 128 or 256 input channels and a multiple of 64 output channels: forward and backward-data of
 // stride-1 layers, and backward-data of strided layers (whose residue classes are stride-1 convolutions over dy).
 // These are the 3x3 layers of the later bottleneck stages of the residual networks the paper trains (section
 // "Experiments and Discussion"); with 2304 or more reduction indices they are the layers where the matrix units, not
@@ -15,9 +15,9 @@
 //     pieces in flight.  (The reduction index inside a group is permuted so that those 64 bytes are four operand fragments; the
 //     pixel fragments are read from LDS in the same order.)
 //   * per 32-clock MFMA the main loop issues one 16-byte LDS read per lane; the tile is staged one 64-channel group at
-//     a time by a fifth wavefront, group g+1 while group g is multiplied, so only the first group's loads are exposed
+//     a time by an extra wavefront, group g+1 while group g is multiplied, so only the first group's loads are exposed
 //     (one barrier per group).
-// Block = NT*32 positions x 128 output channels, 4 multiplying wavefronts + 1 that moves data; wavefront w < 4 owns channels 32w..32w+31 of all NT position
+// Block = NT*32 positions x 128 (or 64) output channels, 4 (or 2) multiplying wavefronts + 1 that moves data; wavefront w owns channels 32w..32w+31 of all NT position
 // tiles (NT accumulators of 32x32).  For 14 x 14 images a tile is exactly one image (14 rows of 16 padded positions).
 #include <stdlib.h>
 
@@ -27,13 +27,10 @@ namespace nsk {
 namespace {
 
 constexpr unsigned W_OOB = 0xF0000000u;
-constexpr int W_BN = 128;                           // output channels per block
 constexpr int W_LDS_MAX = 160 * 1024;               // epilogue strips + staged input + tables
 constexpr int W_MAXLD = 36;                         // 16-byte loads the moving wavefront keeps in flight
-constexpr int W_THREADS = 320;                      // four multiplying wavefronts and one that moves data
 constexpr int W_STAGE_MAX = 576;                    // staged positions of a tile, at most (two rounds of the moving wavefront)
 constexpr int W_TAB = 640;                          // entries of the staged-position table (two per thread)
-constexpr int W_LD0 = (W_STAGE_MAX * 8 + W_THREADS - 1) / W_THREADS;   // loads per thread for the first group
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
@@ -72,7 +69,7 @@ struct WideArgs {
     int rows_per_tile, tiles_per_img, tiles;
     int n_stage;                  // staged positions: NT*32 + 2*(PW + 1)
     int row_bytes;                // LDS bytes per staged position: 2*C + 16
-    unsigned long long magic_pw;  // ceil(2^40 / PW)
+    unsigned magic_pw;            // ceil(2^32 / PW): u / PW = mulhi(u, magic_pw) for u * PW < 2^32
     unsigned src_bytes, out_bytes;
     float *stats;                 // single class only: per-channel partial sums of the stored output (one row per tile)
     int stats_rows;
@@ -83,15 +80,24 @@ template <typename T> __device__ __forceinline__ T sel4(const T (&v)[W_CLS], int
     return c == 0 ? v[0] : c == 1 ? v[1] : c == 2 ? v[2] : v[3];
 }
 
-template <int NT, bool ACCUM>
-__global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArgs a)
+// MW multiplying wavefronts (32 output channels each) and one that moves data; at most two wavefronts per SIMD, so
+// that two of the smaller blocks (MW = 2, 64 output channels) share a CU.
+// MODE: 0 plain, 1 accumulate into the old output, 2 plain with the statistics epilogue (single class).
+template <int NT, int MW, int MODE>
+__global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2))) void conv_halo_wide_kernel(const WideArgs a)
 {
+    constexpr int THREADS = (MW + 1) * 64, BN = MW * 32;
+    constexpr bool ACCUM = MODE == 1, STATS = MODE == 2;
+    constexpr int LD0 = (W_STAGE_MAX * 8 + THREADS - 1) / THREADS;   // loads per thread for the first group
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    constexpr int SROW = 80;                                            // epilogue strip row: 32 channels bf16 + 16 pad
-    unsigned char *strips = smem;                                       // 4 wavefronts x 32 rows
-    unsigned char *in_lds = smem + 4 * 32 * SROW;
-    unsigned *out_tab = (unsigned *)(in_lds + a.n_stage * a.row_bytes); // per class NT*32 byte offsets of the output rows
-    unsigned *in_tab = out_tab + W_CLS * NT * 32;                       // W_TAB byte offsets of the staged positions
+    constexpr int SROW = 80, STRIP = 32 * SROW;                        // epilogue strip: 32 rows of 32 channels bf16 + 16 pad
+    unsigned char *strips = smem;                                       // two per multiplying wavefront
+    unsigned char *in_lds = smem + MW * 2 * STRIP;
+    // per position of the tile: byte offset of output position (row*osh, col*osw) (a class adds its own shift), and
+    // (row << 16 | col) in tile-grid coordinates, 0xFFFFFFFF for positions that are no output at all
+    unsigned *out_tab = (unsigned *)(in_lds + a.n_stage * a.row_bytes);
+    unsigned *rc_tab = out_tab + NT * 32;
+    unsigned *in_tab = rc_tab + NT * 32;                                // W_TAB byte offsets of the staged positions
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -99,10 +105,10 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
 
     // block id -> (tile, column block).  Consecutive ids run on different XCDs; with two column blocks an XCD sees
     // only one half of the filter.
-    const int tiles_n = a.K / W_BN;
+    const int tiles_n = a.K / BN;
     const int nt = (int)blockIdx.x % tiles_n, tile = (int)blockIdx.x / tiles_n;
     const int img = tile / a.tiles_per_img, r0 = (tile - img * a.tiles_per_img) * a.rows_per_tile;
-    const int n0 = nt * W_BN;
+    const int n0 = nt * BN;
 
     const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, a.out_bytes, 0x00020000);
@@ -114,7 +120,7 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
     // classes outermost, taps innermost.  Lane (row r = lane % 32, half h = lane / 32) reads bytes [64h, 64h + 64) of
     // the 128 bytes a piece occupies in filter row n0 + 32*wave + r of its class.  Three pieces are in flight; the
     // first three of a class are requested before the epilogue of the class before it.
-    const unsigned wrow_idx = (unsigned)(n0 + (wave & 3) * 32 + frow);
+    const unsigned wrow_idx = (unsigned)(n0 + (wave < MW ? wave : 0) * 32 + frow);
     u32x4 wf[3][4];
     // per class: filter descriptor, taps, byte offset of the lane's row; (tap, group) of the next piece to load
     __amdgpu_buffer_rsrc_t w_rs;
@@ -137,7 +143,7 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
         }
     };
     filter_class(0);
-    if (wave < 4) {
+    if (wave < MW) {
         load_w(wf[0]);
         load_w(wf[1]);
         load_w(wf[2]);
@@ -145,46 +151,46 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
 
     // ---- staging.  Staged position s is position r0*PW - 1 + s of the zero-padded image (row-major from the top-left
     // corner of the padding); in_tab[s] is its byte offset in src, or out of range for padding.  The tile is staged
-    // one 64-channel group at a time: group 0 by all five wavefronts, group g+1 by the fifth wavefront alone while the
-    // other four multiply group g of the first class (they meet at one barrier per group).  After the first group no
+    // one 64-channel group at a time: group 0 by all wavefronts, group g+1 by the last wavefront alone while the
+    // others multiply group g of the first class (they meet at one barrier per group).  After the first group no
     // input load is exposed, and the multiplying wavefronts have nothing but their filter stream in their (in-order)
     // load queue.  One-time code is kept short on purpose: a block runs once per launch, so all of it is fetched cold.
-    for (int s = tid; s < W_TAB; s += W_THREADS) {
+    for (int s = tid; s < W_TAB; s += THREADS) {
         // u counts from one row above the padded image (so that it is never negative): u / PW is the image row + 2,
         // u % PW the image column + 1
         const unsigned u = (unsigned)((r0 + 1) * a.PW - 1 + s);
-        const unsigned hp1 = (unsigned)(((unsigned long long)u * a.magic_pw) >> 40);
+        const unsigned hp1 = __umulhi(u, a.magic_pw);
         const unsigned wp = u - hp1 * (unsigned)a.PW;
         const bool ok = s < a.n_stage && (hp1 - 2u < (unsigned)a.H) && (wp - 1u < (unsigned)a.W);
         in_tab[s] = ok ? (((unsigned)(img * a.H) + (hp1 - 2u)) * (unsigned)a.W + (wp - 1u)) * (unsigned)(a.C * 2) : W_OOB;
     }
-    for (int e = tid; e < a.ncls * NT * 32; e += W_THREADS) {   // output row of position p of the tile, per class
-        const int c = e / (NT * 32), p = e - c * (NT * 32);
-        const unsigned pr = (unsigned)(((unsigned long long)(unsigned)p * a.magic_pw) >> 40), pc = (unsigned)p - pr * (unsigned)a.PW;
+    for (unsigned p = (unsigned)tid; p < (unsigned)(NT * 32); p += THREADS) {   // (fewer threads than positions when MW = 2)
+        const unsigned pr = __umulhi(p, a.magic_pw), pc = p - pr * (unsigned)a.PW;
         const int row = r0 + (int)pr, col = (int)pc - 1;
-        const bool ok = (int)pr < a.rows_per_tile && row < sel4(a.Mi, c) && (unsigned)col < (unsigned)sel4(a.Mj, c);
-        out_tab[e] = ok ? (unsigned)((img * a.Ho + row * a.osh + sel4(a.oa, c)) * a.Wo + col * a.osw + sel4(a.ob, c)) * (unsigned)(a.Co * 2) : W_OOB;
+        const bool ok = (int)pr < a.rows_per_tile && row < a.H && (unsigned)col < (unsigned)a.W;
+        out_tab[p] = (unsigned)((img * a.Ho + row * a.osh) * a.Wo + col * a.osw) * (unsigned)(a.Co * 2);
+        rc_tab[p] = ok ? (unsigned)row << 16 | (unsigned)col : 0xFFFFFFFFu;
     }
     lds_barrier();   // the tables
     {
         const int nvec = a.n_stage * 8;
-        u32x4 st[W_LD0];
+        u32x4 st[LD0];
 #pragma unroll
-        for (int i = 0; i < W_LD0; ++i)
-            if (i * W_THREADS < nvec) {
-                const int v = tid + W_THREADS * i;   // v / 8 < W_TAB: the table ends with out-of-range entries
+        for (int i = 0; i < LD0; ++i)
+            if (i * THREADS < nvec) {
+                const int v = tid + THREADS * i;   // v / 8 < W_TAB: the table ends with out-of-range entries
                 st[i] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, in_tab[v >> 3] + (unsigned)((v & 7) * 16), 0, 0);
             }
 #pragma unroll
-        for (int i = 0; i < W_LD0; ++i)
-            if (i * W_THREADS < nvec) {
-                const int v = tid + W_THREADS * i;
+        for (int i = 0; i < LD0; ++i)
+            if (i * THREADS < nvec) {
+                const int v = tid + THREADS * i;
                 if (v < nvec) *(u32x4 *)(in_lds + (v >> 3) * a.row_bytes + (v & 7) * 16) = st[i];
             }
     }
     lds_barrier();   // group 0 is staged
 
-    if (wave == 4) {
+    if (wave == MW) {
         __builtin_amdgcn_s_setprio(3);   // its few instructions should not queue behind the MFMAs of the wavefront it shares a SIMD with
         const unsigned lds_w0 = (unsigned)((lane >> 3) * a.row_bytes + (lane & 7) * 16);
         for (int g = 1; g < cpt; ++g) {
@@ -205,15 +211,23 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
     // ---- accumulators: acc[p][4g+j] is channel 8g + 4*fk + j (of the wavefront's 32) at position 32p + frow
     f32x16 acc[NT];
     const int wcol0 = n0 + wave * 32;
+    // byte offset of channel wcol0 + 8*ck at position `pos` of the tile in class `cls`, or out of range where the class
+    // has no output
+    auto out_offset = [&](unsigned shift, unsigned mi, unsigned mj, int pos, int ck) -> unsigned {
+        const unsigned rc = rc_tab[pos];
+        const unsigned off = out_tab[pos];
+        return ((rc >> 16) < mi && (rc & 0xFFFFu) < mj) ? off + shift + (unsigned)((wcol0 + ck * 8) * 2) : W_OOB;   // 0xFFFF fails the row test
+    };
     auto init_acc = [&](int cls) {
         if (ACCUM) {   // start from the old values: the sum is rounded to bf16 exactly once
+            const unsigned shift = (unsigned)((sel4(a.oa, cls) * a.Wo + sel4(a.ob, cls)) * a.Co * 2);
+            const unsigned mi = (unsigned)sel4(a.Mi, cls), mj = (unsigned)sel4(a.Mj, cls);
 #pragma unroll
             for (int p = 0; p < NT; ++p) {
-                const unsigned off = out_tab[cls * (NT * 32) + p * 32 + frow];
+                const unsigned off = out_offset(shift, mi, mj, p * 32 + frow, 0);
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int col = wcol0 + g * 8 + fk * 4;
-                    const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(out_rsrc, off != W_OOB ? off + (unsigned)(col * 2) : W_OOB, 0, 0);
+                    const u32x2 old = __builtin_amdgcn_raw_buffer_load_b64(out_rsrc, off != W_OOB ? off + (unsigned)((g * 8 + fk * 4) * 2) : W_OOB, 0, 0);
                     const bf16x4 ob = __builtin_bit_cast(bf16x4, old);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) acc[p][g * 4 + j] = (float)ob[j];
@@ -227,30 +241,37 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
         }
     };
 
-    // ---- epilogue of one class: round to bf16, transpose one 32x32 accumulator at a time through this wavefront's
-    // strip, store 16 contiguous bytes per lane (64 bytes per position and wavefront)
-    unsigned char *my_st = strips + wave * (32 * SROW);
+    // ---- epilogue of one class: round to bf16, transpose one 32x32 accumulator at a time through one of this
+    // wavefront's two strips (tile p+1 is written while tile p is read back), store 16 contiguous bytes per lane (64
+    // bytes per position and wavefront).  Stores of 8 bytes per lane straight from the accumulators need no LDS but
+    // took 2.5 times as long.
+    unsigned char *my_st = strips + wave * (2 * STRIP);
     auto epilogue = [&](int cls) {
+        const unsigned shift = (unsigned)((sel4(a.oa, cls) * a.Wo + sel4(a.ob, cls)) * a.Co * 2);
+        const unsigned mi = (unsigned)sel4(a.Mi, cls), mj = (unsigned)sel4(a.Mj, cls);
         float ssum[8], ssq[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) ssum[e] = ssq[e] = 0.f;
-#pragma unroll
-        for (int p = 0; p < NT; ++p) {
+        auto to_strip = [&](int p) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 bf16x4 pk;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) pk[j] = (bf16_t)acc[p][g * 4 + j];
-                *(bf16x4 *)(my_st + frow * SROW + (g * 8 + fk * 4) * 2) = pk;
+                *(bf16x4 *)(my_st + (p & 1) * STRIP + frow * SROW + (g * 8 + fk * 4) * 2) = pk;
             }
+        };
+        to_strip(0);
+#pragma unroll
+        for (int p = 0; p < NT; ++p) {
+            if (p + 1 < NT) to_strip(p + 1);
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {
                 const int idx = lane + 64 * jj, pos = idx >> 2, ck = idx & 3;
-                const u32x4 v = *(const u32x4 *)(my_st + pos * SROW + ck * 16);
-                const unsigned off = out_tab[cls * (NT * 32) + p * 32 + pos];
-                const bool live = off != W_OOB;
-                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, live ? off + (unsigned)((wcol0 + ck * 8) * 2) : W_OOB, 0, 0);
-                if (a.stats && live) {
+                const unsigned off = out_offset(shift, mi, mj, p * 32 + pos, ck);
+                const u32x4 v = *(const u32x4 *)(my_st + (p & 1) * STRIP + pos * SROW + ck * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, off, 0, 0);
+                if (STATS && off != W_OOB) {
                     const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -261,7 +282,7 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
                 }
             }
         }
-        if (a.stats) {
+        if (STATS) {
             // lanes with the same lane % 4 hold the same 8 channels
 #pragma unroll
             for (int e = 0; e < 8; ++e)
@@ -368,7 +389,7 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
         }
         if (i < np) piece(wf[0]);
         if (i + 1 < np) piece(wf[1]);
-        const bool more = cls + 1 < a.ncls;
+        const bool more = !STATS && cls + 1 < a.ncls;   // the statistics epilogue comes with a single class
         if (more) {   // the next class's filter is on its way while this one is stored
             filter_class(cls + 1);
             load_w(wf[0]);
@@ -388,6 +409,9 @@ __global__ __launch_bounds__(W_THREADS) void conv_halo_wide_kernel(const WideArg
 
 constexpr int kNT = 7;   // position tiles per block of the one instance built
 
+// 128 output channels per block where the layer has a multiple of that, else 64 (blocks of two multiplying wavefronts)
+int block_channels(const IgemmArgs &g) { return g.Ngemm % 128 == 0 ? 128 : 64; }
+
 struct Plan {
     int rows_per_tile, tiles_per_img, n_stage, row_bytes, smem;
 };
@@ -401,14 +425,16 @@ bool make_plan(const IgemmArgs &g, Plan *p)
     p->tiles_per_img = ceil_div(g.Hs, p->rows_per_tile);
     p->n_stage = kNT * 32 + 2 * (PW + 1);
     p->row_bytes = g.Cs * 2 + 16;
-    p->smem = 4 * 32 * 80 + p->n_stage * p->row_bytes + (W_CLS * kNT * 32 + W_TAB) * 4;
+    p->smem = block_channels(g) / 32 * 2 * 32 * 80 + p->n_stage * p->row_bytes + (2 * kNT * 32 + W_TAB) * 4;
+    // (exactness of the reciprocal division of staged positions by PW; rows fit 16 bits)
+    if (((long long)(g.Hs + 3) * PW + W_TAB) * PW >= (1LL << 32) || g.Hs >= 65535) return false;
     return p->smem <= W_LDS_MAX && p->n_stage <= W_STAGE_MAX;
 }
 
 // Shape tests of one class; `first` is the class the shared fields are compared with.
 bool class_ok(const IgemmArgs &a, const IgemmArgs &first)
 {
-    if (a.ntaps < 1 || a.ntaps > 9 || (a.Cs != 128 && a.Cs != 256) || a.Ngemm % W_BN != 0 || a.Co % 8 != 0) return false;
+    if (a.ntaps < 1 || a.ntaps > 9 || (a.Cs != 64 && a.Cs != 128 && a.Cs != 256) || a.Ngemm % 64 != 0 || a.Co % 8 != 0) return false;
     if (a.Ktot != a.ntaps * a.Cs || a.stats_rows < 0) return false;
     if (a.mult_h != 1 || a.mult_w != 1 || a.Mi > a.Hs || a.Mj > a.Ws || a.Mi < 1 || a.Mj < 1) return false;
     if (a.osh < 1 || a.osw < 1 || a.oa < 0 || a.ob < 0) return false;
@@ -441,7 +467,7 @@ bool classes_ok(const IgemmArgs *a, int count)
     if (getenv("NSK_HALO_WIDE_ALWAYS") != nullptr) return true;
     const long long useful = (long long)a[0].Hs * a[0].Ws, computed = (long long)p.tiles_per_img * kNT * 32;
     if (useful * 3 < computed * 2) return false;
-    return (long long)a[0].Nimg * p.tiles_per_img * (a[0].Ngemm / W_BN) >= 128;
+    return (long long)a[0].Nimg * p.tiles_per_img * (a[0].Ngemm / block_channels(a[0])) >= 128;
 }
 
 int launch_classes(const IgemmArgs *g, int count, hipStream_t stream)
@@ -481,27 +507,43 @@ int launch_classes(const IgemmArgs *g, int count, hipStream_t stream)
     a.tiles = f.Nimg * p.tiles_per_img;
     a.n_stage = p.n_stage;
     a.row_bytes = p.row_bytes;
-    a.magic_pw = ((1ULL << 40) + a.PW - 1) / a.PW;
+    a.magic_pw = (unsigned)(((1ULL << 32) + a.PW - 1) / a.PW);
     a.src_bytes = f.src_bytes;
     a.out_bytes = (unsigned)((long long)f.Nimg * f.Ho * f.Wo * f.Co * 2);
     a.stats = count == 1 ? f.stats : nullptr;
     a.stats_rows = f.stats_rows;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)conv_halo_wide_kernel<kNT, false>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS_MAX);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)conv_halo_wide_kernel<kNT, true>, hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS_MAX);
-        if (e != hipSuccess) {
-            set_last_hip_error(e);
-            return NSK_ERR_HIP;
+        const void *k[6] = {(const void *)conv_halo_wide_kernel<kNT, 4, 0>, (const void *)conv_halo_wide_kernel<kNT, 4, 1>,
+                            (const void *)conv_halo_wide_kernel<kNT, 4, 2>, (const void *)conv_halo_wide_kernel<kNT, 2, 0>,
+                            (const void *)conv_halo_wide_kernel<kNT, 2, 1>, (const void *)conv_halo_wide_kernel<kNT, 2, 2>};
+        for (int i = 0; i < 6; ++i) {
+            const hipError_t e = hipFuncSetAttribute(k[i], hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS_MAX);
+            if (e != hipSuccess) {
+                set_last_hip_error(e);
+                return NSK_ERR_HIP;
+            }
         }
         attr_set = true;
     }
-    const dim3 grid((unsigned)(a.tiles * (a.K / W_BN)));
-    if (f.accumulate)
-        hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, true>), grid, dim3(W_THREADS), p.smem, stream, a);
-    else
-        hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, false>), grid, dim3(W_THREADS), p.smem, stream, a);
+    const int bn = block_channels(f);
+    const int mode = f.accumulate ? 1 : a.stats ? 2 : 0;
+    const dim3 grid((unsigned)(a.tiles * (a.K / bn)));
+    if (bn == 128) {
+        if (mode == 1)
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 1>), grid, dim3(320), p.smem, stream, a);
+        else if (mode == 2)
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 2>), grid, dim3(320), p.smem, stream, a);
+        else
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 0>), grid, dim3(320), p.smem, stream, a);
+    } else {
+        if (mode == 1)
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 1>), grid, dim3(192), p.smem, stream, a);
+        else if (mode == 2)
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 2>), grid, dim3(192), p.smem, stream, a);
+        else
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 0>), grid, dim3(192), p.smem, stream, a);
+    }
     return check_launch();
 }
 

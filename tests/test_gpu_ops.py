@@ -155,6 +155,9 @@ HALO_WIDE_SHAPES = [
     (3, 256, 7, 7, 128),         # a tile of 7 rows of 9 padded positions: two of the seven position tiles are live
     (1, 128, 5, 100, 128),       # wide rows: two rows per tile, halo of 103 positions on each side
     (1, 128, 3, 220, 128),       # one row per tile
+    (2, 64, 12, 12, 128),        # 64 input channels: a single channel group, nothing left for the moving wavefront
+    (2, 128, 10, 10, 64),        # 64 output channels: blocks of two multiplying wavefronts
+    (2, 256, 9, 9, 192),         # 192 output channels: three such blocks per tile
 ]
 
 
@@ -209,6 +212,8 @@ HALO_WIDE_STRIDED = [
     (2, 128, 12, 20, 128, 2, 2, 0),      # 2x2 stride 2: four one-tap classes
     (1, 128, 16, 16, 128, 4, 2, 1),      # 4x4 stride 2: four taps in every class
     (1, 128, 20, 18, 128, 3, (2, 1), 1), # stride 2 along rows only: two classes with 6 and 3 taps
+    (2, 64, 20, 24, 64, 3, 2, 1),        # 64 -> 64: one channel group, blocks of two multiplying wavefronts
+    (1, 192, 14, 14, 64, 3, 2, 1),       # 192 output channels of the backward pass: three blocks per tile
 ]
 
 
