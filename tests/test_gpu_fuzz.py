@@ -1,9 +1,9 @@
 """Seeded sweep over random small convolution problems (both types and layouts, strides 1-3 per axis, padding 0-3,
 dilation 1-2, square and non-square filters, channel counts that select every kernel family), each run forward,
 backward-data (overwrite and accumulate) and backward-weight (overwrite and accumulate) against the oracle.  The
-size thresholds of the special kernels are lowered through their test hooks in three of the four groups, so that the
-small problems the fp64 oracle can afford reach the large-tile, short-reduction and merged-class code paths in
-shapes no hand-written case lists."""
+size thresholds of the special kernels are lowered through their test hooks in four of the five groups, so that the
+small problems the fp64 oracle can afford reach the large-tile, short-reduction, merged-class and wide-halo code
+paths in shapes no hand-written case lists."""
 import numpy as np
 import pytest
 import torch
@@ -21,14 +21,19 @@ HOOKS = [
     {"NSK_PW_MIN_ROWS": "1"},
     {"NSK_BIG_MIN_TILES": "1", "NSK_WIDE_MIN_ROWS": "1"},
     {"NSK_PW_MIN_ROWS": "1", "NSK_BIG_MIN_TILES": "1", "NSK_WIDE_MIN_ROWS": "1", "NSK_STATS_ALWAYS": "1"},
+    {"NSK_HALO_WIDE_ALWAYS": "1"},       # with channel counts the wide halo kernel takes (64, 128, 256 in; multiples of 64 out)
 ]
+WIDE_HALO_GROUP = 4
 CASES_PER_GROUP = 120
 
 
-def _draw(rng):
+def _draw(rng, wide_halo=False):
     while True:
         C, K = (int(rng.choice(CHANNELS)) for _ in range(2))
         R, S = (int(rng.choice([1, 1, 2, 3, 3, 3, 5])) for _ in range(2))
+        if wide_halo:     # both passes reach the kernel: C and K from its channel counts, mostly filters with taps within one pixel
+            C, K = (int(rng.choice([64, 128, 128, 192, 256])) for _ in range(2))
+            R, S = (int(rng.choice([2, 3, 3, 3, 4, 5])) for _ in range(2))
         if rng.random() < 0.7:
             S = R
         sh, sw = (int(rng.choice([1, 1, 1, 2, 2, 3])) for _ in range(2))
@@ -53,7 +58,7 @@ def test_random_convolutions_match_the_oracle(group, monkeypatch):
     rng = np.random.default_rng(4200 + group)
     ws = B.Workspace()
     for case in range(CASES_PER_GROUP):
-        N, C, H, W, K, R, S, st, pd, dl = shape = _draw(rng)
+        N, C, H, W, K, R, S, st, pd, dl = shape = _draw(rng, group == WIDE_HALO_GROUP)
         dtype = "bf16" if rng.random() < 0.65 else "f32"
         layout = B.NSK_NHWC if rng.random() < 0.8 else B.NSK_NCHW
         print(f"fuzz group {group} case {case}: {shape} {dtype} layout={layout} hooks={sorted(HOOKS[group])}", flush=True)
