@@ -261,18 +261,28 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
                 *(bf16x4 *)(my_st + (p & 1) * STRIP + frow * SROW + (g * 8 + fk * 4) * 2) = pk;
             }
         };
+        // tile p's rows are read back (and their output offsets looked up) before tile p+1 is converted and written to
+        // the other strip, and stored after it: the LDS round trip hides behind the conversion
+        u32x4 v[2][2];
+        unsigned off[2][2];
+        auto read_back = [&](int p) {
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int idx = lane + 64 * jj, pos = idx >> 2, ck = idx & 3;
+                off[p & 1][jj] = out_offset(shift, mi, mj, p * 32 + pos, ck);
+                v[p & 1][jj] = *(const u32x4 *)(my_st + (p & 1) * STRIP + pos * SROW + ck * 16);
+            }
+        };
         to_strip(0);
+        read_back(0);
 #pragma unroll
         for (int p = 0; p < NT; ++p) {
             if (p + 1 < NT) to_strip(p + 1);
 #pragma unroll
             for (int jj = 0; jj < 2; ++jj) {
-                const int idx = lane + 64 * jj, pos = idx >> 2, ck = idx & 3;
-                const unsigned off = out_offset(shift, mi, mj, p * 32 + pos, ck);
-                const u32x4 v = *(const u32x4 *)(my_st + (p & 1) * STRIP + pos * SROW + ck * 16);
-                __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, off, 0, 0);
-                if (STATS && off != W_OOB) {
-                    const bf16x8 vb = __builtin_bit_cast(bf16x8, v);
+                __builtin_amdgcn_raw_buffer_store_b128(v[p & 1][jj], out_rsrc, off[p & 1][jj], 0, 0);
+                if (STATS && off[p & 1][jj] != W_OOB) {
+                    const bf16x8 vb = __builtin_bit_cast(bf16x8, v[p & 1][jj]);
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const float f = (float)vb[e];
@@ -281,6 +291,7 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
                     }
                 }
             }
+            if (p + 1 < NT) read_back(p + 1);
         }
         if (STATS) {
             // lanes with the same lane % 4 hold the same 8 channels
