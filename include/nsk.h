@@ -317,6 +317,24 @@ int nsk_gru_gates_fwd(int dtype, int N, int H, const void *gi, const void *gh, c
 int nsk_gru_gates_bwd(int dtype, int N, int H, const void *saved, const void *h_prev, const void *dh_a,
                       const void *dh_b, const void *dh_c, void *dgi, void *dgh, void *dh_direct, void *stream);
 
+/* A whole GRU step in one launch per direction, for the few-row case of the same experiment (batch 50): the
+ * recurrent product and the gate arithmetic fused, so that gh is never stored and a sequence of T steps is 2T
+ * dependent launches instead of 4T.  Same gate convention, same `saved` layout as the two calls above.
+ * nsk_gru_step_supported(N, H) says (1 / 0, host only) whether the sizes are taken: at most 256 rows (the case these
+ * calls are for) and H % 4 == 0; otherwise the calls return NSK_ERR_UNSUPPORTED and the caller uses nsk_linear_* with
+ * nsk_gru_gates_*.
+ * forward: gi [N,3H] (= x_t @ W_ih, without biases), w_hh [3H,H], h_prev -> h_new [N,H], saved [N,4H].
+ * backward: the gradient of h_new is dh_a + dh_direct_next + dgh_next @ W_hh (each may be NULL, not all three):
+ * dh_a arrives from outside the recurrence, dh_direct_next and dgh_next [N,3H] are what this same call wrote for the
+ * step after; w_hh_t [H,3H] is the TRANSPOSED recurrent weight (nsk_transpose2d), so that the column of W_hh a hidden
+ * unit needs is contiguous.  Writes dgi, dgh [N,3H] and dh_direct [N,H] = dh * z as nsk_gru_gates_bwd does. */
+int nsk_gru_step_supported(int N, int H);
+int nsk_gru_step_fwd(int dtype, int N, int H, const void *gi, const void *w_hh, const float *b_ih, const float *b_hh,
+                     const void *h_prev, void *h_new, void *saved, void *stream);
+int nsk_gru_step_bwd(int dtype, int N, int H, const void *saved, const void *h_prev, const void *dh_a,
+                     const void *dh_direct_next, const void *dgh_next, const void *w_hh_t, void *dgi, void *dgh,
+                     void *dh_direct, void *stream);
+
 /* ---------------------------------------------------------------------------------------------------------------
  * Device memory pool and cache (section "Caching and Pooling"): what hands out the raw pointers every entry point
  * above takes, for callers that have no allocator of their own.  Host code; no entry point above uses it.

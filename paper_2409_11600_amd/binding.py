@@ -157,6 +157,12 @@ def lib() -> ctypes.CDLL:
         L.nsk_gru_gates_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp]
         L.nsk_gru_gates_bwd.restype = ci
         L.nsk_gru_gates_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.nsk_gru_step_supported.restype = ci
+        L.nsk_gru_step_supported.argtypes = [ci, ci]
+        L.nsk_gru_step_fwd.restype = ci
+        L.nsk_gru_step_fwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.nsk_gru_step_bwd.restype = ci
+        L.nsk_gru_step_bwd.argtypes = [ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         vpp, szp = ctypes.POINTER(vp), ctypes.POINTER(sz)
         L.nsk_pool_create.restype = ci
         L.nsk_pool_create.argtypes = [ci, vpp]
@@ -184,6 +190,7 @@ EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d
            "nsk_linear_dgrad", "nsk_linear_wgrad", "nsk_transpose2d", "nsk_softmax_xent_fwd", "nsk_softmax_xent_bwd",
            "nsk_sgd_momentum_step", "nsk_adamw_step", "nsk_sgd_momentum_step_multi", "nsk_adamw_step_multi", "nsk_sumsq_accumulate", "nsk_clip_scale",
            "nsk_embedding_fwd", "nsk_embedding_bwd", "nsk_gru_gates_fwd", "nsk_gru_gates_bwd",
+           "nsk_gru_step_supported", "nsk_gru_step_fwd", "nsk_gru_step_bwd",
            "nsk_pool_create", "nsk_pool_get", "nsk_pool_put", "nsk_pool_cached", "nsk_pool_stats", "nsk_pool_destroy")
 NSK_POOL_DEVICE, NSK_POOL_HOST = 0, 1
 NSK_SUMSQ_PARTIALS = 256
@@ -665,6 +672,31 @@ def gru_gates_bwd(saved, h_prev, dh_a, dh_b=None, dh_c=None, dgi=None, dgh=None,
     dh_direct = mk(H) if dh_direct is None else dh_direct
     _check(lib().nsk_gru_gates_bwd(_dtype_code(h_prev), int(N), int(H), _ptr(saved), _ptr(h_prev), _ptr(dh_a), _ptr(dh_b),
                                    _ptr(dh_c), _ptr(dgi), _ptr(dgh), _ptr(dh_direct), _stream()), "nsk_gru_gates_bwd")
+    return dgi, dgh, dh_direct
+
+
+def gru_step_supported(N: int, H: int) -> bool:
+    return bool(lib().nsk_gru_step_supported(int(N), int(H)))
+
+
+def gru_step_fwd(gi, w_hh, b_ih, b_hh, h_prev, h_new=None, saved=None):
+    N, H = h_prev.shape
+    h_new = torch.empty_like(h_prev) if h_new is None else h_new
+    saved = torch.empty((N, 4 * H), dtype=h_prev.dtype, device=h_prev.device) if saved is None else saved
+    _check(lib().nsk_gru_step_fwd(_dtype_code(h_prev), int(N), int(H), _ptr(gi), _ptr(w_hh), _ptr(b_ih), _ptr(b_hh),
+                                  _ptr(h_prev), _ptr(h_new), _ptr(saved), _stream()), "nsk_gru_step_fwd")
+    return h_new, saved
+
+
+def gru_step_bwd(saved, h_prev, w_hh_t, dh_a=None, dh_direct_next=None, dgh_next=None, dgi=None, dgh=None, dh_direct=None):
+    N, H = h_prev.shape
+    mk = lambda w: torch.empty((N, w), dtype=h_prev.dtype, device=h_prev.device)
+    dgi = mk(3 * H) if dgi is None else dgi
+    dgh = mk(3 * H) if dgh is None else dgh
+    dh_direct = mk(H) if dh_direct is None else dh_direct
+    _check(lib().nsk_gru_step_bwd(_dtype_code(h_prev), int(N), int(H), _ptr(saved), _ptr(h_prev), _ptr(dh_a),
+                                  _ptr(dh_direct_next), _ptr(dgh_next), _ptr(w_hh_t), _ptr(dgi), _ptr(dgh), _ptr(dh_direct),
+                                  _stream()), "nsk_gru_step_bwd")
     return dgi, dgh, dh_direct
 
 

@@ -39,8 +39,8 @@ class GpuGruClassifier:
         lp = dt == torch.bfloat16
         self.w = {k: (v.to(dt) if lp and k in ("table", "w_ih", "w_hh", "w_out") else v) for k, v in self.master.items()}
         self.grad = {k: torch.zeros_like(v) for k, v in self.master.items()}
-        # W_hh^T, refreshed after every update: the recurrent product of a step (50 rows) then reads its weight row by
-        # row with contiguous lanes, through the backward-data form of the `@` operator
+        # W_hh^T, refreshed after every update: the backward step kernel reads a hidden unit's column of W_hh as a row of
+        # it (and so does the unfused path's recurrent product, through the backward-data form of the `@` operator)
         self.w_hh_t = torch.empty((self.H, 3 * self.H), dtype=dt, device=dev)
         B.transpose2d(self.w["w_hh"], out=self.w_hh_t)
         z = lambda *s: torch.zeros(s, dtype=dt, device=dev)
@@ -69,6 +69,7 @@ class GpuGruClassifier:
         self.sumsq = torch.empty(1, dtype=torch.float32, device=dev)
         self.scale = torch.empty(1, dtype=torch.float32, device=dev)
         self.t = 0
+        self.fused_steps = B.gru_step_supported(N, H)
 
     def forward(self):
         T, N, H, w = self.T, self.N, self.H, self.w
@@ -76,6 +77,9 @@ class GpuGruClassifier:
         B.linear_fwd(self.x, w["w_ih"], None, out=self.gi, ws=self.ws)
         gi = self.gi.view(T, N, 3 * H)
         for t in range(T):
+            if self.fused_steps:
+                B.gru_step_fwd(gi[t], w["w_hh"], w["b_ih"], w["b_hh"], self.h[t], h_new=self.h[t + 1], saved=self.saved[t])
+                continue
             B.linear_dgrad(self.h[t], self.w_hh_t, out=self.gh, ws=self.ws)      # h @ W_hh (see w_hh_t)
             B.gru_gates_fwd(gi[t], self.gh, w["b_ih"], w["b_hh"], self.h[t], h_new=self.h[t + 1], saved=self.saved[t])
         B.linear_fwd(self.h[T], w["w_out"], w["b_out"], out=self.logits, ws=self.ws)
@@ -89,6 +93,12 @@ class GpuGruClassifier:
         dgi, dgh = self.dgi.view(T, N, 3 * H), self.dgh.view(T, N, 3 * H)
         for t in reversed(range(T)):
             p = t & 1
+            if self.fused_steps:
+                last = t == T - 1
+                B.gru_step_bwd(self.saved[t], self.h[t], self.w_hh_t, dh_a=self.dh_top if last else None,
+                               dh_direct_next=None if last else self.dh_direct[p ^ 1], dgh_next=None if last else dgh[t + 1],
+                               dgi=dgi[t], dgh=dgh[t], dh_direct=self.dh_direct[p])
+                continue
             if t == T - 1:
                 B.gru_gates_bwd(self.saved[t], self.h[t], self.dh_top, dgi=dgi[t], dgh=dgh[t], dh_direct=self.dh_direct[p])
             else:                                            # the two parts of the gradient the step after this one left

@@ -156,6 +156,14 @@ def test_recurrent_entry_points_reject_bad_arguments_without_a_gpu():
     assert L.nsk_gru_gates_bwd(9, 4, 8, *([FAKE] * 8), None) == B.NSK_ERR_BAD_DESC
     assert L.nsk_gru_gates_bwd(B.NSK_F32, 4, 8, FAKE, FAKE, None, None, None, FAKE, FAKE, FAKE, None) == B.NSK_ERR_NULL     # dh_a is required
     assert L.nsk_gru_gates_bwd(B.NSK_F32, 4, 8, FAKE, FAKE, FAKE, ODD, None, FAKE, FAKE, FAKE, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_gru_step_supported(50, 256) == 1 and L.nsk_gru_step_supported(50, 254) == 0 and L.nsk_gru_step_supported(257, 256) == 0
+    assert L.nsk_gru_step_fwd(B.NSK_F32, 0, 8, *([FAKE] * 7), None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_gru_step_fwd(B.NSK_F32, 4, 8, FAKE, None, FAKE, FAKE, FAKE, FAKE, FAKE, None) == B.NSK_ERR_NULL
+    assert L.nsk_gru_step_fwd(B.NSK_F32, 4, 8, FAKE, FAKE, FAKE, FAKE, ODD, FAKE, FAKE, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_gru_step_fwd(B.NSK_F32, 5000, 256, *([FAKE] * 7), None) == B.NSK_ERR_UNSUPPORTED
+    assert L.nsk_gru_step_bwd(B.NSK_F32, 4, 8, FAKE, FAKE, None, None, None, FAKE, FAKE, FAKE, FAKE, None) == B.NSK_ERR_NULL   # no gradient source
+    assert L.nsk_gru_step_bwd(B.NSK_F32, 4, 8, FAKE, FAKE, FAKE, None, ODD, FAKE, FAKE, FAKE, FAKE, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_gru_step_bwd(B.NSK_BF16, 4, 6, FAKE, FAKE, FAKE, None, None, FAKE, FAKE, FAKE, FAKE, None) == B.NSK_ERR_UNSUPPORTED
     assert L.nsk_transpose2d(B.NSK_F32, 0, 4, FAKE, FAKE, None) == B.NSK_ERR_BAD_DESC
     assert L.nsk_transpose2d(B.NSK_F32, 4, 4, FAKE, None, None) == B.NSK_ERR_NULL
     # few rows: the per-element product kernels validate like the rest

@@ -90,6 +90,50 @@ def test_gru_gate_kernels(N, H, dtype):
     assert max_rel_err(host(dgi1), G.gru_gates_bwd(rs, zs, ns, qs, h_prev, dh1)[0]) <= tol
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("N,H", [(50, 256), (4, 8), (3, 40), (1, 4), (64, 128), (130, 20)])
+def test_gru_fused_step_kernels(N, H, dtype):
+    """nsk_gru_step_fwd / bwd: the recurrent product and the gate arithmetic of a step in one launch, against the
+    oracle's product followed by its gate functions."""
+    print(f"gru fused step case N={N} H={H} {dtype}", flush=True)
+    assert B.gru_step_supported(N, H)
+    s = 8400 + N
+    gi = on_grid(gen.normal(s, 0, (N, 3 * H)), dtype)
+    w_hh = on_grid(gen.normal(s, 1, (3 * H, H)) / np.sqrt(H), dtype)
+    b_ih, b_hh = (0.3 * gen.normal(s, 2, (3 * H,))).astype(np.float32), (0.3 * gen.normal(s, 3, (3 * H,))).astype(np.float32)
+    h_prev, dh_a, dhd_next = (on_grid(gen.normal(s, 4 + k, (N, H)), dtype) for k in range(3))
+    dgh_next = on_grid(gen.normal(s, 7, (N, 3 * H)), dtype)
+    tol = TOL[dtype]
+    h_view, h_check = guarded((N, H), torch_dtype(dtype))
+    s_view, s_check = guarded((N, 4 * H), torch_dtype(dtype))
+    g_w, g_h = dev(w_hh, dtype), dev(h_prev, dtype)
+    g_wt = dev(np.ascontiguousarray(w_hh.T), dtype)
+    B.gru_step_fwd(dev(gi, dtype), g_w, dev(b_ih), dev(b_hh), g_h, h_new=h_view, saved=s_view)
+    torch.cuda.synchronize()
+    h_check()
+    s_check()
+    wh, r, z, n, q = G.gru_gates_fwd(gi, h_prev.astype(np.float64) @ w_hh.astype(np.float64).T, b_ih, b_hh, h_prev)
+    assert max_rel_err(host(h_view), wh) <= tol
+    sv = host(s_view)
+    for k, want in enumerate((r, z, n, q)):
+        assert max_rel_err(sv[:, k * H:(k + 1) * H], want) <= tol
+    # backward from the stored gates, with all three gradient sources, then with each of them alone
+    rs, zs, ns, qs = (sv[:, k * H:(k + 1) * H] for k in range(4))
+    rec = dgh_next.astype(np.float64) @ w_hh.astype(np.float64)
+    cases = [(dh_a, dhd_next, dgh_next), (dh_a, None, None), (None, dhd_next, None), (None, None, dgh_next)]
+    for a, d, g in cases:
+        outs = [guarded(sh, torch_dtype(dtype)) for sh in ((N, 3 * H), (N, 3 * H), (N, H))]
+        B.gru_step_bwd(s_view, g_h, g_wt, dh_a=None if a is None else dev(a, dtype), dh_direct_next=None if d is None else dev(d, dtype),
+                       dgh_next=None if g is None else dev(g, dtype), dgi=outs[0][0], dgh=outs[1][0], dh_direct=outs[2][0])
+        torch.cuda.synchronize()
+        for _, check in outs:
+            check()
+        dh = np.zeros((N, H)) + (0 if a is None else a) + (0 if d is None else d) + (0 if g is None else rec)
+        for (view, _), want in zip(outs, G.gru_gates_bwd(rs, zs, ns, qs, h_prev, dh)):
+            assert max_rel_err(host(view), want) <= tol
+    assert not B.gru_step_supported(300, 256) and not B.gru_step_supported(8, 6)
+
+
 def _model(seed, T_, N, E, H, V, K):
     tokens = ((gen.uniform(seed, 0, (T_, N)) * V).astype(np.int32)) % V
     labels = ((gen.uniform(seed, 1, (N,)) * K).astype(np.int32)) % K
@@ -119,12 +163,15 @@ def _oracle_step(tokens, labels, p):
     return loss, fwd, grads
 
 
+@pytest.mark.parametrize("fused", [True, False])
 @pytest.mark.parametrize("shape", [(6, 4, 16, 16, 50, 2), (12, 8, 32, 24, 100, 3)])
-def test_gru_classifier_forward_backward_and_adamw_step_match_the_oracle(shape):
+def test_gru_classifier_forward_backward_and_adamw_step_match_the_oracle(shape, fused):
     T_, N, E, H, V, K = shape
-    print(f"gru classifier T={T_} N={N} E={E} H={H} V={V} K={K} (f32)", flush=True)
+    print(f"gru classifier T={T_} N={N} E={E} H={H} V={V} K={K} (f32) fused steps={fused}", flush=True)
     tokens, labels, p = _model(8200 + T_, T_, N, E, H, V, K)
     m = GpuGruClassifier(tokens, labels, **p, dtype="f32", lr=1e-3, weight_decay=1e-4, clip=0.05)
+    assert m.fused_steps
+    m.fused_steps = fused       # False: one product and one gate kernel per step and direction
     m.forward()
     m.backward()
     torch.cuda.synchronize()
