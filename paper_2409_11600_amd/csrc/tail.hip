@@ -120,17 +120,27 @@ __global__ __launch_bounds__(256) void add_bias_kernel(T *__restrict__ y, const 
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256)
         y[i] = (T)(ld(y, i) + bias[i % K]);
 }
-// db[k] (+)= sum_n dy[n][k]: one wavefront per column, rows in a fixed order.
+// db[k] (+)= sum_n dy[n][k]: a block owns 64 columns (lane = column, so a wavefront reads contiguous bytes of a row),
+// its 16 wavefronts take every 16th row each and their partial sums are added in a fixed order.
 template <typename T>
-__global__ __launch_bounds__(256) void bias_grad_kernel(const T *__restrict__ dy, float *__restrict__ db, int N, int K,
-                                                        int accumulate)
+__global__ __launch_bounds__(1024) void bias_grad_kernel(const T *__restrict__ dy, float *__restrict__ db, int N, int K,
+                                                         int accumulate)
 {
-    const int k = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (k >= K) return;
+    __shared__ float part[16][64];
+    const int lane = threadIdx.x & 63, rl = threadIdx.x >> 6, k = blockIdx.x * 64 + lane;
     float s = 0.f;
-    for (int n = threadIdx.x & 63; n < N; n += 64) s += ld(dy, (long)n * K + k);
-    s = wave_sum(s);
-    if ((threadIdx.x & 63) == 0) db[k] = accumulate ? db[k] + s : s;
+    if (k < K) {
+#pragma unroll 8
+        for (int n = rl; n < N; n += 16) s += ld(dy, (long)n * K + k);
+    }
+    part[rl][lane] = s;
+    __syncthreads();
+    if (rl == 0 && k < K) {
+        float t = 0.f;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) t += part[r][lane];
+        db[k] = accumulate ? db[k] + t : t;
+    }
 }
 
 // Matrix products with very few rows (a recurrent step: 50 samples): a tile kernel would run on a handful of blocks,
@@ -473,12 +483,12 @@ int nsk_linear_wgrad(const nsk_linear_desc_t *desc, const void *x, const void *d
     const nsk_conv_desc_t c = linear_as_conv(desc);
     TAIL_TRY(nsk_conv2d_wgrad(&c, x, dy, dw, accumulate, workspace, workspace_bytes, stream));
     if (db) {
-        const dim3 grid((unsigned)((desc->K + 3) / 4));
+        const dim3 grid((unsigned)((desc->K + 63) / 64));
         if (desc->dtype == NSK_BF16)
-            hipLaunchKernelGGL(bias_grad_kernel<bf16_t>, grid, dim3(256), 0, (hipStream_t)stream, (const bf16_t *)dy, db, desc->N,
+            hipLaunchKernelGGL(bias_grad_kernel<bf16_t>, grid, dim3(1024), 0, (hipStream_t)stream, (const bf16_t *)dy, db, desc->N,
                                desc->K, accumulate);
         else
-            hipLaunchKernelGGL(bias_grad_kernel<float>, grid, dim3(256), 0, (hipStream_t)stream, (const float *)dy, db, desc->N,
+            hipLaunchKernelGGL(bias_grad_kernel<float>, grid, dim3(1024), 0, (hipStream_t)stream, (const float *)dy, db, desc->N,
                                desc->K, accumulate);
         return check_launch();
     }
