@@ -77,12 +77,12 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
     };
     // first staged position of a tile: padded row h0 of its image is the real row above the tile
     auto tile_q0 = [&](int tile) { return (tile / a.tiles_per_img) * a.PI + (tile % a.tiles_per_img) * 8 * a.PW; };
-    auto fill_in_tab = [&](int tile) {
-        const int q0 = tile_q0(tile);
+    auto fill_in_tab = [&](int tile, bool live) {   // !live: a table of out-of-range offsets (loads that fetch nothing)
+        const int q0 = live ? tile_q0(tile) : 0;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int p = tid + 256 * u;
-            if (p < F_MAX_IN) in_tab[p] = p < n_in ? src_offset(q0 + p) : F_OOB;
+            if (p < F_MAX_IN) in_tab[p] = live && p < n_in ? src_offset(q0 + p) : F_OOB;
         }
     };
     u32x4 stage[F_PASSES];
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
     int tile = blockIdx.x;
     int wb = 0;   // LDS buffer holding the tap about to be multiplied
     if (tile < a.tiles) {
-        fill_in_tab(tile);
+        fill_in_tab(tile, true);
         load_tap(0);
         store_tap(0);
         __syncthreads();
@@ -139,9 +139,8 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
         }
         const int next = tile + (int)gridDim.x;
         const bool have_next = next < a.tiles;
-        if (have_next) fill_in_tab(next);
+        fill_in_tab(next, have_next);
         __syncthreads();
-        if (have_next) prefetch_tile();
 
         // filter rows are the MFMA "A" operand, positions the "B" operand: acc[ni][mi][4g+j] is channel
         // 32*ni + 8*g + 4*(lane/32) + j of position 32*mi + lane%32
@@ -169,11 +168,9 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
                     for (int v = 0; v < 16; ++v) acc[ni][mi][v] = 0.f;
         }
 
-#pragma unroll 1
-        for (int t = 0; t < 9; ++t) {
-            // the tap after this one (tap 0 of the next tile after the last): global -> registers now,
-            // registers -> the other LDS buffer after the MFMAs
-            load_tap(t == 8 ? 0 : t + 1);
+        // One tap: the tap after it (tap 0 of the next tile after the last) goes global -> registers before the MFMAs and
+        // registers -> the other LDS buffer after them; the barrier orders LDS only, so loads stay in flight across it.
+        auto multiply_tap = [&](int t) {
             const unsigned char *pa = in_lds + a_base0 + a.tapoff[t] * F_ROW;
             const unsigned char *pb = w_lds + wb * F_WBUF + b_base0;
             f32x4 xf[2][2], wf[2][2];
@@ -199,8 +196,22 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
             }
             store_tap(wb ^ 1);
             wb ^= 1;
-            __syncthreads();
+            lds_barrier();
+        };
+        // Tap 0 apart from the loop: its filter successor is requested BEFORE the next tile.  A wavefront's loads return
+        // in order and every block asks for its next tile at the same moment, so whatever is requested behind that burst
+        // of HBM loads arrives late; this way nothing is needed from behind it for two taps.  (Without a next tile the
+        // table holds out-of-range offsets and the same loads fetch nothing: no branch around them, so the compiler's
+        // wait counts stay exact.)
+        load_tap(1);
+        prefetch_tile();
+        multiply_tap(0);
+#pragma unroll 1
+        for (int t = 1; t < 9; ++t) {
+            load_tap(t == 8 ? 0 : t + 1);
+            multiply_tap(t);
         }
+        __syncthreads();   // also: every wavefront is done with the input tile, it becomes the epilogue staging area
 
         // Epilogue through this wavefront's strip of the (now idle) input tile: 32 positions x 272 B
         unsigned char *my_st = in_lds + wave * (32 * F_ROW);
