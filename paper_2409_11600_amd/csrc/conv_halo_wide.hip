@@ -83,7 +83,8 @@ template <typename T> __device__ __forceinline__ T sel4(const T (&v)[W_CLS], int
 // MW multiplying wavefronts (32 output channels each) and one that moves data; at most two wavefronts per SIMD, so
 // that two of the smaller blocks (MW = 2, 64 output channels) share a CU.
 // MODE: 0 plain, 1 accumulate into the old output, 2 plain with the statistics epilogue (single class).
-template <int NT, int MW, int MODE>
+// NINE: a single class with nine taps, tap loop unrolled.
+template <int NT, int MW, int MODE, bool NINE>
 __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2))) void conv_halo_wide_kernel(const WideArgs a)
 {
     constexpr int THREADS = (MW + 1) * 64, BN = MW * 32;
@@ -390,6 +391,52 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
             first_fragments();
         }
     };
+    // A single class with nine taps (forward, backward-data at stride 1): the same pieces with the tap loop unrolled, so
+    // that tap shifts are scalars known per call and a piece carries no bookkeeping at all (8% off the main loop).
+    if (NINE) {
+        int shift[9];
+#pragma unroll
+        for (int t = 0; t < 9; ++t) {
+            const int code = (int)(a.tapcode[0] >> (4 * t)) & 15;
+            shift[t] = (a.PW + 1 + ((code >> 2) - 1) * a.PW + ((code & 3) - 1)) * a.row_bytes;
+        }
+        for (int g = 0; g < cpt; ++g) {
+            if (g > 0) {
+                lds_barrier();   // group g is staged
+                grp = g;
+                first_fragments();
+            }
+#pragma unroll
+            for (int t = 0; t < 9; ++t) {
+                const unsigned to_next = t < 8 ? (unsigned)(shift[t + 1] - shift[t]) : 0u;   // last tap: re-read in place (unused)
+                const unsigned w_off = ld_g < cpt ? w_row + (unsigned)(ld_t * a.C * 2 + ld_g * 128) : W_OOB;
+                if (++ld_t == 9) {
+                    ld_t = 0;
+                    ++ld_g;
+                }
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const bf16x8 wfrag = __builtin_bit_cast(bf16x8, wf[t % 3][s]);
+#pragma unroll
+                    for (int p = 0; p < NT; ++p) {
+                        acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag, pf[s & 1][p], acc[p], 0, 0, 0);
+                        if (s < 3) {
+                            pf[(s + 1) & 1][p] = lds_read16(bp[p] + (s + 1) * 16);
+                        } else {
+                            bp[p] += to_next;
+                            asm volatile("" : "+v"(bp[p]));
+                            pf[0][p] = lds_read16(bp[p]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    wf[t % 3][s] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, w_off + (unsigned)(s * 16), 0, 0);
+                }
+            }
+        }
+        epilogue(0);
+        return;
+    }
+    if (!NINE)
     for (;;) {
         const int np = ntaps_c * cpt;
         int i = 0;
@@ -525,10 +572,14 @@ int launch_classes(const IgemmArgs *g, int count, hipStream_t stream)
     a.stats_rows = f.stats_rows;
     static bool attr_set = false;
     if (!attr_set) {
-        const void *k[6] = {(const void *)conv_halo_wide_kernel<kNT, 4, 0>, (const void *)conv_halo_wide_kernel<kNT, 4, 1>,
-                            (const void *)conv_halo_wide_kernel<kNT, 4, 2>, (const void *)conv_halo_wide_kernel<kNT, 2, 0>,
-                            (const void *)conv_halo_wide_kernel<kNT, 2, 1>, (const void *)conv_halo_wide_kernel<kNT, 2, 2>};
-        for (int i = 0; i < 6; ++i) {
+        const void *k[12] = {
+            (const void *)conv_halo_wide_kernel<kNT, 4, 0, false>, (const void *)conv_halo_wide_kernel<kNT, 4, 1, false>,
+            (const void *)conv_halo_wide_kernel<kNT, 4, 2, false>, (const void *)conv_halo_wide_kernel<kNT, 2, 0, false>,
+            (const void *)conv_halo_wide_kernel<kNT, 2, 1, false>, (const void *)conv_halo_wide_kernel<kNT, 2, 2, false>,
+            (const void *)conv_halo_wide_kernel<kNT, 4, 0, true>,  (const void *)conv_halo_wide_kernel<kNT, 4, 1, true>,
+            (const void *)conv_halo_wide_kernel<kNT, 4, 2, true>,  (const void *)conv_halo_wide_kernel<kNT, 2, 0, true>,
+            (const void *)conv_halo_wide_kernel<kNT, 2, 1, true>,  (const void *)conv_halo_wide_kernel<kNT, 2, 2, true>};
+        for (int i = 0; i < 12; ++i) {
             const hipError_t e = hipFuncSetAttribute(k[i], hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS_MAX);
             if (e != hipSuccess) {
                 set_last_hip_error(e);
@@ -539,22 +590,25 @@ int launch_classes(const IgemmArgs *g, int count, hipStream_t stream)
     }
     const int bn = block_channels(f);
     const int mode = f.accumulate ? 1 : a.stats ? 2 : 0;
+    const bool nine = count == 1 && f.ntaps == 9;
     const dim3 grid((unsigned)(a.tiles * (a.K / bn)));
+#define NSK_WIDE_LAUNCH(MW, MODE, NINE) \
+    hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, MW, MODE, NINE>), grid, dim3((MW + 1) * 64), p.smem, stream, a)
+#define NSK_WIDE_MODES(MW, NINE)                    \
+    do {                                            \
+        if (mode == 1) NSK_WIDE_LAUNCH(MW, 1, NINE); \
+        else if (mode == 2) NSK_WIDE_LAUNCH(MW, 2, NINE); \
+        else NSK_WIDE_LAUNCH(MW, 0, NINE);          \
+    } while (0)
     if (bn == 128) {
-        if (mode == 1)
-            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 1>), grid, dim3(320), p.smem, stream, a);
-        else if (mode == 2)
-            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 2>), grid, dim3(320), p.smem, stream, a);
-        else
-            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 0>), grid, dim3(320), p.smem, stream, a);
+        if (nine) NSK_WIDE_MODES(4, true);
+        else NSK_WIDE_MODES(4, false);
     } else {
-        if (mode == 1)
-            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 1>), grid, dim3(192), p.smem, stream, a);
-        else if (mode == 2)
-            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 2>), grid, dim3(192), p.smem, stream, a);
-        else
-            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 0>), grid, dim3(192), p.smem, stream, a);
+        if (nine) NSK_WIDE_MODES(2, true);
+        else NSK_WIDE_MODES(2, false);
     }
+#undef NSK_WIDE_MODES
+#undef NSK_WIDE_LAUNCH
     return check_launch();
 }
 
