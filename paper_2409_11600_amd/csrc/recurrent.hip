@@ -159,6 +159,10 @@ __global__ __launch_bounds__(GS_THREADS) void gru_step_fwd_kernel(const T *__res
         const int n0 = blockIdx.y * SLOTS;
         const int n = n0 + slot < N ? n0 + slot : N - 1;   // lanes past the end repeat the last sample and store nothing
         const T *hp = h_prev + (long)n * H;
+        // the gate operands are requested before the dot products, so that the kernel is one round trip, not two
+        const long g0 = (long)n * 3 * H + u;
+        const float gi_r = ld(gi, g0), gi_z = ld(gi, g0 + H), gi_n = ld(gi, g0 + 2 * H), h_old = ld(h_prev, (long)n * H + u);
+        const float br = b_ih[u] + b_hh[u], bz = b_ih[H + u] + b_hh[H + u], bin = b_ih[2 * H + u], bhn = b_hh[2 * H + u];
         f32x4 a0 = {0.f, 0.f, 0.f, 0.f}, a1 = a0, a2 = a0;
         // (unrolled so that the loads of several vectors are in flight together: each is an L2 round trip)
 #pragma unroll 8
@@ -170,12 +174,11 @@ __global__ __launch_bounds__(GS_THREADS) void gru_step_fwd_kernel(const T *__res
         }
         const float gh_r = lanes_sum<L>(a0), gh_z = lanes_sum<L>(a1), gh_n = lanes_sum<L>(a2);
         if (q != 0 || n0 + slot >= N) return;
-        const long g0 = (long)n * 3 * H + u;
-        const float r = sigmoidf(ld(gi, g0) + b_ih[u] + gh_r + b_hh[u]);
-        const float z = sigmoidf(ld(gi, g0 + H) + b_ih[H + u] + gh_z + b_hh[H + u]);
-        const float qq = gh_n + b_hh[2 * H + u];
-        const float c = tanhf(ld(gi, g0 + 2 * H) + b_ih[2 * H + u] + r * qq);
-        h_new[(long)n * H + u] = (T)((1.f - z) * c + z * ld(h_prev, (long)n * H + u));
+        const float r = sigmoidf(gi_r + gh_r + br);
+        const float z = sigmoidf(gi_z + gh_z + bz);
+        const float qq = gh_n + bhn;
+        const float c = tanhf(gi_n + bin + r * qq);
+        h_new[(long)n * H + u] = (T)((1.f - z) * c + z * h_old);
         T *sv = saved + (long)n * 4 * H + u;
         sv[0] = (T)r;
         sv[H] = (T)z;
@@ -197,6 +200,11 @@ __global__ __launch_bounds__(GS_THREADS) void gru_step_bwd_kernel(const T *__res
     {
         const int n0 = blockIdx.y * SLOTS;
         const int n = n0 + slot < N ? n0 + slot : N - 1;
+        // the elementwise operands are requested before the dot product (one round trip, not two)
+        const long i = (long)n * H + u;
+        const T *sv = saved + (long)n * 4 * H + u;
+        const float r = ld(sv, 0), z = ld(sv, H), c = ld(sv, 2 * H), qq = ld(sv, 3 * H), h_old = ld(h_prev, i);
+        const float dh_other = (dh_direct_next ? ld(dh_direct_next, i) : 0.f) + (dh_a ? ld(dh_a, i) : 0.f);
         float dh = 0.f;
         if (dgh_next) {   // the part of the gradient that came back through the recurrent product of the step after
             const T *d = dgh_next + (long)n * J;
@@ -206,13 +214,9 @@ __global__ __launch_bounds__(GS_THREADS) void gru_step_bwd_kernel(const T *__res
             dh = lanes_sum<L>(acc);
         }
         if (q != 0 || n0 + slot >= N) return;
-        const long i = (long)n * H + u;
-        if (dh_direct_next) dh += ld(dh_direct_next, i);
-        if (dh_a) dh += ld(dh_a, i);
-        const T *sv = saved + (long)n * 4 * H + u;
-        const float r = ld(sv, 0), z = ld(sv, H), c = ld(sv, 2 * H), qq = ld(sv, 3 * H);
+        dh += dh_other;
         const float da_n = dh * (1.f - z) * (1.f - c * c);
-        const float da_z = dh * (ld(h_prev, i) - c) * z * (1.f - z);
+        const float da_z = dh * (h_old - c) * z * (1.f - z);
         const float da_r = da_n * qq * r * (1.f - r);
         const long g0 = (long)n * J + u;
         dgi[g0] = (T)da_r;
