@@ -159,6 +159,43 @@ def conv2d_wgrad(x, dy, wshape, stride=1, pad=0, dilation=1, into: Optional[np.n
     return dw
 
 
+# Grouped convolution (not in the paper's workloads; the definition is the textbook one): the C input channels and the
+# K output channels are split into `groups` equal runs, output run g sees input run g only, and w is [K][C/groups][R][S].
+# Written as exactly that: a loop over the groups around the plain functions above.
+
+def conv2d_grouped_fwd(x, w, groups, stride=1, pad=0, dilation=1) -> np.ndarray:
+    x, w = _f64(x), _f64(w)
+    C, K = x.shape[1], w.shape[0]
+    if C % groups or K % groups or w.shape[1] != C // groups:
+        raise ValueError("channel counts do not split into the groups")
+    cg, kg = C // groups, K // groups
+    return np.concatenate([conv2d_fwd(x[:, g * cg:(g + 1) * cg], w[g * kg:(g + 1) * kg], stride, pad, dilation)
+                           for g in range(groups)], axis=1)
+
+
+def conv2d_grouped_dgrad(dy, w, xshape, groups, stride=1, pad=0, dilation=1, into: Optional[np.ndarray] = None) -> np.ndarray:
+    dy, w = _f64(dy), _f64(w)
+    N, C, H, W = (int(v) for v in xshape)
+    K = w.shape[0]
+    cg, kg = C // groups, K // groups
+    parts = [conv2d_dgrad(dy[:, g * kg:(g + 1) * kg], w[g * kg:(g + 1) * kg], (N, cg, H, W), stride, pad, dilation)
+             for g in range(groups)]
+    dx = np.concatenate(parts, axis=1)
+    return dx if into is None else into + dx
+
+
+def conv2d_grouped_wgrad(x, dy, wshape, groups, stride=1, pad=0, dilation=1, into: Optional[np.ndarray] = None) -> np.ndarray:
+    x, dy = _f64(x), _f64(dy)
+    K, cgw, R, S = (int(v) for v in wshape)
+    C = x.shape[1]
+    cg, kg = C // groups, K // groups
+    assert cgw == cg
+    parts = [conv2d_wgrad(x[:, g * cg:(g + 1) * cg], dy[:, g * kg:(g + 1) * kg], (kg, cg, R, S), stride, pad, dilation)
+             for g in range(groups)]
+    dw = np.concatenate(parts, axis=0)
+    return dw if into is None else into + dw
+
+
 def _coords(coords, ndim_hi) -> np.ndarray:
     c = np.ascontiguousarray(coords, dtype=np.int32)
     if c.ndim != 2 or c.shape[1] != 4:

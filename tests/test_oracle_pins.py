@@ -394,3 +394,39 @@ def test_bf16_rounding_golden_and_torch():
     theirs = torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
     assert np.array_equal(ours, theirs)
     assert np.array_equal(gen.to_bf16_grid(a).astype(np.float64), theirs)
+
+
+# ---------------------------------------------------------------------------------------------- grouped convolution
+@pytest.mark.parametrize("case", [(2, 8, 7, 9, 12, 3, 2, 1, 1, 1), (1, 6, 8, 8, 6, 3, 6, 2, 1, 1), (2, 4, 9, 7, 8, 2, 4, (2, 1), (0, 1), (1, 2)),
+                                  (1, 12, 6, 6, 4, 1, 4, 1, 0, 1)])
+def test_grouped_convolution_matches_torch_float64_with_autograd(case):
+    """Forward against torch's CPU float64 grouped convolution, both gradients against its autograd (depthwise included:
+    groups == C)."""
+    N, C, H, W, K, R, G, st, pd, dl = case
+    rng = np.random.default_rng(77 + C + K)
+    x = rng.standard_normal((N, C, H, W))
+    w = rng.standard_normal((K, C // G, R, R))
+    tx, tw = torch.from_numpy(x).requires_grad_(True), torch.from_numpy(w).requires_grad_(True)
+    ty = F.conv2d(tx, tw, None, st, pd, dl, groups=G)
+    y = oracle.conv2d_grouped_fwd(x, w, G, st, pd, dl)
+    assert y.shape == tuple(ty.shape) and np.max(np.abs(y - ty.detach().numpy())) <= 1e-12 * max(1.0, np.abs(y).max())
+    dy = rng.standard_normal(y.shape)
+    ty.backward(torch.from_numpy(dy))
+    dx = oracle.conv2d_grouped_dgrad(dy, w, x.shape, G, st, pd, dl)
+    dw = oracle.conv2d_grouped_wgrad(x, dy, w.shape, G, st, pd, dl)
+    assert np.max(np.abs(dx - tx.grad.numpy())) <= 1e-12 * max(1.0, np.abs(dx).max())
+    assert np.max(np.abs(dw - tw.grad.numpy())) <= 1e-12 * max(1.0, np.abs(dw).max())
+    base = rng.standard_normal(x.shape)
+    assert np.allclose(oracle.conv2d_grouped_dgrad(dy, w, x.shape, G, st, pd, dl, into=base), base + dx, rtol=0, atol=1e-12)
+
+
+def test_grouped_convolution_with_one_group_is_the_plain_one_and_groups_do_not_mix():
+    rng = np.random.default_rng(5)
+    x, w = rng.standard_normal((1, 4, 5, 5)), rng.standard_normal((6, 4, 3, 3))
+    assert np.array_equal(oracle.conv2d_grouped_fwd(x, w, 1, 1, 1, 1), oracle.conv2d_fwd(x, w, 1, 1, 1))
+    w2 = rng.standard_normal((6, 2, 3, 3))
+    y = oracle.conv2d_grouped_fwd(x, w2, 2, 1, 1, 1)
+    x_other = x.copy()
+    x_other[:, 2:] += 10.0                      # changing the second group's input ...
+    y_other = oracle.conv2d_grouped_fwd(x_other, w2, 2, 1, 1, 1)
+    assert np.array_equal(y[:, :3], y_other[:, :3]) and not np.allclose(y[:, 3:], y_other[:, 3:])   # ... moves its outputs only
