@@ -135,6 +135,21 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
 int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy, float *dw,
                      int accumulate, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Grouped convolution (not used by the paper's networks; the residual-network family that the paper's recipe
+ * belongs to has grouped and depthwise members, and the definition is the textbook one): the C input channels and
+ * the K output channels are split into `groups` equal runs, output run g sees input run g only, and the filter is
+ * w[K][C/groups][R][S] (KCRS) or w[K][R][S][C/groups] (KRSC); dw has the same shape.  desc describes the whole
+ * tensors (C and K are the totals).  groups must divide C and K (else NSK_ERR_BAD_DESC); groups = 1 is exactly the
+ * plain call.  Everything else (layouts, types, accumulate, workspace, stream, errors) is as in the plain calls; the
+ * workspace size comes from nsk_conv2d_grouped_workspace_bytes (host only, 0 for an invalid request). */
+size_t nsk_conv2d_grouped_workspace_bytes(const nsk_conv_desc_t *desc, int groups, int pass);
+int nsk_conv2d_grouped_fwd(const nsk_conv_desc_t *desc, int groups, const void *x, const void *w, void *y,
+                           void *workspace, size_t workspace_bytes, void *stream);
+int nsk_conv2d_grouped_dgrad(const nsk_conv_desc_t *desc, int groups, const void *dy, const void *w, void *dx,
+                             int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+int nsk_conv2d_grouped_wgrad(const nsk_conv_desc_t *desc, int groups, const void *x, const void *dy, float *dw,
+                             int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Workspace bytes for the batch-norm pass (NSK_BN_FWD | NSK_BN_BWD); 0 if invalid. */
 size_t nsk_bn_workspace_bytes(const nsk_bn_desc_t *desc, int pass);
 

@@ -93,6 +93,14 @@ def lib() -> ctypes.CDLL:
         L.nsk_conv2d_dgrad.argtypes = [cd, vp, vp, vp, ci, vp, sz, vp]
         L.nsk_conv2d_wgrad.restype = ci
         L.nsk_conv2d_wgrad.argtypes = [cd, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_conv2d_grouped_workspace_bytes.restype = sz
+        L.nsk_conv2d_grouped_workspace_bytes.argtypes = [cd, ci, ci]
+        L.nsk_conv2d_grouped_fwd.restype = ci
+        L.nsk_conv2d_grouped_fwd.argtypes = [cd, ci, vp, vp, vp, vp, sz, vp]
+        L.nsk_conv2d_grouped_dgrad.restype = ci
+        L.nsk_conv2d_grouped_dgrad.argtypes = [cd, ci, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_conv2d_grouped_wgrad.restype = ci
+        L.nsk_conv2d_grouped_wgrad.argtypes = [cd, ci, vp, vp, vp, ci, vp, sz, vp]
         L.nsk_bn_workspace_bytes.restype = sz
         L.nsk_bn_workspace_bytes.argtypes = [bd, ci]
         L.nsk_bn_relu_add_fwd.restype = ci
@@ -182,6 +190,8 @@ def lib() -> ctypes.CDLL:
 
 EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d_out_dims",
            "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
+           "nsk_conv2d_grouped_workspace_bytes", "nsk_conv2d_grouped_fwd", "nsk_conv2d_grouped_dgrad",
+           "nsk_conv2d_grouped_wgrad",
            "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
            "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_conv2d_stats_rows", "nsk_conv2d_fwd_stats",
            "nsk_bn_relu_add_fwd_stats", "nsk_maxpool2d_out_dims",
@@ -356,6 +366,59 @@ def conv2d_wgrad(x, dy, filt_logical, stride=1, pad=0, dilation=1, layout=NSK_NH
     wp, wb = ws.get(lib().nsk_conv2d_workspace_bytes(ctypes.byref(d), NSK_PASS_WGRAD))
     _check(lib().nsk_conv2d_wgrad(ctypes.byref(d), _ptr(x), _ptr(dy), _ptr(out), int(bool(accumulate)), wp, wb,
                                   _stream()), "nsk_conv2d_wgrad")
+    return out
+
+
+def conv2d_grouped_fwd(x, w, groups, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None,
+                       ws: Optional[Workspace] = None):
+    """Grouped convolution: w holds C/groups input channels per output channel."""
+    N, C, H, W = _logical(x, layout)
+    K, Cw, R, S = _filter_logical(w, layout)
+    assert Cw * groups == C and w.dtype == x.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), layout)
+    P, Q = conv2d_out_dims(d)
+    if out is None:
+        out = torch.empty(_act_shape(N, K, P, Q, layout), dtype=x.dtype, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_grouped_workspace_bytes(ctypes.byref(d), int(groups), NSK_PASS_FWD))
+    _check(lib().nsk_conv2d_grouped_fwd(ctypes.byref(d), int(groups), _ptr(x), _ptr(w), _ptr(out), wp, wb, _stream()),
+           "nsk_conv2d_grouped_fwd")
+    return out
+
+
+def conv2d_grouped_dgrad(dy, w, x_logical, groups, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None,
+                         accumulate=False, ws: Optional[Workspace] = None):
+    """x_logical = (N,C,H,W) of the forward input."""
+    N, C, H, W = x_logical
+    K, Cw, R, S = _filter_logical(w, layout)
+    assert Cw * groups == C and w.dtype == dy.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(dy), layout)
+    if out is None:
+        assert not accumulate
+        out = torch.empty(_act_shape(N, C, H, W, layout), dtype=dy.dtype, device=dy.device)
+    ws = ws or Workspace(dy.device)
+    wp, wb = ws.get(lib().nsk_conv2d_grouped_workspace_bytes(ctypes.byref(d), int(groups), NSK_PASS_DGRAD))
+    _check(lib().nsk_conv2d_grouped_dgrad(ctypes.byref(d), int(groups), _ptr(dy), _ptr(w), _ptr(out),
+                                          int(bool(accumulate)), wp, wb, _stream()), "nsk_conv2d_grouped_dgrad")
+    return out
+
+
+def conv2d_grouped_wgrad(x, dy, filt_logical, groups, stride=1, pad=0, dilation=1, layout=NSK_NHWC, out=None,
+                         accumulate=False, ws: Optional[Workspace] = None):
+    """filt_logical = (K, C/groups, R, S).  Returns float32 dw shaped like the filter in `layout`."""
+    N, C, H, W = _logical(x, layout)
+    K, Cw, R, S = filt_logical
+    assert Cw * groups == C and x.dtype == dy.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), layout)
+    if out is None:
+        assert not accumulate
+        shape = (K, R, S, Cw) if layout == NSK_NHWC else (K, Cw, R, S)
+        out = torch.empty(shape, dtype=torch.float32, device=x.device)
+    assert out.dtype == torch.float32
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_grouped_workspace_bytes(ctypes.byref(d), int(groups), NSK_PASS_WGRAD))
+    _check(lib().nsk_conv2d_grouped_wgrad(ctypes.byref(d), int(groups), _ptr(x), _ptr(dy), _ptr(out),
+                                          int(bool(accumulate)), wp, wb, _stream()), "nsk_conv2d_grouped_wgrad")
     return out
 
 

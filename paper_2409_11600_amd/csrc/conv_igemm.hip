@@ -67,6 +67,10 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
     const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const int m0 = blockIdx.x * BM;
     const int n0 = blockIdx.y * BN;
+    // grouped convolution: blockIdx.z names the group (0 for a plain launch); ld = channels between two source pixels
+    const int grp = blockIdx.z, ld = a.src_ld;
+    const int src_c0 = grp * a.Cs;            // first source channel of the group
+    const long wrow0 = (long)grp * a.Ngemm;   // first filter row = first output channel of the group
 
     if (tid < kMaxTaps) {
         s_offh[tid] = a.off_h[tid];
@@ -100,9 +104,9 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         a_img[u] = img * a.Hs;
         a_bh[u] = i * a.mult_h + a.add_h;
         a_bw[u] = j * a.mult_w + a.add_w;
-        a_base[u] = (unsigned)((((long)a_img[u] + a_bh[u]) * a.Ws + a_bw[u]) * a.Cs * (long)sizeof(T));
+        a_base[u] = (unsigned)(((((long)a_img[u] + a_bh[u]) * a.Ws + a_bw[u]) * ld + src_c0) * (long)sizeof(T));
         if (kv == 0)
-            out_off[row] = a_ok[u] ? (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co
+            out_off[row] = a_ok[u] ? (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co + wrow0
                                    : -1L;
     }
     __syncthreads();
@@ -134,7 +138,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
     for (int u = 0; u < B_PASSES; ++u) {
         const int row = r0 + RPP * u;
         const int n = n0 + row;
-        b_row_off[u] = (row < BN && n < a.Ngemm) ? (unsigned)((long)n * a.Ktot * (long)sizeof(T)) : ~0u;
+        b_row_off[u] = (row < BN && n < a.Ngemm) ? (unsigned)((wrow0 + n) * a.Ktot * (long)sizeof(T)) : ~0u;
     }
 
     auto load_tile = [&](int kt) {
@@ -142,7 +146,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
         if (VECLOAD) {
             const bool kok = kk < a.Ktot;
             const int tap = kok ? cur_tap : 0;
-            const unsigned delta = (unsigned)((((int)s_offh[tap] * a.Ws + (int)s_offw[tap]) * a.Cs + cur_c) * (int)sizeof(T));
+            const unsigned delta = (unsigned)((((int)s_offh[tap] * a.Ws + (int)s_offw[tap]) * ld + cur_c) * (int)sizeof(T));
 #pragma unroll
             for (int u = 0; u < A_PASSES; ++u) {
                 const bool ok = kok && ((a_mask[u] >> tap) & 1ull);
@@ -178,13 +182,13 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
                     for (int u = 0; u < A_PASSES; ++u) {
                         const int h = a_bh[u] + oh, w = a_bw[u] + ow;
                         const bool ok = a_ok[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
-                        if (ok) ra[u][e] = src[((long)(a_img[u] + h) * a.Ws + w) * a.Cs + c];
+                        if (ok) ra[u][e] = src[((long)(a_img[u] + h) * a.Ws + w) * ld + src_c0 + c];
                     }
 #pragma unroll
                     for (int u = 0; u < B_PASSES; ++u) {
                         const int row = r0 + RPP * u;
                         const int n = n0 + row;
-                        if (row < BN && n < a.Ngemm) rb[u][e] = wpk[(long)n * a.Ktot + k];
+                        if (row < BN && n < a.Ngemm) rb[u][e] = wpk[(wrow0 + n) * a.Ktot + k];
                     }
                 }
             }
@@ -365,7 +369,7 @@ __global__ __launch_bounds__(256) void igemm_kernel(const IgemmArgs a)
 template <typename T, int BM, int BN, int WM, int WN, int BKB>
 int launch_tile(const IgemmArgs &a, bool vec, hipStream_t stream)
 {
-    dim3 grid(ceil_div(a.M, BM), ceil_div(a.Ngemm, BN));
+    dim3 grid(ceil_div(a.M, BM), ceil_div(a.Ngemm, BN), a.groups);
     if (vec)
         hipLaunchKernelGGL((igemm_kernel<T, BM, BN, WM, WN, BKB, true>), grid, dim3(256), 0, stream, a);
     else
@@ -392,7 +396,9 @@ int auto_tile(const IgemmArgs &a, int es)
 template <typename T> int launch_typed(const IgemmArgs &a, hipStream_t stream)
 {
     constexpr int VEC = Traits<T>::VEC;
-    const bool vec = a.Cs % VEC == 0 && a.Ktot % VEC == 0 && ((uintptr_t)a.src % 16 == 0) && ((uintptr_t)a.wpk % 16 == 0);
+    // (for a grouped launch Cs % VEC == 0 also puts every group's channel run and filter rows on 16-byte boundaries)
+    const bool vec = a.Cs % VEC == 0 && a.src_ld % VEC == 0 && a.Ktot % VEC == 0 && ((uintptr_t)a.src % 16 == 0) &&
+                     ((uintptr_t)a.wpk % 16 == 0);
     switch (forced_tile()) {
     case 1: return launch_tile<T, 256, 64, 64, 64, 64>(a, vec, stream);
     case 2: return launch_tile<T, 256, 64, 64, 64, 128>(a, vec, stream);
@@ -418,7 +424,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
 {
     // the same order of tests as launch_igemm
     if (a.M <= 0 || a.Ngemm <= 0 || a.accumulate) return 0;
-    if (forced_tile() != 0) return 0;
+    if (forced_tile() != 0 || a.groups > 1) return 0;
     if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
     if (halo64_f32_applicable(dtype, a)) return halo64_f32_stats_rows(a);
     if (conv_pw_applicable(dtype, a)) return conv_pw_stats_rows(a);
@@ -439,13 +445,20 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
 int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
 {
     if (a.M <= 0 || a.Ngemm <= 0) return NSK_OK;
+    const bool grouped = a.groups > 1;   // only the generic kernel knows about groups
+    if (grouped && (a.groups > 65535 || a.src_ld != a.groups * a.Cs || a.zero_cell || a.stats)) return NSK_ERR_BAD_DESC;
     if (a.zero_cell) return launch_conv_pw(a, stream);   // the caller has checked that this kernel applies
-    if (forced_tile() == 0 && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
-    if (forced_tile() == 0 && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
-    if (forced_tile() == 0 && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
-    if (forced_tile() == 0 && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
-    if (forced_tile() == 0 && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
+    const bool special = forced_tile() == 0 && !grouped;
+    if (special && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
+    if (special && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
+    if (special && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
+    if (special && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
+    if (special && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
     IgemmArgs b = a;
+    if (!grouped) {
+        b.groups = 1;
+        b.src_ld = b.Cs;
+    }
     const int vec = dtype == NSK_BF16 ? 8 : 4;
     b.vec_out = (b.Ngemm % vec == 0 && b.Co % vec == 0 && (uintptr_t)b.out % 16 == 0) ? 1 : 0;
     return dtype == NSK_BF16 ? launch_typed<bf16_t>(b, stream) : launch_typed<float>(b, stream);

@@ -57,7 +57,10 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int frow = lane & 31, fk = lane >> 5;
-    const int n0 = blockIdx.x * WBN, k0 = blockIdx.y * WBM, split = blockIdx.z;
+    // grouped convolution: blockIdx.z = group * splits + split (one group for a plain launch)
+    const int grp = blockIdx.z / a.splits, split = blockIdx.z - grp * a.splits;
+    const int n0 = blockIdx.x * WBN, k0 = blockIdx.y * WBM;
+    const int ldx = a.ldx, ldy = a.ldy;
     const int NT = a.ntaps * a.C;
     if (tid < kMaxTaps) {
         s_offh[tid] = a.off_h[tid];
@@ -65,8 +68,8 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
     }
     __syncthreads();
 
-    const T *__restrict__ x = (const T *)a.x;
-    const T *__restrict__ dy = (const T *)a.dy;
+    const T *__restrict__ x = (const T *)a.x + (long)grp * a.C;     // the group's channel runs
+    const T *__restrict__ dy = (const T *)a.dy + (long)grp * a.K;
 
     // thread -> (pixel row of the tile, vector of channels); bf16 keeps lanes along the pixel index so
     // the transposing 2-byte LDS writes of a wavefront fall into consecutive addresses.
@@ -120,11 +123,11 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
             const int l = base + la;
             if (l < l_end) {
                 if (VECLOAD) {
-                    if (kA < a.K) ra = *(const Vec *)(dy + (long)l * a.K + kA);
+                    if (kA < a.K) ra = *(const Vec *)(dy + (long)l * ldy + kA);
                 } else {
 #pragma unroll
                     for (int e = 0; e < VEC; ++e)
-                        if (kA + e < a.K) ra[e] = dy[(long)l * a.K + kA + e];
+                        if (kA + e < a.K) ra[e] = dy[(long)l * ldy + kA + e];
                 }
             }
         }
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
                 if (b_ok[u]) {
                     const int h = p * a.sh - a.ph + b_oh[u], w = q * a.sw - a.pw + b_ow[u];
                     if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
-                        rb[u] = *(const Vec *)(x + (((long)img * a.H + h) * a.W + w) * a.C + b_c[u]);
+                        rb[u] = *(const Vec *)(x + (((long)img * a.H + h) * a.W + w) * ldx + b_c[u]);
                 }
             } else {
 #pragma unroll
@@ -150,7 +153,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
                         const int c = n - tap * a.C;
                         const int h = p * a.sh - a.ph + s_offh[tap], w = q * a.sw - a.pw + s_offw[tap];
                         if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W)
-                            rb[u][e] = x[(((long)img * a.H + h) * a.W + w) * a.C + c];
+                            rb[u][e] = x[(((long)img * a.H + h) * a.W + w) * ldx + c];
                     }
                 }
             }
@@ -210,7 +213,7 @@ __global__ __launch_bounds__(256) void wgrad_kernel(const WgradArgs a)
         __syncthreads();
     }
 
-    float *__restrict__ part = a.part + (long)split * a.K * NT;
+    float *__restrict__ part = a.part + ((long)split * a.groups + grp) * a.K * NT;
 #pragma unroll
     for (int ni = 0; ni < FN; ++ni) {
         const int col = n0 + (wn * FN + ni) * 32 + frow;
@@ -270,7 +273,7 @@ template <typename T> int launch_wgrad_typed(const WgradArgs &a, bool vec, hipSt
 {
     const int NT = a.ntaps * a.C;
     const int fn = column_frags(NT);
-    dim3 grid(ceil_div(NT, 64 * fn), ceil_div(a.K, WBM), a.splits);
+    dim3 grid(ceil_div(NT, 64 * fn), ceil_div(a.K, WBM), a.splits * a.groups);
     if (fn == 3) {
         if (vec)
             hipLaunchKernelGGL((wgrad_kernel<T, 3, true>), grid, dim3(256), 0, stream, a);
@@ -285,9 +288,18 @@ template <typename T> int launch_wgrad_typed(const WgradArgs &a, bool vec, hipSt
     return check_launch();
 }
 
-int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream)
+int launch_wgrad(int dtype, const WgradArgs &a0, hipStream_t stream)
 {
+    WgradArgs a = a0;
+    if (a.groups > 1) {
+        if (a.ldx != a.groups * a.C || a.ldy != a.groups * a.K || (long)a.groups * a.splits > 65535) return NSK_ERR_BAD_DESC;
+    } else {
+        a.groups = 1;
+        a.ldx = a.C;
+        a.ldy = a.K;
+    }
     const int VEC = dtype == NSK_BF16 ? 8 : 4;
+    // (with C and K multiples of VEC every group's channel runs start on 16-byte boundaries too)
     const bool vec = a.C % VEC == 0 && a.K % VEC == 0 && (uintptr_t)a.x % 16 == 0 && (uintptr_t)a.dy % 16 == 0;
     if (dtype == NSK_BF16) return launch_wgrad_typed<bf16_t>(a, vec, stream);
     return launch_wgrad_typed<float>(a, vec, stream);

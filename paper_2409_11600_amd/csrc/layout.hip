@@ -41,6 +41,7 @@ struct PackArgs {
     void *out;
     int Nn, ntaps, Cs;
     long sn, sc;
+    long w_gstep;   // grouped filters: blockIdx.z names the group, whose source lies w_gstep elements further
     int tap_off[kMaxTaps];
 };
 
@@ -61,7 +62,8 @@ template <typename T> __global__ __launch_bounds__(256) void pack_filter_kernel(
     const long r = i / a.Cs;
     const int t = (int)(r % a.ntaps);
     const long n = r / a.ntaps;
-    ((T *)a.out)[i] = ((const T *)a.w)[n * a.sn + a.tap_off[t] + c * a.sc];
+    const long g = blockIdx.z;
+    ((T *)a.out)[g * total + i] = ((const T *)a.w)[g * a.w_gstep + n * a.sn + a.tap_off[t] + c * a.sc];
 }
 
 // Zero the pixels (i*osh + oa, j*osw + ob), i < Mi, j < Mj, of every image of an NHWC tensor: the cells
@@ -123,7 +125,14 @@ int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, in
 int launch_pack_filters(int dtype, int count, const void *w, void *const *out, int Nn, const int *ntaps, int Cs, long sn,
                         long sc, const int (*tap_off_host)[kMaxTaps], hipStream_t stream)
 {
-    if (count < 1 || count > kPackMulti) return NSK_ERR_BAD_DESC;
+    return launch_pack_filters_grouped(dtype, count, w, out, Nn, ntaps, Cs, sn, sc, tap_off_host, 1, 0L, stream);
+}
+
+int launch_pack_filters_grouped(int dtype, int count, const void *w, void *const *out, int Nn, const int *ntaps, int Cs,
+                                long sn, long sc, const int (*tap_off_host)[kMaxTaps], int groups, long w_gstep,
+                                hipStream_t stream)
+{
+    if (count < 1 || count > kPackMulti || groups < 1 || groups > 65535) return NSK_ERR_BAD_DESC;
     PackMulti m{};
     long most = 0;
     for (int k = 0; k < count; ++k) {
@@ -135,12 +144,13 @@ int launch_pack_filters(int dtype, int count, const void *w, void *const *out, i
         a.Cs = Cs;
         a.sn = sn;
         a.sc = sc;
+        a.w_gstep = w_gstep;
         for (int t = 0; t < kMaxTaps; ++t) a.tap_off[t] = t < ntaps[k] ? tap_off_host[k][t] : 0;
         const long total = (long)Nn * ntaps[k] * Cs;
         if (total > most) most = total;
     }
     if (most == 0) return NSK_OK;
-    dim3 grid((unsigned)((most + 255) / 256), (unsigned)count);
+    dim3 grid((unsigned)((most + 255) / 256), (unsigned)count, (unsigned)groups);
     if (dtype == NSK_BF16)
         hipLaunchKernelGGL((pack_filter_kernel<bf16_t>), grid, dim3(256), 0, stream, m);
     else

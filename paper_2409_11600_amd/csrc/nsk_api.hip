@@ -85,10 +85,13 @@ struct ConvPlan {
     bool stem = false;   // the space-to-depth path plans its own workspace
 };
 
-ConvPlan plan_conv(const ConvGeo &g, int pass)
+// groups > 1: grouped convolution (the filter holds C/groups input channels per output channel and only the generic
+// kernels run it).
+ConvPlan plan_conv(const ConvGeo &g, int pass, int groups = 1)
 {
     ConvPlan p;
-    p.stem = stem_applicable(g);
+    const size_t w_elems = g.w_elems / (size_t)groups;
+    p.stem = groups == 1 && stem_applicable(g);
     if (p.stem) {
         p.total = stem_workspace_bytes(g, pass);
         return p;
@@ -103,13 +106,13 @@ ConvPlan plan_conv(const ConvGeo &g, int pass)
     if (pass == NSK_PASS_FWD) {
         if (nchw) {
             p.act_in = take(g.x_elems * g.es);
-            p.filt = take(g.w_elems * g.es);
+            p.filt = take(w_elems * g.es);
             p.act_out = take(g.y_elems * g.es);
         }
     } else if (pass == NSK_PASS_DGRAD) {
         if (nchw) p.act_in = take(g.y_elems * g.es);
         // one packed filter per stride parity class; together they hold every tap once
-        p.filt = take(g.w_elems * g.es + 256 * (size_t)g.sh * g.sw);
+        p.filt = take(w_elems * g.es + 256 * (size_t)g.sh * g.sw);
         if (nchw) p.act_out = take(g.x_elems * g.es);
     } else {
         if (nchw) {
@@ -118,15 +121,20 @@ ConvPlan plan_conv(const ConvGeo &g, int pass)
         }
         WgradArgs wa{};
         wgrad_geometry(g, &wa);
-        p.halo = use_wgrad_halo(g, wa);
-        p.wide = !p.halo && wgrad_wide_applicable(g.dtype, wa);
+        p.halo = groups == 1 && use_wgrad_halo(g, wa);
+        p.wide = groups == 1 && !p.halo && wgrad_wide_applicable(g.dtype, wa);
         if (p.halo)
             p.splits = wgrad_halo64_partials(g.dtype, wa, nullptr);
         else if (p.wide)
             p.rows_per_split = wgrad_wide_rows_per_split(wa, &p.splits);
         else
-            p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * g.C, &p.splits);
-        p.part = take((size_t)p.splits * g.w_elems * sizeof(float));
+            p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * (g.C / groups), &p.splits);
+        // a grouped launch puts groups * splits on gridDim.z
+        while ((long)groups * p.splits > 65535) {
+            p.rows_per_split *= 2;
+            p.splits = ceil_div(g.N * g.P * g.Q, p.rows_per_split);
+        }
+        p.part = take((size_t)p.splits * w_elems * sizeof(float));
     }
     p.total = off;
     return p;
@@ -218,14 +226,24 @@ int conv_stats_rows(const ConvGeo &g, bool *fused = nullptr)
     return rows > 0 ? rows : bn_stats_rows(output_as_bn(g));
 }
 
-int conv_fwd_impl(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, float *stats, void *workspace,
-                  size_t workspace_bytes, void *stream)
+// NSK_OK if C and K split into `groups` equal runs.
+int check_groups(const ConvGeo &g, int groups)
+{
+    if (groups < 1 || g.C % groups != 0 || g.K % groups != 0) return NSK_ERR_BAD_DESC;
+    if (groups > 65535) return NSK_ERR_UNSUPPORTED;   // groups ride on gridDim.z
+    return NSK_OK;
+}
+
+int conv_fwd_impl(const nsk_conv_desc_t *desc, int groups, const void *x, const void *w, void *y, float *stats,
+                  void *workspace, size_t workspace_bytes, void *stream)
 {
     ConvGeo g;
     NSK_TRY(conv_geometry(desc, &g, true));
+    NSK_TRY(check_groups(g, groups));
     if (!x || !w || !y) return NSK_ERR_NULL;
     if (misaligned(x) || misaligned(w) || misaligned(y)) return NSK_ERR_ALIGNMENT;
-    const ConvPlan p = plan_conv(g, NSK_PASS_FWD);
+    const ConvPlan p = plan_conv(g, NSK_PASS_FWD, groups);
+    const int cg = g.C / groups, kg = g.K / groups;
     NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -244,7 +262,7 @@ int conv_fwd_impl(const nsk_conv_desc_t *desc, const void *x, const void *w, voi
         NSK_TRY(launch_nchw_to_nhwc(g.dtype, x, ws + p.act_in, g.N, g.C, g.H, g.W, st));
         int tap_off[kMaxTaps];
         for (int t = 0; t < g.R * g.S; ++t) tap_off[t] = t;
-        NSK_TRY(launch_pack_filter(g.dtype, w, ws + p.filt, g.K, g.R * g.S, g.C, (long)g.C * g.R * g.S,
+        NSK_TRY(launch_pack_filter(g.dtype, w, ws + p.filt, g.K, g.R * g.S, cg, (long)cg * g.R * g.S,
                                    (long)g.R * g.S, tap_off, st));
         src = ws + p.act_in;
         filt = ws + p.filt;
@@ -253,6 +271,14 @@ int conv_fwd_impl(const nsk_conv_desc_t *desc, const void *x, const void *w, voi
     IgemmArgs a{};
     fwd_geometry(g, &a);
     a.src = src; a.wpk = filt; a.out = dst;
+    if (groups > 1) {   // `groups` problems of cg -> kg channels on channel runs of the same tensors
+        a.groups = groups;
+        a.src_ld = g.C;
+        a.Cs = cg;
+        a.Ktot = a.ntaps * cg;
+        a.Ngemm = kg;
+        a.wpk_bytes = (unsigned)(g.w_elems / (size_t)groups * g.es);
+    }
     if (fused) {
         a.stats = stats;
         a.stats_rows = rows;
@@ -309,7 +335,7 @@ size_t nsk_conv2d_workspace_bytes(const nsk_conv_desc_t *desc, int pass)
 int nsk_conv2d_fwd(const nsk_conv_desc_t *desc, const void *x, const void *w, void *y, void *workspace,
                    size_t workspace_bytes, void *stream)
 {
-    return conv_fwd_impl(desc, x, w, y, nullptr, workspace, workspace_bytes, stream);
+    return conv_fwd_impl(desc, 1, x, w, y, nullptr, workspace, workspace_bytes, stream);
 }
 
 int nsk_conv2d_stats_rows(const nsk_conv_desc_t *desc)
@@ -324,18 +350,20 @@ int nsk_conv2d_fwd_stats(const nsk_conv_desc_t *desc, const void *x, const void 
 {
     if (!stats) return NSK_ERR_NULL;
     if (misaligned(stats)) return NSK_ERR_ALIGNMENT;
-    return conv_fwd_impl(desc, x, w, y, stats, workspace, workspace_bytes, stream);
+    return conv_fwd_impl(desc, 1, x, w, y, stats, workspace, workspace_bytes, stream);
 }
 
-int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w, void *dx, int accumulate,
-                     void *workspace, size_t workspace_bytes, void *stream)
+static int conv_dgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *dy, const void *w, void *dx,
+                           int accumulate, void *workspace, size_t workspace_bytes, void *stream)
 {
     ConvGeo g;
     NSK_TRY(conv_geometry(desc, &g, true));
+    NSK_TRY(check_groups(g, groups));
     if (!dy || !w || !dx) return NSK_ERR_NULL;
     if (accumulate != 0 && accumulate != 1) return NSK_ERR_BAD_DESC;
     if (misaligned(dy) || misaligned(w) || misaligned(dx)) return NSK_ERR_ALIGNMENT;
-    const ConvPlan p = plan_conv(g, NSK_PASS_DGRAD);
+    const ConvPlan p = plan_conv(g, NSK_PASS_DGRAD, groups);
+    const int cg = g.C / groups, kg = g.K / groups;   // channels of one group (all of them for a plain convolution)
     NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -365,27 +393,31 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
                 if (((tw % g.sw) + g.sw) % g.sw != 0) continue;
                 a->off_h[nt] = (short)(th / g.sh);  // exact division, may be negative
                 a->off_w[nt] = (short)(tw / g.sw);
-                tap_off[nt] = nchw ? r * g.S + s : (r * g.S + s) * g.C;
+                tap_off[nt] = nchw ? r * g.S + s : (r * g.S + s) * cg;
                 ++nt;
             }
         }
-        a->Nimg = g.N; a->Hs = g.P; a->Ws = g.Q; a->Cs = g.K;
+        a->Nimg = g.N; a->Hs = g.P; a->Ws = g.Q; a->Cs = kg;
         a->Mi = ca < g.H ? (g.H - ca + g.sh - 1) / g.sh : 0;
         a->Mj = cb < g.W ? (g.W - cb + g.sw - 1) / g.sw : 0;
         a->M = g.N * a->Mi * a->Mj;
         a->mult_h = 1; a->add_h = 0; a->mult_w = 1; a->add_w = 0;
-        a->ntaps = nt; a->Ktot = nt * g.K;
-        a->Ngemm = g.C;
+        a->ntaps = nt; a->Ktot = nt * kg;
+        a->Ngemm = cg;
+        if (groups > 1) {
+            a->groups = groups;
+            a->src_ld = g.K;
+        }
         a->Ho = g.H; a->Wo = g.W; a->Co = g.C; a->osh = g.sh; a->oa = ca; a->osw = g.sw; a->ob = cb;
         a->accumulate = acc_kernel;
         a->src_bytes = (unsigned)(g.y_elems * g.es);
-        a->wpk_bytes = (unsigned)((size_t)g.C * nt * g.K * g.es);
+        a->wpk_bytes = (unsigned)((size_t)g.C * nt * kg * g.es);
         return nt;
     };
     // Stride 2 with every tap in class (0, 0) (a 1x1 layer): the other three classes are plain zeros, which the
     // short-reduction kernel writes along with class (0, 0) when it takes that class.
     bool zero_cell = false;
-    if (g.sh == 2 && g.sw == 2 && !acc_kernel) {
+    if (g.sh == 2 && g.sw == 2 && !acc_kernel && groups == 1) {
         IgemmArgs a{};
         int tap_off[kMaxTaps];
         bool others_empty = true;
@@ -395,7 +427,9 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
             zero_cell = conv_pw_applicable(g.dtype, a);
         }
     }
-    const long w_sn = nchw ? (long)g.R * g.S : 1L, w_sc = nchw ? (long)g.C * g.R * g.S : (long)g.R * g.S * g.C;
+    // element (k, tap, c) of the filter: k * w_sc + tap_off + c * w_sn; one group's filters are w_gstep elements long
+    const long w_sn = nchw ? (long)g.R * g.S : 1L, w_sc = (long)g.R * g.S * cg;
+    const long w_gstep = (long)kg * w_sc;
     size_t filt_off = p.filt;
     // classes with taps: filters are packed first, then the launches follow (one for all classes where the large-tile
     // kernel takes them together)
@@ -425,16 +459,20 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
                 pk_out[n_pending] = ws + filt_off;
                 pending[n_pending++] = a;
             } else {
-                NSK_TRY(launch_pack_filter(g.dtype, w, ws + filt_off, g.C, nt, g.K, w_sn, w_sc, tap_off, st));
+                int taps1[1][kMaxTaps];
+                for (int t = 0; t < kMaxTaps; ++t) taps1[0][t] = t < nt ? tap_off[t] : 0;
+                void *out1[1] = {ws + filt_off};
+                NSK_TRY(launch_pack_filters_grouped(g.dtype, 1, w, out1, cg, &nt, kg, w_sn, w_sc, taps1, groups, w_gstep, st));
                 NSK_TRY(launch_igemm(g.dtype, a, st));
             }
-            filt_off += align_up((size_t)g.C * nt * g.K * g.es);
+            filt_off += align_up((size_t)g.C * nt * kg * g.es);
         }
     // one packing launch for all classes, then their multiplies
-    if (n_pending > 0) NSK_TRY(launch_pack_filters(g.dtype, n_pending, w, pk_out, g.C, pk_nt, g.K, w_sn, w_sc, pk_taps, st));
-    if (n_pending > 1 && halo_wide_multi_applicable(g.dtype, pending, n_pending)) {
+    if (n_pending > 0)
+        NSK_TRY(launch_pack_filters_grouped(g.dtype, n_pending, w, pk_out, cg, pk_nt, kg, w_sn, w_sc, pk_taps, groups, w_gstep, st));
+    if (n_pending > 1 && groups == 1 && halo_wide_multi_applicable(g.dtype, pending, n_pending)) {
         NSK_TRY(launch_halo_wide_multi(pending, n_pending, st));
-    } else if (n_pending > 1 && igemm_big_multi_applicable(g.dtype, pending, n_pending)) {
+    } else if (n_pending > 1 && groups == 1 && igemm_big_multi_applicable(g.dtype, pending, n_pending)) {
         NSK_TRY(launch_igemm_big_multi(pending, n_pending, st));
     } else {
         for (int i = 0; i < n_pending; ++i) NSK_TRY(launch_igemm(g.dtype, pending[i], st));
@@ -443,15 +481,17 @@ int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w,
     return NSK_OK;
 }
 
-int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy, float *dw, int accumulate,
-                     void *workspace, size_t workspace_bytes, void *stream)
+static int conv_wgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *x, const void *dy, float *dw,
+                           int accumulate, void *workspace, size_t workspace_bytes, void *stream)
 {
     ConvGeo g;
     NSK_TRY(conv_geometry(desc, &g, true));
+    NSK_TRY(check_groups(g, groups));
     if (!x || !dy || !dw) return NSK_ERR_NULL;
     if (accumulate != 0 && accumulate != 1) return NSK_ERR_BAD_DESC;
     if (misaligned(x) || misaligned(dy) || misaligned(dw)) return NSK_ERR_ALIGNMENT;
-    const ConvPlan p = plan_conv(g, NSK_PASS_WGRAD);
+    const ConvPlan p = plan_conv(g, NSK_PASS_WGRAD, groups);
+    const int cg = g.C / groups, kg = g.K / groups;
     NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
@@ -469,6 +509,13 @@ int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy,
     wgrad_geometry(g, &a);
     a.rows_per_split = p.rows_per_split;
     a.splits = p.splits;
+    if (groups > 1) {   // `groups` problems of cg x kg channels; their partial sums stack to [splits][K][taps * cg]
+        a.groups = groups;
+        a.ldx = g.C;
+        a.ldy = g.K;
+        a.C = cg;
+        a.K = kg;
+    }
     if (p.halo)
         NSK_TRY(launch_wgrad_halo64(g.dtype, a, st));
     else if (p.wide)
@@ -477,10 +524,48 @@ int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy,
         NSK_TRY(launch_wgrad(g.dtype, a, st));
     const long RS = (long)g.R * g.S;
     if (nchw)
-        NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, g.C, (long)g.C * RS, 1L, RS, accumulate, st));
+        NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, cg, (long)cg * RS, 1L, RS, accumulate, st));
     else
-        NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, g.C, RS * g.C, (long)g.C, 1L, accumulate, st));
+        NSK_TRY(launch_wgrad_reduce(a.part, dw, p.splits, g.K, a.ntaps, cg, RS * cg, (long)cg, 1L, accumulate, st));
     return NSK_OK;
+}
+
+int nsk_conv2d_dgrad(const nsk_conv_desc_t *desc, const void *dy, const void *w, void *dx, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return conv_dgrad_impl(desc, 1, dy, w, dx, accumulate, workspace, workspace_bytes, stream);
+}
+
+int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy, float *dw, int accumulate,
+                     void *workspace, size_t workspace_bytes, void *stream)
+{
+    return conv_wgrad_impl(desc, 1, x, dy, dw, accumulate, workspace, workspace_bytes, stream);
+}
+
+size_t nsk_conv2d_grouped_workspace_bytes(const nsk_conv_desc_t *desc, int groups, int pass)
+{
+    ConvGeo g;
+    if (pass < NSK_PASS_FWD || pass > NSK_PASS_WGRAD) return 0;
+    if (conv_geometry(desc, &g, true) != NSK_OK || check_groups(g, groups) != NSK_OK) return 0;
+    return plan_conv(g, pass, groups).total;
+}
+
+int nsk_conv2d_grouped_fwd(const nsk_conv_desc_t *desc, int groups, const void *x, const void *w, void *y,
+                           void *workspace, size_t workspace_bytes, void *stream)
+{
+    return conv_fwd_impl(desc, groups, x, w, y, nullptr, workspace, workspace_bytes, stream);
+}
+
+int nsk_conv2d_grouped_dgrad(const nsk_conv_desc_t *desc, int groups, const void *dy, const void *w, void *dx,
+                             int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return conv_dgrad_impl(desc, groups, dy, w, dx, accumulate, workspace, workspace_bytes, stream);
+}
+
+int nsk_conv2d_grouped_wgrad(const nsk_conv_desc_t *desc, int groups, const void *x, const void *dy, float *dw,
+                             int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return conv_wgrad_impl(desc, groups, x, dy, dw, accumulate, workspace, workspace_bytes, stream);
 }
 
 size_t nsk_bn_workspace_bytes(const nsk_bn_desc_t *desc, int pass)

@@ -82,6 +82,11 @@ struct IgemmArgs {
     // writes zeros to the other (up to three) pixels of each row's 2x2 output cell.  Only the short-reduction kernel
     // honours it: set it only after conv_pw_applicable() said yes for these arguments.
     int zero_cell;
+    // Grouped convolution (groups > 1; 0 or 1 = plain): the launch computes `groups` independent problems of the
+    // shape above.  Group g reads channels [g*Cs, (g+1)*Cs) of source pixels that are src_ld channels apart, the filter
+    // rows [g*Ngemm, (g+1)*Ngemm) of wpk, and writes columns [g*Ngemm, (g+1)*Ngemm) of the Co-channel output pixels.
+    // Only the generic kernel runs such launches; src_ld is ignored (taken as Cs) for plain ones.
+    int groups, src_ld;
     short off_h[kMaxTaps];
     short off_w[kMaxTaps];
 };
@@ -131,6 +136,11 @@ struct WgradArgs {
     int L;           // Nimg*P*Q
     int rows_per_split;  // multiple of the kernel's BK
     int splits;
+    // Grouped convolution (groups > 1; 0 or 1 = plain): C and K are the channel counts of ONE group, pixels of x are ldx
+    // channels apart and pixels of dy ldy channels; group g reads the channel runs [g*C, (g+1)*C) and [g*K, (g+1)*K)
+    // and writes rows [g*K, (g+1)*K) of part[split][groups*K][ntaps*C].  Only the generic kernel runs such launches;
+    // ldx and ldy are ignored (taken as C and K) for plain ones.
+    int groups, ldx, ldy;
     short off_h[kMaxTaps];
     short off_w[kMaxTaps];
 };
@@ -181,6 +191,10 @@ int launch_pack_filter(int dtype, const void *w, void *out, int Nn, int ntaps, i
 // The same for up to four tap subsets of one filter in one launch: out[k][n][t][c] with ntaps[k] taps tap_off_host[k][.].
 int launch_pack_filters(int dtype, int count, const void *w, void *const *out, int Nn, const int *ntaps, int Cs, long sn,
                         long sc, const int (*tap_off_host)[kMaxTaps], hipStream_t stream);
+// The same for `groups` filters that lie w_gstep elements apart in w: out[k][g][n][t][c] = w[g*w_gstep + n*sn + ...].
+int launch_pack_filters_grouped(int dtype, int count, const void *w, void *const *out, int Nn, const int *ntaps, int Cs,
+                                long sn, long sc, const int (*tap_off_host)[kMaxTaps], int groups, long w_gstep,
+                                hipStream_t stream);
 
 // out[img][i*osh + oa][j*osw + ob][0..Co) = 0 for i < Mi, j < Mj (NHWC).
 int launch_zero_class(int dtype, void *out, int Nimg, int Ho, int Wo, int Co, int Mi, int Mj, int osh, int oa, int osw,

@@ -106,6 +106,33 @@ def test_compute_calls_reject_bad_arguments_without_a_gpu():
     assert L.nsk_maxpool2d_fwd(ctypes.byref(pd), FAKE, FAKE, FAKE, None) == B.NSK_ERR_UNSUPPORTED
 
 
+def test_grouped_convolution_validation_without_a_gpu():
+    L = B.lib()
+    d = B.conv_desc((2, 12, 8, 8), (8, 3, 3), 1, 1, 1, B.NSK_F32, B.NSK_NHWC)
+    dp = ctypes.byref(d)
+    big = 1 << 30
+    # groups must be positive and divide both channel counts (12 and 8): 1, 2, 4 do, 0, 3, 8 do not
+    for groups in (0, -1, 3, 8, 12):
+        for p in (B.NSK_PASS_FWD, B.NSK_PASS_DGRAD, B.NSK_PASS_WGRAD):
+            assert L.nsk_conv2d_grouped_workspace_bytes(dp, groups, p) == 0
+        assert L.nsk_conv2d_grouped_fwd(dp, groups, FAKE, FAKE, FAKE, FAKE, big, None) == B.NSK_ERR_BAD_DESC
+        assert L.nsk_conv2d_grouped_dgrad(dp, groups, FAKE, FAKE, FAKE, 0, FAKE, big, None) == B.NSK_ERR_BAD_DESC
+        assert L.nsk_conv2d_grouped_wgrad(dp, groups, FAKE, FAKE, FAKE, 0, FAKE, big, None) == B.NSK_ERR_BAD_DESC
+    # one group: the same workspace as the plain call; more groups: the filter-sized parts shrink with the filter
+    for p in (B.NSK_PASS_FWD, B.NSK_PASS_DGRAD, B.NSK_PASS_WGRAD):
+        assert L.nsk_conv2d_grouped_workspace_bytes(dp, 1, p) == L.nsk_conv2d_workspace_bytes(dp, p)
+    assert 0 < L.nsk_conv2d_grouped_workspace_bytes(dp, 4, B.NSK_PASS_DGRAD) <= L.nsk_conv2d_workspace_bytes(dp, B.NSK_PASS_DGRAD)
+    assert L.nsk_conv2d_grouped_workspace_bytes(dp, 4, B.NSK_PASS_WGRAD) >= 8 * 3 * 9 * 4
+    assert L.nsk_conv2d_grouped_workspace_bytes(dp, 4, 3) == 0
+    # the other checks come in the same order as in the plain calls
+    assert L.nsk_conv2d_grouped_fwd(dp, 4, None, FAKE, FAKE, None, 0, None) == B.NSK_ERR_NULL
+    assert L.nsk_conv2d_grouped_fwd(dp, 4, FAKE, ODD, FAKE, None, 0, None) == B.NSK_ERR_ALIGNMENT
+    assert L.nsk_conv2d_grouped_dgrad(dp, 4, FAKE, FAKE, FAKE, 2, FAKE, big, None) == B.NSK_ERR_BAD_DESC
+    assert L.nsk_conv2d_grouped_dgrad(dp, 4, FAKE, FAKE, FAKE, 0, None, 0, None) == B.NSK_ERR_WORKSPACE
+    assert L.nsk_conv2d_grouped_wgrad(dp, 4, FAKE, FAKE, FAKE, 0, FAKE, 16, None) == B.NSK_ERR_WORKSPACE
+    assert L.nsk_conv2d_grouped_wgrad(dp, 4, FAKE, FAKE, ODD, 0, FAKE, big, None) == B.NSK_ERR_ALIGNMENT
+
+
 def test_tail_entry_points_reject_bad_arguments_without_a_gpu():
     L = B.lib()
     # global average pool

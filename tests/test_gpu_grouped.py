@@ -1,0 +1,118 @@
+"""GPU parity of the grouped convolution entry points (nsk_conv2d_grouped_fwd/dgrad/wgrad) against the CPU oracle,
+which defines a grouped convolution as a loop over the groups around the plain one."""
+import numpy as np
+import pytest
+import torch
+
+import nsk_inputs as gen
+import oracle
+from paper_2409_11600_amd import binding as B
+from parity import TOL, guarded, max_rel_err, on_grid, to_gpu, to_host, torch_dtype
+
+pytestmark = pytest.mark.gpu
+
+LAYOUTS = [B.NSK_NHWC, B.NSK_NCHW]
+
+# N, C, H, W, K, R, S, stride, pad, dilation, groups
+GROUPED_SHAPES = [
+    (2, 32, 12, 12, 32, 3, 3, 1, 1, 1, 2),        # two groups of 16 -> 16 (vector loads)
+    (2, 64, 9, 11, 128, 3, 3, 1, 1, 1, 4),        # 16 -> 32 per group, odd extents, ragged row tile
+    (2, 128, 10, 10, 128, 3, 3, 2, 1, 1, 32),     # the 32-group bottleneck shape: 4 -> 4 per group (scalar loads in bf16)
+    (3, 24, 13, 9, 24, 3, 3, 1, 1, 1, 24),        # depthwise
+    (2, 16, 12, 12, 32, 3, 3, 2, 1, 1, 16),       # depthwise with channel multiplier 2, stride 2
+    (2, 24, 14, 12, 36, 3, 2, (2, 1), (1, 0), (1, 2), 3),   # anisotropic stride, pad, dilation; 8 -> 12 per group
+    (1, 40, 9, 9, 20, 1, 1, 1, 0, 1, 5),          # 1x1, 8 -> 4 per group
+    (2, 6, 10, 10, 9, 5, 5, 3, 2, 1, 3),          # stride 3 (classes without taps), odd channel counts
+    (1, 256, 6, 6, 256, 3, 3, 1, 1, 1, 2),        # 128 -> 128 per group: 128-column tiles, long reduction
+    (2, 16, 8, 8, 16, 3, 3, 1, 1, 1, 1),          # one group = the plain call
+]
+
+
+def _case(i, dtype):
+    N, C, H, W, K, R, S, st, pd, dl, G = GROUPED_SHAPES[i]
+    x = on_grid(gen.normal(900 + i, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(900 + i, 1, (K, C // G, R, S)), dtype)
+    P, Q = oracle.conv2d_out_dims(x.shape, (K, C, R, S), st, pd, dl)
+    dy = on_grid(gen.normal(900 + i, 2, (N, K, P, Q)), dtype)
+    return x, w, dy, st, pd, dl, G
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", range(len(GROUPED_SHAPES)))
+def test_grouped_conv_fwd_dgrad_wgrad(i, dtype, layout):
+    x, w, dy, st, pd, dl, G = _case(i, dtype)
+    print(f"grouped conv case {i} {GROUPED_SHAPES[i]} {dtype} layout={layout}", flush=True)
+    tol = TOL[dtype]
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+
+    y_view, y_check = guarded(gdy.shape, torch_dtype(dtype))
+    B.conv2d_grouped_fwd(gx, gw, G, st, pd, dl, layout, out=y_view, ws=ws)
+    torch.cuda.synchronize()
+    y_check()
+    assert max_rel_err(to_host(y_view, layout), oracle.conv2d_grouped_fwd(x, w, G, st, pd, dl)) <= tol
+
+    dx_view, dx_check = guarded(gx.shape, torch_dtype(dtype))
+    B.conv2d_grouped_dgrad(gdy, gw, x.shape, G, st, pd, dl, layout, out=dx_view, ws=ws)
+    torch.cuda.synchronize()
+    dx_check()
+    want_dx = oracle.conv2d_grouped_dgrad(dy, w, x.shape, G, st, pd, dl)
+    got_dx = to_host(dx_view, layout)
+    assert max_rel_err(got_dx, want_dx) <= tol
+    assert np.all(got_dx[want_dx == 0.0] == 0.0)          # cells no tap reaches are written as exact zeros
+
+    dw_view, dw_check = guarded(gw.shape, torch.float32)
+    B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, out=dw_view, ws=ws)
+    torch.cuda.synchronize()
+    dw_check()
+    want_dw = oracle.conv2d_grouped_wgrad(x, dy, w.shape, G, st, pd, dl)
+    assert max_rel_err(to_host(dw_view, layout), want_dw) <= tol
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", [0, 2, 4, 7])
+def test_grouped_conv_accumulate(i, dtype, layout):
+    """accumulate = 1 adds the gradients to what the buffers hold (the paper's gradient accumulation)."""
+    x, w, dy, st, pd, dl, G = _case(i, dtype)
+    print(f"grouped accumulate case {i} {GROUPED_SHAPES[i]} {dtype} layout={layout}", flush=True)
+    tol = TOL[dtype]
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    base = on_grid(gen.normal(900 + i, 3, x.shape), dtype)
+    gacc = to_gpu(base, dtype, layout)
+    B.conv2d_grouped_dgrad(gdy, gw, x.shape, G, st, pd, dl, layout, out=gacc, accumulate=True, ws=ws)
+    base_w = gen.normal(900 + i, 4, w.shape).astype(np.float32)
+    gdw = to_gpu(base_w, "f32", layout)
+    B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, out=gdw, accumulate=True, ws=ws)
+    torch.cuda.synchronize()
+    want_acc = oracle.conv2d_grouped_dgrad(dy, w, x.shape, G, st, pd, dl, into=base.astype(np.float64))
+    assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
+    want_dw = oracle.conv2d_grouped_wgrad(x, dy, w.shape, G, st, pd, dl, into=base_w.astype(np.float64))
+    assert max_rel_err(to_host(gdw, layout), want_dw) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_one_group_is_bitwise_the_plain_call(dtype):
+    """groups = 1 takes the same kernels as the plain entry points."""
+    x, w, dy, st, pd, dl, G = _case(9, dtype)
+    layout = B.NSK_NHWC
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    assert torch.equal(B.conv2d_grouped_fwd(gx, gw, 1, st, pd, dl, layout, ws=ws),
+                       B.conv2d_fwd(gx, gw, st, pd, dl, layout, ws=ws))
+    assert torch.equal(B.conv2d_grouped_dgrad(gdy, gw, x.shape, 1, st, pd, dl, layout, ws=ws),
+                       B.conv2d_dgrad(gdy, gw, x.shape, st, pd, dl, layout, ws=ws))
+    assert torch.equal(B.conv2d_grouped_wgrad(gx, gdy, w.shape, 1, st, pd, dl, layout, ws=ws),
+                       B.conv2d_wgrad(gx, gdy, w.shape, st, pd, dl, layout, ws=ws))
+
+
+def test_grouped_results_are_reproducible():
+    x, w, dy, st, pd, dl, G = _case(1, "bf16")
+    layout = B.NSK_NHWC
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, "bf16", layout), to_gpu(w, "bf16", layout), to_gpu(dy, "bf16", layout)
+    a = B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, ws=ws)
+    b = B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, ws=ws)
+    assert torch.equal(a, b)
