@@ -454,6 +454,8 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (special && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
     if (special && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
     if (special && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
+    if (grouped && forced_tile() == 0 && getenv("NSK_NO_DEPTHWISE") == nullptr && depthwise_applicable(dtype, a))
+        return launch_depthwise(dtype, a, stream);
     IgemmArgs b = a;
     if (!grouped) {
         b.groups = 1;

@@ -17,6 +17,8 @@
 //    as loaded, and a fragment is one conflict-free 4-byte read per lane.
 //  - bf16 (mfma 32x32x16, 8 consecutive k per lane): the tile is transposed on the way into LDS
 //    ([channel][pixel]) so that a fragment is one 16-byte read.
+#include <stdlib.h>
+
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -298,6 +300,7 @@ int launch_wgrad(int dtype, const WgradArgs &a0, hipStream_t stream)
         a.ldx = a.C;
         a.ldy = a.K;
     }
+    if (getenv("NSK_NO_DEPTHWISE") == nullptr && depthwise_wgrad_applicable(dtype, a)) return launch_depthwise_wgrad(dtype, a, stream);
     const int VEC = dtype == NSK_BF16 ? 8 : 4;
     // (with C and K multiples of VEC every group's channel runs start on 16-byte boundaries too)
     const bool vec = a.C % VEC == 0 && a.K % VEC == 0 && (uintptr_t)a.x % 16 == 0 && (uintptr_t)a.dy % 16 == 0;

@@ -123,6 +123,11 @@ bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);
 int halo64_f32_stats_rows(const IgemmArgs &a);
 
+// depthwise layers (grouped launches with one channel per group on both sides, channel count a multiple of the vector
+// width): direct kernels bound by memory bandwidth, no MFMA
+bool depthwise_applicable(int dtype, const IgemmArgs &a);
+int launch_depthwise(int dtype, const IgemmArgs &a, hipStream_t stream);
+
 // ------------------------------------------------------------------ wgrad
 // part[split][k][t][c] = sum over the split's share of rows l = (img, p, q) of
 //   dy[img][p][q][k] * x[img][p*sh - ph + off_h[t]][q*sw - pw + off_w[t]][c]
@@ -154,6 +159,9 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &a, hipStream_t stream);
 bool wgrad_wide_applicable(int dtype, const WgradArgs &a);
 int wgrad_wide_rows_per_split(const WgradArgs &a, int *splits);
 int launch_wgrad_wide(const WgradArgs &a, hipStream_t stream);
+// depthwise layers: partial sums in the layout of the generic kernel's grouped launch
+bool depthwise_wgrad_applicable(int dtype, const WgradArgs &a);
+int launch_depthwise_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);
 // dw[k*sk + t*st + c*sc] (=|+=) sum_s part[s][k][t][c], fixed order.
 int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int ntaps, int C,
                         long sk, long st, long sc, int accumulate, hipStream_t stream);

@@ -25,7 +25,12 @@ GROUPED_SHAPES = [
     (2, 6, 10, 10, 9, 5, 5, 3, 2, 1, 3),          # stride 3 (classes without taps), odd channel counts
     (1, 256, 6, 6, 256, 3, 3, 1, 1, 1, 2),        # 128 -> 128 per group: 128-column tiles, long reduction
     (2, 16, 8, 8, 16, 3, 3, 1, 1, 1, 1),          # one group = the plain call
+    (2, 128, 14, 14, 128, 3, 3, 1, 1, 1, 128),    # depthwise, several blocks of the direct kernels
+    (1, 256, 9, 7, 256, 5, 5, 2, 2, 1, 256),      # depthwise 5x5 stride 2 (25 taps: three register chunks in backward-weight)
+    (2, 40, 11, 13, 40, 3, 3, (2, 1), 1, (1, 2), 40),   # depthwise, anisotropic stride and dilation, 5 or 10 channel vectors
+    (1, 16, 12, 12, 16, 7, 7, 1, 3, 1, 16),       # depthwise 7x7 (49 taps)
 ]
+DEPTHWISE = [3, 10, 11, 12, 13]
 
 
 def _case(i, dtype):
@@ -72,7 +77,7 @@ def test_grouped_conv_fwd_dgrad_wgrad(i, dtype, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [0, 2, 4, 7])
+@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12])
 def test_grouped_conv_accumulate(i, dtype, layout):
     """accumulate = 1 adds the gradients to what the buffers hold (the paper's gradient accumulation)."""
     x, w, dy, st, pd, dl, G = _case(i, dtype)
@@ -91,6 +96,14 @@ def test_grouped_conv_accumulate(i, dtype, layout):
     assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
     want_dw = oracle.conv2d_grouped_wgrad(x, dy, w.shape, G, st, pd, dl, into=base_w.astype(np.float64))
     assert max_rel_err(to_host(gdw, layout), want_dw) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", DEPTHWISE)
+def test_depthwise_shapes_on_the_generic_kernels(i, dtype, monkeypatch):
+    """The direct depthwise kernels switched off: the same shapes through the generic grouped launch."""
+    monkeypatch.setenv("NSK_NO_DEPTHWISE", "1")
+    test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
@@ -116,3 +129,63 @@ def test_grouped_results_are_reproducible():
     a = B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, ws=ws)
     b = B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, ws=ws)
     assert torch.equal(a, b)
+
+
+def test_random_grouped_convolutions_match_the_oracle():
+    """Seeded sweep: random group counts (from 2 to depthwise), channels per group 1..32 on both sides, strides 1-3,
+    padding, dilation, non-square filters; every pass, overwrite and accumulate."""
+    rng = np.random.default_rng(4400)
+    ws = B.Workspace()
+    for case in range(100):
+        while True:
+            G = int(rng.choice([2, 2, 3, 4, 8, 8, 16, 32]))
+            cg, kg = (int(rng.choice([1, 1, 2, 3, 4, 8, 8, 16, 32])) for _ in range(2))
+            R, S = (int(rng.choice([1, 2, 3, 3, 3, 5])) for _ in range(2))
+            if rng.random() < 0.7:
+                S = R
+            sh, sw = (int(rng.choice([1, 1, 1, 2, 2, 3])) for _ in range(2))
+            if rng.random() < 0.7:
+                sw = sh
+            ph, pw = int(rng.integers(0, 1 + R // 2 + 1)), int(rng.integers(0, 1 + S // 2 + 1))
+            dh, dw = (int(rng.choice([1, 1, 1, 2])) for _ in range(2))
+            N, H, W = int(rng.integers(1, 4)), int(rng.integers(4, 15)), int(rng.integers(4, 15))
+            P = (H + 2 * ph - dh * (R - 1) - 1) // sh + 1
+            Q = (W + 2 * pw - dw * (S - 1) - 1) // sw + 1
+            if P >= 1 and Q >= 1:
+                break
+        C, K, st, pd, dl = G * cg, G * kg, (sh, sw), (ph, pw), (dh, dw)
+        shape = (N, C, H, W, K, R, S, st, pd, dl, G)
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        layout = B.NSK_NHWC if rng.random() < 0.75 else B.NSK_NCHW
+        print(f"grouped fuzz case {case}: {shape} {dtype} layout={layout}", flush=True)
+        seed = 6000 + case
+        x = on_grid(gen.normal(seed, 0, (N, C, H, W)), dtype)
+        w = on_grid(gen.he_normal(seed, 1, (K, cg, R, S)), dtype)
+        dy = on_grid(gen.normal(seed, 2, (N, K, P, Q)), dtype)
+        base = on_grid(gen.normal(seed, 3, x.shape), dtype)
+        base_w = gen.normal(seed, 4, w.shape).astype(np.float32)
+        tol = TOL[dtype]
+        gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+        y_view, y_check = guarded(gdy.shape, torch_dtype(dtype))
+        B.conv2d_grouped_fwd(gx, gw, G, st, pd, dl, layout, out=y_view, ws=ws)
+        dx_view, dx_check = guarded(gx.shape, torch_dtype(dtype))
+        B.conv2d_grouped_dgrad(gdy, gw, x.shape, G, st, pd, dl, layout, out=dx_view, ws=ws)
+        gacc = to_gpu(base, dtype, layout)
+        B.conv2d_grouped_dgrad(gdy, gw, x.shape, G, st, pd, dl, layout, out=gacc, accumulate=True, ws=ws)
+        dw_view, dw_check = guarded(gw.shape, torch.float32)
+        B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, out=dw_view, ws=ws)
+        gdw = to_gpu(base_w, "f32", layout)
+        B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, dl, layout, out=gdw, accumulate=True, ws=ws)
+        torch.cuda.synchronize()
+        for chk in (y_check, dx_check, dw_check):
+            chk()
+        assert max_rel_err(to_host(y_view, layout), oracle.conv2d_grouped_fwd(x, w, G, st, pd, dl)) <= tol, shape
+        want_dx = oracle.conv2d_grouped_dgrad(dy, w, x.shape, G, st, pd, dl)
+        got_dx = to_host(dx_view, layout)
+        assert max_rel_err(got_dx, want_dx) <= tol, shape
+        assert np.all(got_dx[want_dx == 0.0] == 0.0), shape
+        want_acc = oracle.conv2d_grouped_dgrad(dy, w, x.shape, G, st, pd, dl, into=base.astype(np.float64))
+        assert max_rel_err(to_host(gacc, layout), want_acc) <= tol, shape
+        want_dw = oracle.conv2d_grouped_wgrad(x, dy, w.shape, G, st, pd, dl)
+        assert max_rel_err(to_host(dw_view, layout), want_dw) <= tol, shape
+        assert max_rel_err(to_host(gdw, layout), want_dw + base_w.astype(np.float64)) <= tol, shape
