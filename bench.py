@@ -22,6 +22,10 @@ size: microseconds and TFLOP/s of forward, backward-data and backward-weight, th
 MFMA peak and the fraction of the layer's own roofline cap min(MFMA peak, intensity x 8 TB/s), and
 the FLOP-weighted total over the bf16 3x3 layers of configurations 4 and 5.  Every call of a layer
 runs on its own buffer set, rotated so that the sets together exceed the 256 MB last-level cache.
+
+--grouped prints the same kind of table for grouped convolution layers (the grouped entry points; not a workload of
+the paper): depthwise layers are bound by memory bandwidth, so the table gives GB/s of algorithmic traffic
+(x + y + w once) against the 8 TB/s peak next to TFLOP/s.
 """
 from __future__ import annotations
 
@@ -64,6 +68,7 @@ def parse():
                     help="time the recurrent workload instead: embedding + GRU(256) + output layer, batch 50, sequence "
                          "length 200, vocabulary 32768, 2 classes, forward + backward through time + clipped AdamW")
     ap.add_argument("--layers", action="store_true", help="per-layer convolution table instead of the step benchmark")
+    ap.add_argument("--grouped", action="store_true", help="table of grouped / depthwise convolution layers")
     return ap.parse_args()
 
 
@@ -135,6 +140,66 @@ def layer_table(repeats=20):
     print(f"bf16 3x3 layers of configurations 4 and 5, all passes: {head:.1f} TFLOP/s = {100 * head * 1e12 / PEAK['mfma_bf16']:.1f}% of the bf16 MFMA peak")
     print(json.dumps({"metric": "bf16 3x3 conv TFLOP/s over configs 4 and 5 (fwd+dgrad+wgrad, FLOP-weighted)", "value": head,
                       "unit": "TFLOP/s", "frac_of_mfma_peak": head * 1e12 / PEAK["mfma_bf16"], "layers": rows}))
+
+
+# N, C, H, K, R, stride, pad, groups: depthwise layers at the sizes of the bottleneck stages, and two 32-group layers
+GROUPED_LAYERS = [
+    (128, 128, 56, 128, 3, 1, 1, 128),
+    (128, 128, 56, 128, 3, 2, 1, 128),
+    (128, 256, 28, 256, 3, 1, 1, 256),
+    (128, 512, 14, 512, 3, 1, 1, 512),
+    (128, 256, 28, 256, 3, 1, 1, 32),
+    (128, 128, 56, 128, 3, 1, 1, 32),
+]
+
+
+def grouped_table(repeats=10):
+    """Grouped convolution layers at full size (see the module docstring)."""
+    import torch
+    from paper_2409_11600_amd import binding as B
+
+    ws = B.Workspace()
+    gen_t = torch.Generator(device="cuda").manual_seed(11)
+    dt, es = torch.bfloat16, 2
+    print(f"{'layer':<46}{'pass':<7}{'us':>9}{'GB/s':>8}{'%hbm':>6}{'TFLOP/s':>9}")
+    rows = []
+    for N, C, H, K, R, stride, pad, G in GROUPED_LAYERS:
+        P = (H + 2 * pad - R) // stride + 1
+        cg = C // G
+        flops = 2.0 * N * P * P * K * cg * R * R
+        xb, yb = N * H * H * C * es, N * P * P * K * es
+        nset = max(2, int(300e6 // (xb + yb)) + 1)
+        sets = []
+        for _ in range(nset):
+            x = torch.randn(N, H, H, C, device="cuda", generator=gen_t).to(dt)
+            dy = torch.randn(N, P, P, K, device="cuda", generator=gen_t).to(dt)
+            sets.append((x, dy, torch.empty_like(dy), torch.empty_like(x)))
+        w = (torch.randn(K, R, R, cg, device="cuda", generator=gen_t) * (2.0 / (cg * R * R)) ** 0.5).to(dt)
+        dw = torch.empty(K, R, R, cg, device="cuda")
+        wbytes = K * R * R * cg
+        passes = {
+            "fwd": (lambda s: B.conv2d_grouped_fwd(s[0], w, G, stride, pad, 1, out=s[2], ws=ws), xb + yb + wbytes * es),
+            "dgrad": (lambda s: B.conv2d_grouped_dgrad(s[1], w, (N, C, H, H), G, stride, pad, 1, out=s[3], ws=ws), xb + yb + wbytes * es),
+            "wgrad": (lambda s: B.conv2d_grouped_wgrad(s[0], s[1], (K, cg, R, R), G, stride, pad, 1, out=dw, ws=ws), xb + yb + wbytes * 4),
+        }
+        name = f"{R}x{R} s{stride} {C}->{K} groups={G} @{H}x{H} N={N} bf16"
+        for pname, (fn, byts) in passes.items():
+            for i in range(2):
+                fn(sets[i % nset])
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for i in range(repeats):
+                fn(sets[i % nset])
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / repeats
+            gbs, tf = byts / ms / 1e6, flops / ms / 1e9
+            print(f"{name:<46}{pname:<7}{ms * 1e3:9.1f}{gbs:8.0f}{100 * gbs * 1e9 / PEAK['hbm']:6.1f}{tf:9.1f}", flush=True)
+            rows.append({"layer": name, "pass": pname, "us": ms * 1e3, "gbytes_per_s": gbs,
+                         "frac_of_hbm_peak": gbs * 1e9 / PEAK["hbm"], "tflops": tf})
+        del sets
+    print(json.dumps({"metric": "grouped convolution layers (fwd, dgrad, wgrad)", "unit": "us", "layers": rows}))
 
 
 def call_cost(net, f, args):
@@ -255,6 +320,9 @@ def main():
         return
     if a.gru:
         gru_bench(a)
+        return
+    if a.grouped:
+        grouped_table()
         return
     wl = gen.workload(a.config, batch=a.batch, stage=a.stage)
     tensors = gen.workload_tensors(wl)

@@ -1,6 +1,8 @@
 // Depthwise convolution (a grouped convolution with one input and one output channel per group; the grouped entry
-// points of the library, not one of the paper's workloads): y[n][p][q][c] = sum over taps of x[n][h][w][c] * w[c][tap].
-// There is no contraction over channels, so nothing here is GEMM-shaped: every pass reads each activation once from
+// points of the library, not one of the paper's workloads): y[n][p][q][c] = sum over taps of x[n][h][w][c] * w[c][tap],
+// and its neighbours with two or four channels per group on both sides (template parameter CG), where an output channel
+// sums over the CG input channels of its group.
+// The contraction over channels is absent or tiny, so nothing here is GEMM-shaped: every pass reads each activation once from
 // HBM (the taps' re-reads hit the caches), does ntaps multiply-adds per element on the vector ALUs and is bound by
 // memory bandwidth.  NHWC puts the channels of a pixel side by side, so a lane owns one 16-byte vector of channels
 // and consecutive lanes read consecutive addresses.
@@ -18,11 +20,13 @@ namespace nsk {
 namespace {
 
 constexpr int DW_PIX = 4;          // output pixels per lane (forward / backward-data)
+constexpr int DW_ROUND = 3;        // taps whose loads are issued together
 constexpr int DW_LDS_MAX = 48 << 10;  // bytes of LDS the transposed filter may take
-constexpr int DW_TC = 9;           // taps per register chunk of the backward-weight kernel
 constexpr int DW_CVB = 16;         // channel vectors per backward-weight block
 
 template <typename T> struct DTraits;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
 template <> struct DTraits<float> {
     static constexpr int VEC = 4;
     typedef f32x4 Vec;
@@ -32,21 +36,53 @@ template <> struct DTraits<bf16_t> {
     typedef bf16x8 Vec;
 };
 
-template <typename T>
+typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+
+// acc += x . w over the two bf16 halves of a dword: one instruction per product pair, no conversion to float.  With one
+// half of w zero it is a single multiply-add on the other half (the zero times a finite x adds nothing).
+__device__ inline float dot2(unsigned x, unsigned w, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x), __builtin_bit_cast(bf16x2, w), acc, false);
+}
+
+// LDS words per (tap, output channel): floats w[k][t][0..CG) for fp32; for bf16 dwords of two filter values each
+// (CG = 1: the value in the half that matches the channel's place in its input dword, zero in the other).
+template <typename T, int CG> constexpr int lds_words() { return sizeof(T) == 4 ? CG : (CG + 1) / 2; }
+
+template <typename T, int CG>
 __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
 {
     typedef typename DTraits<T>::Vec Vec;
     constexpr int VEC = DTraits<T>::VEC;
-    extern __shared__ __attribute__((aligned(16))) float wT[];   // [ntaps][C]
+    constexpr bool F32 = sizeof(T) == 4;
+    constexpr int WPK = lds_words<T, CG>();
+    static_assert(VEC % CG == 0, "a channel vector holds whole groups");
+    extern __shared__ __attribute__((aligned(16))) unsigned wL[];   // [ntaps][C][WPK]
     __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
     const int tid = threadIdx.x;
-    const int C = a.groups, CV = C / VEC, ntaps = a.ntaps;
-    const T *__restrict__ src = (const T *)a.src;
-    const T *__restrict__ wpk = (const T *)a.wpk;      // [C][ntaps]
+    const int C = a.groups * CG, CV = C / VEC, ntaps = a.ntaps;
     T *__restrict__ out = (T *)a.out;
-    for (int i = tid; i < ntaps * C; i += 256) {
-        const int c = i / ntaps, t = i - c * ntaps;
-        wT[t * C + c] = (float)wpk[i];
+    if constexpr (F32) {
+        const float *__restrict__ wpk = (const float *)a.wpk;      // [C][ntaps][CG]
+        for (int i = tid; i < ntaps * C * CG; i += 256) {
+            const int cl = i % CG, r = i / CG;
+            const int c = r / ntaps, t = r - c * ntaps;
+            wL[(t * C + c) * CG + cl] = __float_as_uint(wpk[i]);
+        }
+    } else {
+        const unsigned short *__restrict__ wpk = (const unsigned short *)a.wpk;
+        for (int i = tid; i < ntaps * C * WPK; i += 256) {
+            const int j = i % WPK, r = i / WPK;
+            const int c = r / ntaps, t = r - c * ntaps;
+            unsigned v;
+            if (CG == 1) {
+                v = (unsigned)wpk[r] << ((c & 1) * 16);
+            } else {
+                const unsigned short *q = wpk + (long)r * CG + 2 * j;
+                v = (unsigned)q[0] | ((unsigned)q[1] << 16);
+            }
+            wL[(t * C + c) * WPK + j] = v;
+        }
     }
     if (tid < kMaxTaps) {
         s_offh[tid] = a.off_h[tid];
@@ -60,9 +96,13 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
     if (slot * DW_PIX >= a.M) return;
     const int c0 = cv * VEC;
 
+    // Loads go through a buffer descriptor: an offset of ~0 is out of range and returns zeros, so a tap outside the
+    // image costs no branch and the loads of a round of taps are all in flight together.
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
     bool ok[DW_PIX];
     int bh[DW_PIX], bw[DW_PIX];
-    long src_img[DW_PIX], out_off[DW_PIX];
+    unsigned base[DW_PIX];
+    long out_off[DW_PIX];
     float acc[DW_PIX][VEC];
     const int per_img = a.Mi * a.Mj;
 #pragma unroll
@@ -76,7 +116,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
         const int j = rem - i * a.Mj;
         bh[u] = i * a.mult_h + a.add_h;
         bw[u] = j * a.mult_w + a.add_w;
-        src_img[u] = (long)img * a.Hs;
+        base[u] = (unsigned)(((((long)img * a.Hs + bh[u]) * a.Ws + bw[u]) * C + c0) * (long)sizeof(T));
         out_off[u] = (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * C + c0;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[u][e] = 0.f;
@@ -86,22 +126,48 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
             for (int e = 0; e < VEC; ++e) acc[u][e] = (float)old[e];
         }
     }
-    for (int t = 0; t < ntaps; ++t) {
-        float wv[VEC];
+    for (int t0 = 0; t0 < ntaps; t0 += DW_ROUND) {
+        u32x4 xv[DW_ROUND][DW_PIX];
+        int tt[DW_ROUND];
 #pragma unroll
-        for (int e = 0; e < VEC; e += 4) {
-            const f32x4 q = *(const f32x4 *)&wT[t * C + c0 + e];
-            wv[e] = q[0]; wv[e + 1] = q[1]; wv[e + 2] = q[2]; wv[e + 3] = q[3];
-        }
-        const int oh = s_offh[t], ow = s_offw[t];
+        for (int k = 0; k < DW_ROUND; ++k) {
+            const bool tap_ok = t0 + k < ntaps;
+            tt[k] = tap_ok ? t0 + k : ntaps - 1;
+            const int oh = s_offh[tt[k]], ow = s_offw[tt[k]];
+            const unsigned delta = (unsigned)((oh * a.Ws + ow) * C * (int)sizeof(T));
 #pragma unroll
-        for (int u = 0; u < DW_PIX; ++u) {
-            const int h = bh[u] + oh, w = bw[u] + ow;
-            if (ok[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws) {
-                const Vec xv = *(const Vec *)(src + ((src_img[u] + h) * a.Ws + w) * C + c0);
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) acc[u][e] += (float)xv[e] * wv[e];
+            for (int u = 0; u < DW_PIX; ++u) {
+                const int h = bh[u] + oh, w = bw[u] + ow;
+                const bool in = tap_ok && ok[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
+                xv[k][u] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, in ? base[u] + delta : ~0u, 0, 0));
             }
+        }
+#pragma unroll
+        for (int k = 0; k < DW_ROUND; ++k) {
+            unsigned wv[VEC * WPK];
+#pragma unroll
+            for (int e = 0; e < VEC * WPK; e += 4) {
+                const u32x4 q = *(const u32x4 *)&wL[(tt[k] * C + c0) * WPK + e];
+                wv[e] = q[0]; wv[e + 1] = q[1]; wv[e + 2] = q[2]; wv[e + 3] = q[3];
+            }
+#pragma unroll
+            for (int u = 0; u < DW_PIX; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) {
+                    if constexpr (F32) {
+                        // the CG input channels of output channel e's group are words (e / CG) * CG .. of the vector
+#pragma unroll
+                        for (int cl = 0; cl < CG; ++cl)
+                            acc[u][e] += __uint_as_float(xv[k][u][(e / CG) * CG + cl]) * __uint_as_float(wv[e * CG + cl]);
+                    } else if constexpr (CG == 1) {
+                        acc[u][e] = dot2(xv[k][u][e / 2], wv[e], acc[u][e]);
+                    } else {
+                        // the group's CG input channels are dwords (e / CG) * (CG / 2) .. of the vector
+#pragma unroll
+                        for (int j = 0; j < WPK; ++j)
+                            acc[u][e] = dot2(xv[k][u][(e / CG) * WPK + j], wv[e * WPK + j], acc[u][e]);
+                    }
+                }
         }
     }
 #pragma unroll
@@ -114,23 +180,29 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
     }
 }
 
-template <typename T>
+// Taps per register chunk of the backward-weight kernel: a lane keeps taps x VEC x CG sums.
+template <int CG> constexpr int wgrad_taps() { return CG == 1 ? 9 : (CG == 2 ? 5 : 3); }
+
+template <typename T, int CG>
 __global__ __launch_bounds__(256) void depthwise_wgrad_kernel(const WgradArgs a)
 {
     typedef typename DTraits<T>::Vec Vec;
     constexpr int VEC = DTraits<T>::VEC;
+    constexpr int TC = wgrad_taps<CG>();
     __shared__ float red[256 * VEC];
     __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
     const int tid = threadIdx.x;
-    const int C = a.groups, CV = C / VEC;
+    const int C = a.groups * CG, CV = C / VEC;
     const int cvb = min(CV - (int)blockIdx.x * DW_CVB, DW_CVB);   // channel vectors of this block (>= 1)
     const int PL = 256 / cvb;                                     // pixel lanes
     const int cvl = tid % cvb, pl = tid / cvb;
     const bool active = pl < PL;
     const int c0 = (blockIdx.x * DW_CVB + cvl) * VEC;
     const int split = blockIdx.y;
-    const T *__restrict__ x = (const T *)a.x;
     const T *__restrict__ dy = (const T *)a.dy;
+    // x through a buffer descriptor (an offset of ~0 returns zeros): taps outside the image cost no branch
+    const __amdgpu_buffer_rsrc_t xrsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)a.x, 0, (unsigned)((long)a.Nimg * a.H * a.W * C * (long)sizeof(T)), 0x00020000);
     if (tid < kMaxTaps) {
         s_offh[tid] = a.off_h[tid];
         s_offw[tid] = a.off_w[tid];
@@ -139,53 +211,69 @@ __global__ __launch_bounds__(256) void depthwise_wgrad_kernel(const WgradArgs a)
     const int l_begin = split * a.rows_per_split;
     const int l_end = min(a.L, l_begin + a.rows_per_split);
     const int pq = a.P * a.Q;
-    float *__restrict__ part = a.part + (long)split * C * a.ntaps;   // [C][ntaps]
+    float *__restrict__ part = a.part + (long)split * C * a.ntaps * CG;   // [C][ntaps][CG]
 
-    for (int t0 = 0; t0 < a.ntaps; t0 += DW_TC) {
-        float acc[DW_TC][VEC];
+    for (int t0 = 0; t0 < a.ntaps; t0 += TC) {
+        float acc[TC][VEC][CG];
 #pragma unroll
-        for (int tt = 0; tt < DW_TC; ++tt)
+        for (int tt = 0; tt < TC; ++tt)
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[tt][e] = 0.f;
+            for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                for (int cl = 0; cl < CG; ++cl) acc[tt][e][cl] = 0.f;
         if (active)
+#pragma unroll 2
             for (int l = l_begin + pl; l < l_end; l += PL) {
                 const int img = l / pq;
                 const int rem = l - img * pq;
                 const int p = rem / a.Q;
                 const int q = rem - p * a.Q;
                 const Vec dv = *(const Vec *)(dy + (long)l * C + c0);
+                const int h0 = p * a.sh - a.ph, w0 = q * a.sw - a.pw;
+                const unsigned base = (unsigned)(((((long)img * a.H + h0) * a.W + w0) * C + c0) * (long)sizeof(T));
+                Vec xv[TC];
+#pragma unroll
+                for (int tt = 0; tt < TC; ++tt) {
+                    const int t = min(t0 + tt, a.ntaps - 1);
+                    const int oh = s_offh[t], ow = s_offw[t];
+                    const int h = h0 + oh, w = w0 + ow;
+                    const bool in = t0 + tt < a.ntaps && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+                    const unsigned off = base + (unsigned)((oh * a.W + ow) * C * (int)sizeof(T));
+                    xv[tt] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(xrsrc, in ? off : ~0u, 0, 0));
+                }
                 float df[VEC];
 #pragma unroll
                 for (int e = 0; e < VEC; ++e) df[e] = (float)dv[e];
-                const int h0 = p * a.sh - a.ph, w0 = q * a.sw - a.pw;
 #pragma unroll
-                for (int tt = 0; tt < DW_TC; ++tt) {
-                    const int t = t0 + tt;
-                    if (t >= a.ntaps) break;
-                    const int h = h0 + s_offh[t], w = w0 + s_offw[t];
-                    if ((unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W) {
-                        const Vec xv = *(const Vec *)(x + (((long)img * a.H + h) * a.W + w) * C + c0);
+                for (int tt = 0; tt < TC; ++tt) {
+                    float xf[VEC];
 #pragma unroll
-                        for (int e = 0; e < VEC; ++e) acc[tt][e] += df[e] * (float)xv[e];
-                    }
+                    for (int e = 0; e < VEC; ++e) xf[e] = (float)xv[tt][e];
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e)
+#pragma unroll
+                        for (int cl = 0; cl < CG; ++cl) acc[tt][e][cl] += df[e] * xf[(e / CG) * CG + cl];
                 }
             }
-        // combine the pixel lanes, one tap at a time, in a fixed order
+        // combine the pixel lanes, one (tap, channel of the group) at a time, in a fixed order
 #pragma unroll
-        for (int tt = 0; tt < DW_TC; ++tt) {
+        for (int tt = 0; tt < TC; ++tt) {
             const int t = t0 + tt;
             if (t >= a.ntaps) break;    // uniform over the block
-            if (active)
 #pragma unroll
-                for (int e = 0; e < VEC; ++e) red[pl * (cvb * VEC) + cvl * VEC + e] = acc[tt][e];
-            __syncthreads();
-            if (tid < cvb * VEC) {
-                float s = 0.f;
-                for (int r = 0; r < PL; ++r) s += red[r * (cvb * VEC) + tid];
-                const int c = blockIdx.x * DW_CVB * VEC + tid;
-                part[(long)c * a.ntaps + t] = s;
+            for (int cl = 0; cl < CG; ++cl) {
+                if (active)
+#pragma unroll
+                    for (int e = 0; e < VEC; ++e) red[pl * (cvb * VEC) + cvl * VEC + e] = acc[tt][e][cl];
+                __syncthreads();
+                if (tid < cvb * VEC) {
+                    float s = 0.f;
+                    for (int r = 0; r < PL; ++r) s += red[r * (cvb * VEC) + tid];
+                    const int c = blockIdx.x * DW_CVB * VEC + tid;
+                    part[((long)c * a.ntaps + t) * CG + cl] = s;
+                }
+                __syncthreads();
             }
-            __syncthreads();
         }
     }
 }
@@ -196,41 +284,63 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 
 bool depthwise_applicable(int dtype, const IgemmArgs &a)
 {
-    const int vec = dtype == NSK_BF16 ? 8 : 4;
-    return a.groups > 1 && a.Cs == 1 && a.Ngemm == 1 && a.src_ld == a.groups && a.Co == a.groups &&
-           a.groups % vec == 0 && (long)a.ntaps * a.groups * 4 <= DW_LDS_MAX && a.ntaps >= 1 && !a.stats &&
-           aligned16(a.src) && aligned16(a.out);
+    const int vec = dtype == NSK_BF16 ? 8 : 4, cg = a.Cs;
+    if (!(a.groups > 1 && (cg == 1 || cg == 2 || cg == 4) && a.Ngemm == cg)) return false;
+    const int C = a.groups * cg;
+    const long words = dtype == NSK_BF16 ? (cg + 1) / 2 : cg;
+    return a.src_ld == C && a.Co == C && C % vec == 0 && (long)a.ntaps * C * words * 4 <= DW_LDS_MAX && a.ntaps >= 1 &&
+           !a.stats && aligned16(a.src) && aligned16(a.out);
+}
+
+template <typename T, int CG> int launch_depthwise_typed(const IgemmArgs &a, hipStream_t stream)
+{
+    constexpr int VEC = DTraits<T>::VEC;
+    const int C = a.groups * CG;
+    const long threads = ((long)a.M + DW_PIX - 1) / DW_PIX * (C / VEC);
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    const size_t lds = (size_t)a.ntaps * C * lds_words<T, CG>() * sizeof(unsigned);
+    hipLaunchKernelGGL((depthwise_kernel<T, CG>), dim3(blocks), dim3(256), lds, stream, a);
+    return check_launch();
 }
 
 int launch_depthwise(int dtype, const IgemmArgs &a, hipStream_t stream)
 {
-    const int vec = dtype == NSK_BF16 ? 8 : 4;
-    const long threads = ((long)a.M + DW_PIX - 1) / DW_PIX * (a.groups / vec);
-    const unsigned blocks = (unsigned)((threads + 255) / 256);
-    const size_t lds = (size_t)a.ntaps * a.groups * sizeof(float);
-    if (dtype == NSK_BF16)
-        hipLaunchKernelGGL((depthwise_kernel<bf16_t>), dim3(blocks), dim3(256), lds, stream, a);
-    else
-        hipLaunchKernelGGL((depthwise_kernel<float>), dim3(blocks), dim3(256), lds, stream, a);
-    return check_launch();
+    if (dtype == NSK_BF16) {
+        if (a.Cs == 1) return launch_depthwise_typed<bf16_t, 1>(a, stream);
+        if (a.Cs == 2) return launch_depthwise_typed<bf16_t, 2>(a, stream);
+        return launch_depthwise_typed<bf16_t, 4>(a, stream);
+    }
+    if (a.Cs == 1) return launch_depthwise_typed<float, 1>(a, stream);
+    if (a.Cs == 2) return launch_depthwise_typed<float, 2>(a, stream);
+    return launch_depthwise_typed<float, 4>(a, stream);
 }
 
 bool depthwise_wgrad_applicable(int dtype, const WgradArgs &a)
 {
-    const int vec = dtype == NSK_BF16 ? 8 : 4;
-    return a.groups > 1 && a.C == 1 && a.K == 1 && a.ldx == a.groups && a.ldy == a.groups && a.groups % vec == 0 &&
-           a.splits >= 1 && a.splits <= 65535 && aligned16(a.x) && aligned16(a.dy);
+    const int vec = dtype == NSK_BF16 ? 8 : 4, cg = a.C;
+    if (!(a.groups > 1 && (cg == 1 || cg == 2 || cg == 4) && a.K == cg)) return false;
+    const int C = a.groups * cg;
+    return a.ldx == C && a.ldy == C && C % vec == 0 && a.splits >= 1 && a.splits <= 65535 && aligned16(a.x) &&
+           aligned16(a.dy);
+}
+
+template <typename T, int CG> int launch_depthwise_wgrad_typed(const WgradArgs &a, hipStream_t stream)
+{
+    dim3 grid(ceil_div(a.groups * CG / DTraits<T>::VEC, DW_CVB), a.splits);
+    hipLaunchKernelGGL((depthwise_wgrad_kernel<T, CG>), grid, dim3(256), 0, stream, a);
+    return check_launch();
 }
 
 int launch_depthwise_wgrad(int dtype, const WgradArgs &a, hipStream_t stream)
 {
-    const int vec = dtype == NSK_BF16 ? 8 : 4;
-    dim3 grid(ceil_div(a.groups / vec, DW_CVB), a.splits);
-    if (dtype == NSK_BF16)
-        hipLaunchKernelGGL((depthwise_wgrad_kernel<bf16_t>), grid, dim3(256), 0, stream, a);
-    else
-        hipLaunchKernelGGL((depthwise_wgrad_kernel<float>), grid, dim3(256), 0, stream, a);
-    return check_launch();
+    if (dtype == NSK_BF16) {
+        if (a.C == 1) return launch_depthwise_wgrad_typed<bf16_t, 1>(a, stream);
+        if (a.C == 2) return launch_depthwise_wgrad_typed<bf16_t, 2>(a, stream);
+        return launch_depthwise_wgrad_typed<bf16_t, 4>(a, stream);
+    }
+    if (a.C == 1) return launch_depthwise_wgrad_typed<float, 1>(a, stream);
+    if (a.C == 2) return launch_depthwise_wgrad_typed<float, 2>(a, stream);
+    return launch_depthwise_wgrad_typed<float, 4>(a, stream);
 }
 
 }  // namespace nsk

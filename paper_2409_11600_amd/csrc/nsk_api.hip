@@ -129,6 +129,16 @@ ConvPlan plan_conv(const ConvGeo &g, int pass, int groups = 1)
             p.rows_per_split = wgrad_wide_rows_per_split(wa, &p.splits);
         else
             p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * (g.C / groups), &p.splits);
+        if (groups > 1 && g.C == g.K && (g.C == groups || g.C == 2 * groups || g.C == 4 * groups)) {
+            // depthwise and its neighbours: the direct kernel runs blocks of 16 channel vectors x one split and wants
+            // about four per CU
+            const int vec = g.dtype == NSK_BF16 ? 8 : 4, L = g.N * g.P * g.Q;
+            const int want = 1024 / ceil_div(ceil_div(g.C, vec), 16) > 0 ? 1024 / ceil_div(ceil_div(g.C, vec), 16) : 1;
+            int rows = ceil_div(L, want);
+            if (rows < 64) rows = 64;
+            p.rows_per_split = ceil_div(rows, 32) * 32;
+            p.splits = ceil_div(L, p.rows_per_split);
+        }
         // a grouped launch puts groups * splits on gridDim.z
         while ((long)groups * p.splits > 65535) {
             p.rows_per_split *= 2;

@@ -29,8 +29,11 @@ GROUPED_SHAPES = [
     (1, 256, 9, 7, 256, 5, 5, 2, 2, 1, 256),      # depthwise 5x5 stride 2 (25 taps: three register chunks in backward-weight)
     (2, 40, 11, 13, 40, 3, 3, (2, 1), 1, (1, 2), 40),   # depthwise, anisotropic stride and dilation, 5 or 10 channel vectors
     (1, 16, 12, 12, 16, 7, 7, 1, 3, 1, 16),       # depthwise 7x7 (49 taps)
+    (2, 32, 9, 11, 32, 3, 3, 1, 1, 1, 16),        # two channels per group on both sides (direct kernels)
+    (1, 64, 10, 8, 64, 5, 5, 1, 2, 1, 16),        # four channels per group, 5x5
+    (2, 128, 12, 12, 128, 3, 3, 1, 1, 1, 32),     # the 32-group bottleneck shape at stride 1
 ]
-DEPTHWISE = [3, 10, 11, 12, 13]
+DEPTHWISE = [2, 3, 10, 11, 12, 13, 14, 15, 16]     # shapes the direct kernels take
 
 
 def _case(i, dtype):
@@ -77,7 +80,7 @@ def test_grouped_conv_fwd_dgrad_wgrad(i, dtype, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12])
+@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12, 14, 15])
 def test_grouped_conv_accumulate(i, dtype, layout):
     """accumulate = 1 adds the gradients to what the buffers hold (the paper's gradient accumulation)."""
     x, w, dy, st, pd, dl, G = _case(i, dtype)
