@@ -50,7 +50,7 @@ __device__ inline float dot2(unsigned x, unsigned w, float acc)
 template <typename T, int CG> constexpr int lds_words() { return sizeof(T) == 4 ? CG : (CG + 1) / 2; }
 
 template <typename T, int CG>
-__global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
+__global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const int iters)
 {
     typedef typename DTraits<T>::Vec Vec;
     constexpr int VEC = DTraits<T>::VEC;
@@ -90,15 +90,16 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
     }
     __syncthreads();
 
-    const long f = (long)blockIdx.x * 256 + tid;
-    const int cv = (int)(f % CV);
-    const long slot = f / CV;
-    if (slot * DW_PIX >= a.M) return;
-    const int c0 = cv * VEC;
-
     // Loads go through a buffer descriptor: an offset of ~0 is out of range and returns zeros, so a tap outside the
     // image costs no branch and the loads of a round of taps are all in flight together.
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    // a block takes `iters` consecutive runs of 256 (pixel group, channel vector) pairs: the staged filter serves them all
+    for (int it = 0; it < iters; ++it) {
+    const long f = ((long)blockIdx.x * iters + it) * 256 + tid;
+    const int cv = (int)(f % CV);
+    const long slot = f / CV;
+    if (slot * DW_PIX >= a.M) break;
+    const int c0 = cv * VEC;
     bool ok[DW_PIX];
     int bh[DW_PIX], bw[DW_PIX];
     unsigned base[DW_PIX];
@@ -177,6 +178,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a)
 #pragma unroll
         for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][e];
         *(Vec *)(out + out_off[u]) = o;
+    }
     }
 }
 
@@ -297,9 +299,13 @@ template <typename T, int CG> int launch_depthwise_typed(const IgemmArgs &a, hip
     constexpr int VEC = DTraits<T>::VEC;
     const int C = a.groups * CG;
     const long threads = ((long)a.M + DW_PIX - 1) / DW_PIX * (C / VEC);
-    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    const long runs = (threads + 255) / 256;
+    // enough blocks to fill the chip several times over, each with as many runs as that leaves (at most 8)
+    int iters = (int)(runs / 2048);
+    iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
+    const unsigned blocks = (unsigned)((runs + iters - 1) / iters);
     const size_t lds = (size_t)a.ntaps * C * lds_words<T, CG>() * sizeof(unsigned);
-    hipLaunchKernelGGL((depthwise_kernel<T, CG>), dim3(blocks), dim3(256), lds, stream, a);
+    hipLaunchKernelGGL((depthwise_kernel<T, CG>), dim3(blocks), dim3(256), lds, stream, a, iters);
     return check_launch();
 }
 
