@@ -21,7 +21,8 @@ the loss, their backward passes and the SGD update of every parameter, timed as 
 size: microseconds and TFLOP/s of forward, backward-data and backward-weight, the fraction of the
 MFMA peak and the fraction of the layer's own roofline cap min(MFMA peak, intensity x 8 TB/s), and
 the FLOP-weighted total over the bf16 3x3 layers of configurations 4 and 5.  Every call of a layer
-runs on its own buffer set, rotated so that the sets together exceed the 256 MB last-level cache.
+runs on its own buffer set, rotated so that the sets together exceed the 256 MB last-level cache; the calls of a
+pass are replayed from one HIP graph, so the cost of issuing them from Python is not in the figures.
 
 --grouped prints the same kind of table for grouped convolution layers (the grouped entry points; not a workload of
 the paper): depthwise layers are bound by memory bandwidth, so the table gives GB/s of algorithmic traffic
@@ -72,6 +73,30 @@ def parse():
     return ap.parse_args()
 
 
+def _time_calls(torch, fn, sets, repeats):
+    """Milliseconds per call of fn over `repeats` calls on rotating buffer sets.  The calls are captured into one HIP
+    graph and the replay is timed, so the Python and ctypes cost of issuing a call (10-20 us) does not show in layers
+    that run shorter than that."""
+    nset = len(sets)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for i in range(3):
+            fn(sets[i % nset])
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            for i in range(repeats):
+                fn(sets[i % nset])
+        graph.replay()
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        graph.replay()
+        e1.record(stream)
+        stream.synchronize()
+    return e0.elapsed_time(e1) / repeats
+
+
 def layer_table(repeats=20):
     """Per-layer convolution timings at full size (see the module docstring)."""
     import torch
@@ -116,16 +141,7 @@ def layer_table(repeats=20):
         }
         name = f"{R}x{R} s{stride} {C}->{K} @{H}x{W} N={N} {dtype}"
         for pname, (fn, byts) in passes.items():
-            for i in range(3):
-                fn(sets[i % nset])
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for i in range(repeats):
-                fn(sets[i % nset])
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / repeats
+            ms = _time_calls(torch, fn, sets, repeats)
             cap = min(peak, flops / byts * PEAK["hbm"])
             tf = flops / ms / 1e9
             print(f"{cfg:<5}{name:<38}{pname:<7}{ms * 1e3:9.1f}{tf:9.1f}{100 * tf * 1e12 / peak:7.1f}{cap / 1e12:8.0f}{100 * tf * 1e12 / cap:6.1f}",
@@ -184,16 +200,7 @@ def grouped_table(repeats=10):
         }
         name = f"{R}x{R} s{stride} {C}->{K} groups={G} @{H}x{H} N={N} bf16"
         for pname, (fn, byts) in passes.items():
-            for i in range(2):
-                fn(sets[i % nset])
-            torch.cuda.synchronize()
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for i in range(repeats):
-                fn(sets[i % nset])
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / repeats
+            ms = _time_calls(torch, fn, sets, repeats)
             gbs, tf = byts / ms / 1e6, flops / ms / 1e9
             print(f"{name:<46}{pname:<7}{ms * 1e3:9.1f}{gbs:8.0f}{100 * gbs * 1e9 / PEAK['hbm']:6.1f}{tf:9.1f}", flush=True)
             rows.append({"layer": name, "pass": pname, "us": ms * 1e3, "gbytes_per_s": gbs,

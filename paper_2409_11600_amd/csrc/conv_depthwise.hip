@@ -14,6 +14,8 @@
 //    and one split of the pixels; its pixel lanes stride through the split with the per-tap sums in registers and are
 //    combined through LDS in a fixed order.  The partial sums land in the layout of the generic split kernel, so the
 //    same deterministic reduction finishes the job.
+#include <stdlib.h>
+
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -49,20 +51,36 @@ __device__ inline float dot2(unsigned x, unsigned w, float acc)
 // (CG = 1: the value in the half that matches the channel's place in its input dword, zero in the other).
 template <typename T, int CG> constexpr int lds_words() { return sizeof(T) == 4 ? CG : (CG + 1) / 2; }
 
+// acc[e] += sum over the CG input channels of output channel e's group of x * w, for the VEC output channels of one
+// channel vector; xv = the pixel's vector as loaded, wv = the LDS words of these output channels for one tap.
 template <typename T, int CG>
-__global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const int iters)
+__device__ inline void mac_vec(float (&acc)[DTraits<T>::VEC], const u32x4 &xv,
+                               const unsigned (&wv)[DTraits<T>::VEC * lds_words<T, CG>()])
 {
-    typedef typename DTraits<T>::Vec Vec;
-    constexpr int VEC = DTraits<T>::VEC;
-    constexpr bool F32 = sizeof(T) == 4;
+    constexpr int VEC = DTraits<T>::VEC, WPK = lds_words<T, CG>();
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        if constexpr (sizeof(T) == 4) {
+            // the group's input channels are words (e / CG) * CG .. of the vector
+#pragma unroll
+            for (int cl = 0; cl < CG; ++cl)
+                acc[e] += __uint_as_float(xv[(e / CG) * CG + cl]) * __uint_as_float(wv[e * CG + cl]);
+        } else if constexpr (CG == 1) {
+            acc[e] = dot2(xv[e / 2], wv[e], acc[e]);
+        } else {
+            // the group's input channels are dwords (e / CG) * (CG / 2) .. of the vector
+#pragma unroll
+            for (int j = 0; j < WPK; ++j) acc[e] = dot2(xv[(e / CG) * WPK + j], wv[e * WPK + j], acc[e]);
+        }
+    }
+}
+
+// The filter of a launch, as the kernels keep it in LDS: wL[(tap * C + channel) * WPK + word].
+template <typename T, int CG> __device__ inline void stage_filter(const IgemmArgs &a, unsigned *wL, int C)
+{
     constexpr int WPK = lds_words<T, CG>();
-    static_assert(VEC % CG == 0, "a channel vector holds whole groups");
-    extern __shared__ __attribute__((aligned(16))) unsigned wL[];   // [ntaps][C][WPK]
-    __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
-    const int tid = threadIdx.x;
-    const int C = a.groups * CG, CV = C / VEC, ntaps = a.ntaps;
-    T *__restrict__ out = (T *)a.out;
-    if constexpr (F32) {
+    const int tid = threadIdx.x, ntaps = a.ntaps;
+    if constexpr (sizeof(T) == 4) {
         const float *__restrict__ wpk = (const float *)a.wpk;      // [C][ntaps][CG]
         for (int i = tid; i < ntaps * C * CG; i += 256) {
             const int cl = i % CG, r = i / CG;
@@ -84,6 +102,21 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const
             wL[(t * C + c) * WPK + j] = v;
         }
     }
+}
+
+template <typename T, int CG>
+__global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const int iters)
+{
+    typedef typename DTraits<T>::Vec Vec;
+    constexpr int VEC = DTraits<T>::VEC;
+    constexpr int WPK = lds_words<T, CG>();
+    static_assert(VEC % CG == 0, "a channel vector holds whole groups");
+    extern __shared__ __attribute__((aligned(16))) unsigned wL[];   // [ntaps][C][WPK]
+    __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
+    const int tid = threadIdx.x;
+    const int C = a.groups * CG, CV = C / VEC, ntaps = a.ntaps;
+    T *__restrict__ out = (T *)a.out;
+    stage_filter<T, CG>(a, wL, C);
     if (tid < kMaxTaps) {
         s_offh[tid] = a.off_h[tid];
         s_offw[tid] = a.off_w[tid];
@@ -152,23 +185,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const
                 wv[e] = q[0]; wv[e + 1] = q[1]; wv[e + 2] = q[2]; wv[e + 3] = q[3];
             }
 #pragma unroll
-            for (int u = 0; u < DW_PIX; ++u)
-#pragma unroll
-                for (int e = 0; e < VEC; ++e) {
-                    if constexpr (F32) {
-                        // the CG input channels of output channel e's group are words (e / CG) * CG .. of the vector
-#pragma unroll
-                        for (int cl = 0; cl < CG; ++cl)
-                            acc[u][e] += __uint_as_float(xv[k][u][(e / CG) * CG + cl]) * __uint_as_float(wv[e * CG + cl]);
-                    } else if constexpr (CG == 1) {
-                        acc[u][e] = dot2(xv[k][u][e / 2], wv[e], acc[u][e]);
-                    } else {
-                        // the group's CG input channels are dwords (e / CG) * (CG / 2) .. of the vector
-#pragma unroll
-                        for (int j = 0; j < WPK; ++j)
-                            acc[u][e] = dot2(xv[k][u][(e / CG) * WPK + j], wv[e * WPK + j], acc[u][e]);
-                    }
-                }
+            for (int u = 0; u < DW_PIX; ++u) mac_vec<T, CG>(acc[u], xv[k][u], wv);
         }
     }
 #pragma unroll
@@ -180,6 +197,122 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const
         *(Vec *)(out + out_off[u]) = o;
     }
     }
+}
+
+// Taps that form a grid of up to 8 rows x S consecutive columns, on output columns that map to consecutive source
+// columns (stride 1 along the width): `tap[rr * S + ss]` is the tap at row offset row_off[rr], column offset w_min + ss.
+struct RowPlan {
+    int R, w_min;
+    short row_off[8];
+    unsigned char tap[kMaxTaps];
+};
+
+// The same computation for such launches with the DW_PIX outputs of a lane side by side in one output row: a source row
+// is loaded once for all of them (S + DW_PIX - 1 vectors instead of S * DW_PIX), which halves the traffic between the
+// caches and the CUs for a 3x3 filter.
+template <typename T, int CG, int S>
+__global__ __launch_bounds__(256) void depthwise_row_kernel(const IgemmArgs a, const RowPlan rp, const int iters)
+{
+    typedef typename DTraits<T>::Vec Vec;
+    constexpr int VEC = DTraits<T>::VEC;
+    constexpr int WPK = lds_words<T, CG>();
+    constexpr int NCOL = S + DW_PIX - 1;
+    extern __shared__ __attribute__((aligned(16))) unsigned wL[];   // [ntaps][C][WPK]
+    const int tid = threadIdx.x;
+    const int C = a.groups * CG, CV = C / VEC;
+    T *__restrict__ out = (T *)a.out;
+    stage_filter<T, CG>(a, wL, C);
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const int JG = (a.Mj + DW_PIX - 1) / DW_PIX;      // lanes per output row and channel vector
+    const long slots = (long)a.Nimg * a.Mi * JG;
+    for (int it = 0; it < iters; ++it) {
+        const long f = ((long)blockIdx.x * iters + it) * 256 + tid;
+        const int cv = (int)(f % CV);
+        const long slot = f / CV;
+        if (slot >= slots) break;
+        const int c0 = cv * VEC;
+        const int jg = (int)(slot % JG);
+        const long r = slot / JG;
+        const int i = (int)(r % a.Mi);
+        const int img = (int)(r / a.Mi);
+        const int j0 = jg * DW_PIX;
+        const int bh = i * a.mult_h + a.add_h, bw = j0 + a.add_w + rp.w_min;   // first source column of the lane
+        const long out_off = (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j0 * a.osw + a.ob)) * C + c0;
+        const long out_step = (long)a.osw * C;
+        float acc[DW_PIX][VEC];
+#pragma unroll
+        for (int u = 0; u < DW_PIX; ++u) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[u][e] = 0.f;
+            if (a.accumulate && j0 + u < a.Mj) {   // start from the old values: the sum is rounded to the storage type once
+                const Vec old = *(const Vec *)(out + out_off + u * out_step);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[u][e] = (float)old[e];
+            }
+        }
+        for (int rr = 0; rr < rp.R; ++rr) {
+            const int h = bh + rp.row_off[rr];
+            const bool row_ok = (unsigned)h < (unsigned)a.Hs;
+            const unsigned base = (unsigned)(((((long)img * a.Hs + h) * a.Ws + bw) * C + c0) * (long)sizeof(T));
+            u32x4 xv[NCOL];
+#pragma unroll
+            for (int k = 0; k < NCOL; ++k) {
+                const bool in = row_ok && (unsigned)(bw + k) < (unsigned)a.Ws;
+                xv[k] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                      rsrc, in ? base + (unsigned)(k * C * (int)sizeof(T)) : ~0u, 0, 0));
+            }
+#pragma unroll
+            for (int ss = 0; ss < S; ++ss) {
+                const int t = rp.tap[rr * S + ss];
+                unsigned wv[VEC * WPK];
+#pragma unroll
+                for (int e = 0; e < VEC * WPK; e += 4) {
+                    const u32x4 q = *(const u32x4 *)&wL[(t * C + c0) * WPK + e];
+                    wv[e] = q[0]; wv[e + 1] = q[1]; wv[e + 2] = q[2]; wv[e + 3] = q[3];
+                }
+#pragma unroll
+                for (int u = 0; u < DW_PIX; ++u) mac_vec<T, CG>(acc[u], xv[u + ss], wv);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < DW_PIX; ++u) {
+            if (j0 + u >= a.Mj) continue;
+            Vec o;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][e];
+            *(Vec *)(out + out_off + u * out_step) = o;
+        }
+    }
+}
+
+// Fills the plan if the launch's taps form such a grid (see RowPlan) with S = 3, 5 or 7 columns.
+bool row_plan(const IgemmArgs &a, RowPlan *rp)
+{
+    if (a.mult_w != 1 || a.ntaps < 3) return false;
+    int w_min = a.off_w[0], w_max = a.off_w[0];
+    for (int t = 1; t < a.ntaps; ++t) {
+        if (a.off_w[t] < w_min) w_min = a.off_w[t];
+        if (a.off_w[t] > w_max) w_max = a.off_w[t];
+    }
+    const int S = w_max - w_min + 1;
+    if ((S != 3 && S != 5 && S != 7) || a.ntaps % S != 0 || a.ntaps / S > 8) return false;
+    rp->R = 0;
+    rp->w_min = w_min;
+    bool seen[kMaxTaps] = {};
+    for (int t = 0; t < a.ntaps; ++t) {
+        int rr = 0;
+        while (rr < rp->R && rp->row_off[rr] != a.off_h[t]) ++rr;
+        if (rr == rp->R) {
+            if (rp->R == a.ntaps / S) return false;   // more distinct rows than a full grid has
+            rp->row_off[rp->R++] = a.off_h[t];
+        }
+        const int cell = rr * S + (a.off_w[t] - w_min);
+        if (seen[cell]) return false;
+        seen[cell] = true;
+        rp->tap[cell] = (unsigned char)t;
+    }
+    return rp->R * S == a.ntaps;   // every cell seen exactly once
 }
 
 // Taps per register chunk of the backward-weight kernel: a lane keeps taps x VEC x CG sums.
@@ -298,14 +431,25 @@ template <typename T, int CG> int launch_depthwise_typed(const IgemmArgs &a, hip
 {
     constexpr int VEC = DTraits<T>::VEC;
     const int C = a.groups * CG;
-    const long threads = ((long)a.M + DW_PIX - 1) / DW_PIX * (C / VEC);
+    RowPlan rp{};
+    const bool rows = getenv("NSK_DEPTHWISE_NO_ROWS") == nullptr && row_plan(a, &rp);   // the variable is a test hook
+    const int S = rows ? a.ntaps / rp.R : 0;
+    const long threads = rows ? (long)a.Nimg * a.Mi * ((a.Mj + DW_PIX - 1) / DW_PIX) * (C / VEC)
+                              : ((long)a.M + DW_PIX - 1) / DW_PIX * (C / VEC);
     const long runs = (threads + 255) / 256;
     // enough blocks to fill the chip several times over, each with as many runs as that leaves (at most 8)
     int iters = (int)(runs / 2048);
     iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
     const unsigned blocks = (unsigned)((runs + iters - 1) / iters);
     const size_t lds = (size_t)a.ntaps * C * lds_words<T, CG>() * sizeof(unsigned);
-    hipLaunchKernelGGL((depthwise_kernel<T, CG>), dim3(blocks), dim3(256), lds, stream, a, iters);
+    if (S == 3)
+        hipLaunchKernelGGL((depthwise_row_kernel<T, CG, 3>), dim3(blocks), dim3(256), lds, stream, a, rp, iters);
+    else if (S == 5)
+        hipLaunchKernelGGL((depthwise_row_kernel<T, CG, 5>), dim3(blocks), dim3(256), lds, stream, a, rp, iters);
+    else if (S == 7)
+        hipLaunchKernelGGL((depthwise_row_kernel<T, CG, 7>), dim3(blocks), dim3(256), lds, stream, a, rp, iters);
+    else
+        hipLaunchKernelGGL((depthwise_kernel<T, CG>), dim3(blocks), dim3(256), lds, stream, a, iters);
     return check_launch();
 }
 

@@ -32,8 +32,11 @@ GROUPED_SHAPES = [
     (2, 32, 9, 11, 32, 3, 3, 1, 1, 1, 16),        # two channels per group on both sides (direct kernels)
     (1, 64, 10, 8, 64, 5, 5, 1, 2, 1, 16),        # four channels per group, 5x5
     (2, 128, 12, 12, 128, 3, 3, 1, 1, 1, 32),     # the 32-group bottleneck shape at stride 1
+    (2, 32, 7, 23, 32, 3, 3, 1, 1, 1, 32),        # depthwise, output rows of 23 pixels (ragged groups of four)
+    (1, 16, 9, 10, 16, 5, 3, (2, 1), (2, 1), 1, 16),    # depthwise 5x3, stride 2 down the rows only
+    (2, 24, 10, 9, 24, 5, 5, 2, 2, 1, 24),        # depthwise 5x5 stride 2: backward-data classes of 3x3, 3x2, 2x3 and 2x2 taps
 ]
-DEPTHWISE = [2, 3, 10, 11, 12, 13, 14, 15, 16]     # shapes the direct kernels take
+DEPTHWISE = [2, 3, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19]     # shapes the direct kernels take
 
 
 def _case(i, dtype):
@@ -80,7 +83,7 @@ def test_grouped_conv_fwd_dgrad_wgrad(i, dtype, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12, 14, 15])
+@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12, 14, 15, 17, 18, 19])
 def test_grouped_conv_accumulate(i, dtype, layout):
     """accumulate = 1 adds the gradients to what the buffers hold (the paper's gradient accumulation)."""
     x, w, dy, st, pd, dl, G = _case(i, dtype)
@@ -106,6 +109,14 @@ def test_grouped_conv_accumulate(i, dtype, layout):
 def test_depthwise_shapes_on_the_generic_kernels(i, dtype, monkeypatch):
     """The direct depthwise kernels switched off: the same shapes through the generic grouped launch."""
     monkeypatch.setenv("NSK_NO_DEPTHWISE", "1")
+    test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", DEPTHWISE)
+def test_depthwise_shapes_on_the_per_tap_kernel(i, dtype, monkeypatch):
+    """The row-sharing variant of the direct kernels switched off (it takes the 3-, 5- and 7-wide filters otherwise)."""
+    monkeypatch.setenv("NSK_DEPTHWISE_NO_ROWS", "1")
     test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
 
