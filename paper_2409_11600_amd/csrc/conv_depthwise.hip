@@ -1,6 +1,6 @@
 // Depthwise convolution (a grouped convolution with one input and one output channel per group; the grouped entry
 // points of the library, not one of the paper's workloads): y[n][p][q][c] = sum over taps of x[n][h][w][c] * w[c][tap],
-// and its neighbours with two or four channels per group on both sides (template parameter CG), where an output channel
+// and its neighbours with two, four or (bf16) eight channels per group on both sides (template parameter CG), where an output channel
 // sums over the CG input channels of its group.
 // The contraction over channels is absent or tiny, so nothing here is GEMM-shaped: every pass reads each activation once from
 // HBM (the taps' re-reads hit the caches), does ntaps multiply-adds per element on the vector ALUs and is bound by
@@ -316,7 +316,7 @@ bool row_plan(const IgemmArgs &a, RowPlan *rp)
 }
 
 // Taps per register chunk of the backward-weight kernel: a lane keeps taps x VEC x CG sums.
-template <int CG> constexpr int wgrad_taps() { return CG == 1 ? 9 : (CG == 2 ? 5 : 3); }
+template <int CG> constexpr int wgrad_taps() { return CG == 1 ? 9 : (CG == 2 ? 5 : (CG == 4 ? 3 : 1)); }
 
 template <typename T, int CG>
 __global__ __launch_bounds__(256) void depthwise_wgrad_kernel(const WgradArgs a)
@@ -420,7 +420,8 @@ bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
 bool depthwise_applicable(int dtype, const IgemmArgs &a)
 {
     const int vec = dtype == NSK_BF16 ? 8 : 4, cg = a.Cs;
-    if (!(a.groups > 1 && (cg == 1 || cg == 2 || cg == 4) && a.Ngemm == cg)) return false;
+    // (eight channels per group fill a bf16 channel vector exactly; an fp32 vector holds four)
+    if (!(a.groups > 1 && (cg == 1 || cg == 2 || cg == 4 || (cg == 8 && dtype == NSK_BF16)) && a.Ngemm == cg)) return false;
     const int C = a.groups * cg;
     const long words = dtype == NSK_BF16 ? (cg + 1) / 2 : cg;
     return a.src_ld == C && a.Co == C && C % vec == 0 && (long)a.ntaps * C * words * 4 <= DW_LDS_MAX && a.ntaps >= 1 &&
@@ -458,6 +459,7 @@ int launch_depthwise(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (dtype == NSK_BF16) {
         if (a.Cs == 1) return launch_depthwise_typed<bf16_t, 1>(a, stream);
         if (a.Cs == 2) return launch_depthwise_typed<bf16_t, 2>(a, stream);
+        if (a.Cs == 8) return launch_depthwise_typed<bf16_t, 8>(a, stream);
         return launch_depthwise_typed<bf16_t, 4>(a, stream);
     }
     if (a.Cs == 1) return launch_depthwise_typed<float, 1>(a, stream);
@@ -468,7 +470,7 @@ int launch_depthwise(int dtype, const IgemmArgs &a, hipStream_t stream)
 bool depthwise_wgrad_applicable(int dtype, const WgradArgs &a)
 {
     const int vec = dtype == NSK_BF16 ? 8 : 4, cg = a.C;
-    if (!(a.groups > 1 && (cg == 1 || cg == 2 || cg == 4) && a.K == cg)) return false;
+    if (!(a.groups > 1 && (cg == 1 || cg == 2 || cg == 4 || (cg == 8 && dtype == NSK_BF16)) && a.K == cg)) return false;
     const int C = a.groups * cg;
     return a.ldx == C && a.ldy == C && C % vec == 0 && a.splits >= 1 && a.splits <= 65535 && aligned16(a.x) &&
            aligned16(a.dy);
@@ -486,6 +488,7 @@ int launch_depthwise_wgrad(int dtype, const WgradArgs &a, hipStream_t stream)
     if (dtype == NSK_BF16) {
         if (a.C == 1) return launch_depthwise_wgrad_typed<bf16_t, 1>(a, stream);
         if (a.C == 2) return launch_depthwise_wgrad_typed<bf16_t, 2>(a, stream);
+        if (a.C == 8) return launch_depthwise_wgrad_typed<bf16_t, 8>(a, stream);
         return launch_depthwise_wgrad_typed<bf16_t, 4>(a, stream);
     }
     if (a.C == 1) return launch_depthwise_wgrad_typed<float, 1>(a, stream);

@@ -19,6 +19,8 @@
 // consecutive channels) and lane i receives channel i of the four rows, i.e. four consecutive
 // positions of one channel; rows are padded to 192 bytes so that the four rows read by each of two
 // neighbouring 16-lane groups fall into eight different 32-byte bank groups of the 64-bank LDS.
+#include <stdlib.h>
+
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -349,7 +351,11 @@ int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block)
     const long long total = (long long)(a.H + 2) * (a.W + 2) * a.Nimg;
     int chunks = (int)((total + P - 1) / P);
     if (rows32_f32(dtype, a)) chunks = a.Nimg * (a.H / 2);   // row-aligned chunks of two image rows
-    const int grid = chunks < 256 ? chunks : 256;
+    int grid = chunks < 256 ? chunks : 256;
+    // Every block writes a whole [64][9][64] float partial (147 KB) that the reduction reads again, so a small problem
+    // is not spread over more blocks than gives each two chunks (measured, bf16 8x8 images, batch 256: 23.5 -> 18.8 us;
+    // fp32 chunks are half as long and lose)
+    if (dtype == NSK_BF16 && !rows32_f32(dtype, a) && chunks / 2 < grid) grid = chunks / 2 > 0 ? chunks / 2 : 1;
     const int cpb = (chunks + grid - 1) / grid;
     if (chunks_per_block) *chunks_per_block = cpb;
     return (chunks + cpb - 1) / cpb;

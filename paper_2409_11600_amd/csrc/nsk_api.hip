@@ -129,7 +129,7 @@ ConvPlan plan_conv(const ConvGeo &g, int pass, int groups = 1)
             p.rows_per_split = wgrad_wide_rows_per_split(wa, &p.splits);
         else
             p.rows_per_split = wgrad_rows_per_split(g.dtype, g.N * g.P * g.Q, g.K, g.R * g.S * (g.C / groups), &p.splits);
-        if (groups > 1 && g.C == g.K && (g.C == groups || g.C == 2 * groups || g.C == 4 * groups)) {
+        if (groups > 1 && g.C == g.K && (g.C == groups || g.C == 2 * groups || g.C == 4 * groups || g.C == 8 * groups)) {
             // depthwise and its neighbours: the direct kernel runs blocks of 16 channel vectors x one split and wants
             // about four per CU
             const int vec = g.dtype == NSK_BF16 ? 8 : 4, L = g.N * g.P * g.Q;
