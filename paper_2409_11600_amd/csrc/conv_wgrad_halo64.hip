@@ -48,8 +48,11 @@ template <> struct WH<bf16_t> {
     static constexpr int P = 128, ROW = 192, VPP = 8, FRAG_COL = 64;
 };
 
-template <typename T>
-__global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
+// SPLIT: eight wavefronts with split roles.  Wavefronts 0-3 only multiply; wavefronts 4-7 only move data: while chunk c
+// is multiplied out of one LDS buffer they load chunk c + 1 and write it to the other, so staging (global loads, LDS
+// writes, the address arithmetic) no longer sits between two runs of MFMAs of the same wavefront.  One barrier per chunk.
+template <typename T, bool SPLIT>
+__global__ __launch_bounds__(SPLIT ? 512 : 256) void wgrad_halo64_kernel(const WHArgs a)
 {
     typedef WH<T> C;
     constexpr bool F32 = sizeof(T) == 4;
@@ -60,7 +63,8 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     unsigned *in_tab = (unsigned *)(smem + 2 * BUF);  // [2][XMAX]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;   // index within the role
+    const bool mover = SPLIT && threadIdx.x >= 256;
     const int frow = lane & 31, fk = lane >> 5;
     const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.x, 0, a.bytes, 0x00020000);
     const __amdgpu_buffer_rsrc_t dy_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.dy, 0, a.bytes, 0x00020000);
@@ -97,6 +101,22 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
             stage[XL + u] = __builtin_amdgcn_raw_buffer_load_b128(dy_rsrc, off == WH_OOB ? WH_OOB : off + v * 16, 0, 0);
         }
     };
+    // the same loads with every lane computing its own source offsets (the moving wavefronts have the time, and
+    // no table means no barrier among them)
+    auto issue_loads_direct = [&](int chunk) {
+#pragma unroll
+        for (int u = 0; u < XL; ++u) {
+            const int idx = tid + 256 * u, pos = idx / VPP, v = idx % VPP;
+            const unsigned off = pos < xn ? src_offset(chunk * P - a.halo + pos) : WH_OOB;
+            stage[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off == WH_OOB ? WH_OOB : off + v * 16, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < DL; ++u) {
+            const int idx = tid + 256 * u, pos = idx / VPP, v = idx % VPP;
+            const unsigned off = src_offset(chunk * P + pos);
+            stage[XL + u] = __builtin_amdgcn_raw_buffer_load_b128(dy_rsrc, off == WH_OOB ? WH_OOB : off + v * 16, 0, 0);
+        }
+    };
     auto write_stage = [&](unsigned char *buf) {
 #pragma unroll
         for (int u = 0; u < XL; ++u) {
@@ -109,6 +129,28 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
             *(u32x4 *)(buf + (XMAX + pos) * ROW + v * 16) = stage[XL + u];
         }
     };
+
+    const int c_begin = blockIdx.x * a.chunks_per_block;
+    const int c_end = min(a.chunks, c_begin + a.chunks_per_block);
+    if (mover) {
+        // The moving wavefronts' whole life (kept apart from the multiplying code so that the accumulators are not live
+        // here): one barrier after the first chunk is in place, one at the end of every chunk, as on the other side.
+        if (c_begin < c_end) {
+            issue_loads_direct(c_begin);
+            write_stage(smem);
+            __syncthreads();
+        }
+        for (int c = c_begin; c < c_end; ++c) {
+            const int cur = (c - c_begin) & 1;
+            // the other buffer was last read before the barrier that ended the previous chunk
+            if (c + 1 < c_end) {
+                issue_loads_direct(c + 1);
+                write_stage(smem + (cur ^ 1) * BUF);
+            }
+            __syncthreads();
+        }
+        return;
+    }
 
     // column tiles of this wavefront: nf = wave + 4*ni (tap = nf/2, channel half = nf%2); the fifth
     // one of wavefronts 2 and 3 does not exist: it computes on tap 0 and is never stored.
@@ -138,9 +180,9 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[mi][ni][v] = 0.f;
 
-    const int c_begin = blockIdx.x * a.chunks_per_block;
-    const int c_end = min(a.chunks, c_begin + a.chunks_per_block);
-    if (c_begin < c_end) {
+    if (SPLIT) {
+        if (c_begin < c_end) __syncthreads();   // the first chunk is in place
+    } else if (c_begin < c_end) {
         fill_tab(c_begin, 0);
         __syncthreads();
         issue_loads(0);
@@ -148,10 +190,12 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
     for (int c = c_begin; c < c_end; ++c) {
         const int cur = (c - c_begin) & 1;
         unsigned char *buf = smem + cur * BUF;
-        write_stage(buf);
-        if (c + 1 < c_end) fill_tab(c + 1, cur ^ 1);
-        __syncthreads();
-        if (c + 1 < c_end) issue_loads(cur ^ 1);   // lands in registers while this chunk is computed
+        if (!SPLIT) {
+            write_stage(buf);
+            if (c + 1 < c_end) fill_tab(c + 1, cur ^ 1);
+            __syncthreads();
+            if (c + 1 < c_end) issue_loads(cur ^ 1);   // lands in registers while this chunk is computed
+        }
 
         const unsigned char *xb = buf + lane_off;
         const unsigned char *db = buf + XMAX * ROW + lane_off;
@@ -203,6 +247,7 @@ __global__ __launch_bounds__(256) void wgrad_halo64_kernel(const WHArgs a)
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
+        if (SPLIT) __syncthreads();   // the chunk is consumed and the next one is in place
     }
 
     // acc[mi][ni][v]: row k = 32*mi + 8*(v/4) + 4*(lane/32) + v%4, column c = 32*half + lane%32
@@ -399,10 +444,16 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &g, hipStream_t stream)
     for (int t = 0; t < 9; ++t) a.tapoff[t] = (t / 3 - 1) * a.PW + (t % 3 - 1);
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<float>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<float, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            smem_bytes<float>());
         if (e == hipSuccess)
-            e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<bf16_t>, hipFuncAttributeMaxDynamicSharedMemorySize,
+            e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<bf16_t, false>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    smem_bytes<bf16_t>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<float, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    smem_bytes<float>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)wgrad_halo64_kernel<bf16_t, true>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                     smem_bytes<bf16_t>());
         if (e != hipSuccess) {
             set_last_hip_error(e);
@@ -410,10 +461,18 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &g, hipStream_t stream)
         }
         attr_set = true;
     }
-    if (dtype == NSK_BF16)
-        hipLaunchKernelGGL(wgrad_halo64_kernel<bf16_t>, dim3(blocks), dim3(256), smem_bytes<bf16_t>(), stream, a);
-    else
-        hipLaunchKernelGGL(wgrad_halo64_kernel<float>, dim3(blocks), dim3(256), smem_bytes<float>(), stream, a);
+    const bool split = getenv("NSK_WH_NO_SPLIT") == nullptr;   // the variable is an A/B and test hook
+    if (dtype == NSK_BF16) {
+        if (split)
+            hipLaunchKernelGGL((wgrad_halo64_kernel<bf16_t, true>), dim3(blocks), dim3(512), smem_bytes<bf16_t>(), stream, a);
+        else
+            hipLaunchKernelGGL((wgrad_halo64_kernel<bf16_t, false>), dim3(blocks), dim3(256), smem_bytes<bf16_t>(), stream, a);
+    } else {
+        if (split)
+            hipLaunchKernelGGL((wgrad_halo64_kernel<float, true>), dim3(blocks), dim3(512), smem_bytes<float>(), stream, a);
+        else
+            hipLaunchKernelGGL((wgrad_halo64_kernel<float, false>), dim3(blocks), dim3(256), smem_bytes<float>(), stream, a);
+    }
     return check_launch();
 }
 

@@ -359,6 +359,30 @@ def test_conv_gradients_accumulate(i, dtype, layout):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_halo_backward_weight_many_chunks_per_block(dtype, monkeypatch):
+    """3x3 64->64 backward-weight on enough positions that every block of the halo kernel walks several chunks (the
+    double-buffered hand-over between its moving and its multiplying wavefronts), against the oracle; the variant
+    without split roles must give the same bits."""
+    N, C, H, W, K = 8, 64, 46, 46, 64
+    print(f"halo backward-weight, many chunks: {(N, C, H, W, K)} {dtype}", flush=True)
+    x = on_grid(gen.normal(880, 0, (N, C, H, W)), dtype)
+    dy = on_grid(gen.normal(880, 2, (N, K, H, W)), dtype)
+    layout = B.NSK_NHWC
+    ws = B.Workspace()
+    gx, gdy = to_gpu(x, dtype, layout), to_gpu(dy, dtype, layout)
+    dw_view, dw_check = guarded((K, 3, 3, C), torch.float32)
+    B.conv2d_wgrad(gx, gdy, (K, C, 3, 3), 1, 1, 1, layout, out=dw_view, ws=ws)
+    torch.cuda.synchronize()
+    dw_check()
+    want = oracle.conv2d_wgrad(x, dy, (K, C, 3, 3), 1, 1, 1)
+    assert max_rel_err(to_host(dw_view, layout), want) <= TOL["f32"] * 10   # fp32 sums of exact products
+    monkeypatch.setenv("NSK_WH_NO_SPLIT", "1")
+    plain = B.conv2d_wgrad(gx, gdy, (K, C, 3, 3), 1, 1, 1, layout, ws=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(plain, dw_view)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_conv_is_bitwise_reproducible(dtype):
     x, w, dy, st, pd, dl = _conv_case(1, dtype)
     ws = B.Workspace()
