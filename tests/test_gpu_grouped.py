@@ -37,8 +37,10 @@ GROUPED_SHAPES = [
     (2, 24, 10, 9, 24, 5, 5, 2, 2, 1, 24),        # depthwise 5x5 stride 2: backward-data classes of 3x3, 3x2, 2x3 and 2x2 taps
     (2, 64, 11, 10, 64, 3, 3, 1, 1, 1, 8),        # eight channels per group (direct kernels in bf16, generic in fp32)
     (2, 32, 9, 9, 32, 3, 3, 2, 1, 1, 4),          # the same at stride 2
+    (1, 160, 8, 9, 160, 3, 3, 1, 1, 1, 40),       # four channels per group, 160 channels: three blocks of output channels, the last half empty
+    (1, 72, 7, 7, 72, 5, 5, 1, 2, 1, 36),         # two channels per group, 25 taps (five register chunks in backward-weight)
 ]
-DEPTHWISE = [2, 3, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21]     # shapes the direct kernels take
+DEPTHWISE = [2, 3, 10, 11, 12, 13, 14, 15, 16, 17, 18, 19, 20, 21, 22, 23]     # shapes the direct kernels take
 
 
 def _case(i, dtype):
@@ -85,7 +87,7 @@ def test_grouped_conv_fwd_dgrad_wgrad(i, dtype, layout):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12, 14, 15, 17, 18, 19, 20, 21])
+@pytest.mark.parametrize("i", [0, 2, 4, 7, 10, 11, 12, 14, 15, 17, 18, 19, 20, 21, 22, 23])
 def test_grouped_conv_accumulate(i, dtype, layout):
     """accumulate = 1 adds the gradients to what the buffers hold (the paper's gradient accumulation)."""
     x, w, dy, st, pd, dl, G = _case(i, dtype)
