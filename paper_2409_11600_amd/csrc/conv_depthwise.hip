@@ -315,6 +315,122 @@ bool row_plan(const IgemmArgs &a, RowPlan *rp)
     return rp->R * S == a.ntaps;   // every cell seen exactly once
 }
 
+// The transposed arrangement: taps in a grid of R consecutive ROWS (height stride 1) x up to 8 columns, and the DW_PIX
+// outputs of a lane stacked in one output COLUMN.  Consecutive lanes then hold consecutive channel vectors of consecutive
+// pixels of a row, so every load of a wavefront covers one contiguous kilobyte (the row-sharing kernel's loads cover four
+// pieces a kilobyte apart), and a source column piece is still loaded once for all of a lane's outputs.
+// `tap[ss * R + rr]` is the tap at column offset col_off[ss], row offset h_min + rr.
+struct ColPlan {
+    int S, h_min;
+    short col_off[8];
+    unsigned char tap[kMaxTaps];
+};
+
+template <typename T, int CG, int R>
+__global__ __launch_bounds__(256) void depthwise_col_kernel(const IgemmArgs a, const ColPlan cp, const int iters)
+{
+    typedef typename DTraits<T>::Vec Vec;
+    constexpr int VEC = DTraits<T>::VEC;
+    constexpr int WPK = lds_words<T, CG>();
+    constexpr int NROW = R + DW_PIX - 1;
+    extern __shared__ __attribute__((aligned(16))) unsigned wL[];   // [ntaps][C][WPK]
+    const int tid = threadIdx.x;
+    const int C = a.groups * CG, CV = C / VEC;
+    T *__restrict__ out = (T *)a.out;
+    stage_filter<T, CG>(a, wL, C);
+    __syncthreads();
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const int IG = (a.Mi + DW_PIX - 1) / DW_PIX;      // groups of output rows
+    const long slots = (long)a.Nimg * IG * a.Mj;       // (image, row group, column): the column runs fastest
+    for (int it = 0; it < iters; ++it) {
+        const long f = ((long)blockIdx.x * iters + it) * 256 + tid;
+        const int cv = (int)(f % CV);
+        const long slot = f / CV;
+        if (slot >= slots) break;
+        const int c0 = cv * VEC;
+        const int j = (int)(slot % a.Mj);
+        const long r = slot / a.Mj;
+        const int ig = (int)(r % IG);
+        const int img = (int)(r / IG);
+        const int i0 = ig * DW_PIX;
+        const int bh = i0 + a.add_h + cp.h_min, bw = j * a.mult_w + a.add_w;   // first source row of the lane
+        const long out_off = (((long)img * a.Ho + (i0 * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * C + c0;
+        const long out_step = (long)a.osh * a.Wo * C;
+        float acc[DW_PIX][VEC];
+#pragma unroll
+        for (int u = 0; u < DW_PIX; ++u) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[u][e] = 0.f;
+            if (a.accumulate && i0 + u < a.Mi) {   // start from the old values: the sum is rounded to the storage type once
+                const Vec old = *(const Vec *)(out + out_off + u * out_step);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[u][e] = (float)old[e];
+            }
+        }
+        for (int ss = 0; ss < cp.S; ++ss) {
+            const int w = bw + cp.col_off[ss];
+            const bool col_ok = (unsigned)w < (unsigned)a.Ws;
+            const unsigned base = (unsigned)(((((long)img * a.Hs + bh) * a.Ws + w) * C + c0) * (long)sizeof(T));
+            u32x4 xv[NROW];
+#pragma unroll
+            for (int k = 0; k < NROW; ++k) {
+                const bool in = col_ok && (unsigned)(bh + k) < (unsigned)a.Hs;
+                xv[k] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                                                      rsrc, in ? base + (unsigned)(k * a.Ws * C * (int)sizeof(T)) : ~0u, 0, 0));
+            }
+#pragma unroll
+            for (int rr = 0; rr < R; ++rr) {
+                const int t = cp.tap[ss * R + rr];
+                unsigned wv[VEC * WPK];
+#pragma unroll
+                for (int e = 0; e < VEC * WPK; e += 4) {
+                    const u32x4 q = *(const u32x4 *)&wL[(t * C + c0) * WPK + e];
+                    wv[e] = q[0]; wv[e + 1] = q[1]; wv[e + 2] = q[2]; wv[e + 3] = q[3];
+                }
+#pragma unroll
+                for (int u = 0; u < DW_PIX; ++u) mac_vec<T, CG>(acc[u], xv[u + rr], wv);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < DW_PIX; ++u) {
+            if (i0 + u >= a.Mi) continue;
+            Vec o;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][e];
+            *(Vec *)(out + out_off + u * out_step) = o;
+        }
+    }
+}
+
+// Fills the plan if the launch's taps form such a grid (see ColPlan) with R = 3, 5 or 7 rows.
+bool col_plan(const IgemmArgs &a, ColPlan *cp)
+{
+    if (a.mult_h != 1 || a.ntaps < 3) return false;
+    int h_min = a.off_h[0], h_max = a.off_h[0];
+    for (int t = 1; t < a.ntaps; ++t) {
+        if (a.off_h[t] < h_min) h_min = a.off_h[t];
+        if (a.off_h[t] > h_max) h_max = a.off_h[t];
+    }
+    const int R = h_max - h_min + 1;
+    if ((R != 3 && R != 5 && R != 7) || a.ntaps % R != 0 || a.ntaps / R > 8) return false;
+    cp->S = 0;
+    cp->h_min = h_min;
+    bool seen[kMaxTaps] = {};
+    for (int t = 0; t < a.ntaps; ++t) {
+        int ss = 0;
+        while (ss < cp->S && cp->col_off[ss] != a.off_w[t]) ++ss;
+        if (ss == cp->S) {
+            if (cp->S == a.ntaps / R) return false;   // more distinct columns than a full grid has
+            cp->col_off[cp->S++] = a.off_w[t];
+        }
+        const int cell = ss * R + (a.off_h[t] - h_min);
+        if (seen[cell]) return false;
+        seen[cell] = true;
+        cp->tap[cell] = (unsigned char)t;
+    }
+    return cp->S * R == a.ntaps;   // every cell seen exactly once
+}
+
 // Taps per register chunk of the backward-weight kernel: a lane keeps taps x VEC x CG sums.
 template <int CG> constexpr int wgrad_taps() { return CG == 1 ? 9 : (CG == 2 ? 5 : (CG == 4 ? 3 : 1)); }
 
@@ -433,17 +549,27 @@ template <typename T, int CG> int launch_depthwise_typed(const IgemmArgs &a, hip
     constexpr int VEC = DTraits<T>::VEC;
     const int C = a.groups * CG;
     RowPlan rp{};
-    const bool rows = getenv("NSK_DEPTHWISE_NO_ROWS") == nullptr && row_plan(a, &rp);   // the variable is a test hook
-    const int S = rows ? a.ntaps / rp.R : 0;
-    const long threads = rows ? (long)a.Nimg * a.Mi * ((a.Mj + DW_PIX - 1) / DW_PIX) * (C / VEC)
-                              : ((long)a.M + DW_PIX - 1) / DW_PIX * (C / VEC);
+    ColPlan cp{};
+    // the variables are test hooks; the column arrangement is preferred (contiguous loads)
+    const bool cols = getenv("NSK_DEPTHWISE_NO_COLS") == nullptr && getenv("NSK_DEPTHWISE_NO_ROWS") == nullptr && col_plan(a, &cp);
+    const bool rows = !cols && getenv("NSK_DEPTHWISE_NO_ROWS") == nullptr && row_plan(a, &rp);
+    const int S = rows ? a.ntaps / rp.R : 0, R = cols ? a.ntaps / cp.S : 0;
+    const long threads = cols   ? (long)a.Nimg * ((a.Mi + DW_PIX - 1) / DW_PIX) * a.Mj * (C / VEC)
+                         : rows ? (long)a.Nimg * a.Mi * ((a.Mj + DW_PIX - 1) / DW_PIX) * (C / VEC)
+                                : ((long)a.M + DW_PIX - 1) / DW_PIX * (C / VEC);
     const long runs = (threads + 255) / 256;
     // enough blocks to fill the chip several times over, each with as many runs as that leaves (at most 8)
     int iters = (int)(runs / 2048);
     iters = iters < 1 ? 1 : (iters > 8 ? 8 : iters);
     const unsigned blocks = (unsigned)((runs + iters - 1) / iters);
     const size_t lds = (size_t)a.ntaps * C * lds_words<T, CG>() * sizeof(unsigned);
-    if (S == 3)
+    if (R == 3)
+        hipLaunchKernelGGL((depthwise_col_kernel<T, CG, 3>), dim3(blocks), dim3(256), lds, stream, a, cp, iters);
+    else if (R == 5)
+        hipLaunchKernelGGL((depthwise_col_kernel<T, CG, 5>), dim3(blocks), dim3(256), lds, stream, a, cp, iters);
+    else if (R == 7)
+        hipLaunchKernelGGL((depthwise_col_kernel<T, CG, 7>), dim3(blocks), dim3(256), lds, stream, a, cp, iters);
+    else if (S == 3)
         hipLaunchKernelGGL((depthwise_row_kernel<T, CG, 3>), dim3(blocks), dim3(256), lds, stream, a, rp, iters);
     else if (S == 5)
         hipLaunchKernelGGL((depthwise_row_kernel<T, CG, 5>), dim3(blocks), dim3(256), lds, stream, a, rp, iters);

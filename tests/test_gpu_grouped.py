@@ -119,8 +119,16 @@ def test_depthwise_shapes_on_the_generic_kernels(i, dtype, monkeypatch):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", DEPTHWISE)
 def test_depthwise_shapes_on_the_per_tap_kernel(i, dtype, monkeypatch):
-    """The row-sharing variant of the direct kernels switched off (it takes the 3-, 5- and 7-wide filters otherwise)."""
+    """The load-sharing variants of the direct kernels switched off (they take the 3-, 5- and 7-tap-wide or -high filters otherwise)."""
     monkeypatch.setenv("NSK_DEPTHWISE_NO_ROWS", "1")
+    test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", DEPTHWISE)
+def test_depthwise_shapes_on_the_row_sharing_kernel(i, dtype, monkeypatch):
+    """The column-stacked variant switched off: the row-sharing one takes the shapes it can."""
+    monkeypatch.setenv("NSK_DEPTHWISE_NO_COLS", "1")
     test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
 
