@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void depthwise_kernel(const IgemmArgs a, const
         Vec o;
 #pragma unroll
         for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][e];
-        *(Vec *)(out + out_off[u]) = o;
+        __builtin_nontemporal_store(o, (Vec *)(out + out_off[u]));   // the output is not read again: keep the caches for the input
     }
     }
 }
@@ -281,7 +281,7 @@ __global__ __launch_bounds__(256) void depthwise_row_kernel(const IgemmArgs a, c
             Vec o;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][e];
-            *(Vec *)(out + out_off + u * out_step) = o;
+            __builtin_nontemporal_store(o, (Vec *)(out + out_off + u * out_step));
         }
     }
 }
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(256) void depthwise_col_kernel(const IgemmArgs a, c
             Vec o;
 #pragma unroll
             for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][e];
-            *(Vec *)(out + out_off + u * out_step) = o;
+            __builtin_nontemporal_store(o, (Vec *)(out + out_off + u * out_step));
         }
     }
 }
