@@ -3,6 +3,8 @@
 // Forward records, per output, the window position r*S+s of the FIRST maximum in row-major order;
 // backward is a gather over the (at most ceil(R/sh)*ceil(S/sw)) windows that contain an input
 // element, so no atomics are needed and the result is reproducible.
+#include <stdlib.h>
+
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -108,6 +110,73 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T *__restrict__ 
     } else {
         y[o] = (T)best[0];
         idx[o] = (signed char)where[0];
+    }
+}
+
+// 3x3 windows on vectorised NHWC tensors (the pool of the large-image stem): the nine loads of a lane go through a
+// buffer descriptor (an offset of ~0 is out of range: no branch per tap), so they are all in flight before the first
+// comparison; the comparisons run in the same order as in the general kernel (first maximum wins, padding never does).
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void maxpool3_fwd_nhwc_kernel(const T *__restrict__ x, T *__restrict__ y,
+                                                                signed char *__restrict__ idx, const PoolGeom g,
+                                                                const unsigned x_bytes)
+{
+    typedef T Vec __attribute__((ext_vector_type(VEC)));
+    static_assert(sizeof(Vec) == 16, "one 16-byte load per tap");
+    const int CV = g.C / VEC;
+    const long total = (long)g.N * g.P * g.Q * CV;
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int c = (int)(i % CV) * VEC;
+    long r_ = i / CV;
+    const int q = (int)(r_ % g.Q);
+    r_ /= g.Q;
+    const int p = (int)(r_ % g.P), n = (int)(r_ / g.P);
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)x, 0, x_bytes, 0x00020000);
+    const int h0 = p * g.sh - g.ph, w0 = q * g.sw - g.pw;
+    Vec v[9];
+    bool ok[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        const int h = h0 + t / 3, w = w0 + t % 3;
+        ok[t] = (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+        const unsigned off = (unsigned)(((((long)n * g.H + h) * g.W + w) * g.C + c) * (long)sizeof(T));
+        v[t] = __builtin_bit_cast(Vec, __builtin_amdgcn_raw_buffer_load_b128(rsrc, ok[t] ? off : ~0u, 0, 0));
+    }
+    float best[VEC];
+    int where[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+        best[e] = -INFINITY;
+        where[e] = -1;
+    }
+#pragma unroll
+    for (int t = 0; t < 9; ++t) {
+        if (!ok[t]) continue;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const float f = (float)v[t][e];
+            if (where[e] < 0 || f > best[e]) {
+                best[e] = f;
+                where[e] = t;
+            }
+        }
+    }
+    const long o = (((long)n * g.P + p) * g.Q + q) * g.C + c;
+    Vec yv;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) yv[e] = (T)best[e];
+    __builtin_nontemporal_store(yv, (Vec *)(y + o));
+    if constexpr (VEC == 8) {
+        unsigned long long iv = 0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) iv |= (unsigned long long)(unsigned char)(signed char)where[e] << (8 * e);
+        __builtin_nontemporal_store(iv, (unsigned long long *)(idx + o));
+    } else {
+        unsigned iv = 0;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) iv |= (unsigned)(unsigned char)(signed char)where[e] << (8 * e);
+        __builtin_nontemporal_store(iv, (unsigned *)(idx + o));
     }
 }
 
@@ -264,7 +333,11 @@ int pool_typed(bool fwd, const nsk_pool_desc_t &d, int P, int Q, const void *a, 
     if (total == 0) return NSK_OK;
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (fwd) {
-        if (vec)
+        const unsigned long long x_bytes = (unsigned long long)d.N * d.H * d.W * d.C * sizeof(T);
+        if (vec && d.R == 3 && d.S == 3 && x_bytes < 0xF0000000ull && getenv("NSK_POOL_GENERAL") == nullptr)   // (test hook)
+            hipLaunchKernelGGL((maxpool3_fwd_nhwc_kernel<T, VEC>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g,
+                               (unsigned)x_bytes);
+        else if (vec)
             hipLaunchKernelGGL((maxpool_fwd_kernel<T, VEC, false>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g);
         else if (d.layout == NSK_NCHW)
             hipLaunchKernelGGL((maxpool_fwd_kernel<T, 1, true>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g);

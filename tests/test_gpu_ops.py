@@ -581,3 +581,12 @@ def test_maxpool_fwd_bwd(i, dtype, layout):
     dx = B.maxpool2d_bwd(to_gpu(dy, dtype, layout), idx, shape, 3, 2, 1, layout)
     torch.cuda.synchronize()
     assert max_rel_err(to_host(dx, layout), oracle.maxpool2d_bwd(dy, widx, shape, 3, 2, 1)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", [0, 1, 3])
+def test_maxpool_3x3_on_the_general_kernel(i, dtype, monkeypatch):
+    """The 3x3 fast path of the forward pool switched off: the general kernel must give the same bits."""
+    monkeypatch.setenv("NSK_POOL_GENERAL", "1")
+    test_maxpool_fwd_bwd(i, dtype, B.NSK_NHWC)
+
