@@ -425,6 +425,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     // the same order of tests as launch_igemm
     if (a.M <= 0 || a.Ngemm <= 0 || a.accumulate) return 0;
     if (forced_tile() != 0 || a.groups > 1) return 0;
+    if (tiny_src_applicable(dtype, a) || tiny_out_applicable(dtype, a)) return 0;   // no statistics epilogue there
     if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
     if (halo64_f32_applicable(dtype, a)) return halo64_f32_stats_rows(a);
     if (conv_pw_applicable(dtype, a)) return conv_pw_stats_rows(a);
@@ -449,6 +450,8 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (grouped && (a.groups > 65535 || a.src_ld != a.groups * a.Cs || a.zero_cell || a.stats)) return NSK_ERR_BAD_DESC;
     if (a.zero_cell) return launch_conv_pw(a, stream);   // the caller has checked that this kernel applies
     const bool special = forced_tile() == 0 && !grouped;
+    if (special && tiny_src_applicable(dtype, a)) return launch_tiny_src(dtype, a, stream);
+    if (special && tiny_out_applicable(dtype, a)) return launch_tiny_out(dtype, a, stream);
     if (special && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
     if (special && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
     if (special && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);

@@ -1,0 +1,326 @@
+// Convolution layers with at most four channels on one side and 8..64 on the other: the stride-1 image stem of the
+// small-image residual network the paper trains on CIFAR-10 (3 -> 16 channels, section "Experiments and Discussion").
+// A 3-channel pixel is 6 bytes, so the implicit-GEMM kernels can only gather it element by element into tiles that
+// are mostly padding (24 / 26 / 52 us for a layer whose tensors stream in 3 us).  There is next to no arithmetic
+// here (432 multiply-adds per pixel), so the three passes are direct kernels on the vector ALUs, bound by memory:
+//   * forward (few source channels): a lane owns one output pixel and all its NG output channels; the filter lies in
+//     LDS as floats [tap][source channel][NG] and is read by broadcast;
+//   * backward-data (few output channels): a lane owns one output pixel, loads the CS source channels of each tap's
+//     pixel with 16-byte loads and multiplies them with the filter rows [tap][output channel][CS] from LDS;
+//   * backward-weight: a lane owns one (tap, input channel) column of dw for all K output channels; the 32 column
+//     lanes of a pixel lane read the same dy vector (broadcast) and their own x element; eight pixel lanes per block
+//     are combined through LDS in a fixed order.  Partial sums in the layout of the generic split kernel.
+// Forward and backward-data take the argument set of the implicit-GEMM kernels (taps as offsets around a base pixel,
+// strided output grid), so stride classes, padding, dilation and `accumulate` come for free.
+#include <stdlib.h>
+
+#include "nsk_internal.h"
+
+namespace nsk {
+namespace {
+
+constexpr int TINY_MAX_C = 4;        // channels on the narrow side
+constexpr int TINY_LDS_MAX = 48 << 10;
+
+__device__ inline float tf(float v) { return v; }
+__device__ inline float tf(bf16_t v) { return (float)v; }
+
+// ---------------------------------------------------------------- forward: Cs <= 4 source channels, NG output channels
+template <typename T, int NG>
+__global__ __launch_bounds__(256) void tiny_src_kernel(const IgemmArgs a)
+{
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef T Vec __attribute__((ext_vector_type(VEC)));
+    extern __shared__ __attribute__((aligned(16))) float wL[];   // [ntaps * Cs][NG]
+    __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
+    const int tid = threadIdx.x, Cs = a.Cs, Ktot = a.Ktot;
+    const T *__restrict__ src = (const T *)a.src;
+    const T *__restrict__ wpk = (const T *)a.wpk;   // [NG][Ktot]
+    T *__restrict__ out = (T *)a.out;
+    for (int i = tid; i < Ktot * NG; i += 256) {
+        const int n = i / Ktot, k = i - n * Ktot;
+        wL[k * NG + n] = tf(wpk[i]);
+    }
+    if (tid < kMaxTaps) {
+        s_offh[tid] = a.off_h[tid];
+        s_offw[tid] = a.off_w[tid];
+    }
+    __syncthreads();
+    const int m = blockIdx.x * 256 + tid;
+    if (m >= a.M) return;
+    const int per_img = a.Mi * a.Mj;
+    const int img = m / per_img;
+    const int rem = m - img * per_img;
+    const int i = rem / a.Mj;
+    const int j = rem - i * a.Mj;
+    const int bh = i * a.mult_h + a.add_h, bw = j * a.mult_w + a.add_w;
+    const long out_off = (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co;
+    float acc[NG];
+#pragma unroll
+    for (int n = 0; n < NG; ++n) acc[n] = 0.f;
+    if (a.accumulate) {   // start from the old values: the sum is rounded to the storage type once
+#pragma unroll
+        for (int v = 0; v < NG / VEC; ++v) {
+            const Vec old = *(const Vec *)(out + out_off + v * VEC);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[v * VEC + e] = tf(old[e]);
+        }
+    }
+    // Every load is unconditional (coordinates clamped into the image, the value masked afterwards), so the loads of
+    // several taps are in flight together instead of one dependent load per branch.
+#pragma unroll 3
+    for (int t = 0; t < a.ntaps; ++t) {
+        const int h = bh + s_offh[t], w = bw + s_offw[t];
+        const bool in = (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
+        const int hc = min(max(h, 0), a.Hs - 1), wc = min(max(w, 0), a.Ws - 1);
+        const T *px = src + (((long)img * a.Hs + hc) * a.Ws + wc) * Cs;
+        float xv[TINY_MAX_C];
+#pragma unroll
+        for (int c = 0; c < TINY_MAX_C; ++c) {
+            const float v = tf(px[min(c, Cs - 1)]);
+            xv[c] = (in && c < Cs) ? v : 0.f;
+        }
+#pragma unroll
+        for (int c = 0; c < TINY_MAX_C; ++c) {
+            if (c >= Cs) break;   // uniform
+            const float *wr = wL + (t * Cs + c) * NG;
+#pragma unroll
+            for (int n = 0; n < NG; n += 4) {
+                const f32x4 q = *(const f32x4 *)(wr + n);
+                acc[n] += xv[c] * q[0];
+                acc[n + 1] += xv[c] * q[1];
+                acc[n + 2] += xv[c] * q[2];
+                acc[n + 3] += xv[c] * q[3];
+            }
+        }
+    }
+#pragma unroll
+    for (int v = 0; v < NG / VEC; ++v) {
+        Vec o;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) o[e] = (T)acc[v * VEC + e];
+        *(Vec *)(out + out_off + v * VEC) = o;
+    }
+}
+
+// ---------------------------------------------------------------- backward-data: CS source channels, Ngemm <= 4 outputs
+template <typename T, int CS>
+__global__ __launch_bounds__(256) void tiny_out_kernel(const IgemmArgs a)
+{
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef T Vec __attribute__((ext_vector_type(VEC)));
+    extern __shared__ __attribute__((aligned(16))) float wL[];   // [ntaps][TINY_MAX_C][CS], rows n >= Ngemm are zero
+    __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
+    const int tid = threadIdx.x, NO = a.Ngemm;
+    const T *__restrict__ src = (const T *)a.src;
+    const T *__restrict__ wpk = (const T *)a.wpk;   // [NO][ntaps][CS]
+    T *__restrict__ out = (T *)a.out;
+    for (int i = tid; i < a.ntaps * TINY_MAX_C * CS; i += 256) {
+        const int c = i % CS, r = i / CS;
+        const int n = r % TINY_MAX_C, t = r / TINY_MAX_C;
+        wL[i] = n < NO ? tf(wpk[((long)n * a.ntaps + t) * CS + c]) : 0.f;
+    }
+    if (tid < kMaxTaps) {
+        s_offh[tid] = a.off_h[tid];
+        s_offw[tid] = a.off_w[tid];
+    }
+    __syncthreads();
+    const int m = blockIdx.x * 256 + tid;
+    if (m >= a.M) return;
+    const int per_img = a.Mi * a.Mj;
+    const int img = m / per_img;
+    const int rem = m - img * per_img;
+    const int i = rem / a.Mj;
+    const int j = rem - i * a.Mj;
+    const int bh = i * a.mult_h + a.add_h, bw = j * a.mult_w + a.add_w;
+    const long out_off = (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co;
+    float acc[TINY_MAX_C];
+#pragma unroll
+    for (int n = 0; n < TINY_MAX_C; ++n) acc[n] = (a.accumulate && n < NO) ? tf(out[out_off + n]) : 0.f;
+    // unconditional loads (clamped coordinates, masked values): the loads of consecutive taps overlap
+#pragma unroll 2
+    for (int t = 0; t < a.ntaps; ++t) {
+        const int h = bh + s_offh[t], w = bw + s_offw[t];
+        const bool in = (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
+        const int hc = min(max(h, 0), a.Hs - 1), wc = min(max(w, 0), a.Ws - 1);
+        const T *px = src + (((long)img * a.Hs + hc) * a.Ws + wc) * CS;
+        Vec xv[CS / VEC];
+#pragma unroll
+        for (int v = 0; v < CS / VEC; ++v) xv[v] = *(const Vec *)(px + v * VEC);
+        const float *wr = wL + t * TINY_MAX_C * CS;
+#pragma unroll
+        for (int v = 0; v < CS / VEC; ++v)
+#pragma unroll
+            for (int e = 0; e < VEC; e += 4) {
+                const float x0 = in ? tf(xv[v][e]) : 0.f, x1 = in ? tf(xv[v][e + 1]) : 0.f,
+                            x2 = in ? tf(xv[v][e + 2]) : 0.f, x3 = in ? tf(xv[v][e + 3]) : 0.f;
+#pragma unroll
+                for (int n = 0; n < TINY_MAX_C; ++n) {
+                    const f32x4 q = *(const f32x4 *)(wr + n * CS + v * VEC + e);
+                    acc[n] += x0 * q[0] + x1 * q[1] + x2 * q[2] + x3 * q[3];
+                }
+            }
+    }
+#pragma unroll
+    for (int n = 0; n < TINY_MAX_C; ++n)
+        if (n < NO) out[out_off + n] = (T)acc[n];
+}
+
+// ---------------------------------------------------------------- backward-weight: C <= 4 input channels, KT output channels
+template <typename T, int KT>
+__global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
+{
+    constexpr int VEC = 16 / (int)sizeof(T);
+    typedef T Vec __attribute__((ext_vector_type(VEC)));
+    constexpr int COLS = 32, PL = 256 / COLS;     // column lanes (tap, channel) and pixel lanes of a block
+    __shared__ float red[PL * COLS * 16];
+    __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
+    const int tid = threadIdx.x;
+    const int NT = a.ntaps * a.C;
+    const int col = blockIdx.x * COLS + tid % COLS, pl = tid / COLS;
+    const bool live = col < NT;
+    const int tap = live ? col / a.C : 0, c = live ? col - tap * a.C : 0;
+    const int split = blockIdx.y;
+    const T *__restrict__ x = (const T *)a.x;
+    const T *__restrict__ dy = (const T *)a.dy;
+    if (tid < kMaxTaps) {
+        s_offh[tid] = a.off_h[tid];
+        s_offw[tid] = a.off_w[tid];
+    }
+    __syncthreads();
+    const int oh = s_offh[tap], ow = s_offw[tap];
+    const int l_begin = split * a.rows_per_split;
+    const int l_end = min(a.L, l_begin + a.rows_per_split);
+    const int pq = a.P * a.Q;
+    float acc[KT];
+#pragma unroll
+    for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+#pragma unroll 4
+    for (int l = l_begin + pl; l < l_end; l += PL) {
+        const int img = l / pq;
+        const int rem = l - img * pq;
+        const int p = rem / a.Q;
+        const int q = rem - p * a.Q;
+        const int h = p * a.sh - a.ph + oh, w = q * a.sw - a.pw + ow;
+        const bool in = live && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+        const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 1);   // unconditional load, masked value
+        const float xl = tf(x[(((long)img * a.H + hc) * a.W + wc) * a.C + c]);
+        const float xv = in ? xl : 0.f;
+#pragma unroll
+        for (int v = 0; v < KT / VEC; ++v) {
+            const Vec d = *(const Vec *)(dy + (long)l * KT + v * VEC);   // the same address in all column lanes
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) acc[v * VEC + e] += tf(d[e]) * xv;
+        }
+    }
+    // combine the pixel lanes, 16 output channels at a time, in a fixed order
+    float *__restrict__ part = a.part + (long)split * KT * NT;   // [KT][NT]
+#pragma unroll
+    for (int k0 = 0; k0 < KT; k0 += 16) {
+#pragma unroll
+        for (int k = 0; k < 16; ++k) red[(pl * 16 + k) * COLS + tid % COLS] = acc[k0 + k];
+        __syncthreads();
+        // 512 sums of this round: thread -> (k = tid / 32 and + 8, column lane)
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int k = tid / COLS + kk * PL, cl = tid % COLS;
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < PL; ++r) s += red[(r * 16 + k) * COLS + cl];
+            const int ocol = blockIdx.x * COLS + cl;
+            if (ocol < NT) part[(long)(k0 + k) * NT + ocol] = s;
+        }
+        __syncthreads();
+    }
+}
+
+bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+bool tiny_off() { return getenv("NSK_NO_TINY") != nullptr; }   // test hook
+
+}  // namespace
+
+bool tiny_src_applicable(int dtype, const IgemmArgs &a)
+{
+    const int vec = dtype == NSK_BF16 ? 8 : 4;
+    if (tiny_off() || a.groups > 1 || a.stats || a.zero_cell) return false;
+    if (a.Cs < 1 || a.Cs > TINY_MAX_C || a.Ktot != a.ntaps * a.Cs) return false;
+    if (!(a.Ngemm == 8 || a.Ngemm == 16 || a.Ngemm == 32 || a.Ngemm == 64) || a.Ngemm % vec != 0) return false;
+    return a.Co % vec == 0 && al16(a.out) && (long)a.Ktot * a.Ngemm * 4 <= TINY_LDS_MAX;
+}
+
+int launch_tiny_src(int dtype, const IgemmArgs &a, hipStream_t stream)
+{
+    const dim3 grid(ceil_div(a.M, 256)), block(256);
+    const size_t lds = (size_t)a.Ktot * a.Ngemm * sizeof(float);
+#define NSK_TINY_SRC(T, NG) hipLaunchKernelGGL((tiny_src_kernel<T, NG>), grid, block, lds, stream, a)
+    if (dtype == NSK_BF16) {
+        switch (a.Ngemm) {
+        case 8: NSK_TINY_SRC(bf16_t, 8); break;
+        case 16: NSK_TINY_SRC(bf16_t, 16); break;
+        case 32: NSK_TINY_SRC(bf16_t, 32); break;
+        default: NSK_TINY_SRC(bf16_t, 64); break;
+        }
+    } else {
+        switch (a.Ngemm) {
+        case 8: NSK_TINY_SRC(float, 8); break;
+        case 16: NSK_TINY_SRC(float, 16); break;
+        case 32: NSK_TINY_SRC(float, 32); break;
+        default: NSK_TINY_SRC(float, 64); break;
+        }
+    }
+#undef NSK_TINY_SRC
+    return check_launch();
+}
+
+bool tiny_out_applicable(int dtype, const IgemmArgs &a)
+{
+    if (tiny_off() || a.groups > 1 || a.stats || a.zero_cell) return false;
+    if (a.Ngemm < 1 || a.Ngemm > TINY_MAX_C || a.Ktot != a.ntaps * a.Cs) return false;
+    if (!(a.Cs == 16 || a.Cs == 32 || a.Cs == 64)) return false;
+    return al16(a.src) && (long)a.ntaps * TINY_MAX_C * a.Cs * 4 <= TINY_LDS_MAX;
+}
+
+int launch_tiny_out(int dtype, const IgemmArgs &a, hipStream_t stream)
+{
+    const dim3 grid(ceil_div(a.M, 256)), block(256);
+    const size_t lds = (size_t)a.ntaps * TINY_MAX_C * a.Cs * sizeof(float);
+#define NSK_TINY_OUT(T, CS) hipLaunchKernelGGL((tiny_out_kernel<T, CS>), grid, block, lds, stream, a)
+    if (dtype == NSK_BF16) {
+        if (a.Cs == 16) NSK_TINY_OUT(bf16_t, 16);
+        else if (a.Cs == 32) NSK_TINY_OUT(bf16_t, 32);
+        else NSK_TINY_OUT(bf16_t, 64);
+    } else {
+        if (a.Cs == 16) NSK_TINY_OUT(float, 16);
+        else if (a.Cs == 32) NSK_TINY_OUT(float, 32);
+        else NSK_TINY_OUT(float, 64);
+    }
+#undef NSK_TINY_OUT
+    return check_launch();
+}
+
+bool tiny_wgrad_applicable(int dtype, const WgradArgs &a)
+{
+    if (tiny_off() || a.groups > 1) return false;
+    if (a.C < 1 || a.C > TINY_MAX_C) return false;
+    if (!(a.K == 16 || a.K == 32 || a.K == 64)) return false;
+    return al16(a.dy) && a.splits >= 1 && a.splits <= 65535;
+}
+
+int launch_tiny_wgrad(int dtype, const WgradArgs &a, hipStream_t stream)
+{
+    const dim3 grid(ceil_div(a.ntaps * a.C, 32), a.splits), block(256);
+#define NSK_TINY_WG(T, KT) hipLaunchKernelGGL((tiny_wgrad_kernel<T, KT>), grid, block, 0, stream, a)
+    if (dtype == NSK_BF16) {
+        if (a.K == 16) NSK_TINY_WG(bf16_t, 16);
+        else if (a.K == 32) NSK_TINY_WG(bf16_t, 32);
+        else NSK_TINY_WG(bf16_t, 64);
+    } else {
+        if (a.K == 16) NSK_TINY_WG(float, 16);
+        else if (a.K == 32) NSK_TINY_WG(float, 32);
+        else NSK_TINY_WG(float, 64);
+    }
+#undef NSK_TINY_WG
+    return check_launch();
+}
+
+}  // namespace nsk

@@ -300,6 +300,7 @@ int launch_wgrad(int dtype, const WgradArgs &a0, hipStream_t stream)
         a.ldx = a.C;
         a.ldy = a.K;
     }
+    if (tiny_wgrad_applicable(dtype, a)) return launch_tiny_wgrad(dtype, a, stream);
     if (getenv("NSK_NO_DEPTHWISE") == nullptr && depthwise_wgrad_applicable(dtype, a)) return launch_depthwise_wgrad(dtype, a, stream);
     const int VEC = dtype == NSK_BF16 ? 8 : 4;
     // (with C and K multiples of VEC every group's channel runs start on 16-byte boundaries too)

@@ -123,6 +123,11 @@ bool halo64_f32_applicable(int dtype, const IgemmArgs &a);
 int launch_halo64_f32(const IgemmArgs &a, hipStream_t stream);
 int halo64_f32_stats_rows(const IgemmArgs &a);
 
+// layers with at most four channels on one side (the 3-channel stride-1 image stem): direct kernels, no MFMA
+bool tiny_src_applicable(int dtype, const IgemmArgs &a);    // few source channels (forward)
+int launch_tiny_src(int dtype, const IgemmArgs &a, hipStream_t stream);
+bool tiny_out_applicable(int dtype, const IgemmArgs &a);    // few output channels (backward-data)
+int launch_tiny_out(int dtype, const IgemmArgs &a, hipStream_t stream);
 // depthwise layers (grouped launches with one channel per group on both sides, channel count a multiple of the vector
 // width): direct kernels bound by memory bandwidth, no MFMA
 bool depthwise_applicable(int dtype, const IgemmArgs &a);
@@ -159,6 +164,9 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &a, hipStream_t stream);
 bool wgrad_wide_applicable(int dtype, const WgradArgs &a);
 int wgrad_wide_rows_per_split(const WgradArgs &a, int *splits);
 int launch_wgrad_wide(const WgradArgs &a, hipStream_t stream);
+// at most four input channels: partial sums in the layout of the generic kernel
+bool tiny_wgrad_applicable(int dtype, const WgradArgs &a);
+int launch_tiny_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);
 // depthwise layers: partial sums in the layout of the generic kernel's grouped launch
 bool depthwise_wgrad_applicable(int dtype, const WgradArgs &a);
 int launch_depthwise_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);

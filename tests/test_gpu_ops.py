@@ -32,7 +32,12 @@ CONV_SHAPES = [
     (2, 1, 12, 18, 16, 3, 3, 2, 1, 1),         # 3x3 stride-2, single channel (space-to-depth, 2x2 coarse taps)
     (1, 64, 6, 66, 64, 3, 3, 1, 1, 1),         # 64->64 on a 66-wide image: too wide for the input ring, single-group halo kernel
     (2, 64, 16, 32, 64, 3, 3, 1, 1, 1),        # 64->64 on 32-wide images with H % 8 == 0: the row-aligned fp32 kernels
+    (3, 3, 17, 19, 32, 3, 3, 1, 1, 1),         # 3 -> 32 stride-1 stem, odd extents (direct kernels for few channels)
+    (2, 16, 11, 13, 3, 3, 3, 1, 1, 1),         # 16 -> 3: few OUTPUT channels (the same kernels with the roles swapped)
+    (2, 2, 9, 9, 8, 3, 3, 2, 1, 1),            # 2 -> 8, stride 2 on odd extents (backward-data classes on the direct kernel)
+    (1, 4, 10, 12, 64, 5, 5, 1, 2, (1, 2)),    # 4 -> 64, 5x5 with dilation
 ]
+FEW_CHANNELS = [4, 17, 18, 19, 20]
 
 
 def _conv_case(i, dtype):
@@ -340,7 +345,7 @@ def test_conv_pointwise_kernel(i, layout, monkeypatch):
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("i", [1, 2, 3, 8, 12, 13, 15, 16])
+@pytest.mark.parametrize("i", [1, 2, 3, 4, 8, 12, 13, 15, 16, 17, 18, 19, 20])
 def test_conv_gradients_accumulate(i, dtype, layout):
     x, w, dy, st, pd, dl = _conv_case(i, dtype)
     ws = B.Workspace()
@@ -589,4 +594,12 @@ def test_maxpool_3x3_on_the_general_kernel(i, dtype, monkeypatch):
     """The 3x3 fast path of the forward pool switched off: the general kernel must give the same bits."""
     monkeypatch.setenv("NSK_POOL_GENERAL", "1")
     test_maxpool_fwd_bwd(i, dtype, B.NSK_NHWC)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("i", FEW_CHANNELS)
+def test_few_channel_shapes_on_the_generic_kernels(i, dtype, monkeypatch):
+    """The direct kernels for layers with at most four channels on one side switched off."""
+    monkeypatch.setenv("NSK_NO_TINY", "1")
+    test_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
