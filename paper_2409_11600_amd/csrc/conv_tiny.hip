@@ -195,12 +195,17 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
     float acc[KT];
 #pragma unroll
     for (int k = 0; k < KT; ++k) acc[k] = 0.f;
+    // (img, p, q) of the lane's pixel: decoded once, then stepped (a division per pixel would cost more than its 16 FMAs)
+    int img, p, q;
+    {
+        const int l0 = min(l_begin + pl, a.L - 1);
+        img = l0 / pq;
+        const int rem = l0 - img * pq;
+        p = rem / a.Q;
+        q = rem - p * a.Q;
+    }
 #pragma unroll 4
     for (int l = l_begin + pl; l < l_end; l += PL) {
-        const int img = l / pq;
-        const int rem = l - img * pq;
-        const int p = rem / a.Q;
-        const int q = rem - p * a.Q;
         const int h = p * a.sh - a.ph + oh, w = q * a.sw - a.pw + ow;
         const bool in = live && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
         const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 1);   // unconditional load, masked value
@@ -211,6 +216,14 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
             const Vec d = *(const Vec *)(dy + (long)l * KT + v * VEC);   // the same address in all column lanes
 #pragma unroll
             for (int e = 0; e < VEC; ++e) acc[v * VEC + e] += tf(d[e]) * xv;
+        }
+        q += PL;
+        while (q >= a.Q) {
+            q -= a.Q;
+            if (++p == a.P) {
+                p = 0;
+                ++img;
+            }
         }
     }
     // combine the pixel lanes, 16 output channels at a time, in a fixed order
