@@ -46,8 +46,9 @@ __global__ __launch_bounds__(256) void tiny_src_kernel(const IgemmArgs a)
         s_offw[tid] = a.off_w[tid];
     }
     __syncthreads();
-    const int m = blockIdx.x * 256 + tid;
-    if (m >= a.M) return;
+    const long m_ = (long)blockIdx.x * 256 + tid;
+    if (m_ >= a.M) return;
+    const int m = (int)m_;
     const int per_img = a.Mi * a.Mj;
     const int img = m / per_img;
     const int rem = m - img * per_img;
@@ -125,8 +126,9 @@ __global__ __launch_bounds__(256) void tiny_out_kernel(const IgemmArgs a)
         s_offw[tid] = a.off_w[tid];
     }
     __syncthreads();
-    const int m = blockIdx.x * 256 + tid;
-    if (m >= a.M) return;
+    const long m_ = (long)blockIdx.x * 256 + tid;
+    if (m_ >= a.M) return;
+    const int m = (int)m_;
     const int per_img = a.Mi * a.Mj;
     const int img = m / per_img;
     const int rem = m - img * per_img;

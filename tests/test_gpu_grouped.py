@@ -215,3 +215,42 @@ def test_random_grouped_convolutions_match_the_oracle():
         want_dw = oracle.conv2d_grouped_wgrad(x, dy, w.shape, G, st, pd, dl)
         assert max_rel_err(to_host(dw_view, layout), want_dw) <= tol, shape
         assert max_rel_err(to_host(gdw, layout), want_dw + base_w.astype(np.float64)) <= tol, shape
+
+
+# N, C, H, K, R, stride, pad, groups: the layers bench.py --grouped times
+FULL_SIZE = [
+    (128, 128, 56, 128, 3, 1, 1, 128),
+    (128, 128, 56, 128, 3, 2, 1, 128),
+    (128, 256, 28, 256, 3, 1, 1, 32),
+    (128, 128, 56, 128, 3, 1, 1, 32),
+]
+
+
+@pytest.mark.parametrize("i", range(len(FULL_SIZE)))
+def test_grouped_layers_at_full_size(i):
+    """The grouped layers at the sizes bench.py --grouped times, in its launch configuration (bf16, NHWC).  Groups do
+    not mix, so the oracle's plain functions on the channel runs of a few sampled groups (first, last, two in
+    between) are exact parity for those groups' outputs: every element of them is compared."""
+    N, C, H, K, R, st, pd, G = FULL_SIZE[i]
+    print(f"full-size grouped layer {FULL_SIZE[i]}", flush=True)
+    dtype, layout = "bf16", B.NSK_NHWC
+    cg, kg = C // G, K // G
+    x = on_grid(gen.normal(7000 + i, 0, (N, C, H, H)), dtype)
+    w = on_grid(gen.he_normal(7000 + i, 1, (K, cg, R, R)), dtype)
+    P, Q = oracle.conv2d_out_dims(x.shape, (K, C, R, R), st, pd, 1)
+    dy = on_grid(gen.normal(7000 + i, 2, (N, K, P, Q)), dtype)
+    ws = B.Workspace()
+    gx, gw, gdy = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout), to_gpu(dy, dtype, layout)
+    gy = B.conv2d_grouped_fwd(gx, gw, G, st, pd, 1, layout, ws=ws)
+    gdx = B.conv2d_grouped_dgrad(gdy, gw, x.shape, G, st, pd, 1, layout, ws=ws)
+    gdw = B.conv2d_grouped_wgrad(gx, gdy, w.shape, G, st, pd, 1, layout, ws=ws)
+    torch.cuda.synchronize()
+    for g in sorted({0, G // 3, (2 * G) // 3, G - 1}):
+        cs, ks = slice(g * cg, (g + 1) * cg), slice(g * kg, (g + 1) * kg)
+        xg, wg, dyg = np.ascontiguousarray(x[:, cs]), np.ascontiguousarray(w[ks]), np.ascontiguousarray(dy[:, ks])
+        got_y = gy[..., ks].float().cpu().permute(0, 3, 1, 2).numpy().astype(np.float64)
+        assert max_rel_err(got_y, oracle.conv2d_fwd(xg, wg, st, pd, 1)) <= TOL[dtype], (FULL_SIZE[i], g)
+        got_dx = gdx[..., cs].float().cpu().permute(0, 3, 1, 2).numpy().astype(np.float64)
+        assert max_rel_err(got_dx, oracle.conv2d_dgrad(dyg, wg, xg.shape, st, pd, 1)) <= TOL[dtype], (FULL_SIZE[i], g)
+        got_dw = gdw[ks].cpu().permute(0, 3, 1, 2).numpy().astype(np.float64)
+        assert max_rel_err(got_dw, oracle.conv2d_wgrad(xg, dyg, wg.shape, st, pd, 1)) <= TOL["f32"] * 10, (FULL_SIZE[i], g)
