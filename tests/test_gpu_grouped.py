@@ -254,3 +254,26 @@ def test_grouped_layers_at_full_size(i):
         assert max_rel_err(got_dx, oracle.conv2d_dgrad(dyg, wg, xg.shape, st, pd, 1)) <= TOL[dtype], (FULL_SIZE[i], g)
         got_dw = gdw[ks].cpu().permute(0, 3, 1, 2).numpy().astype(np.float64)
         assert max_rel_err(got_dw, oracle.conv2d_wgrad(xg, dyg, wg.shape, st, pd, 1)) <= TOL["f32"] * 10, (FULL_SIZE[i], g)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_depthwise_channels_do_not_leak_into_each_other(dtype):
+    """An infinity in one channel of a depthwise layer's input reaches that channel's outputs only: every other channel
+    keeps its bits (the kernels pack two bf16 channels per dword, so this is a property worth pinning)."""
+    N, C, H, W = 2, 16, 9, 11
+    x = on_grid(gen.normal(7100, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(7100, 1, (C, 1, 3, 3)), dtype)
+    x_inf = x.copy()
+    x_inf[1, 5, 4, 6] = np.inf
+    layout = B.NSK_NHWC
+    ws = B.Workspace()
+    gw = to_gpu(w, dtype, layout)
+    y0 = B.conv2d_grouped_fwd(to_gpu(x, dtype, layout), gw, C, 1, 1, 1, layout, ws=ws)
+    y1 = B.conv2d_grouped_fwd(to_gpu(x_inf, dtype, layout), gw, C, 1, 1, 1, layout, ws=ws)
+    dx0 = B.conv2d_grouped_dgrad(to_gpu(x, dtype, layout), gw, (N, C, H, W), C, 1, 1, 1, layout, ws=ws)
+    dx1 = B.conv2d_grouped_dgrad(to_gpu(x_inf, dtype, layout), gw, (N, C, H, W), C, 1, 1, 1, layout, ws=ws)
+    torch.cuda.synchronize()
+    others = [c for c in range(C) if c != 5]
+    for a, b in ((y0, y1), (dx0, dx1)):
+        assert torch.equal(a[..., others], b[..., others])
+        assert bool(torch.isfinite(a).all()) and not bool(torch.isfinite(b[..., 5]).all())
