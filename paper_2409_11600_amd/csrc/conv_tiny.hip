@@ -25,6 +25,14 @@ constexpr int TINY_LDS_MAX = 48 << 10;
 __device__ inline float tf(float v) { return v; }
 __device__ inline float tf(bf16_t v) { return (float)v; }
 
+typedef bf16_t bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// acc += x . w over the two bf16 halves of a dword (both halves are terms of the same sum wherever this is used)
+__device__ inline float dot2(unsigned x, unsigned w, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, x), __builtin_bit_cast(bf16x2, w), acc, false);
+}
+
 // ---------------------------------------------------------------- forward: Cs <= 4 source channels, NG output channels
 template <typename T, int NG>
 __global__ __launch_bounds__(256) void tiny_src_kernel(const IgemmArgs a)
@@ -110,16 +118,25 @@ __global__ __launch_bounds__(256) void tiny_out_kernel(const IgemmArgs a)
 {
     constexpr int VEC = 16 / (int)sizeof(T);
     typedef T Vec __attribute__((ext_vector_type(VEC)));
-    extern __shared__ __attribute__((aligned(16))) float wL[];   // [ntaps][TINY_MAX_C][CS], rows n >= Ngemm are zero
+    // filter rows [ntaps][TINY_MAX_C][CS] (rows n >= Ngemm are zero): floats for fp32, the bf16 values themselves
+    // (two per dword) for bf16, whose products are two-element dot products on the raw dwords
+    constexpr bool BF = sizeof(T) == 2;
+    constexpr int WROW = BF ? CS / 2 : CS;       // LDS words per filter row
+    extern __shared__ __attribute__((aligned(16))) float wL[];
     __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
     const int tid = threadIdx.x, NO = a.Ngemm;
     const T *__restrict__ src = (const T *)a.src;
     const T *__restrict__ wpk = (const T *)a.wpk;   // [NO][ntaps][CS]
     T *__restrict__ out = (T *)a.out;
-    for (int i = tid; i < a.ntaps * TINY_MAX_C * CS; i += 256) {
-        const int c = i % CS, r = i / CS;
+    for (int i = tid; i < a.ntaps * TINY_MAX_C * WROW; i += 256) {
+        const int c = i % WROW, r = i / WROW;
         const int n = r % TINY_MAX_C, t = r / TINY_MAX_C;
-        wL[i] = n < NO ? tf(wpk[((long)n * a.ntaps + t) * CS + c]) : 0.f;
+        if constexpr (BF) {
+            const unsigned short *q = (const unsigned short *)wpk + ((long)n * a.ntaps + t) * CS + 2 * c;
+            ((unsigned *)wL)[i] = n < NO ? ((unsigned)q[0] | ((unsigned)q[1] << 16)) : 0u;
+        } else {
+            wL[i] = n < NO ? tf(wpk[((long)n * a.ntaps + t) * CS + c]) : 0.f;
+        }
     }
     if (tid < kMaxTaps) {
         s_offh[tid] = a.off_h[tid];
@@ -149,7 +166,21 @@ __global__ __launch_bounds__(256) void tiny_out_kernel(const IgemmArgs a)
         Vec xv[CS / VEC];
 #pragma unroll
         for (int v = 0; v < CS / VEC; ++v) xv[v] = *(const Vec *)(px + v * VEC);
-        const float *wr = wL + t * TINY_MAX_C * CS;
+        const float *wr = wL + t * TINY_MAX_C * WROW;
+        if constexpr (BF) {
+#pragma unroll
+            for (int v = 0; v < CS / VEC; ++v) {
+                const u32x4 xd = in ? __builtin_bit_cast(u32x4, xv[v]) : u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int n = 0; n < TINY_MAX_C; ++n) {
+                    const u32x4 q = *(const u32x4 *)(wr + n * WROW + v * 4);
+                    acc[n] = dot2(xd[0], q[0], acc[n]);
+                    acc[n] = dot2(xd[1], q[1], acc[n]);
+                    acc[n] = dot2(xd[2], q[2], acc[n]);
+                    acc[n] = dot2(xd[3], q[3], acc[n]);
+                }
+            }
+        } else
 #pragma unroll
         for (int v = 0; v < CS / VEC; ++v)
 #pragma unroll
@@ -298,7 +329,7 @@ bool tiny_out_applicable(int dtype, const IgemmArgs &a)
 int launch_tiny_out(int dtype, const IgemmArgs &a, hipStream_t stream)
 {
     const dim3 grid(ceil_div(a.M, 256)), block(256);
-    const size_t lds = (size_t)a.ntaps * TINY_MAX_C * a.Cs * sizeof(float);
+    const size_t lds = (size_t)a.ntaps * TINY_MAX_C * a.Cs * (dtype == NSK_BF16 ? 2 : 4);
 #define NSK_TINY_OUT(T, CS) hipLaunchKernelGGL((tiny_out_kernel<T, CS>), grid, block, lds, stream, a)
     if (dtype == NSK_BF16) {
         if (a.Cs == 16) NSK_TINY_OUT(bf16_t, 16);
