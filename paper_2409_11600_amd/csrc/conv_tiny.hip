@@ -21,6 +21,7 @@ namespace {
 
 constexpr int TINY_MAX_C = 4;        // channels on the narrow side
 constexpr int TINY_LDS_MAX = 48 << 10;
+constexpr int TINY_PIX = 2;         // output pixels per lane of the forward kernel
 
 __device__ inline float tf(float v) { return v; }
 __device__ inline float tf(bf16_t v) { return (float)v; }
@@ -54,40 +55,54 @@ __global__ __launch_bounds__(256) void tiny_src_kernel(const IgemmArgs a)
         s_offw[tid] = a.off_w[tid];
     }
     __syncthreads();
-    const long m_ = (long)blockIdx.x * 256 + tid;
-    if (m_ >= a.M) return;
-    const int m = (int)m_;
+    // a lane owns TINY_PIX consecutive output pixels: a filter row read from LDS (a broadcast, but it still costs the LDS
+    // pipe a full pass) serves all of them
+    const long m0 = ((long)blockIdx.x * 256 + tid) * TINY_PIX;
+    if (m0 >= a.M) return;
     const int per_img = a.Mi * a.Mj;
-    const int img = m / per_img;
-    const int rem = m - img * per_img;
-    const int i = rem / a.Mj;
-    const int j = rem - i * a.Mj;
-    const int bh = i * a.mult_h + a.add_h, bw = j * a.mult_w + a.add_w;
-    const long out_off = (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co;
-    float acc[NG];
+    int bh[TINY_PIX], bw[TINY_PIX];
+    long src_img[TINY_PIX], out_off[TINY_PIX];
+    bool live[TINY_PIX];
+    float acc[TINY_PIX][NG];
 #pragma unroll
-    for (int n = 0; n < NG; ++n) acc[n] = 0.f;
-    if (a.accumulate) {   // start from the old values: the sum is rounded to the storage type once
+    for (int u = 0; u < TINY_PIX; ++u) {
+        live[u] = m0 + u < a.M;
+        const int m = live[u] ? (int)(m0 + u) : 0;
+        const int img = m / per_img;
+        const int rem = m - img * per_img;
+        const int i = rem / a.Mj;
+        const int j = rem - i * a.Mj;
+        bh[u] = i * a.mult_h + a.add_h;
+        bw[u] = j * a.mult_w + a.add_w;
+        src_img[u] = (long)img * a.Hs;
+        out_off[u] = (((long)img * a.Ho + (i * a.osh + a.oa)) * a.Wo + (j * a.osw + a.ob)) * a.Co;
 #pragma unroll
-        for (int v = 0; v < NG / VEC; ++v) {
-            const Vec old = *(const Vec *)(out + out_off + v * VEC);
+        for (int n = 0; n < NG; ++n) acc[u][n] = 0.f;
+        if (a.accumulate && live[u]) {   // start from the old values: the sum is rounded to the storage type once
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[v * VEC + e] = tf(old[e]);
+            for (int v = 0; v < NG / VEC; ++v) {
+                const Vec old = *(const Vec *)(out + out_off[u] + v * VEC);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) acc[u][v * VEC + e] = tf(old[e]);
+            }
         }
     }
     // Every load is unconditional (coordinates clamped into the image, the value masked afterwards), so the loads of
     // several taps are in flight together instead of one dependent load per branch.
 #pragma unroll 3
     for (int t = 0; t < a.ntaps; ++t) {
-        const int h = bh + s_offh[t], w = bw + s_offw[t];
-        const bool in = (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
-        const int hc = min(max(h, 0), a.Hs - 1), wc = min(max(w, 0), a.Ws - 1);
-        const T *px = src + (((long)img * a.Hs + hc) * a.Ws + wc) * Cs;
-        float xv[TINY_MAX_C];
+        float xv[TINY_PIX][TINY_MAX_C];
 #pragma unroll
-        for (int c = 0; c < TINY_MAX_C; ++c) {
-            const float v = tf(px[min(c, Cs - 1)]);
-            xv[c] = (in && c < Cs) ? v : 0.f;
+        for (int u = 0; u < TINY_PIX; ++u) {
+            const int h = bh[u] + s_offh[t], w = bw[u] + s_offw[t];
+            const bool in = live[u] && (unsigned)h < (unsigned)a.Hs && (unsigned)w < (unsigned)a.Ws;
+            const int hc = min(max(h, 0), a.Hs - 1), wc = min(max(w, 0), a.Ws - 1);
+            const T *px = src + ((src_img[u] + hc) * a.Ws + wc) * Cs;
+#pragma unroll
+            for (int c = 0; c < TINY_MAX_C; ++c) {
+                const float v = tf(px[min(c, Cs - 1)]);
+                xv[u][c] = (in && c < Cs) ? v : 0.f;
+            }
         }
 #pragma unroll
         for (int c = 0; c < TINY_MAX_C; ++c) {
@@ -96,19 +111,26 @@ __global__ __launch_bounds__(256) void tiny_src_kernel(const IgemmArgs a)
 #pragma unroll
             for (int n = 0; n < NG; n += 4) {
                 const f32x4 q = *(const f32x4 *)(wr + n);
-                acc[n] += xv[c] * q[0];
-                acc[n + 1] += xv[c] * q[1];
-                acc[n + 2] += xv[c] * q[2];
-                acc[n + 3] += xv[c] * q[3];
+#pragma unroll
+                for (int u = 0; u < TINY_PIX; ++u) {
+                    acc[u][n] += xv[u][c] * q[0];
+                    acc[u][n + 1] += xv[u][c] * q[1];
+                    acc[u][n + 2] += xv[u][c] * q[2];
+                    acc[u][n + 3] += xv[u][c] * q[3];
+                }
             }
         }
     }
 #pragma unroll
-    for (int v = 0; v < NG / VEC; ++v) {
-        Vec o;
+    for (int u = 0; u < TINY_PIX; ++u) {
+        if (!live[u]) continue;
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) o[e] = (T)acc[v * VEC + e];
-        *(Vec *)(out + out_off + v * VEC) = o;
+        for (int v = 0; v < NG / VEC; ++v) {
+            Vec o;
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) o[e] = (T)acc[u][v * VEC + e];
+            *(Vec *)(out + out_off[u] + v * VEC) = o;
+        }
     }
 }
 
@@ -296,7 +318,7 @@ bool tiny_src_applicable(int dtype, const IgemmArgs &a)
 
 int launch_tiny_src(int dtype, const IgemmArgs &a, hipStream_t stream)
 {
-    const dim3 grid(ceil_div(a.M, 256)), block(256);
+    const dim3 grid(ceil_div(ceil_div(a.M, TINY_PIX), 256)), block(256);
     const size_t lds = (size_t)a.Ktot * a.Ngemm * sizeof(float);
 #define NSK_TINY_SRC(T, NG) hipLaunchKernelGGL((tiny_src_kernel<T, NG>), grid, block, lds, stream, a)
     if (dtype == NSK_BF16) {
