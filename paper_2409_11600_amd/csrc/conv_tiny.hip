@@ -7,9 +7,9 @@
 //     LDS as floats [tap][source channel][NG] and is read by broadcast;
 //   * backward-data (few output channels): a lane owns one output pixel, loads the CS source channels of each tap's
 //     pixel with 16-byte loads and multiplies them with the filter rows [tap][output channel][CS] from LDS;
-//   * backward-weight: a lane owns one (tap, input channel) column of dw for all K output channels; the 32 column
-//     lanes of a pixel lane read the same dy vector (broadcast) and their own x element; eight pixel lanes per block
-//     are combined through LDS in a fixed order.  Partial sums in the layout of the generic split kernel.
+//   * backward-weight: a lane owns two (tap, input channel) columns of dw for all K output channels; the 16 column
+//     lanes of a pixel lane read the same dy vector (broadcast) and their own x elements; sixteen pixel lanes per
+//     block are combined through LDS in a fixed order.  Partial sums in the layout of the generic split kernel.
 // Forward and backward-data take the argument set of the implicit-GEMM kernels (taps as offsets around a base pixel,
 // strided output grid), so stride classes, padding, dilation and `accumulate` come for free.
 #include <stdlib.h>
@@ -227,14 +227,14 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
 {
     constexpr int VEC = 16 / (int)sizeof(T);
     typedef T Vec __attribute__((ext_vector_type(VEC)));
-    constexpr int COLS = 32, PL = 256 / COLS;     // column lanes (tap, channel) and pixel lanes of a block
-    __shared__ float red[PL * COLS * 16];
+    // A block covers COLS = 32 columns (tap, channel) of dw with 16 column lanes of two columns each (the conversion of
+    // the K dy values is then shared by two columns' multiply-adds) and PL = 16 pixel lanes.
+    constexpr int COLS = 32, CL = COLS / 2, PL = 256 / CL;
+    __shared__ float red[PL * 16 * COLS];
     __shared__ short s_offh[kMaxTaps], s_offw[kMaxTaps];
     const int tid = threadIdx.x;
     const int NT = a.ntaps * a.C;
-    const int col = blockIdx.x * COLS + tid % COLS, pl = tid / COLS;
-    const bool live = col < NT;
-    const int tap = live ? col / a.C : 0, c = live ? col - tap * a.C : 0;
+    const int lc = tid % CL, pl = tid / CL;
     const int split = blockIdx.y;
     const T *__restrict__ x = (const T *)a.x;
     const T *__restrict__ dy = (const T *)a.dy;
@@ -243,14 +243,26 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
         s_offw[tid] = a.off_w[tid];
     }
     __syncthreads();
-    const int oh = s_offh[tap], ow = s_offw[tap];
+    bool live[2];
+    int cc[2], oh[2], ow[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int col = blockIdx.x * COLS + 2 * lc + j;
+        live[j] = col < NT;
+        const int tap = live[j] ? col / a.C : 0;
+        cc[j] = live[j] ? col - tap * a.C : 0;
+        oh[j] = s_offh[tap];
+        ow[j] = s_offw[tap];
+    }
     const int l_begin = split * a.rows_per_split;
     const int l_end = min(a.L, l_begin + a.rows_per_split);
     const int pq = a.P * a.Q;
-    float acc[KT];
+    float acc[2][KT];
 #pragma unroll
-    for (int k = 0; k < KT; ++k) acc[k] = 0.f;
-    // (img, p, q) of the lane's pixel: decoded once, then stepped (a division per pixel would cost more than its 16 FMAs)
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int k = 0; k < KT; ++k) acc[j][k] = 0.f;
+    // (img, p, q) of the lane's pixel: decoded once, then stepped (a division per pixel would cost more than its FMAs)
     int img, p, q;
     {
         const int l0 = min(l_begin + pl, a.L - 1);
@@ -259,18 +271,26 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
         p = rem / a.Q;
         q = rem - p * a.Q;
     }
-#pragma unroll 4
+#pragma unroll 2
     for (int l = l_begin + pl; l < l_end; l += PL) {
-        const int h = p * a.sh - a.ph + oh, w = q * a.sw - a.pw + ow;
-        const bool in = live && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
-        const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 1);   // unconditional load, masked value
-        const float xl = tf(x[(((long)img * a.H + hc) * a.W + wc) * a.C + c]);
-        const float xv = in ? xl : 0.f;
+        float xv[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int h = p * a.sh - a.ph + oh[j], w = q * a.sw - a.pw + ow[j];
+            const bool in = live[j] && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)a.W;
+            const int hc = min(max(h, 0), a.H - 1), wc = min(max(w, 0), a.W - 1);   // unconditional load, masked value
+            const float xl = tf(x[(((long)img * a.H + hc) * a.W + wc) * a.C + cc[j]]);
+            xv[j] = in ? xl : 0.f;
+        }
 #pragma unroll
         for (int v = 0; v < KT / VEC; ++v) {
             const Vec d = *(const Vec *)(dy + (long)l * KT + v * VEC);   // the same address in all column lanes
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) acc[v * VEC + e] += tf(d[e]) * xv;
+            for (int e = 0; e < VEC; ++e) {
+                const float df = tf(d[e]);
+                acc[0][v * VEC + e] += df * xv[0];
+                acc[1][v * VEC + e] += df * xv[1];
+            }
         }
         q += PL;
         while (q >= a.Q) {
@@ -286,12 +306,14 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
 #pragma unroll
     for (int k0 = 0; k0 < KT; k0 += 16) {
 #pragma unroll
-        for (int k = 0; k < 16; ++k) red[(pl * 16 + k) * COLS + tid % COLS] = acc[k0 + k];
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int k = 0; k < 16; ++k) red[(pl * 16 + k) * COLS + 2 * lc + j] = acc[j][k0 + k];
         __syncthreads();
-        // 512 sums of this round: thread -> (k = tid / 32 and + 8, column lane)
+        // 512 sums of this round: thread -> (k = tid / 32 and + 8, column)
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
-            const int k = tid / COLS + kk * PL, cl = tid % COLS;
+            const int k = tid / COLS + kk * 8, cl = tid % COLS;
             float s = 0.f;
 #pragma unroll
             for (int r = 0; r < PL; ++r) s += red[(r * 16 + k) * COLS + cl];
