@@ -253,6 +253,35 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     *o = accumulate ? *o + s : s;
 }
 
+// The same for small outputs with many splits (the 16- and 32-channel layers and the 3-channel stem of the CIFAR-sized
+// network: a few thousand outputs, hundreds of splits): 16 interleaved groups of splits instead of four, so that a lane's
+// chain of dependent loads is a quarter as long.  One block covers 16 consecutive outputs; fixed order as above.
+__global__ __launch_bounds__(256) void wgrad_reduce16_kernel(const float *__restrict__ part, float *__restrict__ dw,
+                                                              int splits, int K, int ntaps, int C, long sk, long st,
+                                                              long sc, int accumulate)
+{
+    __shared__ float red[16][16];
+    const long total = (long)K * ntaps * C;
+    const int g = threadIdx.x >> 4, j = threadIdx.x & 15;
+    const long i = (long)blockIdx.x * 16 + j;
+    float s = 0.f;
+    if (i < total)
+#pragma unroll 4
+        for (int sp = g; sp < splits; sp += 16) s += part[(long)sp * total + i];
+    red[g][j] = s;
+    __syncthreads();
+    if (g != 0 || i >= total) return;
+    float r = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; q += 4) r += (red[q][j] + red[q + 1][j]) + (red[q + 2][j] + red[q + 3][j]);
+    const int c = (int)(i % C);
+    const long rr = i / C;
+    const int t = (int)(rr % ntaps);
+    const long k = rr / ntaps;
+    float *o = dw + k * sk + t * st + c * sc;
+    *o = accumulate ? *o + r : r;
+}
+
 int column_frags(int ntapsC) { return ntapsC % 192 == 0 ? 3 : 1; }
 
 }  // namespace
@@ -313,8 +342,12 @@ int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int nta
                         long st, long sc, int accumulate, hipStream_t stream)
 {
     const long total = (long)K * ntaps * C;
-    hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream, part, dw,
-                       splits, K, ntaps, C, sk, st, sc, accumulate);
+    if (total <= 16384 && splits >= 64 && getenv("NSK_REDUCE4") == nullptr)   // (the variable is an A/B hook)
+        hipLaunchKernelGGL(wgrad_reduce16_kernel, dim3((unsigned)((total + 15) / 16)), dim3(256), 0, stream, part, dw,
+                           splits, K, ntaps, C, sk, st, sc, accumulate);
+    else
+        hipLaunchKernelGGL(wgrad_reduce_kernel, dim3((unsigned)((total + 63) / 64)), dim3(256), 0, stream, part, dw,
+                           splits, K, ntaps, C, sk, st, sc, accumulate);
     return check_launch();
 }
 
