@@ -411,7 +411,9 @@ Geom geometry(const nsk_bn_desc_t &d, bool backward)
     if (g.fast) {
         const int VEC = d.dtype == NSK_BF16 ? 8 : 4;
         const int RP = 256 / (d.C / VEC);
-        long G = (g.M + (long)RP * 8 - 1) / ((long)RP * 8);
+        // at least four passes of its 256 threads per block (measured on the 2-8 MB tensors of the CIFAR-sized network:
+        // eight passes leave one block per CU there and the whole step 1.5% slower; two are no better than four)
+        long G = (g.M + (long)RP * 4 - 1) / ((long)RP * 4);
         // Measured: the forward statistics pass over a large tensor (one input stream) is fastest with eight blocks
         // per CU, the backward pass (three input streams) and small tensors with two.
         // More blocks also mean more partial sums for the finalize kernel to read (G x C floats, twice): the larger
