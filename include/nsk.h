@@ -98,6 +98,18 @@ const char *nsk_status_string(int status);
 /* The hipError_t (as int) of the last HIP call that failed on this thread, 0 if none. */
 int nsk_last_hip_error(void);
 
+/* Test and A/B switches.  The library reads these environment variables once, at its first call (never on the
+ * launch path); a process that changes them afterwards calls nsk_test_hooks_reload().  Host only.  Every switch
+ * only moves a problem between kernels that compute the same result, so none changes any output beyond rounding
+ * order (and none is needed in production):
+ *   NSK_NO_BIG, NSK_NO_BIG_MULTI, NSK_NO_PW, NSK_NO_HALO, NSK_NO_HALO_WIDE, NSK_HALO_SINGLE, NSK_NO_STEM,
+ *   NSK_NO_STEM_HALO, NSK_NO_TINY, NSK_NO_WIDE, NSK_NO_DEPTHWISE, NSK_DEPTHWISE_NO_ROWS, NSK_DEPTHWISE_NO_COLS,
+ *   NSK_POOL_GENERAL, NSK_REDUCE4, NSK_WH_NO_SPLIT   (set = that special kernel or variant is not chosen);
+ *   NSK_HALO_WIDE_ALWAYS, NSK_STATS_ALWAYS          (set = chosen also where it does not pay);
+ *   NSK_BIG_MIN_TILES, NSK_PW_MIN_ROWS, NSK_WIDE_MIN_ROWS = n   (size threshold of a special kernel);
+ *   NSK_IGEMM_TILE = 1..3                           (tile shape of the generic kernel). */
+void nsk_test_hooks_reload(void);
+
 /* Output extent of a convolution.  Host only.  NSK_ERR_BAD_DESC if the descriptor is invalid
  * (then *P and *Q are not written); an extent may legitimately come out as 0. */
 int nsk_conv2d_out_dims(const nsk_conv_desc_t *desc, int *P, int *Q);
@@ -189,8 +201,10 @@ int nsk_bn_relu_add_fwd_mask(const nsk_bn_desc_t *desc, const void *x, const voi
 /* nsk_bn_relu_add_fwd with the batch statistics taken from partial sums of x and x*x (layout as written by
  * nsk_conv2d_fwd_stats: [2][stats_rows][C] floats) instead of a reduction pass over x.  relu_mask: NULL, or as in
  * nsk_bn_relu_add_fwd_mask.  The variance is formed as E[x*x] - E[x]^2 in double precision from float partial sums
- * that are not shifted: it loses accuracy when |mean| is hundreds of standard deviations (1e-4 of invstd at about
- * 250); nsk_bn_relu_add_fwd, which subtracts a per-channel shift first, has no such limit. */
+ * that are not shifted: a float partial sum is good to about 3e-8, which is 3e-8 * (mean/sigma)^2 of the variance, so
+ * invstd is off by 1e-4 where |mean| is about 80 standard deviations (measured on a 1x1 layer fed an all-positive
+ * input; the zero padding of a 3x3 layer keeps its outputs below 10).  nsk_bn_relu_add_fwd, which subtracts a
+ * per-channel shift first, has no such limit. */
 int nsk_bn_relu_add_fwd_stats(const nsk_bn_desc_t *desc, const void *x, const void *residual,
                               const float *gamma, const float *beta, void *out, unsigned char *relu_mask,
                               float *save_mean, float *save_invstd, float *running_mean,

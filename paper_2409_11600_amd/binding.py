@@ -79,6 +79,8 @@ def lib() -> ctypes.CDLL:
         ip = ctypes.POINTER(ctypes.c_int)
         L.nsk_version.restype = ci
         L.nsk_version.argtypes = []
+        L.nsk_test_hooks_reload.restype = None
+        L.nsk_test_hooks_reload.argtypes = []
         L.nsk_status_string.restype = ctypes.c_char_p
         L.nsk_status_string.argtypes = [ci]
         L.nsk_last_hip_error.restype = ci
@@ -188,7 +190,7 @@ def lib() -> ctypes.CDLL:
     return _lib
 
 
-EXPORTS = ("nsk_version", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d_out_dims",
+EXPORTS = ("nsk_version", "nsk_test_hooks_reload", "nsk_status_string", "nsk_last_hip_error", "nsk_conv2d_out_dims",
            "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
            "nsk_conv2d_grouped_workspace_bytes", "nsk_conv2d_grouped_fwd", "nsk_conv2d_grouped_dgrad",
            "nsk_conv2d_grouped_wgrad",

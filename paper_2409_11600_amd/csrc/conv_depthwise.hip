@@ -555,8 +555,8 @@ template <typename T, int CG> int launch_depthwise_typed(const IgemmArgs &a, hip
     RowPlan rp{};
     ColPlan cp{};
     // the variables are test hooks; the column arrangement is preferred (contiguous loads)
-    const bool cols = getenv("NSK_DEPTHWISE_NO_COLS") == nullptr && getenv("NSK_DEPTHWISE_NO_ROWS") == nullptr && col_plan(a, &cp);
-    const bool rows = !cols && getenv("NSK_DEPTHWISE_NO_ROWS") == nullptr && row_plan(a, &rp);
+    const bool cols = !hooks().depthwise_no_cols && !hooks().depthwise_no_rows && col_plan(a, &cp);
+    const bool rows = !cols && !hooks().depthwise_no_rows && row_plan(a, &rp);
     const int S = rows ? a.ntaps / rp.R : 0, R = cols ? a.ntaps / cp.S : 0;
     const long threads = cols   ? (long)a.Nimg * ((a.Mi + DW_PIX - 1) / DW_PIX) * a.Mj * (C / VEC)
                          : rows ? (long)a.Nimg * a.Mi * ((a.Mj + DW_PIX - 1) / DW_PIX) * (C / VEC)

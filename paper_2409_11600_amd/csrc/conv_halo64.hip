@@ -548,7 +548,7 @@ bool halo64_applicable(int dtype, const IgemmArgs &a)
 }
 
 namespace {
-bool two_group(const IgemmArgs &g) { return 512 + 2 * (g.Ws + 3) <= P_RING_MAX && getenv("NSK_HALO_SINGLE") == nullptr; }
+bool two_group(const IgemmArgs &g) { return 512 + 2 * (g.Ws + 3) <= P_RING_MAX && !hooks().halo_single; }
 constexpr int kStatsGrid = 256;   // block count when statistics are requested: the row count must not depend on the device
 }  // namespace
 

@@ -522,7 +522,7 @@ bool classes_ok(const IgemmArgs *a, int count)
     // the positions a tile computes beyond the image rows it owns are wasted MFMA work: take the layer only if at
     // least two thirds of it is useful, and only if the tiles fill a good part of the chip (NSK_HALO_WIDE_ALWAYS:
     // test hook, small shapes)
-    if (getenv("NSK_HALO_WIDE_ALWAYS") != nullptr) return true;
+    if (hooks().halo_wide_always) return true;
     const long long useful = (long long)a[0].Hs * a[0].Ws, computed = (long long)p.tiles_per_img * kNT * 32;
     if (useful * 3 < computed * 2) return false;
     return (long long)a[0].Nimg * p.tiles_per_img * (a[0].Ngemm / block_channels(a[0])) >= 128;
@@ -617,7 +617,7 @@ int launch_classes(const IgemmArgs *g, int count, hipStream_t stream)
 // One class with all nine taps on its own grid: the forward pass, or the backward-data pass of a stride-1 layer.
 bool halo_wide_applicable(int dtype, const IgemmArgs &a)
 {
-    if (dtype != NSK_BF16 || getenv("NSK_NO_HALO_WIDE") != nullptr) return false;
+    if (dtype != NSK_BF16 || hooks().no_halo_wide) return false;
     if (a.ntaps != 9 || a.osh != 1 || a.osw != 1 || a.oa != 0 || a.ob != 0) return false;
     if (a.Hs != a.Ho || a.Ws != a.Wo || a.Mi != a.Ho || a.Mj != a.Wo) return false;
     return classes_ok(&a, 1);
@@ -636,7 +636,7 @@ int launch_halo_wide(const IgemmArgs &g, hipStream_t stream) { return launch_cla
 // convolution over the same source grid with at most nine taps.
 bool halo_wide_multi_applicable(int dtype, const IgemmArgs *a, int count)
 {
-    if (dtype != NSK_BF16 || getenv("NSK_NO_HALO_WIDE") != nullptr || count < 2) return false;
+    if (dtype != NSK_BF16 || hooks().no_halo_wide || count < 2) return false;
     for (int i = 0; i < count; ++i)
         if (a[i].stats || a[i].zero_cell) return false;
     return classes_ok(a, count);

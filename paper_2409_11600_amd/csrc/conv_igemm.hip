@@ -380,8 +380,7 @@ int launch_tile(const IgemmArgs &a, bool vec, hipStream_t stream)
 // NSK_IGEMM_TILE=<n> forces a tile variant (A/B experiments); unset or 0 = automatic choice.
 int forced_tile()
 {
-    const char *e = getenv("NSK_IGEMM_TILE");
-    return e ? atoi(e) : 0;
+    return hooks().igemm_tile;
 }
 
 // Automatic tile choice: 0 = 256x32 (64-row wavefront tiles), 1 = 128x64 (32-row), 2 = 128x128 (64-row).
@@ -436,7 +435,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     // statistics pass they replace (config 5 stage A: +45 us on a 140 us layer), so only long reductions use it.
     const int vec = dtype == NSK_BF16 ? 8 : 4;
     if (!(a.Ngemm % vec == 0 && a.Co % vec == 0 && (uintptr_t)a.out % 16 == 0)) return 0;
-    if (a.Ktot < 1024 && getenv("NSK_STATS_ALWAYS") == nullptr) return 0;   // the variable is a test hook
+    if (a.Ktot < 1024 && !hooks().stats_always) return 0;   // the variable is a test hook
     if (a.Ngemm % 4 != 0) return 0;   // 16-byte stores of the partial sums
     static const int bm[3] = {256, 128, 128}, wm[3] = {64, 32, 64};
     const int t = auto_tile(a, dtype == NSK_BF16 ? 2 : 4);
@@ -457,7 +456,7 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (special && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
     if (special && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
     if (special && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
-    if (grouped && forced_tile() == 0 && getenv("NSK_NO_DEPTHWISE") == nullptr && depthwise_applicable(dtype, a))
+    if (grouped && forced_tile() == 0 && !hooks().no_depthwise && depthwise_applicable(dtype, a))
         return launch_depthwise(dtype, a, stream);
     IgemmArgs b = a;
     if (!grouped) {

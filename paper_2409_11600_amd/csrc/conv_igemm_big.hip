@@ -353,7 +353,7 @@ template <int BN> int smem_bytes() { return 2 * (GB_BM + BN) * GB_ROW + 256 * 4;
 
 bool igemm_big_applicable(int dtype, const IgemmArgs &a)
 {
-    if (dtype != NSK_BF16 || getenv("NSK_NO_BIG") != nullptr) return false;
+    if (dtype != NSK_BF16 || hooks().no_big) return false;
     if (a.Cs % GB_BK != 0 || a.Ngemm % 64 != 0 || a.Co % 8 != 0 || a.ntaps > 64 || a.ntaps < 1) return false;
     if (((uintptr_t)a.src | (uintptr_t)a.wpk | (uintptr_t)a.out) & 15) return false;
     const long long out_bytes = (long long)a.Nimg * a.Ho * a.Wo * a.Co * 2;
@@ -365,8 +365,7 @@ bool igemm_big_applicable(int dtype, const IgemmArgs &a)
     // also still fill the chip.  NSK_BIG_MIN_TILES overrides all three tests (tests use it to run small shapes
     // through this kernel).
     const long long tiles = (long long)ceil_div(a.M, GB_BM) * ceil_div(a.Ngemm, a.Ngemm >= 128 ? 128 : 64);
-    const char *e = getenv("NSK_BIG_MIN_TILES");
-    if (e) return tiles >= atoll(e);
+    if (hooks().big_min_tiles >= 0) return tiles >= hooks().big_min_tiles;
     return tiles >= 160 && a.Ngemm >= 128 && a.Ktot >= 8 * GB_BK;
 }
 
@@ -414,7 +413,7 @@ static bool big_shape_ok(const IgemmArgs &a)
 
 bool igemm_big_multi_applicable(int dtype, const IgemmArgs *a, int count)
 {
-    if (dtype != NSK_BF16 || getenv("NSK_NO_BIG") != nullptr || getenv("NSK_NO_BIG_MULTI") != nullptr) return false;
+    if (dtype != NSK_BF16 || hooks().no_big || hooks().no_big_multi) return false;
     if (count < 2 || count > kBigMultiMax) return false;
     long long tiles = 0;
     int longest = 0;
@@ -426,8 +425,7 @@ bool igemm_big_multi_applicable(int dtype, const IgemmArgs *a, int count)
         tiles += (long long)ceil_div(a[i].M, GB_BM) * ceil_div(a[i].Ngemm, a[i].Ngemm >= 128 ? 128 : 64);
         if (a[i].Ktot > longest) longest = a[i].Ktot;
     }
-    const char *e = getenv("NSK_BIG_MIN_TILES");   // test hook, as in igemm_big_applicable
-    if (e) return tiles >= atoll(e);
+    if (hooks().big_min_tiles >= 0) return tiles >= hooks().big_min_tiles;   // test hook, as in igemm_big_applicable
     return tiles >= 160 && a[0].Ngemm >= 128 && longest >= 8 * GB_BK;
 }
 

@@ -26,7 +26,7 @@ namespace nsk {
 
 bool conv_pw_applicable(int dtype, const IgemmArgs &a)
 {
-    if (getenv("NSK_NO_PW")) return false;
+    if (hooks().no_pw) return false;
     if (dtype != NSK_BF16 || (a.accumulate && (a.stats || a.zero_cell))) return false;
     if (a.Cs % 16 != 0 || a.Ktot != a.ntaps * a.Cs) return false;
     const int ks = a.Ktot / 16;
@@ -58,8 +58,7 @@ bool conv_pw_applicable(int dtype, const IgemmArgs &a)
     if ((long)a.Nimg * a.Ho * a.Wo * a.Co * 2 >= (long)PW_OOB || (long)a.src_bytes >= (long)PW_OOB) return false;
     // exact magic-number division of a row index by Mi*Mj and of the remainder by Mj
     if ((long)a.M * a.Mi * a.Mj >= (1L << 40) || (long)a.Mi * a.Mj * a.Mj >= (1L << 40)) return false;
-    const char *e = getenv("NSK_PW_MIN_ROWS");   // test hook
-    if (e) min_rows = atol(e);
+    if (hooks().pw_min_rows >= 0) min_rows = (long)hooks().pw_min_rows;   // test hook
     return a.M >= min_rows;
 }
 

@@ -288,7 +288,7 @@ bool stem_applicable(const ConvGeo &g)
     if (g.C > 4 || g.R != g.S || g.R % 2 == 0 || g.R > 7) return false;
     if (g.ph != (g.R - 1) / 2 || g.pw != g.ph) return false;
     if (g.H % 2 || g.W % 2) return false;
-    return getenv("NSK_NO_STEM") == nullptr;
+    return !hooks().no_stem;
 }
 
 size_t stem_workspace_bytes(const ConvGeo &g, int pass) { return stem_plan(g, stem_geo(g), pass).total; }

@@ -257,7 +257,7 @@ template <int CPP, int NT, int OC> constexpr int stem_halo_smem()
 // True if the 4x4-tap problem on the H x W coarse grid fits the kernels (7x7 stem, 64 output channels).
 bool stem_halo_applicable(int dtype, int U, int K, int Nimg, int H, int W)
 {
-    if (dtype != NSK_BF16 || U != 4 || K != 64 || getenv("NSK_NO_STEM_HALO") != nullptr) return false;
+    if (dtype != NSK_BF16 || U != 4 || K != 64 || hooks().no_stem_halo) return false;
     const int PW = W + 3;
     if (SH_T + 3 * (PW + 1) > SH_MAX_IN) return false;
     const long long pi = (long long)(H + 3) * PW, total = pi * Nimg;

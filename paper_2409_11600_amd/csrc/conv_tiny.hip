@@ -325,7 +325,7 @@ __global__ __launch_bounds__(256) void tiny_wgrad_kernel(const WgradArgs a)
 }
 
 bool al16(const void *p) { return ((uintptr_t)p & 15) == 0; }
-bool tiny_off() { return getenv("NSK_NO_TINY") != nullptr; }   // test hook
+bool tiny_off() { return hooks().no_tiny; }   // test hook
 
 }  // namespace
 

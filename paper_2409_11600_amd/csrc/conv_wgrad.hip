@@ -330,7 +330,7 @@ int launch_wgrad(int dtype, const WgradArgs &a0, hipStream_t stream)
         a.ldy = a.K;
     }
     if (tiny_wgrad_applicable(dtype, a)) return launch_tiny_wgrad(dtype, a, stream);
-    if (getenv("NSK_NO_DEPTHWISE") == nullptr && depthwise_wgrad_applicable(dtype, a)) return launch_depthwise_wgrad(dtype, a, stream);
+    if (!hooks().no_depthwise && depthwise_wgrad_applicable(dtype, a)) return launch_depthwise_wgrad(dtype, a, stream);
     const int VEC = dtype == NSK_BF16 ? 8 : 4;
     // (with C and K multiples of VEC every group's channel runs start on 16-byte boundaries too)
     const bool vec = a.C % VEC == 0 && a.K % VEC == 0 && (uintptr_t)a.x % 16 == 0 && (uintptr_t)a.dy % 16 == 0;
@@ -342,7 +342,7 @@ int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int nta
                         long st, long sc, int accumulate, hipStream_t stream)
 {
     const long total = (long)K * ntaps * C;
-    if (total <= 16384 && splits >= 64 && getenv("NSK_REDUCE4") == nullptr)   // (the variable is an A/B hook)
+    if (total <= 16384 && splits >= 64 && !hooks().reduce4)   // (the variable is an A/B hook)
         hipLaunchKernelGGL(wgrad_reduce16_kernel, dim3((unsigned)((total + 15) / 16)), dim3(256), 0, stream, part, dw,
                            splits, K, ntaps, C, sk, st, sc, accumulate);
     else

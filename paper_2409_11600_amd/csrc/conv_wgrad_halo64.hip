@@ -461,7 +461,7 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &g, hipStream_t stream)
         }
         attr_set = true;
     }
-    const bool split = getenv("NSK_WH_NO_SPLIT") == nullptr;   // the variable is an A/B and test hook
+    const bool split = !hooks().wh_no_split;   // the variable is an A/B and test hook
     if (dtype == NSK_BF16) {
         if (split)
             hipLaunchKernelGGL((wgrad_halo64_kernel<bf16_t, true>), dim3(blocks), dim3(512), smem_bytes<bf16_t>(), stream, a);

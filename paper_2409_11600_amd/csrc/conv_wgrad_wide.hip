@@ -291,7 +291,7 @@ int tile_rows(const WgradArgs &a) { return a.K % 256 == 0 ? 256 : 64; }
 
 bool wgrad_wide_applicable(int dtype, const WgradArgs &a)
 {
-    if (dtype != NSK_BF16 || getenv("NSK_NO_WIDE") != nullptr) return false;
+    if (dtype != NSK_BF16 || hooks().no_wide) return false;
     // a thread's 8 x-columns must share one tap (C % 8), a dy row is loaded in 16-byte pieces up to the tile height
     // (a tile of 64 rows also serves fewer output channels: the missing rows are neither loaded nor stored)
     if (a.C % 8 != 0 || a.K % 8 != 0 || (a.K % 256 != 0 && a.K > 64)) return false;
@@ -302,8 +302,7 @@ bool wgrad_wide_applicable(int dtype, const WgradArgs &a)
     if (xb >= (long long)WW_OOB || db >= (long long)WW_OOB) return false;
     if (WW_KT / a.Q + 1 > 2 * a.P) return false;   // the running pixel decode handles at most two image wraps per k-tile
     // a long reduction per block is what pays for the large tile (NSK_WIDE_MIN_ROWS: test hook)
-    const char *e = getenv("NSK_WIDE_MIN_ROWS");
-    return a.L >= (e ? atoi(e) : 16384);
+    return a.L >= (hooks().wide_min_rows >= 0 ? hooks().wide_min_rows : 16384);
 }
 
 // Number of splits (written to *splits) and rows per split for the wide kernel: about one block per CU.

@@ -68,7 +68,7 @@ void wgrad_geometry(const ConvGeo &g, WgradArgs *a)
 
 bool use_wgrad_halo(const ConvGeo &g, const WgradArgs &a)
 {
-    return wgrad_halo64_applicable(g.dtype, a) && getenv("NSK_NO_HALO") == nullptr;
+    return wgrad_halo64_applicable(g.dtype, a) && !hooks().no_halo;
 }
 
 // Workspace segments (byte offsets, each 256-aligned).
@@ -304,9 +304,56 @@ int conv_fwd_impl(const nsk_conv_desc_t *desc, int groups, const void *x, const 
 
 using namespace nsk;
 
+namespace nsk {
+namespace {
+TestHooks g_hooks;
+bool g_hooks_read = false;
+
+void read_hooks()
+{
+    auto on = [](const char *name) { return getenv(name) != nullptr; };
+    auto num = [](const char *name) { const char *e = getenv(name); return e ? atoll(e) : -1LL; };
+    TestHooks h{};
+    h.no_big = on("NSK_NO_BIG");
+    h.no_big_multi = on("NSK_NO_BIG_MULTI");
+    h.no_pw = on("NSK_NO_PW");
+    h.no_halo = on("NSK_NO_HALO");
+    h.no_halo_wide = on("NSK_NO_HALO_WIDE");
+    h.halo_wide_always = on("NSK_HALO_WIDE_ALWAYS");
+    h.halo_single = on("NSK_HALO_SINGLE");
+    h.no_stem = on("NSK_NO_STEM");
+    h.no_stem_halo = on("NSK_NO_STEM_HALO");
+    h.no_tiny = on("NSK_NO_TINY");
+    h.no_wide = on("NSK_NO_WIDE");
+    h.no_depthwise = on("NSK_NO_DEPTHWISE");
+    h.depthwise_no_rows = on("NSK_DEPTHWISE_NO_ROWS");
+    h.depthwise_no_cols = on("NSK_DEPTHWISE_NO_COLS");
+    h.pool_general = on("NSK_POOL_GENERAL");
+    h.stats_always = on("NSK_STATS_ALWAYS");
+    h.reduce4 = on("NSK_REDUCE4");
+    h.wh_no_split = on("NSK_WH_NO_SPLIT");
+    h.big_min_tiles = num("NSK_BIG_MIN_TILES");
+    h.pw_min_rows = num("NSK_PW_MIN_ROWS");
+    h.wide_min_rows = num("NSK_WIDE_MIN_ROWS");
+    const long long tile = num("NSK_IGEMM_TILE");
+    h.igemm_tile = tile > 0 ? (int)tile : 0;
+    g_hooks = h;
+    g_hooks_read = true;
+}
+}  // namespace
+
+const TestHooks &hooks()
+{
+    if (!g_hooks_read) read_hooks();
+    return g_hooks;
+}
+}  // namespace nsk
+
 extern "C" {
 
 int nsk_version(void) { return 100; }
+
+void nsk_test_hooks_reload(void) { nsk::read_hooks(); }
 
 const char *nsk_status_string(int status)
 {

@@ -32,6 +32,17 @@ __device__ inline void lds_barrier()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Test and A/B switches: environment variables NSK_*, read ONCE (first use, or nsk_test_hooks_reload()) and never on
+// the launch path.  Each one only narrows or widens the choice among kernels that all compute the same result.
+struct TestHooks {
+    bool no_big, no_big_multi, no_pw, no_halo, no_halo_wide, halo_wide_always, halo_single, no_stem, no_stem_halo,
+        no_tiny, no_wide, no_depthwise, depthwise_no_rows, depthwise_no_cols, pool_general, stats_always, reduce4,
+        wh_no_split;
+    long long big_min_tiles, pw_min_rows, wide_min_rows;   // -1: not set
+    int igemm_tile;                                         // 0: not set
+};
+const TestHooks &hooks();
+
 void set_last_hip_error(hipError_t e);
 // Returns NSK_OK or records the error and returns NSK_ERR_HIP.
 inline int check_launch()

@@ -334,7 +334,7 @@ int pool_typed(bool fwd, const nsk_pool_desc_t &d, int P, int Q, const void *a, 
     const dim3 grid((unsigned)((total + 255) / 256)), block(256);
     if (fwd) {
         const unsigned long long x_bytes = (unsigned long long)d.N * d.H * d.W * d.C * sizeof(T);
-        if (vec && d.R == 3 && d.S == 3 && x_bytes < 0xF0000000ull && getenv("NSK_POOL_GENERAL") == nullptr)   // (test hook)
+        if (vec && d.R == 3 && d.S == 3 && x_bytes < 0xF0000000ull && !hooks().pool_general)   // (test hook)
             hipLaunchKernelGGL((maxpool3_fwd_nhwc_kernel<T, VEC>), grid, block, 0, stream, (const T *)a, (T *)b, idx_out, g,
                                (unsigned)x_bytes);
         else if (vec)

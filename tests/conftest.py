@@ -27,3 +27,18 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def nsk_env(monkeypatch):
+    """Sets one of libnsk's NSK_* test switches for the duration of a test.  The library reads its switches once,
+    so every change (and the restoration afterwards) is followed by nsk_test_hooks_reload()."""
+    from paper_2409_11600_amd import binding
+
+    def set_switch(name, value):
+        monkeypatch.setenv(name, value)
+        binding.lib().nsk_test_hooks_reload()
+
+    yield set_switch
+    monkeypatch.undo()
+    binding.lib().nsk_test_hooks_reload()

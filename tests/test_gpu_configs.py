@@ -129,16 +129,83 @@ def test_every_step_of_the_workload_matches_the_oracle(config, stage, batch, lay
 
 
 ACT_L2_BAR = 2e-2      # forward activations of a bf16 chain: relative L2 error
-GRAD_L2_BAR = 0.25     # gradients of a bf16 chain (see test_workload_end_to_end)
+GRAD_L2_BAR = 0.25     # gradients of a bf16 chain whose ReLU masks are its own (see test_workload_end_to_end)
+# With the ORACLE's ReLU masks handed to the backward pass the two executions differ by roundings only; a tensor at
+# depth d of the chain carries about sqrt(d) roundings of 2^-9 relative each, so not every element is inside the
+# single-rounding bar of 2e-2, but nearly all are, and none is far outside (bars a little below / above the measured
+# values, which test_workload_end_to_end prints):
+MASKED_GRAD_L2_BAR = 2.5e-2  # measured: up to 2.1e-2 (a 16-element dgamma), 1.3e-2 on the large tensors
+FRAC_BAR = 0.90            # share of the elements of a tensor of 4096 or more elements within the element-wise bar
+FRAC4_BAR = 0.999          # share within four times the bar (measured: 1.0 everywhere)
+WORST_BAR = 0.25           # no element further off than this (relative, floored at the tensor's RMS; measured <= 0.13)
 
 
 def _within(got, want, tol):
-    """Fraction of elements whose relative error (same floor as max_rel_err) is within tol, and the relative L2 error."""
+    """Shares of the elements whose relative error (same floor as max_rel_err) is within tol and within 4 tol, the
+    largest such error, and the relative L2 error."""
     want = np.asarray(want, dtype=np.float64)
     rms = max(float(np.sqrt(np.mean(want * want))), 1e-30)
     rel = np.abs(got - want) / np.maximum(np.abs(want), rms)
     l2 = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-30))
-    return float(np.mean(rel <= tol)), l2
+    share = float(np.mean(rel <= tol)) if want.size >= 4096 else 1.0     # a share of a few dozen elements says little
+    return share, l2, float(np.mean(rel <= 4 * tol)), float(np.max(rel))
+
+
+def _chain_stats(net, fwd, bwd, wl, tol, kinds=("act", "grad", "dw")):
+    stats = {}
+    for name in net.shapes:
+        if name != "x" and "act" in kinds:
+            stats[f"act:{name}"] = _within(net.host(net.act[name]), fwd["act"][name], tol)
+        if name != wl["output"] and "grad" in kinds:
+            stats[f"grad:{name}"] = _within(net.host(net.grad[name]), bwd["grad"][name], tol)
+    for u in wl["units"]:
+        if u["kind"] != "pool" and "dw" in kinds:
+            n = u["name"]
+            stats[f"dw:{n}"] = _within(net.host(net.dw[n]), bwd["dw"][n], tol)
+            if u["kind"] == "conv_bn":
+                stats[f"dgamma:{n}"] = _within(net.dgamma[n].cpu().numpy(), bwd["dgamma"][n], tol)
+                stats[f"dbeta:{n}"] = _within(net.dbeta[n].cpu().numpy(), bwd["dbeta"][n], tol)
+    print("relative L2 / share within tol / within 4 tol / worst:",
+          ", ".join(f"{k}={v[1]:.1e}/{v[0]:.3f}/{v[2]:.4f}/{v[3]:.2f}" for k, v in stats.items()), flush=True)
+    return stats
+
+
+def _check_bf16_chain(net, fwd, bwd, wl, tol):
+    """Bars of a bf16 chain that runs on its own ReLU masks: relative L2 only for the gradients."""
+    stats = _chain_stats(net, fwd, bwd, wl, tol)
+    bad = {k: v for k, v in stats.items()
+           if k.split(":")[0] in ("act", "grad", "dw") and not v[1] <= (ACT_L2_BAR if k.startswith("act:") else GRAD_L2_BAR)}
+    bad.update({k: v for k, v in stats.items() if k.startswith("act:") and not (v[0] >= FRAC_BAR and v[2] >= FRAC4_BAR)})
+    assert not bad, bad
+
+
+def _oracle_mask(act_nchw, dtype):
+    """The ReLU mask of a stored activation in the format the *_mask calls exchange: one byte per 16-byte vector
+    in NHWC storage order, bit e set iff element e of the vector is > 0."""
+    per = 8 if dtype == "bf16" else 4
+    a = np.ascontiguousarray(np.transpose(act_nchw, (0, 2, 3, 1))).reshape(-1, per)
+    return ((a > 0).astype(np.uint8) << np.arange(per, dtype=np.uint8)).sum(axis=1).astype(np.uint8)
+
+
+def _backward_on_the_oracles_masks(net, fwd, bwd, wl, tol, strict=False):
+    """Runs the backward pass of a network whose forward pass has run, with every ReLU mask replaced by the one
+    of the oracle's stored activation, and holds every gradient to the element-wise bars above (strict: every
+    element of every tensor within tol, the fp32 bar)."""
+    for u in wl["units"]:
+        if u["kind"] == "conv_bn" and u["relu"]:
+            assert u["name"] in net.mask, "this test needs the ReLU-mask calls for every batch-norm with a ReLU"
+            m = torch.from_numpy(_oracle_mask(fwd["act"][u["dst"]], wl["dtype"]))
+            assert m.numel() == net.mask[u["name"]].numel()
+            net.mask[u["name"]].copy_(m)
+    net.backward()
+    torch.cuda.synchronize()
+    stats = _chain_stats(net, fwd, bwd, wl, tol, kinds=("grad", "dw"))
+    if strict:
+        bad = {k: v for k, v in stats.items() if not v[3] <= tol}
+    else:
+        bad = {k: v for k, v in stats.items()
+               if not (v[1] <= MASKED_GRAD_L2_BAR and v[0] >= FRAC_BAR and v[2] >= FRAC4_BAR and v[3] <= WORST_BAR)}
+    assert not bad, bad
 
 
 @pytest.mark.parametrize("fused", [True, False], ids=["fused", "plain"])
@@ -151,7 +218,11 @@ def test_workload_end_to_end(config, stage, batch, layout, fused):
     relative error near 1e-2 about 1% of the masks differ and the relative L2 error of the gradients is
     about sqrt(0.01) = 0.1 however exact each kernel is.  The bf16 bars are therefore: relative L2 error
     <= 2e-2 for every forward activation and <= 0.25 for every gradient (measured: up to 1.1e-2 and
-    0.16); every single step is held to the strict element-wise bar by the per-step test above."""
+    0.16), and stated shares of the elements of every activation within the element-wise bar.  Then the
+    backward pass runs once more with the ORACLE's ReLU masks handed in through the mask argument of the
+    batch-norm calls: with equal masks the two executions differ by roundings only, and every gradient,
+    weight gradient and batch-norm parameter gradient is held to element-wise bars.  Every single step is
+    held to the strict single-rounding bar by the per-step test above."""
     wl, t, fwd, bwd = _setup(config, stage, batch)
     print(f"workload {wl['name']} input {wl['input']} layout={layout} fused={fused} (end to end)", flush=True)
     # fused: statistics handed from the convolution to the batch-norm, ReLU mask handed from forward to backward
@@ -166,21 +237,53 @@ def test_workload_end_to_end(config, stage, batch, layout, fused):
     if wl["dtype"] == "f32":
         assert not bad, bad
         return
-    stats = {}
-    for name in net.shapes:
-        pairs = []
-        if name != "x":
-            pairs.append(("act", net.host(net.act[name]), fwd["act"][name]))
-        if name != wl["output"]:
-            pairs.append(("grad", net.host(net.grad[name]), bwd["grad"][name]))
-        for kind, got, want in pairs:
-            stats[f"{kind}:{name}"] = _within(got, want, tol)
-    for u in wl["units"]:
-        if u["kind"] != "pool":
-            stats[f"dw:{u['name']}"] = _within(net.host(net.dw[u["name"]]), bwd["dw"][u["name"]], tol)
-    print("relative L2 / fraction within tol:", ", ".join(f"{k}={v[1]:.1e}/{v[0]:.3f}" for k, v in stats.items()), flush=True)
-    bad = {k: v for k, v in stats.items() if not v[1] <= (ACT_L2_BAR if k.startswith("act:") else GRAD_L2_BAR)}
-    assert not bad, bad
+    _check_bf16_chain(net, fwd, bwd, wl, tol)
+    if fused and layout == B.NSK_NHWC:
+        _backward_on_the_oracles_masks(net, fwd, bwd, wl, tol)
+
+
+# Full batch, the launch configuration bench.py times (NHWC, statistics from the convolution epilogues, ReLU mask
+# handed to the backward pass, persistent blocks with several tiles each).
+FULL_BATCH = [(2, "A"), (3, "A"), (4, "A"), (5, "B")]
+
+
+@pytest.mark.parametrize("config,stage", FULL_BATCH)
+def test_full_batch_fused_chain_matches_the_oracle(config, stage):
+    """The whole workload at its configured batch through the fused call sequence, every activation, gradient,
+    weight gradient and batch-norm statistic against the oracle's execution of the same unit list.  The step
+    runs twice so that buffers are reused as in the timed loop.
+
+    Configuration 2 (fp32, the workload bench.py reports): every activation, mean and invstd element by element
+    at 1e-4.  Among the 8 M outputs of each of its ReLUs a handful lie within rounding distance of zero, so the
+    two executions disagree on their mask bits, and one flipped bit moves the gradients that depend on it by
+    whole units (measured: 2-3 flips per layer; 0.63 on single elements of the input gradient, 2e-3 on dbeta).
+    The free-running backward pass is therefore held to the share of elements inside the bar, and then the
+    backward pass runs again on the ORACLE's masks, where every element of every gradient, weight gradient, dgamma
+    and dbeta must meet 1e-4.  The bf16 configurations are held to the chain bars above in the same two ways."""
+    wl, t, fwd, bwd = _setup(config, stage, None)
+    print(f"workload {wl['name']} input {wl['input']} full batch, fused (end to end)", flush=True)
+    net = GpuNetwork(wl, t, layout=B.NSK_NHWC, use_relu_mask=True, use_fused_stats=True)
+    net.step()
+    net.step()
+    torch.cuda.synchronize()
+    tol = TOL[wl["dtype"]]
+    worst, bad = _compare(net, fwd, bwd, wl, tol)
+    top = sorted(worst.items(), key=lambda kv: -kv[1])[:5]
+    print("largest errors:", ", ".join(f"{k}={v:.2e}" for k, v in top), flush=True)
+    if wl["dtype"] == "f32":
+        fwd_bad = {k: v for k, v in worst.items() if k.split(":")[0] in ("act", "mean", "invstd") and not v <= tol}
+        assert not fwd_bad, fwd_bad
+        stats = _chain_stats(net, fwd, bwd, wl, tol, kinds=("grad", "dw"))
+        # measured: relative L2 3e-4 on every tensor (a flipped bit moves dbeta and dgamma, which enter every
+        # element of the gradient below them); all but 3e-4 of the elements of the activation gradients within 4 tol
+        free_bad = {k: v for k, v in stats.items() if not (v[1] <= 2e-3 and (not k.startswith("grad:") or v[2] >= 0.999))}
+        assert not free_bad, free_bad
+        _backward_on_the_oracles_masks(net, fwd, bwd, wl, tol, strict=True)
+        return
+    stat_bad = {k: v for k, v in worst.items() if k.split(":")[0] in ("mean", "invstd") and not v <= tol}
+    assert not stat_bad, stat_bad
+    _check_bf16_chain(net, fwd, bwd, wl, tol)
+    _backward_on_the_oracles_masks(net, fwd, bwd, wl, tol)
 
 
 @pytest.mark.parametrize("config,stage,batch", [(2, "A", 4), (4, "A", 2), (5, "B", 2)])

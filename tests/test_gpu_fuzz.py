@@ -52,9 +52,9 @@ def _draw(rng, wide_halo=False):
 
 
 @pytest.mark.parametrize("group", range(len(HOOKS)))
-def test_random_convolutions_match_the_oracle(group, monkeypatch):
+def test_random_convolutions_match_the_oracle(group, nsk_env):
     for k, v in HOOKS[group].items():
-        monkeypatch.setenv(k, v)
+        nsk_env(k, v)
     rng = np.random.default_rng(4200 + group)
     ws = B.Workspace()
     for case in range(CASES_PER_GROUP):

@@ -110,25 +110,25 @@ def test_grouped_conv_accumulate(i, dtype, layout):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", DEPTHWISE)
-def test_depthwise_shapes_on_the_generic_kernels(i, dtype, monkeypatch):
+def test_depthwise_shapes_on_the_generic_kernels(i, dtype, nsk_env):
     """The direct depthwise kernels switched off: the same shapes through the generic grouped launch."""
-    monkeypatch.setenv("NSK_NO_DEPTHWISE", "1")
+    nsk_env("NSK_NO_DEPTHWISE", "1")
     test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", DEPTHWISE)
-def test_depthwise_shapes_on_the_per_tap_kernel(i, dtype, monkeypatch):
+def test_depthwise_shapes_on_the_per_tap_kernel(i, dtype, nsk_env):
     """The load-sharing variants of the direct kernels switched off (they take the 3-, 5- and 7-tap-wide or -high filters otherwise)."""
-    monkeypatch.setenv("NSK_DEPTHWISE_NO_ROWS", "1")
+    nsk_env("NSK_DEPTHWISE_NO_ROWS", "1")
     test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", DEPTHWISE)
-def test_depthwise_shapes_on_the_row_sharing_kernel(i, dtype, monkeypatch):
+def test_depthwise_shapes_on_the_row_sharing_kernel(i, dtype, nsk_env):
     """The column-stacked variant switched off: the row-sharing one takes the shapes it can."""
-    monkeypatch.setenv("NSK_DEPTHWISE_NO_COLS", "1")
+    nsk_env("NSK_DEPTHWISE_NO_COLS", "1")
     test_grouped_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
 

@@ -105,9 +105,9 @@ WIDE_SHAPES = [
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("i", range(len(WIDE_SHAPES)))
-def test_conv_wide_layers_large_tile_kernel(i, layout, monkeypatch):
-    monkeypatch.setenv("NSK_BIG_MIN_TILES", "1")
-    monkeypatch.setenv("NSK_WIDE_MIN_ROWS", "1")
+def test_conv_wide_layers_large_tile_kernel(i, layout, nsk_env):
+    nsk_env("NSK_BIG_MIN_TILES", "1")
+    nsk_env("NSK_WIDE_MIN_ROWS", "1")
     N, C, H, W, K, R, S, st, pd, dl = WIDE_SHAPES[i]
     print(f"wide conv case {i} {WIDE_SHAPES[i]} layout={layout}", flush=True)
     dtype = "bf16"
@@ -168,8 +168,8 @@ HALO_WIDE_SHAPES = [
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("i", range(len(HALO_WIDE_SHAPES)))
-def test_conv_wide_halo_kernel(i, layout, monkeypatch):
-    monkeypatch.setenv("NSK_HALO_WIDE_ALWAYS", "1")
+def test_conv_wide_halo_kernel(i, layout, nsk_env):
+    nsk_env("NSK_HALO_WIDE_ALWAYS", "1")
     N, C, H, W, K = HALO_WIDE_SHAPES[i]
     print(f"wide halo conv case {i} {HALO_WIDE_SHAPES[i]} layout={layout}", flush=True)
     dtype, st, pd, dl = "bf16", 1, 1, 1
@@ -224,8 +224,8 @@ HALO_WIDE_STRIDED = [
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("i", range(len(HALO_WIDE_STRIDED)))
-def test_conv_wide_halo_kernel_strided_backward_data(i, layout, monkeypatch):
-    monkeypatch.setenv("NSK_HALO_WIDE_ALWAYS", "1")
+def test_conv_wide_halo_kernel_strided_backward_data(i, layout, nsk_env):
+    nsk_env("NSK_HALO_WIDE_ALWAYS", "1")
     N, C, H, W, K, R, st, pd = HALO_WIDE_STRIDED[i]
     print(f"wide halo strided dgrad case {i} {HALO_WIDE_STRIDED[i]} layout={layout}", flush=True)
     dtype, dl = "bf16", 1
@@ -293,8 +293,8 @@ PW_SHAPES = [
 
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("i", range(len(PW_SHAPES)))
-def test_conv_pointwise_kernel(i, layout, monkeypatch):
-    monkeypatch.setenv("NSK_PW_MIN_ROWS", "1")
+def test_conv_pointwise_kernel(i, layout, nsk_env):
+    nsk_env("NSK_PW_MIN_ROWS", "1")
     N, C, H, W, K, R, S, st, pd, dl = PW_SHAPES[i]
     if layout == B.NSK_NCHW and N * H * W > 100000:
         pytest.skip("large case once (NHWC)")
@@ -364,7 +364,7 @@ def test_conv_gradients_accumulate(i, dtype, layout):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_halo_backward_weight_many_chunks_per_block(dtype, monkeypatch):
+def test_halo_backward_weight_many_chunks_per_block(dtype, nsk_env):
     """3x3 64->64 backward-weight on enough positions that every block of the halo kernel walks several chunks (the
     double-buffered hand-over between its moving and its multiplying wavefronts), against the oracle; the variant
     without split roles must give the same bits."""
@@ -381,7 +381,7 @@ def test_halo_backward_weight_many_chunks_per_block(dtype, monkeypatch):
     dw_check()
     want = oracle.conv2d_wgrad(x, dy, (K, C, 3, 3), 1, 1, 1)
     assert max_rel_err(to_host(dw_view, layout), want) <= TOL["f32"] * 10   # fp32 sums of exact products
-    monkeypatch.setenv("NSK_WH_NO_SPLIT", "1")
+    nsk_env("NSK_WH_NO_SPLIT", "1")
     plain = B.conv2d_wgrad(gx, gdy, (K, C, 3, 3), 1, 1, 1, layout, ws=ws)
     torch.cuda.synchronize()
     assert torch.equal(plain, dw_view)
@@ -420,17 +420,17 @@ STATS_SHAPES = [
 @pytest.mark.parametrize("layout", LAYOUTS)
 @pytest.mark.parametrize("big", [False, True])
 @pytest.mark.parametrize("i", range(len(STATS_SHAPES)))
-def test_conv_statistics_feed_the_batch_norm(i, big, layout, monkeypatch):
+def test_conv_statistics_feed_the_batch_norm(i, big, layout, nsk_env):
     """nsk_conv2d_fwd_stats leaves per-channel partial sums of its stored output; nsk_bn_relu_add_fwd_stats takes its
     batch statistics from them.  y must equal the plain forward bit for bit, the partial sums must add up to the
     sums of the stored y, and the batch-norm results must agree with the plain call (which reads y once more) and
     with the oracle."""
     dtype, (N, C, H, W, K, R, S, st, pd, dl) = STATS_SHAPES[i]
-    monkeypatch.setenv("NSK_STATS_ALWAYS", "1")     # the generic kernel's statistics epilogue also for short reductions
+    nsk_env("NSK_STATS_ALWAYS", "1")     # the generic kernel's statistics epilogue also for short reductions
     if big:
         if dtype != "bf16" or C % 64 or K % 64:
             pytest.skip("the large-tile kernel takes bf16 layers with channel counts that are multiples of 64")
-        monkeypatch.setenv("NSK_BIG_MIN_TILES", "1")
+        nsk_env("NSK_BIG_MIN_TILES", "1")
     print(f"stats case {STATS_SHAPES[i]} big={big} layout={layout}", flush=True)
     x = on_grid(gen.normal(900 + i, 0, (N, C, H, W)), dtype)
     w = on_grid(gen.he_normal(900 + i, 1, (K, C, R, S)), dtype)
@@ -454,10 +454,49 @@ def test_conv_statistics_feed_the_batch_norm(i, big, layout, monkeypatch):
     torch.cuda.synchronize()
     assert max_rel_err(mean1.cpu().numpy(), mean0.cpu().numpy()) <= 1e-5
     assert max_rel_err(inv1.cpu().numpy(), inv0.cpu().numpy()) <= 1e-5
-    want_out, want_mean, want_inv = oracle.bn_relu_add_fwd(yh, g, b, None, 1e-5, True)
-    assert max_rel_err(mean1.cpu().numpy(), want_mean) <= 1e-5
-    assert max_rel_err(inv1.cpu().numpy(), want_inv) <= 1e-5
+    # the oracle's batch-norm of the ORACLE's convolution output (on the storage grid); the mean is compared on the
+    # scale that matters for the normalised value (a shift of the mean by d moves xhat by d * invstd)
+    y_want = on_grid(oracle.conv2d_fwd(x, w, st, pd, dl).astype(np.float32), dtype)
+    want_out, want_mean, want_inv = oracle.bn_relu_add_fwd(y_want, g, b, None, 1e-5, True)
+    stat_tol = 1e-5 if dtype == "f32" else 2e-4
+    assert np.max(np.abs(mean1.cpu().numpy() - want_mean) * want_inv) <= stat_tol
+    assert max_rel_err(inv1.cpu().numpy(), want_inv) <= stat_tol
     assert max_rel_err(to_host(out1, layout), want_out) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype,offset,least", [("f32", 6.0, 25), ("f32", 20.0, 80), ("bf16", 3.0, 12)])
+def test_fused_statistics_with_a_strongly_offset_convolution_output(dtype, offset, least):
+    """The statistics epilogues add UNSHIFTED float partial sums and the variance is E[y^2] - E[y]^2 in double
+    precision, which loses accuracy as |mean| / sigma grows.  A padded 3x3 layer cannot get there (its border
+    outputs see fewer taps, which bounds |mean| / sigma near 7), a 1x1 layer can: an all-positive input
+    (N(0,1) + offset) through a 1x1 filter with a positive mean gives channel means of tens to more than a hundred
+    standard deviations.  A float partial sum of y^2 is good to about half an ulp (3e-8), which is 3e-8 * (mean /
+    sigma)^2 of the variance: the fused chain must stay inside 4e-8 * (mean / sigma)^2 against the oracle (the header states
+    it: 1e-4 of invstd at about 80 standard deviations)."""
+    N, C, H, W, K = 4, 64, 16, 32, 64
+    x = on_grid(gen.normal(950, 0, (N, C, H, W)) + offset, dtype)
+    w = on_grid(gen.he_normal(950, 1, (K, C, 1, 1)) + 0.05, dtype)
+    g = (1.0 + 0.3 * gen.normal(950, 3, (K,))).astype(np.float32)
+    b = (0.2 * gen.normal(950, 4, (K,))).astype(np.float32)
+    y_want = on_grid(oracle.conv2d_fwd(x, w, 1, 0, 1).astype(np.float32), dtype)
+    want_out, want_mean, want_inv = oracle.bn_relu_add_fwd(y_want, g, b, None, 1e-5, True)
+    ratio = float(np.max(np.abs(want_mean) * want_inv))
+    print(f"offset {offset} {dtype}: |mean| / sigma up to {ratio:.0f}", flush=True)
+    assert ratio > least
+    ws = B.Workspace()
+    gx, gw = to_gpu(x, dtype, B.NSK_NHWC), to_gpu(w, dtype, B.NSK_NHWC)
+    y, stats = B.conv2d_fwd_stats(gx, gw, 1, 0, 1, ws=ws)
+    out, mean, inv = B.bn_relu_add_fwd(y, torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda(), None, 1e-5, True,
+                                       ws=ws, stats=stats)
+    torch.cuda.synchronize()
+    assert max_rel_err(to_host(y, B.NSK_NHWC), y_want) <= TOL[dtype]
+    stat_tol = max(1e-5, 4e-8 * ratio * ratio) if dtype == "f32" else 2e-3
+    assert max_rel_err(inv.cpu().numpy(), want_inv) <= stat_tol
+    assert np.max(np.abs(mean.cpu().numpy() - want_mean) * want_inv) <= stat_tol
+    # out = gamma * xhat + beta with xhat = (y - mean) * invstd: relative errors d_inv of invstd and d_mean * invstd
+    # of the mean move out by gamma * (|xhat| * d_inv + d_mean * invstd)
+    out_tol = TOL[dtype] if dtype == "bf16" else TOL[dtype] + 2 * stat_tol
+    assert max_rel_err(to_host(out, B.NSK_NHWC), want_out) <= out_tol
 
 
 BN_SHAPES = [(4, 64, 9, 11), (3, 16, 16, 16), (2, 256, 7, 7), (2, 1024, 5, 5), (5, 24, 6, 7), (2, 3, 10, 10),
@@ -590,16 +629,16 @@ def test_maxpool_fwd_bwd(i, dtype, layout):
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", [0, 1, 3])
-def test_maxpool_3x3_on_the_general_kernel(i, dtype, monkeypatch):
+def test_maxpool_3x3_on_the_general_kernel(i, dtype, nsk_env):
     """The 3x3 fast path of the forward pool switched off: the general kernel must give the same bits."""
-    monkeypatch.setenv("NSK_POOL_GENERAL", "1")
+    nsk_env("NSK_POOL_GENERAL", "1")
     test_maxpool_fwd_bwd(i, dtype, B.NSK_NHWC)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("i", FEW_CHANNELS)
-def test_few_channel_shapes_on_the_generic_kernels(i, dtype, monkeypatch):
+def test_few_channel_shapes_on_the_generic_kernels(i, dtype, nsk_env):
     """The direct kernels for layers with at most four channels on one side switched off."""
-    monkeypatch.setenv("NSK_NO_TINY", "1")
+    nsk_env("NSK_NO_TINY", "1")
     test_conv_fwd_dgrad_wgrad(i, dtype, B.NSK_NHWC)
 
