@@ -175,6 +175,20 @@ int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *re
                         float *save_invstd, float *running_mean, float *running_var,
                         void *workspace, size_t workspace_bytes, void *stream);
 
+/* nsk_bn_relu_add_fwd for callers that cannot allocate device memory or carry a workspace around: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, arithmetic and results as
+ * nsk_bn_relu_add_fwd, without the workspace: the per-block partial sums go to a device array that is part of the
+ * library image (nsk_static_scratch_bytes() = 8 MiB, held by every GPU the library runs on until the process ends).
+ * No hipMalloc, hipFree or other allocating call is made.  Descriptors whose nsk_bn_workspace_bytes(desc, NSK_BN_FWD)
+ * exceeds that size are rejected with NSK_ERR_WORKSPACE before any HIP call.  All calls on one GPU share the
+ * array: calls that overlap in time on one GPU (two streams, two threads) race and must not be issued; calls on
+ * one stream are ordered and safe.  The array's address is looked up once per device at the first call on that
+ * device (that first call must not be under stream capture). */
+size_t nsk_static_scratch_bytes(void);
+int nsk_bn_relu_add_fwd_static(const nsk_bn_desc_t *desc, const void *x, const void *residual,
+                               const float *gamma, const float *beta, void *out, float *save_mean,
+                               float *save_invstd, float *running_mean, float *running_var, void *stream);
+
 /* Backward of nsk_bn_relu_add_fwd.  x, out: the forward input and its stored result;
  * dout: gradient of out.  With dz = relu ? dout*[out>0] : dout and xhat = (x-mean)*invstd:
  *   dbeta = sum dz, dgamma = sum dz*xhat  (overwritten, [C] float),

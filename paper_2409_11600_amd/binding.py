@@ -107,6 +107,10 @@ def lib() -> ctypes.CDLL:
         L.nsk_bn_workspace_bytes.argtypes = [bd, ci]
         L.nsk_bn_relu_add_fwd.restype = ci
         L.nsk_bn_relu_add_fwd.argtypes = [bd] + [vp] * 10 + [sz, vp]
+        L.nsk_static_scratch_bytes.restype = sz
+        L.nsk_static_scratch_bytes.argtypes = []
+        L.nsk_bn_relu_add_fwd_static.restype = ci
+        L.nsk_bn_relu_add_fwd_static.argtypes = [bd] + [vp] * 10
         L.nsk_bn_relu_add_bwd.restype = ci
         L.nsk_bn_relu_add_bwd.argtypes = [bd] + [vp] * 11 + [sz, vp]
         L.nsk_conv2d_stats_rows.restype = ci
@@ -194,7 +198,8 @@ EXPORTS = ("nsk_version", "nsk_test_hooks_reload", "nsk_status_string", "nsk_las
            "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
            "nsk_conv2d_grouped_workspace_bytes", "nsk_conv2d_grouped_fwd", "nsk_conv2d_grouped_dgrad",
            "nsk_conv2d_grouped_wgrad",
-           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
+           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_static_scratch_bytes", "nsk_bn_relu_add_fwd_static",
+           "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
            "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_conv2d_stats_rows", "nsk_conv2d_fwd_stats",
            "nsk_bn_relu_add_fwd_stats", "nsk_maxpool2d_out_dims",
            "nsk_maxpool2d_fwd", "nsk_maxpool2d_bwd",
@@ -465,6 +470,23 @@ def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=N
     _check(lib().nsk_bn_relu_add_fwd(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
                                      _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean), _ptr(running_var),
                                      wp, wb, _stream()), "nsk_bn_relu_add_fwd")
+    return out, save_mean, save_invstd
+
+
+def bn_relu_add_fwd_static(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=NSK_NHWC, momentum=0.1,
+                           running_mean=None, running_var=None, out=None, save_mean=None, save_invstd=None):
+    """nsk_bn_relu_add_fwd_static: the call that takes no workspace and allocates nothing (its partial sums live in a
+    device array of the library).  The caller passes every output; this wrapper only creates the ones left out."""
+    d = bn_desc(x, layout, eps, momentum, relu)
+    if out is None:
+        out = torch.empty_like(x)
+    if save_mean is None:
+        save_mean = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    if save_invstd is None:
+        save_invstd = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    _check(lib().nsk_bn_relu_add_fwd_static(ctypes.byref(d), _ptr(x), _ptr(residual), _ptr(gamma), _ptr(beta), _ptr(out),
+                                            _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean), _ptr(running_var),
+                                            _stream()), "nsk_bn_relu_add_fwd_static")
     return out, save_mean, save_invstd
 
 

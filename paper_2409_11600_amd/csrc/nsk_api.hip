@@ -4,6 +4,8 @@
 #include <limits.h>
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "nsk_internal.h"
 
 namespace nsk {
@@ -647,6 +649,63 @@ int nsk_bn_relu_add_fwd(const nsk_bn_desc_t *desc, const void *x, const void *re
     NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
     return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var,
                          workspace, nullptr, nullptr, 0, (hipStream_t)stream);
+}
+
+// ---- nsk_bn_relu_add_fwd for callers that cannot allocate: the partial sums live in a file-scope device array.
+// The array's name is a host-side stand-in, not a device address: host code only ever uses the address that
+// hipGetSymbolAddress returns for the current device (each GPU holds its own copy at its own address).
+#define NSK_STATIC_SCRATCH_BYTES (8u << 20)
+static __device__ __align__(256) unsigned char scratch[NSK_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) {
+        nsk::set_last_hip_error(e);
+        return NSK_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return NSK_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr) {
+            nsk::set_last_hip_error(e);
+            return NSK_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return NSK_OK;
+}
+}  // namespace
+
+size_t nsk_static_scratch_bytes(void) { return NSK_STATIC_SCRATCH_BYTES; }
+
+int nsk_bn_relu_add_fwd_static(const nsk_bn_desc_t *desc, const void *x, const void *residual, const float *gamma,
+                               const float *beta, void *out, float *save_mean, float *save_invstd,
+                               float *running_mean, float *running_var, void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (!x || !gamma || !beta || !out || !save_mean || !save_invstd) return NSK_ERR_NULL;
+    if ((running_mean == nullptr) != (running_var == nullptr)) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(residual) || misaligned(out) || misaligned(gamma) || misaligned(beta) ||
+        misaligned(save_mean) || misaligned(save_invstd) || misaligned(running_mean) || misaligned(running_var))
+        return NSK_ERR_ALIGNMENT;
+    // the partial sums of this descriptor must fit the static array (checked before any HIP call)
+    if (nsk_bn_workspace_bytes(desc, NSK_BN_FWD) > NSK_STATIC_SCRATCH_BYTES) return NSK_ERR_WORKSPACE;
+    void *ws = nullptr;
+    NSK_TRY(static_scratch(&ws));
+    // every partial sum the finalize kernel reads is written by the reduction of the same call: nothing to clear
+    return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var, ws,
+                         nullptr, nullptr, 0, (hipStream_t)stream);
 }
 
 int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *out, const void *dout,
