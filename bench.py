@@ -11,6 +11,9 @@ residual block (N=128, C=K=64, 32x32), NHWC.  Prints ONE JSON line:
                launching stream around that kernel's launches INSIDE the timed steps
   cpu_baseline the CPU oracle (tests' reference, never tuned) timed on the host cores on the same
                workload, bounded to about 10-30 s of CPU work
+  bf16_...     (default run only) the figures the target is quoted on: FLOP-weighted TFLOP/s and fraction of the
+               bf16 MFMA peak over the 3x3 layers of configurations 4 and 5 (forward + backward-data +
+               backward-weight, cold buffers), and the step time of the bf16 workloads 3, 4, 5A, 5B
 
 Other workloads: --config {1,2,3,4,5} [--stage A|B] [--batch N].  --breakdown prints a per-call
 table to stderr.  --train-step adds a "train_step" object: the same workload followed by the head of the network,
@@ -55,6 +58,9 @@ def parse():
     ap.add_argument("--no-graph", action="store_true", help="issue every call from Python instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="leave out the bf16 figures the default run appends (3x3 layer TFLOP/s of configurations 4 and 5, "
+                         "step times of the bf16 workloads)")
     ap.add_argument("--no-stats", action="store_true",
                     help="keep the ReLU-mask hand-over but let every batch-norm compute its own statistics")
     ap.add_argument("--no-fusion", action="store_true",
@@ -97,14 +103,11 @@ def _time_calls(torch, fn, sets, repeats):
     return e0.elapsed_time(e1) / repeats
 
 
-def layer_table(repeats=20):
-    """Per-layer convolution timings at full size (see the module docstring)."""
-    import torch
+def distinct_layers(configs=((2, "A"), (3, "A"), (4, "A"), (5, "A"), (5, "B"))):
+    """(tag, (dtype, N, C, H, W, K, R, stride, pad)) of every distinct convolution layer of the given workloads."""
     import nsk_inputs as gen
-    from paper_2409_11600_amd import binding as B
-
     seen, layers = set(), []
-    for config, stage in ((2, "A"), (3, "A"), (4, "A"), (5, "A"), (5, "B")):
+    for config, stage in configs:
         wl = gen.workload(config, stage=stage)
         shapes = gen.tensor_shapes(wl)
         for u in wl["units"]:
@@ -114,11 +117,17 @@ def layer_table(repeats=20):
             if key not in seen:
                 seen.add(key)
                 layers.append((f"C{config}{stage if config == 5 else ''}", key))
+    return layers
+
+
+def time_layers(layers, repeats=20):
+    """Times forward, backward-data and backward-weight of each layer at full size on cold buffers (see the module
+    docstring) and yields one row per pass."""
+    import torch
+    from paper_2409_11600_amd import binding as B
+
     ws = B.Workspace()
     gen_t = torch.Generator(device="cuda").manual_seed(7)
-    head_flops = head_ms = 0.0
-    print(f"{'cfg':<5}{'layer':<38}{'pass':<7}{'us':>9}{'TFLOP/s':>9}{'%peak':>7}{'cap TF':>8}{'%cap':>6}")
-    rows = []
     for cfg, (dtype, N, C, H, W, K, R, stride, pad) in layers:
         dt = torch.bfloat16 if dtype == "bf16" else torch.float32
         es = 2 if dtype == "bf16" else 4
@@ -126,6 +135,9 @@ def layer_table(repeats=20):
         P = (H + 2 * pad - R) // stride + 1
         flops = 2.0 * N * P * P * K * C * R * R
         xb, yb, wb = N * H * W * C * es, N * P * P * K * es, K * R * R * C
+        # a filter narrower than the stride reads only the pixels it touches (a 1x1 stride-2 layer: a quarter of x);
+        # backward-data still writes all of dx (zeros where nothing arrives)
+        touched = min(1.0, R / stride) ** 2
         nset = max(2, int(300e6 // (xb + yb)) + 1)          # buffer sets that together exceed the last-level cache
         sets = []
         for _ in range(nset):
@@ -135,27 +147,80 @@ def layer_table(repeats=20):
         w = (torch.randn(K, R, R, C, device="cuda", generator=gen_t) * (2.0 / (C * R * R)) ** 0.5).to(dt)
         dw = torch.empty(K, R, R, C, device="cuda")
         passes = {
-            "fwd": (lambda s: B.conv2d_fwd(s[0], w, stride, pad, 1, out=s[2], ws=ws), (xb + yb + wb * es)),
+            "fwd": (lambda s: B.conv2d_fwd(s[0], w, stride, pad, 1, out=s[2], ws=ws), (xb * touched + yb + wb * es)),
             "dgrad": (lambda s: B.conv2d_dgrad(s[1], w, (N, C, H, W), stride, pad, 1, out=s[3], ws=ws), (xb + yb + wb * es)),
-            "wgrad": (lambda s: B.conv2d_wgrad(s[0], s[1], (K, C, R, R), stride, pad, 1, out=dw, ws=ws), (xb + yb + wb * 4)),
+            "wgrad": (lambda s: B.conv2d_wgrad(s[0], s[1], (K, C, R, R), stride, pad, 1, out=dw, ws=ws), (xb * touched + yb + wb * 4)),
         }
         name = f"{R}x{R} s{stride} {C}->{K} @{H}x{W} N={N} {dtype}"
         for pname, (fn, byts) in passes.items():
             ms = _time_calls(torch, fn, sets, repeats)
             cap = min(peak, flops / byts * PEAK["hbm"])
             tf = flops / ms / 1e9
-            print(f"{cfg:<5}{name:<38}{pname:<7}{ms * 1e3:9.1f}{tf:9.1f}{100 * tf * 1e12 / peak:7.1f}{cap / 1e12:8.0f}{100 * tf * 1e12 / cap:6.1f}",
-                  flush=True)
-            rows.append({"config": cfg, "layer": name, "pass": pname, "us": ms * 1e3, "tflops": tf,
-                         "frac_of_mfma_peak": tf * 1e12 / peak, "roofline_cap_tflops": cap / 1e12, "frac_of_cap": tf * 1e12 / cap})
-            if dtype == "bf16" and R == 3 and cfg in ("C4", "C5A", "C5B"):
-                head_flops += flops
-                head_ms += ms
+            yield {"config": cfg, "layer": name, "pass": pname, "us": ms * 1e3, "tflops": tf, "flops": flops,
+                   "frac_of_mfma_peak": tf * 1e12 / peak, "roofline_cap_tflops": cap / 1e12, "frac_of_cap": tf * 1e12 / cap,
+                   "is_bf16_3x3": dtype == "bf16" and R == 3 and cfg in ("C4", "C5A", "C5B")}
         del sets
-    head = head_flops / head_ms / 1e9
+
+
+def head_figure(rows):
+    """FLOP-weighted TFLOP/s over the bf16 3x3 layers of configurations 4 and 5, all passes: total FLOPs / total time."""
+    fl = sum(r["flops"] for r in rows if r["is_bf16_3x3"])
+    us = sum(r["us"] for r in rows if r["is_bf16_3x3"])
+    return fl / us / 1e6 if us else 0.0
+
+
+def layer_table(repeats=20):
+    """Per-layer convolution timings at full size (see the module docstring)."""
+    print(f"{'cfg':<5}{'layer':<38}{'pass':<7}{'us':>9}{'TFLOP/s':>9}{'%peak':>7}{'cap TF':>8}{'%cap':>6}")
+    rows = []
+    for r in time_layers(distinct_layers(), repeats):
+        print(f"{r['config']:<5}{r['layer']:<38}{r['pass']:<7}{r['us']:9.1f}{r['tflops']:9.1f}{100 * r['frac_of_mfma_peak']:7.1f}"
+              f"{r['roofline_cap_tflops']:8.0f}{100 * r['frac_of_cap']:6.1f}", flush=True)
+        rows.append(r)
+    head = head_figure(rows)
     print(f"bf16 3x3 layers of configurations 4 and 5, all passes: {head:.1f} TFLOP/s = {100 * head * 1e12 / PEAK['mfma_bf16']:.1f}% of the bf16 MFMA peak")
     print(json.dumps({"metric": "bf16 3x3 conv TFLOP/s over configs 4 and 5 (fwd+dgrad+wgrad, FLOP-weighted)", "value": head,
                       "unit": "TFLOP/s", "frac_of_mfma_peak": head * 1e12 / PEAK["mfma_bf16"], "layers": rows}))
+
+
+def bf16_target_figures(replays=10):
+    """What the target is quoted on, for the default run's JSON line: the bf16 3x3 layers of configurations 4 and 5
+    (each pass on cold buffers, 20 calls from one HIP graph) and the step time of the bf16 workloads (forward +
+    backward, fused call sequence, `replays` replays of one HIP graph each)."""
+    import torch
+    import nsk_inputs as gen
+    from paper_2409_11600_amd.network import GpuNetwork
+
+    layers = [l for l in distinct_layers(((4, "A"), (5, "A"), (5, "B"))) if l[1][0] == "bf16" and l[1][6] == 3]
+    rows = list(time_layers(layers))
+    head = head_figure(rows)
+    out = {"bf16_3x3_conv_tflops": head, "bf16_3x3_conv_frac_of_mfma_peak": head * 1e12 / PEAK["mfma_bf16"],
+           "bf16_3x3_layers": [{k: (round(r[k], 4) if isinstance(r[k], float) else r[k])
+                                for k in ("config", "layer", "pass", "us", "tflops", "frac_of_mfma_peak")} for r in rows],
+           "bf16_step_ms": {}}
+    for config, stage in ((3, "A"), (4, "A"), (5, "A"), (5, "B")):
+        wl = gen.workload(config, stage=stage)
+        net = GpuNetwork(wl, gen.workload_tensors(wl))
+        stream = torch.cuda.Stream()
+        with torch.cuda.stream(stream):
+            for _ in range(2):
+                net.step()
+            stream.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                net.step()
+            graph.replay()
+            stream.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(replays):
+                graph.replay()
+            stream.synchronize()
+            t1 = time.perf_counter()
+        ms = (t1 - t0) * 1e3 / replays
+        out["bf16_step_ms"][wl["name"]] = {"ms_per_step": ms, "images_per_s": wl["input"][0] / ms * 1e3, "batch": wl["input"][0]}
+        del net, graph
+        torch.cuda.empty_cache()
+    return out
 
 
 # N, C, H, K, R, stride, pad, groups: depthwise layers at the sizes of the bottleneck stages, and two 32-group layers
@@ -390,16 +455,15 @@ def main():
         stream.synchronize()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        # ---- timed region B: same steps issued call by call with events around the dominant kernel.
-        # A forward call launches exactly that kernel; a backward-data call also packs the filter
-        # first, so when both are in the group only the forward launches are bracketed.
-        fwd_only = [i for i in dom_idx if calls[i][0].__name__.startswith("nsk_conv2d_fwd")]
-        timed_idx = fwd_only or dom_idx
+        # ---- timed region B: same steps issued call by call with events around EVERY launch of the dominant group
+        # (a backward-data call also packs its filter first: that small launch is inside its bracket).
+        timed_idx = dom_idx
         rec = {i: [] for i in timed_idx}
         for _ in range(a.steps):
             issue(rec)
         stream.synchronize()
-    dom_ms = float(np.mean([e0.elapsed_time(e1) for i in timed_idx for e0, e1 in rec[i]]))
+    dom_all = np.array([e0.elapsed_time(e1) for i in timed_idx for e0, e1 in rec[i]], dtype=np.float64)
+    dom_ms, dom_mean, dom_min = float(np.median(dom_all)), float(np.mean(dom_all)), float(np.min(dom_all))
     ms_per_step = (t1 - t0) * 1e3 / a.steps
     value = batch * a.steps / (t1 - t0)
 
@@ -412,7 +476,9 @@ def main():
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = stored_traffic(wl["name"], kind)
     roof["kernel"] = kind
-    roof["launch_ms"] = dom_ms
+    roof["launch_ms"] = dom_ms      # median over all launches of the group inside the timed steps: what `achieved` uses
+    roof["launch_ms_mean"] = dom_mean
+    roof["launch_ms_min"] = dom_min
     roof["launches_per_step"] = len(dom_idx)
     roof["algorithmic_per_launch"] = flops if roof["bound"] == "mfma" else byts
 
@@ -466,6 +532,9 @@ def main():
         out["train_step"] = {"ms_per_step": (c1 - c0) * 1e3 / a.steps, "images_per_s": batch * a.steps / (c1 - c0),
                              "tail": f"avgpool + fc({Cout}->{classes}) + softmax-xent + backward + SGD-momentum over "
                                      f"{n_params} parameters", "loss": float(tr.loss.item())}
+
+    if a.config == 2 and a.batch is None and not a.no_extras:
+        out.update(bf16_target_figures())
 
     if not a.no_cpu_baseline:
         import oracle
