@@ -102,7 +102,7 @@ int nsk_last_hip_error(void);
  * launch path); a process that changes them afterwards calls nsk_test_hooks_reload().  Host only.  Every switch
  * only moves a problem between kernels that compute the same result, so none changes any output beyond rounding
  * order (and none is needed in production):
- *   NSK_NO_BIG, NSK_NO_BIG_MULTI, NSK_NO_PW, NSK_NO_HALO, NSK_NO_HALO_WIDE, NSK_HALO_SINGLE, NSK_NO_STEM,
+ *   NSK_NO_BIG, NSK_NO_BIG_MULTI, NSK_NO_PW, NSK_NO_HALO, NSK_NO_FS, NSK_NO_HALO_WIDE, NSK_HALO_SINGLE, NSK_NO_STEM,
  *   NSK_NO_STEM_HALO, NSK_NO_TINY, NSK_NO_WIDE, NSK_NO_DEPTHWISE, NSK_DEPTHWISE_NO_ROWS, NSK_DEPTHWISE_NO_COLS,
  *   NSK_POOL_GENERAL, NSK_REDUCE4, NSK_WH_NO_SPLIT   (set = that special kernel or variant is not chosen);
  *   NSK_HALO_WIDE_ALWAYS, NSK_STATS_ALWAYS          (set = chosen also where it does not pay);

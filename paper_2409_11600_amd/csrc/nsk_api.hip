@@ -320,6 +320,7 @@ void read_hooks()
     h.no_big_multi = on("NSK_NO_BIG_MULTI");
     h.no_pw = on("NSK_NO_PW");
     h.no_halo = on("NSK_NO_HALO");
+    h.no_fs = on("NSK_NO_FS");
     h.no_halo_wide = on("NSK_NO_HALO_WIDE");
     h.halo_wide_always = on("NSK_HALO_WIDE_ALWAYS");
     h.halo_single = on("NSK_HALO_SINGLE");

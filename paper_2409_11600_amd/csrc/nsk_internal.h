@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "nsk.h"
 
 namespace nsk {
@@ -22,6 +24,16 @@ inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t elem_size(int dtype) { return dtype == NSK_BF16 ? 2 : 4; }
 
+// Compile-time loop: f(std::integral_constant<int, B>), ..., f(std::integral_constant<int, E - 1>).  For loop bodies
+// whose index must be a constant expression (register arrays, per-iteration schedules chosen with `if constexpr`).
+template <int B, int E, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    if constexpr (B < E) {
+        f(std::integral_constant<int, B>{});
+        static_for<B + 1, E>(f);
+    }
+}
+
 // Block-wide barrier that orders LDS traffic only.  __syncthreads() also drains the wavefront's global loads
 // (its fence covers global memory), which would end every register prefetch at each barrier; kernels whose
 // wavefronts exchange data through LDS alone use this one and keep their loads in flight across it.
@@ -35,7 +47,7 @@ __device__ inline void lds_barrier()
 // Test and A/B switches: environment variables NSK_*, read ONCE (first use, or nsk_test_hooks_reload()) and never on
 // the launch path.  Each one only narrows or widens the choice among kernels that all compute the same result.
 struct TestHooks {
-    bool no_big, no_big_multi, no_pw, no_halo, no_halo_wide, halo_wide_always, halo_single, no_stem, no_stem_halo,
+    bool no_big, no_big_multi, no_pw, no_halo, no_fs, no_halo_wide, halo_wide_always, halo_single, no_stem, no_stem_halo,
         no_tiny, no_wide, no_depthwise, depthwise_no_rows, depthwise_no_cols, pool_general, stats_always, reduce4,
         wh_no_split;
     long long big_min_tiles, pw_min_rows, wide_min_rows;   // -1: not set

@@ -387,6 +387,50 @@ def test_halo_backward_weight_many_chunks_per_block(dtype, nsk_env):
     assert torch.equal(plain, dw_view)
 
 
+# bf16 3x3 stride-1 64->64 layers, forward and backward-data: the filter-stationary kernel (128- or 256-position
+# tiles; blocks that walk several tiles; ragged last tile; images wider than the 256-position ring allows) and, with
+# NSK_NO_FS, the kernels that keep the filter in LDS.  N, H, W
+FS_SHAPES = [(3, 20, 24), (16, 56, 56), (5, 7, 61), (2, 9, 66), (40, 8, 8), (1, 1, 1), (9, 33, 17)]
+
+
+@pytest.mark.parametrize("no_fs", [False, True], ids=["filter_in_registers", "filter_in_lds"])
+@pytest.mark.parametrize("i", range(len(FS_SHAPES)))
+def test_conv_64_to_64_kernels(i, no_fs, nsk_env):
+    N, H, W = FS_SHAPES[i]
+    if no_fs:
+        nsk_env("NSK_NO_FS", "1")
+    print(f"64->64 case {FS_SHAPES[i]} no_fs={no_fs}", flush=True)
+    x = on_grid(gen.normal(1500 + i, 0, (N, 64, H, W)), "bf16")
+    w = on_grid(gen.he_normal(1500 + i, 1, (64, 64, 3, 3)), "bf16")
+    dy = on_grid(gen.normal(1500 + i, 2, (N, 64, H, W)), "bf16")
+    ws = B.Workspace()
+    gx, gw, gdy = (to_gpu(a, "bf16", B.NSK_NHWC) for a in (x, w, dy))
+    y, check_y = guarded((N, H, W, 64), torch.bfloat16)
+    dx, check_dx = guarded((N, H, W, 64), torch.bfloat16)
+    B.conv2d_fwd(gx, gw, 1, 1, 1, out=y, ws=ws)
+    B.conv2d_dgrad(gdy, gw, (N, 64, H, W), 1, 1, 1, out=dx, ws=ws)
+    y_s, stats = B.conv2d_fwd_stats(gx, gw, 1, 1, 1, ws=ws)
+    torch.cuda.synchronize()
+    check_y()
+    check_dx()
+    want_y = oracle.conv2d_fwd(x, w, 1, 1, 1)
+    assert max_rel_err(to_host(y, B.NSK_NHWC), want_y) <= TOL["bf16"]
+    assert max_rel_err(to_host(dx, B.NSK_NHWC), oracle.conv2d_dgrad(dy, w, x.shape, 1, 1, 1)) <= TOL["bf16"]
+    assert torch.equal(y, y_s)
+    # the partial sums against the oracle's y on the storage grid (a stored value may differ from it by one rounding)
+    y_grid = on_grid(want_y.astype(np.float32), "bf16")
+    sums = stats.double().sum(dim=1).cpu().numpy()
+    M = N * H * W
+    sigma = np.sqrt((y_grid * y_grid).sum(axis=(0, 2, 3)) / M) + 1e-30
+    assert np.max(np.abs(sums[0] - y_grid.sum(axis=(0, 2, 3))) / (M * sigma)) <= 1e-3
+    assert np.max(np.abs(sums[1] - (y_grid * y_grid).sum(axis=(0, 2, 3))) / (M * sigma * sigma)) <= 1e-3
+    # accumulating backward-data (one rounding of old + sum)
+    old = on_grid(gen.normal(1500 + i, 3, (N, 64, H, W)), "bf16")
+    acc = to_gpu(old, "bf16", B.NSK_NHWC)
+    B.conv2d_dgrad(gdy, gw, (N, 64, H, W), 1, 1, 1, out=acc, accumulate=True, ws=ws)
+    assert max_rel_err(to_host(acc, B.NSK_NHWC), oracle.conv2d_dgrad(dy, w, x.shape, 1, 1, 1, into=old.astype(np.float64))) <= TOL["bf16"]
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_conv_is_bitwise_reproducible(dtype):
     x, w, dy, st, pd, dl = _conv_case(1, dtype)
