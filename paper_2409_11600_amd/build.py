@@ -12,7 +12,7 @@ INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libnsk.so")
 OBJ = os.path.join(HERE, "_build")
 
-SOURCES = ["nsk_api.hip", "conv_igemm.hip", "conv_igemm_big.hip", "conv_pw.hip", "conv_pw_narrow16.hip", "conv_pw_narrow32.hip", "conv_halo64.hip", "conv_halo_wide.hip", "conv_halo64_f32.hip", "conv_wgrad.hip", "conv_depthwise.hip", "conv_tiny.hip", "conv_wgrad_halo64.hip", "conv_wgrad_wide.hip", "conv_stem.hip", "conv_stem_halo.hip", "layout.hip", "bn.hip", "pool.hip", "tail.hip", "recurrent.hip", "pool_mem.hip"]
+SOURCES = ["nsk_api.hip", "conv_igemm.hip", "conv_igemm_big.hip", "conv_pw.hip", "conv_pw_narrow16.hip", "conv_pw_narrow32.hip", "conv_halo64.hip", "conv_fs64_s2.hip", "conv_halo_wide.hip", "conv_halo64_f32.hip", "conv_wgrad.hip", "conv_depthwise.hip", "conv_tiny.hip", "conv_wgrad_halo64.hip", "conv_wgrad_wide.hip", "conv_stem.hip", "conv_stem_halo.hip", "layout.hip", "bn.hip", "pool.hip", "tail.hip", "recurrent.hip", "pool_mem.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", INCLUDE, "-I", CSRC]

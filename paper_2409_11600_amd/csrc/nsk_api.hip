@@ -530,7 +530,9 @@ static int conv_dgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *
     // one packing launch for all classes, then their multiplies
     if (n_pending > 0)
         NSK_TRY(launch_pack_filters_grouped(g.dtype, n_pending, w, pk_out, cg, pk_nt, kg, w_sn, w_sc, pk_taps, groups, w_gstep, st));
-    if (n_pending > 1 && groups == 1 && halo_wide_multi_applicable(g.dtype, pending, n_pending)) {
+    if (n_pending == 4 && groups == 1 && fs64_dgrad_s2_applicable(g.dtype, pending, n_pending)) {
+        NSK_TRY(launch_fs64_dgrad_s2(pending, n_pending, st));
+    } else if (n_pending > 1 && groups == 1 && halo_wide_multi_applicable(g.dtype, pending, n_pending)) {
         NSK_TRY(launch_halo_wide_multi(pending, n_pending, st));
     } else if (n_pending > 1 && groups == 1 && igemm_big_multi_applicable(g.dtype, pending, n_pending)) {
         NSK_TRY(launch_igemm_big_multi(pending, n_pending, st));

@@ -138,6 +138,10 @@ int halo64_stats_rows(const IgemmArgs &a);
 bool halo_wide_applicable(int dtype, const IgemmArgs &a);
 int launch_halo_wide(const IgemmArgs &a, hipStream_t stream);
 int halo_wide_stats_rows(const IgemmArgs &a);
+// the four residue classes of the backward-data pass of a bf16 3x3 stride-2 64 -> 64 layer in one launch of the
+// filter-stationary kernel (conv_fs64_s2.hip)
+bool fs64_dgrad_s2_applicable(int dtype, const IgemmArgs *a, int count);
+int launch_fs64_dgrad_s2(const IgemmArgs *a, int count, hipStream_t stream);
 // the residue classes of one strided backward-data pass of such a layer in one launch, sharing the staged tiles
 bool halo_wide_multi_applicable(int dtype, const IgemmArgs *a, int count);
 int launch_halo_wide_multi(const IgemmArgs *a, int count, hipStream_t stream);

@@ -431,6 +431,33 @@ def test_conv_64_to_64_kernels(i, no_fs, nsk_env):
     assert max_rel_err(to_host(acc, B.NSK_NHWC), oracle.conv2d_dgrad(dy, w, x.shape, 1, 1, 1, into=old.astype(np.float64))) <= TOL["bf16"]
 
 
+# bf16 3x3 stride-2 pad-1 64->64 layers on even extents: backward-data of all four residue classes in one launch of
+# the filter-stationary kernel (blocks that walk several tiles, ragged last tile, tiles that span many small images);
+# with NSK_NO_FS the same problems on the kernels that take the classes otherwise.  N, H, W
+FS_S2_SHAPES = [(8, 112, 112), (20, 60, 68), (70, 30, 34), (300, 14, 14), (2100, 4, 6)]
+
+
+@pytest.mark.parametrize("no_fs", [False, True], ids=["filter_in_registers", "other_kernels"])
+@pytest.mark.parametrize("i", range(len(FS_S2_SHAPES)))
+def test_conv_64_to_64_stride2_backward_data(i, no_fs, nsk_env):
+    N, H, W = FS_S2_SHAPES[i]
+    if no_fs:
+        nsk_env("NSK_NO_FS", "1")
+    print(f"64->64 stride 2 dgrad case {FS_S2_SHAPES[i]} no_fs={no_fs}", flush=True)
+    w = on_grid(gen.he_normal(1600 + i, 1, (64, 64, 3, 3)), "bf16")
+    dy = on_grid(gen.normal(1600 + i, 2, (N, 64, H // 2, W // 2)), "bf16")
+    ws = B.Workspace()
+    gw, gdy = to_gpu(w, "bf16", B.NSK_NHWC), to_gpu(dy, "bf16", B.NSK_NHWC)
+    dx, check_dx = guarded((N, H, W, 64), torch.bfloat16)
+    B.conv2d_dgrad(gdy, gw, (N, 64, H, W), 2, 1, 1, out=dx, ws=ws)
+    torch.cuda.synchronize()
+    check_dx()
+    want = oracle.conv2d_dgrad(dy, w, (N, 64, H, W), 2, 1, 1)
+    assert max_rel_err(to_host(dx, B.NSK_NHWC), want) <= TOL["bf16"]
+    dx2 = B.conv2d_dgrad(gdy, gw, (N, 64, H, W), 2, 1, 1, ws=ws)
+    assert torch.equal(dx, dx2)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_conv_is_bitwise_reproducible(dtype):
     x, w, dy, st, pd, dl = _conv_case(1, dtype)
