@@ -271,10 +271,9 @@ __global__ __launch_bounds__(256) void conv_fs64_dgrad_s2_kernel(const S2Args a)
                 for (int u = g * 4; u < (g + 1) * 4; ++u) offI[u] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * u) * 4, (int)mineI);
             }
             if constexpr (k == S2_CL) {
-                if (p + 1 < n) {
-                    const unsigned r = wrap(cbase + (unsigned)(8 * g));   // a row of the next tile
-                    *(u32x4 *)(ring + __umul24(r, (unsigned)S2_SLOT) + chunk * 16) = st[g];
-                }
+                // a row of the next tile (after the block's last tile: rows nobody reads; no branch in this loop)
+                const unsigned r = wrap(cbase + (unsigned)(8 * g));
+                *(u32x4 *)(ring + __umul24(r, (unsigned)S2_SLOT) + chunk * 16) = st[g];
                 st[g] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, offI[g] + (unsigned)(chunk * 16), 0, 0);
             }
         };
@@ -289,12 +288,10 @@ __global__ __launch_bounds__(256) void conv_fs64_dgrad_s2_kernel(const S2Args a)
                 // output pipeline: classes 0..2 of this tile, class 3 of the previous one
                 static_for<0, 4>([&](auto cc) {
                     constexpr int oc = decltype(cc)::value, rel = pair - s2_out_base(oc);
-                    if constexpr (rel >= 0 && rel < 8) {
-                        if (oc < 3 || p > 0) out_read(cc, std::integral_constant<int, rel>{}, oc < 3 ? mineF : mineF_prev);
-                    }
-                    if constexpr (rel >= 2 && rel < 10) {
-                        if (oc < 3 || p > 0) out_store(cc, std::integral_constant<int, rel - 2>{});
-                    }
+                    // (in a block's first tile class 3 "of the previous tile" reads an unwritten strip and stores it at
+                    // mineF_prev = out of range, i.e. nowhere)
+                    if constexpr (rel >= 0 && rel < 8) out_read(cc, std::integral_constant<int, rel>{}, oc < 3 ? mineF : mineF_prev);
+                    if constexpr (rel >= 2 && rel < 10) out_store(cc, std::integral_constant<int, rel - 2>{});
                 });
             }
             // conversion pieces scheduled in front of this MFMA
@@ -302,8 +299,7 @@ __global__ __launch_bounds__(256) void conv_fs64_dgrad_s2_kernel(const S2Args a)
                 static_for<0, 2>([&](auto mic) {
                     constexpr S2Epi e = s2_epi(decltype(cc)::value, decltype(mic)::value, i);
                     if constexpr (e.count > 0) {
-                        if (!(decltype(cc)::value == 3 && decltype(mic)::value == 1) || p > 0)
-                            static_for<0, e.count>([&](auto kc) { epilogue_piece(cc, mic, std::integral_constant<int, e.first + decltype(kc)::value>{}); });
+                        static_for<0, e.count>([&](auto kc) { epilogue_piece(cc, mic, std::integral_constant<int, e.first + decltype(kc)::value>{}); });
                     }
                 });
             });

@@ -851,20 +851,18 @@ __global__ __launch_bounds__(256) void conv_fs64_kernel(const HaloArgs a)
                 for (int u = g * 4; u < (g + 1) * 4 && u < NLD; ++u) offI[u] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * u) * 4, (int)mineI);
             }
             if constexpr (k == F_CL) {
-                if (p + 1 < n) {
-                    // a row of the next tile: unwrapped row cs + TILE + 2*halo + ... (below 2*RING)
-                    const unsigned r = wrap(cbase + (unsigned)(8 * g));
-                    *(u32x4 *)(ring + __umul24(r, (unsigned)F_SLOT) + chunk * 16) = st[g];
-                }
+                // a row of the next tile: unwrapped row cs + TILE + 2*halo + ... (below 2*RING); after the block's last
+                // tile these are rows nobody reads (this loop has no branches: every one costs an instruction refetch)
+                const unsigned r = wrap(cbase + (unsigned)(8 * g));
+                *(u32x4 *)(ring + __umul24(r, (unsigned)F_SLOT) + chunk * 16) = st[g];
                 st[g] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, offI[g] + (unsigned)(chunk * 16), 0, 0);
             }
-            if (p > 0) {   // (uniform) the outputs of the previous tile
-                if constexpr (k == F_FA1) so1((T0 + p - 1) * TILE + WPOS * x + (lane & (WPOS - 1)));
-                if constexpr (k == F_FA2) so2();
-                if constexpr (k == F_FB1) so3();
-                if constexpr (k == F_FB2) so4();
-                if constexpr (k == F_FB3) mineF = so5();
-            }
+            // the outputs of the previous tile (in a block's first tile: stored nowhere, their offset is out of range)
+            if constexpr (k == F_FA1) so1((T0 + p - 1) * TILE + WPOS * x + (lane & (WPOS - 1)));
+            if constexpr (k == F_FA2) so2();
+            if constexpr (k == F_FB1) so3();
+            if constexpr (k == F_FB2) so4();
+            if constexpr (k == F_FB3) mineF = p > 0 ? so5() : H_OOB;
         };
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi) tap_addr(0, mi);
@@ -876,29 +874,23 @@ __global__ __launch_bounds__(256) void conv_fs64_kernel(const HaloArgs a)
             if constexpr (ni == 0) {
                 if constexpr (pair + DIST < NPAIR) fetch(std::integral_constant<int, pair + DIST>{});
                 if constexpr (STATS && fs_out_count<MI>(pair) >= 0) {
-                    if (p > 0) static_for<0, (MI == 2 ? 1 : 4)>([&](auto dc) { stats_piece(std::integral_constant<int, fs_out_count<MI>(pair) + decltype(dc)::value>{}); });
+                    static_for<0, (MI == 2 ? 1 : 4)>([&](auto dc) { stats_piece(std::integral_constant<int, fs_out_count<MI>(pair) + decltype(dc)::value>{}); });
                 }
             } else {
                 side(std::integral_constant<int, pair>{});
                 if constexpr (fs_out_read<MI>(pair) >= 0) {
                     constexpr int g = fs_out_read<MI>(pair);
-                    if (p > 0) {
-                        sv[g] = *(const u32x4 *)(strip + (prow + 8 * g) * F_SLOT + chunk * 16);
-                        ooff[g] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * g) * 4, (int)mineF);
-                    }
+                    sv[g] = *(const u32x4 *)(strip + (prow + 8 * g) * F_SLOT + chunk * 16);
+                    ooff[g] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * g) * 4, (int)mineF);
                 }
                 if constexpr (fs_out_store<MI>(pair) >= 0) {
                     constexpr int g = fs_out_store<MI>(pair);
-                    if (p > 0) {
-                        __builtin_amdgcn_raw_buffer_store_b128(sv[g], out_rsrc, ooff[g] + (unsigned)(chunk * 16), 0, 0);
-                        if (STATS && ooff[g] >= H_OOB) sv[g] = u32x4{0u, 0u, 0u, 0u};   // padding positions are not stored and not counted
-                    }
+                    __builtin_amdgcn_raw_buffer_store_b128(sv[g], out_rsrc, ooff[g] + (unsigned)(chunk * 16), 0, 0);
+                    if (STATS && ooff[g] >= H_OOB) sv[g] = u32x4{0u, 0u, 0u, 0u};   // padding positions are not stored and not counted
                 }
             }
             if constexpr (MI == 2) {
-                if constexpr (fs_epilogue1(i) >= 0) {
-                    if (p > 0) epilogue_piece(std::integral_constant<int, 1>{}, std::integral_constant<int, fs_epilogue1(i)>{});
-                }
+                if constexpr (fs_epilogue1(i) >= 0) epilogue_piece(std::integral_constant<int, 1>{}, std::integral_constant<int, fs_epilogue1(i)>{});
                 if constexpr (fs_epilogue0(i) >= 0) epilogue_piece(std::integral_constant<int, 0>{}, std::integral_constant<int, fs_epilogue0(i)>{});
             }
             __builtin_amdgcn_sched_barrier(0);
