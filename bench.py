@@ -65,6 +65,10 @@ def parse():
                     help="keep the ReLU-mask hand-over but let every batch-norm compute its own statistics")
     ap.add_argument("--no-fusion", action="store_true",
                     help="plain entry points only: no statistics hand-over from convolution to batch-norm, no ReLU mask")
+    ap.add_argument("--fused-act", action="store_true",
+                    help="a conv + batch-norm + ReLU that feeds one convolution does not store its normalised activation: that "
+                         "convolution applies it on load (measured: no gain on configuration 2, whose kernels have the fused "
+                         "load, 3-5%% slower where the activation is applied into the workspace instead; off by default)")
     ap.add_argument("--overlap", action="store_true",
                     help="issue the backward-weight calls on a second stream (measured: no gain on MI355X, the "
                          "convolution kernels already hold every CU)")
@@ -399,7 +403,9 @@ def main():
     wl = gen.workload(a.config, batch=a.batch, stage=a.stage)
     tensors = gen.workload_tensors(wl)
     layout = B.NSK_NHWC if a.layout == "nhwc" else B.NSK_NCHW
-    net = GpuNetwork(wl, tensors, layout=layout, use_relu_mask=not a.no_fusion, use_fused_stats=not (a.no_fusion or a.no_stats))
+    fused_act = a.fused_act and not (a.no_fusion or a.no_stats) and a.layout == "nhwc"
+    net = GpuNetwork(wl, tensors, layout=layout, use_relu_mask=not a.no_fusion, use_fused_stats=not (a.no_fusion or a.no_stats),
+                     use_fused_act=fused_act)
     batch = wl["input"][0]
     calls = net.fwd_calls + net.bwd_calls
     costs = [call_cost(net, f, args) for f, args in calls]
@@ -498,6 +504,7 @@ def main():
         "dtype": "f32" if wl["dtype"] == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{wl['name']}: {len(wl['units'])} units, input {list(wl['input'])}, "
                                f"{a.layout}, forward+backward", "batch": batch, "hip_graph": graph is not None, "fused_bn_statistics": not (a.no_fusion or a.no_stats), "relu_mask": not a.no_fusion,
+                   "activations_applied_on_load": sorted(net.fused_away),
                    "streams": 1 if side is None else 2},
         "conv_tflops": conv_flops / (conv_ms * 1e-3) / 1e12,
         "conv_frac_of_mfma_peak": conv_flops / (conv_ms * 1e-3) / PEAK["mfma_bf16" if wl["dtype"] == "bf16" else "mfma_f32"],

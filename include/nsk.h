@@ -229,6 +229,39 @@ int nsk_bn_relu_add_bwd_mask(const nsk_bn_desc_t *desc, const void *x, const uns
                              const float *save_invstd, void *dx, void *dresidual, float *dgamma,
                              float *dbeta, void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- Batch-norm + ReLU applied by the consumers of a convolution's output (the conclusion of the paper names ReLU-fused
+ * operations as future work).  In conv -> batch-norm -> ReLU -> conv the normalised activation a = relu(scale*y + shift)
+ * need not be stored: the second convolution (and, in the backward pass, its backward-weight call) applies it to the raw
+ * y while loading its operand, and the backward pass of the batch-norm takes the ReLU mask from y as well.  One write
+ * and one read of the activation disappear.  NHWC only, relu = 1, no residual on the fused batch-norm (NSK_ERR_UNSUPPORTED
+ * otherwise, and for channel counts the 16-byte vector kernels do not take: see nsk_bn_mask_bytes).
+ *
+ * nsk_bn_fwd_coeffs: the batch statistics from partial sums of y and y*y (as nsk_bn_relu_add_fwd_stats takes them) and
+ *   coeffs[c] = scale = gamma*invstd, coeffs[C + c] = shift = beta - mean*scale (2*C floats, device memory); no pass
+ *   over y.  Workspace: nsk_bn_workspace_bytes(desc, NSK_BN_FWD).
+ * nsk_conv2d_fwd_act / nsk_conv2d_wgrad_act: nsk_conv2d_fwd[_stats] / nsk_conv2d_wgrad with x replaced by
+ *   relu(coeffs[c]*x + coeffs[C + c]) rounded to desc->dtype, the value the apply pass would have stored (zero padding
+ *   stays zero); coeffs belong to the C input channels of desc.  stats may be NULL.  Kernels with a fused operand load
+ *   (the fp32 3x3 64 -> 64 layers on 32-pixel-wide images) read x once and store nothing extra; every other layer is
+ *   served by applying the activation into the workspace first (same results, no saving).  Workspace:
+ *   nsk_conv2d_act_workspace_bytes(desc, NSK_PASS_FWD | NSK_PASS_WGRAD) (host only; may be 0 for a fused kernel);
+ *   nsk_conv2d_act_supported(desc) says whether the two calls take the layer at all.
+ * nsk_bn_relu_bwd_act: nsk_bn_relu_add_bwd for that batch-norm without `out` and without a residual: the ReLU mask is
+ *   [coeffs[c]*x + coeffs[C + c] > 0], the expression the consumers used.  Workspace: nsk_bn_workspace_bytes(desc,
+ *   NSK_BN_BWD). */
+int nsk_bn_fwd_coeffs(const nsk_bn_desc_t *desc, const float *gamma, const float *beta, const float *stats,
+                      int stats_rows, float *save_mean, float *save_invstd, float *running_mean,
+                      float *running_var, float *coeffs, void *workspace, size_t workspace_bytes, void *stream);
+int nsk_conv2d_act_supported(const nsk_conv_desc_t *desc);   /* 1 / 0, host only */
+size_t nsk_conv2d_act_workspace_bytes(const nsk_conv_desc_t *desc, int pass);
+int nsk_conv2d_fwd_act(const nsk_conv_desc_t *desc, const void *x, const float *coeffs, const void *w, void *y,
+                       float *stats, void *workspace, size_t workspace_bytes, void *stream);
+int nsk_conv2d_wgrad_act(const nsk_conv_desc_t *desc, const void *x, const float *coeffs, const void *dy, float *dw,
+                         int accumulate, void *workspace, size_t workspace_bytes, void *stream);
+int nsk_bn_relu_bwd_act(const nsk_bn_desc_t *desc, const void *x, const float *coeffs, const void *dout,
+                        const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
+                        float *dgamma, float *dbeta, void *workspace, size_t workspace_bytes, void *stream);
+
 /* Output extent of a pooling descriptor.  Host only. */
 int nsk_maxpool2d_out_dims(const nsk_pool_desc_t *desc, int *P, int *Q);
 

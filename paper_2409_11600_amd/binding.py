@@ -107,6 +107,18 @@ def lib() -> ctypes.CDLL:
         L.nsk_bn_workspace_bytes.argtypes = [bd, ci]
         L.nsk_bn_relu_add_fwd.restype = ci
         L.nsk_bn_relu_add_fwd.argtypes = [bd] + [vp] * 10 + [sz, vp]
+        L.nsk_bn_fwd_coeffs.restype = ci
+        L.nsk_bn_fwd_coeffs.argtypes = [bd, vp, vp, vp, ci, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.nsk_conv2d_act_supported.restype = ci
+        L.nsk_conv2d_act_supported.argtypes = [cd]
+        L.nsk_conv2d_act_workspace_bytes.restype = sz
+        L.nsk_conv2d_act_workspace_bytes.argtypes = [cd, ci]
+        L.nsk_conv2d_fwd_act.restype = ci
+        L.nsk_conv2d_fwd_act.argtypes = [cd, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.nsk_conv2d_wgrad_act.restype = ci
+        L.nsk_conv2d_wgrad_act.argtypes = [cd, vp, vp, vp, vp, ci, vp, sz, vp]
+        L.nsk_bn_relu_bwd_act.restype = ci
+        L.nsk_bn_relu_bwd_act.argtypes = [bd] + [vp] * 10 + [sz, vp]
         L.nsk_static_scratch_bytes.restype = sz
         L.nsk_static_scratch_bytes.argtypes = []
         L.nsk_bn_relu_add_fwd_static.restype = ci
@@ -198,7 +210,8 @@ EXPORTS = ("nsk_version", "nsk_test_hooks_reload", "nsk_status_string", "nsk_las
            "nsk_conv2d_workspace_bytes", "nsk_conv2d_fwd", "nsk_conv2d_dgrad", "nsk_conv2d_wgrad",
            "nsk_conv2d_grouped_workspace_bytes", "nsk_conv2d_grouped_fwd", "nsk_conv2d_grouped_dgrad",
            "nsk_conv2d_grouped_wgrad",
-           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_static_scratch_bytes", "nsk_bn_relu_add_fwd_static",
+           "nsk_bn_workspace_bytes", "nsk_bn_relu_add_fwd", "nsk_bn_fwd_coeffs", "nsk_conv2d_act_supported", "nsk_conv2d_act_workspace_bytes",
+           "nsk_conv2d_fwd_act", "nsk_conv2d_wgrad_act", "nsk_bn_relu_bwd_act", "nsk_static_scratch_bytes", "nsk_bn_relu_add_fwd_static",
            "nsk_bn_relu_add_bwd", "nsk_bn_mask_bytes",
            "nsk_bn_relu_add_fwd_mask", "nsk_bn_relu_add_bwd_mask", "nsk_conv2d_stats_rows", "nsk_conv2d_fwd_stats",
            "nsk_bn_relu_add_fwd_stats", "nsk_maxpool2d_out_dims",
@@ -471,6 +484,73 @@ def bn_relu_add_fwd(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=N
                                      _ptr(save_mean), _ptr(save_invstd), _ptr(running_mean), _ptr(running_var),
                                      wp, wb, _stream()), "nsk_bn_relu_add_fwd")
     return out, save_mean, save_invstd
+
+
+def bn_fwd_coeffs(y, gamma, beta, stats, eps=1e-5, layout=NSK_NHWC, momentum=0.1, running_mean=None, running_var=None,
+                  ws: Optional[Workspace] = None):
+    """Batch statistics of y from its partial sums and the coefficients of the activation relu(scale*y + shift) that
+    the consumers of y apply on load: returns (save_mean, save_invstd, coeffs) with coeffs float32 [2, C]."""
+    d = bn_desc(y, layout, eps, momentum, True)
+    mean = torch.empty(d.C, dtype=torch.float32, device=y.device)
+    invstd = torch.empty(d.C, dtype=torch.float32, device=y.device)
+    coeffs = torch.empty((2, d.C), dtype=torch.float32, device=y.device)
+    ws = ws or Workspace(y.device)
+    wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_FWD))
+    _check(lib().nsk_bn_fwd_coeffs(ctypes.byref(d), _ptr(gamma), _ptr(beta), _ptr(stats), int(stats.shape[1]), _ptr(mean),
+                                   _ptr(invstd), _ptr(running_mean), _ptr(running_var), _ptr(coeffs), wp, wb, _stream()),
+           "nsk_bn_fwd_coeffs")
+    return mean, invstd, coeffs
+
+
+def conv2d_fwd_act(x, coeffs, w, stride=1, pad=0, dilation=1, out=None, want_stats=False, ws: Optional[Workspace] = None):
+    """Forward convolution of relu(coeffs[0]*x + coeffs[1]) (NHWC).  Returns y, or (y, stats) with want_stats."""
+    N, C, H, W = _logical(x, NSK_NHWC)
+    K, Cw, R, S = _filter_logical(w, NSK_NHWC)
+    assert Cw == C and w.dtype == x.dtype and coeffs.numel() == 2 * C
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), NSK_NHWC)
+    P, Q = conv2d_out_dims(d)
+    if out is None:
+        out = torch.empty(_act_shape(N, K, P, Q, NSK_NHWC), dtype=x.dtype, device=x.device)
+    stats = None
+    if want_stats:
+        rows = int(lib().nsk_conv2d_stats_rows(ctypes.byref(d)))
+        stats = torch.empty((2, rows, K), dtype=torch.float32, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_act_workspace_bytes(ctypes.byref(d), NSK_PASS_FWD))
+    _check(lib().nsk_conv2d_fwd_act(ctypes.byref(d), _ptr(x), _ptr(coeffs), _ptr(w), _ptr(out), _ptr(stats), wp, wb, _stream()),
+           "nsk_conv2d_fwd_act")
+    return (out, stats) if want_stats else out
+
+
+def conv2d_wgrad_act(x, coeffs, dy, filt_logical, stride=1, pad=0, dilation=1, out=None, accumulate=False,
+                     ws: Optional[Workspace] = None):
+    """Backward-weight with x replaced by relu(coeffs[0]*x + coeffs[1]) (NHWC)."""
+    N, C, H, W = _logical(x, NSK_NHWC)
+    K, Cw, R, S = filt_logical
+    assert Cw == C and x.dtype == dy.dtype
+    d = conv_desc((N, C, H, W), (K, R, S), stride, pad, dilation, _dtype_code(x), NSK_NHWC)
+    if out is None:
+        assert not accumulate
+        out = torch.empty((K, R, S, C), dtype=torch.float32, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_conv2d_act_workspace_bytes(ctypes.byref(d), NSK_PASS_WGRAD))
+    _check(lib().nsk_conv2d_wgrad_act(ctypes.byref(d), _ptr(x), _ptr(coeffs), _ptr(dy), _ptr(out), int(bool(accumulate)), wp, wb,
+                                      _stream()), "nsk_conv2d_wgrad_act")
+    return out
+
+
+def bn_relu_bwd_act(x, coeffs, dout, gamma, save_mean, save_invstd, eps=1e-5, ws: Optional[Workspace] = None):
+    """Backward of a batch-norm + ReLU whose output was never stored: returns (dx, dgamma, dbeta)."""
+    d = bn_desc(x, NSK_NHWC, eps, 0.1, True)
+    dx = torch.empty_like(x)
+    dgamma = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    dbeta = torch.empty(d.C, dtype=torch.float32, device=x.device)
+    ws = ws or Workspace(x.device)
+    wp, wb = ws.get(lib().nsk_bn_workspace_bytes(ctypes.byref(d), NSK_BN_BWD))
+    _check(lib().nsk_bn_relu_bwd_act(ctypes.byref(d), _ptr(x), _ptr(coeffs), _ptr(dout), _ptr(gamma), _ptr(save_mean),
+                                     _ptr(save_invstd), _ptr(dx), _ptr(dgamma), _ptr(dbeta), wp, wb, _stream()),
+           "nsk_bn_relu_bwd_act")
+    return dx, dgamma, dbeta
 
 
 def bn_relu_add_fwd_static(x, gamma, beta, residual=None, eps=1e-5, relu=True, layout=NSK_NHWC, momentum=0.1,

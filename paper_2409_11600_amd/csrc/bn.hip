@@ -66,17 +66,22 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
                                                       const float *__restrict__ invstd, int relu, long M, int C,
                                                       long rows_per_block, float *__restrict__ p0,
                                                       float *__restrict__ p1, unsigned char *__restrict__ mask,
-                                                      const unsigned char *__restrict__ mask_in, int noshift = 0)
+                                                      const unsigned char *__restrict__ mask_in, int noshift = 0,
+                                                      const float *__restrict__ act = nullptr)
 {
     typedef typename BT<T>::Vec Vec;
     constexpr int VEC = BT<T>::VEC;
     const int CV = C / VEC, RP = 256 / CV;
     const int cv = threadIdx.x % CV, rr = threadIdx.x / CV;
-    float s0[VEC], s1[VEC], sh[VEC], sc[VEC];
+    float s0[VEC], s1[VEC], sh[VEC], sc[VEC], as[VEC], ab[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
         s0[e] = 0.f;
         s1[e] = 0.f;
+        // act: the normalised activation was never stored (its consumers applied scale and shift on load): the ReLU
+        // mask is recomputed from x with the same coefficients and the same expression
+        as[e] = MODE == 1 && act ? act[cv * VEC + e] : 0.f;
+        ab[e] = MODE == 1 && act ? act[C + cv * VEC + e] : 0.f;
         if (MODE == 0) {
             sh[e] = noshift ? 0.f : (float)x[cv * VEC + e];
             sc[e] = 1.f;
@@ -103,6 +108,10 @@ __global__ __launch_bounds__(256) void bn_reduce_nhwc(const T *__restrict__ x, c
             unsigned bits = 0;
             if (mask_in) {
                 bits = mask_in[off / VEC];        // handed over by the forward pass: `out` is not read at all
+            } else if (act) {
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) bits |= ((float)(T)((float)xv[e] * as[e] + ab[e]) > 0.f ? 1u : 0u) << e;
+                mask[off / VEC] = (unsigned char)bits;
             } else if (relu) {
                 const Vec ov = *(const Vec *)(out + off);
 #pragma unroll
@@ -517,16 +526,17 @@ int bn_fwd_typed(const nsk_bn_desc_t &d, const T *x, const T *res, const float *
 template <typename T>
 int bn_bwd_typed(const nsk_bn_desc_t &d, const T *x, const T *out, const T *dout, const float *gamma,
                  const float *mean, const float *invstd, T *dx, T *dres, float *dgamma, float *dbeta, float *ws,
-                 const unsigned char *mask_in, hipStream_t stream)
+                 const unsigned char *mask_in, hipStream_t stream, const float *act = nullptr)
 {
     const Geom g = geometry(d, true);
+    if (act && !(g.fast && d.relu)) return NSK_ERR_UNSUPPORTED;
     float *p0 = ws, *p1 = ws + (long)g.G * d.C, *coef = p1 + (long)g.G * d.C;
     // the ReLU mask bytes follow the float part of the workspace (see bn_mask_bytes)
     unsigned char *mask = (unsigned char *)ws + align_up((2 * (size_t)bn_partial_blocks(d) * d.C + 4 * (size_t)d.C) * sizeof(float));
     constexpr int VEC = BT<T>::VEC;
     if (g.fast) {
         hipLaunchKernelGGL((bn_reduce_nhwc<T, 1>), dim3(g.G), dim3(256), 0, stream, x, out, dout, mean, invstd,
-                           d.relu, g.M, d.C, g.rows_per_block, p0, p1, mask, mask_in);
+                           d.relu, g.M, d.C, g.rows_per_block, p0, p1, mask, mask_in, 0, act);
     } else {
         hipLaunchKernelGGL((bn_reduce_generic<T, 1>), dim3(d.C, g.G), dim3(256), 0, stream, x, out, dout, mean,
                            invstd, d.relu, d.N, g.HW, g.sn, g.sc, g.ss, g.npg, d.C, p0, p1);
@@ -614,14 +624,63 @@ int launch_bn_stats(const nsk_bn_desc_t &d, const void *x, float *stats, hipStre
 
 int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout, const float *gamma,
                   const float *save_mean, const float *save_invstd, void *dx, void *dres, float *dgamma,
-                  float *dbeta, void *ws, const unsigned char *relu_mask, hipStream_t stream)
+                  float *dbeta, void *ws, const unsigned char *relu_mask, hipStream_t stream, const float *act)
 {
     if (d.dtype == NSK_BF16)
         return bn_bwd_typed<bf16_t>(d, (const bf16_t *)x, (const bf16_t *)out, (const bf16_t *)dout, gamma,
                                     save_mean, save_invstd, (bf16_t *)dx, (bf16_t *)dres, dgamma, dbeta,
-                                    (float *)ws, relu_mask, stream);
+                                    (float *)ws, relu_mask, stream, act);
     return bn_bwd_typed<float>(d, (const float *)x, (const float *)out, (const float *)dout, gamma, save_mean,
-                               save_invstd, (float *)dx, (float *)dres, dgamma, dbeta, (float *)ws, relu_mask, stream);
+                               save_invstd, (float *)dx, (float *)dres, dgamma, dbeta, (float *)ws, relu_mask, stream, act);
+}
+
+// True if the fused-activation calls take this tensor: NHWC with a channel count the vector kernels handle.
+bool bn_act_supported(const nsk_bn_desc_t &d) { return geometry(d, false).fast && geometry(d, true).fast; }
+
+// Batch statistics and the coefficients of out = scale*x + shift (scale = gamma*invstd, shift = beta - mean*scale) from
+// partial sums of x and x^2 ([2][stats_rows][C], not shifted), without the apply pass: coeffs = [2][C] floats.
+int launch_bn_coeffs(const nsk_bn_desc_t &d, const float *gamma, const float *beta, const float *stats, int stats_rows,
+                     float *save_mean, float *save_invstd, float *running_mean, float *running_var, float *coeffs,
+                     void *ws, hipStream_t stream)
+{
+    const Geom g = geometry(d, false);
+    float *p0 = (float *)ws;
+    const float *q0 = stats, *q1 = stats + (long)stats_rows * d.C;
+    int rows = stats_rows;
+    if (stats_rows > 1024 && stats_rows > g.G) {
+        const int run = ceil_div(stats_rows, g.G), r2 = ceil_div(stats_rows, run);
+        hipLaunchKernelGGL(bn_stats_fold, dim3(r2), dim3(256), 0, stream, stats, stats_rows, d.C, run, p0, r2);
+        q0 = p0;
+        q1 = p0 + (long)r2 * d.C;
+        rows = r2;
+    }
+    if (d.dtype == NSK_BF16)
+        hipLaunchKernelGGL((bn_fwd_finalize<bf16_t>), dim3(d.C), dim3(256), 0, stream, q0, q1, rows, d.C, (double)g.M,
+                           (const bf16_t *)nullptr, 0L, gamma, beta, d.eps, d.momentum, save_mean, save_invstd,
+                           running_mean, running_var, coeffs, coeffs + d.C);
+    else
+        hipLaunchKernelGGL((bn_fwd_finalize<float>), dim3(d.C), dim3(256), 0, stream, q0, q1, rows, d.C, (double)g.M,
+                           (const float *)nullptr, 0L, gamma, beta, d.eps, d.momentum, save_mean, save_invstd,
+                           running_mean, running_var, coeffs, coeffs + d.C);
+    return check_launch();
+}
+
+// out = relu(scale*x + shift) with the coefficients of launch_bn_coeffs: the apply pass on its own, for consumers
+// whose kernel has no fused operand load.
+int launch_bn_act(const nsk_bn_desc_t &d, const void *x, const float *coeffs, void *out, hipStream_t stream)
+{
+    const Geom g = geometry(d, false);
+    if (!g.fast) return NSK_ERR_UNSUPPORTED;
+    if (d.dtype == NSK_BF16) {
+        const long nvec = g.total / BT<bf16_t>::VEC;
+        hipLaunchKernelGGL((bn_apply_nhwc<bf16_t, false, true>), dim3(stream_blocks(nvec)), dim3(256), 0, stream, (const bf16_t *)x,
+                           (const bf16_t *)nullptr, (bf16_t *)out, coeffs, coeffs + d.C, nvec, d.C, (unsigned char *)nullptr);
+    } else {
+        const long nvec = g.total / BT<float>::VEC;
+        hipLaunchKernelGGL((bn_apply_nhwc<float, false, true>), dim3(stream_blocks(nvec)), dim3(256), 0, stream, (const float *)x,
+                           (const float *)nullptr, (float *)out, coeffs, coeffs + d.C, nvec, d.C, (unsigned char *)nullptr);
+    }
+    return check_launch();
 }
 
 }  // namespace nsk

@@ -280,7 +280,7 @@ __global__ __launch_bounds__(256) void conv_fs64_dgrad_s2_kernel(const S2Args a)
         static_for<0, DIST>([&](auto pc) { fetch(pc); });
         static_for<0, 2 * NPAIR>([&](auto ic) {
             constexpr int i = decltype(ic)::value, pair = i >> 1, ni = i & 1;
-            constexpr int c = s2_class(pair), mi = s2_mi(pair), step = s2_gstep(pair);
+            constexpr int mi = s2_mi(pair), step = s2_gstep(pair);
             if constexpr (ni == 0) {
                 if constexpr (pair + DIST < NPAIR) fetch(std::integral_constant<int, pair + DIST>{});
             } else {

@@ -43,11 +43,12 @@ struct HaloF32Args {
     int tapoff[9];
     float *stats;      // forward only: per-channel partial sums of the stored output, or nullptr
     int stats_rows;    // 4 rows per block (one per wavefront)
+    const float *act;  // nullptr, or [2][64]: the input is relu(act[c]*src + act[64+c]), applied while the tile is staged
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-template <bool ACCUM>
+template <bool ACCUM, bool ACT = false>
 __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -86,11 +87,24 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
         }
     };
     u32x4 stage[F_PASSES];
+    // ACT: a thread always stages the same four channels (4*chunk ..): their coefficients live in registers, and one
+    // bit per pass remembers whether the position was real (padding must stay zero, not relu(shift))
+    float asc[4] = {0.f, 0.f, 0.f, 0.f}, ash[4] = {0.f, 0.f, 0.f, 0.f};
+    if (ACT) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            asc[e] = a.act[chunk * 4 + e];
+            ash[e] = a.act[64 + chunk * 4 + e];
+        }
+    }
+    unsigned real_bits = 0;
     auto prefetch_tile = [&]() {   // reads the table that fill_in_tab wrote before the last barrier
+        real_bits = 0;
 #pragma unroll
         for (int u = 0; u < F_PASSES; ++u) {
             const unsigned off = in_tab[u * 16 + prow];
             stage[u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, off == F_OOB ? F_OOB : off + chunk * 16, 0, 0);
+            if (ACT) real_bits |= (off != F_OOB ? 1u : 0u) << u;
         }
     };
     // filter tap t: rows n = 0..63, 64 floats each at wpk[n][t][0..63]; 4 vectors per thread
@@ -131,6 +145,16 @@ __global__ __launch_bounds__(256) void conv_halo64_f32_kernel(const HaloF32Args 
 #pragma unroll
         for (int u = 0; u < F_PASSES; ++u) {
             const int p = u * 16 + prow;
+            if (ACT) {
+                f32x4 v = __builtin_bit_cast(f32x4, stage[u]);
+                const bool real = (real_bits >> u) & 1u;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float z = v[e] * asc[e] + ash[e];   // the expression of the batch-norm apply pass
+                    v[e] = real && z > 0.f ? z : 0.f;
+                }
+                stage[u] = __builtin_bit_cast(u32x4, v);
+            }
             if (p < n_in) *(u32x4 *)(in_lds + p * F_ROW + chunk * 16) = stage[u];
         }
         {   // tile pixel tid = (row tid/32, column tid%32): always a real pixel
@@ -323,6 +347,8 @@ int launch_halo64_f32(const IgemmArgs &g, hipStream_t stream)
         hipError_t e = hipFuncSetAttribute((const void *)conv_halo64_f32_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmemF32);
         if (e == hipSuccess)
             e = hipFuncSetAttribute((const void *)conv_halo64_f32_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmemF32);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv_halo64_f32_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, kSmemF32);
         if (e != hipSuccess) {
             set_last_hip_error(e);
             return NSK_ERR_HIP;
@@ -334,7 +360,11 @@ int launch_halo64_f32(const IgemmArgs &g, hipStream_t stream)
     if (g.stats && g.stats_rows != grid * 4) return NSK_ERR_BAD_DESC;   // the planner and the launch disagree
     a.stats = g.stats;
     a.stats_rows = g.stats_rows;
-    if (g.accumulate)
+    a.act = g.act;
+    if (g.act && g.accumulate) return NSK_ERR_BAD_DESC;   // the fused load belongs to the forward pass
+    if (g.act)
+        hipLaunchKernelGGL((conv_halo64_f32_kernel<false, true>), dim3(grid), dim3(256), kSmemF32, stream, a);
+    else if (g.accumulate)
         hipLaunchKernelGGL(conv_halo64_f32_kernel<true>, dim3(grid), dim3(256), kSmemF32, stream, a);
     else
         hipLaunchKernelGGL(conv_halo64_f32_kernel<false>, dim3(grid), dim3(256), kSmemF32, stream, a);

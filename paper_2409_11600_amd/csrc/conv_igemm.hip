@@ -442,9 +442,18 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     return ceil_div(a.M, bm[t]) * (bm[t] / wm[t]);
 }
 
+bool igemm_act_fused(int dtype, const IgemmArgs &a)
+{
+    // the same order of tests as launch_igemm, up to the kernels that have the fused load
+    if (a.M <= 0 || a.Ngemm <= 0 || a.accumulate || a.groups > 1 || a.zero_cell || forced_tile() != 0) return false;
+    if (tiny_src_applicable(dtype, a) || tiny_out_applicable(dtype, a) || halo64_applicable(dtype, a)) return false;
+    return halo64_f32_applicable(dtype, a);
+}
+
 int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
 {
     if (a.M <= 0 || a.Ngemm <= 0) return NSK_OK;
+    if (a.act && !igemm_act_fused(dtype, a)) return NSK_ERR_BAD_DESC;   // the caller applies the activation itself
     const bool grouped = a.groups > 1;   // only the generic kernel knows about groups
     if (grouped && (a.groups > 65535 || a.src_ld != a.groups * a.Cs || a.zero_cell || a.stats)) return NSK_ERR_BAD_DESC;
     if (a.zero_cell) return launch_conv_pw(a, stream);   // the caller has checked that this kernel applies

@@ -280,12 +280,14 @@ constexpr int R32_XL = (R32_XPOS * 16 + 255) / 256;   // 9 x vectors per thread 
 
 struct WR32Args {
     const void *x, *dy;
+    const float *act;   // nullptr, or [2][64]: x is relu(act[c]*x + act[64+c]), applied while a chunk is staged
     float *part;
     int H, PI, chunks_per_img, chunks, chunks_per_block, total_pos;
     unsigned long long magic_pi;
     unsigned bytes;
 };
 
+template <bool ACT>
 __global__ __launch_bounds__(256) void wgrad_rows32_f32_kernel(const WR32Args a)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -297,8 +299,19 @@ __global__ __launch_bounds__(256) void wgrad_rows32_f32_kernel(const WR32Args a)
 
     // staged x position p of chunk (img, h0): padded row h0 + p/34 (real row h0 - 1 + p/34), padded column p%34
     u32x4 stage[R32_XL + 4];
+    // ACT: a thread always stages the same four channels of x (4*(tid%16) ..); one bit per pass marks real positions
+    float asc[4] = {0.f, 0.f, 0.f, 0.f}, ash[4] = {0.f, 0.f, 0.f, 0.f};
+    if (ACT) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            asc[e] = a.act[(tid & 15) * 4 + e];
+            ash[e] = a.act[64 + (tid & 15) * 4 + e];
+        }
+    }
+    unsigned real_bits = 0;
     auto issue_loads = [&](int chunk) {
         const int img = chunk / a.chunks_per_img, h0 = (chunk % a.chunks_per_img) * 2;
+        real_bits = 0;
 #pragma unroll
         for (int u = 0; u < R32_XL; ++u) {
             const int idx = tid + 256 * u, p = idx >> 4, v = idx & 15;
@@ -307,6 +320,7 @@ __global__ __launch_bounds__(256) void wgrad_rows32_f32_kernel(const WR32Args a)
             const bool ok = p < R32_XPOS && (unsigned)h < (unsigned)a.H && (unsigned)w < (unsigned)R32_W;
             const unsigned off = (unsigned)((((img * a.H + h) * R32_W + w) * 64 + v * 4) * 4);
             stage[u] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, ok ? off : WH_OOB, 0, 0);
+            if (ACT) real_bits |= (ok ? 1u : 0u) << u;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -319,6 +333,16 @@ __global__ __launch_bounds__(256) void wgrad_rows32_f32_kernel(const WR32Args a)
 #pragma unroll
         for (int u = 0; u < R32_XL; ++u) {
             const int idx = tid + 256 * u;
+            if (ACT) {
+                f32x4 v = __builtin_bit_cast(f32x4, stage[u]);
+                const bool real = (real_bits >> u) & 1u;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float z = v[e] * asc[e] + ash[e];   // the expression of the batch-norm apply pass
+                    v[e] = real && z > 0.f ? z : 0.f;
+                }
+                stage[u] = __builtin_bit_cast(u32x4, v);
+            }
             if (idx < R32_XPOS * 16) *(u32x4 *)(buf + idx * 16) = stage[u];
         }
 #pragma unroll
@@ -365,6 +389,12 @@ __global__ __launch_bounds__(256) void wgrad_rows32_f32_kernel(const WR32Args a)
 }
 
 bool rows32_f32(int dtype, const WgradArgs &a) { return dtype == NSK_F32 && a.W == R32_W && a.H % 2 == 0; }
+}  // namespace
+
+// True if the kernel launch_wgrad_halo64 picks applies WgradArgs::act while it stages x.
+bool wgrad_halo64_act_fused(int dtype, const WgradArgs &a) { return wgrad_halo64_applicable(dtype, a) && rows32_f32(dtype, a); }
+
+namespace {
 
 template <typename T> int smem_bytes()
 {
@@ -419,16 +449,23 @@ int launch_wgrad_halo64(int dtype, const WgradArgs &g, hipStream_t stream)
         r.bytes = (unsigned)((size_t)g.Nimg * g.H * g.W * 64 * 4);
         static bool r_attr = false;
         if (!r_attr) {
-            hipError_t e = hipFuncSetAttribute((const void *)wgrad_rows32_f32_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R32_BUF);
+            hipError_t e = hipFuncSetAttribute((const void *)wgrad_rows32_f32_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R32_BUF);
+            if (e == hipSuccess)
+                e = hipFuncSetAttribute((const void *)wgrad_rows32_f32_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * R32_BUF);
             if (e != hipSuccess) {
                 set_last_hip_error(e);
                 return NSK_ERR_HIP;
             }
             r_attr = true;
         }
-        hipLaunchKernelGGL(wgrad_rows32_f32_kernel, dim3(blocks), dim3(256), 2 * R32_BUF, stream, r);
+        r.act = g.act;
+        if (g.act)
+            hipLaunchKernelGGL(wgrad_rows32_f32_kernel<true>, dim3(blocks), dim3(256), 2 * R32_BUF, stream, r);
+        else
+            hipLaunchKernelGGL(wgrad_rows32_f32_kernel<false>, dim3(blocks), dim3(256), 2 * R32_BUF, stream, r);
         return check_launch();
     }
+    if (g.act) return NSK_ERR_BAD_DESC;   // only the row-aligned fp32 kernel above applies the activation on load
     WHArgs a{};
     a.x = g.x; a.dy = g.dy; a.part = g.part;
     a.H = g.H; a.W = g.W;

@@ -85,25 +85,44 @@ struct ConvPlan {
     bool halo = false;   // wgrad: the 3x3 64->64 kernel writes one partial per block
     bool wide = false;   // wgrad: the large-tile kernel for wide bf16 layers
     bool stem = false;   // the space-to-depth path plans its own workspace
+    size_t act_tmp = 0;  // fused-activation calls on a kernel without the fused load: the applied activation
+    bool act_fused = false;
 };
 
 // groups > 1: grouped convolution (the filter holds C/groups input channels per output channel and only the generic
 // kernels run it).
-ConvPlan plan_conv(const ConvGeo &g, int pass, int groups = 1)
+void fwd_geometry(const ConvGeo &g, IgemmArgs *a);
+
+// act: the call applies a batch-norm + ReLU to x on load (NHWC, one group); where the kernel that takes the layer has no
+// fused load the activation is applied into the workspace first.
+ConvPlan plan_conv(const ConvGeo &g, int pass, int groups = 1, bool act = false)
 {
     ConvPlan p;
     const size_t w_elems = g.w_elems / (size_t)groups;
     p.stem = groups == 1 && stem_applicable(g);
-    if (p.stem) {
-        p.total = stem_workspace_bytes(g, pass);
-        return p;
-    }
     size_t off = 0;
     auto take = [&](size_t bytes) {
         const size_t at = off;
         off += align_up(bytes);
         return at;
     };
+    if (act) {
+        // (the pointers only matter for alignment tests: every tensor of these calls is 16-byte aligned)
+        if (pass == NSK_PASS_FWD && !p.stem) {
+            IgemmArgs a{};
+            fwd_geometry(g, &a);
+            p.act_fused = igemm_act_fused(g.dtype, a);
+        } else if (pass == NSK_PASS_WGRAD && !p.stem) {
+            WgradArgs wa{};
+            wgrad_geometry(g, &wa);
+            p.act_fused = use_wgrad_halo(g, wa) && wgrad_halo64_act_fused(g.dtype, wa);
+        }
+        if (!p.act_fused) p.act_tmp = take(g.x_elems * g.es);
+    }
+    if (p.stem) {
+        p.total = off + stem_workspace_bytes(g, pass);
+        return p;
+    }
     const bool nchw = g.layout == NSK_NCHW;
     if (pass == NSK_PASS_FWD) {
         if (nchw) {
@@ -246,19 +265,45 @@ int check_groups(const ConvGeo &g, int groups)
     return NSK_OK;
 }
 
+// The input of a fused-activation call as a batch-norm descriptor (for the apply pass of the unfused route).
+nsk_bn_desc_t input_as_bn(const ConvGeo &g)
+{
+    nsk_bn_desc_t d{};
+    d.N = g.N; d.C = g.C; d.H = g.H; d.W = g.W;
+    d.dtype = g.dtype; d.layout = NSK_NHWC;
+    d.eps = 0.f; d.momentum = 0.f; d.relu = 1;
+    return d;
+}
+
+// NSK_OK if the fused-activation calls take this layer: NHWC, one group, channels the vector kernels handle.
+int check_act(const ConvGeo &g, int groups, const float *act)
+{
+    if (!act) return NSK_OK;
+    if (misaligned(act)) return NSK_ERR_ALIGNMENT;
+    if (g.layout != NSK_NHWC || groups != 1 || !bn_act_supported(input_as_bn(g))) return NSK_ERR_UNSUPPORTED;
+    return NSK_OK;
+}
+
 int conv_fwd_impl(const nsk_conv_desc_t *desc, int groups, const void *x, const void *w, void *y, float *stats,
-                  void *workspace, size_t workspace_bytes, void *stream)
+                  void *workspace, size_t workspace_bytes, void *stream, const float *act = nullptr)
 {
     ConvGeo g;
     NSK_TRY(conv_geometry(desc, &g, true));
     NSK_TRY(check_groups(g, groups));
     if (!x || !w || !y) return NSK_ERR_NULL;
     if (misaligned(x) || misaligned(w) || misaligned(y)) return NSK_ERR_ALIGNMENT;
-    const ConvPlan p = plan_conv(g, NSK_PASS_FWD, groups);
+    NSK_TRY(check_act(g, groups, act));
+    const ConvPlan p = plan_conv(g, NSK_PASS_FWD, groups, act != nullptr);
     const int cg = g.C / groups, kg = g.K / groups;
     NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
+    if (act && !p.act_fused) {   // the kernel for this layer has no fused load: apply the activation first
+        NSK_TRY(launch_bn_act(input_as_bn(g), x, act, ws + p.act_tmp, st));
+        x = ws + p.act_tmp;
+        act = nullptr;
+        if (p.stem) ws += align_up(g.x_elems * g.es);
+    }
     bool fused = false;
     const int rows = stats ? conv_stats_rows(g, &fused) : 0;
     if (p.stem) {
@@ -295,6 +340,7 @@ int conv_fwd_impl(const nsk_conv_desc_t *desc, int groups, const void *x, const 
         a.stats = stats;
         a.stats_rows = rows;
     }
+    a.act = act;
     NSK_TRY(launch_igemm(g.dtype, a, st));
     if (stats && !fused) NSK_TRY(launch_bn_stats(output_as_bn(g), dst, stats, st));
     if (g.layout == NSK_NCHW) NSK_TRY(launch_nhwc_to_nchw(g.dtype, dst, y, g.N, g.K, g.P, g.Q, 0, st));
@@ -544,7 +590,8 @@ static int conv_dgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *
 }
 
 static int conv_wgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *x, const void *dy, float *dw,
-                           int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+                           int accumulate, void *workspace, size_t workspace_bytes, void *stream,
+                           const float *act = nullptr)
 {
     ConvGeo g;
     NSK_TRY(conv_geometry(desc, &g, true));
@@ -552,11 +599,18 @@ static int conv_wgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *
     if (!x || !dy || !dw) return NSK_ERR_NULL;
     if (accumulate != 0 && accumulate != 1) return NSK_ERR_BAD_DESC;
     if (misaligned(x) || misaligned(dy) || misaligned(dw)) return NSK_ERR_ALIGNMENT;
-    const ConvPlan p = plan_conv(g, NSK_PASS_WGRAD, groups);
+    NSK_TRY(check_act(g, groups, act));
+    const ConvPlan p = plan_conv(g, NSK_PASS_WGRAD, groups, act != nullptr);
     const int cg = g.C / groups, kg = g.K / groups;
     NSK_TRY(check_ws(workspace, workspace_bytes, p.total));
     hipStream_t st = (hipStream_t)stream;
     char *ws = (char *)workspace;
+    if (act && !p.act_fused) {   // the kernel for this layer has no fused load: apply the activation first
+        NSK_TRY(launch_bn_act(input_as_bn(g), x, act, ws + p.act_tmp, st));
+        x = ws + p.act_tmp;
+        act = nullptr;
+        if (p.stem) ws += align_up(g.x_elems * g.es);
+    }
     const bool nchw = g.layout == NSK_NCHW;
     if (p.stem) return stem_wgrad(g, x, dy, dw, accumulate, ws, st);
     const void *xs = x, *dys = dy;
@@ -568,6 +622,7 @@ static int conv_wgrad_impl(const nsk_conv_desc_t *desc, int groups, const void *
     }
     WgradArgs a{};
     a.x = xs; a.dy = dys; a.part = (float *)(ws + p.part);
+    a.act = act;
     wgrad_geometry(g, &a);
     a.rows_per_split = p.rows_per_split;
     a.splits = p.splits;
@@ -602,6 +657,13 @@ int nsk_conv2d_wgrad(const nsk_conv_desc_t *desc, const void *x, const void *dy,
                      void *workspace, size_t workspace_bytes, void *stream)
 {
     return conv_wgrad_impl(desc, 1, x, dy, dw, accumulate, workspace, workspace_bytes, stream);
+}
+
+int nsk_conv2d_wgrad_act(const nsk_conv_desc_t *desc, const void *x, const float *coeffs, const void *dy, float *dw,
+                         int accumulate, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!coeffs) return NSK_ERR_NULL;
+    return conv_wgrad_impl(desc, 1, x, dy, dw, accumulate, workspace, workspace_bytes, stream, coeffs);
 }
 
 size_t nsk_conv2d_grouped_workspace_bytes(const nsk_conv_desc_t *desc, int groups, int pass)
@@ -709,6 +771,62 @@ int nsk_bn_relu_add_fwd_static(const nsk_bn_desc_t *desc, const void *x, const v
     // every partial sum the finalize kernel reads is written by the reduction of the same call: nothing to clear
     return launch_bn_fwd(*desc, x, residual, gamma, beta, out, save_mean, save_invstd, running_mean, running_var, ws,
                          nullptr, nullptr, 0, (hipStream_t)stream);
+}
+
+// ---- batch-norm + ReLU applied by the CONSUMERS of a convolution's raw output (the normalised activation is never stored)
+int nsk_bn_fwd_coeffs(const nsk_bn_desc_t *desc, const float *gamma, const float *beta, const float *stats,
+                      int stats_rows, float *save_mean, float *save_invstd, float *running_mean, float *running_var,
+                      float *coeffs, void *workspace, size_t workspace_bytes, void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (!gamma || !beta || !stats || !save_mean || !save_invstd || !coeffs) return NSK_ERR_NULL;
+    if (stats_rows < 1) return NSK_ERR_BAD_DESC;
+    if ((running_mean == nullptr) != (running_var == nullptr)) return NSK_ERR_NULL;
+    if (misaligned(gamma) || misaligned(beta) || misaligned(stats) || misaligned(save_mean) || misaligned(save_invstd) ||
+        misaligned(running_mean) || misaligned(running_var) || misaligned(coeffs))
+        return NSK_ERR_ALIGNMENT;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_FWD)));
+    return launch_bn_coeffs(*desc, gamma, beta, stats, stats_rows, save_mean, save_invstd, running_mean, running_var,
+                            coeffs, workspace, (hipStream_t)stream);
+}
+
+int nsk_conv2d_act_supported(const nsk_conv_desc_t *desc)
+{
+    ConvGeo g;
+    if (conv_geometry(desc, &g, true) != NSK_OK) return 0;
+    return g.layout == NSK_NHWC && bn_act_supported(input_as_bn(g)) ? 1 : 0;
+}
+
+size_t nsk_conv2d_act_workspace_bytes(const nsk_conv_desc_t *desc, int pass)
+{
+    ConvGeo g;
+    if (pass != NSK_PASS_FWD && pass != NSK_PASS_WGRAD) return 0;
+    if (conv_geometry(desc, &g, true) != NSK_OK) return 0;
+    if (g.layout != NSK_NHWC || !bn_act_supported(input_as_bn(g))) return 0;
+    return plan_conv(g, pass, 1, true).total;
+}
+
+int nsk_conv2d_fwd_act(const nsk_conv_desc_t *desc, const void *x, const float *coeffs, const void *w, void *y,
+                       float *stats, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!coeffs) return NSK_ERR_NULL;
+    if (misaligned(stats)) return NSK_ERR_ALIGNMENT;
+    return conv_fwd_impl(desc, 1, x, w, y, stats, workspace, workspace_bytes, stream, coeffs);
+}
+
+int nsk_bn_relu_bwd_act(const nsk_bn_desc_t *desc, const void *x, const float *coeffs, const void *dout,
+                        const float *gamma, const float *save_mean, const float *save_invstd, void *dx, float *dgamma,
+                        float *dbeta, void *workspace, size_t workspace_bytes, void *stream)
+{
+    NSK_TRY(bn_geometry(desc));
+    if (!x || !coeffs || !dout || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta) return NSK_ERR_NULL;
+    if (misaligned(x) || misaligned(coeffs) || misaligned(dout) || misaligned(dx) || misaligned(gamma) ||
+        misaligned(save_mean) || misaligned(save_invstd) || misaligned(dgamma) || misaligned(dbeta))
+        return NSK_ERR_ALIGNMENT;
+    if (!desc->relu || desc->layout != NSK_NHWC || !bn_act_supported(*desc)) return NSK_ERR_UNSUPPORTED;
+    NSK_TRY(check_ws(workspace, workspace_bytes, nsk_bn_workspace_bytes(desc, NSK_BN_BWD)));
+    return launch_bn_bwd(*desc, x, nullptr, dout, gamma, save_mean, save_invstd, dx, nullptr, dgamma, dbeta, workspace,
+                         nullptr, (hipStream_t)stream, coeffs);
 }
 
 int nsk_bn_relu_add_bwd(const nsk_bn_desc_t *desc, const void *x, const void *out, const void *dout,

@@ -101,6 +101,10 @@ struct IgemmArgs {
     // igemm_stats_rows() named the row count for exactly this launch.
     float *stats;
     int stats_rows;
+    // Forward with the producing batch-norm and ReLU applied to the input on load: src holds the RAW output of the
+    // previous convolution and the kernel multiplies relu(act[c]*src + act[Cs + c]) (zero padding stays zero).  Only
+    // kernels for which igemm_act_fused() says yes take it; nullptr otherwise.
+    const float *act;
     // Backward-data of a stride-2 layer whose taps all fall into residue class (0, 0): the launch for that class also
     // writes zeros to the other (up to three) pixels of each row's 2x2 output cell.  Only the short-reduction kernel
     // honours it: set it only after conv_pw_applicable() said yes for these arguments.
@@ -114,6 +118,8 @@ struct IgemmArgs {
     short off_w[kMaxTaps];
 };
 int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream);
+// True if the kernel launch_igemm picks for these arguments applies IgemmArgs::act while it stages its input.
+bool igemm_act_fused(int dtype, const IgemmArgs &a);
 // Rows of partial sums the kernel launch_igemm would pick writes from its epilogue; 0 if that kernel has no
 // statistics epilogue (the caller then runs a separate reduction pass).  Host only, depends on the shape alone.
 int igemm_stats_rows(int dtype, const IgemmArgs &a);
@@ -178,6 +184,9 @@ struct WgradArgs {
     // and writes rows [g*K, (g+1)*K) of part[split][groups*K][ntaps*C].  Only the generic kernel runs such launches;
     // ldx and ldy are ignored (taken as C and K) for plain ones.
     int groups, ldx, ldy;
+    // nullptr, or [2][C]: x holds the RAW output of the producing convolution and the kernel uses
+    // relu(act[c]*x + act[C + c]); only where wgrad_halo64_act_fused() says yes
+    const float *act;
     short off_h[kMaxTaps];
     short off_w[kMaxTaps];
 };
@@ -187,6 +196,7 @@ int launch_wgrad(int dtype, const WgradArgs &a, hipStream_t stream);
 bool wgrad_halo64_applicable(int dtype, const WgradArgs &a);
 int wgrad_halo64_partials(int dtype, const WgradArgs &a, int *chunks_per_block);
 int launch_wgrad_halo64(int dtype, const WgradArgs &a, hipStream_t stream);
+bool wgrad_halo64_act_fused(int dtype, const WgradArgs &a);
 // wide bf16 layers (C, K multiples of 64, long reduction): large tiles, about one block per CU
 bool wgrad_wide_applicable(int dtype, const WgradArgs &a);
 int wgrad_wide_rows_per_split(const WgradArgs &a, int *splits);
@@ -255,7 +265,13 @@ int launch_bn_stats(const nsk_bn_desc_t &d, const void *x, float *stats, hipStre
 int launch_bn_bwd(const nsk_bn_desc_t &d, const void *x, const void *out, const void *dout,
                   const float *gamma, const float *save_mean, const float *save_invstd, void *dx,
                   void *dres, float *dgamma, float *dbeta, void *ws, const unsigned char *relu_mask,
-                  hipStream_t stream);
+                  hipStream_t stream, const float *act = nullptr);
+// The normalised activation applied by its consumers on load (scale and shift per channel: coeffs = [2][C] floats)
+bool bn_act_supported(const nsk_bn_desc_t &d);
+int launch_bn_coeffs(const nsk_bn_desc_t &d, const float *gamma, const float *beta, const float *stats, int stats_rows,
+                     float *save_mean, float *save_invstd, float *running_mean, float *running_var, float *coeffs,
+                     void *ws, hipStream_t stream);
+int launch_bn_act(const nsk_bn_desc_t &d, const void *x, const float *coeffs, void *out, hipStream_t stream);
 int launch_maxpool_fwd(const nsk_pool_desc_t &d, int P, int Q, const void *x, void *y,
                        signed char *idx, hipStream_t stream);
 int launch_maxpool_bwd(const nsk_pool_desc_t &d, int P, int Q, const void *dy,

@@ -37,7 +37,7 @@ def _to_device(a: np.ndarray, dtype, layout, device, is_filter=False):
 
 class GpuNetwork:
     def __init__(self, wl: dict, tensors: dict, layout: int = B.NSK_NHWC, device: str = "cuda:0", eps: float = 1e-5,
-                 use_relu_mask: bool = True, use_fused_stats: bool = True):
+                 use_relu_mask: bool = True, use_fused_stats: bool = True, use_fused_act: bool = False):
         self.wl, self.layout, self.device = wl, layout, torch.device(device)
         self.dtype = torch.bfloat16 if wl["dtype"] == "bf16" else torch.float32
         self.code = B.NSK_BF16 if wl["dtype"] == "bf16" else B.NSK_F32
@@ -64,6 +64,24 @@ class GpuNetwork:
 
         fwd_plan, bwd_plan = [], []
         written = {wl["output"]}
+        # use_fused_act: a conv + batch-norm + ReLU (no residual) whose result feeds exactly one convolution never
+        # stores its normalised activation; the consumer applies it to the raw convolution output on load
+        # (nsk_conv2d_fwd_act / nsk_conv2d_wgrad_act) and the batch-norm's backward pass takes its mask from there too.
+        # fused_away[tensor name] = name of the unit that would have produced it.
+        self.fused_away: Dict[str, str] = {}
+        self.coeffs: Dict[str, torch.Tensor] = {}
+        if use_fused_act and use_fused_stats and layout == B.NSK_NHWC:
+            for u in wl["units"]:
+                if u["kind"] != "conv_bn" or not u["relu"] or u["res"] or u["dst"] == wl["output"]:
+                    continue
+                readers = [v for v in wl["units"] if v["src"] == u["dst"]]
+                as_res = [v for v in wl["units"] if v.get("res") == u["dst"]]
+                if len(readers) != 1 or as_res or readers[0]["kind"] not in ("conv", "conv_bn"):
+                    continue
+                v = readers[0]
+                vd = B.conv_desc(self.shapes[v["src"]], (v["K"], v["R"], v["S"]), v["stride"], v["pad"], 1, self.code, layout)
+                if L.nsk_conv2d_act_supported(ctypes.byref(vd)):
+                    self.fused_away[u["dst"]] = u["name"]
         for u in wl["units"]:
             name = u["name"]
             N, C, H, W = self.shapes[u["src"]]
@@ -82,9 +100,17 @@ class GpuNetwork:
             self._keep.append(cd)
             for ps in (B.NSK_PASS_FWD, B.NSK_PASS_DGRAD, B.NSK_PASS_WGRAD):
                 ws_bytes = max(ws_bytes, L.nsk_conv2d_workspace_bytes(ctypes.byref(cd), ps))
+            producer = self.fused_away.get(u["src"])     # the unit whose activation this convolution applies on load
+            if producer:
+                for ps in (B.NSK_PASS_FWD, B.NSK_PASS_WGRAD):
+                    ws_bytes = max(ws_bytes, L.nsk_conv2d_act_workspace_bytes(ctypes.byref(cd), ps))
             if u["kind"] == "conv":
-                fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
-                                                    ptr(self.act[u["dst"]])), "ws"))
+                if producer:
+                    fwd_plan.append((L.nsk_conv2d_fwd_act, (ctypes.byref(cd), ptr(self.y[producer]), ptr(self.coeffs[producer]),
+                                                            ptr(self.w[name]), ptr(self.act[u["dst"]]), None), "ws"))
+                else:
+                    fwd_plan.append((L.nsk_conv2d_fwd, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
+                                                        ptr(self.act[u["dst"]])), "ws"))
                 continue
             self.gamma[name] = torch.from_numpy(np.asarray(p["gamma"], np.float32)).to(dev)
             self.beta[name] = torch.from_numpy(np.asarray(p["beta"], np.float32)).to(dev)
@@ -110,8 +136,19 @@ class GpuNetwork:
                 # from them instead of reading the activation once more
                 rows = int(L.nsk_conv2d_stats_rows(ctypes.byref(cd)))
                 self.stats[name] = torch.empty((2, rows, K), dtype=torch.float32, device=dev)
-                fwd_plan.append((L.nsk_conv2d_fwd_stats, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
-                                                          ptr(self.y[name]), ptr(self.stats[name])), "ws"))
+                if producer:
+                    fwd_plan.append((L.nsk_conv2d_fwd_act, (ctypes.byref(cd), ptr(self.y[producer]), ptr(self.coeffs[producer]),
+                                                            ptr(self.w[name]), ptr(self.y[name]), ptr(self.stats[name])), "ws"))
+                else:
+                    fwd_plan.append((L.nsk_conv2d_fwd_stats, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(self.w[name]),
+                                                              ptr(self.y[name]), ptr(self.stats[name])), "ws"))
+                if u["dst"] in self.fused_away:
+                    # statistics and coefficients only: the consumer applies the activation
+                    self.coeffs[name] = torch.empty((2, K), dtype=torch.float32, device=dev)
+                    fwd_plan.append((L.nsk_bn_fwd_coeffs, (ctypes.byref(bd), ptr(self.gamma[name]), ptr(self.beta[name]),
+                                                           ptr(self.stats[name]), rows, ptr(self.mean[name]),
+                                                           ptr(self.invstd[name]), None, None, ptr(self.coeffs[name])), "ws"))
+                    continue
                 fwd_plan.append((L.nsk_bn_relu_add_fwd_stats, (ctypes.byref(bd), ptr(self.y[name]), ptr(res),
                                                                ptr(self.gamma[name]), ptr(self.beta[name]),
                                                                ptr(self.act[u["dst"]]), ptr(self.mask.get(name)),
@@ -155,7 +192,12 @@ class GpuNetwork:
                     assert u["res"] not in written, "residual gradient must be the first contribution"
                     dres = self.grad[u["res"]]
                     written.add(u["res"])
-                if name in self.mask:
+                if u["dst"] in self.fused_away:
+                    bwd_plan.append((L.nsk_bn_relu_bwd_act, (ctypes.byref(bd), ptr(self.y[name]), ptr(self.coeffs[name]),
+                                                             ptr(g_dst), ptr(self.gamma[name]), ptr(self.mean[name]),
+                                                             ptr(self.invstd[name]), ptr(self.dy[name]),
+                                                             ptr(self.dgamma[name]), ptr(self.dbeta[name])), "ws"))
+                elif name in self.mask:
                     bwd_plan.append((L.nsk_bn_relu_add_bwd_mask, (ctypes.byref(bd), ptr(self.y[name]), ptr(self.mask[name]),
                                                                   ptr(g_dst), ptr(self.gamma[name]), ptr(self.mean[name]),
                                                                   ptr(self.invstd[name]), ptr(self.dy[name]), ptr(dres),
@@ -168,8 +210,13 @@ class GpuNetwork:
                 dy = self.dy[name]
             else:
                 dy = g_dst
-            bwd_plan.append((L.nsk_conv2d_wgrad, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(dy), ptr(self.dw[name]), 0),
-                             "side"))
+            producer = self.fused_away.get(u["src"])
+            if producer:
+                bwd_plan.append((L.nsk_conv2d_wgrad_act, (ctypes.byref(cd), ptr(self.y[producer]), ptr(self.coeffs[producer]),
+                                                          ptr(dy), ptr(self.dw[name]), 0), "side"))
+            else:
+                bwd_plan.append((L.nsk_conv2d_wgrad, (ctypes.byref(cd), ptr(self.act[u["src"]]), ptr(dy), ptr(self.dw[name]), 0),
+                                 "side"))
             acc = 1 if u["src"] in written else 0
             bwd_plan.append((L.nsk_conv2d_dgrad, (ctypes.byref(cd), ptr(dy), ptr(self.w[name]), ptr(self.grad[u["src"]]),
                                                   acc), "ws"))

@@ -32,7 +32,7 @@ def _compare(net, fwd, bwd, wl, tol):
         worst[f"{kind}:{name}"] = e
 
     for name in net.shapes:
-        if name != "x":
+        if name != "x" and name not in net.fused_away:      # (an activation its consumer applies on load is never stored)
             chk("act", name, net.host(net.act[name]), fwd["act"][name])
         if name != wl["output"]:
             chk("grad", name, net.host(net.grad[name]), bwd["grad"][name])
@@ -154,7 +154,7 @@ def _within(got, want, tol):
 def _chain_stats(net, fwd, bwd, wl, tol, kinds=("act", "grad", "dw")):
     stats = {}
     for name in net.shapes:
-        if name != "x" and "act" in kinds:
+        if name != "x" and "act" in kinds and name not in net.fused_away:
             stats[f"act:{name}"] = _within(net.host(net.act[name]), fwd["act"][name], tol)
         if name != wl["output"] and "grad" in kinds:
             stats[f"grad:{name}"] = _within(net.host(net.grad[name]), bwd["grad"][name], tol)
@@ -240,6 +240,46 @@ def test_workload_end_to_end(config, stage, batch, layout, fused):
     _check_bf16_chain(net, fwd, bwd, wl, tol)
     if fused and layout == B.NSK_NHWC:
         _backward_on_the_oracles_masks(net, fwd, bwd, wl, tol)
+
+
+FUSED_ACT_CASES = [(2, "A", 8), (2, "A", None), (3, "A", 8), (4, "A", 2), (5, "A", 2)]
+
+
+@pytest.mark.parametrize("config,stage,batch", FUSED_ACT_CASES)
+def test_workload_with_activations_applied_on_load(config, stage, batch):
+    """The call sequence in which a conv + batch-norm + ReLU that feeds one convolution never stores its normalised
+    activation (nsk_bn_fwd_coeffs, nsk_conv2d_fwd_act, nsk_conv2d_wgrad_act, nsk_bn_relu_bwd_act) against the oracle's
+    execution of the same unit list.  fp32 at reduced batch: every tensor element by element at 1e-4; full batch
+    and bf16: the chain bars (the ReLU masks of this path live in no buffer, so the oracle's cannot be handed in)."""
+    wl, t, fwd, bwd = _setup(config, stage, batch)
+    print(f"workload {wl['name']} input {wl['input']} activations applied on load", flush=True)
+    net = GpuNetwork(wl, t, layout=B.NSK_NHWC, use_relu_mask=True, use_fused_stats=True, use_fused_act=True)
+    assert net.fused_away, "no convolution of this workload takes its activation on load"
+    print("  never stored:", sorted(net.fused_away), flush=True)
+    net.step()
+    net.step()
+    torch.cuda.synchronize()
+    tol = TOL[wl["dtype"]]
+    worst, bad = _compare(net, fwd, bwd, wl, tol)
+    top = sorted(worst.items(), key=lambda kv: -kv[1])[:5]
+    print("largest errors:", ", ".join(f"{k}={v:.2e}" for k, v in top), flush=True)
+    if wl["dtype"] == "f32" and batch is not None:
+        assert not bad, bad
+        return
+    if wl["dtype"] == "f32":
+        fwd_bad = {k: v for k, v in worst.items() if k.split(":")[0] in ("act", "mean", "invstd") and not v <= tol}
+        assert not fwd_bad, fwd_bad
+        stats = _chain_stats(net, fwd, bwd, wl, tol, kinds=("grad", "dw"))
+        free_bad = {k: v for k, v in stats.items() if not (v[1] <= 2e-3 and (not k.startswith("grad:") or v[2] >= 0.999))}
+        assert not free_bad, free_bad
+        return
+    _check_bf16_chain(net, fwd, bwd, wl, tol)
+    # the fused sequence must agree with the unfused one to rounding (same kernels, same arithmetic)
+    ref = GpuNetwork(wl, t, layout=B.NSK_NHWC, use_relu_mask=True, use_fused_stats=True, use_fused_act=False)
+    ref.step()
+    torch.cuda.synchronize()
+    for name in net.dw:
+        assert max_rel_err(net.host(net.dw[name]), net.host(ref.dw[name])) <= 1e-2, name
 
 
 # Full batch, the launch configuration bench.py times (NHWC, statistics from the convolution epilogues, ReLU mask

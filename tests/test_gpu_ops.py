@@ -570,6 +570,63 @@ def test_fused_statistics_with_a_strongly_offset_convolution_output(dtype, offse
     assert max_rel_err(to_host(out, B.NSK_NHWC), want_out) <= out_tol
 
 
+# conv -> batch-norm -> ReLU -> conv with the normalised activation never stored: the second convolution and its
+# backward-weight call apply it to the raw output of the first on load, the batch-norm's backward pass takes the ReLU
+# mask from there.  dtype, (N, C, H, W) of the raw tensor, K, R, stride, pad of the consuming convolution
+ACT_SHAPES = [
+    ("f32", (4, 64, 16, 32), 64, 3, 1, 1),      # fp32 3x3 64->64 on 32-wide images: kernels with the fused operand load
+    ("f32", (128, 64, 32, 32), 64, 3, 1, 1),    # the same at the size of the configured block: several tiles per block
+    ("bf16", (3, 64, 20, 24), 64, 3, 1, 1),     # no fused load for this layer: activation applied into the workspace
+    ("f32", (2, 16, 15, 17), 32, 3, 2, 1),      # strided consumer, generic kernels
+    ("bf16", (2, 256, 9, 9), 64, 1, 1, 0),      # 1x1 consumer
+]
+
+
+@pytest.mark.parametrize("i", range(len(ACT_SHAPES)))
+def test_fused_activation_calls(i):
+    dtype, shape, K, R, stride, pad = ACT_SHAPES[i]
+    N, C, H, W = shape
+    print(f"fused activation case {ACT_SHAPES[i]}", flush=True)
+    seed = 1700 + i
+    y_raw = on_grid(1.3 * gen.normal(seed, 0, shape) + 0.2, dtype)
+    g = (1.0 + 0.3 * gen.normal(seed, 1, (C,))).astype(np.float32)
+    b = (0.2 * gen.normal(seed, 2, (C,))).astype(np.float32)
+    w = on_grid(gen.he_normal(seed, 3, (K, C, R, R)), dtype)
+    # the oracle's chain: batch-norm + ReLU (stored on the grid), then the convolution and its backward passes
+    a_want, mean_want, inv_want = oracle.bn_relu_add_fwd(y_raw, g, b, None, 1e-5, True)
+    a_grid = on_grid(a_want.astype(np.float32), dtype)
+    z_want = oracle.conv2d_fwd(a_grid, w, stride, pad, 1)
+    dz = on_grid(gen.normal(seed, 4, z_want.shape), dtype)
+    dw_want = oracle.conv2d_wgrad(a_grid, dz, w.shape, stride, pad, 1)
+    da = on_grid(gen.normal(seed, 5, shape), dtype)                       # gradient arriving at the activation
+    m32, i32 = mean_want.astype(np.float32), inv_want.astype(np.float32)
+    dy_want, _, dg_want, db_want = oracle.bn_relu_add_bwd(y_raw, a_grid, da, g, m32, i32, True, want_dresidual=False)
+    # input of nsk_bn_fwd_coeffs: one row of partial sums of the raw tensor (exact sums, rounded to float)
+    y64 = y_raw.astype(np.float64)
+    stats = np.stack([y64.sum(axis=(0, 2, 3)), (y64 * y64).sum(axis=(0, 2, 3))]).astype(np.float32).reshape(2, 1, C)
+    ws = B.Workspace()
+    gy, gw = to_gpu(y_raw, dtype, B.NSK_NHWC), to_gpu(w, dtype, B.NSK_NHWC)
+    gg, gb = torch.from_numpy(g).cuda(), torch.from_numpy(b).cuda()
+    mean, inv, coeffs = B.bn_fwd_coeffs(gy, gg, gb, torch.from_numpy(stats).cuda(), 1e-5, ws=ws)
+    assert max_rel_err(mean.cpu().numpy(), mean_want) <= 1e-5
+    assert max_rel_err(inv.cpu().numpy(), inv_want) <= 1e-5
+    z, zstats = B.conv2d_fwd_act(gy, coeffs, gw, stride, pad, 1, want_stats=True, ws=ws)
+    z_plain = B.conv2d_fwd_act(gy, coeffs, gw, stride, pad, 1, ws=ws)
+    dw = B.conv2d_wgrad_act(gy, coeffs, to_gpu(dz, dtype, B.NSK_NHWC), w.shape, stride, pad, 1, ws=ws)
+    dy, dg, db = B.bn_relu_bwd_act(gy, coeffs, to_gpu(da, dtype, B.NSK_NHWC), gg, mean, inv, ws=ws)
+    torch.cuda.synchronize()
+    tol = TOL[dtype]
+    assert max_rel_err(to_host(z, B.NSK_NHWC), z_want) <= tol
+    assert torch.equal(z, z_plain)
+    zs = zstats.double().sum(dim=1).cpu().numpy()
+    zh = to_host(z, B.NSK_NHWC)
+    assert np.max(np.abs(zs[0] - zh.sum(axis=(0, 2, 3))) / (np.sqrt((zh * zh).sum(axis=(0, 2, 3)) * zh[:, 0].size) + 1e-30)) <= 1e-5
+    assert max_rel_err(to_host(dw, B.NSK_NHWC), dw_want) <= tol
+    assert max_rel_err(to_host(dy, B.NSK_NHWC), dy_want) <= tol
+    assert max_rel_err(dg.cpu().numpy(), dg_want) <= 1e-4
+    assert max_rel_err(db.cpu().numpy(), db_want) <= 1e-4
+
+
 BN_SHAPES = [(4, 64, 9, 11), (3, 16, 16, 16), (2, 256, 7, 7), (2, 1024, 5, 5), (5, 24, 6, 7), (2, 3, 10, 10),
              (3, 40, 33, 17)]
 
