@@ -318,6 +318,404 @@ __global__ __launch_bounds__(256) void conv_fs64_dgrad_s2_kernel(const S2Args a)
     static_for<0, 8>([&](auto gc) { out_store(std::integral_constant<int, 3>{}, gc); });
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------------
+// FORWARD of the same layer (3x3, stride 2, pad 1, 64 -> 64, even extents).  The input splits into four parity planes,
+// plane (a, b) = x[2I-1+a][2J-1+b]; output position (I, J) reads plane (a, b) at (I + dI, J + dJ) with
+//   filter row r = 0, 1, 2  ->  (a, dI) = (0, 0), (1, 0), (0, 1)   and the same for columns,
+// so in flat coordinates of a (P+1) x (Q+1) grid every tap is one plane and one of the shifts {0, 1, PW, PW+1}: the
+// stride disappears.  A pixel of a plane is 128 contiguous bytes of x, so a plane is staged like any other tensor, by
+// byte offset per row, in whole cache lines.  Each plane has an input ring of its own, sized for the shifts that
+// reach it (halo PW+1, PW, 1 and 0 rows for planes (0,0), (0,1), (1,0), (1,1)): 4 x 2 x 128 + 2*PW + 2 rows.
+//
+// Four wavefronts, the nine taps' filter fragments in registers, a tile of 128 positions (32 per wavefront, two
+// MFMAs per input fragment), one LDS-only barrier per tile.  The layer reads four input pixels per output pixel: it
+// is bound by memory, and next to that by the NUMBER of instructions per tile (with one wavefront per SIMD an MFMA
+// hides only a handful of other instructions of the same wavefront):
+//   * ring rows are 128 bytes with 16 bytes of padding after every second row (row r at (r/2)*272 + (r%2)*128):
+//     fragment reads are conflict-free without a swizzle, so the four reduction steps of a tap are immediate offsets
+//     of one address register, and advancing any address by a tile is an add and a wrap;
+//   * every address (nine taps, sixteen staging pieces) lives in a register and is advanced in place;
+//   * one division per lane and tile yields the offsets of all four planes (carries instead of a division each)
+//     and, two tiles later, of the outputs;
+//   * plane (1,1) is only reached by the centre tap, without a shift: its rows are private to the wavefront that
+//     stages them, so the rows a tile has just consumed serve as the strip through which that wavefront turns its
+//     accumulators into whole output pixels (no LDS beyond the rings).
+// Input rows are requested two tiles ahead of their use (a tile in registers, a tile in the ring), outputs are
+// converted after a tile's last MFMA and stored (and counted for the batch-norm statistics) during the next tile.
+constexpr int F2_TILE = 128, F2_WPOS = 32, F2_NPAIR = 36, F2_DIST = 4;
+constexpr int F2_PAIR_BYTES = 272;       // two ring rows and their padding
+constexpr int F2_MAX_PW = 88;            // grid width (Q + 1) the rings hold: 4*256 + 2*PW + 3 rows <= 160 KB
+constexpr int F2_AGPR_STEPS = 28;        // 224 accumulation registers of filter next to the 32 accumulators
+constexpr int F2_STATS_GRID = 256;       // block count when statistics are requested (independent of the device)
+
+struct F2Args {
+    const void *src, *wpk;   // x [N][H][W][64]; packed filter [64][9][64], taps in (r, s) order
+    void *out;               // y [N][P][Q][64]
+    float *stats;            // nullptr, or partial sums of the stored output: 4 rows per block
+    int stats_rows;
+    int N, H, W, P, Q, PW, PR, PI, total_pos, tiles;
+    unsigned img_bytes, row2_bytes;   // H*W*128 and 2*W*128: x bytes per image and per two rows
+    unsigned long long magic_pi, magic_pw;
+    unsigned src_bytes, out_bytes;
+};
+
+// tap t = 3r + s  ->  plane 2a + b and shift 2*dI + dJ
+constexpr int f2_plane(int t) { return ((t / 3) == 1 ? 2 : 0) + ((t % 3) == 1 ? 1 : 0); }
+constexpr int f2_shift(int t) { return ((t / 3) == 2 ? 2 : 0) + ((t % 3) == 2 ? 1 : 0); }
+// rows a tile needs beyond its own 128 in plane c: (0,0): PW+1, (0,1): PW, (1,0): 1, (1,1): 0
+__device__ __host__ constexpr int f2_halo(int c, int PW) { return c == 0 ? PW + 1 : c == 1 ? PW : c == 2 ? 1 : 0; }
+__device__ __host__ constexpr int f2_ring_rows(int c, int PW) { return (2 * F2_TILE + f2_halo(c, PW) + 1) & ~1; }
+__host__ constexpr int f2_lds_bytes(int PW)
+{
+    return (f2_ring_rows(0, PW) + f2_ring_rows(1, PW) + f2_ring_rows(2, PW) + f2_ring_rows(3, PW)) / 2 * F2_PAIR_BYTES;
+}
+
+// Order of the 16 input pieces (piece = plane c, rows 8u .. 8u+7 of a wavefront's 32): the two pixels of a 256-byte
+// pair of x (planes (a,1) at a position and (a,0) at the next one for a = 0, planes (1,1) and (1,0) for a = 1) are
+// requested one after the other
+constexpr int f2_piece_c(int j) { return (j >> 3) == 0 ? ((j & 1) == 0 ? 1 : 0) : ((j & 1) == 0 ? 3 : 2); }
+constexpr int f2_piece_u(int j) { return (j >> 1) & 3; }
+
+// The compile-time schedule of a tile.  With one wavefront per SIMD an MFMA (32 clocks) hides about six independent
+// or four dependent instructions of the same wavefront and no more, so the side work is spread over the 72 slots in
+// front of the MFMAs a few instructions at a time.  Slot 2m is in front of the first MFMA of pair m (it also holds the
+// request of the input fragment four pairs ahead), slot 2m+1 in front of the second.
+enum { F2_NONE, F2_IA1, F2_IA2, F2_IA3, F2_IP, F2_OR, F2_OS, F2_ST, F2_TAPU, F2_CLW, F2_CLA };
+struct F2Act { int kind, arg; };
+constexpr F2Act f2_action(int slot)
+{
+    const int m = slot >> 1;
+    if (m >= 14 && m < 30) return {(slot & 1) ? F2_CLA : F2_CLW, m - 14};   // input piece m - 14: commit and reload | advance
+    switch (slot) {
+    // input offsets of tile p+2 (a division per lane, then one plane at a time; the first pieces are planes 1, 0)
+    case 1: return {F2_IA1, 0}; case 7: return {F2_IA2, 0}; case 13: return {F2_IA3, 0};
+    case 19: return {F2_IP, 1}; case 25: return {F2_IP, 0}; case 22: return {F2_IP, 3}; case 26: return {F2_IP, 2};
+    // output vector g of tile p-1: strip -> registers, store, statistics in two halves
+    case 3: return {F2_OR, 0}; case 5: return {F2_OS, 0}; case 6: return {F2_ST, 0}; case 8: return {F2_ST, 1};
+    case 9: return {F2_OR, 1}; case 11: return {F2_OS, 1}; case 12: return {F2_ST, 2}; case 14: return {F2_ST, 3};
+    case 15: return {F2_OR, 2}; case 17: return {F2_OS, 2}; case 18: return {F2_ST, 4}; case 20: return {F2_ST, 5};
+    case 21: return {F2_OR, 3}; case 23: return {F2_OS, 3}; case 24: return {F2_ST, 6}; case 27: return {F2_ST, 7};
+    // a tap's address moves on to the next tile once its last fragment has been requested
+    case 61: return {F2_TAPU, 0}; case 63: return {F2_TAPU, 1}; case 64: return {F2_TAPU, 2}; case 65: return {F2_TAPU, 3};
+    case 66: return {F2_TAPU, 4}; case 67: return {F2_TAPU, 5}; case 68: return {F2_TAPU, 6}; case 69: return {F2_TAPU, 7};
+    case 70: return {F2_TAPU, 8};
+    default: return {F2_NONE, 0};
+    }
+}
+// LDS access by address (a number of bytes from the start of the workgroup's LDS) and an index in units of T
+template <typename T>
+__device__ inline T lds_get(unsigned addr, int idx)
+{
+    typedef T __attribute__((address_space(3))) LT;
+    return ((const LT *)(size_t)addr)[idx];
+}
+template <typename T>
+__device__ inline void lds_put(unsigned addr, int idx, const T &v)
+{
+    typedef T __attribute__((address_space(3))) LT;
+    ((LT *)(size_t)addr)[idx] = v;
+}
+
+template <bool STATS>
+__global__ __launch_bounds__(256) void conv_fs64_fwd_s2_kernel(const F2Args a)
+{
+    constexpr int TILE = F2_TILE, WPOS = F2_WPOS, NPAIR = F2_NPAIR, DIST = F2_DIST;
+    constexpr unsigned ADV = TILE / 2 * F2_PAIR_BYTES;          // LDS bytes of a tile's rows
+    // This kernel has no other LDS: the dynamic allocation starts at LDS address 0, and the tile loop addresses it
+    // with plain numbers (no base to add to every address).
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int x = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int frow = lane & 31, fk = lane >> 5;
+    const int prow = lane >> 3, chunk = lane & 7;
+    const unsigned chunk16 = (unsigned)chunk * 16u;
+    const __amdgpu_buffer_rsrc_t src_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)a.src, 0, a.src_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, a.out_bytes, 0x00020000);
+    unsigned rbase[4], rsize[4], rend[4];
+    {
+        unsigned at = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            rbase[c] = at;
+            rsize[c] = (unsigned)(f2_ring_rows(c, a.PW) / 2 * F2_PAIR_BYTES);
+            at += rsize[c];
+            rend[c] = at;
+        }
+    }
+    auto row_addr = [&](int c, unsigned r) -> unsigned { return rbase[c] + (r >> 1) * (unsigned)F2_PAIR_BYTES + (r & 1u) * 128u; };
+    // an address of ring c one tile later (ring sizes are whole row pairs and a tile is 64 of them)
+    auto advance = [&](unsigned addr, int c) -> unsigned {
+        const unsigned t = addr + ADV;
+        return t >= rend[c] ? t - rsize[c] : t;
+    };
+
+    const int tiles_per_block = (a.tiles + (int)gridDim.x - 1) / (int)gridDim.x;
+    const int T0 = blockIdx.x * tiles_per_block;
+    const int n = min(a.tiles, T0 + tiles_per_block) - T0;      // tiles of this block
+
+    float ssum[8], ssq[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ssum[e] = ssq[e] = 0.f;
+    // lane (prow, chunk) has counted channels 8*chunk .. 8*chunk+7 of the rows it stored: add up over prow, one row
+    // of partial sums per wavefront
+    auto write_stats = [&]() {
+        if constexpr (STATS) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+#pragma unroll
+                for (int o = 8; o < 64; o <<= 1) {
+                    ssum[e] += __shfl_xor(ssum[e], o, 64);
+                    ssq[e] += __shfl_xor(ssq[e], o, 64);
+                }
+            if (lane < 8) {
+                float *r0 = a.stats + (size_t)(blockIdx.x * 4 + x) * 64 + lane * 8;
+                float *r1 = r0 + (size_t)a.stats_rows * 64;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    r0[e] = ssum[e];
+                    r1[e] = ssq[e];
+                }
+            }
+        }
+    };
+    if (n <= 0) {                                                // uniform for the block: no barrier is skipped
+        write_stats();                                           // zeros: every row of the buffer is written
+        return;
+    }
+    const int Q0 = T0 * TILE;                                    // flat position held by row 0 of every ring
+
+    // Position q -> (image, I, J) in small pieces (state in so_*).  so_q keeps the unclamped position; a tile that
+    // does not exist is handed in as position 2^30, beyond every grid this kernel takes (no branch in the tile loop).
+    // so_src is the byte offset of x[2I-1][2J-1] (possibly outside x: only sums with a plane's own offset are used).
+    unsigned so_q, so_img, so_rem, so_i, so_j, so_src, so_out;
+    auto so1 = [&](int q) {
+        so_q = (unsigned)q;
+        const unsigned qc = so_q < (unsigned)a.total_pos ? so_q : 0u;
+        so_img = (unsigned)(((unsigned long long)qc * a.magic_pi) >> 40);
+        so_rem = qc - so_img * (unsigned)a.PI;
+    };
+    auto so2 = [&]() {
+        so_i = (unsigned)(((unsigned long long)so_rem * a.magic_pw) >> 40);
+        so_j = so_rem - so_i * (unsigned)a.PW;
+    };
+    auto so3 = [&]() {
+        const unsigned t = so_img * a.img_bytes + so_i * a.row2_bytes;      // x[img][2I][0]; a quarter of it is y[img][I][0]
+        so_src = t + so_j * 256u - (unsigned)((a.W + 1) * 128);
+        const bool ok = (so_q < (unsigned)a.total_pos) & (so_i < (unsigned)a.P) & (so_j < (unsigned)a.Q);
+        so_out = ok ? (t >> 2) + so_j * 128u : S2_OOB;
+    };
+    // Byte offset of the plane-c pixel of the position (di rows, dj columns) after the one just divided (carries into
+    // the next grid row and the next image instead of a division per plane), out of range where that pixel does not
+    // exist
+    auto plane_off = [&](int c, int di, int dj) -> unsigned {
+        const int pa = c >> 1, pb = c & 1;
+        unsigned j = so_j + (unsigned)dj, i = so_i + (unsigned)di;
+        unsigned off = so_src + (unsigned)(dj * 256 + (pa * a.W + pb) * 128) + (unsigned)di * a.row2_bytes;
+        if (dj) {
+            const bool cj = j >= (unsigned)a.PW;
+            j = cj ? j - (unsigned)a.PW : j;
+            off += cj ? a.row2_bytes - (unsigned)(a.PW * 256) : 0u;
+            i += cj ? 1u : 0u;
+        }
+        if (di || dj) {
+            const bool ci = i >= (unsigned)a.PR;
+            i = ci ? i - (unsigned)a.PR : i;
+            off += ci ? a.img_bytes - (unsigned)a.PR * a.row2_bytes : 0u;
+        }
+        const bool okh = pa ? i < (unsigned)a.P : i >= 1u, okw = pb ? j < (unsigned)a.Q : j >= 1u;
+        const bool ok = (so_q + (unsigned)(di * a.PW + dj) < (unsigned)a.total_pos) & okh & okw;
+        return ok ? off : S2_OOB;
+    };
+    auto plane_off_halo = [&](int c) -> unsigned { return plane_off(c, c < 2 ? 1 : 0, c == 0 || c == 2 ? 1 : 0); };
+
+    bf16x8 wf[36][2];
+    u32x4 st[16];      // input rows on their way from global memory to the rings: piece 4*c + u of plane c
+    unsigned fq[3];    // output offsets of this lane's row of the previous, the current and the next tile
+    fq[0] = S2_OOB;
+    {
+        // ---- requests first: the filter (whole block: 64 rows x 72 vectors) and, per plane, ring rows [0, TILE + halo)
+        // in passes of 4 wavefronts x 32 rows (at most two passes: TILE + halo <= 256)
+        u32x4 wtmp[18], v[2][16];
+        const u32x4 *w = (const u32x4 *)a.wpk;
+#pragma unroll
+        for (int u = 0; u < 18; ++u) wtmp[u] = w[tid + 256 * u];
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps) {
+            so1(Q0 + TILE * ps + WPOS * x + (lane & 31));
+            so2();
+            so3();
+            if (ps == 0) fq[1] = so_out;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const unsigned mine = TILE * ps + WPOS * x < TILE + f2_halo(c, a.PW) ? plane_off(c, 0, 0) : S2_OOB;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const unsigned o = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * u) * 4, (int)mine) + chunk16;
+                    v[ps][4 * c + u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, o, 0, 0);
+                }
+            }
+        }
+        // ---- the filter through LDS into operand registers: wf[s][ni] = wpk[32*ni + frow][16*s + 8*fk .. + 7]
+#pragma unroll
+        for (int u = 0; u < 18; ++u) {
+            const int i = tid + 256 * u, row = i / 72, vv = i - row * 72;
+            *(u32x4 *)(smem + row * S2_W_STRIDE + vv * 16) = wtmp[u];
+        }
+        lds_barrier();
+        const unsigned char *wl = smem + frow * S2_W_STRIDE + fk * 16;
+#pragma unroll
+        for (int s = 0; s < 36; ++s)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) wf[s][ni] = *(const bf16x8 *)(wl + ni * 32 * S2_W_STRIDE + s * 32);
+#pragma unroll
+        for (int s = 0; s < F2_AGPR_STEPS; ++s)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni) asm volatile("" : "+a"(wf[s][ni]));
+        lds_barrier();                                           // everyone has read the filter: the rings may be written
+#pragma unroll
+        for (int ps = 0; ps < 2; ++ps)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    // (rows past TILE + halo hold zeros here and are written again, with tile 1's rows, during tile 0)
+                    const unsigned r = (unsigned)(TILE * ps + WPOS * x + prow + 8 * u);
+                    *(u32x4 *)(smem + row_addr(c, r) + chunk16) = v[ps][4 * c + u];
+                }
+        // the rows tile 1 needs beyond tile 0's (plane c: rows [TILE + halo_c, 2*TILE + halo_c)) are requested now and
+        // go to the rings during tile 0; from then on the rows of tile p+2 are requested during tile p
+        so1(1 < n ? Q0 + TILE + WPOS * x + (lane & 31) : 0x40000000);
+        so2();
+        so3();
+        fq[2] = so_out;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const unsigned mine = plane_off_halo(c);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const unsigned o = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * u) * 4, (int)mine) + chunk16;
+                st[4 * c + u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, o, 0, 0);
+            }
+        }
+    }
+
+    // this lane's LDS addresses: fragment rows of the nine taps (tile 0), staging rows of the sixteen pieces (the rows
+    // tile 1 adds), and its places in the wavefront's strip (rows 32x .. 32x+31 of plane (1,1), tile parity 0)
+    unsigned ta[9], wa[16];
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+        ta[t] = row_addr(f2_plane(t), (unsigned)(x * WPOS + frow + (f2_shift(t) >> 1) * a.PW + (f2_shift(t) & 1))) + (unsigned)fk * 16u;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+#pragma unroll
+        for (int u = 0; u < 4; ++u) wa[4 * c + u] = row_addr(c, (unsigned)(TILE + f2_halo(c, a.PW) + WPOS * x + prow + 8 * u)) + chunk16;
+    const unsigned strip_w = row_addr(3, (unsigned)(WPOS * x + frow)) + (unsigned)fk * 8u;
+    const unsigned strip_r = row_addr(3, (unsigned)(WPOS * x + prow)) + chunk16;     // + 8g rows = g * 4 row pairs
+    unsigned mineI[4], offI[2];
+    u32x4 sv[4];
+    unsigned ooff[4];
+
+    f32x16 acc[2];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    lds_barrier();
+
+    auto stats_dword = [&](unsigned w, int d) {
+        const float lo = __builtin_bit_cast(float, w << 16), hi = __builtin_bit_cast(float, w & 0xFFFF0000u);
+        ssum[2 * d] += lo;
+        ssq[2 * d] += lo * lo;
+        ssum[2 * d + 1] += hi;
+        ssq[2 * d + 1] += hi * hi;
+    };
+
+    for (int p = 0; p < n; ++p) {
+        // the strip of tile p-1 (read now) and of tile p (written at the end): the half of plane (1,1)'s ring that the
+        // tile has consumed
+        const unsigned tog_r = (unsigned)((p + 1) & 1) * ADV, tog_w = (unsigned)(p & 1) * ADV;
+        bf16x8 af[DIST + 1];
+        auto fetch = [&](auto pc) {
+            constexpr int pair = decltype(pc)::value;
+            af[pair % (DIST + 1)] = lds_get<bf16x8>(ta[pair >> 2], 2 * (pair & 3));
+        };
+        auto side = [&](auto sc) {
+            constexpr F2Act act = f2_action(decltype(sc)::value);
+            constexpr int k = act.kind, g = act.arg;
+            // input rows of tile p+2: this lane computes the offsets of row WPOS*x + lane%32 of each plane
+            if constexpr (k == F2_IA1) so1(p + 2 < n ? Q0 + TILE * (p + 2) + WPOS * x + (lane & 31) : 0x40000000);
+            if constexpr (k == F2_IA2) so2();
+            if constexpr (k == F2_IA3) so3();
+            if constexpr (k == F2_IP) {
+                mineI[g] = plane_off_halo(g);
+                if constexpr (g == f2_piece_c(0)) offI[0] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * f2_piece_u(0)) * 4, (int)mineI[g]);
+            }
+            // output vector g of tile p-1: strip -> registers, then to y
+            if constexpr (k == F2_OR) {
+                sv[g] = lds_get<u32x4>(strip_r + tog_r, g * (4 * F2_PAIR_BYTES / 16));
+                ooff[g] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * g) * 4, (int)fq[0]);
+            }
+            if constexpr (k == F2_OS) {
+                __builtin_amdgcn_raw_buffer_store_b128(sv[g], out_rsrc, ooff[g] + chunk16, 0, 0);
+                if constexpr (STATS) {                           // padding positions are neither stored nor counted
+                    if (ooff[g] >= S2_OOB) sv[g] = u32x4{0u, 0u, 0u, 0u};
+                }
+            }
+            if constexpr (k == F2_ST && STATS) {
+                stats_dword(sv[g >> 1][2 * (g & 1)], 2 * (g & 1));
+                stats_dword(sv[g >> 1][2 * (g & 1) + 1], 2 * (g & 1) + 1);
+            }
+            if constexpr (k == F2_TAPU) ta[g] = advance(ta[g], f2_plane(g));
+            // input piece j = g: what was requested a tile ago goes to the ring, the same registers take the rows of
+            // tile p+2; one slot later the ring address moves on and the next piece's offset is fetched from its lane
+            if constexpr (k == F2_CLW) {
+                constexpr int c = f2_piece_c(g), u = f2_piece_u(g);
+                lds_put<u32x4>(wa[4 * c + u], 0, st[4 * c + u]);
+                st[4 * c + u] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, offI[g & 1] + chunk16, 0, 0);
+            }
+            if constexpr (k == F2_CLA) {
+                constexpr int c = f2_piece_c(g), u = f2_piece_u(g);
+                wa[4 * c + u] = advance(wa[4 * c + u], c);
+                if constexpr (g + 1 < 16)
+                    offI[(g + 1) & 1] = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * f2_piece_u(g + 1)) * 4, (int)mineI[f2_piece_c(g + 1)]);
+            }
+        };
+        static_for<0, DIST>([&](auto pc) { fetch(pc); });
+        static_for<0, 2 * NPAIR>([&](auto ic) {
+            constexpr int i = decltype(ic)::value, pair = i >> 1, ni = i & 1;
+            if constexpr (ni == 0 && pair + DIST < NPAIR) fetch(std::integral_constant<int, pair + DIST>{});
+            side(ic);
+            __builtin_amdgcn_sched_barrier(0);
+            acc[ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[pair][ni], af[pair % (DIST + 1)], pair == 0 ? zero16 : acc[ni], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        });
+        // acc[ni][4g+j] is channel 32ni + 8g + 4fk + j of position frow: piece e = 4*ni + g converts four of them and
+        // writes 8 bytes of the strip (row frow, 16-byte chunk e)
+        static_for<0, 8>([&](auto ec) {
+            constexpr int ni = decltype(ec)::value >> 2, g = decltype(ec)::value & 3;
+            bf16x4 pk;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) pk[jj] = (bf16_t)acc[ni][g * 4 + jj];
+            lds_put<bf16x4>(strip_w + tog_w, 2 * (ni * 4 + g), pk);
+        });
+        fq[0] = fq[1];
+        fq[1] = fq[2];
+        fq[2] = so_out;
+        lds_barrier();
+    }
+    // the last tile's outputs
+    const unsigned tog_r = (unsigned)((n + 1) & 1) * ADV;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        const u32x4 v = lds_get<u32x4>(strip_r + tog_r, g * (4 * F2_PAIR_BYTES / 16));
+        const unsigned o = (unsigned)__builtin_amdgcn_ds_bpermute((prow + 8 * g) * 4, (int)fq[0]);
+        __builtin_amdgcn_raw_buffer_store_b128(v, out_rsrc, o + chunk16, 0, 0);
+        if (STATS && o < S2_OOB) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) stats_dword(v[d], d);
+        }
+    }
+    write_stats();
+}
+
 }  // namespace
 
 // True if the launches described by a[0..count) are the four residue classes of the backward-data pass of a bf16 3x3
@@ -345,6 +743,78 @@ bool fs64_dgrad_s2_applicable(int dtype, const IgemmArgs *a, int count)
     if ((unsigned long long)g.src_bytes >= S2_OOB || out_bytes + 4096 >= S2_OOB) return false;
     // worth it only when the tiles fill a good part of the chip
     return total >= 64 * S2_TILE;
+}
+
+// True for the forward pass of a bf16 3x3 stride-2 pad-1 64 -> 64 layer on even extents, taps in (r, s) order.
+bool fs64_fwd_s2_applicable(int dtype, const IgemmArgs &g)
+{
+    if (dtype != NSK_BF16 || hooks().no_fs) return false;
+    if (g.Cs != 64 || g.Ngemm != 64 || g.Co != 64 || g.ntaps != 9 || g.Ktot != 576 || g.accumulate || g.zero_cell || g.groups > 1 || g.act) return false;
+    if (g.mult_h != 2 || g.mult_w != 2 || g.add_h != -1 || g.add_w != -1 || g.osh != 1 || g.osw != 1 || g.oa != 0 || g.ob != 0) return false;
+    if (g.Hs % 2 != 0 || g.Ws % 2 != 0 || g.Mi != g.Hs / 2 || g.Mj != g.Ws / 2 || g.Ho != g.Mi || g.Wo != g.Mj) return false;
+    for (int t = 0; t < 9; ++t)
+        if (g.off_h[t] != t / 3 || g.off_w[t] != t % 3) return false;
+    if (((uintptr_t)g.src | (uintptr_t)g.wpk | (uintptr_t)g.out) & 15) return false;
+    const int PW = g.Mj + 1;
+    if (PW > F2_MAX_PW) return false;
+    const long long pi = (long long)(g.Mi + 1) * PW, total = pi * g.Nimg;
+    if (total >= (1LL << 30) || total * pi >= (1LL << 40) || pi * PW >= (1LL << 40)) return false;   // exactness of the reciprocal divisions
+    if ((unsigned long long)g.src_bytes + 4096 >= S2_OOB) return false;
+    // worth it only when the tiles fill a good part of the chip
+    return total >= 128LL * F2_TILE;
+}
+
+static int f2_grid(const IgemmArgs &g, int want)
+{
+    const int tiles = ceil_div((g.Mi + 1) * (g.Mj + 1) * g.Nimg, F2_TILE);
+    return tiles < want ? tiles : want;
+}
+
+// Rows of partial sums the forward launch writes: one per wavefront
+int fs64_fwd_s2_stats_rows(const IgemmArgs &g) { return f2_grid(g, F2_STATS_GRID) * 4; }
+
+int launch_fs64_fwd_s2(const IgemmArgs &g, hipStream_t stream)
+{
+    F2Args a{};
+    a.src = g.src; a.wpk = g.wpk; a.out = g.out;
+    a.stats = g.stats; a.stats_rows = g.stats_rows;
+    a.N = g.Nimg; a.H = g.Hs; a.W = g.Ws; a.P = g.Mi; a.Q = g.Mj;
+    a.PW = a.Q + 1; a.PR = a.P + 1; a.PI = a.PR * a.PW;
+    a.total_pos = a.PI * a.N;
+    a.tiles = ceil_div(a.total_pos, F2_TILE);
+    a.img_bytes = (unsigned)(a.H * a.W * 128);
+    a.row2_bytes = (unsigned)(2 * a.W * 128);
+    a.magic_pi = ((1ULL << 40) + a.PI - 1) / a.PI;
+    a.magic_pw = ((1ULL << 40) + a.PW - 1) / a.PW;
+    a.src_bytes = g.src_bytes;
+    a.out_bytes = (unsigned)((size_t)g.Nimg * g.Ho * g.Wo * 64 * 2);
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return NSK_ERR_HIP;
+        cus = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    }
+    const int grid = f2_grid(g, g.stats ? F2_STATS_GRID : cus);
+    if (g.stats && g.stats_rows != grid * 4) return NSK_ERR_BAD_DESC;   // the planner and the launch disagree
+    const int smem = f2_lds_bytes(a.PW);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const int smem_max = f2_lds_bytes(F2_MAX_PW);
+        hipError_t e = hipFuncSetAttribute((const void *)conv_fs64_fwd_s2_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)conv_fs64_fwd_s2_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, smem_max);
+        if (e != hipSuccess) {
+            set_last_hip_error(e);
+            return NSK_ERR_HIP;
+        }
+        attr_set = true;
+    }
+    if (g.stats)
+        hipLaunchKernelGGL(conv_fs64_fwd_s2_kernel<true>, dim3(grid), dim3(256), smem, stream, a);
+    else
+        hipLaunchKernelGGL(conv_fs64_fwd_s2_kernel<false>, dim3(grid), dim3(256), smem, stream, a);
+    return check_launch();
 }
 
 int launch_fs64_dgrad_s2(const IgemmArgs *g, int count, hipStream_t stream)

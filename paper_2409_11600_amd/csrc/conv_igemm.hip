@@ -427,6 +427,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     if (tiny_src_applicable(dtype, a) || tiny_out_applicable(dtype, a)) return 0;   // no statistics epilogue there
     if (halo64_applicable(dtype, a)) return halo64_stats_rows(a);
     if (halo64_f32_applicable(dtype, a)) return halo64_f32_stats_rows(a);
+    if (fs64_fwd_s2_applicable(dtype, a)) return fs64_fwd_s2_stats_rows(a);
     if (conv_pw_applicable(dtype, a)) return conv_pw_stats_rows(a);
     if (halo_wide_applicable(dtype, a)) return halo_wide_stats_rows(a);
     if (igemm_big_applicable(dtype, a)) return igemm_big_stats_rows(a);
@@ -462,6 +463,7 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (special && tiny_out_applicable(dtype, a)) return launch_tiny_out(dtype, a, stream);
     if (special && halo64_applicable(dtype, a)) return launch_halo64(a, stream);
     if (special && halo64_f32_applicable(dtype, a)) return launch_halo64_f32(a, stream);
+    if (special && fs64_fwd_s2_applicable(dtype, a)) return launch_fs64_fwd_s2(a, stream);
     if (special && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
     if (special && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
     if (special && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);

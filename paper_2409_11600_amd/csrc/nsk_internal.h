@@ -148,6 +148,10 @@ int halo_wide_stats_rows(const IgemmArgs &a);
 // filter-stationary kernel (conv_fs64_s2.hip)
 bool fs64_dgrad_s2_applicable(int dtype, const IgemmArgs *a, int count);
 int launch_fs64_dgrad_s2(const IgemmArgs *a, int count, hipStream_t stream);
+// forward of the same layer (stride 2 as four parity planes of the input), same file
+bool fs64_fwd_s2_applicable(int dtype, const IgemmArgs &a);
+int fs64_fwd_s2_stats_rows(const IgemmArgs &a);
+int launch_fs64_fwd_s2(const IgemmArgs &a, hipStream_t stream);
 // the residue classes of one strided backward-data pass of such a layer in one launch, sharing the staged tiles
 bool halo_wide_multi_applicable(int dtype, const IgemmArgs *a, int count);
 int launch_halo_wide_multi(const IgemmArgs *a, int count, hipStream_t stream);

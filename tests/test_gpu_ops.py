@@ -458,6 +458,41 @@ def test_conv_64_to_64_stride2_backward_data(i, no_fs, nsk_env):
     assert torch.equal(dx, dx2)
 
 
+# The forward pass of the same layers: the filter-stationary kernel on four parity planes of the input (one tile per
+# block, several tiles per block, ragged last tile, tiles over many small images, the widest image its rings hold and
+# one that is wider and goes elsewhere), plain and with the batch-norm statistics.  N, H, W
+FS_S2_FWD_SHAPES = FS_S2_SHAPES + [(24, 112, 112), (90, 60, 68), (6, 124, 124), (5, 128, 126)]
+
+
+@pytest.mark.parametrize("no_fs", [False, True], ids=["filter_in_registers", "other_kernels"])
+@pytest.mark.parametrize("i", range(len(FS_S2_FWD_SHAPES)))
+def test_conv_64_to_64_stride2_forward(i, no_fs, nsk_env):
+    N, H, W = FS_S2_FWD_SHAPES[i]
+    if no_fs:
+        nsk_env("NSK_NO_FS", "1")
+    print(f"64->64 stride 2 forward case {FS_S2_FWD_SHAPES[i]} no_fs={no_fs}", flush=True)
+    x = on_grid(gen.normal(1700 + i, 0, (N, 64, H, W)), "bf16")
+    w = on_grid(gen.he_normal(1700 + i, 1, (64, 64, 3, 3)), "bf16")
+    ws = B.Workspace()
+    gx, gw = to_gpu(x, "bf16", B.NSK_NHWC), to_gpu(w, "bf16", B.NSK_NHWC)
+    y, check_y = guarded((N, H // 2, W // 2, 64), torch.bfloat16)
+    B.conv2d_fwd(gx, gw, 2, 1, 1, out=y, ws=ws)
+    y_s, stats = B.conv2d_fwd_stats(gx, gw, 2, 1, 1, ws=ws)
+    torch.cuda.synchronize()
+    check_y()
+    want_y = oracle.conv2d_fwd(x, w, 2, 1, 1)
+    assert max_rel_err(to_host(y, B.NSK_NHWC), want_y) <= TOL["bf16"]
+    assert torch.equal(y, y_s)
+    y_grid = on_grid(want_y.astype(np.float32), "bf16")
+    sums = stats.double().sum(dim=1).cpu().numpy()
+    M = N * (H // 2) * (W // 2)
+    sigma = np.sqrt((y_grid * y_grid).sum(axis=(0, 2, 3)) / M) + 1e-30
+    assert np.max(np.abs(sums[0] - y_grid.sum(axis=(0, 2, 3))) / (M * sigma)) <= 1e-3
+    assert np.max(np.abs(sums[1] - (y_grid * y_grid).sum(axis=(0, 2, 3))) / (M * sigma * sigma)) <= 1e-3
+    y2 = B.conv2d_fwd(gx, gw, 2, 1, 1, ws=ws)
+    assert torch.equal(y, y2)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_conv_is_bitwise_reproducible(dtype):
     x, w, dy, st, pd, dl = _conv_case(1, dtype)
