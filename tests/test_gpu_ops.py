@@ -459,9 +459,9 @@ def test_conv_64_to_64_stride2_backward_data(i, no_fs, nsk_env):
 
 
 # The forward pass of the same layers: the filter-stationary kernel on four parity planes of the input (one tile per
-# block, several tiles per block, ragged last tile, tiles over many small images, the widest image its rings hold and
-# one that is wider and goes elsewhere), plain and with the batch-norm statistics.  N, H, W
-FS_S2_FWD_SHAPES = FS_S2_SHAPES + [(24, 112, 112), (90, 60, 68), (6, 124, 124), (5, 128, 126)]
+# block, several tiles per block, ragged last tile, tiles over many small images, the widest image its rings hold
+# (174 columns: all of the LDS) and one that is wider and goes elsewhere), plain and with the batch-norm statistics.  N, H, W
+FS_S2_FWD_SHAPES = FS_S2_SHAPES + [(24, 112, 112), (90, 60, 68), (6, 124, 124), (6, 64, 174), (6, 64, 178)]
 
 
 @pytest.mark.parametrize("no_fs", [False, True], ids=["filter_in_registers", "other_kernels"])
