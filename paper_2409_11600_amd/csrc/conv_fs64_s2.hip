@@ -422,9 +422,10 @@ __global__ __launch_bounds__(256) void conv_fs64_fwd_s2_kernel(const F2Args a)
 {
     constexpr int TILE = F2_TILE, WPOS = F2_WPOS, NPAIR = F2_NPAIR, DIST = F2_DIST;
     constexpr unsigned ADV = TILE / 2 * F2_PAIR_BYTES;          // LDS bytes of a tile's rows
-    // This kernel has no other LDS: the dynamic allocation starts at LDS address 0, and the tile loop addresses it
-    // with plain numbers (no base to add to every address).
+    // The tile loop addresses LDS with plain 32-bit numbers kept in registers: the start of the allocation goes into
+    // them once, here, and no access adds a base.
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const int tid = threadIdx.x, lane = tid & 63;
     const int x = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int frow = lane & 31, fk = lane >> 5;
@@ -434,7 +435,7 @@ __global__ __launch_bounds__(256) void conv_fs64_fwd_s2_kernel(const F2Args a)
     const __amdgpu_buffer_rsrc_t out_rsrc = __builtin_amdgcn_make_buffer_rsrc(a.out, 0, a.out_bytes, 0x00020000);
     unsigned rbase[4], rsize[4], rend[4];
     {
-        unsigned at = 0;
+        unsigned at = lds0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             rbase[c] = at;
@@ -581,7 +582,7 @@ __global__ __launch_bounds__(256) void conv_fs64_fwd_s2_kernel(const F2Args a)
                 for (int u = 0; u < 4; ++u) {
                     // (rows past TILE + halo hold zeros here and are written again, with tile 1's rows, during tile 0)
                     const unsigned r = (unsigned)(TILE * ps + WPOS * x + prow + 8 * u);
-                    *(u32x4 *)(smem + row_addr(c, r) + chunk16) = v[ps][4 * c + u];
+                    lds_put<u32x4>(row_addr(c, r) + chunk16, 0, v[ps][4 * c + u]);
                 }
         // the rows tile 1 needs beyond tile 0's (plane c: rows [TILE + halo_c, 2*TILE + halo_c)) are requested now and
         // go to the rings during tile 0; from then on the rows of tile p+2 are requested during tile p
