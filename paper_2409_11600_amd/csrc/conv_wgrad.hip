@@ -253,6 +253,30 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const float *__restri
     *o = accumulate ? *o + s : s;
 }
 
+// The same sums in the same order for outputs that lie in dw as they lie in a partial sum (NHWC, one group): a lane takes
+// V consecutive outputs with one 8- or 16-byte load per split, so a wavefront's load is 512 or 1024 contiguous bytes.
+template <int V>
+__global__ __launch_bounds__(256) void wgrad_reduce_vec_kernel(const float *__restrict__ part, float *__restrict__ dw,
+                                                                int splits, long total, int accumulate)
+{
+    typedef float fv __attribute__((ext_vector_type(V)));
+    __shared__ fv red[4][64];
+    const int g = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const long i = ((long)blockIdx.x * 64 + l) * V;      // total % V == 0: a vector is inside or outside as a whole
+    fv s;
+#pragma unroll
+    for (int e = 0; e < V; ++e) s[e] = 0.f;
+    if (i < total)
+#pragma unroll 8
+        for (int sp = g; sp < splits; sp += 4) s += *(const fv *)(part + (long)sp * total + i);
+    red[g][l] = s;
+    __syncthreads();
+    if (g != 0 || i >= total) return;
+    s = (red[0][l] + red[1][l]) + (red[2][l] + red[3][l]);
+    fv *o = (fv *)(dw + i);
+    *o = accumulate ? *o + s : s;
+}
+
 // The same for small outputs with many splits (the 16- and 32-channel layers and the 3-channel stem of the CIFAR-sized
 // network: a few thousand outputs, hundreds of splits): 16 interleaved groups of splits instead of four, so that a lane's
 // chain of dependent loads is a quarter as long.  One block covers 16 consecutive outputs; fixed order as above.
@@ -342,6 +366,17 @@ int launch_wgrad_reduce(const float *part, float *dw, int splits, int K, int nta
                         long st, long sc, int accumulate, hipStream_t stream)
 {
     const long total = (long)K * ntaps * C;
+    // dw in the order of the partial sums: vector loads (bitwise the same sums); enough blocks to cover the chip
+    const bool flat = sc == 1 && st == (long)C && sk == (long)ntaps * C && !hooks().reduce4 &&
+                      (((uintptr_t)part | (uintptr_t)dw) & 15) == 0;
+    if (flat && total % 4 == 0 && total >= 4 * 64 * 512) {
+        hipLaunchKernelGGL(wgrad_reduce_vec_kernel<4>, dim3((unsigned)((total / 4 + 63) / 64)), dim3(256), 0, stream, part, dw, splits, total, accumulate);
+        return check_launch();
+    }
+    if (flat && total % 2 == 0 && total >= 2 * 64 * 256) {
+        hipLaunchKernelGGL(wgrad_reduce_vec_kernel<2>, dim3((unsigned)((total / 2 + 63) / 64)), dim3(256), 0, stream, part, dw, splits, total, accumulate);
+        return check_launch();
+    }
     if (total <= 16384 && splits >= 64 && !hooks().reduce4)   // (the variable is an A/B hook)
         hipLaunchKernelGGL(wgrad_reduce16_kernel, dim3((unsigned)((total + 15) / 16)), dim3(256), 0, stream, part, dw,
                            splits, K, ntaps, C, sk, st, sc, accumulate);
