@@ -73,6 +73,14 @@ struct WideArgs {
     unsigned src_bytes, out_bytes;
     float *stats;                 // single class only: per-channel partial sums of the stored output (one row per tile)
     int stats_rows;
+    // MERGE launches (the forward pass of a stride-2 layer): the classes are the four parity planes of the input,
+    // plane (pa, pb) = x[2I-1+pa][2J-1+pb] on the output's own grid, each with the taps that fall on it (shifts 0 or +1);
+    // they are staged one after the other, add into ONE set of accumulators and share one epilogue.  The filter is
+    // the forward filter itself ([K][wrow_taps][C]); tapidx holds, 4 bits per tap of a class, the tap's place in it.
+    int pa[W_CLS], pb[W_CLS];
+    unsigned long long tapidx[W_CLS];
+    int wrow_taps;
+    int Hx, Wx;                   // extent of x
 };
 
 template <typename T> __device__ __forceinline__ T sel4(const T (&v)[W_CLS], int c)
@@ -84,10 +92,14 @@ template <typename T> __device__ __forceinline__ T sel4(const T (&v)[W_CLS], int
 // that two of the smaller blocks (MW = 2, 64 output channels) share a CU.
 // MODE: 0 plain, 1 accumulate into the old output, 2 plain with the statistics epilogue (single class).
 // NINE: a single class with nine taps, tap loop unrolled.
-template <int NT, int MW, int MODE, bool NINE>
-__global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2))) void conv_halo_wide_kernel(const WideArgs a)
+// MERGE: see WideArgs.  The input of such a launch is four times that of a stride-1 layer for the same MFMA count, in
+// sixteen stages (plane, 64-channel group) of which the shortest is multiplied in 900 clocks: TWO wavefronts move data,
+// each half of a stage's rows, with the requests running two stages ahead of the LDS writes.
+template <int NT, int MW, int MODE, bool NINE, bool MERGE = false>
+__global__ __launch_bounds__((MW + (MERGE ? 2 : 1)) * 64) __attribute__((amdgpu_waves_per_eu(2))) void conv_halo_wide_kernel(const WideArgs a)
 {
-    constexpr int THREADS = (MW + 1) * 64, BN = MW * 32;
+    static_assert(!(MERGE && (NINE || MODE == 1)), "merged planes: the generic piece loop, no accumulation into old outputs");
+    constexpr int THREADS = (MW + (MERGE ? 2 : 1)) * 64, BN = MW * 32;
     constexpr bool ACCUM = MODE == 1, STATS = MODE == 2;
     constexpr int LD0 = (W_STAGE_MAX * 8 + THREADS - 1) / THREADS;   // loads per thread for the first group
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -127,15 +139,19 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
     __amdgpu_buffer_rsrc_t w_rs;
     int w_ntaps = 1, ld_t = 0, ld_g = 0;
     unsigned w_row = 0;
+    unsigned long long w_tapidx = 0;
     auto filter_class = [&](int c) {
         w_ntaps = sel4(a.ntaps, c);
         w_rs = __builtin_amdgcn_make_buffer_rsrc((void *)sel4(a.wpk, c), 0, sel4(a.wpk_bytes, c), 0x00020000);
-        w_row = wrow_idx * (unsigned)(w_ntaps * a.C * 2) + (unsigned)(fk * 64);
+        w_row = wrow_idx * (unsigned)((MERGE ? a.wrow_taps : w_ntaps) * a.C * 2) + (unsigned)(fk * 64);
+        if (MERGE) w_tapidx = sel4(a.tapidx, c);
         ld_t = 0;
         ld_g = 0;
     };
+    // byte offset of tap t of the class inside a filter row
+    auto tap_bytes = [&](int t) -> unsigned { return (unsigned)((MERGE ? (int)(w_tapidx >> (4 * t)) & 15 : t) * a.C * 2); };
     auto load_w = [&](u32x4 (&Wf)[4]) {   // past the last piece of the class: nothing (zeros)
-        const unsigned off = ld_g < cpt ? w_row + (unsigned)(ld_t * a.C * 2 + ld_g * 128) : W_OOB;
+        const unsigned off = ld_g < cpt ? w_row + tap_bytes(ld_t) + (unsigned)(ld_g * 128) : W_OOB;
 #pragma unroll
         for (int s = 0; s < 4; ++s) Wf[s] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, off + (unsigned)(s * 16), 0, 0);
         if (++ld_t >= w_ntaps) {
@@ -144,7 +160,7 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
         }
     };
     filter_class(0);
-    if (wave < MW) {
+    if (wave < MW) {   // (the moving wavefronts have no filter rows)
         load_w(wf[0]);
         load_w(wf[1]);
         load_w(wf[2]);
@@ -156,15 +172,22 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
     // others multiply group g of the first class (they meet at one barrier per group).  After the first group no
     // input load is exposed, and the multiplying wavefronts have nothing but their filter stream in their (in-order)
     // load queue.  One-time code is kept short on purpose: a block runs once per launch, so all of it is fetched cold.
-    for (int s = tid; s < W_TAB; s += THREADS) {
+    // byte offset in src of staged position s (of plane c with merged planes), out of range for padding
+    auto stage_offset = [&](int s, int c) -> unsigned {
         // u counts from one row above the padded image (so that it is never negative): u / PW is the image row + 2,
         // u % PW the image column + 1
         const unsigned u = (unsigned)((r0 + 1) * a.PW - 1 + s);
         const unsigned hp1 = __umulhi(u, a.magic_pw);
         const unsigned wp = u - hp1 * (unsigned)a.PW;
+        if (MERGE) {   // grid position (I, J) = (hp1 - 2, wp - 1) of plane c is pixel (2I - 1 + pa, 2J - 1 + pb) of x
+            const unsigned h = 2u * (hp1 - 2u) - 1u + (unsigned)sel4(a.pa, c), w = 2u * (wp - 1u) - 1u + (unsigned)sel4(a.pb, c);
+            const bool ok = s < a.n_stage && h < (unsigned)a.Hx && w < (unsigned)a.Wx;
+            return ok ? (((unsigned)(img * a.Hx) + h) * (unsigned)a.Wx + w) * (unsigned)(a.C * 2) : W_OOB;
+        }
         const bool ok = s < a.n_stage && (hp1 - 2u < (unsigned)a.H) && (wp - 1u < (unsigned)a.W);
-        in_tab[s] = ok ? (((unsigned)(img * a.H) + (hp1 - 2u)) * (unsigned)a.W + (wp - 1u)) * (unsigned)(a.C * 2) : W_OOB;
-    }
+        return ok ? (((unsigned)(img * a.H) + (hp1 - 2u)) * (unsigned)a.W + (wp - 1u)) * (unsigned)(a.C * 2) : W_OOB;
+    };
+    for (int s = tid; s < W_TAB; s += THREADS) in_tab[s] = stage_offset(s, 0);
     for (unsigned p = (unsigned)tid; p < (unsigned)(NT * 32); p += THREADS) {   // (fewer threads than positions when MW = 2)
         const unsigned pr = __umulhi(p, a.magic_pw), pc = p - pr * (unsigned)a.PW;
         const int row = r0 + (int)pr, col = (int)pc - 1;
@@ -191,7 +214,54 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
     }
     lds_barrier();   // group 0 is staged
 
-    if (wave == MW) {
+    if (MERGE && wave >= MW) {
+        __builtin_amdgcn_s_setprio(3);
+        // Stage k = (plane k / cpt, group k % cpt), k = 1 .. 4*cpt - 1, is written to LDS while stage k - 1 is multiplied
+        // (its columns were last read a whole plane, or two stages, ago) and was requested two stages earlier.  This
+        // wavefront owns rows [m*HALF, m*HALF + HALF) of every stage: row (lane / 8) + 8*i of them in load i, 16 bytes per
+        // lane.  The byte offset of a row is computed once per plane, by lane r % 64 for row r (register r / 64), and
+        // reaches the eight lanes that load the row through a lane exchange.
+        constexpr int NL = 18, HALF = 8 * NL;          // n_stage <= 2 * HALF (the launcher checks)
+        const int m = wave - MW;
+        const unsigned lds_w0 = (unsigned)((m * HALF + (lane >> 3)) * a.row_bytes + (lane & 7) * 16);
+        const int stages = a.ncls * cpt;
+        unsigned mine[3];
+        int mine_cls = -1;
+        u32x4 stA[NL], stB[NL];
+        auto request = [&](int k, u32x4 (&st)[NL]) {
+            if (k >= stages) return;
+            const int c = k / cpt, g = k & (cpt - 1);   // cpt is 2 or 4
+            if (c != mine_cls) {
+#pragma unroll
+                for (int q = 0; q < 3; ++q) mine[q] = stage_offset(m * HALF + 64 * q + lane, c);
+                mine_cls = c;
+            }
+#pragma unroll
+            for (int i = 0; i < NL; ++i) {
+                const unsigned off = (unsigned)__builtin_amdgcn_ds_bpermute(((lane >> 3) + 8 * (i & 7)) * 4, (int)mine[i >> 3]);
+                st[i] = __builtin_amdgcn_raw_buffer_load_b128(src_rsrc, off + (unsigned)(g * 128 + (lane & 7) * 16), 0, 0);
+            }
+        };
+        auto commit = [&](int k, const u32x4 (&st)[NL]) {
+            const int g = k & (cpt - 1);
+#pragma unroll
+            for (int i = 0; i < NL; ++i)
+                if (m * HALF + (lane >> 3) + 8 * i < a.n_stage) *(u32x4 *)(in_lds + lds_w0 + (unsigned)(8 * i * a.row_bytes + g * 128)) = st[i];
+        };
+        request(1, stA);
+        request(2, stB);
+        for (int k = 1; k < stages; k += 2) {
+            commit(k, stA);
+            request(k + 2, stA);
+            lds_barrier();   // stage k is in place
+            if (k + 1 >= stages) break;
+            commit(k + 1, stB);
+            request(k + 3, stB);
+            lds_barrier();   // stage k + 1 is in place
+        }
+        return;
+    }
+    if (!MERGE && wave == MW) {
         __builtin_amdgcn_s_setprio(3);   // its few instructions should not queue behind the MFMAs of the wavefront it shares a SIMD with
         const unsigned lds_w0 = (unsigned)((lane >> 3) * a.row_bytes + (lane & 7) * 16);
         for (int g = 1; g < cpt; ++g) {
@@ -366,14 +436,14 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
                 }
                 if (s == 0 && p == 1) {
                     const bool class_ends = gn == cpt;
-                    wait_group = !class_ends && tn == 0 && cls == 0;   // group gn of the first class: staged behind a barrier
+                    wait_group = !class_ends && tn == 0 && (MERGE || cls == 0);   // group gn is staged behind a barrier
                     // without a piece to read ahead the fragments are re-read where they are: in range, unused
                     if (!class_ends && !wait_group)
                         to_next = (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tn) + gn * 128) -
                                   (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tap) + grp * 128);   // wraps for negative steps
                 }
                 if (s == 0 && p == 2) {   // the filter piece to request into this set: three pieces ahead
-                    if (ld_g < cpt) w_off = w_row + (unsigned)(ld_t * a.C * 2 + ld_g * 128);
+                    if (ld_g < cpt) w_off = w_row + tap_bytes(ld_t) + (unsigned)(ld_g * 128);
                     if (++ld_t >= w_ntaps) {
                         ld_t = 0;
                         ++ld_g;
@@ -447,20 +517,23 @@ __global__ __launch_bounds__((MW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
         }
         if (i < np) piece(wf[0]);
         if (i + 1 < np) piece(wf[1]);
-        const bool more = !STATS && cls + 1 < a.ncls;   // the statistics epilogue comes with a single class
+        const bool more = (MERGE || !STATS) && cls + 1 < a.ncls;   // the statistics epilogue comes with a single class (or merged ones)
         if (more) {   // the next class's filter is on its way while this one is stored
             filter_class(cls + 1);
             load_w(wf[0]);
             load_w(wf[1]);
             load_w(wf[2]);
         }
-        epilogue(cls);
+        if (!MERGE || !more) epilogue(MERGE ? 0 : cls);   // merged planes: one output, described by every class alike
         if (!more) break;
         ++cls;
         tap = 0;
         grp = 0;
         ntaps_c = w_ntaps;
-        init_acc(cls);
+        if (MERGE)
+            lds_barrier();   // the first group of the next plane is staged
+        else
+            init_acc(cls);
         first_fragments();
     }
 }
@@ -643,5 +716,118 @@ bool halo_wide_multi_applicable(int dtype, const IgemmArgs *a, int count)
 }
 
 int launch_halo_wide_multi(const IgemmArgs *a, int count, hipStream_t stream) { return launch_classes(a, count, stream); }
+
+// ---- the forward pass of a 3x3 stride-2 pad-1 layer on even extents: four parity planes of x, staged one after the
+// other on the output's own grid, merged into one set of accumulators (MERGE instances of the kernel)
+namespace {
+// the layer as the stride-1 problem the planner knows: the output grid, x's channels
+IgemmArgs s2_as_plane_problem(const IgemmArgs &a)
+{
+    IgemmArgs v = a;
+    v.Hs = a.Mi;
+    v.Ws = a.Mj;
+    return v;
+}
+}  // namespace
+
+bool halo_wide_fwd_s2_applicable(int dtype, const IgemmArgs &a)
+{
+    if (dtype != NSK_BF16 || hooks().no_halo_wide || a.groups > 1 || a.accumulate || a.zero_cell || a.act) return false;
+    if (a.ntaps != 9 || (a.Cs != 128 && a.Cs != 256) || a.Ktot != 9 * a.Cs || a.Ngemm % 64 != 0 || a.Co % 8 != 0 || a.Co != a.Ngemm) return false;
+    if (a.mult_h != 2 || a.mult_w != 2 || a.add_h != -1 || a.add_w != -1 || a.osh != 1 || a.osw != 1 || a.oa != 0 || a.ob != 0) return false;
+    if (a.Hs % 2 != 0 || a.Ws % 2 != 0 || a.Mi != a.Hs / 2 || a.Mj != a.Ws / 2 || a.Ho != a.Mi || a.Wo != a.Mj || a.stats_rows < 0) return false;
+    for (int t = 0; t < 9; ++t)
+        if (a.off_h[t] != t / 3 || a.off_w[t] != t % 3) return false;
+    if ((unsigned long long)a.wpk_bytes >= W_OOB || (((uintptr_t)a.wpk | (uintptr_t)a.src | (uintptr_t)a.out) & 15)) return false;
+    const IgemmArgs v = s2_as_plane_problem(a);
+    Plan p;
+    if (!make_plan(v, &p) || p.n_stage > 288) return false;   // (two moving wavefronts of 144 rows each)
+    const long long out_bytes = (long long)a.Nimg * a.Ho * a.Wo * a.Co * 2;
+    if ((unsigned long long)a.src_bytes >= W_OOB || out_bytes >= (long long)W_OOB) return false;
+    if (hooks().halo_wide_always) return true;
+    const long long useful = (long long)v.Hs * v.Ws, computed = (long long)p.tiles_per_img * kNT * 32;
+    if (useful * 3 < computed * 2) return false;
+    return (long long)a.Nimg * p.tiles_per_img * (a.Ngemm / block_channels(a)) >= 128;
+}
+
+int halo_wide_fwd_s2_stats_rows(const IgemmArgs &a)
+{
+    Plan p;
+    if (!make_plan(s2_as_plane_problem(a), &p)) return 0;
+    return a.Nimg * p.tiles_per_img;
+}
+
+int launch_halo_wide_fwd_s2(const IgemmArgs &g, hipStream_t stream)
+{
+    const IgemmArgs v = s2_as_plane_problem(g);
+    Plan p;
+    if (!make_plan(v, &p) || p.n_stage > 288) return NSK_ERR_BAD_DESC;
+    WideArgs a{};
+    a.src = g.src; a.out = g.out;
+    a.ncls = 4;
+    // planes in the order of their tap counts (the longest first: the later stages are staged behind it); tap (r, s) of
+    // the filter lies on plane (r == 1, s == 1) with shift (r == 2, s == 2)
+    static const int plane_a[4] = {0, 0, 1, 1}, plane_b[4] = {0, 1, 0, 1};
+    for (int c = 0; c < 4; ++c) {
+        a.wpk[c] = g.wpk; a.wpk_bytes[c] = g.wpk_bytes;
+        a.Mi[c] = g.Mi; a.Mj[c] = g.Mj; a.oa[c] = 0; a.ob[c] = 0;
+        a.pa[c] = plane_a[c]; a.pb[c] = plane_b[c];
+        int n = 0;
+        unsigned long long code = 0, idx = 0;
+        for (int t = 0; t < 9; ++t) {
+            const int r = t / 3, sc = t % 3;
+            if ((r == 1) != (plane_a[c] == 1) || (sc == 1) != (plane_b[c] == 1)) continue;
+            const int dh = r == 2 ? 1 : 0, dw = sc == 2 ? 1 : 0;
+            code |= (unsigned long long)((dh + 1) * 4 + (dw + 1)) << (4 * n);
+            idx |= (unsigned long long)t << (4 * n);
+            ++n;
+        }
+        a.ntaps[c] = n; a.tapcode[c] = code; a.tapidx[c] = idx;
+    }
+    a.wrow_taps = 9;
+    a.Hx = g.Hs; a.Wx = g.Ws;
+    a.N = g.Nimg; a.H = v.Hs; a.W = v.Ws; a.C = g.Cs; a.K = g.Ngemm;
+    a.Ho = g.Ho; a.Wo = g.Wo; a.Co = g.Co; a.osh = 1; a.osw = 1;
+    a.PW = v.Ws + 2;
+    a.rows_per_tile = p.rows_per_tile;
+    a.tiles_per_img = p.tiles_per_img;
+    a.tiles = g.Nimg * p.tiles_per_img;
+    a.n_stage = p.n_stage;
+    a.row_bytes = p.row_bytes;
+    a.magic_pw = (unsigned)(((1ULL << 32) + a.PW - 1) / a.PW);
+    a.src_bytes = g.src_bytes;
+    a.out_bytes = (unsigned)((long long)g.Nimg * g.Ho * g.Wo * g.Co * 2);
+    a.stats = g.stats;
+    a.stats_rows = g.stats_rows;
+    if (g.stats && g.stats_rows != a.tiles) return NSK_ERR_BAD_DESC;   // the planner and the launch disagree
+    static bool attr_set = false;
+    if (!attr_set) {
+        const void *k[4] = {
+            (const void *)conv_halo_wide_kernel<kNT, 4, 0, false, true>, (const void *)conv_halo_wide_kernel<kNT, 4, 2, false, true>,
+            (const void *)conv_halo_wide_kernel<kNT, 2, 0, false, true>, (const void *)conv_halo_wide_kernel<kNT, 2, 2, false, true>};
+        for (int i = 0; i < 4; ++i) {
+            const hipError_t e = hipFuncSetAttribute(k[i], hipFuncAttributeMaxDynamicSharedMemorySize, W_LDS_MAX);
+            if (e != hipSuccess) {
+                set_last_hip_error(e);
+                return NSK_ERR_HIP;
+            }
+        }
+        attr_set = true;
+    }
+    const int bn = block_channels(g);
+    const dim3 grid((unsigned)(a.tiles * (a.K / bn)));
+    if (bn == 128) {
+        if (a.stats)
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 2, false, true>), grid, dim3(6 * 64), p.smem, stream, a);
+        else
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 4, 0, false, true>), grid, dim3(6 * 64), p.smem, stream, a);
+    } else {
+        if (a.stats)
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 2, false, true>), grid, dim3(4 * 64), p.smem, stream, a);
+        else
+            hipLaunchKernelGGL((conv_halo_wide_kernel<kNT, 2, 0, false, true>), grid, dim3(4 * 64), p.smem, stream, a);
+    }
+    return check_launch();
+}
 
 }  // namespace nsk

@@ -430,6 +430,7 @@ int igemm_stats_rows(int dtype, const IgemmArgs &a)
     if (fs64_fwd_s2_applicable(dtype, a)) return fs64_fwd_s2_stats_rows(a);
     if (conv_pw_applicable(dtype, a)) return conv_pw_stats_rows(a);
     if (halo_wide_applicable(dtype, a)) return halo_wide_stats_rows(a);
+    if (halo_wide_fwd_s2_applicable(dtype, a)) return halo_wide_fwd_s2_stats_rows(a);
     if (igemm_big_applicable(dtype, a)) return igemm_big_stats_rows(a);
     // generic kernel: needs the vector epilogue; one row per wavefront row of every row block.  Measured: with a
     // short reduction the per-block cross-lane sums and the many rows of partial sums cost more than the separate
@@ -466,6 +467,7 @@ int launch_igemm(int dtype, const IgemmArgs &a, hipStream_t stream)
     if (special && fs64_fwd_s2_applicable(dtype, a)) return launch_fs64_fwd_s2(a, stream);
     if (special && conv_pw_applicable(dtype, a)) return launch_conv_pw(a, stream);
     if (special && halo_wide_applicable(dtype, a)) return launch_halo_wide(a, stream);
+    if (special && halo_wide_fwd_s2_applicable(dtype, a)) return launch_halo_wide_fwd_s2(a, stream);
     if (special && igemm_big_applicable(dtype, a)) return launch_igemm_big(a, stream);
     if (grouped && forced_tile() == 0 && !hooks().no_depthwise && depthwise_applicable(dtype, a))
         return launch_depthwise(dtype, a, stream);

@@ -144,6 +144,10 @@ int halo64_stats_rows(const IgemmArgs &a);
 bool halo_wide_applicable(int dtype, const IgemmArgs &a);
 int launch_halo_wide(const IgemmArgs &a, hipStream_t stream);
 int halo_wide_stats_rows(const IgemmArgs &a);
+// forward of a 3x3 stride-2 pad-1 layer with 128 or 256 input channels: the same kernel on four parity planes of x
+bool halo_wide_fwd_s2_applicable(int dtype, const IgemmArgs &a);
+int halo_wide_fwd_s2_stats_rows(const IgemmArgs &a);
+int launch_halo_wide_fwd_s2(const IgemmArgs &a, hipStream_t stream);
 // the four residue classes of the backward-data pass of a bf16 3x3 stride-2 64 -> 64 layer in one launch of the
 // filter-stationary kernel (conv_fs64_s2.hip)
 bool fs64_dgrad_s2_applicable(int dtype, const IgemmArgs *a, int count);

@@ -254,6 +254,51 @@ def test_conv_wide_halo_kernel_strided_backward_data(i, layout, nsk_env):
     assert max_rel_err(to_host(gacc, layout), want_acc) <= tol
 
 
+# The forward pass of 3x3 stride-2 pad-1 layers with 128 or 256 input channels on even extents: the same kernel on the
+# four parity planes of the input, staged one after the other (two moving wavefronts, requests two stages ahead) and
+# merged into one set of accumulators.  N, C, H, W, K
+HALO_WIDE_FWD_S2 = [
+    (2, 256, 28, 28, 256),       # the bottleneck-stage layer itself: one image per tile, two column blocks
+    (3, 128, 28, 28, 128),       # two channel groups: a plane's first group lands on the columns read two stages before
+    (2, 128, 18, 22, 64),        # the tile ends inside its last position tile; blocks of two multiplying wavefronts
+    (1, 256, 40, 26, 128),       # two tiles per image, the second with fewer rows
+    (2, 128, 8, 56, 192),        # seven rows of 30 padded positions per tile; three column blocks of 64
+    (1, 128, 12, 58, 128),       # 31 padded positions per row: the most staged rows the two moving wavefronts take (288)
+]
+
+
+@pytest.mark.parametrize("layout", LAYOUTS)
+@pytest.mark.parametrize("i", range(len(HALO_WIDE_FWD_S2)))
+def test_conv_wide_halo_kernel_stride2_forward(i, layout, nsk_env):
+    nsk_env("NSK_HALO_WIDE_ALWAYS", "1")
+    N, C, H, W, K = HALO_WIDE_FWD_S2[i]
+    print(f"wide halo stride-2 forward case {i} {HALO_WIDE_FWD_S2[i]} layout={layout}", flush=True)
+    dtype, st, pd, dl = "bf16", 2, 1, 1
+    x = on_grid(gen.normal(1450 + i, 0, (N, C, H, W)), dtype)
+    w = on_grid(gen.he_normal(1450 + i, 1, (K, C, 3, 3)), dtype)
+    ws = B.Workspace()
+    gx, gw = to_gpu(x, dtype, layout), to_gpu(w, dtype, layout)
+    out_shape = (N, K, H // 2, W // 2) if layout == B.NSK_NCHW else (N, H // 2, W // 2, K)
+    y_view, y_check = guarded(out_shape, torch_dtype(dtype))
+    B.conv2d_fwd(gx, gw, st, pd, dl, layout, out=y_view, ws=ws)
+    y1, stats = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    y2, _ = B.conv2d_fwd_stats(gx, gw, st, pd, dl, layout, ws=ws)
+    torch.cuda.synchronize()
+    y_check()
+    want_y = oracle.conv2d_fwd(x, w, st, pd, dl)
+    assert max_rel_err(to_host(y_view, layout), want_y) <= TOL[dtype]
+    assert torch.equal(y1, y2) and torch.equal(y1.flatten(), y_view.reshape(y1.shape).flatten())   # reproducible; same as plain
+    yh = to_host(y1, layout)
+    sums = stats.double().sum(dim=1).cpu().numpy()
+    want0, want1 = yh.sum(axis=(0, 2, 3)), (yh * yh).sum(axis=(0, 2, 3))
+    assert np.max(np.abs(sums[0] - want0) / (np.sqrt(want1 * yh[:, 0].size) + 1e-30)) <= 1e-6
+    assert np.max(np.abs(sums[1] - want1) / (want1 + 1e-30)) <= 1e-5
+    # the kernels that take the layer otherwise
+    nsk_env("NSK_NO_HALO_WIDE", "1")
+    y3 = B.conv2d_fwd(gx, gw, st, pd, dl, layout, ws=ws)
+    assert max_rel_err(to_host(y3, layout), want_y) <= TOL[dtype]
+
+
 
 # Short-reduction bf16 layers (1, 2 or 4 taps, at most 256 reduction indices) for the kernel that keeps the filter
 # in LDS and loads pixels straight into MFMA operands.
