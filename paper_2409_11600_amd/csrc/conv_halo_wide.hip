@@ -436,7 +436,7 @@ __global__ __launch_bounds__((MW + (MERGE ? 2 : 1)) * 64) __attribute__((amdgpu_
                 }
                 if (s == 0 && p == 1) {
                     const bool class_ends = gn == cpt;
-                    wait_group = !class_ends && tn == 0 && (MERGE || cls == 0);   // group gn is staged behind a barrier
+                    wait_group = !class_ends && tn == 0 && cls == 0;   // group gn of the first class: staged behind a barrier
                     // without a piece to read ahead the fragments are re-read where they are: in range, unused
                     if (!class_ends && !wait_group)
                         to_next = (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tn) + gn * 128) -
@@ -461,6 +461,81 @@ __global__ __launch_bounds__((MW + (MERGE ? 2 : 1)) * 64) __attribute__((amdgpu_
             first_fragments();
         }
     };
+    // Merged planes: the pieces of all planes are ONE sequence (plane, group, tap), so the filter stream runs through
+    // the plane changes without a restart; every stage (plane, group) but the first waits for its barrier.
+    if (MERGE) {
+        int ld_c = 0;   // plane of the next filter piece to request
+        auto piece_m = [&](u32x4 (&Wf)[4]) {
+            int tn = 0, gn = 0, cn = 0;
+            bool wait_stage = false;
+            unsigned to_next = 0u, w_off = W_OOB;
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const bf16x8 wfrag = __builtin_bit_cast(bf16x8, Wf[s]);
+#pragma unroll
+                for (int p = 0; p < NT; ++p) {
+                    acc[p] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wfrag, pf[s & 1][p], acc[p], 0, 0, 0);
+                    if (s < 3) {
+                        pf[(s + 1) & 1][p] = lds_read16(bp[p] + (s + 1) * 16);
+                    } else {
+                        bp[p] += to_next;
+                        asm volatile("" : "+v"(bp[p]));
+                        pf[0][p] = lds_read16(bp[p]);
+                    }
+                    if (s == 0 && p == 0) {   // the piece after this one
+                        tn = tap + 1;
+                        gn = grp;
+                        cn = cls;
+                        if (tn == ntaps_c) {
+                            tn = 0;
+                            if (++gn == cpt) {
+                                gn = 0;
+                                ++cn;
+                            }
+                        }
+                    }
+                    if (s == 0 && p == 1) {
+                        wait_stage = cn < a.ncls && tn == 0;   // a new stage: staged behind a barrier
+                        if (cn < a.ncls && !wait_stage)        // the next tap of the same stage: read ahead
+                            to_next = (unsigned)(__builtin_amdgcn_readlane(my_tap, 16 * cls + tn) - __builtin_amdgcn_readlane(my_tap, 16 * cls + tap));
+                    }
+                    if (s == 0 && p == 2) {   // the filter piece to request into this set: three pieces ahead
+                        if (ld_c < a.ncls) w_off = w_row + tap_bytes(ld_t) + (unsigned)(ld_g * 128);
+                        if (++ld_t >= w_ntaps) {
+                            ld_t = 0;
+                            if (++ld_g >= cpt) {
+                                ld_g = 0;
+                                if (++ld_c < a.ncls) {
+                                    w_ntaps = sel4(a.ntaps, ld_c);
+                                    w_tapidx = sel4(a.tapidx, ld_c);
+                                }
+                            }
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                Wf[s] = __builtin_amdgcn_raw_buffer_load_b128(w_rs, w_off + (unsigned)(s * 16), 0, 0);
+            }
+            tap = tn;
+            grp = gn;
+            if (cn != cls) {
+                cls = cn;
+                if (cls < a.ncls) ntaps_c = sel4(a.ntaps, cls);
+            }
+            if (wait_stage) {
+                lds_barrier();   // the stage is in place
+                first_fragments();
+            }
+        };
+        const int total = 9 * cpt;   // a multiple of three
+        for (int i = 0; i < total; i += 3) {
+            piece_m(wf[0]);
+            piece_m(wf[1]);
+            piece_m(wf[2]);
+        }
+        epilogue(0);   // one output, described by every class alike
+        return;
+    }
     // A single class with nine taps (forward, backward-data at stride 1): the same pieces with the tap loop unrolled, so
     // that tap shifts are scalars known per call and a piece carries no bookkeeping at all (8% off the main loop).
     if (NINE) {
@@ -506,7 +581,7 @@ __global__ __launch_bounds__((MW + (MERGE ? 2 : 1)) * 64) __attribute__((amdgpu_
         epilogue(0);
         return;
     }
-    if (!NINE)
+    if (!NINE && !MERGE)
     for (;;) {
         const int np = ntaps_c * cpt;
         int i = 0;
@@ -517,23 +592,20 @@ __global__ __launch_bounds__((MW + (MERGE ? 2 : 1)) * 64) __attribute__((amdgpu_
         }
         if (i < np) piece(wf[0]);
         if (i + 1 < np) piece(wf[1]);
-        const bool more = (MERGE || !STATS) && cls + 1 < a.ncls;   // the statistics epilogue comes with a single class (or merged ones)
+        const bool more = !STATS && cls + 1 < a.ncls;   // the statistics epilogue comes with a single class
         if (more) {   // the next class's filter is on its way while this one is stored
             filter_class(cls + 1);
             load_w(wf[0]);
             load_w(wf[1]);
             load_w(wf[2]);
         }
-        if (!MERGE || !more) epilogue(MERGE ? 0 : cls);   // merged planes: one output, described by every class alike
+        epilogue(cls);
         if (!more) break;
         ++cls;
         tap = 0;
         grp = 0;
         ntaps_c = w_ntaps;
-        if (MERGE)
-            lds_barrier();   // the first group of the next plane is staged
-        else
-            init_acc(cls);
+        init_acc(cls);
         first_fragments();
     }
 }
